@@ -1,0 +1,313 @@
+"""CPU oracle for the HPSGD hot path.  TEST INFRASTRUCTURE ONLY.
+
+A plain, slow, float64 numpy statement of what the hot path computes: the local
+training step of one worker (forward, backprop through time, SGD commit to the
+worker's replica), the replica merge and the replica sync, plus the two
+schedules that chain them.  Only the tests, the smoke check and the benchmark's
+cpu_baseline leg may import it; the product path never does.  It shares no code
+with the HIP path and takes no value from it.
+
+What fixes each function:
+  * commit        -- Alg. 2, "update replica": r_i <- r_i - mu * grad.
+  * merge         -- Eq. 1 with Alg. 3's all-reduce read as a mean over the n
+                     workers: W <- W_prev - mu * sum_i sum_e grad_i^e / n, written
+                     with replica_k - snapshot = -mu * (accumulated gradients of k).
+  * sync          -- Alg. 2, "make replica": r_i <- clone(w).
+  * model forward / backward -- the paper names a GRU (Sec. 1) and cross-entropy
+                     with plain SGD (Sec. 4.1) but prints no model equations; the
+                     cell is the one of the library the paper ran on (gate order
+                     r, z, n; two bias vectors; candidate n = tanh(W_in x + b_in +
+                     r * (W_hn h + b_hn)); h_0 = 0), loss = mean cross-entropy.
+  * schedules     -- Sec. 3.1/3.2: s_seq is the no-staleness order (Local SGD,
+                     Alg. 1, by Eq. 2); s_ovl applies each merge one round late,
+                     the one-synchronisation delay stated after Alg. 3.
+
+Pins (tests/test_oracle_*.py): central finite differences of every parameter,
+a double-precision library GRU with autograd, the T=1 closed form, loss = ln C at
+zero weights, Eq. 2, K identical replicas, K=1 == plain SGD, lr=0, SSGD and
+Local-SGD equivalences, a closed-form delayed recursion on a quadratic.
+Absolute task accuracy (the paper's accuracy curves): parity unpinned -- those
+need the paper's dataset and CNNs and are not part of this path.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+F64 = np.float64
+
+
+def _f64(params: dict) -> dict:
+    return {k: np.asarray(v, dtype=F64).copy() for k, v in params.items()}
+
+
+def sigmoid(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+# ----------------------------------------------------------------------------
+# softmax cross-entropy, mean over rows
+# ----------------------------------------------------------------------------
+def softmax_ce(logits, y):
+    """loss = mean_i -log softmax(logits_i)[y_i];  returns (loss, dloss/dlogits)."""
+    n = logits.shape[0]
+    m = logits.max(axis=1, keepdims=True)
+    e = np.exp(logits - m)
+    s = e.sum(axis=1, keepdims=True)
+    p = e / s
+    logp = (logits - m) - np.log(s)
+    loss = -logp[np.arange(n), y].mean()
+    d = p.copy()
+    d[np.arange(n), y] -= 1.0
+    return loss, d / n
+
+
+# ----------------------------------------------------------------------------
+# one GRU layer
+# ----------------------------------------------------------------------------
+def gru_layer_forward(W_ih, W_hh, b_ih, b_hh, x):
+    """x [T,B,in] -> hs [T+1,B,H] (hs[0] = 0, hs[t+1] = h after step t) and saved gates."""
+    T, B, _ = x.shape
+    H = W_hh.shape[1]
+    hs = np.zeros((T + 1, B, H), F64)
+    r = np.zeros((T, B, H), F64)
+    z = np.zeros((T, B, H), F64)
+    n = np.zeros((T, B, H), F64)
+    q = np.zeros((T, B, H), F64)
+    for t in range(T):
+        gx = x[t] @ W_ih.T + b_ih
+        gh = hs[t] @ W_hh.T + b_hh
+        r[t] = sigmoid(gx[:, 0:H] + gh[:, 0:H])
+        z[t] = sigmoid(gx[:, H:2 * H] + gh[:, H:2 * H])
+        q[t] = gh[:, 2 * H:3 * H]
+        n[t] = np.tanh(gx[:, 2 * H:3 * H] + r[t] * q[t])
+        hs[t + 1] = (1.0 - z[t]) * n[t] + z[t] * hs[t]
+    return hs, (r, z, n, q)
+
+
+def gru_layer_backward(W_ih, W_hh, x, hs, saved, dh_out):
+    """dh_out [T,B,H]: dLoss/d(h_t) arriving from above at every step.
+
+    Returns dW_ih, dW_hh, db_ih, db_hh, dx [T,B,in].
+    """
+    r, z, n, q = saved
+    T, B, _ = x.shape
+    H = W_hh.shape[1]
+    dW_ih = np.zeros_like(W_ih)
+    dW_hh = np.zeros_like(W_hh)
+    db_ih = np.zeros(3 * H, F64)
+    db_hh = np.zeros(3 * H, F64)
+    dx = np.zeros_like(x)
+    dh_next = np.zeros((B, H), F64)
+    for t in range(T - 1, -1, -1):
+        dh = dh_out[t] + dh_next
+        h_prev = hs[t]
+        dn = dh * (1.0 - z[t])
+        dz = dh * (h_prev - n[t])
+        da_n = dn * (1.0 - n[t] ** 2)
+        dr = da_n * q[t]
+        dq = da_n * r[t]
+        da_r = dr * r[t] * (1.0 - r[t])
+        da_z = dz * z[t] * (1.0 - z[t])
+        dgx = np.concatenate([da_r, da_z, da_n], axis=1)
+        dgh = np.concatenate([da_r, da_z, dq], axis=1)
+        dW_ih += dgx.T @ x[t]
+        dW_hh += dgh.T @ h_prev
+        db_ih += dgx.sum(axis=0)
+        db_hh += dgh.sum(axis=0)
+        dx[t] = dgx @ W_ih
+        dh_next = dh * z[t] + dgh @ W_hh
+    return dW_ih, dW_hh, db_ih, db_hh, dx
+
+
+# ----------------------------------------------------------------------------
+# whole models: loss and gradient of every parameter
+# ----------------------------------------------------------------------------
+def _n_layers(params):
+    l = 0
+    while f"l{l}.W_ih" in params:
+        l += 1
+    return l
+
+
+def gru_loss_and_grads(params, x, y):
+    """GRU classifier (x float [T,B,I], y int [B], head on the last hidden state) or
+    GRU language model (x int [T,B] token ids, y int [T,B] next tokens, head at every step;
+    recognised by the presence of an embedding table)."""
+    p = _f64(params)
+    L = _n_layers(p)
+    lm = "embed.E" in p
+    if lm:
+        tokens = np.asarray(x)
+        inp = p["embed.E"][tokens]          # [T,B,E]
+    else:
+        inp = np.asarray(x, F64)
+    T, B = inp.shape[0], inp.shape[1]
+    layer_in, layer_hs, layer_saved = [], [], []
+    for l in range(L):
+        hs, saved = gru_layer_forward(p[f"l{l}.W_ih"], p[f"l{l}.W_hh"],
+                                      p[f"l{l}.b_ih"], p[f"l{l}.b_hh"], inp)
+        layer_in.append(inp)
+        layer_hs.append(hs)
+        layer_saved.append(saved)
+        inp = hs[1:]
+    top = layer_hs[-1]
+    H = top.shape[2]
+    Wo, bo = p["head.W"], p["head.b"]
+    g = {}
+    dh_out = np.zeros((T, B, H), F64)
+    if lm:
+        feats = top[1:].reshape(T * B, H)
+        logits = feats @ Wo.T + bo
+        loss, dlog = softmax_ce(logits, np.asarray(y).reshape(T * B))
+        g["head.W"] = dlog.T @ feats
+        g["head.b"] = dlog.sum(axis=0)
+        dh_out = (dlog @ Wo).reshape(T, B, H)
+    else:
+        feats = top[T]
+        logits = feats @ Wo.T + bo
+        loss, dlog = softmax_ce(logits, np.asarray(y))
+        g["head.W"] = dlog.T @ feats
+        g["head.b"] = dlog.sum(axis=0)
+        dh_out[T - 1] = dlog @ Wo
+    for l in range(L - 1, -1, -1):
+        dW_ih, dW_hh, db_ih, db_hh, dx = gru_layer_backward(
+            p[f"l{l}.W_ih"], p[f"l{l}.W_hh"], layer_in[l], layer_hs[l], layer_saved[l], dh_out)
+        g[f"l{l}.W_ih"], g[f"l{l}.W_hh"] = dW_ih, dW_hh
+        g[f"l{l}.b_ih"], g[f"l{l}.b_hh"] = db_ih, db_hh
+        dh_out = dx
+    if lm:
+        dE = np.zeros_like(p["embed.E"])
+        np.add.at(dE, tokens.reshape(-1), dh_out.reshape(T * B, -1))
+        g["embed.E"] = dE
+    return loss, g
+
+
+def mlp_loss_and_grads(params, x, y):
+    """ReLU MLP, x float [B,D0], y int [B]; ReLU'(0) = 0."""
+    p = _f64(params)
+    L = 0
+    while f"fc{L}.W" in p:
+        L += 1
+    acts = [np.asarray(x, F64)]
+    for i in range(L):
+        a = acts[-1] @ p[f"fc{i}.W"].T + p[f"fc{i}.b"]
+        if i < L - 1:
+            a = np.maximum(a, 0.0)
+        acts.append(a)
+    loss, delta = softmax_ce(acts[-1], np.asarray(y))
+    g = {}
+    for i in range(L - 1, -1, -1):
+        g[f"fc{i}.W"] = delta.T @ acts[i]
+        g[f"fc{i}.b"] = delta.sum(axis=0)
+        if i > 0:
+            delta = (delta @ p[f"fc{i}.W"]) * (acts[i] > 0.0)
+    return loss, g
+
+
+def loss_and_grads(params, x, y):
+    if "fc0.W" in params:
+        return mlp_loss_and_grads(params, x, y)
+    return gru_loss_and_grads(params, x, y)
+
+
+# ----------------------------------------------------------------------------
+# the three primitives
+# ----------------------------------------------------------------------------
+def commit(replica, grads, lr):
+    """Alg. 2 'update replica': r <- r - mu * grad, every parameter, plain SGD."""
+    return {k: np.asarray(replica[k], F64) - lr * grads[k] for k in replica}
+
+
+def local_step(replica, x, y, lr):
+    """Forward + backward on the replica's parameters, then the commit.  Returns (replica', loss)."""
+    loss, g = loss_and_grads(replica, x, y)
+    return commit(replica, g, lr), loss
+
+
+def merge(global_, replicas, snapshot):
+    """Eq. 1 in delta form: global <- global + (1/K) * sum_k (replica_k - snapshot).
+
+    Works on dicts of tensors or on plain arrays.
+    """
+    if isinstance(global_, dict):
+        return {k: merge(global_[k], [r[k] for r in replicas], snapshot[k]) for k in global_}
+    K = len(replicas)
+    acc = np.zeros_like(np.asarray(global_, F64))
+    for r in replicas:
+        acc = acc + (np.asarray(r, F64) - np.asarray(snapshot, F64))
+    return np.asarray(global_, F64) + acc / K
+
+
+def sync(global_):
+    """Alg. 2 'make replica': an exact copy of the global model."""
+    if isinstance(global_, dict):
+        return {k: np.array(v, copy=True) for k, v in global_.items()}
+    return np.array(global_, copy=True)
+
+
+# ----------------------------------------------------------------------------
+# schedules
+# ----------------------------------------------------------------------------
+def s_seq(init, batch_fn, K, lr, gamma, rounds, step_fn=None):
+    """No-staleness order: `rounds` x { gamma local steps on every worker; merge; sync }.
+
+    batch_fn(worker, step) -> (x, y).  step_fn defaults to local_step (a test may pass
+    another per-worker update with the same signature).  Returns (global, losses[step][worker]).
+    """
+    step_fn = step_fn or local_step
+    G = _f64(init)
+    losses = []
+    step = 0
+    for _ in range(rounds):
+        S = sync(G)
+        R = [sync(G) for _ in range(K)]
+        for _ in range(gamma):
+            row = []
+            for k in range(K):
+                R[k], loss = step_fn(R[k], *batch_fn(k, step), lr)
+                row.append(loss)
+            losses.append(row)
+            step += 1
+        G = merge(G, R, S)
+    return G, losses
+
+
+def s_ovl(init, batch_fn, K, lr, rounds, step_fn=None, trace=None):
+    """Overlapped order: the merge of round t-1 runs beside the local step of round t.
+
+    Two buffer generations g in {0,1}.  Round t trains generation g (cloned from the
+    global model at the end of round t-1, i.e. holding merges <= t-2); meanwhile the
+    other generation's delta (round t-1) is merged.  The first round merges nothing,
+    the last delta is merged in a drain step.  If `trace` is a list, the global model
+    as it stands at the end of every round is appended to it.  Returns (global, losses).
+    """
+    step_fn = step_fn or local_step
+    G = _f64(init)
+    S = [sync(G), None]
+    R = [[sync(G) for _ in range(K)], None]
+    g = 0
+    losses = []
+    for t in range(rounds):
+        row = []
+        for k in range(K):
+            R[g][k], loss = step_fn(R[g][k], *batch_fn(k, t), lr)
+            row.append(loss)
+        losses.append(row)
+        if t > 0:
+            G = merge(G, R[1 - g], S[1 - g])
+        if trace is not None:
+            trace.append(sync(G))
+        S[1 - g] = sync(G)
+        R[1 - g] = [sync(G) for _ in range(K)]
+        g = 1 - g
+    G = merge(G, R[1 - g], S[1 - g])
+    return G, losses
+
+
+def overlap_counts(gamma, k):
+    """Sec. 3.2 worked example: with t_sync = k * t_train, one Local-SGD loop (gamma local
+    steps, one more training pass, one synchronisation) lasts (gamma + 1 + k) * t_train.
+    In that time a worker that never waits trains gamma + k + 1 times and, synchronising
+    back to back, completes (gamma + 1) / k + 1 synchronisations.  Returns (trainings, syncs)."""
+    span = (gamma + 1) + k           # in units of t_train
+    return span, span / k
