@@ -1,0 +1,149 @@
+/*
+ * hpsgd.h -- C ABI of the HPSGD hot path on one MI355X (gfx950).
+ *
+ * HPSGD (Hierarchical Parallel SGD): every worker trains a replica of the global
+ * model while the previous round's changes are being synchronised; the average
+ * change of the replicas is then merged into the global model (Abstract; Sec. 3).
+ * K workers are simulated on one GPU as a group dimension: every buffer that a
+ * worker owns is an array of K equally strided slices.
+ *
+ * Conventions for every entry point
+ *   - All data pointers are DEVICE pointers unless a parameter says HOST.
+ *   - The caller owns every device buffer, the workspace included.  The library never
+ *     allocates or frees device memory and never synchronises, creates or destroys a
+ *     stream; the context holds host memory only.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     enqueue work and return; ordering between streams is the caller's job.
+ *   - Return value: HPSGD_OK or an error code.  Arguments are validated before
+ *     anything is enqueued; on error nothing has been written.
+ *   - Float buffers must be 16-byte aligned, strides multiples of 4 floats.
+ *   - Results are deterministic: fixed reduction orders, no floating-point atomics.
+ */
+#ifndef HPSGD_H
+#define HPSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hpsgd_ctx hpsgd_ctx; /* opaque, host memory only: shapes, layout table, launch plan */
+
+enum hpsgd_status {
+  HPSGD_OK = 0,
+  HPSGD_EINVAL = 1,       /* null pointer, K < 1, negative size, unknown enum */
+  HPSGD_ESHAPE = 2,       /* model description inconsistent or out of supported range */
+  HPSGD_EALIGN = 3,       /* pointer not 16-byte aligned or stride not a multiple of 4 floats */
+  HPSGD_EALIAS = 4,       /* output overlaps an input it must not overlap */
+  HPSGD_EWORKSPACE = 5,   /* workspace null or misaligned */
+  HPSGD_EUNSUPPORTED = 6, /* valid request the library does not implement */
+  HPSGD_EHIP = 7          /* a HIP call or launch failed */
+};
+
+enum hpsgd_model_kind {
+  HPSGD_GRU_CLASSIFIER = 0, /* GRU stack, linear + softmax head on the last hidden state */
+  HPSGD_GRU_LM = 1,         /* embedding, GRU stack, linear + softmax head at every step */
+  HPSGD_MLP = 2             /* ReLU multilayer perceptron with a softmax head */
+};
+
+enum hpsgd_precision {
+  HPSGD_FP32 = 0,     /* fp32 operands on the fp32 matrix cores */
+  HPSGD_BF16_MFMA = 1 /* GEMM operands rounded to bf16 (nearest-even), fp32 accumulate;
+                         parameters, gate math, softmax and gradients stay fp32 */
+};
+
+#define HPSGD_MAX_WORKERS 32
+#define HPSGD_MAX_MLP_DIMS 8
+
+typedef struct hpsgd_model_desc {
+  int kind;      /* enum hpsgd_model_kind */
+  int prec;      /* enum hpsgd_precision */
+  int layers;    /* GRU layers (GRU kinds) */
+  int input;     /* input width I (classifier) */
+  int hidden;    /* hidden width H */
+  int seq_len;   /* T */
+  int batch;     /* B, per worker */
+  int classes;   /* C (classifier); the LM's class count is `vocab` */
+  int vocab;     /* V (LM) */
+  int embed;     /* E (LM) */
+  int n_mlp_dims;                   /* MLP: number of layer widths, input and output included */
+  int mlp_dims[HPSGD_MAX_MLP_DIMS]; /* MLP: widths d0, d1, ..., d_last */
+} hpsgd_model_desc;
+
+/* ---- context --------------------------------------------------------------------------
+ * Describes the model every worker trains (Sec. 3.1: each worker runs the same local
+ * training phase on its own sub-dataset) and the number of workers K.  Host memory only. */
+int hpsgd_create(const hpsgd_model_desc *desc, int K, hpsgd_ctx **out);
+int hpsgd_destroy(hpsgd_ctx *ctx);
+
+/* Number of fp32 parameters P of one replica. */
+size_t hpsgd_param_count(const hpsgd_ctx *ctx);
+/* Number of parameter tensors in the flat layout. */
+int hpsgd_param_entries(const hpsgd_ctx *ctx);
+/* i-th tensor of the flat layout: name (owned by ctx), offset in floats, rows, cols
+ * (cols = 1 for vectors).  Matrices are row-major [out, in]; the three GRU gates are
+ * stacked r, z, n along `out`.  Returns HPSGD_EINVAL if i is out of range. */
+int hpsgd_param_entry(const hpsgd_ctx *ctx, int i, const char **name, size_t *offset,
+                      int *rows, int *cols);
+/* Bytes of device workspace hpsgd_local_step_all needs for all K workers
+ * (activations saved for the backward pass, gradients, per-row losses). */
+size_t hpsgd_workspace_bytes(const hpsgd_ctx *ctx);
+
+/* ---- local training step (Alg. 2: compute the local gradients on the replica, then
+ *      "update replica" r_i <- r_i - mu * grad) ------------------------------------------
+ * One step for all K workers as grouped launches.  Worker k reads its parameters at
+ * replicas_in + k*replica_stride and writes the updated ones at replicas_out +
+ * k*replica_stride (replicas_out == replicas_in is allowed: in-place; any other overlap
+ * is HPSGD_EALIAS).  replica_stride >= P, in floats.
+ *   x: GRU classifier  fp32  [K][T][B][I]   (time-major batch)
+ *      GRU LM          int32 [K][T][B]      token ids in [0, V)
+ *      MLP             fp32  [K][B][d0]
+ *   y: int32 labels [K][B]; for the LM the next-token ids [K][T][B].
+ *      Labels outside [0, classes) are not checked on the device: caller's duty.
+ *   loss_out: device, K floats (mean cross-entropy of each worker's batch), or NULL.
+ *   workspace: hpsgd_workspace_bytes(ctx) bytes, 256-byte aligned, contents undefined
+ *      on entry and on exit; two calls that may run concurrently need two workspaces. */
+int hpsgd_local_step_all(hpsgd_ctx *ctx, const float *replicas_in, float *replicas_out,
+                         size_t replica_stride, const void *x, const int32_t *y, float lr,
+                         float *loss_out, void *workspace, void *hip_stream);
+
+/* The same for ONE worker (`worker` in [0, K) selects nothing but the workspace slice,
+ * so that different workers may be stepped on different streams).  loss_out: 1 float. */
+int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float *replica_out,
+                     const void *x, const int32_t *y, float lr, float *loss_out,
+                     void *workspace, void *hip_stream);
+
+/* ---- batch gather (Sec. 3.2: every worker samples its own sub-dataset) ----------------
+ * Time-major gather of n_idx samples: for b < n_idx, c < n_chunks
+ *     out[(c*n_idx + b)*chunk_bytes ...] = shard[idx[b]*row_bytes + c*chunk_bytes ...]
+ * n_chunks = 1 is a plain row gather.  chunk_bytes and row_bytes are multiples of 4,
+ * n_chunks*chunk_bytes <= row_bytes.  Bit-exact.  idx values are the caller's duty. */
+int hpsgd_gather_batch(const void *shard, const int32_t *idx, int n_idx, size_t row_bytes,
+                       int n_chunks, size_t chunk_bytes, void *out, void *hip_stream);
+
+/* ---- merge (Eq. 1; Alg. 3 "update global model" with the all-reduce taken as the mean
+ *      over the K workers): global[j] += (1/K) * sum_k (replicas[k][j] - snapshot[j]) ----
+ * replicas: HOST array of K DEVICE pointers (1 <= K <= HPSGD_MAX_WORKERS).
+ * snapshot: the global model as it was when the replicas were cloned; may equal `global`.
+ * The sum runs over k in increasing order in fp32.  P == 0 is a successful no-op.
+ * `global` must not overlap any replica (HPSGD_EALIAS). */
+int hpsgd_merge(float *global, const float *const *replicas, const float *snapshot, int K,
+                size_t P, void *hip_stream);
+
+/* ---- sync (Alg. 2 "make replica": r_i = clone(w)) -------------------------------------
+ * replica <- global, bit-exact. */
+int hpsgd_sync_replica(const float *global, float *replica, size_t P, void *hip_stream);
+/* One pass over `global` that writes all K replicas (HOST array of DEVICE pointers) and,
+ * if not NULL, the snapshot. */
+int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *snapshot,
+                   size_t P, void *hip_stream);
+
+/* Human-readable name of a status code (static string). */
+const char *hpsgd_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HPSGD_H */

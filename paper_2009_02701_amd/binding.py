@@ -1,0 +1,199 @@
+"""ctypes binding of libhpsgd.so: argument marshalling only.
+
+Every arithmetic step of the hot path runs in the library's HIP kernels; torch tensors
+are used for device memory and streams.  If the shared library is missing or a call
+returns an error code this module raises -- there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhpsgd.so")
+
+KIND = {"gru_cls": 0, "gru_lm": 1, "mlp": 2}
+PREC = {"fp32": 0, "bf16": 1}
+MAX_MLP_DIMS = 8
+
+EXPORTS = [
+    "hpsgd_create", "hpsgd_destroy", "hpsgd_param_count", "hpsgd_param_entries",
+    "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
+    "hpsgd_gather_batch", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
+]
+
+
+class ModelDesc(C.Structure):
+    _fields_ = [("kind", C.c_int), ("prec", C.c_int), ("layers", C.c_int), ("input", C.c_int),
+                ("hidden", C.c_int), ("seq_len", C.c_int), ("batch", C.c_int), ("classes", C.c_int),
+                ("vocab", C.c_int), ("embed", C.c_int), ("n_mlp_dims", C.c_int),
+                ("mlp_dims", C.c_int * MAX_MLP_DIMS)]
+
+
+class HpsgdError(RuntimeError):
+    def __init__(self, code, what):
+        super().__init__(f"{what}: {code}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library():
+    """Load libhpsgd.so (built in-tree by __graft_entry__.build()); raise if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(LIB_PATH)
+    vp, sz, i32p = C.c_void_p, C.c_size_t, C.c_void_p
+    lib.hpsgd_create.argtypes = [C.POINTER(ModelDesc), C.c_int, C.POINTER(vp)]
+    lib.hpsgd_destroy.argtypes = [vp]
+    lib.hpsgd_param_count.argtypes = [vp]
+    lib.hpsgd_param_count.restype = sz
+    lib.hpsgd_param_entries.argtypes = [vp]
+    lib.hpsgd_param_entry.argtypes = [vp, C.c_int, C.POINTER(C.c_char_p), C.POINTER(sz),
+                                      C.POINTER(C.c_int), C.POINTER(C.c_int)]
+    lib.hpsgd_workspace_bytes.argtypes = [vp]
+    lib.hpsgd_workspace_bytes.restype = sz
+    lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
+    lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
+    lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
+    lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
+    lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
+    lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
+    lib.hpsgd_strerror.argtypes = [C.c_int]
+    lib.hpsgd_strerror.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise HpsgdError(f"{rc} ({load_library().hpsgd_strerror(rc).decode()})", what)
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr() if t is not None else None)
+
+
+def make_desc(cfg: dict) -> ModelDesc:
+    d = ModelDesc()
+    d.kind = KIND[cfg["kind"]]
+    d.prec = PREC[cfg.get("prec", "fp32")]
+    for f in ("layers", "input", "hidden", "seq_len", "batch", "classes", "vocab", "embed"):
+        setattr(d, f, int(cfg.get(f, 0)))
+    dims = cfg.get("dims", [])
+    d.n_mlp_dims = len(dims)
+    for i, v in enumerate(dims[:MAX_MLP_DIMS]):
+        d.mlp_dims[i] = int(v)
+    return d
+
+
+class Context:
+    """hpsgd_ctx: the model every worker trains, K workers, flat layout and workspace size."""
+
+    def __init__(self, cfg: dict, K: int | None = None):
+        self.lib = load_library()
+        self.cfg = dict(cfg)
+        self.K = int(cfg["K"] if K is None else K)
+        self._h = C.c_void_p()
+        desc = make_desc(cfg)
+        _check(self.lib.hpsgd_create(C.byref(desc), self.K, C.byref(self._h)), "hpsgd_create")
+        self.P = int(self.lib.hpsgd_param_count(self._h))
+        self.stride = (self.P + 3) // 4 * 4
+        self.entries = []
+        for i in range(self.lib.hpsgd_param_entries(self._h)):
+            name, off, rows, cols = C.c_char_p(), C.c_size_t(), C.c_int(), C.c_int()
+            _check(self.lib.hpsgd_param_entry(self._h, i, C.byref(name), C.byref(off), C.byref(rows),
+                                              C.byref(cols)), "hpsgd_param_entry")
+            self.entries.append((name.value.decode(), int(off.value), int(rows.value), int(cols.value)))
+        self.workspace_bytes = int(self.lib.hpsgd_workspace_bytes(self._h))
+
+    def __del__(self):
+        if getattr(self, "_h", None) and self._h.value:
+            self.lib.hpsgd_destroy(self._h)
+            self._h = C.c_void_p()
+
+    # ---- flat layout helpers (host side, numpy) ----
+    def flatten(self, params: dict) -> np.ndarray:
+        flat = np.zeros(self.P, np.float32)
+        for name, off, rows, cols in self.entries:
+            flat[off:off + rows * cols] = np.asarray(params[name], np.float32).reshape(-1)
+        return flat
+
+    def unflatten(self, flat) -> dict:
+        flat = np.asarray(flat)
+        out = {}
+        for name, off, rows, cols in self.entries:
+            v = flat[off:off + rows * cols]
+            out[name] = v.reshape(rows, cols) if cols > 1 or name.endswith((".W", ".W_ih", ".W_hh", ".E")) \
+                else v.reshape(rows)
+        return out
+
+    def new_workspace(self, device="cuda"):
+        return torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=device)
+
+    @staticmethod
+    def _ws_ptr(ws):
+        p = ws.data_ptr()
+        return C.c_void_p((p + 255) // 256 * 256)
+
+    # ---- entry points ----
+    def local_step_all(self, replicas_in, replicas_out, x, y, lr, loss_out, workspace, stream=None):
+        """replicas_*: float32 [K, stride] tensors (row k = worker k's flat replica)."""
+        _check(self.lib.hpsgd_local_step_all(self._h, _ptr(replicas_in), _ptr(replicas_out),
+                                             replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
+                                             _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
+               "hpsgd_local_step_all")
+
+    def local_step(self, worker, replica_in, replica_out, x, y, lr, loss_out, workspace, stream=None):
+        _check(self.lib.hpsgd_local_step(self._h, int(worker), _ptr(replica_in), _ptr(replica_out),
+                                         _ptr(x), _ptr(y), float(lr), _ptr(loss_out),
+                                         self._ws_ptr(workspace), _stream(stream)),
+               "hpsgd_local_step")
+
+
+def _ptr_array(tensors):
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def merge(global_, replicas, snapshot, stream=None):
+    """global += mean_k(replicas[k] - snapshot); `replicas` is a list of K flat tensors (or a [K, n] tensor)."""
+    reps = list(replicas)
+    P = global_.numel()
+    _check(load_library().hpsgd_merge(_ptr(global_), _ptr_array(reps), _ptr(snapshot), len(reps), P,
+                                      _stream(stream)), "hpsgd_merge")
+
+
+def sync_replica(global_, replica, stream=None):
+    _check(load_library().hpsgd_sync_replica(_ptr(global_), _ptr(replica), global_.numel(),
+                                             _stream(stream)), "hpsgd_sync_replica")
+
+
+def sync_all(global_, replicas, snapshot, stream=None):
+    reps = list(replicas)
+    _check(load_library().hpsgd_sync_all(_ptr(global_), _ptr_array(reps), len(reps), _ptr(snapshot),
+                                         global_.numel(), _stream(stream)), "hpsgd_sync_all")
+
+
+def gather_batch(shard, idx, n_chunks, chunk_elems, out, row_elems=None, stream=None):
+    """Time-major gather: out[c, b, :] = shard[idx[b], c*chunk : (c+1)*chunk] (4-byte elements)."""
+    es = shard.element_size()
+    row = (shard[0].numel() if row_elems is None else row_elems) * es
+    _check(load_library().hpsgd_gather_batch(_ptr(shard), _ptr(idx), idx.numel(), row, int(n_chunks),
+                                             int(chunk_elems) * es, _ptr(out), _stream(stream)),
+           "hpsgd_gather_batch")

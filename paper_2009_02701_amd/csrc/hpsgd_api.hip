@@ -1,0 +1,481 @@
+// C-ABI layer: argument validation, the flat parameter layout, the workspace layout and
+// the launch plan of one local training step.  Host code only; every arithmetic step runs
+// in the kernels declared in kernels.h.
+#include "../../include/hpsgd.h"
+
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+using namespace hpsgd;
+
+namespace {
+
+struct Entry {
+  std::string name;
+  size_t offset;
+  int rows, cols;
+};
+
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Region {  // one workspace buffer: K slices of `stride` floats
+  size_t offset = 0, stride = 0;
+};
+
+}  // namespace
+
+struct hpsgd_ctx {
+  hpsgd_model_desc d;
+  int K;
+  std::vector<Entry> entries;
+  size_t P = 0;
+  size_t ws_floats = 0;
+  // workspace regions (floats)
+  Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss;
+  std::vector<Region> hs, sv;   // per GRU layer
+  std::vector<Region> act;      // per MLP layer output
+
+  int find(const std::string& n) const {
+    for (size_t i = 0; i < entries.size(); ++i)
+      if (entries[i].name == n) return (int)i;
+    return -1;
+  }
+  size_t off(const std::string& n) const { return entries[find(n)].offset; }
+
+  Region alloc(size_t per_worker) {
+    Region r;
+    r.stride = round_up(per_worker, 64);
+    r.offset = ws_floats;
+    ws_floats += r.stride * (size_t)K;
+    return r;
+  }
+};
+
+namespace {
+
+void add_entry(hpsgd_ctx* c, const std::string& name, int rows, int cols) {
+  c->entries.push_back({name, c->P, rows, cols});
+  c->P += (size_t)rows * (size_t)cols;
+}
+
+int build_layout(hpsgd_ctx* c) {
+  const hpsgd_model_desc& d = c->d;
+  const long big = 1L << 30;
+  if (d.kind == HPSGD_GRU_CLASSIFIER || d.kind == HPSGD_GRU_LM) {
+    const bool lm = d.kind == HPSGD_GRU_LM;
+    if (d.layers < 1 || d.layers > 16 || d.hidden < 1 || d.seq_len < 1 || d.batch < 1) return HPSGD_ESHAPE;
+    if (lm ? (d.vocab < 2 || d.embed < 1) : (d.input < 1 || d.classes < 2)) return HPSGD_ESHAPE;
+    if ((long)d.seq_len * d.batch * 4L * d.hidden >= big) return HPSGD_ESHAPE;
+    if (d.seq_len > 65535) return HPSGD_ESHAPE;
+    int width = lm ? d.embed : d.input;
+    const int classes = lm ? d.vocab : d.classes;
+    if ((long)d.seq_len * d.batch * (long)classes >= big) return HPSGD_ESHAPE;
+    if (lm) add_entry(c, "embed.E", d.vocab, d.embed);
+    for (int l = 0; l < d.layers; ++l) {
+      const std::string p = "l" + std::to_string(l);
+      add_entry(c, p + ".W_ih", 3 * d.hidden, width);
+      add_entry(c, p + ".W_hh", 3 * d.hidden, d.hidden);
+      add_entry(c, p + ".b_ih", 3 * d.hidden, 1);
+      add_entry(c, p + ".b_hh", 3 * d.hidden, 1);
+      width = d.hidden;
+    }
+    add_entry(c, "head.W", classes, d.hidden);
+    add_entry(c, "head.b", classes, 1);
+
+    const size_t TB = (size_t)d.seq_len * d.batch, H = d.hidden;
+    c->grad = c->alloc(c->P);
+    if (lm) c->xe = c->alloc(TB * d.embed);
+    for (int l = 0; l < d.layers; ++l) {
+      c->hs.push_back(c->alloc((TB + d.batch) * H));
+      c->sv.push_back(c->alloc(TB * 4 * H));
+    }
+    c->gx = c->alloc(TB * 3 * H);
+    c->dgh = c->alloc(TB * 3 * H);
+    c->gh = c->alloc((size_t)d.batch * 3 * H);
+    c->D = c->alloc((size_t)d.batch * H);
+    size_t wmax = H;
+    if (lm && (size_t)d.embed > wmax) wmax = d.embed;
+    c->dx = c->alloc(TB * wmax);
+    const size_t nrows = lm ? TB : (size_t)d.batch;
+    c->logits = c->alloc(nrows * classes);
+    c->rowloss = c->alloc(nrows);
+  } else if (d.kind == HPSGD_MLP) {
+    if (d.n_mlp_dims < 2 || d.n_mlp_dims > HPSGD_MAX_MLP_DIMS || d.batch < 1) return HPSGD_ESHAPE;
+    for (int i = 0; i < d.n_mlp_dims; ++i)
+      if (d.mlp_dims[i] < 1 || (long)d.mlp_dims[i] * d.batch >= big) return HPSGD_ESHAPE;
+    if (d.mlp_dims[d.n_mlp_dims - 1] < 2) return HPSGD_ESHAPE;
+    for (int i = 0; i + 1 < d.n_mlp_dims; ++i) {
+      const std::string p = "fc" + std::to_string(i);
+      add_entry(c, p + ".W", d.mlp_dims[i + 1], d.mlp_dims[i]);
+      add_entry(c, p + ".b", d.mlp_dims[i + 1], 1);
+    }
+    c->grad = c->alloc(c->P);
+    for (int i = 1; i < d.n_mlp_dims; ++i) c->act.push_back(c->alloc((size_t)d.batch * d.mlp_dims[i]));
+    c->rowloss = c->alloc(d.batch);
+  } else {
+    return HPSGD_EINVAL;
+  }
+  return HPSGD_OK;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a0 < b0 + nb && b0 < a0 + na;
+}
+
+#define HIP_TRY(expr)                       \
+  do {                                      \
+    if ((expr) != hipSuccess) return HPSGD_EHIP; \
+  } while (0)
+
+// GEMM helper: C = op(A) op(B) for `groups` workers.
+int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda,
+         long sA, int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC,
+         int epi, const float* aux, long sAux) {
+  GemmDesc g;
+  g.A = A; g.lda = lda; g.strideA = sA; g.transA = tA;
+  g.B = B; g.ldb = ldb; g.strideB = sB; g.transB = tB;
+  g.C = C; g.ldc = ldc; g.strideC = sC;
+  g.aux = aux; g.strideAux = sAux;
+  g.M = M; g.N = N; g.Kd = Kd; g.groups = groups;
+  g.epilogue = epi; g.bf16 = bf16;
+  return launch_gemm(g, s) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
+}
+
+#define TRY(expr)                  \
+  do {                             \
+    int rc_ = (expr);              \
+    if (rc_ != HPSGD_OK) return rc_; \
+  } while (0)
+
+// One local step for `groups` workers whose workspace slices start at worker k0.
+int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, size_t rstride,
+             const void* x, const int32_t* y, float lr, float* loss_out, float* ws, hipStream_t s) {
+  const hpsgd_model_desc& d = c->d;
+  const int bf = d.prec == HPSGD_BF16_MFMA ? 1 : 0;
+  auto reg = [&](const Region& r) { return ws + r.offset + (size_t)k0 * r.stride; };
+  float* grad = reg(c->grad);
+  const long sG = (long)c->grad.stride;
+  const long sR = (long)rstride;
+  const int B = d.batch;
+
+  if (d.kind == HPSGD_MLP) {
+    const int L = d.n_mlp_dims - 1;
+    const int* dims = d.mlp_dims;
+    // forward
+    const float* a_in = (const float*)x;
+    long s_in = (long)B * dims[0];
+    for (int i = 0; i < L; ++i) {
+      const std::string p = "fc" + std::to_string(i);
+      float* a_out = reg(c->act[i]);
+      TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->off(p + ".W"),
+               dims[i], sR, 1, a_out, dims[i + 1], (long)c->act[i].stride,
+               i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->off(p + ".b"), sR));
+      a_in = a_out;
+      s_in = (long)c->act[i].stride;
+    }
+    // loss; the logits buffer becomes the output delta
+    float* delta = reg(c->act[L - 1]);
+    float* rowloss = reg(c->rowloss);
+    HIP_TRY(launch_softmax_ce(delta, (long)c->act[L - 1].stride, y, B, delta, rowloss,
+                              (long)c->rowloss.stride, B, dims[L], groups, s));
+    if (loss_out) HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, B, groups, s));
+    // backward
+    for (int i = L - 1; i >= 0; --i) {
+      const std::string p = "fc" + std::to_string(i);
+      const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;
+      const long s_prev = i > 0 ? (long)c->act[i - 1].stride : (long)B * dims[0];
+      const long s_delta = (long)c->act[i].stride;
+      // dW = delta^T a_prev
+      TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
+               s_prev, 0, grad + c->off(p + ".W"), dims[i], sG, EPI_STORE, nullptr, 0));
+      HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + c->off(p + ".b"), sG, B, dims[i + 1],
+                            groups, s));
+      if (i > 0) {
+        // delta_prev = (delta W) * [a_prev > 0], written over a_prev
+        float* dprev = reg(c->act[i - 1]);
+        TRY(gemm(s, groups, bf, B, dims[i], dims[i + 1], delta, dims[i + 1], s_delta, 0,
+                 rin + c->off(p + ".W"), dims[i], sR, 0, dprev, dims[i], s_prev, EPI_RELU_MASK, dprev,
+                 s_prev));
+        delta = dprev;
+      }
+    }
+  } else {
+    const bool lm = d.kind == HPSGD_GRU_LM;
+    const int T = d.seq_len, H = d.hidden, L = d.layers;
+    const int TB = T * B;
+    const int classes = lm ? d.vocab : d.classes;
+    const int32_t* tok = (const int32_t*)x;
+    float* gx = reg(c->gx);
+    float* dgh = reg(c->dgh);
+    float* gh = reg(c->gh);
+    float* D = reg(c->D);
+    float* dx = reg(c->dx);
+    float* logits = reg(c->logits);
+    float* rowloss = reg(c->rowloss);
+    const long s_gx = (long)c->gx.stride, s_gh = (long)c->gh.stride, s_D = (long)c->D.stride;
+    const long s_dx = (long)c->dx.stride, s_log = (long)c->logits.stride;
+
+    // ---- forward
+    const float* lin = (const float*)x;
+    long s_lin = (long)TB * d.input;
+    int width = d.input;
+    if (lm) {
+      float* xe = reg(c->xe);
+      HIP_TRY(launch_embed_fwd(rin + c->off("embed.E"), sR, tok, TB, xe, (long)c->xe.stride, TB,
+                               d.embed, groups, s));
+      lin = xe;
+      s_lin = (long)c->xe.stride;
+      width = d.embed;
+    }
+    for (int l = 0; l < L; ++l) {
+      const std::string p = "l" + std::to_string(l);
+      float* hs = reg(c->hs[l]);
+      float* sv = reg(c->sv[l]);
+      const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
+      HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s));
+      TRY(gemm(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, rin + c->off(p + ".W_ih"), width,
+               sR, 1, gx, 3 * H, s_gx, EPI_BIAS, rin + c->off(p + ".b_ih"), sR));
+      for (int t = 0; t < T; ++t) {
+        TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0,
+                 rin + c->off(p + ".W_hh"), H, sR, 1, gh, 3 * H, s_gh, EPI_BIAS,
+                 rin + c->off(p + ".b_hh"), sR));
+        HIP_TRY(launch_gru_cell_fwd(gx + (size_t)t * B * 3 * H, s_gx, gh, s_gh, hs + (size_t)t * B * H,
+                                    hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
+                                    s_sv, B, H, groups, s));
+      }
+      lin = hs + (size_t)B * H;
+      s_lin = s_hs;
+      width = H;
+    }
+    // ---- head and loss
+    const float* top = reg(c->hs[L - 1]);
+    const long s_top = (long)c->hs[L - 1].stride;
+    const int nrows = lm ? TB : B;
+    const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
+    const size_t oW = c->off("head.W"), ob = c->off("head.b");
+    TRY(gemm(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
+             s_log, EPI_BIAS, rin + ob, sR));
+    HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
+                              classes, groups, s));
+    if (loss_out)
+      HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
+    // ---- backward: head
+    TRY(gemm(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW,
+             H, sG, EPI_STORE, nullptr, 0));
+    HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
+    const float* above = nullptr;
+    if (lm) {
+      TRY(gemm(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H,
+               s_dx, EPI_STORE, nullptr, 0));
+      above = dx;
+      HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
+    } else {
+      TRY(gemm(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
+               EPI_STORE, nullptr, 0));
+    }
+    // ---- backward: GRU layers, top to bottom
+    for (int l = L - 1; l >= 0; --l) {
+      const std::string p = "l" + std::to_string(l);
+      const float* hs = reg(c->hs[l]);
+      const float* sv = reg(c->sv[l]);
+      const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
+      const int win = l > 0 ? H : (lm ? d.embed : d.input);
+      const float* layer_in;
+      long s_layer_in;
+      if (l > 0) {
+        layer_in = reg(c->hs[l - 1]) + (size_t)B * H;
+        s_layer_in = (long)c->hs[l - 1].stride;
+      } else if (lm) {
+        layer_in = reg(c->xe);
+        s_layer_in = (long)c->xe.stride;
+      } else {
+        layer_in = (const float*)x;
+        s_layer_in = (long)TB * d.input;
+      }
+      float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
+      for (int t = T - 1; t >= 0; --t) {
+        HIP_TRY(launch_gru_cell_bwd(D, s_D, above ? above + (size_t)t * B * H : nullptr, s_dx,
+                                    sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
+                                    dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx, B, H,
+                                    groups, s));
+        if (t > 0)
+          TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0,
+                   rin + c->off(p + ".W_hh"), H, sR, 0, D, H, s_D, EPI_ACCUM, nullptr, 0));
+      }
+      TRY(gemm(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
+               grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0));
+      TRY(gemm(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0,
+               grad + c->off(p + ".W_hh"), H, sG, EPI_STORE, nullptr, 0));
+      HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
+      HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
+      if (l > 0 || lm) {
+        TRY(gemm(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, rin + c->off(p + ".W_ih"), win, sR,
+                 0, dx, win, s_dx, EPI_STORE, nullptr, 0));
+        above = dx;
+      }
+      if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
+    }
+    if (lm) {
+      const size_t oE = c->off("embed.E");
+      HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
+      HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, s));
+    }
+  }
+  // ---- commit (Alg. 2 "update replica")
+  HIP_TRY(launch_commit(rin, rout, rstride, grad, (size_t)sG, lr, groups, c->P, s));
+  return HPSGD_OK;
+}
+
+int check_step_args(const hpsgd_ctx* c, const float* rin, float* rout, size_t rstride, int groups,
+                    const void* x, const int32_t* y, const void* ws) {
+  if (!c || !rin || !rout || !x || !y) return HPSGD_EINVAL;
+  if (!ws) return HPSGD_EWORKSPACE;
+  if (((uintptr_t)ws & 255) != 0) return HPSGD_EWORKSPACE;
+  if (!aligned16(rin) || !aligned16(rout) || !aligned16(x) || ((uintptr_t)y & 3) != 0) return HPSGD_EALIGN;
+  if (groups > 1 && (rstride < c->P || (rstride & 3) != 0)) return HPSGD_EALIGN;
+  const size_t span = ((size_t)(groups - 1) * rstride + c->P) * sizeof(float);
+  if (rin != rout && overlaps(rin, span, rout, span)) return HPSGD_EALIAS;
+  const size_t ws_bytes = c->ws_floats * sizeof(float);
+  if (overlaps(ws, ws_bytes, rin, span) || overlaps(ws, ws_bytes, rout, span)) return HPSGD_EALIAS;
+  return HPSGD_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int hpsgd_create(const hpsgd_model_desc* desc, int K, hpsgd_ctx** out) {
+  if (!desc || !out) return HPSGD_EINVAL;
+  *out = nullptr;
+  if (K < 1 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;
+  if (desc->prec != HPSGD_FP32 && desc->prec != HPSGD_BF16_MFMA) return HPSGD_EINVAL;
+  hpsgd_ctx* c = new (std::nothrow) hpsgd_ctx();
+  if (!c) return HPSGD_EINVAL;
+  c->d = *desc;
+  c->K = K;
+  const int rc = build_layout(c);
+  if (rc != HPSGD_OK) {
+    delete c;
+    return rc;
+  }
+  *out = c;
+  return HPSGD_OK;
+}
+
+int hpsgd_destroy(hpsgd_ctx* ctx) {
+  delete ctx;
+  return HPSGD_OK;
+}
+
+size_t hpsgd_param_count(const hpsgd_ctx* ctx) { return ctx ? ctx->P : 0; }
+int hpsgd_param_entries(const hpsgd_ctx* ctx) { return ctx ? (int)ctx->entries.size() : 0; }
+
+int hpsgd_param_entry(const hpsgd_ctx* ctx, int i, const char** name, size_t* offset, int* rows,
+                      int* cols) {
+  if (!ctx || i < 0 || i >= (int)ctx->entries.size()) return HPSGD_EINVAL;
+  const Entry& e = ctx->entries[i];
+  if (name) *name = e.name.c_str();
+  if (offset) *offset = e.offset;
+  if (rows) *rows = e.rows;
+  if (cols) *cols = e.cols;
+  return HPSGD_OK;
+}
+
+size_t hpsgd_workspace_bytes(const hpsgd_ctx* ctx) { return ctx ? ctx->ws_floats * sizeof(float) : 0; }
+
+int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,
+                         size_t replica_stride, const void* x, const int32_t* y, float lr,
+                         float* loss_out, void* workspace, void* hip_stream) {
+  if (!ctx) return HPSGD_EINVAL;
+  TRY(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
+  return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
+                  (float*)workspace, (hipStream_t)hip_stream);
+}
+
+int hpsgd_local_step(hpsgd_ctx* ctx, int worker, const float* replica_in, float* replica_out,
+                     const void* x, const int32_t* y, float lr, float* loss_out, void* workspace,
+                     void* hip_stream) {
+  if (!ctx || worker < 0 || worker >= ctx->K) return HPSGD_EINVAL;
+  TRY(check_step_args(ctx, replica_in, replica_out, ctx->P, 1, x, y, workspace));
+  return run_step(ctx, worker, 1, replica_in, replica_out, round_up(ctx->P, 4), x, y, lr, loss_out,
+                  (float*)workspace, (hipStream_t)hip_stream);
+}
+
+int hpsgd_gather_batch(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
+                       int n_chunks, size_t chunk_bytes, void* out, void* hip_stream) {
+  if (n_idx < 0 || n_chunks < 0) return HPSGD_EINVAL;
+  if (n_idx == 0 || n_chunks == 0 || chunk_bytes == 0) return HPSGD_OK;
+  if (!shard || !idx || !out) return HPSGD_EINVAL;
+  if ((row_bytes & 3) || (chunk_bytes & 3) || ((uintptr_t)shard & 3) || ((uintptr_t)out & 3) ||
+      ((uintptr_t)idx & 3))
+    return HPSGD_EALIGN;
+  if ((size_t)n_chunks * chunk_bytes > row_bytes || n_chunks > 65535) return HPSGD_ESHAPE;
+  return launch_gather(shard, idx, n_idx, row_bytes, n_chunks, chunk_bytes, out,
+                       (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
+}
+
+int hpsgd_merge(float* global, const float* const* replicas, const float* snapshot, int K, size_t P,
+                void* hip_stream) {
+  if (K < 1 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;
+  if (P == 0) return HPSGD_OK;
+  if (!global || !replicas || !snapshot) return HPSGD_EINVAL;
+  if (!aligned16(global) || !aligned16(snapshot)) return HPSGD_EALIGN;
+  PtrPack pk;
+  for (int k = 0; k < K; ++k) {
+    if (!replicas[k]) return HPSGD_EINVAL;
+    if (!aligned16(replicas[k])) return HPSGD_EALIGN;
+    if (overlaps(global, P * sizeof(float), replicas[k], P * sizeof(float))) return HPSGD_EALIAS;
+    pk.p[k] = const_cast<float*>(replicas[k]);
+  }
+  if (snapshot != global && overlaps(global, P * sizeof(float), snapshot, P * sizeof(float)))
+    return HPSGD_EALIAS;
+  return launch_merge(global, pk, snapshot, K, P, (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK
+                                                                                          : HPSGD_EHIP;
+}
+
+int hpsgd_sync_all(const float* global, float* const* replicas, int K, float* snapshot, size_t P,
+                   void* hip_stream) {
+  if (K < 0 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;
+  if (P == 0) return HPSGD_OK;
+  if (!global || (K > 0 && !replicas)) return HPSGD_EINVAL;
+  if (!aligned16(global) || (snapshot && !aligned16(snapshot))) return HPSGD_EALIGN;
+  PtrPack pk;
+  for (int k = 0; k < K; ++k) {
+    if (!replicas[k]) return HPSGD_EINVAL;
+    if (!aligned16(replicas[k])) return HPSGD_EALIGN;
+    if (overlaps(global, P * sizeof(float), replicas[k], P * sizeof(float))) return HPSGD_EALIAS;
+    pk.p[k] = replicas[k];
+  }
+  if (snapshot && overlaps(global, P * sizeof(float), snapshot, P * sizeof(float))) return HPSGD_EALIAS;
+  if (K == 0 && !snapshot) return HPSGD_OK;
+  return launch_sync_all(global, pk, K, snapshot, P, (hipStream_t)hip_stream) == hipSuccess
+             ? HPSGD_OK
+             : HPSGD_EHIP;
+}
+
+int hpsgd_sync_replica(const float* global, float* replica, size_t P, void* hip_stream) {
+  float* one[1] = {replica};
+  if (!replica) return P == 0 ? HPSGD_OK : HPSGD_EINVAL;
+  return hpsgd_sync_all(global, one, 1, nullptr, P, hip_stream);
+}
+
+const char* hpsgd_strerror(int status) {
+  switch (status) {
+    case HPSGD_OK: return "ok";
+    case HPSGD_EINVAL: return "invalid argument";
+    case HPSGD_ESHAPE: return "unsupported or inconsistent shape";
+    case HPSGD_EALIGN: return "pointer or stride not aligned";
+    case HPSGD_EALIAS: return "buffers overlap";
+    case HPSGD_EWORKSPACE: return "workspace null or misaligned";
+    case HPSGD_EUNSUPPORTED: return "not supported";
+    case HPSGD_EHIP: return "HIP call failed";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

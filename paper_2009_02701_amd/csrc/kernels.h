@@ -1,0 +1,77 @@
+// Internal launch interface between the C-ABI layer and the HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#define HPSGD_KMAX 32
+
+namespace hpsgd {
+
+struct PtrPack {  // K device pointers passed by value as a kernel argument
+  float* p[HPSGD_KMAX];
+};
+
+// ---- HBM-streaming kernels over flat parameter buffers ----
+hipError_t launch_merge(float* global, const PtrPack& replicas, const float* snapshot, int K,
+                        size_t P, hipStream_t s);
+hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, float* snapshot,
+                           size_t P, hipStream_t s);
+// out[k] = in[k] - lr * grad[k] for K strided slices of P floats
+hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
+                         size_t grad_stride, float lr, int K, size_t P, hipStream_t s);
+// p[g*stride + i] = 0 for i < n (p 16-byte aligned, stride a multiple of 4)
+hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s);
+hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
+                         int n_chunks, size_t chunk_bytes, void* out, hipStream_t s);
+
+// ---- grouped GEMM on the fp32 / bf16 matrix cores ----
+enum Epilogue : int {
+  EPI_STORE = 0,      // C = acc
+  EPI_BIAS = 1,       // C = acc + bias[n]
+  EPI_BIAS_RELU = 2,  // C = max(acc + bias[n], 0)
+  EPI_ACCUM = 3,      // C += acc
+  EPI_RELU_MASK = 4   // C = acc * (mask[m,n] > 0)      (mask has C's layout)
+};
+
+struct GemmDesc {
+  // C[g] (M x N, row-major, ldc) = op(A[g]) (M x Kd) * op(B[g]) (Kd x N)
+  const float* A; long lda; long strideA; int transA;  // transA=0: A stored [M][Kd]; 1: stored [Kd][M]
+  const float* B; long ldb; long strideB; int transB;  // transB=0: B stored [Kd][N]; 1: stored [N][Kd]
+  float* C; long ldc; long strideC;
+  const float* aux; long strideAux;                    // bias [N] or mask [M][N] (ldc)
+  int M, N, Kd, groups;
+  int epilogue;
+  int bf16;                                            // round operands to bf16, use the bf16 MFMA
+};
+hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
+
+// ---- GRU cell, loss, reductions ----
+// forward cell for one time step of all groups:
+//   gx [B][3H] (b_ih included), gh [B][3H] (b_hh included), h_prev [B][H] -> h [B][H], saved [B][4H] = r|z|n|q
+hipError_t launch_gru_cell_fwd(const float* gx, long s_gx, const float* gh, long s_gh,
+                               const float* h_prev, float* h, long s_h, float* saved, long s_saved,
+                               int B, int H, int groups, hipStream_t s);
+// backward cell: dh = D + above (above nullable); writes dgx [B][3H], dgh [B][3H], D = dh*z
+hipError_t launch_gru_cell_bwd(float* D, long s_D, const float* above, long s_above,
+                               const float* saved, long s_saved, const float* h_prev, long s_h,
+                               float* dgx, float* dgh, long s_dg, int B, int H, int groups,
+                               hipStream_t s);
+// mean softmax cross-entropy over N rows of C logits; dlogits = (p - onehot)/N; row losses to rowloss
+hipError_t launch_softmax_ce(const float* logits, long s_logits, const int32_t* y, long s_y,
+                             float* dlogits, float* rowloss, long s_rowloss, int N, int C,
+                             int groups, hipStream_t s);
+// loss[g] = (1/N) sum_i rowloss[g][i], fixed order
+hipError_t launch_loss_mean(const float* rowloss, long s_rowloss, float* loss, int N, int groups,
+                            hipStream_t s);
+// out[g][n] = sum_r in[g][r][n]
+hipError_t launch_colsum(const float* in, long ld, long s_in, float* out, long s_out, int R, int N,
+                         int groups, hipStream_t s);
+// embedding rows: out[g][i][:] = E[g][tok[g][i]][:]
+hipError_t launch_embed_fwd(const float* E, long s_E, const int32_t* tok, long s_tok, float* out,
+                            long s_out, int N, int Ew, int groups, hipStream_t s);
+// dE[g][v][:] = sum over positions i with tok[g][i]==v of dx[g][i][:], in increasing i; other rows untouched
+hipError_t launch_embed_bwd(const float* dx, long s_dx, const int32_t* tok, long s_tok, float* dE,
+                            long s_dE, int N, int Ew, int groups, hipStream_t s);
+
+}  // namespace hpsgd

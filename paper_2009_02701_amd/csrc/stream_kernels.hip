@@ -1,0 +1,203 @@
+// HBM-streaming kernels over flat fp32 parameter buffers: replica merge (Eq. 1), replica
+// sync (Alg. 2 "make replica"), SGD commit (Alg. 2 "update replica"), zero fill and the
+// time-major batch gather.  All are grid-stride loops over 16-byte vectors: every lane
+// keeps K+2 independent loads in flight and every wave reads and writes 1 KiB contiguous.
+#include "kernels.h"
+
+namespace hpsgd {
+
+static constexpr int kThreads = 256;
+static constexpr int kMaxBlocks = 256 * 8;  // 256 CUs, up to 8 resident blocks each
+
+static inline int stream_blocks(size_t n_items) {
+  size_t b = (n_items + kThreads - 1) / kThreads;
+  if (b > (size_t)kMaxBlocks) b = kMaxBlocks;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+// ---------------------------------------------------------------------------- merge
+// global[j] += (1/K) * sum_k (replica_k[j] - snapshot[j]); the sum over k runs in order.
+template <int KT>
+__global__ void __launch_bounds__(kThreads)
+merge_kernel(float* global, PtrPack rep, const float* snapshot, int Krt, float inv_k,
+             size_t n4, size_t P) {
+  const int K = KT > 0 ? KT : Krt;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+    const float4 s = reinterpret_cast<const float4*>(snapshot)[i];
+    const float4 g = reinterpret_cast<const float4*>(global)[i];
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const float4 r = reinterpret_cast<const float4*>(rep.p[k])[i];
+      acc.x += r.x - s.x;
+      acc.y += r.y - s.y;
+      acc.z += r.z - s.z;
+      acc.w += r.w - s.w;
+    }
+    float4 o;
+    o.x = g.x + acc.x * inv_k;
+    o.y = g.y + acc.y * inv_k;
+    o.z = g.z + acc.z * inv_k;
+    o.w = g.w + acc.w * inv_k;
+    reinterpret_cast<float4*>(global)[i] = o;
+  }
+  // ragged tail (P not a multiple of 4): the first block's first lanes
+  if (blockIdx.x == 0) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    if (j < P) {
+      const float s = snapshot[j];
+      float acc = 0.f;
+      for (int k = 0; k < K; ++k) acc += rep.p[k][j] - s;
+      global[j] = global[j] + acc * inv_k;
+    }
+  }
+}
+
+hipError_t launch_merge(float* global, const PtrPack& replicas, const float* snapshot, int K,
+                        size_t P, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t n4 = P / 4;
+  const int blocks = stream_blocks(n4);
+  const float inv_k = 1.0f / (float)K;
+#define HPSGD_MERGE_CASE(KT)                                                                  \
+  hipLaunchKernelGGL(merge_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, replicas, \
+                     snapshot, K, inv_k, n4, P)
+  switch (K) {
+    case 1: HPSGD_MERGE_CASE(1); break;
+    case 2: HPSGD_MERGE_CASE(2); break;
+    case 4: HPSGD_MERGE_CASE(4); break;
+    case 8: HPSGD_MERGE_CASE(8); break;
+    case 16: HPSGD_MERGE_CASE(16); break;
+    default: HPSGD_MERGE_CASE(0); break;
+  }
+#undef HPSGD_MERGE_CASE
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- sync
+template <int KT>
+__global__ void __launch_bounds__(kThreads)
+sync_kernel(const float* __restrict__ global, PtrPack rep, int Krt, float* snapshot, size_t n4,
+            size_t P) {
+  const int K = KT > 0 ? KT : Krt;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+    const float4 g = reinterpret_cast<const float4*>(global)[i];
+#pragma unroll
+    for (int k = 0; k < K; ++k) reinterpret_cast<float4*>(rep.p[k])[i] = g;
+    if (snapshot) reinterpret_cast<float4*>(snapshot)[i] = g;
+  }
+  if (blockIdx.x == 0) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    if (j < P) {
+      const float g = global[j];
+      for (int k = 0; k < K; ++k) rep.p[k][j] = g;
+      if (snapshot) snapshot[j] = g;
+    }
+  }
+}
+
+hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, float* snapshot,
+                           size_t P, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t n4 = P / 4;
+  const int blocks = stream_blocks(n4);
+#define HPSGD_SYNC_CASE(KT)                                                                  \
+  hipLaunchKernelGGL(sync_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, replicas, K, \
+                     snapshot, n4, P)
+  switch (K) {
+    case 1: HPSGD_SYNC_CASE(1); break;
+    case 2: HPSGD_SYNC_CASE(2); break;
+    case 4: HPSGD_SYNC_CASE(4); break;
+    case 8: HPSGD_SYNC_CASE(8); break;
+    case 16: HPSGD_SYNC_CASE(16); break;
+    default: HPSGD_SYNC_CASE(0); break;
+  }
+#undef HPSGD_SYNC_CASE
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- commit
+// out[k][j] = in[k][j] - lr * grad[k][j]
+__global__ void __launch_bounds__(kThreads)
+commit_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+              size_t grad_stride, float lr, size_t n4, size_t P) {
+  const int k = blockIdx.y;
+  const float* ink = in + (size_t)k * stride;
+  float* outk = out + (size_t)k * stride;
+  const float* gk = grad + (size_t)k * grad_stride;
+  const size_t step = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += step) {
+    const float4 w = reinterpret_cast<const float4*>(ink)[i];
+    const float4 g = reinterpret_cast<const float4*>(gk)[i];
+    float4 o;
+    o.x = w.x - lr * g.x;
+    o.y = w.y - lr * g.y;
+    o.z = w.z - lr * g.z;
+    o.w = w.w - lr * g.w;
+    reinterpret_cast<float4*>(outk)[i] = o;
+  }
+  if (blockIdx.x == 0) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    if (j < P) outk[j] = ink[j] - lr * gk[j];
+  }
+}
+
+hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
+                         size_t grad_stride, float lr, int K, size_t P, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t n4 = P / 4;
+  int blocks = stream_blocks(n4);
+  if (blocks * K > kMaxBlocks) blocks = (kMaxBlocks + K - 1) / K;
+  hipLaunchKernelGGL(commit_kernel, dim3(blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
+                     grad_stride, lr, n4, P);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- fill
+// p[g*stride + i] = 0 for i < n, g < groups
+__global__ void __launch_bounds__(kThreads) fill_zero_kernel(float* p, size_t n4, size_t n, size_t stride) {
+  float* pg = p + (size_t)blockIdx.y * stride;
+  const size_t step = (size_t)gridDim.x * kThreads;
+  const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += step)
+    reinterpret_cast<float4*>(pg)[i] = z;
+  if (blockIdx.x == 0) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    if (j < n) pg[j] = 0.f;
+  }
+}
+
+hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s) {
+  if (n == 0 || groups == 0) return hipSuccess;
+  const size_t n4 = n / 4;
+  int blocks = stream_blocks(n4);
+  if (blocks * groups > kMaxBlocks) blocks = (kMaxBlocks + groups - 1) / groups;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks, groups), dim3(kThreads), 0, s, p, n4, n, stride);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- gather
+// out[(c*n_idx + b)*chunk ...] = shard[idx[b]*row + c*chunk ...], in 4-byte words.
+__global__ void __launch_bounds__(kThreads)
+gather_kernel(const uint32_t* __restrict__ shard, const int32_t* __restrict__ idx, int n_idx,
+              size_t row_w, int n_chunks, size_t chunk_w, uint32_t* __restrict__ out) {
+  const size_t b = blockIdx.x;           // sample
+  const size_t c = blockIdx.y;           // chunk (time step)
+  const uint32_t* src = shard + (size_t)idx[b] * row_w + c * chunk_w;
+  uint32_t* dst = out + (c * (size_t)n_idx + b) * chunk_w;
+  for (size_t w = threadIdx.x; w < chunk_w; w += kThreads) dst[w] = src[w];
+}
+
+hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
+                         int n_chunks, size_t chunk_bytes, void* out, hipStream_t s) {
+  if (n_idx == 0 || n_chunks == 0 || chunk_bytes == 0) return hipSuccess;
+  hipLaunchKernelGGL(gather_kernel, dim3(n_idx, n_chunks), dim3(kThreads), 0, s,
+                     (const uint32_t*)shard, idx, n_idx, row_bytes / 4, n_chunks, chunk_bytes / 4,
+                     (uint32_t*)out);
+  return hipGetLastError();
+}
+
+}  // namespace hpsgd

@@ -1,0 +1,150 @@
+"""Device-side driver of the HPSGD schedules over the C-ABI library.
+
+Owns the device buffers (global model, two generations of K replicas and snapshots,
+workspace, resident data shards) and enqueues the library calls: batch gather, local
+step of all K workers, merge, sync.  Two schedules:
+
+  * s_seq(gamma, rounds): no staleness -- gamma local steps, merge, sync (Local SGD in the
+    gradient form of Eq. 1; gamma = 1 is SSGD).
+  * s_ovl(rounds): the paper's hierarchy (Sec. 3.1): the synchronising side (stream B) merges
+    the previous round's replica changes while the training side (stream A) already runs
+    the next local step on the other buffer generation; the global update therefore lands one
+    synchronisation late (Sec. 3.2, after Alg. 3).
+
+No arithmetic happens here: torch is used for memory, streams and events only.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as hb
+
+
+class Trainer:
+    def __init__(self, cfg: dict, init_params: dict, shards: list, orders: list, device="cuda"):
+        self.cfg = cfg
+        self.ctx = hb.Context(cfg)
+        self.K, self.P, self.stride = self.ctx.K, self.ctx.P, self.ctx.stride
+        dev = torch.device(device)
+        self.dev = dev
+        K, B = self.K, cfg["batch"]
+        flat = np.zeros(self.stride, np.float32)
+        flat[:self.P] = self.ctx.flatten(init_params)
+        self.G = torch.from_numpy(flat).to(dev)
+        self.S = [torch.zeros(self.stride, dtype=torch.float32, device=dev) for _ in range(2)]
+        self.R = [torch.zeros(K, self.stride, dtype=torch.float32, device=dev) for _ in range(2)]
+        self.ws = [self.ctx.new_workspace(dev), None]
+        self.loss = torch.zeros(K, dtype=torch.float32, device=dev)
+        self.losses = []
+        # resident shards and the batch order
+        kind = cfg["kind"]
+        self.kind = kind
+        self.xs = [torch.from_numpy(np.ascontiguousarray(s[0])).to(dev) for s in shards]
+        self.ys = [torch.from_numpy(np.ascontiguousarray(s[1])).to(dev) if s[1] is not None else None
+                   for s in shards]
+        self.order = [torch.from_numpy(np.ascontiguousarray(o)).to(dev) for o in orders]
+        self.n_batches = orders[0].size // B
+        if kind == "gru_cls":
+            T, I = cfg["seq_len"], cfg["input"]
+            self.xb = torch.zeros(K, T, B, I, dtype=torch.float32, device=dev)
+            self.yb = torch.zeros(K, B, dtype=torch.int32, device=dev)
+        elif kind == "mlp":
+            self.xb = torch.zeros(K, B, cfg["dims"][0], dtype=torch.float32, device=dev)
+            self.yb = torch.zeros(K, B, dtype=torch.int32, device=dev)
+        else:
+            T = cfg["seq_len"]
+            self.xb = torch.zeros(K, T, B, dtype=torch.int32, device=dev)
+            self.yb = torch.zeros(K, T, B, dtype=torch.int32, device=dev)
+        self.stream_a = torch.cuda.Stream(device=dev)
+        self.stream_b = torch.cuda.Stream(device=dev)
+        torch.cuda.synchronize(dev)
+
+    # ------------------------------------------------------------------ pieces
+    def gather(self, step: int, stream=None):
+        """Assemble every worker's mini-batch `step` from its resident shard (bit-exact)."""
+        cfg, B = self.cfg, self.cfg["batch"]
+        s = step % self.n_batches
+        for k in range(self.K):
+            idx = self.order[k][s * B:(s + 1) * B]
+            if self.kind == "gru_cls":
+                hb.gather_batch(self.xs[k], idx, cfg["seq_len"], cfg["input"], self.xb[k], stream=stream)
+                hb.gather_batch(self.ys[k], idx, 1, 1, self.yb[k], row_elems=1, stream=stream)
+            elif self.kind == "mlp":
+                hb.gather_batch(self.xs[k], idx, 1, cfg["dims"][0], self.xb[k], stream=stream)
+                hb.gather_batch(self.ys[k], idx, 1, 1, self.yb[k], row_elems=1, stream=stream)
+            else:
+                T = cfg["seq_len"]
+                tok = self.xs[k].view(-1)
+                hb.gather_batch(tok, idx, T, 1, self.xb[k], row_elems=T + 1, stream=stream)
+                hb.gather_batch(tok[1:], idx, T, 1, self.yb[k], row_elems=T + 1, stream=stream)
+
+    def local_step(self, gen: int, lr: float, stream=None, ws=0):
+        if self.ws[ws] is None:
+            self.ws[ws] = self.ctx.new_workspace(self.dev)
+        self.ctx.local_step_all(self.R[gen], self.R[gen], self.xb, self.yb, lr, self.loss,
+                                self.ws[ws], stream=stream)
+
+    def merge(self, gen: int, stream=None):
+        hb.merge(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
+                 self.S[gen][:self.P], stream=stream)
+
+    def sync_all(self, gen: int, stream=None):
+        hb.sync_all(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
+                    self.S[gen][:self.P], stream=stream)
+
+    def global_params(self) -> dict:
+        torch.cuda.synchronize(self.dev)
+        return self.ctx.unflatten(self.G[:self.P].cpu().numpy())
+
+    def replica_params(self, gen: int, k: int) -> dict:
+        torch.cuda.synchronize(self.dev)
+        return self.ctx.unflatten(self.R[gen][k, :self.P].cpu().numpy())
+
+    # ------------------------------------------------------------------ schedules
+    def s_seq(self, lr: float, gamma: int, rounds: int, record_loss=True):
+        st = self.stream_a
+        st.wait_stream(torch.cuda.current_stream())
+        step = 0
+        for _ in range(rounds):
+            self.sync_all(0, st)
+            for _ in range(gamma):
+                self.gather(step, st)
+                self.local_step(0, lr, st)
+                if record_loss:
+                    with torch.cuda.stream(st):
+                        self.losses.append(self.loss.clone())
+                step += 1
+            self.merge(0, st)
+        st.synchronize()
+
+    def s_ovl(self, lr: float, rounds: int, record_loss=True, single_stream=False):
+        """Overlapped schedule; with single_stream=True the same op list runs on one stream."""
+        sa = self.stream_a
+        sb = sa if single_stream else self.stream_b
+        sa.wait_stream(torch.cuda.current_stream())
+        self.sync_all(0, sa)
+        g = 0
+        ev_a = torch.cuda.Event()
+        ev_b = torch.cuda.Event()
+        ev_a.record(sa)
+        for t in range(rounds):
+            # stream B: merge of round t-1 (other generation); must follow that round's local step
+            if t > 0:
+                sb.wait_event(ev_a)
+                self.merge(1 - g, sb)
+            ev_b.record(sb)
+            # stream A: local step of round t on generation g
+            self.gather(t, sa)
+            self.local_step(g, lr, sa)
+            if record_loss:
+                with torch.cuda.stream(sa):
+                    self.losses.append(self.loss.clone())
+            # boundary: A waits for B, then clones the global model into the other generation
+            sa.wait_event(ev_b)
+            self.sync_all(1 - g, sa)
+            ev_a.record(sa)
+            g = 1 - g
+        self.merge(1 - g, sa)
+        sa.synchronize()
+        sb.synchronize()

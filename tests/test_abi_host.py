@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, reports the flat layout the workloads use, and rejects bad arguments before
+anything is launched."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2009_02701_amd import binding as hb
+from paper_2009_02701_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "hpsgd.h")).read()
+    declared = set(re.findall(r"\b(hpsgd_[a-z_]+)\s*\(", hdr))
+    assert declared == set(hb.EXPORTS), declared ^ set(hb.EXPORTS)
+    lib = C.CDLL(hb.LIB_PATH)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+@pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "gru_lm", "mlp"])
+def test_flat_layout_matches_workload_shapes(name):
+    cfg = wl.CONFIGS[name]
+    ctx = hb.Context(cfg)
+    shapes = wl.param_shapes(cfg)
+    assert ctx.P == wl.param_count(cfg)
+    assert [e[0] for e in ctx.entries] == [n for n, _ in shapes]
+    off = 0
+    for (n, o, rows, cols), (_, shp) in zip(ctx.entries, shapes):
+        assert o == off and rows * cols == int(np.prod(shp)) and rows == shp[0]
+        off += rows * cols
+    assert ctx.workspace_bytes > 4 * ctx.P * ctx.K
+
+
+def test_param_counts_of_the_five_configs():
+    assert hb.Context(wl.CONFIGS["tiny_gru"]).P == 5130
+    assert hb.Context(wl.CONFIGS["gru_cls"]).P == 991242
+    assert hb.Context(wl.CONFIGS["gru_lm"]).P == 23045904
+    assert hb.Context(wl.CONFIGS["mlp"]).P == 1863690
+
+
+def test_flatten_roundtrip():
+    cfg = wl.CONFIGS["tiny_gru"]
+    ctx = hb.Context(cfg)
+    p = wl.init_params(cfg)
+    back = ctx.unflatten(ctx.flatten(p))
+    for k in p:
+        assert back[k].shape == p[k].shape and np.array_equal(back[k], p[k])
+
+
+def test_create_rejects_bad_descriptions():
+    lib = hb.load_library()
+    h = C.c_void_p()
+    good = hb.make_desc(wl.CONFIGS["tiny_gru"])
+    assert lib.hpsgd_create(C.byref(good), 0, C.byref(h)) == 1          # K < 1
+    assert lib.hpsgd_create(C.byref(good), 33, C.byref(h)) == 1         # K > max
+    assert lib.hpsgd_create(None, 2, C.byref(h)) == 1
+    bad = hb.make_desc(wl.scaled(wl.CONFIGS["tiny_gru"], hidden=0))
+    assert lib.hpsgd_create(C.byref(bad), 2, C.byref(h)) == 2           # shape
+    bad = hb.make_desc(wl.scaled(wl.CONFIGS["mlp"], dims=[5]))
+    assert lib.hpsgd_create(C.byref(bad), 2, C.byref(h)) == 2
+    bad = hb.make_desc(wl.CONFIGS["tiny_gru"])
+    bad.kind = 9
+    assert lib.hpsgd_create(C.byref(bad), 2, C.byref(h)) == 1
+    assert not h.value
+
+
+def test_merge_and_sync_reject_bad_arguments_before_launch():
+    """Fake (never dereferenced) addresses: every call must fail in validation."""
+    lib = hb.load_library()
+    vp = C.c_void_p
+    A, B, S = 0x10000, 0x20000, 0x30000
+    reps = (vp * 2)(B, B + 0x8000)
+    assert lib.hpsgd_merge(vp(A), reps, vp(S), 0, 16, None) == 1         # K < 1
+    assert lib.hpsgd_merge(vp(A), reps, vp(S), 40, 16, None) == 1        # K > max
+    assert lib.hpsgd_merge(None, reps, vp(S), 2, 16, None) == 1          # null
+    assert lib.hpsgd_merge(vp(A), None, vp(S), 2, 16, None) == 1
+    assert lib.hpsgd_merge(vp(A + 4), reps, vp(S), 2, 16, None) == 3     # misaligned
+    bad = (vp * 2)(B, A + 16)
+    assert lib.hpsgd_merge(vp(A), bad, vp(S), 2, 16, None) == 4          # replica overlaps global
+    assert lib.hpsgd_merge(vp(A), reps, vp(A + 16), 2, 16, None) == 4    # partial snapshot overlap
+    assert lib.hpsgd_merge(vp(A), reps, vp(S), 2, 0, None) == 0          # empty: no-op
+    assert lib.hpsgd_sync_all(vp(A), reps, 2, vp(A), 16, None) == 4
+    assert lib.hpsgd_sync_all(vp(A), reps, 2, vp(S + 8), 16, None) == 3
+    assert lib.hpsgd_sync_replica(vp(A), None, 16, None) == 1
+    assert lib.hpsgd_sync_replica(vp(A), vp(A), 16, None) == 4
+    assert lib.hpsgd_gather_batch(vp(A), vp(B), 4, 6, 1, 4, vp(S), None) == 3   # row bytes not /4
+    assert lib.hpsgd_gather_batch(vp(A), vp(B), 4, 8, 3, 4, vp(S), None) == 2   # chunks exceed row
+    assert lib.hpsgd_gather_batch(vp(A), vp(B), -1, 8, 1, 4, vp(S), None) == 1
+
+
+def test_local_step_rejects_bad_arguments_before_launch():
+    lib = hb.load_library()
+    ctx = hb.Context(wl.CONFIGS["tiny_gru"])
+    vp = C.c_void_p
+    R, O, X, Y, W = 0x100000, 0x200000, 0x300000, 0x400000, 0x1000000
+    call = lambda r, o, stride, x, y, w: lib.hpsgd_local_step_all(ctx._h, vp(r), vp(o), stride, vp(x), vp(y),
+                                                                   0.1, None, vp(w), None)
+    assert call(0, O, 5132, X, Y, W) == 1
+    assert call(R, O, 5132, X, Y, 0) == 5
+    assert call(R, O, 5132, X, Y, W + 16) == 5
+    assert call(R + 4, O, 5132, X, Y, W) == 3
+    assert call(R, O, 5130, X, Y, W) == 3                                # stride not a multiple of 4
+    assert call(R, O, 5000, X, Y, W) == 3                                # stride < P
+    assert call(R, R + 64, 5132, X, Y, W) == 4                           # partial overlap in/out
+    assert call(R, O, 5132, X, Y, R) == 4                                # workspace over the replicas
+    assert lib.hpsgd_local_step(ctx._h, 2, vp(R), vp(O), vp(X), vp(Y), 0.1, None, vp(W), None) == 1
+    assert hb.load_library().hpsgd_strerror(4) == b"buffers overlap"

@@ -1,0 +1,135 @@
+"""GPU parity of hpsgd_local_step(_all) and of the schedules against the float64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hpsgd_oracle as oc
+from paper_2009_02701_amd import binding as hb
+from paper_2009_02701_amd import harness
+from paper_2009_02701_amd import workloads as wl
+
+from parity import TOL_BF16, TOL_FP32, rel_err, workload, worst_rel_err
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+# Small cases with sizes that are not multiples of any tile (ragged M, N and contraction
+# tails, unaligned tensor offsets) next to tile-aligned ones that span several tiles.
+SMALL = {
+    "gru_cls_ragged": wl.scaled(wl.CONFIGS["gru_cls"], input=13, hidden=40, seq_len=6, batch=5, classes=7, K=3),
+    "gru_cls_2layer": wl.scaled(wl.CONFIGS["gru_cls"], layers=2, input=24, hidden=72, seq_len=5, batch=9, classes=10, K=2),
+    "gru_cls_tiles": wl.scaled(wl.CONFIGS["gru_cls"], input=64, hidden=160, seq_len=4, batch=70, classes=10, K=2),
+    "tiny_gru": wl.CONFIGS["tiny_gru"],
+    "mlp_ragged": wl.scaled(wl.CONFIGS["mlp"], dims=[37, 70, 33, 5], batch=11, K=3),
+    "mlp_tiles": wl.scaled(wl.CONFIGS["mlp"], dims=[200, 300, 140, 10], batch=130, K=2),
+    "lm_small_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=50, embed=12, hidden=24, seq_len=7, batch=5, K=2),
+    "lm_tiles_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=300, embed=40, hidden=72, seq_len=6, batch=12, K=2),
+}
+
+
+def _one_step(cfg, lr):
+    """One local step of all K workers from the initial model; returns per-worker (replica', loss)."""
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.sync_all(0)
+    tr.gather(0)
+    tr.local_step(0, lr)
+    torch.cuda.synchronize()
+    loss = tr.loss.cpu().numpy()
+    return tr, init, batch_fn, [tr.replica_params(0, k) for k in range(cfg["K"])], loss
+
+
+@pytest.mark.parametrize("name", list(SMALL))
+def test_gradients_and_loss_match_oracle(name):
+    """The change of the replica under a large probe learning rate is -lr * gradient:
+    compares every gradient tensor and the loss of every worker."""
+    cfg = SMALL[name]
+    lr = 8.0
+    tr, init, batch_fn, reps, loss = _one_step(cfg, lr)
+    for k in range(cfg["K"]):
+        x, y = batch_fn(k, 0)
+        want_loss, g = oc.loss_and_grads(init, x, y)
+        assert abs(loss[k] - want_loss) <= TOL_FP32 * abs(want_loss), (k, loss[k], want_loss)
+        got_g = {n: (init[n].astype(np.float64) - reps[k][n].astype(np.float64)) / lr for n in init}
+        err, worst, errs = worst_rel_err(got_g, g)
+        assert err <= TOL_FP32, (k, worst, errs)
+
+
+@pytest.mark.parametrize("name", ["gru_cls_ragged", "mlp_ragged", "lm_small_fp32"])
+def test_lr_zero_leaves_replicas_bit_unchanged(name):
+    cfg = SMALL[name]
+    tr, init, _, reps, _ = _one_step(cfg, 0.0)
+    for k in range(cfg["K"]):
+        for n in init:
+            assert np.array_equal(reps[k][n].view(np.uint32), init[n].view(np.uint32)), n
+
+
+@pytest.mark.parametrize("name", ["gru_cls_ragged", "mlp_ragged", "lm_small_fp32"])
+def test_single_worker_entry_point_equals_grouped(name):
+    """hpsgd_local_step on worker k gives bit-identical results to that worker's slice of
+    hpsgd_local_step_all, out of place."""
+    cfg = SMALL[name]
+    tr, init, _, reps, loss = _one_step(cfg, cfg["lr"])
+    ctx = tr.ctx
+    flat = torch.from_numpy(ctx.flatten(init)).to(DEV)
+    for k in range(cfg["K"]):
+        out = torch.zeros_like(flat)
+        l1 = torch.zeros(1, device=DEV)
+        ctx.local_step(k, flat, out, tr.xb[k], tr.yb[k], cfg["lr"], l1, tr.ws[0])
+        torch.cuda.synchronize()
+        got = ctx.unflatten(out.cpu().numpy())
+        for n in init:
+            assert np.array_equal(got[n].view(np.uint32), reps[k][n].view(np.uint32)), (k, n)
+        assert float(l1[0]) == float(loss[k])
+
+
+def _schedule_parity(cfg, kind, tol, **kw):
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    K, lr = cfg["K"], cfg["lr"]
+    if kind == "seq":
+        tr.s_seq(lr, kw["gamma"], kw["rounds"])
+        want, losses = oc.s_seq(init, batch_fn, K, lr, kw["gamma"], kw["rounds"])
+    else:
+        tr.s_ovl(lr, kw["rounds"])
+        want, losses = oc.s_ovl(init, batch_fn, K, lr, kw["rounds"])
+    got = tr.global_params()
+    err, worst, errs = worst_rel_err(got, want)
+    assert err <= tol, (worst, errs)
+    # what the schedule changed (the sum of merged deltas) must match too, not only the model
+    delta_got = {n: got[n].astype(np.float64) - init[n] for n in init}
+    delta_want = {n: want[n] - init[n].astype(np.float64) for n in init}
+    derr, dworst, derrs = worst_rel_err(delta_got, delta_want)
+    assert derr <= max(50 * tol, 5e-3), (dworst, derrs)
+    gl = np.stack([l.cpu().numpy() for l in tr.losses])
+    assert rel_err(gl, np.asarray(losses)) <= tol
+    return tr
+
+
+@pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=3)), ("seq", dict(gamma=3, rounds=2)),
+                                   ("ovl", dict(rounds=3))])
+def test_config1_tiny_gru_schedules(sched):
+    _schedule_parity(wl.CONFIGS["tiny_gru"], sched[0], TOL_FP32, **sched[1])
+
+
+@pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=3)), ("ovl", dict(rounds=3))])
+def test_config2_gru_classifier(sched):
+    _schedule_parity(wl.CONFIGS["gru_cls"], sched[0], TOL_FP32, **sched[1])
+
+
+@pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=3)), ("ovl", dict(rounds=3))])
+def test_config4_mlp(sched):
+    _schedule_parity(wl.CONFIGS["mlp"], sched[0], TOL_FP32, **sched[1])
+
+
+def test_overlapped_two_streams_equals_one_stream_bitwise():
+    """The two-stream schedule must give the bits of the same op list run on one stream,
+    and the same bits run to run."""
+    cfg = wl.scaled(wl.CONFIGS["gru_cls"], input=32, hidden=96, seq_len=6, batch=16, K=4)
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for single in (False, True, False):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+        tr.s_ovl(cfg["lr"], rounds=4, single_stream=single)
+        outs.append(tr.G.cpu().numpy().view(np.uint32).copy())
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])

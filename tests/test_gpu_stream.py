@@ -1,0 +1,175 @@
+"""GPU parity of the HBM-streaming entry points: hpsgd_merge, hpsgd_sync_*, hpsgd_gather_batch."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import hpsgd_oracle as oc
+from paper_2009_02701_amd import binding as hb
+from paper_2009_02701_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+CFG5 = wl.CONFIGS["merge_stress"]
+
+
+def _vec(seed, n, scale=1.0):
+    return (scale * np.random.default_rng(seed).standard_normal(n)).astype(np.float32)
+
+
+# sizes: empty, below one vector, ragged tails, several grid-stride passes (> 2048*256*4 floats)
+@pytest.mark.parametrize("P", [0, 1, 3, 4, 1021, 65536, 1000003, 2048 * 256 * 4 * 2 + 7])
+@pytest.mark.parametrize("K", [1, 2, 3, 4, 8, 16, 32])
+def test_merge_matches_oracle(P, K):
+    if P > 2_000_000 and K not in (1, 8):
+        pytest.skip("large size only for two K")
+    g0, s0 = _vec(1, P), _vec(2, P)
+    reps = [(s0 + _vec(10 + k, P, 1e-2)).astype(np.float32) for k in range(K)]
+    G = torch.from_numpy(g0.copy()).to(DEV)
+    S = torch.from_numpy(s0).to(DEV)
+    R = [torch.from_numpy(r).to(DEV) for r in reps]
+    hb.merge(G, R, S)
+    torch.cuda.synchronize()
+    want = oc.merge(g0, reps, s0)
+    got = G.cpu().numpy().astype(np.float64)
+    if P:
+        # the update (mean delta) carries the rounding of K fp32 subtractions and adds
+        upd_scale = np.abs(want - g0).max()
+        assert np.abs(got - want).max() <= 1e-4 * upd_scale + 6e-8 * np.abs(want).max()
+    # inputs untouched
+    assert np.array_equal(S.cpu().numpy(), s0)
+    for k in range(K):
+        assert np.array_equal(R[k].cpu().numpy(), reps[k])
+
+
+def test_merge_snapshot_may_alias_global_eq2():
+    """global == snapshot (same buffer): the result is the replica average (Eq. 2)."""
+    P, K = 100003, 4
+    s0 = _vec(3, P)
+    reps = [(s0 + _vec(20 + k, P, 1e-2)).astype(np.float32) for k in range(K)]
+    G = torch.from_numpy(s0.copy()).to(DEV)
+    hb.merge(G, [torch.from_numpy(r).to(DEV) for r in reps], G)
+    torch.cuda.synchronize()
+    want = np.mean(np.asarray(reps, np.float64), axis=0)
+    assert np.abs(G.cpu().numpy() - want).max() <= 2e-7 * np.abs(want).max()
+
+
+def test_merge_identical_replicas_bit_exact_for_power_of_two_K():
+    """K equal replicas: global + (replica - snapshot); exact in fp32 when K is a power of two
+    and the partial sums stay representable (small integers here)."""
+    P, K = 4099, 8
+    g = np.random.default_rng(4)
+    g0 = g.integers(-50, 50, P).astype(np.float32)
+    s0 = g.integers(-50, 50, P).astype(np.float32)
+    r = g.integers(-50, 50, P).astype(np.float32)
+    G = torch.from_numpy(g0.copy()).to(DEV)
+    Rt = torch.from_numpy(r).to(DEV)
+    hb.merge(G, [Rt] * K, torch.from_numpy(s0).to(DEV))
+    torch.cuda.synchronize()
+    assert np.array_equal(G.cpu().numpy(), g0 + (r - s0))
+
+
+def test_merge_stress_closed_form_reduced_size():
+    """Config 5 recipe at 1/100 size: replicas = global + delta_k before each merge, so after n
+    iterations global = base + n * mean_k(delta_k)."""
+    P, K, iters = 1_000_003, CFG5["K"], 5
+    base = wl.flat_base(CFG5, P)
+    deltas = [wl.flat_delta(CFG5, k, P) for k in range(K)]
+    G = torch.from_numpy(base.copy()).to(DEV)
+    S = torch.empty_like(G)
+    R = [torch.empty_like(G) for _ in range(K)]
+    D = [torch.from_numpy(d).to(DEV) for d in deltas]
+    ref = base.astype(np.float64)
+    for _ in range(iters):
+        hb.sync_all(G, R, S)
+        for k in range(K):
+            R[k].add_(D[k])          # untimed helper, not part of the path
+        hb.merge(G, R, S)
+        snap = ref.astype(np.float32)  # what the device holds is the rounded model
+        reps = [(snap + deltas[k]).astype(np.float32) for k in range(K)]
+        ref = oc.merge(snap, reps, snap)
+    torch.cuda.synchronize()
+    got = G.cpu().numpy().astype(np.float64)
+    want = base.astype(np.float64) + iters * np.mean(np.asarray(deltas, np.float64), axis=0)
+    assert np.abs(got - want).max() <= 1e-6           # closed form (fp32 storage of the model)
+    assert np.abs(got - ref).max() <= 5e-7            # step-by-step oracle
+
+
+def test_merge_stress_full_size_sampled():
+    """Config 5 at its full size (100M floats, K = 8), the launch the benchmark times;
+    the oracle recomputes a sample of outputs one by one."""
+    P, K = CFG5["P"], CFG5["K"]
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    G = torch.rand(P, device=DEV, generator=gen) * 2 - 1
+    S = torch.empty_like(G)
+    R = torch.empty(K, P, device=DEV)
+    hb.sync_all(G, list(R), S)
+    torch.cuda.synchronize()
+    idx = np.unique(np.concatenate([np.arange(0, 4096), np.arange(P - 4096, P),
+                                    np.random.default_rng(6).integers(0, P, 200_000)]))
+    it = torch.from_numpy(idx).to(DEV)
+    assert torch.equal(S[it], G[it]) and all(torch.equal(R[k][it], G[it]) for k in range(K))
+    assert torch.equal(R[K - 1], G) and torch.equal(S, G)           # sync is bit-exact, whole vector
+    for k in range(K):
+        R[k].add_(torch.randn(P, device=DEV, generator=gen) * 1e-3)
+    g0 = G[it].cpu().numpy()
+    s0 = S[it].cpu().numpy()
+    reps = [R[k][it].cpu().numpy() for k in range(K)]
+    hb.merge(G, list(R), S)
+    torch.cuda.synchronize()
+    want = oc.merge(g0, reps, s0)
+    got = G[it].cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want - g0).max() + 6e-8 * np.abs(want).max()
+
+
+@pytest.mark.parametrize("P", [0, 1, 5, 4096, 1000003])
+@pytest.mark.parametrize("K", [0, 1, 3, 8])
+def test_sync_is_bit_exact(P, K):
+    g0 = _vec(7, P)
+    G = torch.from_numpy(g0).to(DEV)
+    R = [torch.full((P,), 7.0, device=DEV) for _ in range(K)]
+    S = torch.full((P,), 7.0, device=DEV)
+    hb.sync_all(G, R, S)
+    one = torch.full((P,), 7.0, device=DEV)
+    hb.sync_replica(G, one)
+    torch.cuda.synchronize()
+    want = oc.sync(g0)
+    for t in R + [S, one]:
+        assert np.array_equal(t.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
+def test_gather_time_major_bit_exact():
+    cfg = wl.scaled(wl.CONFIGS["gru_cls"], input=13, seq_len=7, batch=5)
+    x, y = wl.make_shard(cfg, 0)
+    idx = wl.batch_indices(cfg, 0, 3)
+    want_x, want_y = wl.host_batch(cfg, (x, y), idx)
+    xs, ys, it = (torch.from_numpy(a).to(DEV) for a in (x, y, idx))
+    out = torch.zeros(7, 5, 13, device=DEV)
+    outy = torch.zeros(5, dtype=torch.int32, device=DEV)
+    hb.gather_batch(xs, it, 7, 13, out)
+    hb.gather_batch(ys, it, 1, 1, outy, row_elems=1)
+    torch.cuda.synchronize()
+    assert np.array_equal(out.cpu().numpy().view(np.uint32), want_x.view(np.uint32))
+    assert np.array_equal(outy.cpu().numpy(), want_y)
+
+
+def test_gather_tokens_and_shifted_targets_bit_exact():
+    cfg = wl.scaled(wl.CONFIGS["gru_lm"], seq_len=9, batch=6, vocab=50)
+    tok, _ = wl.make_shard(cfg, 1)
+    idx = wl.batch_indices(cfg, 1, 2)
+    want_x, want_y = wl.host_batch(cfg, (tok, None), idx)
+    ts, it = torch.from_numpy(tok).to(DEV), torch.from_numpy(idx).to(DEV)
+    ox = torch.zeros(9, 6, dtype=torch.int32, device=DEV)
+    oy = torch.zeros(9, 6, dtype=torch.int32, device=DEV)
+    flat = ts.view(-1)
+    hb.gather_batch(flat, it, 9, 1, ox, row_elems=10)
+    hb.gather_batch(flat[1:], it, 9, 1, oy, row_elems=10)
+    torch.cuda.synchronize()
+    assert np.array_equal(ox.cpu().numpy(), want_x) and np.array_equal(oy.cpu().numpy(), want_y)
+
+
+def test_gather_empty_is_noop():
+    out = torch.zeros(4, device=DEV)
+    hb.gather_batch(torch.zeros(8, device=DEV), torch.zeros(0, dtype=torch.int32, device=DEV), 1, 4, out,
+                    row_elems=4)
+    torch.cuda.synchronize()
+    assert float(out.abs().sum()) == 0.0
