@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the HPSGD hot path on one MI355X.
+
+One "step" is one round of the overlapped schedule on the GRU classifier workload
+(config 2: I128 H512 T35 B64, K=4 workers, fp32): batch gather, local step of all K workers
+(forward, BPTT, SGD commit) on stream A, merge of the previous round on stream B, and the
+replica sync at the round boundary.  Inputs (shards, parameters) are resident in HBM before
+the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_MFMA_TFLOPS = 157.3
+PEAK_BF16_MFMA_TFLOPS = 2500.0
+PEAK_HBM_GBS = 8000.0
+
+# HBM traffic per launch of a role's kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for the current kernels.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def role_work(cfg, role_name):
+    """Algorithmic work of ONE launch group of a role, all K workers: (bound, amount, unit-peak)."""
+    K, B, T, H, I, C = cfg["K"], cfg["batch"], cfg["seq_len"], cfg["hidden"], cfg["input"], cfg["classes"]
+    TB = T * B
+    f = {
+        "gemm_input_projection": 2.0 * TB * 3 * H * I * K,
+        "gemm_recurrent_fwd": 2.0 * B * 3 * H * H * K,
+        "gemm_recurrent_bwd": 2.0 * B * 3 * H * H * K,
+        "gemm_weight_grad": None,   # mixed group (two GEMMs + column sums), see below
+        "gemm_head": None,
+    }
+    if role_name in ("gemm_input_projection", "gemm_recurrent_fwd", "gemm_recurrent_bwd"):
+        return "mfma", f[role_name], PEAK_FP32_MFMA_TFLOPS * 1e12
+    if role_name == "gemm_weight_grad":
+        # per step: dW_ih + dW_hh GEMMs and two column-sum launches = 4 launch groups
+        return "mfma", (2.0 * 3 * H * I * TB + 2.0 * 3 * H * H * TB) * K / 4.0, PEAK_FP32_MFMA_TFLOPS * 1e12
+    if role_name == "gru_cell_fwd":
+        return "hbm", 48.0 * B * H * K, PEAK_HBM_GBS * 1e9      # 12 floats per (b, unit)
+    if role_name == "gru_cell_bwd":
+        return "hbm", 56.0 * B * H * K, PEAK_HBM_GBS * 1e9      # 14 floats per (b, unit)
+    if role_name == "commit":
+        P = 3 * H * I + 3 * H * H + 6 * H + C * H + C
+        return "hbm", 12.0 * P * K, PEAK_HBM_GBS * 1e9
+    return None, None, None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-merge-stress", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K workers are a group dimension on it); "
+              "--gpus must be 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2009_02701_amd import binding as hb
+    from paper_2009_02701_amd import harness, workloads as wl
+
+    dev = "cuda:0"
+    cfg = wl.CONFIGS["gru_cls"]
+    K, B, lr = cfg["K"], cfg["batch"], cfg["lr"]
+    init = wl.init_params(cfg)
+    shards = [wl.make_shard(cfg, k) for k in range(K)]
+    orders = [wl.batch_order(cfg, k) for k in range(K)]
+    tr = harness.Trainer(cfg, init, shards, orders, device=dev)
+    names = tr.ctx.role_names()
+
+    # ---- pass 0: which role dominates the local step (all roles timed, a few rounds)
+    tr.ovl_begin()
+    for t in range(3):
+        tr.ovl_round(t, lr)
+    torch.cuda.synchronize()
+    tr.ctx.timer_enable(range(hb.ROLE_COUNT))
+    probe_rounds = 5
+    for t in range(probe_rounds):
+        tr.ovl_round(3 + t, lr)
+    torch.cuda.synchronize()
+    breakdown = {}
+    for r, nm in enumerate(names):
+        n, ms = tr.ctx.timer_read(r)
+        if n:
+            breakdown[nm] = {"launches_per_step": n / probe_rounds, "avg_us": 1e3 * ms / n,
+                             "us_per_step": 1e3 * ms / probe_rounds}
+    dominant = max(breakdown, key=lambda k: breakdown[k]["us_per_step"])
+    dom_role = names.index(dominant)
+    tr.ctx.timer_enable([dom_role])
+
+    # ---- warm-up, then the timed region (the dominant role's launches carry event pairs)
+    step = 3 + probe_rounds
+    for t in range(args.warmup):
+        tr.ovl_round(step, lr)
+        step += 1
+    torch.cuda.synchronize()
+    tr.ctx.timer_read(dom_role)
+    t0 = time.perf_counter()
+    for t in range(args.steps):
+        tr.ovl_round(step, lr)
+        step += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    n_dom, ms_dom = tr.ctx.timer_read(dom_role)
+    tr.ctx.timer_enable([])
+    tr.ovl_drain()
+    ms_per_step = 1e3 * (t1 - t0) / args.steps
+    value = K * B / (ms_per_step * 1e-3)
+
+    bound, work, peak = role_work(cfg, dominant)
+    roofline = None
+    if bound is not None and n_dom:
+        dur = ms_dom * 1e-3 / n_dom
+        ach = work / dur
+        scale = 1e12 if bound == "mfma" else 1e9
+        roofline = {"kernel": dominant, "bound": bound, "achieved": ach / scale, "peak": peak / scale,
+                    "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": ach / peak,
+                    "avg_launch_us": dur * 1e6, "launches_timed": n_dom,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(dominant)}
+    for nm, v in breakdown.items():
+        b_, w_, p_ = role_work(cfg, nm)
+        if b_ is not None:
+            v["frac_of_peak"] = w_ / (v["avg_us"] * 1e-6) / p_
+            v["bound"] = b_
+
+    # ---- merge-only stress (config 5): merge + sync of 100M floats, K = 8, pure HBM streaming
+    merge_stress = None
+    if not args.no_merge_stress:
+        c5 = wl.CONFIGS["merge_stress"]
+        P5, K5, iters = c5["P"], c5["K"], c5["iters"]
+        del tr
+        torch.cuda.empty_cache()
+        gen = torch.Generator(device=dev).manual_seed(wl.BASE_SEED)
+        G = torch.rand(P5, device=dev, generator=gen) * 2 - 1
+        S = torch.empty_like(G)
+        R = torch.empty(K5, P5, device=dev)
+        reps = list(R)
+        hb.sync_all(G, reps, S)
+        for k in range(K5):
+            R[k].add_(torch.randn(P5, device=dev, generator=gen) * 1e-3)
+        st = torch.cuda.current_stream()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * iters + 1)]
+        for _ in range(3):
+            hb.merge(G, reps, S)
+            hb.sync_all(G, reps, S)
+        torch.cuda.synchronize()
+        ev[0].record(st)
+        for i in range(iters):
+            hb.merge(G, reps, S)
+            ev[2 * i + 1].record(st)
+            hb.sync_all(G, reps, S)
+            ev[2 * i + 2].record(st)
+        torch.cuda.synchronize()
+        t_merge = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(iters)) / iters
+        t_sync = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(iters)) / iters
+        bm, bs = 4.0 * (K5 + 3) * P5, 4.0 * (K5 + 2) * P5
+        merge_stress = {
+            "workload": "flat fp32 vector P=1e8, K=8, merge+sync x50",
+            "merge_ms": t_merge, "merge_GBps": bm / t_merge / 1e6, "merge_frac_hbm": bm / t_merge / 1e6 / PEAK_HBM_GBS,
+            "sync_ms": t_sync, "sync_GBps": bs / t_sync / 1e6, "sync_frac_hbm": bs / t_sync / 1e6 / PEAK_HBM_GBS,
+            "merge_plus_sync_GBps": (bm + bs) / (t_merge + t_sync) / 1e6,
+        }
+        del G, S, R, reps
+        torch.cuda.empty_cache()
+
+    # ---- CPU baseline: the float64 oracle on the host cores, same workload, bounded sample
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import hpsgd_oracle as oc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            cores = os.cpu_count()
+        bf = lambda k, s: wl.host_batch(cfg, shards[k], wl.batch_indices(cfg, k, s))
+        oc.s_seq(init, bf, K, lr, gamma=1, rounds=1)   # warm
+        rounds, el = 0, 0.0
+        c0 = time.perf_counter()
+        while el < 10.0 or rounds < 2:
+            oc.s_seq(init, bf, K, lr, gamma=1, rounds=1)
+            rounds += 1
+            el = time.perf_counter() - c0
+        cpu = {"value": K * B * rounds / el, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{rounds} rounds of (local step of all {K} workers + merge + sync) on the same "
+                         f"config-2 inputs, float64 numpy, {el:.1f} s"}
+
+    out = {
+        "metric": "local-step samples/sec (GRU classifier, overlapped HPSGD round: gather + local step "
+                  "+ merge + sync)",
+        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "config 2: GRU classifier I128 H512 T35 B64 C10, K=4 workers, fp32, "
+                               "merge every local step (overlapped on a second stream)",
+                   "global_batch": K * B, "seq_len": cfg["seq_len"], "parallelism": "1 GPU, K=4 simulated workers"},
+        "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

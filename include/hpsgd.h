@@ -16,7 +16,8 @@
  *     enqueue work and return; ordering between streams is the caller's job.
  *   - Return value: HPSGD_OK or an error code.  Arguments are validated before
  *     anything is enqueued; on error nothing has been written.
- *   - Float buffers must be 16-byte aligned, strides multiples of 4 floats.
+ *   - Parameter buffers (global, snapshot, replicas) must be 16-byte aligned and replica
+ *     strides multiples of 4 floats; batch inputs and labels need 4-byte alignment only.
  *   - Results are deterministic: fixed reduction orders, no floating-point atomics.
  */
 #ifndef HPSGD_H
@@ -139,6 +140,33 @@ int hpsgd_sync_replica(const float *global, float *replica, size_t P, void *hip_
  * if not NULL, the snapshot. */
 int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *snapshot,
                    size_t P, void *hip_stream);
+
+/* ---- kernel timing for benchmarks (not part of the method) ------------------------------
+ * The launches of one local step fall into roles.  While a role's bit is set in the mask,
+ * hpsgd_local_step(_all) records a HIP event pair on the caller's stream around every launch
+ * group of that role (the only HIP objects the context ever creates; hpsgd_destroy frees
+ * them).  hpsgd_timer_read waits for the recorded events, returns the number of timed
+ * launch groups of `role` and their summed duration in milliseconds, and clears that role. */
+enum hpsgd_role {
+  HPSGD_ROLE_OTHER = 0,        /* zero fills */
+  HPSGD_ROLE_GEMM_INPUT = 1,   /* time-batched input projection  X W_ih^T */
+  HPSGD_ROLE_GEMM_REC_FWD = 2, /* per-step recurrent GEMM        h W_hh^T */
+  HPSGD_ROLE_GEMM_REC_BWD = 3, /* per-step BPTT GEMM             dGh W_hh */
+  HPSGD_ROLE_GEMM_WGRAD = 4,   /* time-batched weight gradients and bias column sums */
+  HPSGD_ROLE_GEMM_DX = 5,      /* gradient to the layer below    dGx W_ih */
+  HPSGD_ROLE_GEMM_HEAD = 6,    /* head forward and backward GEMMs */
+  HPSGD_ROLE_CELL_FWD = 7,     /* gate nonlinearities and cell update */
+  HPSGD_ROLE_CELL_BWD = 8,     /* BPTT gate gradients */
+  HPSGD_ROLE_LOSS = 9,         /* softmax cross-entropy and loss mean */
+  HPSGD_ROLE_EMBED = 10,       /* embedding lookup and its gradient */
+  HPSGD_ROLE_COMMIT = 11,      /* SGD commit to the replica */
+  HPSGD_ROLE_MLP_FWD = 12,     /* MLP forward GEMMs */
+  HPSGD_ROLE_MLP_BWD = 13,     /* MLP backward GEMMs and bias column sums */
+  HPSGD_ROLE_COUNT = 14
+};
+int hpsgd_timer_enable(hpsgd_ctx *ctx, unsigned role_mask);
+int hpsgd_timer_read(hpsgd_ctx *ctx, int role, long *launches, double *total_ms);
+const char *hpsgd_role_name(int role); /* static string, NULL if out of range */
 
 /* Human-readable name of a status code (static string). */
 const char *hpsgd_strerror(int status);

@@ -23,7 +23,9 @@ EXPORTS = [
     "hpsgd_create", "hpsgd_destroy", "hpsgd_param_count", "hpsgd_param_entries",
     "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
     "hpsgd_gather_batch", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
+    "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
 ]
+ROLE_COUNT = 14
 
 
 class ModelDesc(C.Structure):
@@ -66,6 +68,10 @@ def load_library():
     lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
+    lib.hpsgd_timer_enable.argtypes = [vp, C.c_uint]
+    lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
+    lib.hpsgd_role_name.argtypes = [C.c_int]
+    lib.hpsgd_role_name.restype = C.c_char_p
     lib.hpsgd_strerror.argtypes = [C.c_int]
     lib.hpsgd_strerror.restype = C.c_char_p
     _lib = lib
@@ -148,6 +154,22 @@ class Context:
     def _ws_ptr(ws):
         p = ws.data_ptr()
         return C.c_void_p((p + 255) // 256 * 256)
+
+    # ---- kernel timing (benchmarks) ----
+    def timer_enable(self, roles):
+        mask = 0
+        for r in roles:
+            mask |= 1 << int(r)
+        _check(self.lib.hpsgd_timer_enable(self._h, mask), "hpsgd_timer_enable")
+
+    def timer_read(self, role):
+        """(launch groups, total ms) of `role` since the last read; waits for the events."""
+        n, ms = C.c_long(), C.c_double()
+        _check(self.lib.hpsgd_timer_read(self._h, int(role), C.byref(n), C.byref(ms)), "hpsgd_timer_read")
+        return int(n.value), float(ms.value)
+
+    def role_names(self):
+        return [self.lib.hpsgd_role_name(i).decode() for i in range(ROLE_COUNT)]
 
     # ---- entry points ----
     def local_step_all(self, replicas_in, replicas_out, x, y, lr, loss_out, workspace, stream=None):

@@ -36,6 +36,13 @@ struct hpsgd_ctx {
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
+  // optional per-role kernel timing (benchmarks): event pairs recorded around launches
+  unsigned timer_mask = 0;
+  struct Stamp { int role; hipEvent_t a, b; };
+  std::vector<Stamp> stamps;
+  std::vector<hipEvent_t> free_events;
+  double role_ms[HPSGD_ROLE_COUNT] = {0};
+  long role_launches[HPSGD_ROLE_COUNT] = {0};
 
   int find(const std::string& n) const {
     for (size_t i = 0; i < entries.size(); ++i)
@@ -127,9 +134,39 @@ inline bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return a0 < b0 + nb && b0 < a0 + na;
 }
 
-#define HIP_TRY(expr)                       \
-  do {                                      \
-    if ((expr) != hipSuccess) return HPSGD_EHIP; \
+// Records an event pair around the launches issued while it is alive, if its role is timed.
+struct TimerScope {
+  hpsgd_ctx* c;
+  hipStream_t s;
+  int idx = -1;
+  static hipEvent_t get(hpsgd_ctx* c) {
+    hipEvent_t e = nullptr;
+    if (!c->free_events.empty()) {
+      e = c->free_events.back();
+      c->free_events.pop_back();
+    } else if (hipEventCreate(&e) != hipSuccess) {
+      e = nullptr;
+    }
+    return e;
+  }
+  TimerScope(hpsgd_ctx* c_, int role, hipStream_t s_) : c(c_), s(s_) {
+    if (!(c->timer_mask & (1u << role))) return;
+    hipEvent_t a = get(c), b = get(c);
+    if (!a || !b) return;
+    c->stamps.push_back({role, a, b});
+    idx = (int)c->stamps.size() - 1;
+    (void)hipEventRecord(a, s);
+  }
+  ~TimerScope() {
+    if (idx >= 0) (void)hipEventRecord(c->stamps[idx].b, s);
+  }
+};
+
+// inside run_step: `role` names what the next launches are for
+#define HIP_TRY(expr)                              \
+  do {                                             \
+    TimerScope ts_(c, role, s);                    \
+    if ((expr) != hipSuccess) return HPSGD_EHIP;   \
   } while (0)
 
 // GEMM helper: C = op(A) op(B) for `groups` workers.
@@ -146,9 +183,15 @@ int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float*
   return launch_gemm(g, s) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
 }
 
-#define TRY(expr)                  \
-  do {                             \
-    int rc_ = (expr);              \
+#define TRY(expr)                    \
+  do {                               \
+    TimerScope ts_(c, role, s);      \
+    int rc_ = (expr);                \
+    if (rc_ != HPSGD_OK) return rc_; \
+  } while (0)
+#define TRY0(expr)                   \
+  do {                               \
+    int rc_ = (expr);                \
     if (rc_ != HPSGD_OK) return rc_; \
   } while (0)
 
@@ -162,6 +205,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const long sG = (long)c->grad.stride;
   const long sR = (long)rstride;
   const int B = d.batch;
+  int role = HPSGD_ROLE_OTHER;
 
   if (d.kind == HPSGD_MLP) {
     const int L = d.n_mlp_dims - 1;
@@ -172,6 +216,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     for (int i = 0; i < L; ++i) {
       const std::string p = "fc" + std::to_string(i);
       float* a_out = reg(c->act[i]);
+      role = HPSGD_ROLE_MLP_FWD;
       TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->off(p + ".W"),
                dims[i], sR, 1, a_out, dims[i + 1], (long)c->act[i].stride,
                i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->off(p + ".b"), sR));
@@ -181,6 +226,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // loss; the logits buffer becomes the output delta
     float* delta = reg(c->act[L - 1]);
     float* rowloss = reg(c->rowloss);
+    role = HPSGD_ROLE_LOSS;
     HIP_TRY(launch_softmax_ce(delta, (long)c->act[L - 1].stride, y, B, delta, rowloss,
                               (long)c->rowloss.stride, B, dims[L], groups, s));
     if (loss_out) HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, B, groups, s));
@@ -191,6 +237,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_prev = i > 0 ? (long)c->act[i - 1].stride : (long)B * dims[0];
       const long s_delta = (long)c->act[i].stride;
       // dW = delta^T a_prev
+      role = HPSGD_ROLE_MLP_BWD;
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
                s_prev, 0, grad + c->off(p + ".W"), dims[i], sG, EPI_STORE, nullptr, 0));
       HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + c->off(p + ".b"), sG, B, dims[i + 1],
@@ -226,6 +273,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     int width = d.input;
     if (lm) {
       float* xe = reg(c->xe);
+      role = HPSGD_ROLE_EMBED;
       HIP_TRY(launch_embed_fwd(rin + c->off("embed.E"), sR, tok, TB, xe, (long)c->xe.stride, TB,
                                d.embed, groups, s));
       lin = xe;
@@ -237,13 +285,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       float* hs = reg(c->hs[l]);
       float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
+      role = HPSGD_ROLE_OTHER;
       HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s));
+      role = HPSGD_ROLE_GEMM_INPUT;
       TRY(gemm(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, rin + c->off(p + ".W_ih"), width,
                sR, 1, gx, 3 * H, s_gx, EPI_BIAS, rin + c->off(p + ".b_ih"), sR));
       for (int t = 0; t < T; ++t) {
+        role = HPSGD_ROLE_GEMM_REC_FWD;
         TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0,
                  rin + c->off(p + ".W_hh"), H, sR, 1, gh, 3 * H, s_gh, EPI_BIAS,
                  rin + c->off(p + ".b_hh"), sR));
+        role = HPSGD_ROLE_CELL_FWD;
         HIP_TRY(launch_gru_cell_fwd(gx + (size_t)t * B * 3 * H, s_gx, gh, s_gh, hs + (size_t)t * B * H,
                                     hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
                                     s_sv, B, H, groups, s));
@@ -258,13 +310,16 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const int nrows = lm ? TB : B;
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
     const size_t oW = c->off("head.W"), ob = c->off("head.b");
+    role = HPSGD_ROLE_GEMM_HEAD;
     TRY(gemm(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
              s_log, EPI_BIAS, rin + ob, sR));
+    role = HPSGD_ROLE_LOSS;
     HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
                               classes, groups, s));
     if (loss_out)
       HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
     // ---- backward: head
+    role = HPSGD_ROLE_GEMM_HEAD;
     TRY(gemm(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW,
              H, sG, EPI_STORE, nullptr, 0));
     HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
@@ -299,34 +354,41 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
       for (int t = T - 1; t >= 0; --t) {
+        role = HPSGD_ROLE_CELL_BWD;
         HIP_TRY(launch_gru_cell_bwd(D, s_D, above ? above + (size_t)t * B * H : nullptr, s_dx,
                                     sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
                                     dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx, B, H,
                                     groups, s));
+        role = HPSGD_ROLE_GEMM_REC_BWD;
         if (t > 0)
           TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0,
                    rin + c->off(p + ".W_hh"), H, sR, 0, D, H, s_D, EPI_ACCUM, nullptr, 0));
       }
+      role = HPSGD_ROLE_GEMM_WGRAD;
       TRY(gemm(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
                grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0));
       TRY(gemm(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0,
                grad + c->off(p + ".W_hh"), H, sG, EPI_STORE, nullptr, 0));
       HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
       HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
+      role = HPSGD_ROLE_GEMM_DX;
       if (l > 0 || lm) {
         TRY(gemm(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, rin + c->off(p + ".W_ih"), win, sR,
                  0, dx, win, s_dx, EPI_STORE, nullptr, 0));
         above = dx;
       }
+      role = HPSGD_ROLE_OTHER;
       if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
     }
     if (lm) {
+      role = HPSGD_ROLE_EMBED;
       const size_t oE = c->off("embed.E");
       HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
       HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, s));
     }
   }
   // ---- commit (Alg. 2 "update replica")
+  role = HPSGD_ROLE_COMMIT;
   HIP_TRY(launch_commit(rin, rout, rstride, grad, (size_t)sG, lr, groups, c->P, s));
   return HPSGD_OK;
 }
@@ -336,7 +398,8 @@ int check_step_args(const hpsgd_ctx* c, const float* rin, float* rout, size_t rs
   if (!c || !rin || !rout || !x || !y) return HPSGD_EINVAL;
   if (!ws) return HPSGD_EWORKSPACE;
   if (((uintptr_t)ws & 255) != 0) return HPSGD_EWORKSPACE;
-  if (!aligned16(rin) || !aligned16(rout) || !aligned16(x) || ((uintptr_t)y & 3) != 0) return HPSGD_EALIGN;
+  if (!aligned16(rin) || !aligned16(rout) || ((uintptr_t)x & 3) != 0 || ((uintptr_t)y & 3) != 0)
+    return HPSGD_EALIGN;
   if (groups > 1 && (rstride < c->P || (rstride & 3) != 0)) return HPSGD_EALIGN;
   const size_t span = ((size_t)(groups - 1) * rstride + c->P) * sizeof(float);
   if (rin != rout && overlaps(rin, span, rout, span)) return HPSGD_EALIAS;
@@ -368,6 +431,13 @@ int hpsgd_create(const hpsgd_model_desc* desc, int K, hpsgd_ctx** out) {
 }
 
 int hpsgd_destroy(hpsgd_ctx* ctx) {
+  if (ctx) {
+    for (auto& st : ctx->stamps) {
+      (void)hipEventDestroy(st.a);
+      (void)hipEventDestroy(st.b);
+    }
+    for (auto e : ctx->free_events) (void)hipEventDestroy(e);
+  }
   delete ctx;
   return HPSGD_OK;
 }
@@ -392,7 +462,7 @@ int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replic
                          size_t replica_stride, const void* x, const int32_t* y, float lr,
                          float* loss_out, void* workspace, void* hip_stream) {
   if (!ctx) return HPSGD_EINVAL;
-  TRY(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
+  TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
   return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
                   (float*)workspace, (hipStream_t)hip_stream);
 }
@@ -401,7 +471,7 @@ int hpsgd_local_step(hpsgd_ctx* ctx, int worker, const float* replica_in, float*
                      const void* x, const int32_t* y, float lr, float* loss_out, void* workspace,
                      void* hip_stream) {
   if (!ctx || worker < 0 || worker >= ctx->K) return HPSGD_EINVAL;
-  TRY(check_step_args(ctx, replica_in, replica_out, ctx->P, 1, x, y, workspace));
+  TRY0(check_step_args(ctx, replica_in, replica_out, ctx->P, 1, x, y, workspace));
   return run_step(ctx, worker, 1, replica_in, replica_out, round_up(ctx->P, 4), x, y, lr, loss_out,
                   (float*)workspace, (hipStream_t)hip_stream);
 }
@@ -462,6 +532,52 @@ int hpsgd_sync_replica(const float* global, float* replica, size_t P, void* hip_
   float* one[1] = {replica};
   if (!replica) return P == 0 ? HPSGD_OK : HPSGD_EINVAL;
   return hpsgd_sync_all(global, one, 1, nullptr, P, hip_stream);
+}
+
+int hpsgd_timer_enable(hpsgd_ctx* ctx, unsigned role_mask) {
+  if (!ctx) return HPSGD_EINVAL;
+  ctx->timer_mask = role_mask & ((1u << HPSGD_ROLE_COUNT) - 1u);
+  return HPSGD_OK;
+}
+
+int hpsgd_timer_read(hpsgd_ctx* ctx, int role, long* launches, double* total_ms) {
+  if (!ctx || role < 0 || role >= HPSGD_ROLE_COUNT) return HPSGD_EINVAL;
+  // fold every recorded pair into the per-role totals, then hand back and clear this role's
+  for (auto& st : ctx->stamps) {
+    if (hipEventSynchronize(st.b) != hipSuccess) return HPSGD_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, st.a, st.b) != hipSuccess) return HPSGD_EHIP;
+    ctx->role_ms[st.role] += ms;
+    ctx->role_launches[st.role] += 1;
+    ctx->free_events.push_back(st.a);
+    ctx->free_events.push_back(st.b);
+  }
+  ctx->stamps.clear();
+  if (launches) *launches = ctx->role_launches[role];
+  if (total_ms) *total_ms = ctx->role_ms[role];
+  ctx->role_launches[role] = 0;
+  ctx->role_ms[role] = 0.0;
+  return HPSGD_OK;
+}
+
+const char* hpsgd_role_name(int role) {
+  switch (role) {
+    case HPSGD_ROLE_OTHER: return "other";
+    case HPSGD_ROLE_GEMM_INPUT: return "gemm_input_projection";
+    case HPSGD_ROLE_GEMM_REC_FWD: return "gemm_recurrent_fwd";
+    case HPSGD_ROLE_GEMM_REC_BWD: return "gemm_recurrent_bwd";
+    case HPSGD_ROLE_GEMM_WGRAD: return "gemm_weight_grad";
+    case HPSGD_ROLE_GEMM_DX: return "gemm_input_grad";
+    case HPSGD_ROLE_GEMM_HEAD: return "gemm_head";
+    case HPSGD_ROLE_CELL_FWD: return "gru_cell_fwd";
+    case HPSGD_ROLE_CELL_BWD: return "gru_cell_bwd";
+    case HPSGD_ROLE_LOSS: return "softmax_ce";
+    case HPSGD_ROLE_EMBED: return "embedding";
+    case HPSGD_ROLE_COMMIT: return "commit";
+    case HPSGD_ROLE_MLP_FWD: return "mlp_fwd";
+    case HPSGD_ROLE_MLP_BWD: return "mlp_bwd";
+    default: return nullptr;
+  }
 }
 
 const char* hpsgd_strerror(int status) {

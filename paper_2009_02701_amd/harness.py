@@ -120,31 +120,46 @@ class Trainer:
 
     def s_ovl(self, lr: float, rounds: int, record_loss=True, single_stream=False):
         """Overlapped schedule; with single_stream=True the same op list runs on one stream."""
-        sa = self.stream_a
-        sb = sa if single_stream else self.stream_b
-        sa.wait_stream(torch.cuda.current_stream())
-        self.sync_all(0, sa)
-        g = 0
-        ev_a = torch.cuda.Event()
-        ev_b = torch.cuda.Event()
-        ev_a.record(sa)
+        self.ovl_begin(single_stream)
         for t in range(rounds):
-            # stream B: merge of round t-1 (other generation); must follow that round's local step
-            if t > 0:
-                sb.wait_event(ev_a)
-                self.merge(1 - g, sb)
-            ev_b.record(sb)
-            # stream A: local step of round t on generation g
-            self.gather(t, sa)
-            self.local_step(g, lr, sa)
-            if record_loss:
-                with torch.cuda.stream(sa):
-                    self.losses.append(self.loss.clone())
-            # boundary: A waits for B, then clones the global model into the other generation
-            sa.wait_event(ev_b)
-            self.sync_all(1 - g, sa)
-            ev_a.record(sa)
-            g = 1 - g
-        self.merge(1 - g, sa)
-        sa.synchronize()
-        sb.synchronize()
+            self.ovl_round(t, lr, record_loss)
+        self.ovl_drain()
+
+    def ovl_begin(self, single_stream=False):
+        self._sa = self.stream_a
+        self._sb = self.stream_a if single_stream else self.stream_b
+        self._sa.wait_stream(torch.cuda.current_stream())
+        self.sync_all(0, self._sa)
+        self._g = 0
+        self._ev_a = torch.cuda.Event()
+        self._ev_b = torch.cuda.Event()
+        self._ev_a.record(self._sa)
+        self._have_delta = False
+
+    def ovl_round(self, t: int, lr: float, record_loss=False):
+        sa, sb, g = self._sa, self._sb, self._g
+        # synchronising side (stream B): merge the previous round's replica changes, once the
+        # local step that produced them (and the clone after it) is done
+        if self._have_delta:
+            sb.wait_event(self._ev_a)
+            self.merge(1 - g, sb)
+        self._ev_b.record(sb)
+        # training side (stream A): this round's local step on generation g
+        self.gather(t, sa)
+        self.local_step(g, lr, sa)
+        if record_loss:
+            with torch.cuda.stream(sa):
+                self.losses.append(self.loss.clone())
+        # boundary: A waits for B's merge, then clones the global model into the other generation
+        sa.wait_event(self._ev_b)
+        self.sync_all(1 - g, sa)
+        self._ev_a.record(sa)
+        self._g = 1 - g
+        self._have_delta = True
+
+    def ovl_drain(self):
+        if self._have_delta:
+            self.merge(1 - self._g, self._sa)
+            self._have_delta = False
+        self._sa.synchronize()
+        self._sb.synchronize()
