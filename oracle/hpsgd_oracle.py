@@ -40,6 +40,12 @@ def _f64(params: dict) -> dict:
     return {k: np.asarray(v, dtype=F64).copy() for k, v in params.items()}
 
 
+def _mm(a, b, rnd):
+    """Matrix product; `rnd` (None = exact float64) models operand rounding: a test may pass a
+    function that rounds every GEMM operand to a narrower format before the product."""
+    return a @ b if rnd is None else rnd(a) @ rnd(b)
+
+
 def sigmoid(a):
     return 1.0 / (1.0 + np.exp(-a))
 
@@ -64,7 +70,7 @@ def softmax_ce(logits, y):
 # ----------------------------------------------------------------------------
 # one GRU layer
 # ----------------------------------------------------------------------------
-def gru_layer_forward(W_ih, W_hh, b_ih, b_hh, x):
+def gru_layer_forward(W_ih, W_hh, b_ih, b_hh, x, rnd=None):
     """x [T,B,in] -> hs [T+1,B,H] (hs[0] = 0, hs[t+1] = h after step t) and saved gates."""
     T, B, _ = x.shape
     H = W_hh.shape[1]
@@ -74,8 +80,8 @@ def gru_layer_forward(W_ih, W_hh, b_ih, b_hh, x):
     n = np.zeros((T, B, H), F64)
     q = np.zeros((T, B, H), F64)
     for t in range(T):
-        gx = x[t] @ W_ih.T + b_ih
-        gh = hs[t] @ W_hh.T + b_hh
+        gx = _mm(x[t], W_ih.T, rnd) + b_ih
+        gh = _mm(hs[t], W_hh.T, rnd) + b_hh
         r[t] = sigmoid(gx[:, 0:H] + gh[:, 0:H])
         z[t] = sigmoid(gx[:, H:2 * H] + gh[:, H:2 * H])
         q[t] = gh[:, 2 * H:3 * H]
@@ -84,7 +90,7 @@ def gru_layer_forward(W_ih, W_hh, b_ih, b_hh, x):
     return hs, (r, z, n, q)
 
 
-def gru_layer_backward(W_ih, W_hh, x, hs, saved, dh_out):
+def gru_layer_backward(W_ih, W_hh, x, hs, saved, dh_out, rnd=None):
     """dh_out [T,B,H]: dLoss/d(h_t) arriving from above at every step.
 
     Returns dW_ih, dW_hh, db_ih, db_hh, dx [T,B,in].
@@ -110,12 +116,12 @@ def gru_layer_backward(W_ih, W_hh, x, hs, saved, dh_out):
         da_z = dz * z[t] * (1.0 - z[t])
         dgx = np.concatenate([da_r, da_z, da_n], axis=1)
         dgh = np.concatenate([da_r, da_z, dq], axis=1)
-        dW_ih += dgx.T @ x[t]
-        dW_hh += dgh.T @ h_prev
+        dW_ih += _mm(dgx.T, x[t], rnd)
+        dW_hh += _mm(dgh.T, h_prev, rnd)
         db_ih += dgx.sum(axis=0)
         db_hh += dgh.sum(axis=0)
-        dx[t] = dgx @ W_ih
-        dh_next = dh * z[t] + dgh @ W_hh
+        dx[t] = _mm(dgx, W_ih, rnd)
+        dh_next = dh * z[t] + _mm(dgh, W_hh, rnd)
     return dW_ih, dW_hh, db_ih, db_hh, dx
 
 
@@ -129,7 +135,7 @@ def _n_layers(params):
     return l
 
 
-def gru_loss_and_grads(params, x, y):
+def gru_loss_and_grads(params, x, y, rnd=None):
     """GRU classifier (x float [T,B,I], y int [B], head on the last hidden state) or
     GRU language model (x int [T,B] token ids, y int [T,B] next tokens, head at every step;
     recognised by the presence of an embedding table)."""
@@ -145,7 +151,7 @@ def gru_loss_and_grads(params, x, y):
     layer_in, layer_hs, layer_saved = [], [], []
     for l in range(L):
         hs, saved = gru_layer_forward(p[f"l{l}.W_ih"], p[f"l{l}.W_hh"],
-                                      p[f"l{l}.b_ih"], p[f"l{l}.b_hh"], inp)
+                                      p[f"l{l}.b_ih"], p[f"l{l}.b_hh"], inp, rnd)
         layer_in.append(inp)
         layer_hs.append(hs)
         layer_saved.append(saved)
@@ -157,21 +163,21 @@ def gru_loss_and_grads(params, x, y):
     dh_out = np.zeros((T, B, H), F64)
     if lm:
         feats = top[1:].reshape(T * B, H)
-        logits = feats @ Wo.T + bo
+        logits = _mm(feats, Wo.T, rnd) + bo
         loss, dlog = softmax_ce(logits, np.asarray(y).reshape(T * B))
-        g["head.W"] = dlog.T @ feats
+        g["head.W"] = _mm(dlog.T, feats, rnd)
         g["head.b"] = dlog.sum(axis=0)
-        dh_out = (dlog @ Wo).reshape(T, B, H)
+        dh_out = _mm(dlog, Wo, rnd).reshape(T, B, H)
     else:
         feats = top[T]
-        logits = feats @ Wo.T + bo
+        logits = _mm(feats, Wo.T, rnd) + bo
         loss, dlog = softmax_ce(logits, np.asarray(y))
-        g["head.W"] = dlog.T @ feats
+        g["head.W"] = _mm(dlog.T, feats, rnd)
         g["head.b"] = dlog.sum(axis=0)
-        dh_out[T - 1] = dlog @ Wo
+        dh_out[T - 1] = _mm(dlog, Wo, rnd)
     for l in range(L - 1, -1, -1):
         dW_ih, dW_hh, db_ih, db_hh, dx = gru_layer_backward(
-            p[f"l{l}.W_ih"], p[f"l{l}.W_hh"], layer_in[l], layer_hs[l], layer_saved[l], dh_out)
+            p[f"l{l}.W_ih"], p[f"l{l}.W_hh"], layer_in[l], layer_hs[l], layer_saved[l], dh_out, rnd)
         g[f"l{l}.W_ih"], g[f"l{l}.W_hh"] = dW_ih, dW_hh
         g[f"l{l}.b_ih"], g[f"l{l}.b_hh"] = db_ih, db_hh
         dh_out = dx
@@ -182,7 +188,7 @@ def gru_loss_and_grads(params, x, y):
     return loss, g
 
 
-def mlp_loss_and_grads(params, x, y):
+def mlp_loss_and_grads(params, x, y, rnd=None):
     """ReLU MLP, x float [B,D0], y int [B]; ReLU'(0) = 0."""
     p = _f64(params)
     L = 0
@@ -190,24 +196,24 @@ def mlp_loss_and_grads(params, x, y):
         L += 1
     acts = [np.asarray(x, F64)]
     for i in range(L):
-        a = acts[-1] @ p[f"fc{i}.W"].T + p[f"fc{i}.b"]
+        a = _mm(acts[-1], p[f"fc{i}.W"].T, rnd) + p[f"fc{i}.b"]
         if i < L - 1:
             a = np.maximum(a, 0.0)
         acts.append(a)
     loss, delta = softmax_ce(acts[-1], np.asarray(y))
     g = {}
     for i in range(L - 1, -1, -1):
-        g[f"fc{i}.W"] = delta.T @ acts[i]
+        g[f"fc{i}.W"] = _mm(delta.T, acts[i], rnd)
         g[f"fc{i}.b"] = delta.sum(axis=0)
         if i > 0:
-            delta = (delta @ p[f"fc{i}.W"]) * (acts[i] > 0.0)
+            delta = _mm(delta, p[f"fc{i}.W"], rnd) * (acts[i] > 0.0)
     return loss, g
 
 
-def loss_and_grads(params, x, y):
+def loss_and_grads(params, x, y, rnd=None):
     if "fc0.W" in params:
-        return mlp_loss_and_grads(params, x, y)
-    return gru_loss_and_grads(params, x, y)
+        return mlp_loss_and_grads(params, x, y, rnd)
+    return gru_loss_and_grads(params, x, y, rnd)
 
 
 # ----------------------------------------------------------------------------

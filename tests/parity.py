@@ -31,3 +31,10 @@ def workload(cfg):
     orders = [wl.batch_order(cfg, k) for k in range(K)]
     batch_fn = lambda k, s: wl.host_batch(cfg, shards[k], wl.batch_indices(cfg, k, s))
     return init, shards, orders, batch_fn
+
+
+def round_bf16(a):
+    """Round-to-nearest-even to bfloat16 (8 significand bits), returned as float64."""
+    u = np.asarray(a, np.float32).view(np.uint32).astype(np.uint64)
+    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
+    return u.astype(np.uint32).view(np.float32).astype(np.float64)

@@ -8,7 +8,7 @@ from paper_2009_02701_amd import binding as hb
 from paper_2009_02701_amd import harness
 from paper_2009_02701_amd import workloads as wl
 
-from parity import TOL_BF16, TOL_FP32, rel_err, workload, worst_rel_err
+from parity import TOL_BF16, TOL_FP32, rel_err, round_bf16, workload, worst_rel_err
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -24,6 +24,14 @@ SMALL = {
     "mlp_tiles": wl.scaled(wl.CONFIGS["mlp"], dims=[200, 300, 140, 10], batch=130, K=2),
     "lm_small_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=50, embed=12, hidden=24, seq_len=7, batch=5, K=2),
     "lm_tiles_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=300, embed=40, hidden=72, seq_len=6, batch=12, K=2),
+}
+
+
+BF16 = {
+    "lm_small_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=50, embed=12, hidden=24, seq_len=7, batch=5, K=2),
+    "lm_tiles_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=300, embed=40, hidden=72, seq_len=6, batch=12, K=2),
+    "gru_cls_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=64, hidden=160, seq_len=4, batch=70, K=2),
+    "mlp_bf16": wl.scaled(wl.CONFIGS["mlp"], prec="bf16", dims=[200, 300, 140, 10], batch=130, K=2),
 }
 
 
@@ -53,6 +61,30 @@ def test_gradients_and_loss_match_oracle(name):
         got_g = {n: (init[n].astype(np.float64) - reps[k][n].astype(np.float64)) / lr for n in init}
         err, worst, errs = worst_rel_err(got_g, g)
         assert err <= TOL_FP32, (k, worst, errs)
+
+
+@pytest.mark.parametrize("name", list(BF16))
+def test_bf16_gradients_and_loss_match_oracle(name):
+    """bf16 GEMM operands, fp32 accumulate: the float64 oracle within 2e-2 per tensor."""
+    cfg = BF16[name]
+    lr = 8.0
+    tr, init, batch_fn, reps, loss = _one_step(cfg, lr)
+    # the ReLU MLP is not one of the bf16 workloads: a rounded pre-activation can flip a ReLU
+    # mask, which moves whole terms of a gradient sum; it gets a looser bar against float64
+    tol = 0.15 if cfg["kind"] == "mlp" else TOL_BF16
+    for k in range(cfg["K"]):
+        x, y = batch_fn(k, 0)
+        want_loss, g = oc.loss_and_grads(init, x, y)
+        assert abs(loss[k] - want_loss) <= TOL_BF16 * abs(want_loss), (k, loss[k], want_loss)
+        got_g = {n: (init[n].astype(np.float64) - reps[k][n].astype(np.float64)) / lr for n in init}
+        err, worst, errs = worst_rel_err(got_g, g)
+        assert err <= tol, (k, worst, errs)
+        # the oracle with every GEMM operand rounded to bf16: what is left is accumulation
+        # order and the fp32 elementwise math, so the bar is far tighter
+        rl, rg = oc.loss_and_grads(init, x, y, rnd=round_bf16)
+        assert abs(loss[k] - rl) <= 1e-4 * abs(rl)
+        err, worst, errs = worst_rel_err(got_g, rg)
+        assert err <= 2e-3, (k, worst, errs)
 
 
 @pytest.mark.parametrize("name", ["gru_cls_ragged", "mlp_ragged", "lm_small_fp32"])
@@ -120,6 +152,11 @@ def test_config2_gru_classifier(sched):
 @pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=3)), ("ovl", dict(rounds=3))])
 def test_config4_mlp(sched):
     _schedule_parity(wl.CONFIGS["mlp"], sched[0], TOL_FP32, **sched[1])
+
+
+@pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=2))])
+def test_config3_gru_language_model_bf16(sched):
+    _schedule_parity(wl.CONFIGS["gru_lm"], sched[0], TOL_BF16, **sched[1])
 
 
 def test_overlapped_two_streams_equals_one_stream_bitwise():
