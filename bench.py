@@ -26,30 +26,50 @@ PEAK_HBM_GBS = 8000.0
 MEASURED_TRAFFIC_BYTES = {}
 
 
-def role_work(cfg, role_name):
-    """Algorithmic work of ONE launch group of a role, all K workers: (bound, amount, unit-peak)."""
-    K, B, T, H, I, C = cfg["K"], cfg["batch"], cfg["seq_len"], cfg["hidden"], cfg["input"], cfg["classes"]
+WORKLOAD_TEXT = {
+    "gru_cls": "config 2: GRU classifier I128 H512 T35 B64 C10, K=4 workers, fp32, merge every local step "
+               "(overlapped on a second stream)",
+    "gru_lm": "config 3: GRU language model V10000 E256 H1024 L2 T35 B32, K=8 workers, bf16 GEMM operands / "
+              "fp32 accumulate, merge every local step (overlapped)",
+    "mlp": "config 4: MLP 784-1024-1024-10, B128, K=16 workers, fp32, merge every local step (overlapped)",
+    "tiny_gru": "config 1: tiny GRU I16 H32 T8 B4, K=2 (launch-bound, parity case)",
+}
+
+
+def role_work_per_step(cfg, role_name):
+    """Algorithmic work of ALL launches of a role in one local step of all K workers:
+    (bound, flops or bytes per step, peak in the same unit per second)."""
+    kind, K, B = cfg["kind"], cfg["K"], cfg["batch"]
+    mfma_peak = (PEAK_BF16_MFMA_TFLOPS if cfg.get("prec") == "bf16" else PEAK_FP32_MFMA_TFLOPS) * 1e12
+    hbm = PEAK_HBM_GBS * 1e9
+    if kind == "mlp":
+        d = cfg["dims"]
+        fwd = sum(2.0 * B * d[i] * d[i + 1] for i in range(len(d) - 1)) * K
+        bwd = (sum(2.0 * B * d[i] * d[i + 1] for i in range(len(d) - 1))
+               + sum(2.0 * B * d[i] * d[i + 1] for i in range(1, len(d) - 1))) * K
+        P = sum(d[i] * d[i + 1] + d[i + 1] for i in range(len(d) - 1))
+        return {"mlp_fwd": ("mfma", fwd, mfma_peak), "mlp_bwd": ("mfma", bwd, mfma_peak),
+                "commit": ("hbm", 12.0 * P * K, hbm)}.get(role_name, (None, None, None))
+    T, H, L = cfg["seq_len"], cfg["hidden"], cfg["layers"]
     TB = T * B
-    f = {
-        "gemm_input_projection": 2.0 * TB * 3 * H * I * K,
-        "gemm_recurrent_fwd": 2.0 * B * 3 * H * H * K,
-        "gemm_recurrent_bwd": 2.0 * B * 3 * H * H * K,
-        "gemm_weight_grad": None,   # mixed group (two GEMMs + column sums), see below
-        "gemm_head": None,
+    lm = kind == "gru_lm"
+    widths = [cfg["embed"] if lm else cfg["input"]] + [H] * (L - 1)
+    classes = cfg["vocab"] if lm else cfg["classes"]
+    nrows = TB if lm else B
+    P = sum(3 * H * w + 3 * H * H + 6 * H for w in widths) + classes * H + classes + (cfg["vocab"] * cfg["embed"] if lm else 0)
+    table = {
+        "gemm_input_projection": ("mfma", sum(2.0 * TB * 3 * H * w for w in widths) * K, mfma_peak),
+        "gemm_recurrent_fwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K, mfma_peak),
+        "gemm_recurrent_bwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K, mfma_peak),
+        "gemm_weight_grad": ("mfma", sum(2.0 * 3 * H * w * TB + 2.0 * 3 * H * H * TB for w in widths) * K, mfma_peak),
+        "gemm_input_grad": ("mfma", sum(2.0 * TB * 3 * H * w for w in (widths if lm else widths[1:])) * K, mfma_peak),
+        "gemm_head": ("mfma", 3 * 2.0 * nrows * classes * H * K, mfma_peak),
+        "gru_cell_fwd": ("hbm", 48.0 * B * H * T * L * K, hbm),
+        "gru_cell_bwd": ("hbm", 56.0 * B * H * T * L * K, hbm),
+        "softmax_ce": ("hbm", 8.0 * nrows * classes * K, hbm),
+        "commit": ("hbm", 12.0 * P * K, hbm),
     }
-    if role_name in ("gemm_input_projection", "gemm_recurrent_fwd", "gemm_recurrent_bwd"):
-        return "mfma", f[role_name], PEAK_FP32_MFMA_TFLOPS * 1e12
-    if role_name == "gemm_weight_grad":
-        # per step: dW_ih + dW_hh GEMMs and two column-sum launches = 4 launch groups
-        return "mfma", (2.0 * 3 * H * I * TB + 2.0 * 3 * H * H * TB) * K / 4.0, PEAK_FP32_MFMA_TFLOPS * 1e12
-    if role_name == "gru_cell_fwd":
-        return "hbm", 48.0 * B * H * K, PEAK_HBM_GBS * 1e9      # 12 floats per (b, unit)
-    if role_name == "gru_cell_bwd":
-        return "hbm", 56.0 * B * H * K, PEAK_HBM_GBS * 1e9      # 14 floats per (b, unit)
-    if role_name == "commit":
-        P = 3 * H * I + 3 * H * H + 6 * H + C * H + C
-        return "hbm", 12.0 * P * K, PEAK_HBM_GBS * 1e9
-    return None, None, None
+    return table.get(role_name, (None, None, None))
 
 
 def main():
@@ -59,6 +79,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge-stress", action="store_true")
+    ap.add_argument("--workload", default="gru_cls", choices=["gru_cls", "gru_lm", "mlp", "tiny_gru"],
+                    help="default: config 2, the one the headline metric is quoted on")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (K workers are a group dimension on it); "
@@ -71,7 +93,7 @@ def main():
     from paper_2009_02701_amd import harness, workloads as wl
 
     dev = "cuda:0"
-    cfg = wl.CONFIGS["gru_cls"]
+    cfg = wl.CONFIGS[args.workload]
     K, B, lr = cfg["K"], cfg["batch"], cfg["lr"]
     init = wl.init_params(cfg)
     shards = [wl.make_shard(cfg, k) for k in range(K)]
@@ -116,22 +138,24 @@ def main():
     tr.ctx.timer_enable([])
     tr.ovl_drain()
     ms_per_step = 1e3 * (t1 - t0) / args.steps
-    value = K * B / (ms_per_step * 1e-3)
+    samples_per_step = K * B * (cfg["seq_len"] if cfg["kind"] == "gru_lm" else 1)
+    unit = "tokens/s" if cfg["kind"] == "gru_lm" else "samples/s"
+    value = samples_per_step / (ms_per_step * 1e-3)
 
-    bound, work, peak = role_work(cfg, dominant)
+    bound, work, peak = role_work_per_step(cfg, dominant)
     roofline = None
     if bound is not None and n_dom:
         dur = ms_dom * 1e-3 / n_dom
-        ach = work / dur
+        ach = work / breakdown[dominant]["launches_per_step"] / dur
         scale = 1e12 if bound == "mfma" else 1e9
         roofline = {"kernel": dominant, "bound": bound, "achieved": ach / scale, "peak": peak / scale,
                     "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": ach / peak,
                     "avg_launch_us": dur * 1e6, "launches_timed": n_dom,
                     "traffic": MEASURED_TRAFFIC_BYTES.get(dominant)}
     for nm, v in breakdown.items():
-        b_, w_, p_ = role_work(cfg, nm)
+        b_, w_, p_ = role_work_per_step(cfg, nm)
         if b_ is not None:
-            v["frac_of_peak"] = w_ / (v["avg_us"] * 1e-6) / p_
+            v["frac_of_peak"] = w_ / (v["us_per_step"] * 1e-6) / p_
             v["bound"] = b_
 
     # ---- merge-only stress (config 5): merge + sync of 100M floats, K = 8, pure HBM streaming
@@ -191,19 +215,17 @@ def main():
             oc.s_seq(init, bf, K, lr, gamma=1, rounds=1)
             rounds += 1
             el = time.perf_counter() - c0
-        cpu = {"value": K * B * rounds / el, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+        cpu = {"value": samples_per_step * rounds / el, "unit": unit, "cores": int(cores), "kind": "oracle",
                "sample": f"{rounds} rounds of (local step of all {K} workers + merge + sync) on the same "
-                         f"config-2 inputs, float64 numpy, {el:.1f} s"}
+                         f"{args.workload} inputs, float64 numpy, {el:.1f} s"}
 
     out = {
-        "metric": "local-step samples/sec (GRU classifier, overlapped HPSGD round: gather + local step "
-                  "+ merge + sync)",
-        "value": value, "unit": "samples/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "metric": "local-step samples/sec (overlapped HPSGD round: gather + local step + merge + sync)",
+        "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "config 2: GRU classifier I128 H512 T35 B64 C10, K=4 workers, fp32, "
-                               "merge every local step (overlapped on a second stream)",
-                   "global_batch": K * B, "seq_len": cfg["seq_len"], "parallelism": "1 GPU, K=4 simulated workers"},
+        "dtype": "bf16" if cfg.get("prec") == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
+                   "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
     }
     print(json.dumps(out))

@@ -124,6 +124,12 @@ int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float 
 int hpsgd_gather_batch(const void *shard, const int32_t *idx, int n_idx, size_t row_bytes,
                        int n_chunks, size_t chunk_bytes, void *out, void *hip_stream);
 
+/* The same gather for K workers in one launch: shards, idx and outs are HOST arrays of K
+ * DEVICE pointers (worker k: shards[k], idx[k] with n_idx entries, outs[k]). */
+int hpsgd_gather_batch_all(const void *const *shards, const int32_t *const *idx, int K, int n_idx,
+                           size_t row_bytes, int n_chunks, size_t chunk_bytes, void *const *outs,
+                           void *hip_stream);
+
 /* ---- merge (Eq. 1; Alg. 3 "update global model" with the all-reduce taken as the mean
  *      over the K workers): global[j] += (1/K) * sum_k (replicas[k][j] - snapshot[j]) ----
  * replicas: HOST array of K DEVICE pointers (1 <= K <= HPSGD_MAX_WORKERS).

@@ -22,7 +22,7 @@ MAX_MLP_DIMS = 8
 EXPORTS = [
     "hpsgd_create", "hpsgd_destroy", "hpsgd_param_count", "hpsgd_param_entries",
     "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
-    "hpsgd_gather_batch", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
+    "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
     "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
 ]
 ROLE_COUNT = 14
@@ -65,6 +65,8 @@ def load_library():
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
+    lib.hpsgd_gather_batch_all.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, C.c_int, sz, C.c_int, sz,
+                                           C.POINTER(vp), vp]
     lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
@@ -219,3 +221,13 @@ def gather_batch(shard, idx, n_chunks, chunk_elems, out, row_elems=None, stream=
     _check(load_library().hpsgd_gather_batch(_ptr(shard), _ptr(idx), idx.numel(), row, int(n_chunks),
                                              int(chunk_elems) * es, _ptr(out), _stream(stream)),
            "hpsgd_gather_batch")
+
+
+def gather_batch_all(shards, idxs, n_chunks, chunk_elems, outs, row_elems=None, stream=None):
+    """gather_batch for K workers in one launch (lists of K shard / index / output tensors)."""
+    es = shards[0].element_size()
+    row = (shards[0][0].numel() if row_elems is None else row_elems) * es
+    _check(load_library().hpsgd_gather_batch_all(_ptr_array(shards), _ptr_array(idxs), len(shards),
+                                                 idxs[0].numel(), row, int(n_chunks),
+                                                 int(chunk_elems) * es, _ptr_array(outs), _stream(stream)),
+           "hpsgd_gather_batch_all")

@@ -1,0 +1,277 @@
+// Fused recurrent kernels: one launch per time step does the recurrent GEMM on the matrix
+// cores AND the elementwise cell math in its epilogue, so neither gh_t nor dh_t ever goes
+// through HBM and the per-step launch count drops from two to one.
+//
+// Forward, step t:   gh = h_{t-1} W_hh^T (+ b_hh);  r, z, n, h_t from gx_t, gh, h_{t-1}.
+// Backward, step t:  dh_t = dgh_{t+1} W_hh + dh_{t+1} * z_{t+1} (+ gradient from above);
+//                    gate gradients of step t from dh_t and the saved r, z, n, q.
+//
+// Tiling (64-lane waves, v_mfma_f32_16x16x4_f32): a workgroup of 4 waves owns 32 batch rows
+// x 16 hidden units (all three gates of those units in the forward kernel, so the epilogue
+// has r, z and n of a unit in one thread).  The contraction is split over the 4 waves in
+// 16-wide chunks (chunk c belongs to wave c % 4); partial sums are combined through LDS.
+// MFMA 16x16x4 lane layout: A lane l holds A[m = l%16][k = l/16], B lane l holds
+// B[k = l/16][n = l%16], accumulator register v holds C[4*(l/16) + v][l%16].  Because the
+// order of the contraction index is free as long as both operands agree, a lane loads one
+// float4 (4 consecutive k of its row) per operand and feeds component s to MFMA number s:
+// lane group g then covers k = 16c + 4g + s.  Operands therefore go straight from L2 to
+// registers with 16-byte loads; LDS is used only for the cross-wave reduction.
+#include "kernels.h"
+
+namespace hpsgd {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+static constexpr int FR = 32;   // batch rows per workgroup
+static constexpr int FJ = 16;   // hidden units per workgroup
+
+__device__ __forceinline__ float sigm(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+__device__ __forceinline__ float4 ld4_or_zero(const float* p, bool ok) {
+  return ok ? *reinterpret_cast<const float4*>(p) : make_float4(0.f, 0.f, 0.f, 0.f);
+}
+
+__device__ __forceinline__ floatx4 mfma4(const float4& a, const float4& b, floatx4 acc) {
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.x, b.x, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.y, b.y, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.z, b.z, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a.w, b.w, acc, 0, 0, 0);
+  return acc;
+}
+
+// ---------------------------------------------------------------------------- forward
+// NCH: upper bound of contraction chunks per wave (H <= 64*NCH).
+template <int NCH>
+__global__ void __launch_bounds__(256)
+gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
+                    const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
+                    float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
+                    int B, int H) {
+  __shared__ float red[4][6][4][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int g = blockIdx.z;
+  const int j0 = blockIdx.x * FJ;
+  const int r0 = blockIdx.y * FR;
+  const float* W = W_hh + g * s_rep;
+  const float* hp = h_prev + g * s_hs;
+  const int nchunks = H / 16;
+
+  floatx4 acc[2][3];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+  // weights of this wave's chunks: 3 gates x NCH float4
+  float4 w[NCH][3];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = wave + 4 * i;
+    const bool ok = c < nchunks;
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      w[i][q] = ld4_or_zero(W + (long)(q * H + j0 + lr) * H + 16 * c + 4 * lg, ok);
+  }
+  // all operand loads are issued before the first MFMA so that their latencies overlap
+  float4 a[NCH][2];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = wave + 4 * i;
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int row = r0 + rb * 16 + lr;
+      a[i][rb] = ld4_or_zero(hp + (long)row * H + 16 * c + 4 * lg, c < nchunks && row < B);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int q = 0; q < 3; ++q) acc[rb][q] = mfma4(a[i][rb], w[i][q], acc[rb][q]);
+  // cross-wave reduction: wave w finishes accumulator register v = w of every block
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][rb * 3 + q][v][lane] = acc[rb][q][v];
+  __syncthreads();
+  const float* bh = b_hh + g * s_rep;
+  const int j = j0 + lr;
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    float gh[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      gh[q] = ((red[0][rb * 3 + q][wave][lane] + red[1][rb * 3 + q][wave][lane]) +
+               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bh[q * H + j];
+    if (row < B) {
+      const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
+      const float hpv = hp[(long)row * H + j];
+      const float r = sigm(gxr[j] + gh[0]);
+      const float z = sigm(gxr[H + j] + gh[1]);
+      const float qv = gh[2];
+      const float n = tanhf(gxr[2 * H + j] + r * qv);
+      h_out[g * s_hs + (long)row * H + j] = (1.0f - z) * n + z * hpv;
+      float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+      sv[j] = r;
+      sv[H + j] = z;
+      sv[2 * H + j] = n;
+      sv[3 * H + j] = qv;
+    }
+  }
+}
+
+hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
+                               long s_gx, const float* h_prev, float* h_out, long s_hs, float* sv_t,
+                               long s_sv, int B, int H, int groups, hipStream_t s) {
+  dim3 grid(H / FJ, (B + FR - 1) / FR, groups);
+#define HPSGD_FWD(N)                                                                              \
+  hipLaunchKernelGGL(gru_fwd_step_kernel<N>, grid, dim3(256), 0, s, W_hh, b_hh, s_rep, gx_t, s_gx, \
+                     h_prev, h_out, s_hs, sv_t, s_sv, B, H)
+  const int per_wave = (H / 16 + 3) / 4;
+  if (per_wave <= 2) HPSGD_FWD(2);
+  else if (per_wave <= 4) HPSGD_FWD(4);
+  else if (per_wave <= 8) HPSGD_FWD(8);
+  else HPSGD_FWD(16);
+#undef HPSGD_FWD
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- backward
+// WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along the contraction).
+// D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last step) and dh_t * z_t
+// on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
+template <int NCH>
+__global__ void __launch_bounds__(256)
+gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __restrict__ dgh_next,
+                    long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
+                    long s_above, const float* __restrict__ sv_t, long s_sv,
+                    const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
+                    float* __restrict__ dgh_t, int B, int H) {
+  __shared__ float red[4][2][4][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int g = blockIdx.z;
+  const int j0 = blockIdx.x * FJ;
+  const int r0 = blockIdx.y * FR;
+  const int H3 = 3 * H;
+  const int nchunks = H3 / 16;
+
+  floatx4 acc[2];
+  acc[0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  acc[1] = acc[0];
+  if (dgh_next) {
+    const float* Wt = WT + g * s_wt + (long)(j0 + lr) * H3;
+    const float* dg = dgh_next + g * s_dg;
+    float4 w[NCH];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = wave + 4 * i;
+      w[i] = ld4_or_zero(Wt + 16 * c + 4 * lg, c < nchunks);
+    }
+    float4 a[NCH][2];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = wave + 4 * i;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const int row = r0 + rb * 16 + lr;
+        a[i][rb] = ld4_or_zero(dg + (long)row * H3 + 16 * c + 4 * lg, c < nchunks && row < B);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      acc[0] = mfma4(a[i][0], w[i], acc[0]);
+      acc[1] = mfma4(a[i][1], w[i], acc[1]);
+    }
+  }
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][rb][v][lane] = acc[rb][v];
+  __syncthreads();
+  const int j = j0 + lr;
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const float rec = (red[0][rb][wave][lane] + red[1][rb][wave][lane]) +
+                      (red[2][rb][wave][lane] + red[3][rb][wave][lane]);
+    if (row < B) {
+      const long e = (long)row * H + j;
+      float dh = D[g * s_D + e] + rec;
+      if (above) dh += above[g * s_above + e];
+      const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+      const float r = sv[j], z = sv[H + j], n = sv[2 * H + j], q = sv[3 * H + j];
+      const float hp = h_prev[g * s_hs + e];
+      const float dn = dh * (1.0f - z);
+      const float dz = dh * (hp - n);
+      const float da_n = dn * (1.0f - n * n);
+      const float dq = da_n * r;
+      const float da_r = da_n * q * r * (1.0f - r);
+      const float da_z = dz * z * (1.0f - z);
+      float* ox = dgx_t + g * s_dg + (long)row * H3;
+      float* oh = dgh_t + g * s_dg + (long)row * H3;
+      ox[j] = da_r;
+      ox[H + j] = da_z;
+      ox[2 * H + j] = da_n;
+      oh[j] = da_r;
+      oh[H + j] = da_z;
+      oh[2 * H + j] = dq;
+      D[g * s_D + e] = dh * z;
+    }
+  }
+}
+
+hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next, long s_dg, float* D,
+                               long s_D, const float* above, long s_above, const float* sv_t,
+                               long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
+                               int B, int H, int groups, hipStream_t s) {
+  dim3 grid(H / FJ, (B + FR - 1) / FR, groups);
+#define HPSGD_BWD(N)                                                                             \
+  hipLaunchKernelGGL(gru_bwd_step_kernel<N>, grid, dim3(256), 0, s, WT, s_wt, dgh_next, s_dg, D, \
+                     s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H)
+  const int per_wave = (3 * H / 16 + 3) / 4;
+  if (per_wave <= 6) HPSGD_BWD(6);
+  else if (per_wave <= 12) HPSGD_BWD(12);
+  else if (per_wave <= 24) HPSGD_BWD(24);
+  else HPSGD_BWD(48);
+#undef HPSGD_BWD
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- transpose
+// out[c][r] = in[r][c] for an R x C matrix per group (32x32 tiles through LDS).
+__global__ void __launch_bounds__(256)
+transpose_kernel(const float* __restrict__ in, long s_in, float* __restrict__ out, long s_out, int R,
+                 int C) {
+  __shared__ float tile[32][33];
+  const int g = blockIdx.z;
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+  for (int i = ty; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < R && c < C) ? in[g * s_in + (long)r * C + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < R && c < C) out[g * s_out + (long)c * R + r] = tile[tx][i];
+  }
+}
+
+hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
+                            int groups, hipStream_t s) {
+  dim3 grid((C + 31) / 32, (R + 31) / 32, groups);
+  hipLaunchKernelGGL(transpose_kernel, grid, dim3(256), 0, s, in, s_in, out, s_out, R, C);
+  return hipGetLastError();
+}
+
+// The fused kernels need 16-byte loads along the contraction: H a multiple of 16, operand
+// bases 16-byte aligned, and at most 64*NCH_max contraction elements per wave quarter.
+bool gru_fused_supported(int H) { return H % 16 == 0 && H >= 16 && H <= 1024; }
+
+}  // namespace hpsgd

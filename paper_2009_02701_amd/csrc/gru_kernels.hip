@@ -183,30 +183,42 @@ hipError_t launch_loss_mean(const float* rowloss, long s_rowloss, float* loss, i
 }
 
 // ---------------------------------------------------------------------------- column sums
-// out[n] = sum_r in[r][n].  A workgroup covers 64 columns with 4 row slices; the slices
-// are combined through LDS in a fixed order.
-__global__ void __launch_bounds__(kThreads)
+// out[n] = sum_r in[r][n].  A workgroup of 1024 threads covers 64 columns with 16 row slices
+// (slice s takes rows s, s+16, ...); the slices are combined through LDS in a fixed order.
+static constexpr int kColsumSlices = 16;
+
+__global__ void __launch_bounds__(64 * kColsumSlices)
 colsum_kernel(const float* __restrict__ in, long ld, long s_in, float* __restrict__ out, long s_out,
               int R, int N) {
-  __shared__ float red[4][64];
+  __shared__ float red[kColsumSlices][64];
   const int g = blockIdx.y;
-  const int c = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int lane = threadIdx.x & 63;
+  const int c = blockIdx.x * 64 + lane;
   const int slice = threadIdx.x >> 6;
-  float acc = 0.f;
+  float a0 = 0.f, a1 = 0.f;
   if (c < N) {
     const float* p = in + g * s_in + c;
-    for (int r = slice; r < R; r += 4) acc += p[(long)r * ld];
+    int r = slice;
+    for (; r + kColsumSlices < R; r += 2 * kColsumSlices) {
+      a0 += p[(long)r * ld];
+      a1 += p[(long)(r + kColsumSlices) * ld];
+    }
+    if (r < R) a0 += p[(long)r * ld];
   }
-  red[slice][threadIdx.x & 63] = acc;
+  red[slice][lane] = a0 + a1;
   __syncthreads();
-  if (slice == 0 && c < N)
-    out[g * s_out + c] = (red[0][threadIdx.x] + red[1][threadIdx.x]) + (red[2][threadIdx.x] + red[3][threadIdx.x]);
+  if (slice == 0 && c < N) {
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < kColsumSlices; ++i) v += red[i][lane];
+    out[g * s_out + c] = v;
+  }
 }
 
 hipError_t launch_colsum(const float* in, long ld, long s_in, float* out, long s_out, int R, int N,
                          int groups, hipStream_t s) {
-  hipLaunchKernelGGL(colsum_kernel, dim3((N + 63) / 64, groups), dim3(kThreads), 0, s, in, ld, s_in,
-                     out, s_out, R, N);
+  hipLaunchKernelGGL(colsum_kernel, dim3((N + 63) / 64, groups), dim3(64 * kColsumSlices), 0, s, in,
+                     ld, s_in, out, s_out, R, N);
   return hipGetLastError();
 }
 

@@ -33,7 +33,7 @@ struct hpsgd_ctx {
   size_t P = 0;
   size_t ws_floats = 0;
   // workspace regions (floats)
-  Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss;
+  Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
@@ -102,6 +102,7 @@ int build_layout(hpsgd_ctx* c) {
     c->dgh = c->alloc(TB * 3 * H);
     c->gh = c->alloc((size_t)d.batch * 3 * H);
     c->D = c->alloc((size_t)d.batch * H);
+    c->wt = c->alloc(3 * H * H);
     size_t wmax = H;
     if (lm && (size_t)d.embed > wmax) wmax = d.embed;
     c->dx = c->alloc(TB * wmax);
@@ -290,11 +291,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       role = HPSGD_ROLE_GEMM_INPUT;
       TRY(gemm(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, rin + c->off(p + ".W_ih"), width,
                sR, 1, gx, 3 * H, s_gx, EPI_BIAS, rin + c->off(p + ".b_ih"), sR));
+      const float* Whh = rin + c->off(p + ".W_hh");
+      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       for (int t = 0; t < T; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0,
-                 rin + c->off(p + ".W_hh"), H, sR, 1, gh, 3 * H, s_gh, EPI_BIAS,
-                 rin + c->off(p + ".b_hh"), sR));
+        if (fused) {
+          HIP_TRY(launch_gru_fwd_step(Whh, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H, s_gx,
+                                      hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
+                                      sv + (size_t)t * B * 4 * H, s_sv, B, H, groups, s));
+          continue;
+        }
+        TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0, Whh, H, sR, 1, gh, 3 * H,
+                 s_gh, EPI_BIAS, rin + c->off(p + ".b_hh"), sR));
         role = HPSGD_ROLE_CELL_FWD;
         HIP_TRY(launch_gru_cell_fwd(gx + (size_t)t * B * 3 * H, s_gx, gh, s_gh, hs + (size_t)t * B * H,
                                     hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
@@ -353,16 +361,32 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         s_layer_in = (long)TB * d.input;
       }
       float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
+      const float* Whh = rin + c->off(p + ".W_hh");
+      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
+      float* wt = reg(c->wt);
+      const long s_wt = (long)c->wt.stride;
+      if (fused) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
+      }
       for (int t = T - 1; t >= 0; --t) {
+        const float* above_t = above ? above + (size_t)t * B * H : nullptr;
+        if (fused) {
+          role = HPSGD_ROLE_GEMM_REC_BWD;
+          HIP_TRY(launch_gru_bwd_step(wt, s_wt, t + 1 < T ? dgh + (size_t)(t + 1) * B * 3 * H : nullptr, s_gx,
+                                      D, s_D, above_t, s_dx, sv + (size_t)t * B * 4 * H, s_sv,
+                                      hs + (size_t)t * B * H, s_hs, dgx + (size_t)t * B * 3 * H,
+                                      dgh + (size_t)t * B * 3 * H, B, H, groups, s));
+          continue;
+        }
         role = HPSGD_ROLE_CELL_BWD;
-        HIP_TRY(launch_gru_cell_bwd(D, s_D, above ? above + (size_t)t * B * H : nullptr, s_dx,
-                                    sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
-                                    dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx, B, H,
-                                    groups, s));
+        HIP_TRY(launch_gru_cell_bwd(D, s_D, above_t, s_dx, sv + (size_t)t * B * 4 * H, s_sv,
+                                    hs + (size_t)t * B * H, s_hs, dgx + (size_t)t * B * 3 * H,
+                                    dgh + (size_t)t * B * 3 * H, s_gx, B, H, groups, s));
         role = HPSGD_ROLE_GEMM_REC_BWD;
         if (t > 0)
-          TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0,
-                   rin + c->off(p + ".W_hh"), H, sR, 0, D, H, s_D, EPI_ACCUM, nullptr, 0));
+          TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0, Whh, H, sR, 0, D,
+                   H, s_D, EPI_ACCUM, nullptr, 0));
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
       TRY(gemm(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
@@ -487,6 +511,22 @@ int hpsgd_gather_batch(const void* shard, const int32_t* idx, int n_idx, size_t 
   if ((size_t)n_chunks * chunk_bytes > row_bytes || n_chunks > 65535) return HPSGD_ESHAPE;
   return launch_gather(shard, idx, n_idx, row_bytes, n_chunks, chunk_bytes, out,
                        (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
+}
+
+int hpsgd_gather_batch_all(const void* const* shards, const int32_t* const* idx, int K, int n_idx,
+                           size_t row_bytes, int n_chunks, size_t chunk_bytes, void* const* outs,
+                           void* hip_stream) {
+  if (K < 0 || K > HPSGD_MAX_WORKERS || n_idx < 0 || n_chunks < 0) return HPSGD_EINVAL;
+  if (K == 0 || n_idx == 0 || n_chunks == 0 || chunk_bytes == 0) return HPSGD_OK;
+  if (!shards || !idx || !outs) return HPSGD_EINVAL;
+  if ((row_bytes & 3) || (chunk_bytes & 3)) return HPSGD_EALIGN;
+  if ((size_t)n_chunks * chunk_bytes > row_bytes || n_chunks > 65535) return HPSGD_ESHAPE;
+  for (int k = 0; k < K; ++k) {
+    if (!shards[k] || !idx[k] || !outs[k]) return HPSGD_EINVAL;
+    if (((uintptr_t)shards[k] & 3) || ((uintptr_t)outs[k] & 3) || ((uintptr_t)idx[k] & 3)) return HPSGD_EALIGN;
+  }
+  return launch_gather_all(shards, idx, K, n_idx, row_bytes, n_chunks, chunk_bytes, outs,
+                           (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
 }
 
 int hpsgd_merge(float* global, const float* const* replicas, const float* snapshot, int K, size_t P,

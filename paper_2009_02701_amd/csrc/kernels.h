@@ -25,6 +25,10 @@ hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipSt
 hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
                          int n_chunks, size_t chunk_bytes, void* out, hipStream_t s);
 
+hipError_t launch_gather_all(const void* const* shards, const int32_t* const* idx, int K, int n_idx,
+                             size_t row_bytes, int n_chunks, size_t chunk_bytes, void* const* outs,
+                             hipStream_t s);
+
 // ---- grouped GEMM on the fp32 / bf16 matrix cores ----
 enum Epilogue : int {
   EPI_STORE = 0,      // C = acc
@@ -57,6 +61,19 @@ hipError_t launch_gru_cell_bwd(float* D, long s_D, const float* above, long s_ab
                                const float* saved, long s_saved, const float* h_prev, long s_h,
                                float* dgx, float* dgh, long s_dg, int B, int H, int groups,
                                hipStream_t s);
+// ---- fused recurrent steps (recurrent GEMM + cell math in one launch), see gru_fused.hip ----
+bool gru_fused_supported(int H);
+hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
+                               long s_gx, const float* h_prev, float* h_out, long s_hs, float* sv_t,
+                               long s_sv, int B, int H, int groups, hipStream_t s);
+hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next, long s_dg, float* D,
+                               long s_D, const float* above, long s_above, const float* sv_t,
+                               long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
+                               int B, int H, int groups, hipStream_t s);
+// out[c][r] = in[r][c], R x C per group
+hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
+                            int groups, hipStream_t s);
+
 // mean softmax cross-entropy over N rows of C logits; dlogits = (p - onehot)/N; row losses to rowloss
 hipError_t launch_softmax_ce(const float* logits, long s_logits, const int32_t* y, long s_y,
                              float* dlogits, float* rowloss, long s_rowloss, int N, int C,

@@ -191,6 +191,37 @@ gather_kernel(const uint32_t* __restrict__ shard, const int32_t* __restrict__ id
   for (size_t w = threadIdx.x; w < chunk_w; w += kThreads) dst[w] = src[w];
 }
 
+// The same for K workers in one launch: worker k = blockIdx.z reads shard[k], idx[k], writes out[k].
+struct GatherPack {
+  const uint32_t* shard[HPSGD_KMAX];
+  const int32_t* idx[HPSGD_KMAX];
+  uint32_t* out[HPSGD_KMAX];
+};
+
+__global__ void __launch_bounds__(kThreads)
+gather_all_kernel(GatherPack pk, int n_idx, size_t row_w, size_t chunk_w) {
+  const size_t b = blockIdx.x, c = blockIdx.y;
+  const int k = blockIdx.z;
+  const uint32_t* src = pk.shard[k] + (size_t)pk.idx[k][b] * row_w + c * chunk_w;
+  uint32_t* dst = pk.out[k] + (c * (size_t)n_idx + b) * chunk_w;
+  for (size_t w = threadIdx.x; w < chunk_w; w += kThreads) dst[w] = src[w];
+}
+
+hipError_t launch_gather_all(const void* const* shards, const int32_t* const* idx, int K, int n_idx,
+                             size_t row_bytes, int n_chunks, size_t chunk_bytes, void* const* outs,
+                             hipStream_t s) {
+  if (K == 0 || n_idx == 0 || n_chunks == 0 || chunk_bytes == 0) return hipSuccess;
+  GatherPack pk;
+  for (int k = 0; k < K; ++k) {
+    pk.shard[k] = (const uint32_t*)shards[k];
+    pk.idx[k] = idx[k];
+    pk.out[k] = (uint32_t*)outs[k];
+  }
+  hipLaunchKernelGGL(gather_all_kernel, dim3(n_idx, n_chunks, K), dim3(kThreads), 0, s, pk, n_idx,
+                     row_bytes / 4, chunk_bytes / 4);
+  return hipGetLastError();
+}
+
 hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
                          int n_chunks, size_t chunk_bytes, void* out, hipStream_t s) {
   if (n_idx == 0 || n_chunks == 0 || chunk_bytes == 0) return hipSuccess;

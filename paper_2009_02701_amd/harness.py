@@ -63,21 +63,21 @@ class Trainer:
     # ------------------------------------------------------------------ pieces
     def gather(self, step: int, stream=None):
         """Assemble every worker's mini-batch `step` from its resident shard (bit-exact)."""
-        cfg, B = self.cfg, self.cfg["batch"]
+        cfg, B, K = self.cfg, self.cfg["batch"], self.K
         s = step % self.n_batches
-        for k in range(self.K):
-            idx = self.order[k][s * B:(s + 1) * B]
-            if self.kind == "gru_cls":
-                hb.gather_batch(self.xs[k], idx, cfg["seq_len"], cfg["input"], self.xb[k], stream=stream)
-                hb.gather_batch(self.ys[k], idx, 1, 1, self.yb[k], row_elems=1, stream=stream)
-            elif self.kind == "mlp":
-                hb.gather_batch(self.xs[k], idx, 1, cfg["dims"][0], self.xb[k], stream=stream)
-                hb.gather_batch(self.ys[k], idx, 1, 1, self.yb[k], row_elems=1, stream=stream)
-            else:
-                T = cfg["seq_len"]
-                tok = self.xs[k].view(-1)
-                hb.gather_batch(tok, idx, T, 1, self.xb[k], row_elems=T + 1, stream=stream)
-                hb.gather_batch(tok[1:], idx, T, 1, self.yb[k], row_elems=T + 1, stream=stream)
+        idx = [self.order[k][s * B:(s + 1) * B] for k in range(K)]
+        xb, yb = list(self.xb), list(self.yb)
+        if self.kind == "gru_cls":
+            hb.gather_batch_all(self.xs, idx, cfg["seq_len"], cfg["input"], xb, stream=stream)
+            hb.gather_batch_all(self.ys, idx, 1, 1, yb, row_elems=1, stream=stream)
+        elif self.kind == "mlp":
+            hb.gather_batch_all(self.xs, idx, 1, cfg["dims"][0], xb, stream=stream)
+            hb.gather_batch_all(self.ys, idx, 1, 1, yb, row_elems=1, stream=stream)
+        else:
+            T = cfg["seq_len"]
+            tok = [x.view(-1) for x in self.xs]
+            hb.gather_batch_all(tok, idx, T, 1, xb, row_elems=T + 1, stream=stream)
+            hb.gather_batch_all([t[1:] for t in tok], idx, T, 1, yb, row_elems=T + 1, stream=stream)
 
     def local_step(self, gen: int, lr: float, stream=None, ws=0):
         if self.ws[ws] is None:

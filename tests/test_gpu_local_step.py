@@ -23,6 +23,8 @@ SMALL = {
     "mlp_ragged": wl.scaled(wl.CONFIGS["mlp"], dims=[37, 70, 33, 5], batch=11, K=3),
     "mlp_tiles": wl.scaled(wl.CONFIGS["mlp"], dims=[200, 300, 140, 10], batch=130, K=2),
     "lm_small_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=50, embed=12, hidden=24, seq_len=7, batch=5, K=2),
+    "lm_fused_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=60, embed=16, hidden=48, seq_len=5, batch=7, K=2),
+    "cls_fused_3layer": wl.scaled(wl.CONFIGS["gru_cls"], layers=3, input=20, hidden=64, seq_len=5, batch=33, K=2),
     "lm_tiles_fp32": wl.scaled(wl.CONFIGS["gru_lm"], prec="fp32", vocab=300, embed=40, hidden=72, seq_len=6, batch=12, K=2),
 }
 

@@ -173,3 +173,21 @@ def test_gather_empty_is_noop():
                     row_elems=4)
     torch.cuda.synchronize()
     assert float(out.abs().sum()) == 0.0
+
+
+def test_gather_all_workers_one_launch_bit_exact():
+    cfg = wl.scaled(wl.CONFIGS["gru_cls"], input=13, seq_len=7, batch=5, K=3)
+    shards = [wl.make_shard(cfg, k) for k in range(3)]
+    idx = [wl.batch_indices(cfg, k, 2) for k in range(3)]
+    xs = [torch.from_numpy(s[0]).to(DEV) for s in shards]
+    ys = [torch.from_numpy(s[1]).to(DEV) for s in shards]
+    its = [torch.from_numpy(i).to(DEV) for i in idx]
+    ox = torch.zeros(3, 7, 5, 13, device=DEV)
+    oy = torch.zeros(3, 5, dtype=torch.int32, device=DEV)
+    hb.gather_batch_all(xs, its, 7, 13, list(ox))
+    hb.gather_batch_all(ys, its, 1, 1, list(oy), row_elems=1)
+    torch.cuda.synchronize()
+    for k in range(3):
+        wx, wy = wl.host_batch(cfg, shards[k], idx[k])
+        assert np.array_equal(ox[k].cpu().numpy().view(np.uint32), wx.view(np.uint32))
+        assert np.array_equal(oy[k].cpu().numpy(), wy)
