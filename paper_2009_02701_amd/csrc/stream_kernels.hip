@@ -1,13 +1,26 @@
 // HBM-streaming kernels over flat fp32 parameter buffers: replica merge (Eq. 1), replica
 // sync (Alg. 2 "make replica"), SGD commit (Alg. 2 "update replica"), zero fill and the
-// time-major batch gather.  All are grid-stride loops over 16-byte vectors: every lane
-// keeps K+2 independent loads in flight and every wave reads and writes 1 KiB contiguous.
+// time-major batch gather.  All work on 16-byte vectors: every lane keeps K+2 independent
+// loads in flight and every wave reads and writes 1 KiB contiguous per stream.  Merge and
+// sync are launched with one vector per lane (a grid as long as the buffer): on this chip
+// that measured 10-20% faster than a resident grid-stride grid, and the merge's operands,
+// each touched exactly once, are read and written with non-temporal hints.
 #include "kernels.h"
 
 namespace hpsgd {
 
 static constexpr int kThreads = 256;
 static constexpr int kMaxBlocks = 256 * 8;  // 256 CUs, up to 8 resident blocks each
+
+// one 256-lane workgroup per 256 vectors (the kernels still stride, should the cap bind)
+static inline int onepass_blocks(size_t n_items) {
+  size_t b = (n_items + kThreads - 1) / kThreads;
+  if (b > (size_t)1 << 30) b = (size_t)1 << 30;
+  if (b < 1) b = 1;
+  return (int)b;
+}
+
+typedef float f4v __attribute__((ext_vector_type(4)));
 
 static inline int stream_blocks(size_t n_items) {
   size_t b = (n_items + kThreads - 1) / kThreads;
@@ -25,23 +38,15 @@ merge_kernel(float* global, PtrPack rep, const float* snapshot, int Krt, float i
   const int K = KT > 0 ? KT : Krt;
   const size_t stride = (size_t)gridDim.x * kThreads;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
-    const float4 s = reinterpret_cast<const float4*>(snapshot)[i];
-    const float4 g = reinterpret_cast<const float4*>(global)[i];
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    const f4v s = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(snapshot) + i);
+    const f4v g = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(global) + i);
+    f4v acc = (f4v){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const float4 r = reinterpret_cast<const float4*>(rep.p[k])[i];
-      acc.x += r.x - s.x;
-      acc.y += r.y - s.y;
-      acc.z += r.z - s.z;
-      acc.w += r.w - s.w;
+      const f4v r = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(rep.p[k]) + i);
+      acc += r - s;
     }
-    float4 o;
-    o.x = g.x + acc.x * inv_k;
-    o.y = g.y + acc.y * inv_k;
-    o.z = g.z + acc.z * inv_k;
-    o.w = g.w + acc.w * inv_k;
-    reinterpret_cast<float4*>(global)[i] = o;
+    __builtin_nontemporal_store(g + acc * inv_k, reinterpret_cast<f4v*>(global) + i);
   }
   // ragged tail (P not a multiple of 4): the first block's first lanes
   if (blockIdx.x == 0) {
@@ -59,7 +64,7 @@ hipError_t launch_merge(float* global, const PtrPack& replicas, const float* sna
                         size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t n4 = P / 4;
-  const int blocks = stream_blocks(n4);
+  const int blocks = onepass_blocks(n4);
   const float inv_k = 1.0f / (float)K;
 #define HPSGD_MERGE_CASE(KT)                                                                  \
   hipLaunchKernelGGL(merge_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, replicas, \
@@ -103,7 +108,7 @@ hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, 
                            size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t n4 = P / 4;
-  const int blocks = stream_blocks(n4);
+  const int blocks = onepass_blocks(n4);
 #define HPSGD_SYNC_CASE(KT)                                                                  \
   hipLaunchKernelGGL(sync_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, replicas, K, \
                      snapshot, n4, P)
@@ -149,8 +154,7 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const size_t n4 = P / 4;
-  int blocks = stream_blocks(n4);
-  if (blocks * K > kMaxBlocks) blocks = (kMaxBlocks + K - 1) / K;
+  const int blocks = onepass_blocks(n4);
   hipLaunchKernelGGL(commit_kernel, dim3(blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
                      grad_stride, lr, n4, P);
   return hipGetLastError();
