@@ -39,6 +39,31 @@ __device__ __forceinline__ floatx4 mfma4(const float4& a, const float4& b, float
   return acc;
 }
 
+// Workgroups are dispatched to the 8 XCDs round-robin (workgroup i runs on XCD i % 8) and
+// each XCD has its own L2, which starts cold at every launch.  The linear id is therefore
+// mapped to (worker g, unit tile x, row tile y) so that one XCD touches as few distinct
+// weight slices and activation rows as possible: whole workers per XCD when there are at
+// least 8 of them, else a contiguous range of a worker's unit tiles (with all its row tiles).
+__device__ __forceinline__ void step_tile(int NJ, int RT, int groups, int& g, int& x, int& y) {
+  const int i = blockIdx.x;
+  if (groups % 8 == 0) {
+    const int c = i & 7, li = i >> 3, per = NJ * RT;
+    g = c + 8 * (li / per);
+    const int r = li % per;
+    x = r % NJ;
+    y = r / NJ;
+  } else if (8 % groups == 0 && NJ % (8 / groups) == 0) {
+    const int s = 8 / groups, c = i & 7, li = i >> 3, xs = NJ / s;
+    g = c / s;
+    x = (c % s) * xs + li % xs;
+    y = li / xs;
+  } else {
+    x = i % NJ;
+    y = (i / NJ) % RT;
+    g = i / (NJ * RT);
+  }
+}
+
 // ---------------------------------------------------------------------------- forward
 // NCH: upper bound of contraction chunks per wave (H <= 64*NCH).
 template <int NCH>
@@ -46,13 +71,14 @@ __global__ void __launch_bounds__(256)
 gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
                     const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
                     float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
-                    int B, int H) {
+                    int B, int H, int groups) {
   __shared__ float red[4][6][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lg = lane >> 4;
-  const int g = blockIdx.z;
-  const int j0 = blockIdx.x * FJ;
-  const int r0 = blockIdx.y * FR;
+  int g, tx, ty;
+  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
+  const int j0 = tx * FJ;
+  const int r0 = ty * FR;
   const float* W = W_hh + g * s_rep;
   const float* hp = h_prev + g * s_hs;
   const int nchunks = H / 16;
@@ -63,8 +89,10 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
 
-  // weights of this wave's chunks: 3 gates x NCH float4
-  float4 w[NCH][3];
+  // All loads are issued before the first MFMA, chunk by chunk (weights of the 3 gates, then
+  // the two row blocks of h), so the MFMAs of chunk i only wait for the loads up to chunk i;
+  // the epilogue's own inputs (gx_t, h_prev, bias) follow and arrive during the matrix work.
+  float4 w[NCH][3], a[NCH][2];
 #pragma unroll
   for (int i = 0; i < NCH; ++i) {
     const int c = wave + 4 * i;
@@ -72,17 +100,25 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 #pragma unroll
     for (int q = 0; q < 3; ++q)
       w[i][q] = ld4_or_zero(W + (long)(q * H + j0 + lr) * H + 16 * c + 4 * lg, ok);
-  }
-  // all operand loads are issued before the first MFMA so that their latencies overlap
-  float4 a[NCH][2];
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int c = wave + 4 * i;
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb) {
       const int row = r0 + rb * 16 + lr;
-      a[i][rb] = ld4_or_zero(hp + (long)row * H + 16 * c + 4 * lg, c < nchunks && row < B);
+      a[i][rb] = ld4_or_zero(hp + (long)row * H + 16 * c + 4 * lg, ok && row < B);
     }
+  }
+  const float* bh = b_hh + g * s_rep;
+  const int j = j0 + lr;
+  float gxv[2][3], hpv[2], bias[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const bool ok = row < B;
+    const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
+    hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
   }
 #pragma unroll
   for (int i = 0; i < NCH; ++i)
@@ -98,8 +134,6 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 #pragma unroll
       for (int v = 0; v < 4; ++v) red[wave][rb * 3 + q][v][lane] = acc[rb][q][v];
   __syncthreads();
-  const float* bh = b_hh + g * s_rep;
-  const int j = j0 + lr;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
@@ -107,15 +141,13 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 #pragma unroll
     for (int q = 0; q < 3; ++q)
       gh[q] = ((red[0][rb * 3 + q][wave][lane] + red[1][rb * 3 + q][wave][lane]) +
-               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bh[q * H + j];
+               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bias[q];
     if (row < B) {
-      const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
-      const float hpv = hp[(long)row * H + j];
-      const float r = sigm(gxr[j] + gh[0]);
-      const float z = sigm(gxr[H + j] + gh[1]);
+      const float r = sigm(gxv[rb][0] + gh[0]);
+      const float z = sigm(gxv[rb][1] + gh[1]);
       const float qv = gh[2];
-      const float n = tanhf(gxr[2 * H + j] + r * qv);
-      h_out[g * s_hs + (long)row * H + j] = (1.0f - z) * n + z * hpv;
+      const float n = tanhf(gxv[rb][2] + r * qv);
+      h_out[g * s_hs + (long)row * H + j] = (1.0f - z) * n + z * hpv[rb];
       float* sv = sv_t + g * s_sv + (long)row * 4 * H;
       sv[j] = r;
       sv[H + j] = z;
@@ -128,10 +160,10 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
                                long s_gx, const float* h_prev, float* h_out, long s_hs, float* sv_t,
                                long s_sv, int B, int H, int groups, hipStream_t s) {
-  dim3 grid(H / FJ, (B + FR - 1) / FR, groups);
+  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
 #define HPSGD_FWD(N)                                                                              \
   hipLaunchKernelGGL(gru_fwd_step_kernel<N>, grid, dim3(256), 0, s, W_hh, b_hh, s_rep, gx_t, s_gx, \
-                     h_prev, h_out, s_hs, sv_t, s_sv, B, H)
+                     h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups)
   const int per_wave = (H / 16 + 3) / 4;
   if (per_wave <= 2) HPSGD_FWD(2);
   else if (per_wave <= 4) HPSGD_FWD(4);
@@ -151,36 +183,51 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
                     long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
                     long s_above, const float* __restrict__ sv_t, long s_sv,
                     const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
-                    float* __restrict__ dgh_t, int B, int H) {
+                    float* __restrict__ dgh_t, int B, int H, int groups) {
   __shared__ float red[4][2][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lg = lane >> 4;
-  const int g = blockIdx.z;
-  const int j0 = blockIdx.x * FJ;
-  const int r0 = blockIdx.y * FR;
+  int g, tx, ty;
+  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
+  const int j0 = tx * FJ;
+  const int r0 = ty * FR;
   const int H3 = 3 * H;
   const int nchunks = H3 / 16;
 
   floatx4 acc[2];
   acc[0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   acc[1] = acc[0];
+  const int j = j0 + lr;
+  // the epilogue's inputs do not depend on the matrix work: they are requested first and
+  // arrive while it runs
+  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const bool ok = row < B;
+    const long e = (long)row * H + j;
+    const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+    r_[rb] = ok ? sv[j] : 0.f;
+    z_[rb] = ok ? sv[H + j] : 0.f;
+    n_[rb] = ok ? sv[2 * H + j] : 0.f;
+    q_[rb] = ok ? sv[3 * H + j] : 0.f;
+    hp_[rb] = ok ? h_prev[g * s_hs + e] : 0.f;
+    dh_[rb] = ok ? D[g * s_D + e] : 0.f;
+    if (ok && above) dh_[rb] += above[g * s_above + e];
+  }
   if (dgh_next) {
     const float* Wt = WT + g * s_wt + (long)(j0 + lr) * H3;
     const float* dg = dgh_next + g * s_dg;
-    float4 w[NCH];
+    float4 w[NCH], a[NCH][2];
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = wave + 4 * i;
-      w[i] = ld4_or_zero(Wt + 16 * c + 4 * lg, c < nchunks);
-    }
-    float4 a[NCH][2];
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = wave + 4 * i;
+      const bool ok = c < nchunks;
+      w[i] = ld4_or_zero(Wt + 16 * c + 4 * lg, ok);
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) {
         const int row = r0 + rb * 16 + lr;
-        a[i][rb] = ld4_or_zero(dg + (long)row * H3 + 16 * c + 4 * lg, c < nchunks && row < B);
+        a[i][rb] = ld4_or_zero(dg + (long)row * H3 + 16 * c + 4 * lg, ok && row < B);
       }
     }
 #pragma unroll
@@ -194,7 +241,6 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
 #pragma unroll
     for (int v = 0; v < 4; ++v) red[wave][rb][v][lane] = acc[rb][v];
   __syncthreads();
-  const int j = j0 + lr;
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
@@ -202,13 +248,10 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
                       (red[2][rb][wave][lane] + red[3][rb][wave][lane]);
     if (row < B) {
       const long e = (long)row * H + j;
-      float dh = D[g * s_D + e] + rec;
-      if (above) dh += above[g * s_above + e];
-      const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
-      const float r = sv[j], z = sv[H + j], n = sv[2 * H + j], q = sv[3 * H + j];
-      const float hp = h_prev[g * s_hs + e];
+      const float dh = dh_[rb] + rec;
+      const float r = r_[rb], z = z_[rb], n = n_[rb], q = q_[rb];
       const float dn = dh * (1.0f - z);
-      const float dz = dh * (hp - n);
+      const float dz = dh * (hp_[rb] - n);
       const float da_n = dn * (1.0f - n * n);
       const float dq = da_n * r;
       const float da_r = da_n * q * r * (1.0f - r);
@@ -230,10 +273,10 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                long s_D, const float* above, long s_above, const float* sv_t,
                                long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
                                int B, int H, int groups, hipStream_t s) {
-  dim3 grid(H / FJ, (B + FR - 1) / FR, groups);
+  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
 #define HPSGD_BWD(N)                                                                             \
   hipLaunchKernelGGL(gru_bwd_step_kernel<N>, grid, dim3(256), 0, s, WT, s_wt, dgh_next, s_dg, D, \
-                     s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H)
+                     s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups)
   const int per_wave = (3 * H / 16 + 3) / 4;
   if (per_wave <= 6) HPSGD_BWD(6);
   else if (per_wave <= 12) HPSGD_BWD(12);
@@ -242,6 +285,271 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
 #undef HPSGD_BWD
   return hipGetLastError();
 }
+
+// ---------------------------------------------------------------------------- bf16 variants
+// Same tiling with v_mfma_f32_16x16x32_bf16: A lane l holds A[m = l%16][k = 8*(l/16) .. +7],
+// B lane l holds B[k = 8*(l/16) .. +7][n = l%16]: one 16-byte load per operand per 32-wide
+// contraction chunk.  The operands come from bf16 copies (weights converted once per local
+// step, h_t / dgh_t written in both precisions by the previous step's epilogue), i.e. every
+// GEMM operand is the nearest-even bf16 rounding of the fp32 value; accumulation, the cell
+// math and everything stored for later use stay fp32.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+__device__ __forceinline__ bf16x8 ldb8_or_zero(const __bf16* p, bool ok) {
+  bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+  return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
+}
+
+template <int NCH>
+__global__ void __launch_bounds__(256)
+gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh,
+                         long s_rep, const float* __restrict__ gx_t, long s_gx,
+                         const float* __restrict__ h_prev, float* __restrict__ h_out, long s_hs,
+                         const __bf16* __restrict__ hb_prev, __bf16* __restrict__ hb_out, long s_hb,
+                         float* __restrict__ sv_t, long s_sv, int B, int H, int groups) {
+  __shared__ float red[4][6][4][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  int g, tx, ty;
+  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
+  const int j0 = tx * FJ;
+  const int r0 = ty * FR;
+  const __bf16* W = Wb + g * s_wb;
+  const __bf16* hbp = hb_prev + g * s_hb;
+  const float* hp = h_prev + g * s_hs;
+  const int nchunks = H / 32;
+
+  floatx4 acc[2][3];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+
+  bf16x8 w[NCH][3], a[NCH][2];
+#pragma unroll
+  for (int i = 0; i < NCH; ++i) {
+    const int c = wave + 4 * i;
+    const bool ok = c < nchunks;
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      w[i][q] = ldb8_or_zero(W + (long)(q * H + j0 + lr) * H + 32 * c + 8 * lg, ok);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb) {
+      const int row = r0 + rb * 16 + lr;
+      a[i][rb] = ldb8_or_zero(hbp + (long)row * H + 32 * c + 8 * lg, ok && row < B);
+    }
+  }
+  const float* bh = b_hh + g * s_rep;
+  const int j = j0 + lr;
+  float gxv[2][3], hpv[2], bias[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const bool ok = row < B;
+    const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
+    hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
+  }
+#pragma unroll
+  for (int i = 0; i < NCH; ++i)
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int q = 0; q < 3; ++q)
+        acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][rb], w[i][q], acc[rb][q], 0, 0, 0);
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v) red[wave][rb * 3 + q][v][lane] = acc[rb][q][v];
+  __syncthreads();
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    float gh[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+      gh[q] = ((red[0][rb * 3 + q][wave][lane] + red[1][rb * 3 + q][wave][lane]) +
+               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bias[q];
+    if (row < B) {
+      const float r = sigm(gxv[rb][0] + gh[0]);
+      const float z = sigm(gxv[rb][1] + gh[1]);
+      const float qv = gh[2];
+      const float n = tanhf(gxv[rb][2] + r * qv);
+      const float hn = (1.0f - z) * n + z * hpv[rb];
+      h_out[g * s_hs + (long)row * H + j] = hn;
+      hb_out[g * s_hb + (long)row * H + j] = (__bf16)hn;
+      float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+      sv[j] = r;
+      sv[H + j] = z;
+      sv[2 * H + j] = n;
+      sv[3 * H + j] = qv;
+    }
+  }
+}
+
+hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep,
+                                    const float* gx_t, long s_gx, const float* h_prev, float* h_out,
+                                    long s_hs, const void* hb_prev, void* hb_out, long s_hb, float* sv_t,
+                                    long s_sv, int B, int H, int groups, hipStream_t s) {
+  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
+#define HPSGD_FWDB(N)                                                                             \
+  hipLaunchKernelGGL(gru_fwd_step_bf16_kernel<N>, grid, dim3(256), 0, s, (const __bf16*)Wb, s_wb,  \
+                     b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev,         \
+                     (__bf16*)hb_out, s_hb, sv_t, s_sv, B, H, groups)
+  const int per_wave = (H / 32 + 3) / 4;
+  if (per_wave <= 2) HPSGD_FWDB(2);
+  else if (per_wave <= 4) HPSGD_FWDB(4);
+  else if (per_wave <= 8) HPSGD_FWDB(8);
+  else HPSGD_FWDB(16);
+#undef HPSGD_FWDB
+  return hipGetLastError();
+}
+
+template <int NCH>
+__global__ void __launch_bounds__(256)
+gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
+                         const __bf16* __restrict__ dghb_next, __bf16* __restrict__ dghb_t, long s_dgb,
+                         float* __restrict__ D, long s_D, const float* __restrict__ above,
+                         long s_above, const float* __restrict__ sv_t, long s_sv,
+                         const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
+                         float* __restrict__ dgh_t, long s_dg, int B, int H, int groups) {
+  __shared__ float red[4][2][4][64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  int g, tx, ty;
+  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
+  const int j0 = tx * FJ;
+  const int r0 = ty * FR;
+  const int H3 = 3 * H;
+  const int nchunks = H3 / 32;
+  const int j = j0 + lr;
+
+  floatx4 acc[2];
+  acc[0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  acc[1] = acc[0];
+  if (dghb_next) {
+    const __bf16* Wt = WTb + g * s_wt + (long)(j0 + lr) * H3;
+    const __bf16* dg = dghb_next + g * s_dgb;
+    bf16x8 w[NCH], a[NCH][2];
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = wave + 4 * i;
+      const bool ok = c < nchunks;
+      w[i] = ldb8_or_zero(Wt + 32 * c + 8 * lg, ok);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) {
+        const int row = r0 + rb * 16 + lr;
+        a[i][rb] = ldb8_or_zero(dg + (long)row * H3 + 32 * c + 8 * lg, ok && row < B);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0], w[i], acc[0], 0, 0, 0);
+      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1], w[i], acc[1], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[wave][rb][v][lane] = acc[rb][v];
+  __syncthreads();
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const float rec = (red[0][rb][wave][lane] + red[1][rb][wave][lane]) +
+                      (red[2][rb][wave][lane] + red[3][rb][wave][lane]);
+    if (row < B) {
+      const long e = (long)row * H + j;
+      float dh = D[g * s_D + e] + rec;
+      if (above) dh += above[g * s_above + e];
+      const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+      const float r = sv[j], z = sv[H + j], n = sv[2 * H + j], q = sv[3 * H + j];
+      const float hp = h_prev[g * s_hs + e];
+      const float dn = dh * (1.0f - z);
+      const float dz = dh * (hp - n);
+      const float da_n = dn * (1.0f - n * n);
+      const float dq = da_n * r;
+      const float da_r = da_n * q * r * (1.0f - r);
+      const float da_z = dz * z * (1.0f - z);
+      float* ox = dgx_t + g * s_dg + (long)row * H3;
+      float* oh = dgh_t + g * s_dg + (long)row * H3;
+      __bf16* ob = dghb_t + g * s_dgb + (long)row * H3;
+      ox[j] = da_r;
+      ox[H + j] = da_z;
+      ox[2 * H + j] = da_n;
+      oh[j] = da_r;
+      oh[H + j] = da_z;
+      oh[2 * H + j] = dq;
+      ob[j] = (__bf16)da_r;
+      ob[H + j] = (__bf16)da_z;
+      ob[2 * H + j] = (__bf16)dq;
+      D[g * s_D + e] = dh * z;
+    }
+  }
+}
+
+hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb_next, void* dghb_t,
+                                    long s_dgb, float* D, long s_D, const float* above, long s_above,
+                                    const float* sv_t, long s_sv, const float* h_prev, long s_hs,
+                                    float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
+                                    hipStream_t s) {
+  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
+#define HPSGD_BWDB(N)                                                                              \
+  hipLaunchKernelGGL(gru_bwd_step_bf16_kernel<N>, grid, dim3(256), 0, s, (const __bf16*)WTb, s_wt,  \
+                     (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, \
+                     s_sv, h_prev, s_hs, dgx_t, dgh_t, s_dg, B, H, groups)
+  const int per_wave = (3 * H / 32 + 3) / 4;
+  if (per_wave <= 6) HPSGD_BWDB(6);
+  else if (per_wave <= 12) HPSGD_BWDB(12);
+  else if (per_wave <= 24) HPSGD_BWDB(24);
+  else HPSGD_BWDB(48);
+#undef HPSGD_BWDB
+  return hipGetLastError();
+}
+
+// out (bf16) = nearest-even rounding of in (fp32), R x C per group; TRANSPOSE: out[c][r] = in[r][c].
+template <bool TRANSPOSE>
+__global__ void __launch_bounds__(256)
+cvt_bf16_kernel(const float* __restrict__ in, long s_in, __bf16* __restrict__ out, long s_out, int R,
+                int C) {
+  __shared__ float tile[32][33];
+  const int g = blockIdx.z;
+  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
+  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  if (!TRANSPOSE) {
+    for (int i = ty; i < 32; i += 8) {
+      const int r = r0 + i, c = c0 + tx;
+      if (r < R && c < C) out[g * s_out + (long)r * C + c] = (__bf16)in[g * s_in + (long)r * C + c];
+    }
+    return;
+  }
+  for (int i = ty; i < 32; i += 8) {
+    const int r = r0 + i, c = c0 + tx;
+    tile[i][tx] = (r < R && c < C) ? in[g * s_in + (long)r * C + c] : 0.f;
+  }
+  __syncthreads();
+  for (int i = ty; i < 32; i += 8) {
+    const int c = c0 + i, r = r0 + tx;
+    if (r < R && c < C) out[g * s_out + (long)c * R + r] = (__bf16)tile[tx][i];
+  }
+}
+
+hipError_t launch_cvt_bf16(const float* in, long s_in, void* out, long s_out, int R, int C,
+                           bool transpose, int groups, hipStream_t s) {
+  dim3 grid((C + 31) / 32, (R + 31) / 32, groups);
+  if (transpose)
+    hipLaunchKernelGGL(cvt_bf16_kernel<true>, grid, dim3(256), 0, s, in, s_in, (__bf16*)out, s_out, R, C);
+  else
+    hipLaunchKernelGGL(cvt_bf16_kernel<false>, grid, dim3(256), 0, s, in, s_in, (__bf16*)out, s_out, R, C);
+  return hipGetLastError();
+}
+
+bool gru_fused_bf16_supported(int H) { return H % 32 == 0 && H >= 32 && H <= 2048; }
 
 // ---------------------------------------------------------------------------- transpose
 // out[c][r] = in[r][c] for an R x C matrix per group (32x32 tiles through LDS).

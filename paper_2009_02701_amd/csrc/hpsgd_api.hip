@@ -34,6 +34,7 @@ struct hpsgd_ctx {
   size_t ws_floats = 0;
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
+  Region hb, dghb;              // bf16 copies of h and dgh (bf16 precision only)
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
@@ -103,6 +104,10 @@ int build_layout(hpsgd_ctx* c) {
     c->gh = c->alloc((size_t)d.batch * 3 * H);
     c->D = c->alloc((size_t)d.batch * H);
     c->wt = c->alloc(3 * H * H);
+    if (d.prec == HPSGD_BF16_MFMA) {
+      c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
+      c->dghb = c->alloc((TB * 3 * H + 1) / 2);
+    }
     size_t wmax = H;
     if (lm && (size_t)d.embed > wmax) wmax = d.embed;
     c->dx = c->alloc(TB * wmax);
@@ -293,8 +298,27 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                sR, 1, gx, 3 * H, s_gx, EPI_BIAS, rin + c->off(p + ".b_ih"), sR));
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
+      const bool fused_b = bf && gru_fused_bf16_supported(H);
+      // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
+      // not use) and of h
+      void* wb = reg(c->wt);
+      const long s_wb = 2 * (long)c->wt.stride;
+      __bf16* hb = fused_b ? (__bf16*)reg(c->hb) : nullptr;
+      const long s_hb = 2 * (long)c->hb.stride;
+      if (fused_b) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_cvt_bf16(Whh, sR, wb, s_wb, 3 * H, H, false, groups, s));
+        HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
+      }
       for (int t = 0; t < T; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
+        if (fused_b) {
+          HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H,
+                                           s_gx, hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
+                                           hb + (size_t)t * B * H, hb + (size_t)(t + 1) * B * H, s_hb,
+                                           sv + (size_t)t * B * 4 * H, s_sv, B, H, groups, s));
+          continue;
+        }
         if (fused) {
           HIP_TRY(launch_gru_fwd_step(Whh, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H, s_gx,
                                       hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
@@ -363,14 +387,30 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
+      const bool fused_b = bf && gru_fused_bf16_supported(H);
       float* wt = reg(c->wt);
       const long s_wt = (long)c->wt.stride;
+      __bf16* dghb = fused_b ? (__bf16*)reg(c->dghb) : nullptr;
+      const long s_dgb = 2 * (long)c->dghb.stride;
       if (fused) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
       }
+      if (fused_b) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_cvt_bf16(Whh, sR, wt, 2 * s_wt, 3 * H, H, true, groups, s));
+      }
       for (int t = T - 1; t >= 0; --t) {
         const float* above_t = above ? above + (size_t)t * B * H : nullptr;
+        if (fused_b) {
+          role = HPSGD_ROLE_GEMM_REC_BWD;
+          HIP_TRY(launch_gru_bwd_step_bf16(wt, 2 * s_wt, t + 1 < T ? dghb + (size_t)(t + 1) * B * 3 * H : nullptr,
+                                           dghb + (size_t)t * B * 3 * H, s_dgb, D, s_D, above_t, s_dx,
+                                           sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
+                                           dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx, B, H,
+                                           groups, s));
+          continue;
+        }
         if (fused) {
           role = HPSGD_ROLE_GEMM_REC_BWD;
           HIP_TRY(launch_gru_bwd_step(wt, s_wt, t + 1 < T ? dgh + (size_t)(t + 1) * B * 3 * H : nullptr, s_gx,

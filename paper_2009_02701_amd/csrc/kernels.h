@@ -70,6 +70,20 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                long s_D, const float* above, long s_above, const float* sv_t,
                                long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
                                int B, int H, int groups, hipStream_t s);
+// bf16-operand variants (strides of bf16 buffers are in bf16 elements)
+bool gru_fused_bf16_supported(int H);
+hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep,
+                                    const float* gx_t, long s_gx, const float* h_prev, float* h_out,
+                                    long s_hs, const void* hb_prev, void* hb_out, long s_hb, float* sv_t,
+                                    long s_sv, int B, int H, int groups, hipStream_t s);
+hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb_next, void* dghb_t,
+                                    long s_dgb, float* D, long s_D, const float* above, long s_above,
+                                    const float* sv_t, long s_sv, const float* h_prev, long s_hs,
+                                    float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
+                                    hipStream_t s);
+// out(bf16) = round(in), R x C per group; transpose: out[c][r] = in[r][c]
+hipError_t launch_cvt_bf16(const float* in, long s_in, void* out, long s_out, int R, int C,
+                           bool transpose, int groups, hipStream_t s);
 // out[c][r] = in[r][c], R x C per group
 hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
                             int groups, hipStream_t s);
