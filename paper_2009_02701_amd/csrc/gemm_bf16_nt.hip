@@ -1,0 +1,256 @@
+// Grouped bf16 GEMM, both operands unit-stride along the contraction ("NT"):
+//
+//   C[g] (M x N, fp32) = A[g] (M x Kd) * B[g]^T,   A stored [M][Kd], B stored [N][Kd]
+//
+// Each operand is either fp32 (rounded to bf16 nearest-even while it is staged) or already
+// bf16 (a rounded copy made once by its producer), chosen per operand at compile time.
+// Every GEMM of the bf16 training step is brought into this one shape by keeping transposed
+// bf16 copies of the operands whose natural layout is contraction-major (see hpsgd_api.hip).
+//
+// Tile 128 x 128 x 64 per workgroup of 4 waves (each wave 64 x 64 = 2 x 2 blocks of
+// v_mfma_f32_32x32x16_bf16), LDS double-buffered with one barrier per k-tile: while the
+// matrix cores work on buffer kt&1, the global loads of tile kt+1 are in flight and are
+// written to the other buffer afterwards.  72 KB of LDS per workgroup keeps two workgroups
+// per CU, so one's barrier wait is covered by the other's MFMAs.
+// LDS rows are [i][k] with a pitch of 72 halves (144 B): the 16-byte operand reads of 16
+// consecutive rows then fall on 64 distinct banks.
+#include "kernels.h"
+
+namespace hpsgd {
+
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+static constexpr int NBM = 128, NBN = 128, NBK = 64, NPITCH = NBK + 8;
+static constexpr int NTHREADS = 256;
+
+// 8 consecutive contraction elements of one row, as loaded from memory.  Loads are
+// branch-free and nothing touches the loaded registers until they are packed for LDS (any
+// use would force a wait right after the load and undo the prefetch): the caller clamps the
+// row and the column into range (rows beyond M or N only feed outputs that are never stored)
+// and a unit that lies beyond Kd is zeroed when it is packed.
+template <typename T>
+struct Unit8;
+
+template <>
+struct Unit8<float> {
+  float4 lo, hi;
+  __device__ __forceinline__ void load(const float* __restrict__ p) {
+    lo = *reinterpret_cast<const float4*>(p);
+    hi = *reinterpret_cast<const float4*>(p + 4);
+  }
+  __device__ __forceinline__ bf16x8 pack(bool valid) const {
+    bf16x8 v;
+    v[0] = (__bf16)lo.x; v[1] = (__bf16)lo.y; v[2] = (__bf16)lo.z; v[3] = (__bf16)lo.w;
+    v[4] = (__bf16)hi.x; v[5] = (__bf16)hi.y; v[6] = (__bf16)hi.z; v[7] = (__bf16)hi.w;
+    if (!valid) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = (__bf16)0.f;
+    }
+    return v;
+  }
+};
+
+template <>
+struct Unit8<__bf16> {
+  bf16x8 v;
+  __device__ __forceinline__ void load(const __bf16* __restrict__ p) {
+    v = *reinterpret_cast<const bf16x8*>(p);
+  }
+  __device__ __forceinline__ bf16x8 pack(bool valid) const {
+    bf16x8 r = v;
+    if (!valid) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) r[e] = (__bf16)0.f;
+    }
+    return r;
+  }
+};
+
+struct GemmNtDesc {
+  const void* A; long lda; long strideA;   // in elements of A's type
+  const void* B; long ldb; long strideB;
+  float* C; long ldc; long strideC;
+  const float* bias; long strideBias;      // per column n, nullable
+  int M, N, Kd, groups;
+};
+
+template <typename TA, typename TB>
+__global__ void __launch_bounds__(NTHREADS, 2)
+gemm_bf16_nt_kernel(GemmNtDesc d) {
+  constexpr int UPT = NBM * (NBK / 8) / NTHREADS;  // 8-element units per thread per operand (4)
+  extern __shared__ __attribute__((aligned(16))) unsigned char nt_smem[];
+  __bf16(*sA)[NBM * NPITCH] = reinterpret_cast<__bf16(*)[NBM * NPITCH]>(nt_smem);
+  __bf16(*sB)[NBN * NPITCH] = reinterpret_cast<__bf16(*)[NBN * NPITCH]>(nt_smem + 2 * NBM * NPITCH * 2);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int lrow = lane & 31, lk = lane >> 5;
+  // Tile order.  Workgroup i runs on XCD i % 8 and every XCD has its own L2.  The dimension
+  // with more tiles ("slow") is dealt out to the XCDs (tile s goes to XCD s % 8), and on an
+  // XCD consecutive workgroups sweep the other ("fast") dimension for a fixed slow tile:
+  // the slow operand's tile is then fetched from memory by one L2 only and is reused at once
+  // by all fast tiles, while the fast operand (the smaller one) stays resident in every L2.
+  int g, tile_m, tile_n;
+  {
+    const int tm = (d.M + NBM - 1) / NBM, tn = (d.N + NBN - 1) / NBN;
+    const bool slow_is_n = tn >= tm;
+    const int ts = slow_is_n ? tn : tm, tf = slow_is_n ? tm : tn;
+    const int s8 = (ts + 7) >> 3;
+    const int c = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int f = li % tf, sl = (li / tf) % s8;
+    g = li / (tf * s8);
+    const int st = c + 8 * sl;
+    if (st >= ts) return;  // padding of the last round of slow tiles
+    tile_m = slow_is_n ? f : st;
+    tile_n = slow_is_n ? st : f;
+  }
+  const int m0 = tile_m * NBM, n0 = tile_n * NBN;
+  const TA* __restrict__ A = reinterpret_cast<const TA*>(d.A) + (long)g * d.strideA;
+  const TB* __restrict__ B = reinterpret_cast<const TB*>(d.B) + (long)g * d.strideB;
+
+  // two register stages: while tile kt is multiplied out of LDS, the global loads of tiles
+  // kt+1 and kt+2 are in flight
+  Unit8<TA> ra[2][UPT];
+  Unit8<TB> rb[2][UPT];
+  // per-thread row bases (clamped into the matrix) are loop invariants
+  const TA* arow[UPT];
+  const TB* brow[UPT];
+#pragma unroll
+  for (int u = 0; u < UPT; ++u) {
+    const int i = (tid + u * NTHREADS) >> 3;
+    arow[u] = A + (long)min(m0 + i, d.M - 1) * d.lda;
+    brow[u] = B + (long)min(n0 + i, d.N - 1) * d.ldb;
+  }
+  const int kofs = (tid & 7) << 3;  // NTHREADS is a multiple of 8: the same for every unit of a thread
+  bool rvalid[2] = {true, true};
+  auto load_tiles = [&](int st, int kt) {
+    const int k = kt * NBK + kofs;
+    rvalid[st] = k < d.Kd;                // Kd is a multiple of 8: a unit is all in or all out
+    const int kc = rvalid[st] ? k : 0;
+#pragma unroll
+    for (int u = 0; u < UPT; ++u) {
+      ra[st][u].load(arow[u] + kc);
+      rb[st][u].load(brow[u] + kc);
+    }
+  };
+  auto store_tiles = [&](int st, int buf) {
+#pragma unroll
+    for (int u = 0; u < UPT; ++u) {
+      const int unit = tid + u * NTHREADS;
+      const int i = unit >> 3, k = (unit & 7) << 3;
+      *reinterpret_cast<bf16x8*>(&sA[buf][i * NPITCH + k]) = ra[st][u].pack(rvalid[st]);
+      *reinterpret_cast<bf16x8*>(&sB[buf][i * NPITCH + k]) = rb[st][u].pack(rvalid[st]);
+    }
+  };
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  auto compute = [&](int buf) {
+#pragma unroll
+    for (int kk = 0; kk < NBK; kk += 16) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[i] = *reinterpret_cast<const bf16x8*>(&sA[buf][(wm * 64 + i * 32 + lrow) * NPITCH + kk + 8 * lk]);
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        b[j] = *reinterpret_cast<const bf16x8*>(&sB[buf][(wn * 64 + j * 32 + lrow) * NPITCH + kk + 8 * lk]);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  // The loop body has no branch: tiles past the end of the contraction load from column 0
+  // and are packed as zeros, so the extra stores and MFMAs of the last round add nothing.
+  // (With conditionals around the loads the compiler can no longer count the outstanding
+  // loads and waits for all of them before every LDS store, which undoes the prefetch.)
+  const int nk = (d.Kd + NBK - 1) / NBK;
+  load_tiles(0, 0);
+  store_tiles(0, 0);
+  load_tiles(0, 1);
+  load_tiles(1, 2);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    compute(0);               // tile kt
+    store_tiles(0, 1);        // tile kt+1 -> buffer 1
+    load_tiles(0, kt + 3);
+    __syncthreads();
+    compute(1);               // tile kt+1
+    store_tiles(1, 0);        // tile kt+2 -> buffer 0
+    load_tiles(1, kt + 4);
+    __syncthreads();
+  }
+
+  float* C = d.C + (long)g * d.strideC;
+  const float* bias = d.bias ? d.bias + (long)g * d.strideBias : nullptr;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int col = n0 + wn * 64 + j * 32 + lrow;
+    if (col >= d.N) continue;
+    const float bv = bias ? bias[col] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = m0 + wm * 64 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+        if (row < d.M) C[(long)row * d.ldc + col] = acc[i][j][v] + bv;
+      }
+  }
+}
+
+// a_bf16 / b_bf16: the operand is stored as bf16 (else fp32).  Leading dimensions and group
+// strides are in elements of the operand's own type.  Requires 16-byte aligned bases, row
+// pitches and group strides that are multiples of 16 bytes, and Kd a multiple of 8
+// (gemm_bf16_nt_supported); returns hipErrorInvalidValue otherwise.
+bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, int Kd) {
+  const long q = is_bf16 ? 8 : 4;
+  return ((uintptr_t)p & 15) == 0 && ld % q == 0 && stride % q == 0 && Kd % 8 == 0 && Kd >= 8;
+}
+
+hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
+                               long ldb, long sB, float* C, long ldc, long sC, const float* bias,
+                               long sBias, int M, int N, int Kd, int groups, hipStream_t s) {
+  if (M <= 0 || N <= 0 || groups <= 0) return hipSuccess;
+  GemmNtDesc d;
+  d.A = A; d.lda = lda; d.strideA = sA;
+  d.B = B; d.ldb = ldb; d.strideB = sB;
+  d.C = C; d.ldc = ldc; d.strideC = sC;
+  d.bias = bias; d.strideBias = sBias;
+  d.M = M; d.N = N; d.Kd = Kd; d.groups = groups;
+  if (!gemm_bf16_nt_supported(A, a_bf16, lda, sA, Kd) || !gemm_bf16_nt_supported(B, b_bf16, ldb, sB, Kd))
+    return hipErrorInvalidValue;
+  const int tm = (M + NBM - 1) / NBM, tn = (N + NBN - 1) / NBN;
+  const int ts = tn >= tm ? tn : tm, tf = tn >= tm ? tm : tn;
+  dim3 grid(8 * ((ts + 7) / 8) * tf * groups);  // see the tile order in the kernel
+  dim3 block(NTHREADS);
+  constexpr size_t smem = (size_t)2 * (NBM + NBN) * NPITCH * sizeof(__bf16);  // 72 KB: above the static limit
+#define HPSGD_NT(TA, TB)                                                                          \
+  do {                                                                                            \
+    static bool ready = false; /* per instantiation: allow the large dynamic LDS allocation */    \
+    if (!ready) {                                                                                 \
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel<TA, TB>,                \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);  \
+      if (e != hipSuccess) return e;                                                              \
+      ready = true;                                                                               \
+    }                                                                                             \
+    hipLaunchKernelGGL((gemm_bf16_nt_kernel<TA, TB>), grid, block, smem, s, d);       \
+  } while (0)
+  if (a_bf16 && b_bf16) HPSGD_NT(__bf16, __bf16);
+  else if (a_bf16) HPSGD_NT(__bf16, float);
+  else if (b_bf16) HPSGD_NT(float, __bf16);
+  else HPSGD_NT(float, float);
+#undef HPSGD_NT
+  return hipGetLastError();
+}
+
+}  // namespace hpsgd

@@ -512,11 +512,12 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
   return hipGetLastError();
 }
 
-// out (bf16) = nearest-even rounding of in (fp32), R x C per group; TRANSPOSE: out[c][r] = in[r][c].
+// out (bf16) = nearest-even rounding of in (fp32, R x C, row pitch ld_in) per group;
+// TRANSPOSE: out[c][r] = in[r][c] with row pitch ld_out, else out[r][c] with row pitch ld_out.
 template <bool TRANSPOSE>
 __global__ void __launch_bounds__(256)
-cvt_bf16_kernel(const float* __restrict__ in, long s_in, __bf16* __restrict__ out, long s_out, int R,
-                int C) {
+cvt_bf16_kernel(const float* __restrict__ in, long ld_in, long s_in, __bf16* __restrict__ out,
+                long ld_out, long s_out, int R, int C) {
   __shared__ float tile[32][33];
   const int g = blockIdx.z;
   const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
@@ -524,28 +525,30 @@ cvt_bf16_kernel(const float* __restrict__ in, long s_in, __bf16* __restrict__ ou
   if (!TRANSPOSE) {
     for (int i = ty; i < 32; i += 8) {
       const int r = r0 + i, c = c0 + tx;
-      if (r < R && c < C) out[g * s_out + (long)r * C + c] = (__bf16)in[g * s_in + (long)r * C + c];
+      if (r < R && c < C) out[g * s_out + (long)r * ld_out + c] = (__bf16)in[g * s_in + (long)r * ld_in + c];
     }
     return;
   }
   for (int i = ty; i < 32; i += 8) {
     const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < R && c < C) ? in[g * s_in + (long)r * C + c] : 0.f;
+    tile[i][tx] = (r < R && c < C) ? in[g * s_in + (long)r * ld_in + c] : 0.f;
   }
   __syncthreads();
   for (int i = ty; i < 32; i += 8) {
     const int c = c0 + i, r = r0 + tx;
-    if (r < R && c < C) out[g * s_out + (long)c * R + r] = (__bf16)tile[tx][i];
+    if (r < R && c < C) out[g * s_out + (long)c * ld_out + r] = (__bf16)tile[tx][i];
   }
 }
 
-hipError_t launch_cvt_bf16(const float* in, long s_in, void* out, long s_out, int R, int C,
-                           bool transpose, int groups, hipStream_t s) {
+hipError_t launch_cvt_bf16(const float* in, long ld_in, long s_in, void* out, long ld_out, long s_out,
+                           int R, int C, bool transpose, int groups, hipStream_t s) {
   dim3 grid((C + 31) / 32, (R + 31) / 32, groups);
   if (transpose)
-    hipLaunchKernelGGL(cvt_bf16_kernel<true>, grid, dim3(256), 0, s, in, s_in, (__bf16*)out, s_out, R, C);
+    hipLaunchKernelGGL(cvt_bf16_kernel<true>, grid, dim3(256), 0, s, in, ld_in, s_in, (__bf16*)out, ld_out,
+                       s_out, R, C);
   else
-    hipLaunchKernelGGL(cvt_bf16_kernel<false>, grid, dim3(256), 0, s, in, s_in, (__bf16*)out, s_out, R, C);
+    hipLaunchKernelGGL(cvt_bf16_kernel<false>, grid, dim3(256), 0, s, in, ld_in, s_in, (__bf16*)out, ld_out,
+                       s_out, R, C);
   return hipGetLastError();
 }
 

@@ -35,6 +35,10 @@ struct hpsgd_ctx {
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
   Region hb, dghb;              // bf16 copies of h and dgh (bf16 precision only)
+  // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
+  // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
+  Region dgxT, dghT, xT, dlogT, wihT, woT;
+  std::vector<Region> hsT;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
@@ -107,6 +111,17 @@ int build_layout(hpsgd_ctx* c) {
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
+      const size_t TBp = round_up(TB, 8), TB1p = round_up(TB + d.batch, 8);
+      const size_t win0 = lm ? d.embed : d.input;
+      const size_t wmax = win0 > H ? win0 : H;
+      c->dgxT = c->alloc(3 * H * TBp / 2);
+      c->dghT = c->alloc(3 * H * TBp / 2);
+      c->xT = c->alloc(win0 * TBp / 2);
+      for (int l = 0; l < d.layers; ++l) c->hsT.push_back(c->alloc(H * TB1p / 2));
+      const size_t nr = lm ? TB : (size_t)d.batch;
+      c->dlogT = c->alloc((size_t)classes * round_up(nr, 8) / 2);
+      c->wihT = c->alloc(wmax * 3 * H / 2);
+      c->woT = c->alloc(H * round_up(classes, 8) / 2);
     }
     size_t wmax = H;
     if (lm && (size_t)d.embed > wmax) wmax = d.embed;
@@ -187,6 +202,29 @@ int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float*
   g.M = M; g.N = N; g.Kd = Kd; g.groups = groups;
   g.epilogue = epi; g.bf16 = bf16;
   return launch_gemm(g, s) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
+}
+
+// A k-contiguous view of a GEMM operand for the NT kernel (p == nullptr: none available).
+struct NtView {
+  const void* p = nullptr;
+  int bf16 = 0;
+  long ld = 0, stride = 0;
+};
+
+// bf16 precision: use the NT kernel when both operands have a usable contraction-contiguous
+// view (C = a b^T), otherwise the generic kernel on the original fp32 operands.
+int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda, long sA,
+          int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC, int epi,
+          const float* aux, long sAux, const NtView& a, const NtView& b) {
+  if (bf16 && a.p && b.p && (epi == EPI_STORE || epi == EPI_BIAS) &&
+      gemm_bf16_nt_supported(a.p, a.bf16, a.ld, a.stride, Kd) &&
+      gemm_bf16_nt_supported(b.p, b.bf16, b.ld, b.stride, Kd) && ((uintptr_t)C & 3) == 0) {
+    return launch_gemm_bf16_nt(a.p, a.bf16, a.ld, a.stride, b.p, b.bf16, b.ld, b.stride, C, ldc, sC,
+                               epi == EPI_BIAS ? aux : nullptr, sAux, M, N, Kd, groups, s) == hipSuccess
+               ? HPSGD_OK
+               : HPSGD_EHIP;
+  }
+  return gemm(s, groups, bf16, M, N, Kd, A, lda, sA, tA, B, ldb, sB, tB, C, ldc, sC, epi, aux, sAux);
 }
 
 #define TRY(expr)                    \
@@ -294,8 +332,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       role = HPSGD_ROLE_OTHER;
       HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s));
       role = HPSGD_ROLE_GEMM_INPUT;
-      TRY(gemm(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, rin + c->off(p + ".W_ih"), width,
-               sR, 1, gx, 3 * H, s_gx, EPI_BIAS, rin + c->off(p + ".b_ih"), sR));
+      {
+        const float* Wih = rin + c->off(p + ".W_ih");
+        const NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
+        TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
+                  EPI_BIAS, rin + c->off(p + ".b_ih"), sR, va, vb));
+      }
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
@@ -307,7 +349,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_hb = 2 * (long)c->hb.stride;
       if (fused_b) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_cvt_bf16(Whh, sR, wb, s_wb, 3 * H, H, false, groups, s));
+        HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
         HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
       }
       for (int t = 0; t < T; ++t) {
@@ -343,27 +385,56 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
     const size_t oW = c->off("head.W"), ob = c->off("head.b");
     role = HPSGD_ROLE_GEMM_HEAD;
-    TRY(gemm(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
-             s_log, EPI_BIAS, rin + ob, sR));
+    {
+      const NtView va{feats, 0, H, s_top}, vb{rin + oW, 0, H, sR};
+      TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
+                s_log, EPI_BIAS, rin + ob, sR, va, vb));
+    }
     role = HPSGD_ROLE_LOSS;
     HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
                               classes, groups, s));
     if (loss_out)
       HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
     // ---- backward: head
+    // bf16 precision: transposed bf16 copies (contraction-contiguous operands for the NT kernel)
+    const bool ntc = bf && (B % 8 == 0) && (H % 8 == 0);
+    const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
+    const long nrp = (long)round_up(nrows, 8), clp = (long)round_up(classes, 8);
+    auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
+    if (ntc) {
+      role = HPSGD_ROLE_OTHER;
+      for (int l = 0; l < L; ++l)  // hs^T of every layer: [H][(T+1)B]
+        HIP_TRY(launch_cvt_bf16(reg(c->hs[l]), H, (long)c->hs[l].stride, bfreg(c->hsT[l]), TB1p,
+                                2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
+      HIP_TRY(launch_cvt_bf16(logits, classes, s_log, bfreg(c->dlogT), nrp, 2 * (long)c->dlogT.stride, nrows,
+                              classes, true, groups, s));
+      HIP_TRY(launch_cvt_bf16(rin + oW, H, sR, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
+                              groups, s));
+    }
     role = HPSGD_ROLE_GEMM_HEAD;
-    TRY(gemm(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW,
-             H, sG, EPI_STORE, nullptr, 0));
-    HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
+    {
+      NtView va, vb, vw;
+      if (ntc) {
+        va = NtView{bfreg(c->dlogT), 1, nrp, 2 * (long)c->dlogT.stride};
+        vb = NtView{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
+        vw = NtView{bfreg(c->woT), 1, clp, 2 * (long)c->woT.stride};
+      }
+      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW, H,
+                sG, EPI_STORE, nullptr, 0, va, vb));
+      HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
+      const NtView vl{logits, 0, classes, s_log};
+      if (lm) {
+        TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H, s_dx,
+                  EPI_STORE, nullptr, 0, vl, vw));
+      } else {
+        TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
+                  EPI_STORE, nullptr, 0, vl, vw));
+      }
+    }
     const float* above = nullptr;
     if (lm) {
-      TRY(gemm(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H,
-               s_dx, EPI_STORE, nullptr, 0));
       above = dx;
       HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
-    } else {
-      TRY(gemm(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
-               EPI_STORE, nullptr, 0));
     }
     // ---- backward: GRU layers, top to bottom
     for (int l = L - 1; l >= 0; --l) {
@@ -398,7 +469,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (fused_b) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_cvt_bf16(Whh, sR, wt, 2 * s_wt, 3 * H, H, true, groups, s));
+        HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
       }
       for (int t = T - 1; t >= 0; --t) {
         const float* above_t = above ? above + (size_t)t * B * H : nullptr;
@@ -428,17 +499,43 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0, Whh, H, sR, 0, D,
                    H, s_D, EPI_ACCUM, nullptr, 0));
       }
+      const float* Wih = rin + c->off(p + ".W_ih");
+      const bool need_dx = l > 0 || lm;
+      NtView v_dgxT, v_dghT, v_xT, v_hsT, v_wihT;
+      if (ntc && win % 8 == 0) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_cvt_bf16(dgx, 3 * H, s_gx, bfreg(c->dgxT), TBp, 2 * (long)c->dgxT.stride, TB, 3 * H, true,
+                                groups, s));
+        HIP_TRY(launch_cvt_bf16(dgh, 3 * H, s_gx, bfreg(c->dghT), TBp, 2 * (long)c->dghT.stride, TB, 3 * H, true,
+                                groups, s));
+        v_dgxT = NtView{bfreg(c->dgxT), 1, TBp, 2 * (long)c->dgxT.stride};
+        v_dghT = NtView{bfreg(c->dghT), 1, TBp, 2 * (long)c->dghT.stride};
+        v_hsT = NtView{bfreg(c->hsT[l]), 1, TB1p, 2 * (long)c->hsT[l].stride};
+        if (l > 0) {
+          v_xT = NtView{bfreg(c->hsT[l - 1]) + B, 1, TB1p, 2 * (long)c->hsT[l - 1].stride};
+        } else {
+          HIP_TRY(launch_cvt_bf16(layer_in, win, s_layer_in, bfreg(c->xT), TBp, 2 * (long)c->xT.stride, TB, win,
+                                  true, groups, s));
+          v_xT = NtView{bfreg(c->xT), 1, TBp, 2 * (long)c->xT.stride};
+        }
+        if (need_dx) {
+          HIP_TRY(launch_cvt_bf16(Wih, win, sR, bfreg(c->wihT), 3 * H, 2 * (long)c->wihT.stride, 3 * H, win, true,
+                                  groups, s));
+          v_wihT = NtView{bfreg(c->wihT), 1, 3 * H, 2 * (long)c->wihT.stride};
+        }
+      }
       role = HPSGD_ROLE_GEMM_WGRAD;
-      TRY(gemm(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
-               grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0));
-      TRY(gemm(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0,
-               grad + c->off(p + ".W_hh"), H, sG, EPI_STORE, nullptr, 0));
+      TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
+                grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0, v_dgxT, v_xT));
+      TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, grad + c->off(p + ".W_hh"), H,
+                sG, EPI_STORE, nullptr, 0, v_dghT, v_hsT));
       HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
       HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
       role = HPSGD_ROLE_GEMM_DX;
-      if (l > 0 || lm) {
-        TRY(gemm(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, rin + c->off(p + ".W_ih"), win, sR,
-                 0, dx, win, s_dx, EPI_STORE, nullptr, 0));
+      if (need_dx) {
+        const NtView v_dgx{dgx, 0, 3 * H, s_gx};
+        TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
+                  nullptr, 0, v_dgx, v_wihT));
         above = dx;
       }
       role = HPSGD_ROLE_OTHER;

@@ -81,9 +81,15 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
                                     const float* sv_t, long s_sv, const float* h_prev, long s_hs,
                                     float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
                                     hipStream_t s);
-// out(bf16) = round(in), R x C per group; transpose: out[c][r] = in[r][c]
-hipError_t launch_cvt_bf16(const float* in, long s_in, void* out, long s_out, int R, int C,
-                           bool transpose, int groups, hipStream_t s);
+// out(bf16) = round(in), in is R x C with row pitch ld_in; transpose: out[c][r] = in[r][c];
+// ld_out is the row pitch of out, strides of out in bf16 elements
+hipError_t launch_cvt_bf16(const float* in, long ld_in, long s_in, void* out, long ld_out, long s_out,
+                           int R, int C, bool transpose, int groups, hipStream_t s);
+// bf16 GEMM with both operands unit-stride along the contraction (gemm_bf16_nt.hip)
+bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, int Kd);
+hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
+                               long ldb, long sB, float* C, long ldc, long sC, const float* bias,
+                               long sBias, int M, int N, int Kd, int groups, hipStream_t s);
 // out[c][r] = in[r][c], R x C per group
 hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
                             int groups, hipStream_t s);

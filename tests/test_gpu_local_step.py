@@ -33,6 +33,9 @@ BF16 = {
     "lm_small_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=50, embed=12, hidden=24, seq_len=7, batch=5, K=2),
     "lm_tiles_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=300, embed=40, hidden=72, seq_len=6, batch=12, K=2),
     "lm_fused_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=9, K=2),
+    "lm_nt_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=8, K=2),
+    "lm_nt_bf16_tiles": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=72, hidden=160, seq_len=19, batch=16, K=2),
+    "cls_nt_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", layers=2, input=64, hidden=160, seq_len=4, batch=72, K=2),
     "gru_cls_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=64, hidden=160, seq_len=4, batch=70, K=2),
     "mlp_bf16": wl.scaled(wl.CONFIGS["mlp"], prec="bf16", dims=[200, 300, 140, 10], batch=130, K=2),
 }
