@@ -514,35 +514,53 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
 
 // out (bf16) = nearest-even rounding of in (fp32, R x C, row pitch ld_in) per group;
 // TRANSPOSE: out[c][r] = in[r][c] with row pitch ld_out, else out[r][c] with row pitch ld_out.
+// 64 x 64 tiles: rows are read 256 bytes at a time, and the transposed tile is written as
+// packed pairs of bf16, 128 bytes per output row.
 template <bool TRANSPOSE>
 __global__ void __launch_bounds__(256)
 cvt_bf16_kernel(const float* __restrict__ in, long ld_in, long s_in, __bf16* __restrict__ out,
                 long ld_out, long s_out, int R, int C) {
-  __shared__ float tile[32][33];
+  __shared__ float tile[64][65];
   const int g = blockIdx.z;
-  const int c0 = blockIdx.x * 32, r0 = blockIdx.y * 32;
-  const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+  const int c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;  // 64 x 4
+  const float* src = in + g * s_in;
+  __bf16* dst = out + g * s_out;
   if (!TRANSPOSE) {
-    for (int i = ty; i < 32; i += 8) {
+    for (int i = ty; i < 64; i += 4) {
       const int r = r0 + i, c = c0 + tx;
-      if (r < R && c < C) out[g * s_out + (long)r * ld_out + c] = (__bf16)in[g * s_in + (long)r * ld_in + c];
+      if (r < R && c < C) dst[(long)r * ld_out + c] = (__bf16)src[(long)r * ld_in + c];
     }
     return;
   }
-  for (int i = ty; i < 32; i += 8) {
+  for (int i = ty; i < 64; i += 4) {
     const int r = r0 + i, c = c0 + tx;
-    tile[i][tx] = (r < R && c < C) ? in[g * s_in + (long)r * ld_in + c] : 0.f;
+    tile[i][tx] = (r < R && c < C) ? src[(long)r * ld_in + c] : 0.f;
   }
   __syncthreads();
-  for (int i = ty; i < 32; i += 8) {
-    const int c = c0 + i, r = r0 + tx;
-    if (r < R && c < C) out[g * s_out + (long)c * ld_out + r] = (__bf16)tile[tx][i];
+  // output row = input column c0 + i; a lane writes input rows r0 + 2*px, +1 as one 4-byte pair
+  const int px = threadIdx.x & 31, py = threadIdx.x >> 5;  // 32 pairs x 8
+  const bool pair_ok = (ld_out & 1) == 0 && (s_out & 1) == 0 && ((uintptr_t)out & 3) == 0;
+  for (int i = py; i < 64; i += 8) {
+    const int c = c0 + i, r = r0 + 2 * px;
+    if (c >= C || r >= R) continue;
+    __bf16* o = dst + (long)c * ld_out + r;
+    if (pair_ok && r + 1 < R) {
+      typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+      bf16x2 v;
+      v[0] = (__bf16)tile[2 * px][i];
+      v[1] = (__bf16)tile[2 * px + 1][i];
+      *reinterpret_cast<bf16x2*>(o) = v;
+    } else {
+      o[0] = (__bf16)tile[2 * px][i];
+      if (r + 1 < R) o[1] = (__bf16)tile[2 * px + 1][i];
+    }
   }
 }
 
 hipError_t launch_cvt_bf16(const float* in, long ld_in, long s_in, void* out, long ld_out, long s_out,
                            int R, int C, bool transpose, int groups, hipStream_t s) {
-  dim3 grid((C + 31) / 32, (R + 31) / 32, groups);
+  dim3 grid((C + 63) / 64, (R + 63) / 64, groups);
   if (transpose)
     hipLaunchKernelGGL(cvt_bf16_kernel<true>, grid, dim3(256), 0, s, in, ld_in, s_in, (__bf16*)out, ld_out,
                        s_out, R, C);

@@ -239,34 +239,63 @@ hipError_t launch_embed_fwd(const float* E, long s_E, const int32_t* tok, long s
   return hipGetLastError();
 }
 
-// Position i acts only if it is the first occurrence of its token; it then sums, in
-// increasing position, the rows of every position that holds the same token.  No atomics,
-// so duplicate ids (frequent under a Zipf draw) cost a serial loop, not contention.
-__global__ void __launch_bounds__(64)
+// One workgroup per position i.  It acts only if i is the first occurrence of its token v;
+// it then adds, in increasing position, the rows of every position that holds v (thread c
+// owns column c).  No atomics: duplicate ids, frequent under a Zipf draw, cost the owner a
+// short serial loop instead of contention, and the order of the sum is fixed.
+__global__ void __launch_bounds__(kThreads)
 embed_bwd_kernel(const float* __restrict__ dx, long s_dx, const int32_t* __restrict__ tok,
                  long s_tok, float* __restrict__ dE, long s_dE, int N, int Ew) {
-  const int g = blockIdx.y, i = blockIdx.x;
+  __shared__ int list[kThreads];  // positions of this chunk that hold v, ascending
+  __shared__ int wcnt[kThreads / 64];
+  const int g = blockIdx.y, i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int32_t* tk = tok + g * s_tok;
   const int v = tk[i];
-  // first occurrence?  (wave-parallel scan of the earlier positions)
   int seen = 0;
-  for (int j = threadIdx.x; j < i; j += 64) seen |= (tk[j] == v);
-  if (__any(seen)) return;
+  for (int j = tid; j < i; j += kThreads) seen |= (tk[j] == v);
+  if (__syncthreads_or(seen)) return;
   const float* src = dx + g * s_dx;
   float* dst = dE + g * s_dE + (long)v * Ew;
-  for (int c0 = 0; c0 < Ew; c0 += 64) {
-    const int c = c0 + threadIdx.x;
+  for (int c0 = 0; c0 < Ew; c0 += kThreads) {
+    const int c = c0 + tid;
+    const bool cok = c < Ew;
     float acc = 0.f;
-    for (int j = i; j < N; ++j) {
-      if (tk[j] == v && c < Ew) acc += src[(long)j * Ew + c];
+    for (int j0 = i; j0 < N; j0 += kThreads) {
+      // compact the matching positions of this chunk (order preserved)
+      const int j = j0 + tid;
+      const bool m = j < N && tk[j] == v;
+      const unsigned long long mask = __ballot(m);
+      if (lane == 0) wcnt[wave] = __popcll(mask);
+      __syncthreads();
+      int base = 0, n = 0;
+#pragma unroll
+      for (int w = 0; w < kThreads / 64; ++w) {
+        if (w < wave) base += wcnt[w];
+        n += wcnt[w];
+      }
+      if (m) list[base + __popcll(mask & ((1ull << lane) - 1ull))] = j;
+      __syncthreads();
+      // rows are fetched eight at a time (independent loads) and added in position order
+      if (cok) {
+        int k = 0;
+        for (; k + 8 <= n; k += 8) {
+          float r[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) r[u] = src[(long)list[k + u] * Ew + c];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) acc += r[u];
+        }
+        for (; k < n; ++k) acc += src[(long)list[k] * Ew + c];
+      }
+      __syncthreads();
     }
-    if (c < Ew) dst[c] = acc;
+    if (cok) dst[c] = acc;
   }
 }
 
 hipError_t launch_embed_bwd(const float* dx, long s_dx, const int32_t* tok, long s_tok, float* dE,
                             long s_dE, int N, int Ew, int groups, hipStream_t s) {
-  hipLaunchKernelGGL(embed_bwd_kernel, dim3(N, groups), dim3(64), 0, s, dx, s_dx, tok, s_tok, dE,
+  hipLaunchKernelGGL(embed_bwd_kernel, dim3(N, groups), dim3(kThreads), 0, s, dx, s_dx, tok, s_tok, dE,
                      s_dE, N, Ew);
   return hipGetLastError();
 }

@@ -211,6 +211,19 @@ gather_all_kernel(GatherPack pk, int n_idx, size_t row_w, size_t chunk_w) {
   for (size_t w = threadIdx.x; w < chunk_w; w += kThreads) dst[w] = src[w];
 }
 
+// Chunks of a few words (token ids, labels): one thread per output word instead of one
+// workgroup per chunk.  Output word o = (c*n_idx + b)*chunk_w + w.
+__global__ void __launch_bounds__(kThreads)
+gather_all_small_kernel(GatherPack pk, int n_idx, size_t row_w, int n_chunks, size_t chunk_w) {
+  const int k = blockIdx.y;
+  const size_t total = (size_t)n_chunks * n_idx * chunk_w;
+  const size_t o = (size_t)blockIdx.x * kThreads + threadIdx.x;
+  if (o >= total) return;
+  const size_t w = o % chunk_w, cb = o / chunk_w;
+  const size_t b = cb % n_idx, c = cb / n_idx;
+  pk.out[k][o] = pk.shard[k][(size_t)pk.idx[k][b] * row_w + c * chunk_w + w];
+}
+
 hipError_t launch_gather_all(const void* const* shards, const int32_t* const* idx, int K, int n_idx,
                              size_t row_bytes, int n_chunks, size_t chunk_bytes, void* const* outs,
                              hipStream_t s) {
@@ -221,8 +234,14 @@ hipError_t launch_gather_all(const void* const* shards, const int32_t* const* id
     pk.idx[k] = idx[k];
     pk.out[k] = (uint32_t*)outs[k];
   }
-  hipLaunchKernelGGL(gather_all_kernel, dim3(n_idx, n_chunks, K), dim3(kThreads), 0, s, pk, n_idx,
-                     row_bytes / 4, chunk_bytes / 4);
+  if (chunk_bytes / 4 < 32) {
+    const size_t total = (size_t)n_chunks * n_idx * (chunk_bytes / 4);
+    hipLaunchKernelGGL(gather_all_small_kernel, dim3((unsigned)((total + kThreads - 1) / kThreads), K),
+                       dim3(kThreads), 0, s, pk, n_idx, row_bytes / 4, n_chunks, chunk_bytes / 4);
+  } else {
+    hipLaunchKernelGGL(gather_all_kernel, dim3(n_idx, n_chunks, K), dim3(kThreads), 0, s, pk, n_idx,
+                       row_bytes / 4, chunk_bytes / 4);
+  }
   return hipGetLastError();
 }
 
