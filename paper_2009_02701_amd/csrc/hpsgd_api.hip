@@ -43,7 +43,8 @@ struct hpsgd_ctx {
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
   unsigned timer_mask = 0;
-  struct Stamp { int role; hipEvent_t a, b; };
+  bool timer_nested = false;    // an enclosing scope already brackets the current launches
+  struct Stamp { int role; int launches; hipEvent_t a, b; };
   std::vector<Stamp> stamps;
   std::vector<hipEvent_t> free_events;
   double role_ms[HPSGD_ROLE_COUNT] = {0};
@@ -170,17 +171,20 @@ struct TimerScope {
     }
     return e;
   }
-  TimerScope(hpsgd_ctx* c_, int role, hipStream_t s_) : c(c_), s(s_) {
-    if (!(c->timer_mask & (1u << role))) return;
+  // launches: how many kernel launches the pair brackets (a whole time loop is bracketed by
+  // one pair: an event record between two dependent launches costs far more than the launch)
+  TimerScope(hpsgd_ctx* c_, int role, hipStream_t s_, int launches = 1) : c(c_), s(s_) {
+    if (launches <= 0 || !(c->timer_mask & (1u << role)) || c->timer_nested) return;
     hipEvent_t a = get(c), b = get(c);
     if (!a || !b) return;
-    c->stamps.push_back({role, a, b});
+    c->stamps.push_back({role, launches, a, b});
     idx = (int)c->stamps.size() - 1;
     (void)hipEventRecord(a, s);
   }
   ~TimerScope() {
     if (idx >= 0) (void)hipEventRecord(c->stamps[idx].b, s);
   }
+  bool active() const { return idx >= 0; }
 };
 
 // inside run_step: `role` names what the next launches are for
@@ -250,6 +254,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const long sR = (long)rstride;
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
+  c->timer_nested = false;
 
   if (d.kind == HPSGD_MLP) {
     const int L = d.n_mlp_dims - 1;
@@ -352,6 +357,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
         HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
       }
+      // one event pair around the whole time loop when its launches are all of one role
+      TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (fused || fused_b) ? T : 0);
+      c->timer_nested = loop_fwd.active() && (fused || fused_b);
       for (int t = 0; t < T; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         if (fused_b) {
@@ -374,6 +382,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                     hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
                                     s_sv, B, H, groups, s));
       }
+      c->timer_nested = false;
       lin = hs + (size_t)B * H;
       s_lin = s_hs;
       width = H;
@@ -471,6 +480,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
       }
+      {
+      TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (fused || fused_b) ? T : 0);
+      c->timer_nested = loop_bwd.active() && (fused || fused_b);
       for (int t = T - 1; t >= 0; --t) {
         const float* above_t = above ? above + (size_t)t * B * H : nullptr;
         if (fused_b) {
@@ -498,6 +510,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (t > 0)
           TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0, Whh, H, sR, 0, D,
                    H, s_D, EPI_ACCUM, nullptr, 0));
+      }
+      c->timer_nested = false;
       }
       const float* Wih = rin + c->off(p + ".W_ih");
       const bool need_dx = l > 0 || lm;
@@ -725,7 +739,7 @@ int hpsgd_timer_read(hpsgd_ctx* ctx, int role, long* launches, double* total_ms)
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, st.a, st.b) != hipSuccess) return HPSGD_EHIP;
     ctx->role_ms[st.role] += ms;
-    ctx->role_launches[st.role] += 1;
+    ctx->role_launches[st.role] += st.launches;
     ctx->free_events.push_back(st.a);
     ctx->free_events.push_back(st.b);
   }
