@@ -12,10 +12,9 @@
 // 16-wide chunks (chunk c belongs to wave c % 4); partial sums are combined through LDS.
 // MFMA 16x16x4 lane layout: A lane l holds A[m = l%16][k = l/16], B lane l holds
 // B[k = l/16][n = l%16], accumulator register v holds C[4*(l/16) + v][l%16].  Because the
-// order of the contraction index is free as long as both operands agree, a lane loads one
+// order of the contraction index is free as long as both operands agree, a lane fetches one
 // float4 (4 consecutive k of its row) per operand and feeds component s to MFMA number s:
-// lane group g then covers k = 16c + 4g + s.  Operands therefore go straight from L2 to
-// registers with 16-byte loads; LDS is used only for the cross-wave reduction.
+// lane group g then covers k = 16c + 4g + s, so operand fragments are 16-byte reads.
 #include "kernels.h"
 
 namespace hpsgd {
@@ -64,48 +63,104 @@ __device__ __forceinline__ void step_tile(int NJ, int RT, int groups, int& g, in
   }
 }
 
-// ---------------------------------------------------------------------------- forward
-// NCH: upper bound of contraction chunks per wave (H <= 64*NCH).
-template <int NCH>
+// ---------------------------------------------------------------------------- fp32 step kernels
+// Operands take the path global -> registers -> LDS -> MFMA layout: the workgroup fetches
+// 128-wide slabs of its weight rows and activation rows with fully contiguous loads (one wave
+// instruction = two whole 512-byte row segments).  Loading straight into the MFMA layout
+// would need 16 row pieces of 64 bytes per instruction, which a fresh launch with a cold L2
+// serves about 1.7x slower.
+static constexpr int SK = 128;      // slab width along the contraction
+static constexpr int SP = SK + 4;   // LDS row pitch in floats: 16 rows x 16-byte reads hit 64 banks
+
+// acc[rb][q] += sum_k A[rb*16 + ..][k] * W_q[..][k].  Wbase points at the workgroup's first
+// weight row, gate block q starts w_qstride floats further, rows are KD floats apart;
+// Abase at its first activation row (rows >= rows_valid read as zero).  lds: 2*RT*SP floats.
+// The global loads of NB slabs at a time are all issued before the first of them is used
+// (one exposed memory latency per batch; config-2 sizes are a single batch), then the
+// slabs go through the two LDS buffers one barrier apart.
+template <int NQ, int NB>
+__device__ __forceinline__ void staged_contraction(const float* __restrict__ Wbase, long w_qstride,
+                                                   const float* __restrict__ Abase, int KD,
+                                                   int rows_valid, float* __restrict__ lds,
+                                                   floatx4 (&acc)[2][NQ]) {
+  constexpr int RT = 16 * NQ + 32;  // rows of one slab tile: weight rows, then 32 activation rows
+  constexpr int UPT = RT / 8;       // float4 units per thread per slab (RT*32 units / 256 threads)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int nslab = (KD + SK - 1) / SK;
+  // per-thread row pointers and validity of its UPT units (the same for every slab)
+  const float* rowp[UPT];
+  bool rowok[UPT];
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int row = (tid + i * 256) >> 5;
+    if (row < 16 * NQ) {
+      rowp[i] = Wbase + (row >> 4) * w_qstride + (long)(row & 15) * KD;
+      rowok[i] = true;
+    } else {
+      const int ar = row - 16 * NQ;
+      rowok[i] = ar < rows_valid;
+      rowp[i] = Abase + (long)(rowok[i] ? ar : 0) * KD;
+    }
+  }
+  const int colofs = (tid & 31) << 2;
+  for (int s0 = 0; s0 < nslab; s0 += NB) {
+    float4 regs[NB][UPT];
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb) {
+      const int col = (s0 + sb) * SK + colofs;
+      const bool cok = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
+#pragma unroll
+      for (int i = 0; i < UPT; ++i) regs[sb][i] = ld4_or_zero(rowp[i] + col, cok && rowok[i]);
+    }
+    auto sstore = [&](int sb) {
+#pragma unroll
+      for (int i = 0; i < UPT; ++i) {
+        const int u = tid + i * 256;
+        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + (u >> 5)) * SP + ((u & 31) << 2)]) = regs[sb][i];
+      }
+    };
+    sstore(0);
+    __syncthreads();
+#pragma unroll
+    for (int sb = 0; sb < NB; ++sb) {
+      if (sb + 1 < NB) sstore(sb + 1);  // slabs past the end were loaded as zeros
+      const int b = sb & 1;
+#pragma unroll
+      for (int ci = 0; ci < 2; ++ci) {
+        const int kcol = 16 * (wave + 4 * ci) + 4 * lg;  // chunk (wave + 4*ci) of this slab
+        float4 a[2], w[NQ];
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+          w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * SP + kcol]);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+          a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * SP + kcol]);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) acc[rb][q] = mfma4(a[rb], w[q], acc[rb][q]);
+      }
+      __syncthreads();
+    }
+  }
+}
+
+// Forward step: h_out = cell(gx_t, h_prev W_hh^T + b_hh, h_prev); saves r|z|n|q of the step.
 __global__ void __launch_bounds__(256)
 gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
-                    const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
-                    float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
-                    int B, int H, int groups) {
-  __shared__ float red[4][6][4][64];
+                           const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
+                           float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
+                           int B, int H, int groups) {
+  extern __shared__ __attribute__((aligned(16))) float staged_lds[];
+  float* red = staged_lds + 2 * 80 * SP;  // [4][6][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ;
-  const int r0 = ty * FR;
-  const float* W = W_hh + g * s_rep;
+  const int j0 = tx * FJ, r0 = ty * FR;
   const float* hp = h_prev + g * s_hs;
-  const int nchunks = H / 16;
-
-  floatx4 acc[2][3];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-
-  // All loads are issued before the first MFMA, chunk by chunk (weights of the 3 gates, then
-  // the two row blocks of h), so the MFMAs of chunk i only wait for the loads up to chunk i;
-  // the epilogue's own inputs (gx_t, h_prev, bias) follow and arrive during the matrix work.
-  float4 w[NCH][3], a[NCH][2];
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int c = wave + 4 * i;
-    const bool ok = c < nchunks;
-#pragma unroll
-    for (int q = 0; q < 3; ++q)
-      w[i][q] = ld4_or_zero(W + (long)(q * H + j0 + lr) * H + 16 * c + 4 * lg, ok);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const int row = r0 + rb * 16 + lr;
-      a[i][rb] = ld4_or_zero(hp + (long)row * H + 16 * c + 4 * lg, ok && row < B);
-    }
-  }
+  // the epilogue's own inputs first: they arrive during the matrix work
   const float* bh = b_hh + g * s_rep;
   const int j = j0 + lr;
   float gxv[2][3], hpv[2], bias[3];
@@ -120,28 +175,29 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
     for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
     hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
   }
+  floatx4 acc[2][3];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i)
+  for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int q = 0; q < 3; ++q) acc[rb][q] = mfma4(a[i][rb], w[i][q], acc[rb][q]);
-  // cross-wave reduction: wave w finishes accumulator register v = w of every block
+    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  staged_contraction<3, 4>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
+                           staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][rb * 3 + q][v][lane] = acc[rb][q][v];
+      for (int v = 0; v < 4; ++v) red[((wave * 6 + rb * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
   __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
     float gh[3];
 #pragma unroll
-    for (int q = 0; q < 3; ++q)
-      gh[q] = ((red[0][rb * 3 + q][wave][lane] + red[1][rb * 3 + q][wave][lane]) +
-               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bias[q];
+    for (int q = 0; q < 3; ++q) {
+      const int o = ((rb * 3 + q) * 4 + wave) * 64 + lane;
+      gh[q] = ((red[o] + red[o + 6 * 256]) + (red[o + 12 * 256] + red[o + 18 * 256])) + bias[q];
+    }
     if (row < B) {
       const float r = sigm(gxv[rb][0] + gh[0]);
       const float z = sigm(gxv[rb][1] + gh[1]);
@@ -157,49 +213,43 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   }
 }
 
+static constexpr size_t kFwdStagedLds = (2 * 80 * SP + 4 * 6 * 4 * 64) * sizeof(float);
+static constexpr size_t kBwdStagedLds = (2 * 48 * SP + 4 * 2 * 4 * 64) * sizeof(float);
+
 hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
-                               long s_gx, const float* h_prev, float* h_out, long s_hs, float* sv_t,
-                               long s_sv, int B, int H, int groups, hipStream_t s) {
+                                      long s_gx, const float* h_prev, float* h_out, long s_hs,
+                                      float* sv_t, long s_sv, int B, int H, int groups, hipStream_t s) {
+  static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdStagedLds);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-#define HPSGD_FWD(N)                                                                              \
-  hipLaunchKernelGGL(gru_fwd_step_kernel<N>, grid, dim3(256), 0, s, W_hh, b_hh, s_rep, gx_t, s_gx, \
-                     h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups)
-  const int per_wave = (H / 16 + 3) / 4;
-  if (per_wave <= 2) HPSGD_FWD(2);
-  else if (per_wave <= 4) HPSGD_FWD(4);
-  else if (per_wave <= 8) HPSGD_FWD(8);
-  else HPSGD_FWD(16);
-#undef HPSGD_FWD
+  hipLaunchKernelGGL(gru_fwd_step_kernel, grid, dim3(256), kFwdStagedLds, s, W_hh, b_hh, s_rep,
+                     gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
 }
 
-// ---------------------------------------------------------------------------- backward
-// WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along the contraction).
-// D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last step) and dh_t * z_t
-// on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
-template <int NCH>
+// Backward step.  WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along
+// the contraction).  D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last
+// step) and dh_t * z_t on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
 __global__ void __launch_bounds__(256)
 gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __restrict__ dgh_next,
-                    long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
-                    long s_above, const float* __restrict__ sv_t, long s_sv,
-                    const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
-                    float* __restrict__ dgh_t, int B, int H, int groups) {
-  __shared__ float red[4][2][4][64];
+                           long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
+                           long s_above, const float* __restrict__ sv_t, long s_sv,
+                           const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
+                           float* __restrict__ dgh_t, int B, int H, int groups) {
+  extern __shared__ __attribute__((aligned(16))) float staged_lds[];
+  float* red = staged_lds + 2 * 48 * SP;  // [4][2][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ;
-  const int r0 = ty * FR;
+  const int j0 = tx * FJ, r0 = ty * FR;
   const int H3 = 3 * H;
-  const int nchunks = H3 / 16;
-
-  floatx4 acc[2];
-  acc[0] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  acc[1] = acc[0];
   const int j = j0 + lr;
-  // the epilogue's inputs do not depend on the matrix work: they are requested first and
-  // arrive while it runs
   float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
@@ -215,37 +265,22 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
     dh_[rb] = ok ? D[g * s_D + e] : 0.f;
     if (ok && above) dh_[rb] += above[g * s_above + e];
   }
-  if (dgh_next) {
-    const float* Wt = WT + g * s_wt + (long)(j0 + lr) * H3;
-    const float* dg = dgh_next + g * s_dg;
-    float4 w[NCH], a[NCH][2];
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = wave + 4 * i;
-      const bool ok = c < nchunks;
-      w[i] = ld4_or_zero(Wt + 16 * c + 4 * lg, ok);
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const int row = r0 + rb * 16 + lr;
-        a[i][rb] = ld4_or_zero(dg + (long)row * H3 + 16 * c + 4 * lg, ok && row < B);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      acc[0] = mfma4(a[i][0], w[i], acc[0]);
-      acc[1] = mfma4(a[i][1], w[i], acc[1]);
-    }
-  }
+  floatx4 acc[2][1];
+  acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  acc[1][0] = acc[0][0];
+  if (dgh_next)
+    staged_contraction<1, 12>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
+                              B - r0, staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][rb][v][lane] = acc[rb][v];
+    for (int v = 0; v < 4; ++v) red[((wave * 2 + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
   __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
-    const float rec = (red[0][rb][wave][lane] + red[1][rb][wave][lane]) +
-                      (red[2][rb][wave][lane] + red[3][rb][wave][lane]);
+    const int o = (rb * 4 + wave) * 64 + lane;
+    const float rec = (red[o] + red[o + 2 * 256]) + (red[o + 4 * 256] + red[o + 6 * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
       const float dh = dh_[rb] + rec;
@@ -269,20 +304,13 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   }
 }
 
-hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next, long s_dg, float* D,
-                               long s_D, const float* above, long s_above, const float* sv_t,
-                               long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
-                               int B, int H, int groups, hipStream_t s) {
+hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next, long s_dg,
+                                      float* D, long s_D, const float* above, long s_above,
+                                      const float* sv_t, long s_sv, const float* h_prev, long s_hs,
+                                      float* dgx_t, float* dgh_t, int B, int H, int groups, hipStream_t s) {
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-#define HPSGD_BWD(N)                                                                             \
-  hipLaunchKernelGGL(gru_bwd_step_kernel<N>, grid, dim3(256), 0, s, WT, s_wt, dgh_next, s_dg, D, \
-                     s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups)
-  const int per_wave = (3 * H / 16 + 3) / 4;
-  if (per_wave <= 6) HPSGD_BWD(6);
-  else if (per_wave <= 12) HPSGD_BWD(12);
-  else if (per_wave <= 24) HPSGD_BWD(24);
-  else HPSGD_BWD(48);
-#undef HPSGD_BWD
+  hipLaunchKernelGGL(gru_bwd_step_kernel, grid, dim3(256), kBwdStagedLds, s, WT, s_wt, dgh_next,
+                     s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups);
   return hipGetLastError();
 }
 
