@@ -116,6 +116,18 @@ int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float 
                      const void *x, const int32_t *y, float lr, float *loss_out,
                      void *workspace, void *hip_stream);
 
+/* Optional second stream (hipStream_t as void*, NULL = none, the default).  When set,
+ * hpsgd_local_step(_all) runs the weight-gradient GEMMs of time steps that backpropagation
+ * through time has already passed on this stream, beside the rest of the recurrence -- the
+ * same idea as the paper's hierarchy (Sec. 3.1: work that does not depend on the training
+ * loop runs beside it), applied inside one local step.  The library orders the two streams
+ * with two HIP events owned by the context and joins before the local step's remaining work,
+ * so the caller still sees everything complete in order on the stream it passed.  The stream
+ * must belong to the same device and must not be the stream passed to the local step.
+ * Results are deterministic but differ in the last bits from the single-stream order (the
+ * gradients are summed chunk by chunk). */
+int hpsgd_set_aux_stream(hpsgd_ctx *ctx, void *hip_stream);
+
 /* ---- batch gather (Sec. 3.2: every worker samples its own sub-dataset) ----------------
  * Time-major gather of n_idx samples: for b < n_idx, c < n_chunks
  *     out[(c*n_idx + b)*chunk_bytes ...] = shard[idx[b]*row_bytes + c*chunk_bytes ...]

@@ -23,7 +23,7 @@ EXPORTS = [
     "hpsgd_create", "hpsgd_destroy", "hpsgd_param_count", "hpsgd_param_entries",
     "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
     "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
-    "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
+    "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
 ]
 ROLE_COUNT = 14
 
@@ -70,6 +70,7 @@ def load_library():
     lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
+    lib.hpsgd_set_aux_stream.argtypes = [vp, vp]
     lib.hpsgd_timer_enable.argtypes = [vp, C.c_uint]
     lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.hpsgd_role_name.argtypes = [C.c_int]
@@ -156,6 +157,12 @@ class Context:
     def _ws_ptr(ws):
         p = ws.data_ptr()
         return C.c_void_p((p + 255) // 256 * 256)
+
+    def set_aux_stream(self, stream):
+        """Second stream for the weight-gradient GEMMs that can run beside the recurrence (None = off)."""
+        self._aux = stream  # keep the torch stream alive
+        _check(self.lib.hpsgd_set_aux_stream(self._h, C.c_void_p(stream.cuda_stream if stream is not None else None)),
+               "hpsgd_set_aux_stream")
 
     # ---- kernel timing (benchmarks) ----
     def timer_enable(self, roles):

@@ -155,6 +155,9 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
   float* red = staged_lds + 2 * 80 * SP;  // [4][6][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the recurrence is the critical path: its waves issue ahead of any throughput kernel
+  // (weight-gradient GEMMs, merge) that shares the SIMD
+  __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
@@ -244,6 +247,9 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
   float* red = staged_lds + 2 * 48 * SP;  // [4][2][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the recurrence is the critical path: its waves issue ahead of any throughput kernel
+  // (weight-gradient GEMMs, merge) that shares the SIMD
+  __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
@@ -337,6 +343,9 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
                          float* __restrict__ sv_t, long s_sv, int B, int H, int groups) {
   __shared__ float red[4][6][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the recurrence is the critical path: its waves issue ahead of any throughput kernel
+  // (weight-gradient GEMMs, merge) that shares the SIMD
+  __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
@@ -448,6 +457,9 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          float* __restrict__ dgh_t, long s_dg, int B, int H, int groups) {
   __shared__ float red[4][2][4][64];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  // the recurrence is the critical path: its waves issue ahead of any throughput kernel
+  // (weight-gradient GEMMs, merge) that shares the SIMD
+  __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);

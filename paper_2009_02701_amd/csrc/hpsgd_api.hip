@@ -42,6 +42,10 @@ struct hpsgd_ctx {
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
+  // optional second stream for work that can run beside the recurrence, and the two events
+  // that order it against the caller's stream
+  hipStream_t aux = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   unsigned timer_mask = 0;
   bool timer_nested = false;    // an enclosing scope already brackets the current launches
   struct Stamp { int role; int launches; hipEvent_t a, b; };
@@ -480,10 +484,36 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
       }
+      // fp32 path with an auxiliary stream: the weight-gradient GEMMs of the time steps that
+      // BPTT has already finished run on that stream beside the rest of the recurrence (the
+      // recurrence is latency-bound and leaves the matrix cores mostly idle).  The steps are
+      // cut into chunks; chunk c's GEMMs are issued when BPTT has walked past it, the last
+      // one follows on the main stream after the join.  Fixed chunking: deterministic.
+      const int NC = (c->aux && fused && T >= 8) ? 4 : 1;
+      auto chunk_lo = [&](int ch) { return (int)((long)T * ch / NC); };
+      auto wgrad_rows = [&](hipStream_t st, int t0, int t1, int epi) -> int {
+        const size_t r0 = (size_t)t0 * B;
+        const int rows = (t1 - t0) * B;
+        int rc = gemm(st, groups, bf, 3 * H, win, rows, dgx + r0 * 3 * H, 3 * H, s_gx, 1, layer_in + r0 * win,
+                      win, s_layer_in, 0, grad + c->off(p + ".W_ih"), win, sG, epi, nullptr, 0);
+        if (rc != HPSGD_OK) return rc;
+        return gemm(st, groups, bf, 3 * H, H, rows, dgh + r0 * 3 * H, 3 * H, s_gx, 1, hs + r0 * H, H, s_hs, 0,
+                    grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0);
+      };
       {
       TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (fused || fused_b) ? T : 0);
       c->timer_nested = loop_bwd.active() && (fused || fused_b);
+      int next_chunk = NC - 1;  // the chunk BPTT is walking through
       for (int t = T - 1; t >= 0; --t) {
+        if (NC > 1 && next_chunk >= 1 && t < chunk_lo(next_chunk)) {
+          // steps [chunk_lo, chunk_hi) are done: hand their weight gradients to the aux stream
+          if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
+            return HPSGD_EHIP;
+          const int rc = wgrad_rows(c->aux, chunk_lo(next_chunk), chunk_lo(next_chunk + 1),
+                                    next_chunk == NC - 1 ? EPI_STORE : EPI_ACCUM);
+          if (rc != HPSGD_OK) return rc;
+          --next_chunk;
+        }
         const float* above_t = above ? above + (size_t)t * B * H : nullptr;
         if (fused_b) {
           role = HPSGD_ROLE_GEMM_REC_BWD;
@@ -539,10 +569,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         }
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
-      TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
-                grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0, v_dgxT, v_xT));
-      TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, grad + c->off(p + ".W_hh"), H,
-                sG, EPI_STORE, nullptr, 0, v_dghT, v_hsT));
+      if (NC > 1) {
+        // join, then the first chunk's share on top of what the aux stream accumulated
+        if (hipEventRecord(c->ev_join, c->aux) != hipSuccess || hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess)
+          return HPSGD_EHIP;
+        TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
+      } else {
+        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
+                  grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0, v_dgxT, v_xT));
+        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, grad + c->off(p + ".W_hh"),
+                  H, sG, EPI_STORE, nullptr, 0, v_dghT, v_hsT));
+      }
       HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
       HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
       role = HPSGD_ROLE_GEMM_DX;
@@ -612,6 +649,8 @@ int hpsgd_destroy(hpsgd_ctx* ctx) {
       (void)hipEventDestroy(st.b);
     }
     for (auto e : ctx->free_events) (void)hipEventDestroy(e);
+    if (ctx->ev_fork) (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join) (void)hipEventDestroy(ctx->ev_join);
   }
   delete ctx;
   return HPSGD_OK;
@@ -723,6 +762,17 @@ int hpsgd_sync_replica(const float* global, float* replica, size_t P, void* hip_
   float* one[1] = {replica};
   if (!replica) return P == 0 ? HPSGD_OK : HPSGD_EINVAL;
   return hpsgd_sync_all(global, one, 1, nullptr, P, hip_stream);
+}
+
+int hpsgd_set_aux_stream(hpsgd_ctx* ctx, void* hip_stream) {
+  if (!ctx) return HPSGD_EINVAL;
+  if (hip_stream && !ctx->ev_fork) {
+    if (hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) != hipSuccess)
+      return HPSGD_EHIP;
+  }
+  ctx->aux = (hipStream_t)hip_stream;
+  return HPSGD_OK;
 }
 
 int hpsgd_timer_enable(hpsgd_ctx* ctx, unsigned role_mask) {

@@ -22,7 +22,8 @@ from . import binding as hb
 
 
 class Trainer:
-    def __init__(self, cfg: dict, init_params: dict, shards: list, orders: list, device="cuda"):
+    def __init__(self, cfg: dict, init_params: dict, shards: list, orders: list, device="cuda",
+                 aux_stream=True):
         self.cfg = cfg
         self.ctx = hb.Context(cfg)
         self.K, self.P, self.stride = self.ctx.K, self.ctx.P, self.ctx.stride
@@ -58,6 +59,9 @@ class Trainer:
             self.yb = torch.zeros(K, T, B, dtype=torch.int32, device=dev)
         self.stream_a = torch.cuda.Stream(device=dev)
         self.stream_b = torch.cuda.Stream(device=dev)
+        # third stream: weight-gradient GEMMs beside the BPTT recurrence, inside a local step
+        self.stream_aux = torch.cuda.Stream(device=dev) if aux_stream else None
+        self.ctx.set_aux_stream(self.stream_aux)
         torch.cuda.synchronize(dev)
 
     # ------------------------------------------------------------------ pieces

@@ -94,6 +94,31 @@ def test_merge_and_sync_reject_bad_arguments_before_launch():
     assert lib.hpsgd_gather_batch(vp(A), vp(B), -1, 8, 1, 4, vp(S), None) == 1
 
 
+def test_gather_all_and_aux_stream_reject_bad_arguments():
+    lib = hb.load_library()
+    vp = C.c_void_p
+    sh = (vp * 2)(0x10000, 0x20000)
+    ix = (vp * 2)(0x30000, 0x40000)
+    out = (vp * 2)(0x50000, 0x60000)
+    call = lib.hpsgd_gather_batch_all
+    assert call(sh, ix, 40, 4, 8, 1, 8, out, None) == 1                  # K > max
+    assert call(sh, ix, 2, -1, 8, 1, 8, out, None) == 1
+    assert call(None, ix, 2, 4, 8, 1, 8, out, None) == 1
+    assert call(sh, ix, 2, 4, 6, 1, 4, out, None) == 3                   # row bytes not a multiple of 4
+    assert call(sh, ix, 2, 4, 8, 3, 4, out, None) == 2                   # chunks exceed the row
+    bad = (vp * 2)(0x10000, 0)
+    assert call(bad, ix, 2, 4, 8, 1, 8, out, None) == 1                  # null shard pointer
+    bad = (vp * 2)(0x10000, 0x20002)
+    assert call(bad, ix, 2, 4, 8, 1, 8, out, None) == 3                  # misaligned shard pointer
+    assert call(sh, ix, 0, 4, 8, 1, 8, out, None) == 0                   # no workers: no-op
+    assert lib.hpsgd_set_aux_stream(None, None) == 1
+    ctx = hb.Context(wl.CONFIGS["tiny_gru"])
+    assert lib.hpsgd_set_aux_stream(ctx._h, None) == 0                   # switching it off needs no GPU
+    assert lib.hpsgd_timer_enable(None, 0) == 1
+    assert lib.hpsgd_timer_read(ctx._h, 99, None, None) == 1
+    assert lib.hpsgd_role_name(99) is None and lib.hpsgd_role_name(3) == b"gemm_recurrent_bwd"
+
+
 def test_local_step_rejects_bad_arguments_before_launch():
     lib = hb.load_library()
     ctx = hb.Context(wl.CONFIGS["tiny_gru"])

@@ -165,6 +165,30 @@ def test_config3_gru_language_model_bf16(sched):
     _schedule_parity(wl.CONFIGS["gru_lm"], sched[0], TOL_BF16, **sched[1])
 
 
+def test_aux_stream_overlap_matches_single_stream_order():
+    """Weight-gradient GEMMs issued chunk by chunk on the auxiliary stream (beside BPTT) give
+    the oracle's gradients too, and the same result as the single-stream order up to fp32
+    summation order."""
+    cfg = wl.scaled(wl.CONFIGS["gru_cls"], input=32, hidden=96, seq_len=11, batch=16, K=3)
+    init, shards, orders, batch_fn = workload(cfg)
+    outs = []
+    for aux in (True, False):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, aux_stream=aux)
+        tr.sync_all(0)
+        tr.gather(0)
+        tr.local_step(0, 8.0)
+        torch.cuda.synchronize()
+        outs.append([tr.replica_params(0, k) for k in range(cfg["K"])])
+    for k in range(cfg["K"]):
+        _, g = oc.loss_and_grads(init, *batch_fn(k, 0))
+        for reps in outs:
+            got = {n: (init[n].astype(np.float64) - reps[k][n].astype(np.float64)) / 8.0 for n in init}
+            err, worst, errs = worst_rel_err(got, g)
+            assert err <= TOL_FP32, (k, worst, errs)
+        for n in init:
+            assert rel_err(outs[0][k][n], outs[1][k][n]) <= 1e-5, n
+
+
 def test_overlapped_two_streams_equals_one_stream_bitwise():
     """The two-stream schedule must give the bits of the same op list run on one stream,
     and the same bits run to run."""
