@@ -78,7 +78,10 @@ static constexpr int SP = SK + 4;   // LDS row pitch in floats: 16 rows x 16-byt
 // The global loads of NB slabs at a time are all issued before the first of them is used
 // (one exposed memory latency per batch; config-2 sizes are a single batch), then the
 // slabs go through the two LDS buffers one barrier apart.
-template <int NQ, int NB>
+// BF16: the rows hold bf16 pairs; all sizes (w_qstride, KD) are then counted in 4-byte words
+// (two bf16 each), the data movement is the same byte for byte, and one 16-byte fragment
+// feeds a single v_mfma_f32_16x16x32_bf16 (lane l: k = 32c + 8*(l/16) .. +7).
+template <int NQ, int NB, bool BF16>
 __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wbase, long w_qstride,
                                                    const float* __restrict__ Abase, int KD,
                                                    int rows_valid, float* __restrict__ lds,
@@ -139,7 +142,16 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-          for (int q = 0; q < NQ; ++q) acc[rb][q] = mfma4(a[rb], w[q], acc[rb][q]);
+          for (int q = 0; q < NQ; ++q) {
+            if (BF16) {
+              typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+              acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[rb]),
+                                                                   __builtin_bit_cast(bf16x8_t, w[q]),
+                                                                   acc[rb][q], 0, 0, 0);
+            } else {
+              acc[rb][q] = mfma4(a[rb], w[q], acc[rb][q]);
+            }
+          }
       }
       __syncthreads();
     }
@@ -183,7 +195,7 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  staged_contraction<3, 4>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
+  staged_contraction<3, 4, false>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
                            staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
@@ -275,7 +287,7 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   acc[1][0] = acc[0][0];
   if (dgh_next)
-    staged_contraction<1, 12>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
+    staged_contraction<1, 12, false>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
                               B - r0, staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
@@ -321,27 +333,20 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
 }
 
 // ---------------------------------------------------------------------------- bf16 variants
-// Same tiling with v_mfma_f32_16x16x32_bf16: A lane l holds A[m = l%16][k = 8*(l/16) .. +7],
-// B lane l holds B[k = 8*(l/16) .. +7][n = l%16]: one 16-byte load per operand per 32-wide
-// contraction chunk.  The operands come from bf16 copies (weights converted once per local
+// Same tiling and the same staged data path with v_mfma_f32_16x16x32_bf16: A lane l holds
+// A[m = l%16][k = 8*(l/16) .. +7], B lane l holds B[k = 8*(l/16) .. +7][n = l%16]: one 16-byte
+// fragment per operand per 32-wide contraction chunk.  The operands come from bf16 copies (weights converted once per local
 // step, h_t / dgh_t written in both precisions by the previous step's epilogue), i.e. every
 // GEMM operand is the nearest-even bf16 rounding of the fp32 value; accumulation, the cell
 // math and everything stored for later use stay fp32.
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-
-__device__ __forceinline__ bf16x8 ldb8_or_zero(const __bf16* p, bool ok) {
-  bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-  return ok ? *reinterpret_cast<const bf16x8*>(p) : z;
-}
-
-template <int NCH>
 __global__ void __launch_bounds__(256)
 gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh,
                          long s_rep, const float* __restrict__ gx_t, long s_gx,
                          const float* __restrict__ h_prev, float* __restrict__ h_out, long s_hs,
                          const __bf16* __restrict__ hb_prev, __bf16* __restrict__ hb_out, long s_hb,
                          float* __restrict__ sv_t, long s_sv, int B, int H, int groups) {
-  __shared__ float red[4][6][4][64];
+  extern __shared__ __attribute__((aligned(16))) float staged_lds[];
+  float* red = staged_lds + 2 * 80 * SP;  // [4][6][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -349,33 +354,8 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ;
-  const int r0 = ty * FR;
-  const __bf16* W = Wb + g * s_wb;
-  const __bf16* hbp = hb_prev + g * s_hb;
+  const int j0 = tx * FJ, r0 = ty * FR;
   const float* hp = h_prev + g * s_hs;
-  const int nchunks = H / 32;
-
-  floatx4 acc[2][3];
-#pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-
-  bf16x8 w[NCH][3], a[NCH][2];
-#pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int c = wave + 4 * i;
-    const bool ok = c < nchunks;
-#pragma unroll
-    for (int q = 0; q < 3; ++q)
-      w[i][q] = ldb8_or_zero(W + (long)(q * H + j0 + lr) * H + 32 * c + 8 * lg, ok);
-#pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-      const int row = r0 + rb * 16 + lr;
-      a[i][rb] = ldb8_or_zero(hbp + (long)row * H + 32 * c + 8 * lg, ok && row < B);
-    }
-  }
   const float* bh = b_hh + g * s_rep;
   const int j = j0 + lr;
   float gxv[2][3], hpv[2], bias[3];
@@ -390,28 +370,31 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
     for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
     hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
   }
+  floatx4 acc[2][3];
 #pragma unroll
-  for (int i = 0; i < NCH; ++i)
+  for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-      for (int q = 0; q < 3; ++q)
-        acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][rb], w[i][q], acc[rb][q], 0, 0, 0);
+    for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  // rows of bf16 pairs, addressed in 4-byte words
+  staged_contraction<3, 4, true>(reinterpret_cast<const float*>(Wb + g * s_wb + (long)j0 * H), (long)H * H / 2,
+                                 reinterpret_cast<const float*>(hb_prev + g * s_hb + (long)r0 * H), H / 2,
+                                 B - r0, staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[wave][rb * 3 + q][v][lane] = acc[rb][q][v];
+      for (int v = 0; v < 4; ++v) red[((wave * 6 + rb * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
   __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
     float gh[3];
 #pragma unroll
-    for (int q = 0; q < 3; ++q)
-      gh[q] = ((red[0][rb * 3 + q][wave][lane] + red[1][rb * 3 + q][wave][lane]) +
-               (red[2][rb * 3 + q][wave][lane] + red[3][rb * 3 + q][wave][lane])) + bias[q];
+    for (int q = 0; q < 3; ++q) {
+      const int o = ((rb * 3 + q) * 4 + wave) * 64 + lane;
+      gh[q] = ((red[o] + red[o + 6 * 256]) + (red[o + 12 * 256] + red[o + 18 * 256])) + bias[q];
+    }
     if (row < B) {
       const float r = sigm(gxv[rb][0] + gh[0]);
       const float z = sigm(gxv[rb][1] + gh[1]);
@@ -433,21 +416,20 @@ hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh
                                     const float* gx_t, long s_gx, const float* h_prev, float* h_out,
                                     long s_hs, const void* hb_prev, void* hb_out, long s_hb, float* sv_t,
                                     long s_sv, int B, int H, int groups, hipStream_t s) {
+  static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_bf16_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdStagedLds);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-#define HPSGD_FWDB(N)                                                                             \
-  hipLaunchKernelGGL(gru_fwd_step_bf16_kernel<N>, grid, dim3(256), 0, s, (const __bf16*)Wb, s_wb,  \
-                     b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev,         \
-                     (__bf16*)hb_out, s_hb, sv_t, s_sv, B, H, groups)
-  const int per_wave = (H / 32 + 3) / 4;
-  if (per_wave <= 2) HPSGD_FWDB(2);
-  else if (per_wave <= 4) HPSGD_FWDB(4);
-  else if (per_wave <= 8) HPSGD_FWDB(8);
-  else HPSGD_FWDB(16);
-#undef HPSGD_FWDB
+  hipLaunchKernelGGL(gru_fwd_step_bf16_kernel, grid, dim3(256), kFwdStagedLds, s, (const __bf16*)Wb, s_wb,
+                     b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev, (__bf16*)hb_out,
+                     s_hb, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
 }
 
-template <int NCH>
 __global__ void __launch_bounds__(256)
 gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          const __bf16* __restrict__ dghb_next, __bf16* __restrict__ dghb_t, long s_dgb,
@@ -455,7 +437,8 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          long s_above, const float* __restrict__ sv_t, long s_sv,
                          const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
                          float* __restrict__ dgh_t, long s_dg, int B, int H, int groups) {
-  __shared__ float red[4][2][4][64];
+  extern __shared__ __attribute__((aligned(16))) float staged_lds[];
+  float* red = staged_lds + 2 * 48 * SP;  // [4][2][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -463,55 +446,47 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
   step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ;
-  const int r0 = ty * FR;
+  const int j0 = tx * FJ, r0 = ty * FR;
   const int H3 = 3 * H;
-  const int nchunks = H3 / 32;
   const int j = j0 + lr;
-
-  floatx4 acc[2];
-  acc[0] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  acc[1] = acc[0];
-  if (dghb_next) {
-    const __bf16* Wt = WTb + g * s_wt + (long)(j0 + lr) * H3;
-    const __bf16* dg = dghb_next + g * s_dgb;
-    bf16x8 w[NCH], a[NCH][2];
+  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2];
 #pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      const int c = wave + 4 * i;
-      const bool ok = c < nchunks;
-      w[i] = ldb8_or_zero(Wt + 32 * c + 8 * lg, ok);
-#pragma unroll
-      for (int rb = 0; rb < 2; ++rb) {
-        const int row = r0 + rb * 16 + lr;
-        a[i][rb] = ldb8_or_zero(dg + (long)row * H3 + 32 * c + 8 * lg, ok && row < B);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < NCH; ++i) {
-      acc[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][0], w[i], acc[0], 0, 0, 0);
-      acc[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][1], w[i], acc[1], 0, 0, 0);
-    }
+  for (int rb = 0; rb < 2; ++rb) {
+    const int row = r0 + rb * 16 + 4 * lg + wave;
+    const bool ok = row < B;
+    const long e = (long)row * H + j;
+    const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
+    r_[rb] = ok ? sv[j] : 0.f;
+    z_[rb] = ok ? sv[H + j] : 0.f;
+    n_[rb] = ok ? sv[2 * H + j] : 0.f;
+    q_[rb] = ok ? sv[3 * H + j] : 0.f;
+    hp_[rb] = ok ? h_prev[g * s_hs + e] : 0.f;
+    dh_[rb] = ok ? D[g * s_D + e] : 0.f;
+    if (ok && above) dh_[rb] += above[g * s_above + e];
   }
+  floatx4 acc[2][1];
+  acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  acc[1][0] = acc[0][0];
+  if (dghb_next)
+    staged_contraction<1, 12, true>(reinterpret_cast<const float*>(WTb + g * s_wt + (long)j0 * H3), 0,
+                                    reinterpret_cast<const float*>(dghb_next + g * s_dgb + (long)r0 * H3),
+                                    H3 / 2, B - r0, staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[wave][rb][v][lane] = acc[rb][v];
+    for (int v = 0; v < 4; ++v) red[((wave * 2 + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
   __syncthreads();
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
-    const float rec = (red[0][rb][wave][lane] + red[1][rb][wave][lane]) +
-                      (red[2][rb][wave][lane] + red[3][rb][wave][lane]);
+    const int o = (rb * 4 + wave) * 64 + lane;
+    const float rec = (red[o] + red[o + 2 * 256]) + (red[o + 4 * 256] + red[o + 6 * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
-      float dh = D[g * s_D + e] + rec;
-      if (above) dh += above[g * s_above + e];
-      const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
-      const float r = sv[j], z = sv[H + j], n = sv[2 * H + j], q = sv[3 * H + j];
-      const float hp = h_prev[g * s_hs + e];
+      const float dh = dh_[rb] + rec;
+      const float r = r_[rb], z = z_[rb], n = n_[rb], q = q_[rb];
       const float dn = dh * (1.0f - z);
-      const float dz = dh * (hp - n);
+      const float dz = dh * (hp_[rb] - n);
       const float da_n = dn * (1.0f - n * n);
       const float dq = da_n * r;
       const float da_r = da_n * q * r * (1.0f - r);
@@ -539,16 +514,9 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
                                     float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
                                     hipStream_t s) {
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-#define HPSGD_BWDB(N)                                                                              \
-  hipLaunchKernelGGL(gru_bwd_step_bf16_kernel<N>, grid, dim3(256), 0, s, (const __bf16*)WTb, s_wt,  \
-                     (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, \
-                     s_sv, h_prev, s_hs, dgx_t, dgh_t, s_dg, B, H, groups)
-  const int per_wave = (3 * H / 32 + 3) / 4;
-  if (per_wave <= 6) HPSGD_BWDB(6);
-  else if (per_wave <= 12) HPSGD_BWDB(12);
-  else if (per_wave <= 24) HPSGD_BWDB(24);
-  else HPSGD_BWDB(48);
-#undef HPSGD_BWDB
+  hipLaunchKernelGGL(gru_bwd_step_bf16_kernel, grid, dim3(256), kBwdStagedLds, s, (const __bf16*)WTb, s_wt,
+                     (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, s_sv,
+                     h_prev, s_hs, dgx_t, dgh_t, s_dg, B, H, groups);
   return hipGetLastError();
 }
 
