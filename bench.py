@@ -21,9 +21,12 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM traffic per launch of a role's kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured for the current kernels.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per launch of a role's kernel on the default workload, from two rocprofv3 --pmc runs
+# (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration with a plain 1 GiB copy kernel;
+# summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Other workloads: not collected (null).
+MEASURED_TRAFFIC_BYTES = {
+    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 9101.7 + 3584.0) * 1024, "gemm_recurrent_fwd": (2.0 * 7527.3 + 2560.0) * 1024},
+}
 
 
 WORKLOAD_TEXT = {
@@ -164,7 +167,7 @@ def main():
                     "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": ach / peak,
                     "avg_launch_us": dur * 1e6, "launches_timed": n_dom,
                     "ms_per_step_with_event_pairs": ms_per_step_instrumented,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(dominant)}
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)}
     for nm, v in breakdown.items():
         b_, w_, p_ = role_work_per_step(cfg, nm)
         if b_ is not None:
