@@ -210,11 +210,18 @@ static hipError_t launch_cfg(const GemmDesc& d, int vecA, int vecB, hipStream_t 
   return hipGetLastError();
 }
 
-hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s);  // gemm_bf16.hip
+hipError_t launch_gemm_bf16(const GemmDesc& d, hipStream_t s);      // gemm_bf16.hip
+hipError_t launch_gemm_f32_fast(const GemmDesc& d, hipStream_t s);  // gemm_f32_fast.hip
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
   if (d.M <= 0 || d.N <= 0 || d.groups <= 0) return hipSuccess;
   if (d.bf16) return launch_gemm_bf16(d, s);
+  if (!d.background) {
+    // aligned operands: the pipelined kernel.  Not for background work: its 72 KB of LDS per
+    // workgroup would keep the recurrent step kernels (59 KB each) off the CUs it occupies.
+    const hipError_t e = launch_gemm_f32_fast(d, s);
+    if (e != hipErrorNotSupported) return e;
+  }
   auto vec_ok = [](const float* p, long ld, long stride) {
     return (((uintptr_t)p & 15) == 0 && (ld & 3) == 0 && (stride & 3) == 0) ? 1 : 0;
   };

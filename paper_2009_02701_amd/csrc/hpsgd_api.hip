@@ -201,8 +201,9 @@ struct TimerScope {
 // GEMM helper: C = op(A) op(B) for `groups` workers.
 int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda,
          long sA, int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC,
-         int epi, const float* aux, long sAux) {
+         int epi, const float* aux, long sAux, int background = 0) {
   GemmDesc g;
+  g.background = background;
   g.A = A; g.lda = lda; g.strideA = sA; g.transA = tA;
   g.B = B; g.ldb = ldb; g.strideB = sB; g.transB = tB;
   g.C = C; g.ldc = ldc; g.strideC = sC;
@@ -494,11 +495,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       auto wgrad_rows = [&](hipStream_t st, int t0, int t1, int epi) -> int {
         const size_t r0 = (size_t)t0 * B;
         const int rows = (t1 - t0) * B;
+        const int bg = st != s;  // on the auxiliary stream: beside the recurrence
         int rc = gemm(st, groups, bf, 3 * H, win, rows, dgx + r0 * 3 * H, 3 * H, s_gx, 1, layer_in + r0 * win,
-                      win, s_layer_in, 0, grad + c->off(p + ".W_ih"), win, sG, epi, nullptr, 0);
+                      win, s_layer_in, 0, grad + c->off(p + ".W_ih"), win, sG, epi, nullptr, 0, bg);
         if (rc != HPSGD_OK) return rc;
         return gemm(st, groups, bf, 3 * H, H, rows, dgh + r0 * 3 * H, 3 * H, s_gx, 1, hs + r0 * H, H, s_hs, 0,
-                    grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0);
+                    grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0, bg);
       };
       {
       TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (fused || fused_b) ? T : 0);

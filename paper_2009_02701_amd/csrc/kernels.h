@@ -47,6 +47,8 @@ struct GemmDesc {
   int M, N, Kd, groups;
   int epilogue;
   int bf16;                                            // round operands to bf16, use the bf16 MFMA
+  int background;                                      // runs beside latency-critical kernels: keep the
+                                                       // LDS footprint small so both fit on a CU
 };
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
 
