@@ -69,34 +69,39 @@ __device__ __forceinline__ void step_tile(int NJ, int RT, int groups, int& g, in
 // instruction = two whole 512-byte row segments).  Loading straight into the MFMA layout
 // would need 16 row pieces of 64 bytes per instruction, which a fresh launch with a cold L2
 // serves about 1.7x slower.
-static constexpr int SK = 128;      // slab width along the contraction
-static constexpr int SP = SK + 4;   // LDS row pitch in floats: 16 rows x 16-byte reads hit 64 banks
+static constexpr int SK = 128;      // slab width along the contraction (4-byte words)
+static constexpr int SP = SK + 4;   // LDS row pitch in words: 16 rows x 16-byte reads hit 64 banks
 
 // acc[rb][q] += sum_k A[rb*16 + ..][k] * W_q[..][k].  Wbase points at the workgroup's first
 // weight row, gate block q starts w_qstride floats further, rows are KD floats apart;
-// Abase at its first activation row (rows >= rows_valid read as zero).  lds: 2*RT*SP floats.
-// The global loads of NB slabs at a time are all issued before the first of them is used
-// (one exposed memory latency per batch; config-2 sizes are a single batch), then the
-// slabs go through the two LDS buffers one barrier apart.
+// Abase at its first activation row (rows >= rows_valid read as zero).  lds: 2*RT*(W+4) words.
+// The global loads of NB slabs (W words wide) at a time are all issued before the first of
+// them is used (one exposed memory latency per batch), then the slabs go through the two LDS
+// buffers one barrier apart.  W = 64 halves the LDS footprint so that more workgroups share
+// a CU and cover each other's latency.
 // BF16: the rows hold bf16 pairs; all sizes (w_qstride, KD) are then counted in 4-byte words
 // (two bf16 each), the data movement is the same byte for byte, and one 16-byte fragment
 // feeds a single v_mfma_f32_16x16x32_bf16 (lane l: k = 32c + 8*(l/16) .. +7).
-template <int NQ, int NB, bool BF16>
+template <int NQ, int NB, bool BF16, int W = SK>
 __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wbase, long w_qstride,
                                                    const float* __restrict__ Abase, int KD,
                                                    int rows_valid, float* __restrict__ lds,
                                                    floatx4 (&acc)[2][NQ]) {
-  constexpr int RT = 16 * NQ + 32;  // rows of one slab tile: weight rows, then 32 activation rows
-  constexpr int UPT = RT / 8;       // float4 units per thread per slab (RT*32 units / 256 threads)
+  constexpr int RT = 16 * NQ + 32;       // rows of one slab tile: weight rows, then 32 activation rows
+  constexpr int UR = W / 4;              // float4 units per row
+  constexpr int UPT = RT * UR / 256;     // float4 units per thread per slab
+  constexpr int P = W + 4;               // LDS row pitch
+  constexpr int NC = W / 64;             // 16-word chunks per wave per slab
+  static_assert(RT * UR % 256 == 0 && (W == 64 || W == 128), "slab shape");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int lr = lane & 15, lg = lane >> 4;
-  const int nslab = (KD + SK - 1) / SK;
+  const int nslab = (KD + W - 1) / W;
   // per-thread row pointers and validity of its UPT units (the same for every slab)
   const float* rowp[UPT];
   bool rowok[UPT];
 #pragma unroll
   for (int i = 0; i < UPT; ++i) {
-    const int row = (tid + i * 256) >> 5;
+    const int row = (tid + i * 256) / UR;
     if (row < 16 * NQ) {
       rowp[i] = Wbase + (row >> 4) * w_qstride + (long)(row & 15) * KD;
       rowok[i] = true;
@@ -106,12 +111,12 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
       rowp[i] = Abase + (long)(rowok[i] ? ar : 0) * KD;
     }
   }
-  const int colofs = (tid & 31) << 2;
+  const int colofs = (tid % UR) << 2;
   for (int s0 = 0; s0 < nslab; s0 += NB) {
     float4 regs[NB][UPT];
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb) {
-      const int col = (s0 + sb) * SK + colofs;
+      const int col = (s0 + sb) * W + colofs;
       const bool cok = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
 #pragma unroll
       for (int i = 0; i < UPT; ++i) regs[sb][i] = ld4_or_zero(rowp[i] + col, cok && rowok[i]);
@@ -120,7 +125,7 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
 #pragma unroll
       for (int i = 0; i < UPT; ++i) {
         const int u = tid + i * 256;
-        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + (u >> 5)) * SP + ((u & 31) << 2)]) = regs[sb][i];
+        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + u / UR) * P + ((u % UR) << 2)]) = regs[sb][i];
       }
     };
     sstore(0);
@@ -130,15 +135,15 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
       if (sb + 1 < NB) sstore(sb + 1);  // slabs past the end were loaded as zeros
       const int b = sb & 1;
 #pragma unroll
-      for (int ci = 0; ci < 2; ++ci) {
+      for (int ci = 0; ci < NC; ++ci) {
         const int kcol = 16 * (wave + 4 * ci) + 4 * lg;  // chunk (wave + 4*ci) of this slab
         float4 a[2], w[NQ];
 #pragma unroll
         for (int q = 0; q < NQ; ++q)
-          w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * SP + kcol]);
+          w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
-          a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * SP + kcol]);
+          a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * P + kcol]);
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -230,6 +235,11 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
 
 static constexpr size_t kFwdStagedLds = (2 * 80 * SP + 4 * 6 * 4 * 64) * sizeof(float);
 static constexpr size_t kBwdStagedLds = (2 * 48 * SP + 4 * 2 * 4 * 64) * sizeof(float);
+// bf16 variants: 64-word slabs, so that two or three workgroups fit on a CU (config 3 launches
+// two workgroups per CU; resident together they cover each other's load latency)
+static constexpr int SKB = 64;
+static constexpr size_t kFwdBf16Lds = (2 * 80 * (SKB + 4) + 4 * 6 * 4 * 64) * sizeof(float);
+static constexpr size_t kBwdBf16Lds = (2 * 48 * (SKB + 4) + 4 * 2 * 4 * 64) * sizeof(float);
 
 hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
                                       long s_gx, const float* h_prev, float* h_out, long s_hs,
@@ -339,14 +349,14 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
 // step, h_t / dgh_t written in both precisions by the previous step's epilogue), i.e. every
 // GEMM operand is the nearest-even bf16 rounding of the fp32 value; accumulation, the cell
 // math and everything stored for later use stay fp32.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh,
                          long s_rep, const float* __restrict__ gx_t, long s_gx,
                          const float* __restrict__ h_prev, float* __restrict__ h_out, long s_hs,
                          const __bf16* __restrict__ hb_prev, __bf16* __restrict__ hb_out, long s_hb,
                          float* __restrict__ sv_t, long s_sv, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 80 * SP;  // [4][6][4][64]
+  float* red = staged_lds + 2 * 80 * (SKB + 4);  // [4][6][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -376,7 +386,7 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
   // rows of bf16 pairs, addressed in 4-byte words
-  staged_contraction<3, 4, true>(reinterpret_cast<const float*>(Wb + g * s_wb + (long)j0 * H), (long)H * H / 2,
+  staged_contraction<3, 8, true, SKB>(reinterpret_cast<const float*>(Wb + g * s_wb + (long)j0 * H), (long)H * H / 2,
                                  reinterpret_cast<const float*>(hb_prev + g * s_hb + (long)r0 * H), H / 2,
                                  B - r0, staged_lds, acc);
 #pragma unroll
@@ -419,18 +429,18 @@ hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh
   static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
   if (!ready) {
     hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_bf16_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdStagedLds);
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdBf16Lds);
     if (e != hipSuccess) return e;
     ready = true;
   }
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-  hipLaunchKernelGGL(gru_fwd_step_bf16_kernel, grid, dim3(256), kFwdStagedLds, s, (const __bf16*)Wb, s_wb,
+  hipLaunchKernelGGL(gru_fwd_step_bf16_kernel, grid, dim3(256), kFwdBf16Lds, s, (const __bf16*)Wb, s_wb,
                      b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev, (__bf16*)hb_out,
                      s_hb, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256, 2)
 gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          const __bf16* __restrict__ dghb_next, __bf16* __restrict__ dghb_t, long s_dgb,
                          float* __restrict__ D, long s_D, const float* __restrict__ above,
@@ -438,7 +448,7 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
                          float* __restrict__ dgh_t, long s_dg, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 48 * SP;  // [4][2][4][64]
+  float* red = staged_lds + 2 * 48 * (SKB + 4);  // [4][2][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -468,7 +478,7 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
   acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   acc[1][0] = acc[0][0];
   if (dghb_next)
-    staged_contraction<1, 12, true>(reinterpret_cast<const float*>(WTb + g * s_wt + (long)j0 * H3), 0,
+    staged_contraction<1, 12, true, SKB>(reinterpret_cast<const float*>(WTb + g * s_wt + (long)j0 * H3), 0,
                                     reinterpret_cast<const float*>(dghb_next + g * s_dgb + (long)r0 * H3),
                                     H3 / 2, B - r0, staged_lds, acc);
 #pragma unroll
@@ -514,7 +524,7 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
                                     float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
                                     hipStream_t s) {
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-  hipLaunchKernelGGL(gru_bwd_step_bf16_kernel, grid, dim3(256), kBwdStagedLds, s, (const __bf16*)WTb, s_wt,
+  hipLaunchKernelGGL(gru_bwd_step_bf16_kernel, grid, dim3(256), kBwdBf16Lds, s, (const __bf16*)WTb, s_wt,
                      (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, s_sv,
                      h_prev, s_hs, dgx_t, dgh_t, s_dg, B, H, groups);
   return hipGetLastError();
