@@ -238,6 +238,7 @@ static constexpr size_t kBwdStagedLds = (2 * 48 * SP + 4 * 2 * 4 * 64) * sizeof(
 // bf16 variants: 64-word slabs, so that two or three workgroups fit on a CU (config 3 launches
 // two workgroups per CU; resident together they cover each other's load latency)
 static constexpr int SKB = 64;
+static constexpr int TTP = 40;  // pitch (bf16) of a staged transposed-output row of 32 batch rows
 static constexpr size_t kFwdBf16Lds = (2 * 80 * (SKB + 4) + 4 * 6 * 4 * 64) * sizeof(float);
 static constexpr size_t kBwdBf16Lds = (2 * 48 * (SKB + 4) + 4 * 2 * 4 * 64) * sizeof(float);
 
@@ -354,9 +355,12 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
                          long s_rep, const float* __restrict__ gx_t, long s_gx,
                          const float* __restrict__ h_prev, float* __restrict__ h_out, long s_hs,
                          const __bf16* __restrict__ hb_prev, __bf16* __restrict__ hb_out, long s_hb,
-                         float* __restrict__ sv_t, long s_sv, int B, int H, int groups) {
+                         float* __restrict__ sv_t, long s_sv, __bf16* __restrict__ hT_out, long ld_hT,
+                         long s_hT, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
   float* red = staged_lds + 2 * 80 * (SKB + 4);  // [4][6][4][64]
+  // transposed output tile [16 units][32 rows] (the slab buffers are free by then)
+  __bf16* tt = reinterpret_cast<__bf16*>(staged_lds);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -413,6 +417,7 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
       const float hn = (1.0f - z) * n + z * hpv[rb];
       h_out[g * s_hs + (long)row * H + j] = hn;
       hb_out[g * s_hb + (long)row * H + j] = (__bf16)hn;
+      if (hT_out) tt[lr * TTP + rb * 16 + 4 * lg + wave] = (__bf16)hn;
       float* sv = sv_t + g * s_sv + (long)row * 4 * H;
       sv[j] = r;
       sv[H + j] = z;
@@ -420,12 +425,23 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
       sv[3 * H + j] = qv;
     }
   }
+  if (hT_out) {
+    // 64-byte row segments of the transposed copy [unit][time*B + row], 16 bytes per thread
+    __syncthreads();
+    if (tid < 64) {
+      const int u = tid >> 2, part = tid & 3;
+      if (r0 + 8 * part < B)  // B is a multiple of 8: a chunk of 8 rows is all in or all out
+        *reinterpret_cast<uint4*>(hT_out + g * s_hT + (long)(j0 + u) * ld_hT + r0 + 8 * part) =
+            *reinterpret_cast<const uint4*>(tt + u * TTP + 8 * part);
+    }
+  }
 }
 
 hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep,
                                     const float* gx_t, long s_gx, const float* h_prev, float* h_out,
                                     long s_hs, const void* hb_prev, void* hb_out, long s_hb, float* sv_t,
-                                    long s_sv, int B, int H, int groups, hipStream_t s) {
+                                    long s_sv, void* hT_out, long ld_hT, long s_hT, int B, int H,
+                                    int groups, hipStream_t s) {
   static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
   if (!ready) {
     hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_bf16_kernel,
@@ -436,7 +452,7 @@ hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
   hipLaunchKernelGGL(gru_fwd_step_bf16_kernel, grid, dim3(256), kFwdBf16Lds, s, (const __bf16*)Wb, s_wb,
                      b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev, (__bf16*)hb_out,
-                     s_hb, sv_t, s_sv, B, H, groups);
+                     s_hb, sv_t, s_sv, (__bf16*)hT_out, ld_hT, s_hT, B, H, groups);
   return hipGetLastError();
 }
 
@@ -446,9 +462,13 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          float* __restrict__ D, long s_D, const float* __restrict__ above,
                          long s_above, const float* __restrict__ sv_t, long s_sv,
                          const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
-                         float* __restrict__ dgh_t, long s_dg, int B, int H, int groups) {
+                         float* __restrict__ dgh_t, long s_dg, __bf16* __restrict__ dgxb_t,
+                         __bf16* __restrict__ dgxT_t, __bf16* __restrict__ dghT_t, long ld_T, long s_T,
+                         int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
   float* red = staged_lds + 2 * 48 * (SKB + 4);  // [4][2][4][64]
+  // transposed output tile [da_r | da_z | da_n | dq][16 units][32 rows] (the slab buffers are free by then)
+  __bf16* tt = reinterpret_cast<__bf16*>(staged_lds);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -513,7 +533,34 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
       ob[j] = (__bf16)da_r;
       ob[H + j] = (__bf16)da_z;
       ob[2 * H + j] = (__bf16)dq;
+      if (dgxb_t) {
+        // bf16 copies for the time-batched GEMMs: dgx row-major (input gradient), and the
+        // four distinct gate-gradient blocks staged for the transposed copies
+        __bf16* oxb = dgxb_t + g * s_dgb + (long)row * H3;
+        oxb[j] = (__bf16)da_r;
+        oxb[H + j] = (__bf16)da_z;
+        oxb[2 * H + j] = (__bf16)da_n;
+        const int rl = rb * 16 + 4 * lg + wave;
+        tt[(0 * 16 + lr) * TTP + rl] = (__bf16)da_r;
+        tt[(1 * 16 + lr) * TTP + rl] = (__bf16)da_z;
+        tt[(2 * 16 + lr) * TTP + rl] = (__bf16)da_n;
+        tt[(3 * 16 + lr) * TTP + rl] = (__bf16)dq;
+      }
       D[g * s_D + e] = dh * z;
+    }
+  }
+  if (dgxb_t) {
+    // transposed copies [gate unit][time*B + row] as 64-byte row segments, 16 bytes per
+    // thread: dgx^T = (da_r, da_z, da_n), dgh^T = (da_r, da_z, dq)
+    __syncthreads();
+    const int blk = tid >> 6, u = (tid >> 2) & 15, part = tid & 3;  // blk: which staged block
+    if (r0 + 8 * part < B) {  // B is a multiple of 8: a chunk of 8 rows is all in or all out
+      const uint4 v = *reinterpret_cast<const uint4*>(tt + (blk * 16 + u) * TTP + 8 * part);
+      const long col = r0 + 8 * part;
+      const int gate = blk == 3 ? 2 : blk;
+      const long o = g * s_T + (long)(gate * H + j0 + u) * ld_T + col;
+      if (blk != 3) *reinterpret_cast<uint4*>(dgxT_t + o) = v;
+      if (blk != 2) *reinterpret_cast<uint4*>(dghT_t + o) = v;
     }
   }
 }
@@ -521,12 +568,14 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
 hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb_next, void* dghb_t,
                                     long s_dgb, float* D, long s_D, const float* above, long s_above,
                                     const float* sv_t, long s_sv, const float* h_prev, long s_hs,
-                                    float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
+                                    float* dgx_t, float* dgh_t, long s_dg, void* dgxb_t, void* dgxT_t,
+                                    void* dghT_t, long ld_T, long s_T, int B, int H, int groups,
                                     hipStream_t s) {
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
   hipLaunchKernelGGL(gru_bwd_step_bf16_kernel, grid, dim3(256), kBwdBf16Lds, s, (const __bf16*)WTb, s_wt,
                      (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, s_sv,
-                     h_prev, s_hs, dgx_t, dgh_t, s_dg, B, H, groups);
+                     h_prev, s_hs, dgx_t, dgh_t, s_dg, (__bf16*)dgxb_t, (__bf16*)dgxT_t, (__bf16*)dghT_t, ld_T,
+                     s_T, B, H, groups);
   return hipGetLastError();
 }
 

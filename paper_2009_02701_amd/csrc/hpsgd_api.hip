@@ -34,7 +34,7 @@ struct hpsgd_ctx {
   size_t ws_floats = 0;
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
-  Region hb, dghb;              // bf16 copies of h and dgh (bf16 precision only)
+  Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
   Region dgxT, dghT, xT, dlogT, wihT, woT;
@@ -116,6 +116,7 @@ int build_layout(hpsgd_ctx* c) {
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
+      c->dgxb = c->alloc((TB * 3 * H + 1) / 2);
       const size_t TBp = round_up(TB, 8), TB1p = round_up(TB + d.batch, 8);
       const size_t win0 = lm ? d.embed : d.input;
       const size_t wmax = win0 > H ? win0 : H;
@@ -321,6 +322,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const long s_gx = (long)c->gx.stride, s_gh = (long)c->gh.stride, s_D = (long)c->D.stride;
     const long s_dx = (long)c->dx.stride, s_log = (long)c->logits.stride;
 
+    // bf16 precision: the weight-gradient and input-gradient GEMMs take contraction-contiguous
+    // bf16 operands ("NT" form); the fused step kernels write those copies themselves
+    const bool ntc = bf && (B % 8 == 0) && (H % 8 == 0);
+    const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
+    auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -357,10 +363,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_wb = 2 * (long)c->wt.stride;
       __bf16* hb = fused_b ? (__bf16*)reg(c->hb) : nullptr;
       const long s_hb = 2 * (long)c->hb.stride;
+      __bf16* hT = (fused_b && ntc) ? bfreg(c->hsT[l]) : nullptr;  // hsT exists in bf16 precision only
+      const long s_hT = hT ? 2 * (long)c->hsT[l].stride : 0;
       if (fused_b) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
         HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
+        if (hT)  // h_0 = 0: the first B columns of the transposed copy
+          HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
       }
       // one event pair around the whole time loop when its launches are all of one role
       TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (fused || fused_b) ? T : 0);
@@ -371,7 +381,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H,
                                            s_gx, hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
                                            hb + (size_t)t * B * H, hb + (size_t)(t + 1) * B * H, s_hb,
-                                           sv + (size_t)t * B * 4 * H, s_sv, B, H, groups, s));
+                                           sv + (size_t)t * B * 4 * H, s_sv,
+                                           hT ? hT + (size_t)(t + 1) * B : nullptr, TB1p, s_hT, B, H, groups,
+                                           s));
           continue;
         }
         if (fused) {
@@ -411,15 +423,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
     // ---- backward: head
     // bf16 precision: transposed bf16 copies (contraction-contiguous operands for the NT kernel)
-    const bool ntc = bf && (B % 8 == 0) && (H % 8 == 0);
-    const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
     const long nrp = (long)round_up(nrows, 8), clp = (long)round_up(classes, 8);
-    auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
     if (ntc) {
       role = HPSGD_ROLE_OTHER;
-      for (int l = 0; l < L; ++l)  // hs^T of every layer: [H][(T+1)B]
-        HIP_TRY(launch_cvt_bf16(reg(c->hs[l]), H, (long)c->hs[l].stride, bfreg(c->hsT[l]), TB1p,
-                                2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
+      if (!gru_fused_bf16_supported(H))  // else written by the forward step kernels
+        for (int l = 0; l < L; ++l)      // hs^T of every layer: [H][(T+1)B]
+          HIP_TRY(launch_cvt_bf16(reg(c->hs[l]), H, (long)c->hs[l].stride, bfreg(c->hsT[l]), TB1p,
+                                  2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
       HIP_TRY(launch_cvt_bf16(logits, classes, s_log, bfreg(c->dlogT), nrp, 2 * (long)c->dlogT.stride, nrows,
                               classes, true, groups, s));
       HIP_TRY(launch_cvt_bf16(rin + oW, H, sR, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
@@ -477,6 +487,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_wt = (long)c->wt.stride;
       __bf16* dghb = fused_b ? (__bf16*)reg(c->dghb) : nullptr;
       const long s_dgb = 2 * (long)c->dghb.stride;
+      const bool stepT = fused_b && ntc && win % 8 == 0;  // the step kernels write the bf16 copies
+      __bf16* dgxb = stepT ? bfreg(c->dgxb) : nullptr;
+      const long s_T = 2 * (long)c->dgxT.stride;
       if (fused) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
@@ -522,7 +535,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           HIP_TRY(launch_gru_bwd_step_bf16(wt, 2 * s_wt, t + 1 < T ? dghb + (size_t)(t + 1) * B * 3 * H : nullptr,
                                            dghb + (size_t)t * B * 3 * H, s_dgb, D, s_D, above_t, s_dx,
                                            sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
-                                           dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx, B, H,
+                                           dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx,
+                                           dgxb ? dgxb + (size_t)t * B * 3 * H : nullptr,
+                                           dgxb ? bfreg(c->dgxT) + (size_t)t * B : nullptr,
+                                           dgxb ? bfreg(c->dghT) + (size_t)t * B : nullptr, TBp, s_T, B, H,
                                            groups, s));
           continue;
         }
@@ -550,10 +566,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       NtView v_dgxT, v_dghT, v_xT, v_hsT, v_wihT;
       if (ntc && win % 8 == 0) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_cvt_bf16(dgx, 3 * H, s_gx, bfreg(c->dgxT), TBp, 2 * (long)c->dgxT.stride, TB, 3 * H, true,
-                                groups, s));
-        HIP_TRY(launch_cvt_bf16(dgh, 3 * H, s_gx, bfreg(c->dghT), TBp, 2 * (long)c->dghT.stride, TB, 3 * H, true,
-                                groups, s));
+        if (!stepT) {
+          HIP_TRY(launch_cvt_bf16(dgx, 3 * H, s_gx, bfreg(c->dgxT), TBp, 2 * (long)c->dgxT.stride, TB, 3 * H,
+                                  true, groups, s));
+          HIP_TRY(launch_cvt_bf16(dgh, 3 * H, s_gx, bfreg(c->dghT), TBp, 2 * (long)c->dghT.stride, TB, 3 * H,
+                                  true, groups, s));
+        }
         v_dgxT = NtView{bfreg(c->dgxT), 1, TBp, 2 * (long)c->dgxT.stride};
         v_dghT = NtView{bfreg(c->dghT), 1, TBp, 2 * (long)c->dghT.stride};
         v_hsT = NtView{bfreg(c->hsT[l]), 1, TB1p, 2 * (long)c->hsT[l].stride};
@@ -586,7 +604,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
       role = HPSGD_ROLE_GEMM_DX;
       if (need_dx) {
-        const NtView v_dgx{dgx, 0, 3 * H, s_gx};
+        const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
         TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
                   nullptr, 0, v_dgx, v_wihT));
         above = dx;

@@ -22,6 +22,9 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s);
 // p[g*stride + i] = 0 for i < n (p 16-byte aligned, stride a multiple of 4)
 hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s);
+// p[g*stride + r*ld + c] = 0 for r < rows, c < cols (4-byte words)
+hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t stride, int groups,
+                               hipStream_t s);
 hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,
                          int n_chunks, size_t chunk_bytes, void* out, hipStream_t s);
 
@@ -77,11 +80,13 @@ bool gru_fused_bf16_supported(int H);
 hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep,
                                     const float* gx_t, long s_gx, const float* h_prev, float* h_out,
                                     long s_hs, const void* hb_prev, void* hb_out, long s_hb, float* sv_t,
-                                    long s_sv, int B, int H, int groups, hipStream_t s);
+                                    long s_sv, void* hT_out, long ld_hT, long s_hT, int B, int H,
+                                    int groups, hipStream_t s);
 hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb_next, void* dghb_t,
                                     long s_dgb, float* D, long s_D, const float* above, long s_above,
                                     const float* sv_t, long s_sv, const float* h_prev, long s_hs,
-                                    float* dgx_t, float* dgh_t, long s_dg, int B, int H, int groups,
+                                    float* dgx_t, float* dgh_t, long s_dg, void* dgxb_t, void* dgxT_t,
+                                    void* dghT_t, long ld_T, long s_T, int B, int H, int groups,
                                     hipStream_t s);
 // out(bf16) = round(in), in is R x C with row pitch ld_in; transpose: out[c][r] = in[r][c];
 // ld_out is the row pitch of out, strides of out in bf16 elements

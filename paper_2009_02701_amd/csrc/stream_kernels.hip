@@ -183,6 +183,25 @@ hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipSt
   return hipGetLastError();
 }
 
+// p[g*stride + r*ld + c] = 0 for r < rows, c < cols: a column block of a row-major matrix
+__global__ void __launch_bounds__(kThreads)
+fill_zero_2d_kernel(float* p, long ld, int rows, int cols, size_t stride) {
+  float* pg = p + (size_t)blockIdx.y * stride;
+  const long n = (long)rows * cols;
+  for (long i = (long)blockIdx.x * kThreads + threadIdx.x; i < n; i += (long)gridDim.x * kThreads)
+    pg[(i / cols) * ld + i % cols] = 0.f;
+}
+
+hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t stride, int groups,
+                               hipStream_t s) {
+  if (rows <= 0 || cols <= 0 || groups <= 0) return hipSuccess;
+  const long n = (long)rows * cols;
+  int blocks = (int)((n + kThreads - 1) / kThreads);
+  if (blocks > 256) blocks = 256;
+  hipLaunchKernelGGL(fill_zero_2d_kernel, dim3(blocks, groups), dim3(kThreads), 0, s, p, ld, rows, cols, stride);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------- gather
 // out[(c*n_idx + b)*chunk ...] = shard[idx[b]*row + c*chunk ...], in 4-byte words.
 __global__ void __launch_bounds__(kThreads)
