@@ -1,0 +1,243 @@
+// Helpers of the bf16 training path that are not contractions: rounded / transposed operand
+// copies, the softmax-CE that emits bf16 logit gradients, and row sums of a bf16 matrix.
+// Every time-batched GEMM of that path takes contraction-contiguous bf16 operands; these
+// kernels produce the ones that no other kernel's epilogue writes.
+#include "kernels.h"
+
+namespace hpsgd {
+
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ bf16x4 load4_as_bf16(const float* p) {
+  const float4 v = *reinterpret_cast<const float4*>(p);
+  bf16x4 r;
+  r[0] = (__bf16)v.x; r[1] = (__bf16)v.y; r[2] = (__bf16)v.z; r[3] = (__bf16)v.w;
+  return r;
+}
+__device__ __forceinline__ bf16x4 load4_as_bf16(const __bf16* p) {
+  return *reinterpret_cast<const bf16x4*>(p);
+}
+
+// in: R x C (fp32 or bf16, row pitch ld_in).  out_p (nullable): the bf16 rounding, row pitch
+// ld_p.  out_t (nullable): its transpose, out_t[c][r], row pitch ld_t.  One 64 x 64 tile per
+// workgroup, read once: 16-byte (fp32) or 8-byte (bf16) loads, 8-byte plain stores, and the
+// transposed tile goes through LDS and leaves as 16-byte pieces of 8 consecutive input rows.
+// Needs C % 4 == 0, R % 8 == 0 and the alignments cvt2_supported checks.
+template <typename TIN>
+__global__ void __launch_bounds__(256)
+cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restrict__ out_p, long ld_p,
+            long s_p, __bf16* __restrict__ out_t, long ld_t, long s_t, int R, int C) {
+  __shared__ __attribute__((aligned(16))) __bf16 tile[64][72];  // [column][row]
+  const int g = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
+  const TIN* src = in + g * s_in;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rl = ty + 16 * i, r = r0 + rl, c = c0 + 4 * tx;
+    bf16x4 v;
+    v[0] = v[1] = v[2] = v[3] = (__bf16)0.f;
+    if (r < R && c < C) {
+      v = load4_as_bf16(src + (long)r * ld_in + c);
+      if (out_p) *reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c) = v;
+    }
+    if (out_t) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) tile[4 * tx + e][rl] = v[e];
+    }
+  }
+  if (!out_t) return;
+  __syncthreads();
+#pragma unroll
+  for (int q = 0; q < 2; ++q) {
+    const int idx = threadIdx.x + 256 * q, col = idx >> 3, part = idx & 7;
+    const int c = c0 + col, r = r0 + 8 * part;
+    if (c < C && r < R)
+      *reinterpret_cast<uint4*>(out_t + g * s_t + (long)c * ld_t + r) =
+          *reinterpret_cast<const uint4*>(&tile[col][8 * part]);
+  }
+}
+
+bool cvt2_supported(const void* in, int in_bf16, long ld_in, long s_in, const void* out_p, long ld_p,
+                    long s_p, const void* out_t, long ld_t, long s_t, int R, int C) {
+  const uintptr_t in_mask = in_bf16 ? 7 : 15;
+  if (((uintptr_t)in & in_mask) != 0 || ld_in % 4 != 0 || s_in % 4 != 0 || C % 4 != 0 || R % 8 != 0) return false;
+  if (out_p && (((uintptr_t)out_p & 7) != 0 || ld_p % 4 != 0 || s_p % 4 != 0)) return false;
+  if (out_t && (((uintptr_t)out_t & 15) != 0 || ld_t % 8 != 0 || s_t % 8 != 0)) return false;
+  return R > 0 && C > 0;
+}
+
+hipError_t launch_cvt2(const void* in, int in_bf16, long ld_in, long s_in, void* out_p, long ld_p, long s_p,
+                       void* out_t, long ld_t, long s_t, int R, int C, int groups, hipStream_t s) {
+  if (!cvt2_supported(in, in_bf16, ld_in, s_in, out_p, ld_p, s_p, out_t, ld_t, s_t, R, C))
+    return hipErrorInvalidValue;
+  dim3 grid((C + 63) / 64, (R + 63) / 64, groups);
+  if (in_bf16)
+    hipLaunchKernelGGL(cvt2_kernel<__bf16>, grid, dim3(256), 0, s, (const __bf16*)in, ld_in, s_in,
+                       (__bf16*)out_p, ld_p, s_p, (__bf16*)out_t, ld_t, s_t, R, C);
+  else
+    hipLaunchKernelGGL(cvt2_kernel<float>, grid, dim3(256), 0, s, (const float*)in, ld_in, s_in,
+                       (__bf16*)out_p, ld_p, s_p, (__bf16*)out_t, ld_t, s_t, R, C);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- softmax-CE, bf16 gradient
+// One workgroup per row; the row (C <= 1024 * V4 logits) is read once into registers.
+// Writes dlogits = (softmax - onehot)/N rounded to bf16 (row pitch ld_d), the row's loss
+// -log softmax[y] and the row's (max, 1/sum) pair; the logits stay as they are.
+template <int V4>
+__global__ void __launch_bounds__(256)
+softmax_ce_bf16_kernel(const float* __restrict__ logits, long s_logits, const int32_t* __restrict__ y,
+                       long s_y, __bf16* __restrict__ dlog, long ld_d, long s_d,
+                       float* __restrict__ rowloss, long s_rowloss, float2* __restrict__ rowstat,
+                       long s_rowstat, int N, int C) {
+  __shared__ float red[4];
+  __shared__ float bcast;
+  const int g = blockIdx.y, row = blockIdx.x;
+  const float* lr = logits + g * s_logits + (long)row * C;
+  const int label = y[g * s_y + row];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float4 v[V4];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int c = 4 * (tid + 256 * i);
+    if (c < C) {
+      v[i] = *reinterpret_cast<const float4*>(lr + c);
+      m = fmaxf(fmaxf(m, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if (lane == 0) red[wave] = m;
+  __syncthreads();
+  if (tid == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  m = bcast;
+  __syncthreads();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int c = 4 * (tid + 256 * i);
+    if (c < C) {
+      v[i].x = expf(v[i].x - m); v[i].y = expf(v[i].y - m);
+      v[i].z = expf(v[i].z - m); v[i].w = expf(v[i].w - m);
+      sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+  if (lane == 0) red[wave] = sum;
+  __syncthreads();
+  if (tid == 0) bcast = (red[0] + red[1]) + (red[2] + red[3]);
+  __syncthreads();
+  sum = bcast;
+  const float inv_sum = 1.0f / sum, inv_n = 1.0f / (float)N;
+  if (tid == 0) {
+    rowloss[g * s_rowloss + row] = -((lr[label] - m) - logf(sum));
+    rowstat[g * s_rowstat + row] = make_float2(m, inv_sum);
+  }
+  __bf16* dr = dlog + g * s_d + (long)row * ld_d;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int c = 4 * (tid + 256 * i);
+    if (c < C) {
+      bf16x4 o;
+      o[0] = (__bf16)((v[i].x * inv_sum - (c + 0 == label ? 1.0f : 0.0f)) * inv_n);
+      o[1] = (__bf16)((v[i].y * inv_sum - (c + 1 == label ? 1.0f : 0.0f)) * inv_n);
+      o[2] = (__bf16)((v[i].z * inv_sum - (c + 2 == label ? 1.0f : 0.0f)) * inv_n);
+      o[3] = (__bf16)((v[i].w * inv_sum - (c + 3 == label ? 1.0f : 0.0f)) * inv_n);
+      *reinterpret_cast<bf16x4*>(dr + c) = o;
+    }
+  }
+}
+
+bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* dlog, long ld_d, long s_d,
+                               int C) {
+  return C % 4 == 0 && C >= 4 && C <= 1024 * 10 && ((uintptr_t)logits & 15) == 0 && s_logits % 4 == 0 &&
+         ((uintptr_t)dlog & 7) == 0 && ld_d % 4 == 0 && s_d % 4 == 0;
+}
+
+hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
+                                  long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
+                                  long s_rowstat, int N, int C, int groups, hipStream_t s) {
+  if (!softmax_ce_bf16_supported(logits, s_logits, dlog, ld_d, s_d, C)) return hipErrorInvalidValue;
+  dim3 grid(N, groups);
+#define HPSGD_SM(V4)                                                                                    \
+  hipLaunchKernelGGL(softmax_ce_bf16_kernel<V4>, grid, dim3(256), 0, s, logits, s_logits, y, s_y,       \
+                     (__bf16*)dlog, ld_d, s_d, rowloss, s_rowloss, reinterpret_cast<float2*>(rowstat),        \
+                     s_rowstat / 2, N, C)
+  if (C <= 1024) HPSGD_SM(1);
+  else if (C <= 4096) HPSGD_SM(4);
+  else HPSGD_SM(10);
+#undef HPSGD_SM
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- bias gradient of the head
+// out[c] = (1/N) sum_r (softmax[r][c] - [y_r == c]), recomputed in fp32 from the logits and
+// the rows' (max, 1/sum) pairs: the bias gradient is not a GEMM operand and is not rounded.
+// A workgroup of 1024 threads covers 64 columns with 16 row slices, combined in a fixed order.
+__global__ void __launch_bounds__(1024)
+colsum_softmax_kernel(const float* __restrict__ logits, long s_logits, const float2* __restrict__ rowstat,
+                      long s_rowstat, const int32_t* __restrict__ y, long s_y, float* __restrict__ out,
+                      long s_out, int N, int C) {
+  __shared__ float red[16][64];
+  const int g = blockIdx.y, lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane;
+  float a = 0.f;
+  if (c < C) {
+    const float* p = logits + g * s_logits + c;
+    for (int r = slice; r < N; r += 16) {
+      const float2 st = rowstat[g * s_rowstat + r];
+      a += expf(p[(long)r * C] - st.x) * st.y - (y[g * s_y + r] == c ? 1.0f : 0.0f);
+    }
+  }
+  red[slice][lane] = a;
+  __syncthreads();
+  if (slice == 0 && c < C) {
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) v += red[i][lane];
+    out[g * s_out + c] = v / (float)N;
+  }
+}
+
+hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
+                                 const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
+                                 hipStream_t s) {
+  hipLaunchKernelGGL(colsum_softmax_kernel, dim3((C + 63) / 64, groups), dim3(1024), 0, s, logits, s_logits,
+                     reinterpret_cast<const float2*>(rowstat), s_rowstat / 2, y, s_y, out, s_out, N, C);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------- row sums of a bf16 matrix
+// out[r] = sum_c in[r][c] (fp32 accumulation): one wave per row, lanes stride over 8-element
+// pieces, fixed combination order.  C % 8 == 0, rows 16-byte aligned.
+__global__ void __launch_bounds__(256)
+rowsum_bf16_kernel(const __bf16* __restrict__ in, long ld, long s_in, float* __restrict__ out, long s_out,
+                   int R, int C) {
+  const int g = blockIdx.y, lane = threadIdx.x & 63;
+  const int r = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= R) return;
+  const __bf16* p = in + g * s_in + (long)r * ld;
+  float a = 0.f;
+  for (int c = 8 * lane; c < C; c += 512) {
+    typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+    const bf16x8 v = *reinterpret_cast<const bf16x8*>(p + c);
+    a += (((float)v[0] + (float)v[1]) + ((float)v[2] + (float)v[3])) +
+         (((float)v[4] + (float)v[5]) + ((float)v[6] + (float)v[7]));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) a += __shfl_xor(a, o);
+  if (lane == 0) out[g * s_out + r] = a;
+}
+
+hipError_t launch_rowsum_bf16(const void* in, long ld, long s_in, float* out, long s_out, int R, int C,
+                              int groups, hipStream_t s) {
+  if (C % 8 != 0 || ld % 8 != 0 || s_in % 8 != 0 || ((uintptr_t)in & 15) != 0) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(rowsum_bf16_kernel, dim3((R + 3) / 4, groups), dim3(256), 0, s, (const __bf16*)in, ld,
+                     s_in, out, s_out, R, C);
+  return hipGetLastError();
+}
+
+}  // namespace hpsgd

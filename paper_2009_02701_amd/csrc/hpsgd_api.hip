@@ -38,6 +38,8 @@ struct hpsgd_ctx {
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
   Region dgxT, dghT, xT, dlogT, wihT, woT;
+  Region xb, wihb, wob, dlogb;  // row-major bf16 copies: layer-0 input, W_ih, head.W, dlogits
+  Region rowstat;               // per logits row: (max, 1 / sum of exponentials)
   std::vector<Region> hsT;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
@@ -128,6 +130,11 @@ int build_layout(hpsgd_ctx* c) {
       c->dlogT = c->alloc((size_t)classes * round_up(nr, 8) / 2);
       c->wihT = c->alloc(wmax * 3 * H / 2);
       c->woT = c->alloc(H * round_up(classes, 8) / 2);
+      c->xb = c->alloc((TB * win0 + 1) / 2);
+      c->wihb = c->alloc((wmax * 3 * H + 1) / 2);
+      c->wob = c->alloc(((size_t)classes * H + 1) / 2);
+      c->dlogb = c->alloc((nr * round_up(classes, 8) + 1) / 2);
+      c->rowstat = c->alloc(2 * nr);
     }
     size_t wmax = H;
     if (lm && (size_t)d.embed > wmax) wmax = d.embed;
@@ -327,6 +334,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const bool ntc = bf && (B % 8 == 0) && (H % 8 == 0);
     const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
     auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
+    bool xT_ready = false;  // the transposed bf16 layer-0 input was made in the forward pass
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -347,16 +355,37 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
       role = HPSGD_ROLE_OTHER;
       HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s));
-      role = HPSGD_ROLE_GEMM_INPUT;
-      {
-        const float* Wih = rin + c->off(p + ".W_ih");
-        const NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
-        TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
-                  EPI_BIAS, rin + c->off(p + ".b_ih"), sR, va, vb));
-      }
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
+      {
+        const float* Wih = rin + c->off(p + ".W_ih");
+        NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
+        // bf16 precision: both operands as row-major bf16 copies (the layer below wrote its
+        // h in bf16; the layer-0 input and W_ih are rounded here, the input also transposed
+        // for the weight-gradient GEMM)
+        if (fused_b && ntc && width % 8 == 0) {
+          role = HPSGD_ROLE_OTHER;
+          const long s_xb = 2 * (long)c->xb.stride, s_wb2 = 2 * (long)c->wihb.stride;
+          if (l > 0) {
+            va = NtView{(const __bf16*)reg(c->hb) + (size_t)B * H, 1, H, 2 * (long)c->hb.stride};
+          } else if (cvt2_supported(lin, 0, width, s_lin, bfreg(c->xb), width, s_xb, bfreg(c->xT), TBp,
+                                    2 * (long)c->xT.stride, TB, width)) {
+            HIP_TRY(launch_cvt2(lin, 0, width, s_lin, bfreg(c->xb), width, s_xb, bfreg(c->xT), TBp,
+                                2 * (long)c->xT.stride, TB, width, groups, s));
+            va = NtView{bfreg(c->xb), 1, width, s_xb};
+            xT_ready = true;
+          }
+          if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, nullptr, 0, 0, 3 * H, width)) {
+            HIP_TRY(launch_cvt2(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, nullptr, 0, 0, 3 * H, width,
+                                groups, s));
+            vb = NtView{bfreg(c->wihb), 1, width, s_wb2};
+          }
+        }
+        role = HPSGD_ROLE_GEMM_INPUT;
+        TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
+                  EPI_BIAS, rin + c->off(p + ".b_ih"), sR, va, vb));
+      }
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
       // not use) and of h
       void* wb = reg(c->wt);
@@ -410,49 +439,90 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const int nrows = lm ? TB : B;
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
     const size_t oW = c->off("head.W"), ob = c->off("head.b");
-    role = HPSGD_ROLE_GEMM_HEAD;
-    {
-      const NtView va{feats, 0, H, s_top}, vb{rin + oW, 0, H, sR};
+    const long nrp = (long)round_up(nrows, 8), clp = (long)round_up(classes, 8);
+    const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
+    const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
+    // bf16 precision with every head operand available as bf16: h of the top layer (written
+    // by its step kernels), head.W rounded once (row-major and transposed in one pass), the
+    // logit gradient emitted in bf16 by the loss kernel and transposed from there
+    const bool headb =
+        ntc && gru_fused_bf16_supported(H) && classes % 8 == 0 &&
+        cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
+        softmax_ce_bf16_supported(logits, s_log, bfreg(c->dlogb), clp, s_dlb, classes) &&
+        cvt2_supported(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes);
+    if (headb) {
+      role = HPSGD_ROLE_OTHER;
+      HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
+                          groups, s));
+      const long s_hb = 2 * (long)c->hb.stride;
+      const NtView va{(const __bf16*)reg(c->hb) + (size_t)(lm ? B : T * B) * H, 1, H, s_hb};
+      const NtView vb{bfreg(c->wob), 1, H, s_wob};
+      role = HPSGD_ROLE_GEMM_HEAD;
       TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
                 s_log, EPI_BIAS, rin + ob, sR, va, vb));
-    }
-    role = HPSGD_ROLE_LOSS;
-    HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
-                              classes, groups, s));
-    if (loss_out)
-      HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
-    // ---- backward: head
-    // bf16 precision: transposed bf16 copies (contraction-contiguous operands for the NT kernel)
-    const long nrp = (long)round_up(nrows, 8), clp = (long)round_up(classes, 8);
-    if (ntc) {
+      role = HPSGD_ROLE_LOSS;
+      HIP_TRY(launch_softmax_ce_bf16(logits, s_log, y, nrows, bfreg(c->dlogb), clp, s_dlb, rowloss,
+                                     (long)c->rowloss.stride, reg(c->rowstat), (long)c->rowstat.stride, nrows,
+                                     classes, groups, s));
+      if (loss_out)
+        HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
       role = HPSGD_ROLE_OTHER;
-      if (!gru_fused_bf16_supported(H))  // else written by the forward step kernels
-        for (int l = 0; l < L; ++l)      // hs^T of every layer: [H][(T+1)B]
-          HIP_TRY(launch_cvt_bf16(reg(c->hs[l]), H, (long)c->hs[l].stride, bfreg(c->hsT[l]), TB1p,
-                                  2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
-      HIP_TRY(launch_cvt_bf16(logits, classes, s_log, bfreg(c->dlogT), nrp, 2 * (long)c->dlogT.stride, nrows,
-                              classes, true, groups, s));
-      HIP_TRY(launch_cvt_bf16(rin + oW, H, sR, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
-                              groups, s));
-    }
-    role = HPSGD_ROLE_GEMM_HEAD;
-    {
-      NtView va, vb, vw;
-      if (ntc) {
-        va = NtView{bfreg(c->dlogT), 1, nrp, 2 * (long)c->dlogT.stride};
-        vb = NtView{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
-        vw = NtView{bfreg(c->woT), 1, clp, 2 * (long)c->woT.stride};
-      }
+      HIP_TRY(launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows,
+                          classes, groups, s));
+      role = HPSGD_ROLE_GEMM_HEAD;
+      const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
+      const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
       TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW, H,
-                sG, EPI_STORE, nullptr, 0, va, vb));
-      HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
-      const NtView vl{logits, 0, classes, s_log};
-      if (lm) {
-        TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H, s_dx,
-                  EPI_STORE, nullptr, 0, vl, vw));
-      } else {
-        TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
-                  EPI_STORE, nullptr, 0, vl, vw));
+                sG, EPI_STORE, nullptr, 0, vdT, vhT));
+      HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
+                                    grad + ob, sG, nrows, classes, groups, s));
+      const NtView vdl{bfreg(c->dlogb), 1, clp, s_dlb}, vwT{bfreg(c->woT), 1, clp, s_woT};
+      TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
+                lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
+    } else {
+      role = HPSGD_ROLE_GEMM_HEAD;
+      {
+        const NtView va{feats, 0, H, s_top}, vb{rin + oW, 0, H, sR};
+        TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
+                  s_log, EPI_BIAS, rin + ob, sR, va, vb));
+      }
+      role = HPSGD_ROLE_LOSS;
+      HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
+                                classes, groups, s));
+      if (loss_out)
+        HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
+      // ---- backward: head
+      // bf16 precision: transposed bf16 copies (contraction-contiguous operands for the NT kernel)
+      if (ntc) {
+        role = HPSGD_ROLE_OTHER;
+        if (!gru_fused_bf16_supported(H))  // else written by the forward step kernels
+          for (int l = 0; l < L; ++l)      // hs^T of every layer: [H][(T+1)B]
+            HIP_TRY(launch_cvt_bf16(reg(c->hs[l]), H, (long)c->hs[l].stride, bfreg(c->hsT[l]), TB1p,
+                                    2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
+        HIP_TRY(launch_cvt_bf16(logits, classes, s_log, bfreg(c->dlogT), nrp, 2 * (long)c->dlogT.stride, nrows,
+                                classes, true, groups, s));
+        HIP_TRY(launch_cvt_bf16(rin + oW, H, sR, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
+                                groups, s));
+      }
+      role = HPSGD_ROLE_GEMM_HEAD;
+      {
+        NtView va, vb, vw;
+        if (ntc) {
+          va = NtView{bfreg(c->dlogT), 1, nrp, 2 * (long)c->dlogT.stride};
+          vb = NtView{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
+          vw = NtView{bfreg(c->woT), 1, clp, 2 * (long)c->woT.stride};
+        }
+        TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW, H,
+                  sG, EPI_STORE, nullptr, 0, va, vb));
+        HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
+        const NtView vl{logits, 0, classes, s_log};
+        if (lm) {
+          TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H, s_dx,
+                    EPI_STORE, nullptr, 0, vl, vw));
+        } else {
+          TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
+                    EPI_STORE, nullptr, 0, vl, vw));
+        }
       }
     }
     const float* above = nullptr;
@@ -578,8 +648,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (l > 0) {
           v_xT = NtView{bfreg(c->hsT[l - 1]) + B, 1, TB1p, 2 * (long)c->hsT[l - 1].stride};
         } else {
-          HIP_TRY(launch_cvt_bf16(layer_in, win, s_layer_in, bfreg(c->xT), TBp, 2 * (long)c->xT.stride, TB, win,
-                                  true, groups, s));
+          if (!xT_ready)
+            HIP_TRY(launch_cvt_bf16(layer_in, win, s_layer_in, bfreg(c->xT), TBp, 2 * (long)c->xT.stride, TB,
+                                    win, true, groups, s));
           v_xT = NtView{bfreg(c->xT), 1, TBp, 2 * (long)c->xT.stride};
         }
         if (need_dx) {

@@ -92,6 +92,26 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
 // ld_out is the row pitch of out, strides of out in bf16 elements
 hipError_t launch_cvt_bf16(const float* in, long ld_in, long s_in, void* out, long ld_out, long s_out,
                            int R, int C, bool transpose, int groups, hipStream_t s);
+// in (fp32, or bf16 when in_bf16) R x C -> out_p = bf16 rounding (nullable), out_t = its
+// transpose (nullable), one read of `in`; strides of each buffer in its own elements
+bool cvt2_supported(const void* in, int in_bf16, long ld_in, long s_in, const void* out_p, long ld_p,
+                    long s_p, const void* out_t, long ld_t, long s_t, int R, int C);
+hipError_t launch_cvt2(const void* in, int in_bf16, long ld_in, long s_in, void* out_p, long ld_p, long s_p,
+                       void* out_t, long ld_t, long s_t, int R, int C, int groups, hipStream_t s);
+// mean softmax-CE whose logit gradient is written rounded to bf16 (row pitch ld_d); logits intact
+bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* dlog, long ld_d, long s_d,
+                               int C);
+// rowstat: per row (max logit, 1 / sum of exponentials), two floats (group stride s_rowstat floats, even)
+hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
+                                  long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
+                                  long s_rowstat, int N, int C, int groups, hipStream_t s);
+// out[c] = mean over rows of (softmax - onehot), from the logits and the rows' rowstat pairs
+hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
+                                 const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
+                                 hipStream_t s);
+// out[r] = sum_c in[r][c], in bf16 (R x C, row pitch ld), fp32 accumulation
+hipError_t launch_rowsum_bf16(const void* in, long ld, long s_in, float* out, long s_out, int R, int C,
+                              int groups, hipStream_t s);
 // bf16 GEMM with both operands unit-stride along the contraction (gemm_bf16_nt.hip)
 bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, int Kd);
 hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,

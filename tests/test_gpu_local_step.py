@@ -35,6 +35,8 @@ BF16 = {
     "lm_fused_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=9, K=2),
     "lm_nt_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=8, K=2),
     "lm_nt_bf16_tiles": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=72, hidden=160, seq_len=19, batch=16, K=2),
+    "lm_nt_bf16_v2048": wl.scaled(wl.CONFIGS["gru_lm"], vocab=2048, embed=32, hidden=64, seq_len=3, batch=8, K=2),
+    "cls_nt_bf16_c16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=40, hidden=96, classes=16, seq_len=3, batch=24, K=2),
     "cls_nt_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", layers=2, input=64, hidden=160, seq_len=4, batch=72, K=2),
     "gru_cls_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=64, hidden=160, seq_len=4, batch=70, K=2),
     "mlp_bf16": wl.scaled(wl.CONFIGS["mlp"], prec="bf16", dims=[200, 300, 140, 10], batch=130, K=2),
