@@ -41,6 +41,7 @@ struct hpsgd_ctx {
   Region xb, wihb, wob, dlogb;  // row-major bf16 copies: layer-0 input, W_ih, head.W, dlogits
   Region rowstat;               // per logits row: (max, 1 / sum of exponentials)
   std::vector<Region> hsT;
+  std::vector<Region> whhT, wihTl;  // per layer: transposed bf16 W_hh and W_ih, made in the forward pass
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
@@ -125,7 +126,11 @@ int build_layout(hpsgd_ctx* c) {
       c->dgxT = c->alloc(3 * H * TBp / 2);
       c->dghT = c->alloc(3 * H * TBp / 2);
       c->xT = c->alloc(win0 * TBp / 2);
-      for (int l = 0; l < d.layers; ++l) c->hsT.push_back(c->alloc(H * TB1p / 2));
+      for (int l = 0; l < d.layers; ++l) {
+        c->hsT.push_back(c->alloc(H * TB1p / 2));
+        c->whhT.push_back(c->alloc((3 * H * H + 1) / 2));
+        c->wihTl.push_back(c->alloc(((l == 0 ? win0 : H) * 3 * H + 1) / 2));
+      }
       const size_t nr = lm ? TB : (size_t)d.batch;
       c->dlogT = c->alloc((size_t)classes * round_up(nr, 8) / 2);
       c->wihT = c->alloc(wmax * 3 * H / 2);
@@ -335,6 +340,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
     auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
     bool xT_ready = false;  // the transposed bf16 layer-0 input was made in the forward pass
+    // per layer: the transposed bf16 W_hh / W_ih were made in the forward pass, in the same
+    // read as the row-major copies
+    bool whhT_ready[16] = {false}, wihT_ready[16] = {false};
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -376,10 +384,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
             va = NtView{bfreg(c->xb), 1, width, s_xb};
             xT_ready = true;
           }
-          if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, nullptr, 0, 0, 3 * H, width)) {
-            HIP_TRY(launch_cvt2(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, nullptr, 0, 0, 3 * H, width,
+          const bool need_T = l > 0 || lm;  // the input gradient of this layer is needed
+          __bf16* wT = need_T ? bfreg(c->wihTl[l]) : nullptr;
+          const long s_wT = 2 * (long)c->wihTl[l].stride;
+          if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width)) {
+            HIP_TRY(launch_cvt2(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width,
                                 groups, s));
             vb = NtView{bfreg(c->wihb), 1, width, s_wb2};
+            wihT_ready[l] = need_T;
           }
         }
         role = HPSGD_ROLE_GEMM_INPUT;
@@ -396,7 +408,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_hT = hT ? 2 * (long)c->hsT[l].stride : 0;
       if (fused_b) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
+        const long s_whT = 2 * (long)c->whhT[l].stride;
+        if (cvt2_supported(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H)) {
+          HIP_TRY(launch_cvt2(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H, groups, s));
+          whhT_ready[l] = true;
+        } else {
+          HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
+        }
         HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
         if (hT)  // h_0 = 0: the first B columns of the transposed copy
           HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
@@ -564,7 +582,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
       }
-      if (fused_b) {
+      const void* wtb = wt;   // bf16 W_hh^T of this layer
+      long s_wtb = 2 * s_wt;
+      if (fused_b && whhT_ready[l]) {
+        wtb = bfreg(c->whhT[l]);
+        s_wtb = 2 * (long)c->whhT[l].stride;
+      } else if (fused_b) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
       }
@@ -602,7 +625,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         const float* above_t = above ? above + (size_t)t * B * H : nullptr;
         if (fused_b) {
           role = HPSGD_ROLE_GEMM_REC_BWD;
-          HIP_TRY(launch_gru_bwd_step_bf16(wt, 2 * s_wt, t + 1 < T ? dghb + (size_t)(t + 1) * B * 3 * H : nullptr,
+          HIP_TRY(launch_gru_bwd_step_bf16(wtb, s_wtb, t + 1 < T ? dghb + (size_t)(t + 1) * B * 3 * H : nullptr,
                                            dghb + (size_t)t * B * 3 * H, s_dgb, D, s_D, above_t, s_dx,
                                            sv + (size_t)t * B * 4 * H, s_sv, hs + (size_t)t * B * H, s_hs,
                                            dgx + (size_t)t * B * 3 * H, dgh + (size_t)t * B * 3 * H, s_gx,
@@ -653,7 +676,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                     win, true, groups, s));
           v_xT = NtView{bfreg(c->xT), 1, TBp, 2 * (long)c->xT.stride};
         }
-        if (need_dx) {
+        if (need_dx && wihT_ready[l]) {
+          v_wihT = NtView{bfreg(c->wihTl[l]), 1, 3 * H, 2 * (long)c->wihTl[l].stride};
+        } else if (need_dx) {
           HIP_TRY(launch_cvt_bf16(Wih, win, sR, bfreg(c->wihT), 3 * H, 2 * (long)c->wihT.stride, 3 * H, win, true,
                                   groups, s));
           v_wihT = NtView{bfreg(c->wihT), 1, 3 * H, 2 * (long)c->wihT.stride};
