@@ -72,10 +72,14 @@ struct GemmNtDesc {
   const void* B; long ldb; long strideB;
   float* C; long ldc; long strideC;
   const float* bias; long strideBias;      // per column n, nullable
+  const float* win; long strideWin;        // nullable; else C = win - lr * acc (win has C's layout, may be C)
+  float lr;
   int M, N, Kd, groups;
 };
 
-template <typename TA, typename TB>
+// COMMIT: the epilogue is C = win - lr * acc; the tile of win is requested before the
+// contraction starts, so that the epilogue does not wait for it.
+template <typename TA, typename TB, bool COMMIT>
 __global__ void __launch_bounds__(NTHREADS, 2)
 gemm_bf16_nt_kernel(GemmNtDesc d) {
   constexpr int UPT = NBM * (NBK / 8) / NTHREADS;  // 8-element units per thread per operand (4)
@@ -151,7 +155,6 @@ gemm_bf16_nt_kernel(GemmNtDesc d) {
     for (int j = 0; j < 2; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
   auto compute = [&](int buf) {
 #pragma unroll
     for (int kk = 0; kk < NBK; kk += 16) {
@@ -191,20 +194,64 @@ gemm_bf16_nt_kernel(GemmNtDesc d) {
     __syncthreads();
   }
 
+  // Epilogue through LDS (the operand buffers are free after the last barrier): the
+  // accumulators are laid out as the 128 x 128 tile, then every wave instruction moves two
+  // whole 512-byte row segments, so the stores (and the loads of W in the commit form, all
+  // requested before the first is used) are fully coalesced 16-byte accesses.
   float* C = d.C + (long)g * d.strideC;
   const float* bias = d.bias ? d.bias + (long)g * d.strideBias : nullptr;
+  float* sC = reinterpret_cast<float*>(nt_smem);
+  constexpr int CP = NBN + 4;  // pitch in floats
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int col = n0 + wn * 64 + j * 32 + lrow;
-    if (col >= d.N) continue;
-    const float bv = bias ? bias[col] : 0.f;
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * 64 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-        if (row < d.M) C[(long)row * d.ldc + col] = acc[i][j][v] + bv;
+      for (int v = 0; v < 16; ++v)
+        sC[(wm * 64 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + wn * 64 + j * 32 + lrow] = acc[i][j][v];
+  __syncthreads();
+  const int c4 = (tid & 31) << 2, rbase = tid >> 5;
+  const int col = n0 + c4;
+  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
+                   (!COMMIT || (((uintptr_t)d.win & 15) == 0 && (d.strideWin & 3) == 0));
+  if (vec && col + 3 < d.N) {
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!COMMIT && bias) bv = make_float4(bias[col], bias[col + 1], bias[col + 2], bias[col + 3]);
+    float4 w[COMMIT ? 16 : 1];
+    if (COMMIT) {
+      const float* W = d.win + (long)g * d.strideWin;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const int row = min(m0 + rbase + 8 * p, d.M - 1);  // clamped: not stored when outside
+        w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
       }
+    }
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      const int rl = rbase + 8 * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      const float4 a = *reinterpret_cast<const float4*>(&sC[rl * CP + c4]);
+      float4 o;
+      if (COMMIT) {
+        const float4 wv = w[COMMIT ? p : 0];
+        o = make_float4(wv.x - d.lr * a.x, wv.y - d.lr * a.y, wv.z - d.lr * a.z, wv.w - d.lr * a.w);
+      } else {
+        o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
+      }
+      *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+    }
+  } else {
+    const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
+    for (int p = 0; p < 16; ++p) {
+      const int rl = rbase + 8 * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      for (int e = 0; e < 4; ++e) {
+        if (col + e >= d.N) break;
+        const long off = (long)row * d.ldc + col + e;
+        const float a = sC[rl * CP + c4 + e];
+        C[off] = COMMIT ? W[off] - d.lr * a : a + (bias ? bias[col + e] : 0.f);
+      }
+    }
   }
 }
 
@@ -219,13 +266,15 @@ bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, in
 
 hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
                                long ldb, long sB, float* C, long ldc, long sC, const float* bias,
-                               long sBias, int M, int N, int Kd, int groups, hipStream_t s) {
+                               long sBias, const float* win, long sWin, float lr, int M, int N, int Kd,
+                               int groups, hipStream_t s) {
   if (M <= 0 || N <= 0 || groups <= 0) return hipSuccess;
   GemmNtDesc d;
   d.A = A; d.lda = lda; d.strideA = sA;
   d.B = B; d.ldb = ldb; d.strideB = sB;
   d.C = C; d.ldc = ldc; d.strideC = sC;
   d.bias = bias; d.strideBias = sBias;
+  d.win = win; d.strideWin = sWin; d.lr = lr;
   d.M = M; d.N = N; d.Kd = Kd; d.groups = groups;
   if (!gemm_bf16_nt_supported(A, a_bf16, lda, sA, Kd) || !gemm_bf16_nt_supported(B, b_bf16, ldb, sB, Kd))
     return hipErrorInvalidValue;
@@ -234,22 +283,28 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
   dim3 grid(8 * ((ts + 7) / 8) * tf * groups);  // see the tile order in the kernel
   dim3 block(NTHREADS);
   constexpr size_t smem = (size_t)2 * (NBM + NBN) * NPITCH * sizeof(__bf16);  // 72 KB: above the static limit
-#define HPSGD_NT(TA, TB)                                                                          \
+#define HPSGD_NT1(TA, TB, CM)                                                                     \
   do {                                                                                            \
     static bool ready = false; /* per instantiation: allow the large dynamic LDS allocation */    \
     if (!ready) {                                                                                 \
-      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel<TA, TB>,                \
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_nt_kernel<TA, TB, CM>,            \
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);  \
       if (e != hipSuccess) return e;                                                              \
       ready = true;                                                                               \
     }                                                                                             \
-    hipLaunchKernelGGL((gemm_bf16_nt_kernel<TA, TB>), grid, block, smem, s, d);       \
+    hipLaunchKernelGGL((gemm_bf16_nt_kernel<TA, TB, CM>), grid, block, smem, s, d);               \
+  } while (0)
+#define HPSGD_NT(TA, TB)                \
+  do {                                  \
+    if (win) HPSGD_NT1(TA, TB, true);   \
+    else HPSGD_NT1(TA, TB, false);      \
   } while (0)
   if (a_bf16 && b_bf16) HPSGD_NT(__bf16, __bf16);
   else if (a_bf16) HPSGD_NT(__bf16, float);
   else if (b_bf16) HPSGD_NT(float, __bf16);
   else HPSGD_NT(float, float);
 #undef HPSGD_NT
+#undef HPSGD_NT1
   return hipGetLastError();
 }
 

@@ -187,6 +187,7 @@ gemm_f32_kernel(GemmDesc d, int vecA, int vecB) {
           case EPI_BIAS_RELU: val = fmaxf(val + bias, 0.f); break;
           case EPI_ACCUM: val += C[off]; break;
           case EPI_RELU_MASK: val = aux[off] > 0.f ? val : 0.f; break;
+          case EPI_COMMIT: val = aux[off] - d.alpha * val; break;
           default: break;
         }
         C[off] = val;

@@ -79,7 +79,9 @@ struct FastOperand {
   }
 };
 
-template <int BM, int BN, bool TA, bool TB>
+// COMMIT: the epilogue is C = W - alpha * acc (EPI_COMMIT); the tile of W is requested before
+// the contraction starts, so that the epilogue does not wait for it.
+template <int BM, int BN, bool TA, bool TB, bool COMMIT>
 __global__ void __launch_bounds__(FTHREADS)
 gemm_f32_fast_kernel(GemmDesc d) {
   using OpA = FastOperand<BM, !TA>;   // A is unit-stride along k when stored [M][Kd]
@@ -107,6 +109,22 @@ gemm_f32_fast_kernel(GemmDesc d) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  floatx16 wv[COMMIT ? TM : 1][COMMIT ? TN : 1];
+  if (COMMIT) {
+    const float* W = d.aux + (long)g * d.strideAux;
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+      const int col = n0 + wn * (BN / 2) + j * 32 + lrow;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
+          wv[COMMIT ? i : 0][COMMIT ? j : 0][v] =
+              W[(long)min(row, d.M - 1) * d.ldc + min(col, d.N - 1)];  // clamped: never stored when outside
+        }
+    }
+  }
 
   auto compute = [&](int buf) {
 #pragma unroll
@@ -169,12 +187,16 @@ gemm_f32_fast_kernel(GemmDesc d) {
         if (row >= d.M) continue;
         const long off = (long)row * d.ldc + col;
         float val = acc[i][j][v];
-        switch (d.epilogue) {
-          case EPI_BIAS: val += bias; break;
-          case EPI_BIAS_RELU: val = fmaxf(val + bias, 0.f); break;
-          case EPI_ACCUM: val += C[off]; break;
-          case EPI_RELU_MASK: val = aux[off] > 0.f ? val : 0.f; break;
-          default: break;
+        if (COMMIT) {
+          val = wv[COMMIT ? i : 0][COMMIT ? j : 0][v] - d.alpha * val;
+        } else {
+          switch (d.epilogue) {
+            case EPI_BIAS: val += bias; break;
+            case EPI_BIAS_RELU: val = fmaxf(val + bias, 0.f); break;
+            case EPI_ACCUM: val += C[off]; break;
+            case EPI_RELU_MASK: val = aux[off] > 0.f ? val : 0.f; break;
+            default: break;
+          }
         }
         C[off] = val;
       }
@@ -182,29 +204,35 @@ gemm_f32_fast_kernel(GemmDesc d) {
   }
 }
 
-template <int BM, int BN, bool TA, bool TB>
+template <int BM, int BN, bool TA, bool TB, bool COMMIT>
 static hipError_t launch_fast_cfg(const GemmDesc& d, hipStream_t s) {
   using OpA = FastOperand<BM, !TA>;
   using OpB = FastOperand<BN, TB>;
   constexpr size_t smem = (size_t)2 * (OpA::LDS_FLOATS + OpB::LDS_FLOATS) * sizeof(float);
   static bool ready = false;  // per instantiation: allow dynamic LDS above 64 KB
   if (!ready) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_f32_fast_kernel<BM, BN, TA, TB>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_f32_fast_kernel<BM, BN, TA, TB, COMMIT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     ready = true;
   }
   dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, d.groups);
-  hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB>), grid, dim3(FTHREADS), smem, s, d);
+  hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB, COMMIT>), grid, dim3(FTHREADS), smem, s, d);
   return hipGetLastError();
+}
+
+template <int BM, int BN, bool COMMIT>
+static hipError_t launch_fast_layout2(const GemmDesc& d, hipStream_t s) {
+  if (!d.transA && d.transB) return launch_fast_cfg<BM, BN, false, true, COMMIT>(d, s);
+  if (!d.transA && !d.transB) return launch_fast_cfg<BM, BN, false, false, COMMIT>(d, s);
+  if (d.transA && !d.transB) return launch_fast_cfg<BM, BN, true, false, COMMIT>(d, s);
+  return launch_fast_cfg<BM, BN, true, true, COMMIT>(d, s);
 }
 
 template <int BM, int BN>
 static hipError_t launch_fast_layout(const GemmDesc& d, hipStream_t s) {
-  if (!d.transA && d.transB) return launch_fast_cfg<BM, BN, false, true>(d, s);
-  if (!d.transA && !d.transB) return launch_fast_cfg<BM, BN, false, false>(d, s);
-  if (d.transA && !d.transB) return launch_fast_cfg<BM, BN, true, false>(d, s);
-  return launch_fast_cfg<BM, BN, true, true>(d, s);
+  return d.epilogue == EPI_COMMIT ? launch_fast_layout2<BM, BN, true>(d, s)
+                                  : launch_fast_layout2<BM, BN, false>(d, s);
 }
 
 // Returns hipErrorNotSupported (nothing launched) when an operand does not allow 16-byte loads

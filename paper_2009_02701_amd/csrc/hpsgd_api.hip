@@ -44,6 +44,7 @@ struct hpsgd_ctx {
   std::vector<Region> whhT, wihTl;  // per layer: transposed bf16 W_hh and W_ih, made in the forward pass
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
+  std::vector<Region> dact;     // per MLP hidden layer: gradient w.r.t. its output
   // optional per-role kernel timing (benchmarks): event pairs recorded around launches
   // optional second stream for work that can run beside the recurrence, and the two events
   // that order it against the caller's stream
@@ -159,6 +160,7 @@ int build_layout(hpsgd_ctx* c) {
     }
     c->grad = c->alloc(c->P);
     for (int i = 1; i < d.n_mlp_dims; ++i) c->act.push_back(c->alloc((size_t)d.batch * d.mlp_dims[i]));
+    for (int i = 1; i + 1 < d.n_mlp_dims; ++i) c->dact.push_back(c->alloc((size_t)d.batch * d.mlp_dims[i]));
     c->rowloss = c->alloc(d.batch);
   } else {
     return HPSGD_EINVAL;
@@ -214,9 +216,10 @@ struct TimerScope {
 // GEMM helper: C = op(A) op(B) for `groups` workers.
 int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda,
          long sA, int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC,
-         int epi, const float* aux, long sAux, int background = 0) {
+         int epi, const float* aux, long sAux, int background = 0, float alpha = 0.f) {
   GemmDesc g;
   g.background = background;
+  g.alpha = alpha;
   g.A = A; g.lda = lda; g.strideA = sA; g.transA = tA;
   g.B = B; g.ldb = ldb; g.strideB = sB; g.transB = tB;
   g.C = C; g.ldc = ldc; g.strideC = sC;
@@ -237,16 +240,17 @@ struct NtView {
 // view (C = a b^T), otherwise the generic kernel on the original fp32 operands.
 int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda, long sA,
           int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC, int epi,
-          const float* aux, long sAux, const NtView& a, const NtView& b) {
-  if (bf16 && a.p && b.p && (epi == EPI_STORE || epi == EPI_BIAS) &&
+          const float* aux, long sAux, const NtView& a, const NtView& b, float alpha = 0.f) {
+  if (bf16 && a.p && b.p && (epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_COMMIT) &&
       gemm_bf16_nt_supported(a.p, a.bf16, a.ld, a.stride, Kd) &&
       gemm_bf16_nt_supported(b.p, b.bf16, b.ld, b.stride, Kd) && ((uintptr_t)C & 3) == 0) {
     return launch_gemm_bf16_nt(a.p, a.bf16, a.ld, a.stride, b.p, b.bf16, b.ld, b.stride, C, ldc, sC,
-                               epi == EPI_BIAS ? aux : nullptr, sAux, M, N, Kd, groups, s) == hipSuccess
+                               epi == EPI_BIAS ? aux : nullptr, sAux, epi == EPI_COMMIT ? aux : nullptr, sAux,
+                               alpha, M, N, Kd, groups, s) == hipSuccess
                ? HPSGD_OK
                : HPSGD_EHIP;
   }
-  return gemm(s, groups, bf16, M, N, Kd, A, lda, sA, tA, B, ldb, sB, tB, C, ldc, sC, epi, aux, sAux);
+  return gemm(s, groups, bf16, M, N, Kd, A, lda, sA, tA, B, ldb, sB, tB, C, ldc, sC, epi, aux, sAux, 0, alpha);
 }
 
 #define TRY(expr)                    \
@@ -273,6 +277,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
+  // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
+  // (replica_out = replica_in - lr * dW, no gradient buffer round trip); every other
+  // parameter goes through the gradient buffer and the commit kernel at the end.  A matrix
+  // is only updated after the last kernel that reads it (the input-gradient GEMM of its
+  // layer) has been issued, so the step may run in place.
+  std::vector<char> fused_commit(c->entries.size(), 0);
+  auto commit_view = [&](const std::string& name, const float*& w_in, float*& w_out) {
+    const size_t o = c->off(name);
+    w_in = rin + o;
+    w_out = rout + o;
+    fused_commit[c->find(name)] = 1;
+  };
 
   if (d.kind == HPSGD_MLP) {
     const int L = d.n_mlp_dims - 1;
@@ -302,21 +318,25 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const std::string p = "fc" + std::to_string(i);
       const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;
       const long s_prev = i > 0 ? (long)c->act[i - 1].stride : (long)B * dims[0];
-      const long s_delta = (long)c->act[i].stride;
-      // dW = delta^T a_prev
+      const long s_delta = i == L - 1 ? (long)c->act[i].stride : (long)c->dact[i].stride;
       role = HPSGD_ROLE_MLP_BWD;
+      float* dprev = nullptr;
+      if (i > 0) {
+        // delta_prev = (delta W) * [a_prev > 0]: before W is updated
+        dprev = reg(c->dact[i - 1]);
+        TRY(gemm(s, groups, bf, B, dims[i], dims[i + 1], delta, dims[i + 1], s_delta, 0,
+                 rin + c->off(p + ".W"), dims[i], sR, 0, dprev, dims[i], (long)c->dact[i - 1].stride,
+                 EPI_RELU_MASK, a_prev, s_prev));
+      }
+      // W' = W - lr * delta^T a_prev
+      const float* w_in;
+      float* w_out;
+      commit_view(p + ".W", w_in, w_out);
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
-               s_prev, 0, grad + c->off(p + ".W"), dims[i], sG, EPI_STORE, nullptr, 0));
+               s_prev, 0, w_out, dims[i], sR, EPI_COMMIT, w_in, sR, 0, lr));
       HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + c->off(p + ".b"), sG, B, dims[i + 1],
                             groups, s));
-      if (i > 0) {
-        // delta_prev = (delta W) * [a_prev > 0], written over a_prev
-        float* dprev = reg(c->act[i - 1]);
-        TRY(gemm(s, groups, bf, B, dims[i], dims[i + 1], delta, dims[i + 1], s_delta, 0,
-                 rin + c->off(p + ".W"), dims[i], sR, 0, dprev, dims[i], s_prev, EPI_RELU_MASK, dprev,
-                 s_prev));
-        delta = dprev;
-      }
+      if (i > 0) delta = dprev;
     }
   } else {
     const bool lm = d.kind == HPSGD_GRU_LM;
@@ -488,15 +508,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows,
                           classes, groups, s));
       role = HPSGD_ROLE_GEMM_HEAD;
-      const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
-      const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
-      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW, H,
-                sG, EPI_STORE, nullptr, 0, vdT, vhT));
-      HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
-                                    grad + ob, sG, nrows, classes, groups, s));
       const NtView vdl{bfreg(c->dlogb), 1, clp, s_dlb}, vwT{bfreg(c->woT), 1, clp, s_woT};
       TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
                 lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
+      const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
+      const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
+      const float* w_in;
+      float* w_out;
+      commit_view("head.W", w_in, w_out);
+      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, w_out, H, sR,
+                EPI_COMMIT, w_in, sR, vdT, vhT, lr));
+      HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
+                                    grad + ob, sG, nrows, classes, groups, s));
     } else {
       role = HPSGD_ROLE_GEMM_HEAD;
       {
@@ -530,9 +553,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           vb = NtView{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
           vw = NtView{bfreg(c->woT), 1, clp, 2 * (long)c->woT.stride};
         }
-        TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, grad + oW, H,
-                  sG, EPI_STORE, nullptr, 0, va, vb));
-        HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
         const NtView vl{logits, 0, classes, s_log};
         if (lm) {
           TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H, s_dx,
@@ -541,6 +561,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
                     EPI_STORE, nullptr, 0, vl, vw));
         }
+        const float* w_in;
+        float* w_out;
+        commit_view("head.W", w_in, w_out);
+        TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, w_out, H, sR,
+                  EPI_COMMIT, w_in, sR, va, vb, lr));
+        HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
       }
     }
     const float* above = nullptr;
@@ -684,6 +710,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           v_wihT = NtView{bfreg(c->wihT), 1, 3 * H, 2 * (long)c->wihT.stride};
         }
       }
+      role = HPSGD_ROLE_GEMM_DX;
+      if (need_dx) {  // reads W_ih: before its update
+        const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
+        TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
+                  nullptr, 0, v_dgx, v_wihT));
+        above = dx;
+      }
       role = HPSGD_ROLE_GEMM_WGRAD;
       if (NC > 1) {
         // join, then the first chunk's share on top of what the aux stream accumulated
@@ -691,20 +724,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           return HPSGD_EHIP;
         TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
       } else {
-        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
-                  grad + c->off(p + ".W_ih"), win, sG, EPI_STORE, nullptr, 0, v_dgxT, v_xT));
-        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, grad + c->off(p + ".W_hh"),
-                  H, sG, EPI_STORE, nullptr, 0, v_dghT, v_hsT));
+        const float* w_in;
+        float* w_out;
+        commit_view(p + ".W_ih", w_in, w_out);
+        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, w_out, win,
+                  sR, EPI_COMMIT, w_in, sR, v_dgxT, v_xT, lr));
+        commit_view(p + ".W_hh", w_in, w_out);
+        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, w_out, H, sR, EPI_COMMIT,
+                  w_in, sR, v_dghT, v_hsT, lr));
       }
+      role = HPSGD_ROLE_GEMM_WGRAD;
       HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
       HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
-      role = HPSGD_ROLE_GEMM_DX;
-      if (need_dx) {
-        const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
-        TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
-                  nullptr, 0, v_dgx, v_wihT));
-        above = dx;
-      }
       role = HPSGD_ROLE_OTHER;
       if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
     }
@@ -716,8 +747,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     }
   }
   // ---- commit (Alg. 2 "update replica")
+  // the parameters not updated by a GEMM epilogue: one launch per contiguous run of them
   role = HPSGD_ROLE_COMMIT;
-  HIP_TRY(launch_commit(rin, rout, rstride, grad, (size_t)sG, lr, groups, c->P, s));
+  for (size_t e = 0; e < c->entries.size();) {
+    if (fused_commit[e]) {
+      ++e;
+      continue;
+    }
+    const size_t lo = c->entries[e].offset;
+    while (e < c->entries.size() && !fused_commit[e]) ++e;
+    const size_t hi = e < c->entries.size() ? c->entries[e].offset : c->P;
+    HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
+  }
   return HPSGD_OK;
 }
 

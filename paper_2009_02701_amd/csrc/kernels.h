@@ -38,7 +38,9 @@ enum Epilogue : int {
   EPI_BIAS = 1,       // C = acc + bias[n]
   EPI_BIAS_RELU = 2,  // C = max(acc + bias[n], 0)
   EPI_ACCUM = 3,      // C += acc
-  EPI_RELU_MASK = 4   // C = acc * (mask[m,n] > 0)      (mask has C's layout)
+  EPI_RELU_MASK = 4,  // C = acc * (mask[m,n] > 0)      (mask has C's layout)
+  EPI_COMMIT = 5      // C = W[m,n] - alpha * acc       (W = aux, C's layout; C may be W itself):
+                      // the SGD update of a weight matrix applied where its gradient is produced
 };
 
 struct GemmDesc {
@@ -50,6 +52,7 @@ struct GemmDesc {
   int M, N, Kd, groups;
   int epilogue;
   int bf16;                                            // round operands to bf16, use the bf16 MFMA
+  float alpha;                                         // EPI_COMMIT: the learning rate
   int background;                                      // runs beside latency-critical kernels: keep the
                                                        // LDS footprint small so both fit on a CU
 };
@@ -116,7 +119,8 @@ hipError_t launch_rowsum_bf16(const void* in, long ld, long s_in, float* out, lo
 bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, int Kd);
 hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
                                long ldb, long sB, float* C, long ldc, long sC, const float* bias,
-                               long sBias, int M, int N, int Kd, int groups, hipStream_t s);
+                               long sBias, const float* win, long sWin, float lr, int M, int N, int Kd,
+                               int groups, hipStream_t s);
 // out[c][r] = in[r][c], R x C per group
 hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
                             int groups, hipStream_t s);

@@ -150,9 +150,25 @@ commit_kernel(const float* in, float* out, size_t stride, const float* __restric
   }
 }
 
+// the same, one element per thread: for ranges that do not start on a 16-byte boundary
+__global__ void __launch_bounds__(kThreads)
+commit_scalar_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+                     size_t grad_stride, float lr, size_t P) {
+  const size_t k = blockIdx.y;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < P; i += (size_t)gridDim.x * kThreads)
+    out[k * stride + i] = in[k * stride + i] - lr * grad[k * grad_stride + i];
+}
+
 hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
+  if ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)grad) & 15) != 0 || ((stride | grad_stride) & 3) != 0) {
+    size_t blocks = (P + kThreads - 1) / kThreads;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(commit_scalar_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, out, stride,
+                       grad, grad_stride, lr, P);
+    return hipGetLastError();
+  }
   const size_t n4 = P / 4;
   const int blocks = onepass_blocks(n4);
   hipLaunchKernelGGL(commit_kernel, dim3(blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
