@@ -79,9 +79,7 @@ struct FastOperand {
   }
 };
 
-// COMMIT: the epilogue is C = W - alpha * acc (EPI_COMMIT); the tile of W is requested before
-// the contraction starts, so that the epilogue does not wait for it.
-template <int BM, int BN, bool TA, bool TB, bool COMMIT>
+template <int BM, int BN, bool TA, bool TB>
 __global__ void __launch_bounds__(FTHREADS)
 gemm_f32_fast_kernel(GemmDesc d) {
   using OpA = FastOperand<BM, !TA>;   // A is unit-stride along k when stored [M][Kd]
@@ -109,23 +107,6 @@ gemm_f32_fast_kernel(GemmDesc d) {
     for (int j = 0; j < TN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-  floatx16 wv[COMMIT ? TM : 1][COMMIT ? TN : 1];
-  if (COMMIT) {
-    const float* W = d.aux + (long)g * d.strideAux;
-#pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int col = n0 + wn * (BN / 2) + j * 32 + lrow;
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-          wv[COMMIT ? i : 0][COMMIT ? j : 0][v] =
-              W[(long)min(row, d.M - 1) * d.ldc + min(col, d.N - 1)];  // clamped: never stored when outside
-        }
-    }
-  }
-
   auto compute = [&](int buf) {
 #pragma unroll
     for (int c = 0; c < FBK / 8; ++c) {
@@ -171,32 +152,85 @@ gemm_f32_fast_kernel(GemmDesc d) {
     __syncthreads();
   }
 
+  // Epilogue through LDS (the operand buffers are free after the last barrier): the
+  // accumulators are laid out as the BM x BN tile, then every thread moves 16-byte pieces of
+  // whole rows, so the stores and the loads of the extra operand (the old C, the ReLU mask or
+  // the weights to update; all requested before the first is used) are fully coalesced.
   float* C = d.C + (long)g * d.strideC;
   const float* aux = d.aux ? d.aux + (long)g * d.strideAux : nullptr;
+  float* sC = fast_lds;
+  constexpr int CP = BN + 4;                       // pitch in floats
+  constexpr int RPP = FTHREADS / (BN / 4);         // rows per pass
+  constexpr int PASSES = BM / RPP;
+  static_assert((size_t)BM * CP <= 2 * (OpA::LDS_FLOATS + OpB::LDS_FLOATS), "epilogue tile fits the operand buffers");
 #pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int col = n0 + wn * (BN / 2) + j * 32 + lrow;
-    if (col >= d.N) continue;
-    float bias = 0.f;
-    if (d.epilogue == EPI_BIAS || d.epilogue == EPI_BIAS_RELU) bias = aux[col];
+  for (int j = 0; j < TN; ++j)
 #pragma unroll
-    for (int i = 0; i < TM; ++i) {
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = m0 + wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4);
-        if (row >= d.M) continue;
-        const long off = (long)row * d.ldc + col;
-        float val = acc[i][j][v];
-        if (COMMIT) {
-          val = wv[COMMIT ? i : 0][COMMIT ? j : 0][v] - d.alpha * val;
-        } else {
-          switch (d.epilogue) {
-            case EPI_BIAS: val += bias; break;
-            case EPI_BIAS_RELU: val = fmaxf(val + bias, 0.f); break;
-            case EPI_ACCUM: val += C[off]; break;
-            case EPI_RELU_MASK: val = aux[off] > 0.f ? val : 0.f; break;
-            default: break;
-          }
+      for (int v = 0; v < 16; ++v)
+        sC[(wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + wn * (BN / 2) + j * 32 + lrow] =
+            acc[i][j][v];
+  __syncthreads();
+  const int c4 = (tid % (BN / 4)) << 2, rbase = tid / (BN / 4);
+  const int col = n0 + c4;
+  const int epi = d.epilogue;
+  // the extra matrix operand, in C's layout
+  const float* X = epi == EPI_ACCUM ? C : (epi == EPI_RELU_MASK || epi == EPI_COMMIT) ? aux : nullptr;
+  const long xs = epi == EPI_ACCUM ? d.strideC : d.strideAux;
+  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
+                   (!X || (((uintptr_t)(epi == EPI_ACCUM ? d.C : d.aux) & 15) == 0 && (xs & 3) == 0));
+  if (vec && col + 3 < d.N) {
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (epi == EPI_BIAS || epi == EPI_BIAS_RELU) bv = make_float4(aux[col], aux[col + 1], aux[col + 2], aux[col + 3]);
+    float4 x[PASSES];
+    if (X) {
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int row = min(m0 + rbase + RPP * p, d.M - 1);  // clamped: not stored when outside
+        x[p] = *reinterpret_cast<const float4*>(X + (long)row * d.ldc + col);
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int rl = rbase + RPP * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      const float4 a = *reinterpret_cast<const float4*>(&sC[rl * CP + c4]);
+      float4 o = a;
+      switch (epi) {
+        case EPI_BIAS: o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w); break;
+        case EPI_BIAS_RELU:
+          o = make_float4(fmaxf(a.x + bv.x, 0.f), fmaxf(a.y + bv.y, 0.f), fmaxf(a.z + bv.z, 0.f),
+                          fmaxf(a.w + bv.w, 0.f));
+          break;
+        case EPI_ACCUM: o = make_float4(a.x + x[p].x, a.y + x[p].y, a.z + x[p].z, a.w + x[p].w); break;
+        case EPI_RELU_MASK:
+          o = make_float4(x[p].x > 0.f ? a.x : 0.f, x[p].y > 0.f ? a.y : 0.f, x[p].z > 0.f ? a.z : 0.f,
+                          x[p].w > 0.f ? a.w : 0.f);
+          break;
+        case EPI_COMMIT:
+          o = make_float4(x[p].x - d.alpha * a.x, x[p].y - d.alpha * a.y, x[p].z - d.alpha * a.z,
+                          x[p].w - d.alpha * a.w);
+          break;
+        default: break;
+      }
+      *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+    }
+  } else {
+    for (int p = 0; p < PASSES; ++p) {
+      const int rl = rbase + RPP * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      for (int e = 0; e < 4; ++e) {
+        if (col + e >= d.N) break;
+        const long off = (long)row * d.ldc + col + e;
+        float val = sC[rl * CP + c4 + e];
+        switch (epi) {
+          case EPI_BIAS: val += aux[col + e]; break;
+          case EPI_BIAS_RELU: val = fmaxf(val + aux[col + e], 0.f); break;
+          case EPI_ACCUM: val += C[off]; break;
+          case EPI_RELU_MASK: val = aux[off] > 0.f ? val : 0.f; break;
+          case EPI_COMMIT: val = aux[off] - d.alpha * val; break;
+          default: break;
         }
         C[off] = val;
       }
@@ -204,35 +238,29 @@ gemm_f32_fast_kernel(GemmDesc d) {
   }
 }
 
-template <int BM, int BN, bool TA, bool TB, bool COMMIT>
+template <int BM, int BN, bool TA, bool TB>
 static hipError_t launch_fast_cfg(const GemmDesc& d, hipStream_t s) {
   using OpA = FastOperand<BM, !TA>;
   using OpB = FastOperand<BN, TB>;
   constexpr size_t smem = (size_t)2 * (OpA::LDS_FLOATS + OpB::LDS_FLOATS) * sizeof(float);
   static bool ready = false;  // per instantiation: allow dynamic LDS above 64 KB
   if (!ready) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_f32_fast_kernel<BM, BN, TA, TB, COMMIT>,
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_f32_fast_kernel<BM, BN, TA, TB>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     ready = true;
   }
   dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, d.groups);
-  hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB, COMMIT>), grid, dim3(FTHREADS), smem, s, d);
+  hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB>), grid, dim3(FTHREADS), smem, s, d);
   return hipGetLastError();
-}
-
-template <int BM, int BN, bool COMMIT>
-static hipError_t launch_fast_layout2(const GemmDesc& d, hipStream_t s) {
-  if (!d.transA && d.transB) return launch_fast_cfg<BM, BN, false, true, COMMIT>(d, s);
-  if (!d.transA && !d.transB) return launch_fast_cfg<BM, BN, false, false, COMMIT>(d, s);
-  if (d.transA && !d.transB) return launch_fast_cfg<BM, BN, true, false, COMMIT>(d, s);
-  return launch_fast_cfg<BM, BN, true, true, COMMIT>(d, s);
 }
 
 template <int BM, int BN>
 static hipError_t launch_fast_layout(const GemmDesc& d, hipStream_t s) {
-  return d.epilogue == EPI_COMMIT ? launch_fast_layout2<BM, BN, true>(d, s)
-                                  : launch_fast_layout2<BM, BN, false>(d, s);
+  if (!d.transA && d.transB) return launch_fast_cfg<BM, BN, false, true>(d, s);
+  if (!d.transA && !d.transB) return launch_fast_cfg<BM, BN, false, false>(d, s);
+  if (d.transA && !d.transB) return launch_fast_cfg<BM, BN, true, false>(d, s);
+  return launch_fast_cfg<BM, BN, true, true>(d, s);
 }
 
 // Returns hipErrorNotSupported (nothing launched) when an operand does not allow 16-byte loads
