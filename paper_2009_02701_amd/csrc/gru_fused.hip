@@ -113,26 +113,35 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
   }
   const int colofs = (tid % UR) << 2;
   for (int s0 = 0; s0 < nslab; s0 += NB) {
+    // Branch-free loads (a conditional around a load makes the compiler wait for every
+    // outstanding load before the first use): rows beyond rows_valid read row 0, columns beyond
+    // KD read column 0, and such units are zeroed when they are written to LDS.
     float4 regs[NB][UPT];
+    bool cok[NB];
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb) {
       const int col = (s0 + sb) * W + colofs;
-      const bool cok = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
+      cok[sb] = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
+      const int colc = cok[sb] ? col : 0;
 #pragma unroll
-      for (int i = 0; i < UPT; ++i) regs[sb][i] = ld4_or_zero(rowp[i] + col, cok && rowok[i]);
+      for (int i = 0; i < UPT; ++i) regs[sb][i] = *reinterpret_cast<const float4*>(rowp[i] + colc);
     }
     auto sstore = [&](int sb) {
 #pragma unroll
       for (int i = 0; i < UPT; ++i) {
         const int u = tid + i * 256;
-        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + u / UR) * P + ((u % UR) << 2)]) = regs[sb][i];
+        const bool ok = cok[sb] && rowok[i];
+        const float4 v = regs[sb][i];  // (selected per component: a select between two float4
+                                       // objects would keep the whole register array in memory)
+        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + u / UR) * P + ((u % UR) << 2)]) =
+            make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
       }
     };
+    __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
     sstore(0);
     __syncthreads();
 #pragma unroll
     for (int sb = 0; sb < NB; ++sb) {
-      if (sb + 1 < NB) sstore(sb + 1);  // slabs past the end were loaded as zeros
       const int b = sb & 1;
 #pragma unroll
       for (int ci = 0; ci < NC; ++ci) {
@@ -158,19 +167,131 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
             }
           }
       }
+      // the next slab goes to the other buffer as late as possible: its global loads have
+      // had the matrix work above to arrive (slabs past the end are written as zeros).
+      // The scheduling fences keep the compiler from sinking the MFMAs below the wait for
+      // that slab's loads, which would put the matrix work behind the memory latency.
+      __builtin_amdgcn_sched_barrier(0);
+      if (sb + 1 < NB) sstore(sb + 1);
       __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
     }
   }
 }
 
+// The same contraction as a rolling pipeline: 64-word slabs, the loads of slab s+3 are issued
+// while slab s is multiplied, so the wave never sits behind a long burst of load instructions
+// (a CU accepts only ~64 bytes of vector loads per clock: issuing a workgroup's whole operand
+// set up front keeps its waves busy issuing for microseconds before the first MFMA).
+// Registers hold 4 slabs in flight; LDS holds 2 (one barrier per slab).  lds: 2*RT*68 words.
+template <int NQ, bool BF16>
+__device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wbase, long w_qstride,
+                                                    const float* __restrict__ Abase, int KD,
+                                                    int rows_valid, float* __restrict__ lds,
+                                                    floatx4 (&acc)[2][NQ]) {
+  constexpr int W = 64, RT = 16 * NQ + 32, UR = W / 4, UPT = RT * UR / 256, P = W + 4;
+  constexpr int PD = 3, RS = PD + 1;  // prefetch distance in slabs, register sets
+  static_assert(RT * UR % 256 == 0, "slab shape");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int nslab = (KD + W - 1) / W;
+  const float* rowp[UPT];
+  bool rowok[UPT];
+#pragma unroll
+  for (int i = 0; i < UPT; ++i) {
+    const int row = (tid + i * 256) / UR;
+    if (row < 16 * NQ) {
+      rowp[i] = Wbase + (row >> 4) * w_qstride + (long)(row & 15) * KD;
+      rowok[i] = true;
+    } else {
+      const int ar = row - 16 * NQ;
+      rowok[i] = ar < rows_valid;
+      rowp[i] = Abase + (long)(rowok[i] ? ar : 0) * KD;
+    }
+  }
+  const int colofs = (tid % UR) << 2;
+  float4 regs[RS][UPT];
+  bool cok[RS];
+  // branch-free (a conditional around a load makes the compiler wait for every outstanding
+  // load before the first use): a unit beyond KD (a whole slab past the end, or the ragged
+  // tail of the last one) is zeroed at the LDS store; its load still happens, from one
+  // address for all lanes (a single cache line: next to nothing of the CU's load bandwidth)
+  auto issue = [&](int set, int slab) {
+    const int col = slab * W + colofs;
+    cok[set] = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
+#pragma unroll
+    for (int i = 0; i < UPT; ++i)
+      regs[set][i] = *reinterpret_cast<const float4*>(cok[set] ? rowp[i] + col : Wbase);
+  };
+  auto sstore = [&](int set, int buf) {
+#pragma unroll
+    for (int i = 0; i < UPT; ++i) {
+      const int u = tid + i * 256;
+      const bool ok = cok[set] && rowok[i];
+      const float4 v = regs[set][i];  // (selected per component: a select between two float4
+                                      // objects would keep the whole register array in memory)
+      *reinterpret_cast<float4*>(&lds[(buf * RT + u / UR) * P + ((u % UR) << 2)]) =
+          make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
+    }
+  };
+#pragma unroll
+  for (int u = 0; u < PD; ++u) issue(u, u);
+  const int kcol = 16 * wave + 4 * lg;  // each wave takes one 16-word chunk of a slab
+  for (int s0 = 0; s0 < nslab; s0 += RS) {
+#pragma unroll
+    for (int u = 0; u < RS; ++u) {  // slab s0 + u: register set u, LDS buffer u & 1
+      const int b = u & 1;
+      // the fences keep the compiler from sinking the loads below the MFMAs or hoisting the
+      // zeroing selects of the next store (which wait for their loads) above them
+      __builtin_amdgcn_sched_barrier(0);
+      sstore(u, b);  // waits for this slab only: the later ones stay in flight
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+      issue((u + PD) % RS, s0 + u + PD);  // into the set stored one slab ago
+      float4 a[2], w[NQ];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q)
+        w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+        a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * P + kcol]);
+      if (BF16) {
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int q = 0; q < NQ; ++q) {
+            typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+            acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[rb]),
+                                                                 __builtin_bit_cast(bf16x8_t, w[q]),
+                                                                 acc[rb][q], 0, 0, 0);
+          }
+      } else {
+        // the four contraction steps outermost: consecutive MFMAs update different
+        // accumulators; every accumulator still receives its steps in order
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+#pragma unroll
+          for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+              const float av = e == 0 ? a[rb].x : e == 1 ? a[rb].y : e == 2 ? a[rb].z : a[rb].w;
+              const float wv = e == 0 ? w[q].x : e == 1 ? w[q].y : e == 2 ? w[q].z : w[q].w;
+              acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wv, acc[rb][q], 0, 0, 0);
+            }
+      }
+    }
+  }
+  __syncthreads();  // the LDS buffers may be reused by the caller
+}
+
 // Forward step: h_out = cell(gx_t, h_prev W_hh^T + b_hh, h_prev); saves r|z|n|q of the step.
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
                            const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
                            float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
                            int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 80 * SP;  // [4][6][4][64]
+  float* red = staged_lds + 2 * 80 * 68;  // [4][6][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -188,20 +309,21 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
-    const bool ok = row < B;
+    // unconditional loads from a row clamped into the batch (a select on a loaded value
+    // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
+    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
     const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
-    hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
+    for (int q = 0; q < 3; ++q) gxv[rb][q] = gxr[q * H + j];
+    hpv[rb] = hp[(long)row * H + j];
   }
   floatx4 acc[2][3];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  staged_contraction<3, 4, false>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
-                           staged_lds, acc);
+  rolling_contraction<3, false>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
+                                staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -233,8 +355,8 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   }
 }
 
-static constexpr size_t kFwdStagedLds = (2 * 80 * SP + 4 * 6 * 4 * 64) * sizeof(float);
-static constexpr size_t kBwdStagedLds = (2 * 48 * SP + 4 * 2 * 4 * 64) * sizeof(float);
+static constexpr size_t kFwdStagedLds = (2 * 80 * 68 + 4 * 6 * 4 * 64) * sizeof(float);
+static constexpr size_t kBwdStagedLds = (2 * 48 * 68 + 4 * 2 * 4 * 64) * sizeof(float);
 // bf16 variants: 64-word slabs, so that two or three workgroups fit on a CU (config 3 launches
 // two workgroups per CU; resident together they cover each other's load latency)
 static constexpr int SKB = 64;
@@ -261,14 +383,14 @@ hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep,
 // Backward step.  WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along
 // the contraction).  D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last
 // step) and dh_t * z_t on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
-__global__ void __launch_bounds__(256)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __restrict__ dgh_next,
                            long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
                            long s_above, const float* __restrict__ sv_t, long s_sv,
                            const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
                            float* __restrict__ dgh_t, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 48 * SP;  // [4][2][4][64]
+  float* red = staged_lds + 2 * 48 * 68;  // [4][2][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
@@ -279,27 +401,28 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   const int j0 = tx * FJ, r0 = ty * FR;
   const int H3 = 3 * H;
   const int j = j0 + lr;
-  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2];
+  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2], ab_[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
-    const bool ok = row < B;
+    // unconditional loads from a row clamped into the batch (a select on a loaded value
+    // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
+    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
     const long e = (long)row * H + j;
     const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
-    r_[rb] = ok ? sv[j] : 0.f;
-    z_[rb] = ok ? sv[H + j] : 0.f;
-    n_[rb] = ok ? sv[2 * H + j] : 0.f;
-    q_[rb] = ok ? sv[3 * H + j] : 0.f;
-    hp_[rb] = ok ? h_prev[g * s_hs + e] : 0.f;
-    dh_[rb] = ok ? D[g * s_D + e] : 0.f;
-    if (ok && above) dh_[rb] += above[g * s_above + e];
+    r_[rb] = sv[j];
+    z_[rb] = sv[H + j];
+    n_[rb] = sv[2 * H + j];
+    q_[rb] = sv[3 * H + j];
+    hp_[rb] = h_prev[g * s_hs + e];
+    dh_[rb] = D[g * s_D + e];
+    ab_[rb] = above ? above[g * s_above + e] : 0.f;
   }
   floatx4 acc[2][1];
   acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   acc[1][0] = acc[0][0];
   if (dgh_next)
-    staged_contraction<1, 12, false>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
-                              B - r0, staged_lds, acc);
+    rolling_contraction<1, false>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
+                                  B - r0, staged_lds, acc);
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
@@ -312,7 +435,7 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
     const float rec = (red[o] + red[o + 2 * 256]) + (red[o + 4 * 256] + red[o + 6 * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
-      const float dh = dh_[rb] + rec;
+      const float dh = (dh_[rb] + ab_[rb]) + rec;
       const float r = r_[rb], z = z_[rb], n = n_[rb], q = q_[rb];
       const float dn = dh * (1.0f - z);
       const float dz = dh * (hp_[rb] - n);
@@ -350,7 +473,7 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
 // step, h_t / dgh_t written in both precisions by the previous step's epilogue), i.e. every
 // GEMM operand is the nearest-even bf16 rounding of the fp32 value; accumulation, the cell
 // math and everything stored for later use stay fp32.
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh,
                          long s_rep, const float* __restrict__ gx_t, long s_gx,
                          const float* __restrict__ h_prev, float* __restrict__ h_out, long s_hs,
@@ -377,12 +500,13 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
   for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
-    const bool ok = row < B;
+    // unconditional loads from a row clamped into the batch (a select on a loaded value
+    // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
+    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
     const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
 #pragma unroll
-    for (int q = 0; q < 3; ++q) gxv[rb][q] = ok ? gxr[q * H + j] : 0.f;
-    hpv[rb] = ok ? hp[(long)row * H + j] : 0.f;
+    for (int q = 0; q < 3; ++q) gxv[rb][q] = gxr[q * H + j];
+    hpv[rb] = hp[(long)row * H + j];
   }
   floatx4 acc[2][3];
 #pragma unroll
@@ -390,7 +514,7 @@ gru_fwd_step_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* 
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
   // rows of bf16 pairs, addressed in 4-byte words
-  staged_contraction<3, 8, true, SKB>(reinterpret_cast<const float*>(Wb + g * s_wb + (long)j0 * H), (long)H * H / 2,
+  rolling_contraction<3, true>(reinterpret_cast<const float*>(Wb + g * s_wb + (long)j0 * H), (long)H * H / 2,
                                  reinterpret_cast<const float*>(hb_prev + g * s_hb + (long)r0 * H), H / 2,
                                  B - r0, staged_lds, acc);
 #pragma unroll
@@ -456,7 +580,7 @@ hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh
   return hipGetLastError();
 }
 
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
                          const __bf16* __restrict__ dghb_next, __bf16* __restrict__ dghb_t, long s_dgb,
                          float* __restrict__ D, long s_D, const float* __restrict__ above,
@@ -479,26 +603,27 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
   const int j0 = tx * FJ, r0 = ty * FR;
   const int H3 = 3 * H;
   const int j = j0 + lr;
-  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2];
+  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2], ab_[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
-    const bool ok = row < B;
+    // unconditional loads from a row clamped into the batch (a select on a loaded value
+    // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
+    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
     const long e = (long)row * H + j;
     const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
-    r_[rb] = ok ? sv[j] : 0.f;
-    z_[rb] = ok ? sv[H + j] : 0.f;
-    n_[rb] = ok ? sv[2 * H + j] : 0.f;
-    q_[rb] = ok ? sv[3 * H + j] : 0.f;
-    hp_[rb] = ok ? h_prev[g * s_hs + e] : 0.f;
-    dh_[rb] = ok ? D[g * s_D + e] : 0.f;
-    if (ok && above) dh_[rb] += above[g * s_above + e];
+    r_[rb] = sv[j];
+    z_[rb] = sv[H + j];
+    n_[rb] = sv[2 * H + j];
+    q_[rb] = sv[3 * H + j];
+    hp_[rb] = h_prev[g * s_hs + e];
+    dh_[rb] = D[g * s_D + e];
+    ab_[rb] = above ? above[g * s_above + e] : 0.f;
   }
   floatx4 acc[2][1];
   acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   acc[1][0] = acc[0][0];
   if (dghb_next)
-    staged_contraction<1, 12, true, SKB>(reinterpret_cast<const float*>(WTb + g * s_wt + (long)j0 * H3), 0,
+    rolling_contraction<1, true>(reinterpret_cast<const float*>(WTb + g * s_wt + (long)j0 * H3), 0,
                                     reinterpret_cast<const float*>(dghb_next + g * s_dgb + (long)r0 * H3),
                                     H3 / 2, B - r0, staged_lds, acc);
 #pragma unroll
@@ -513,7 +638,7 @@ gru_bwd_step_bf16_kernel(const __bf16* __restrict__ WTb, long s_wt,
     const float rec = (red[o] + red[o + 2 * 256]) + (red[o + 4 * 256] + red[o + 6 * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
-      const float dh = dh_[rb] + rec;
+      const float dh = (dh_[rb] + ab_[rb]) + rec;
       const float r = r_[rb], z = z_[rb], n = n_[rb], q = q_[rb];
       const float dn = dh * (1.0f - z);
       const float dz = dh * (hp_[rb] - n);
