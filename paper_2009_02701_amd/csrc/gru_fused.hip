@@ -184,12 +184,14 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
 // (a CU accepts only ~64 bytes of vector loads per clock: issuing a workgroup's whole operand
 // set up front keeps its waves busy issuing for microseconds before the first MFMA).
 // Registers hold 4 slabs in flight; LDS holds 2 (one barrier per slab).  lds: 2*RT*68 words.
-template <int NQ, bool BF16>
+// RB: 16-row blocks of activations per workgroup (2, or 1 when that is what it takes to put
+// two workgroups on every CU: their barrier and load phases then cover each other).
+template <int NQ, bool BF16, int RB = 2>
 __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wbase, long w_qstride,
                                                     const float* __restrict__ Abase, int KD,
                                                     int rows_valid, float* __restrict__ lds,
-                                                    floatx4 (&acc)[2][NQ]) {
-  constexpr int W = 64, RT = 16 * NQ + 32, UR = W / 4, UPT = RT * UR / 256, P = W + 4;
+                                                    floatx4 (&acc)[RB][NQ]) {
+  constexpr int W = 64, RT = 16 * NQ + 16 * RB, UR = W / 4, UPT = RT * UR / 256, P = W + 4;
   constexpr int PD = 3, RS = PD + 1;  // prefetch distance in slabs, register sets
   static_assert(RT * UR % 256 == 0, "slab shape");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -248,16 +250,16 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
       issue((u + PD) % RS, s0 + u + PD);  // into the set stored one slab ago
-      float4 a[2], w[NQ];
+      float4 a[RB], w[NQ];
 #pragma unroll
       for (int q = 0; q < NQ; ++q)
         w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
 #pragma unroll
-      for (int rb = 0; rb < 2; ++rb)
+      for (int rb = 0; rb < RB; ++rb)
         a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * P + kcol]);
       if (BF16) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
+        for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
           for (int q = 0; q < NQ; ++q) {
             typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -271,7 +273,7 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
 #pragma unroll
         for (int e = 0; e < 4; ++e)
 #pragma unroll
-          for (int rb = 0; rb < 2; ++rb)
+          for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
               const float av = e == 0 ? a[rb].x : e == 1 ? a[rb].y : e == 2 ? a[rb].z : a[rb].w;
@@ -285,30 +287,32 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
 }
 
 // Forward step: h_out = cell(gx_t, h_prev W_hh^T + b_hh, h_prev); saves r|z|n|q of the step.
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int RB>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
                            const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
                            float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
                            int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 80 * 68;  // [4][6][4][64]
+  float* red = staged_lds + 2 * (48 + 16 * RB) * 68;  // [4][3 * RB][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
   __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
-  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ, r0 = ty * FR;
+  constexpr int FRB = 16 * RB;  // batch rows per workgroup
+  step_tile(H / FJ, (B + FRB - 1) / FRB, groups, g, tx, ty);
+  const int j0 = tx * FJ, r0 = ty * FRB;
   const float* hp = h_prev + g * s_hs;
   // the epilogue's own inputs first: they arrive during the matrix work
   const float* bh = b_hh + g * s_rep;
   const int j = j0 + lr;
-  float gxv[2][3], hpv[2], bias[3];
+  float gxv[RB][3], hpv[RB], bias[3];
 #pragma unroll
   for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     // unconditional loads from a row clamped into the batch (a select on a loaded value
     // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
     const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
@@ -317,28 +321,28 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
     for (int q = 0; q < 3; ++q) gxv[rb][q] = gxr[q * H + j];
     hpv[rb] = hp[(long)row * H + j];
   }
-  floatx4 acc[2][3];
+  floatx4 acc[RB][3];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  rolling_contraction<3, false>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
+  rolling_contraction<3, false, RB>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
                                 staged_lds, acc);
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[((wave * 6 + rb * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
+      for (int v = 0; v < 4; ++v) red[((wave * 3 * RB + rb * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
   __syncthreads();
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
     float gh[3];
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
       const int o = ((rb * 3 + q) * 4 + wave) * 64 + lane;
-      gh[q] = ((red[o] + red[o + 6 * 256]) + (red[o + 12 * 256] + red[o + 18 * 256])) + bias[q];
+      gh[q] = ((red[o] + red[o + 3 * RB * 256]) + (red[o + 6 * RB * 256] + red[o + 9 * RB * 256])) + bias[q];
     }
     if (row < B) {
       const float r = sigm(gxv[rb][0] + gh[0]);
@@ -355,8 +359,6 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   }
 }
 
-static constexpr size_t kFwdStagedLds = (2 * 80 * 68 + 4 * 6 * 4 * 64) * sizeof(float);
-static constexpr size_t kBwdStagedLds = (2 * 48 * 68 + 4 * 2 * 4 * 64) * sizeof(float);
 // bf16 variants: 64-word slabs, so that two or three workgroups fit on a CU (config 3 launches
 // two workgroups per CU; resident together they cover each other's load latency)
 static constexpr int SKB = 64;
@@ -364,46 +366,64 @@ static constexpr int TTP = 40;  // pitch (bf16) of a staged transposed-output ro
 static constexpr size_t kFwdBf16Lds = (2 * 80 * (SKB + 4) + 4 * 6 * 4 * 64) * sizeof(float);
 static constexpr size_t kBwdBf16Lds = (2 * 48 * (SKB + 4) + 4 * 2 * 4 * 64) * sizeof(float);
 
-hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
-                                      long s_gx, const float* h_prev, float* h_out, long s_hs,
-                                      float* sv_t, long s_sv, int B, int H, int groups, hipStream_t s) {
+// Two workgroups per CU hide each other's barrier and load phases: when 32-row tiles give
+// fewer workgroups than that, 16-row tiles are used.
+static bool step_rows16(int B, int H, int groups) {
+  return B > 16 && (long)(H / FJ) * ((B + FR - 1) / FR) * groups < 2 * 256;
+}
+
+template <int RB>
+static hipError_t launch_fwd_rb(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t, long s_gx,
+                                const float* h_prev, float* h_out, long s_hs, float* sv_t, long s_sv, int B,
+                                int H, int groups, hipStream_t s) {
+  constexpr size_t lds = (2 * (48 + 16 * RB) * 68 + 4 * 3 * RB * 4 * 64) * sizeof(float);
   static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
   if (!ready) {
-    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFwdStagedLds);
+    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_kernel<RB>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ready = true;
   }
-  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-  hipLaunchKernelGGL(gru_fwd_step_kernel, grid, dim3(256), kFwdStagedLds, s, W_hh, b_hh, s_rep,
-                     gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups);
+  dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
+  hipLaunchKernelGGL(gru_fwd_step_kernel<RB>, grid, dim3(256), lds, s, W_hh, b_hh, s_rep, gx_t, s_gx, h_prev,
+                     h_out, s_hs, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
+}
+
+hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
+                                      long s_gx, const float* h_prev, float* h_out, long s_hs,
+                                      float* sv_t, long s_sv, int B, int H, int groups, hipStream_t s) {
+  return step_rows16(B, H, groups)
+             ? launch_fwd_rb<1>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups, s)
+             : launch_fwd_rb<2>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups, s);
 }
 
 // Backward step.  WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along
 // the contraction).  D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last
 // step) and dh_t * z_t on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+template <int RB>
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __restrict__ dgh_next,
                            long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
                            long s_above, const float* __restrict__ sv_t, long s_sv,
                            const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
                            float* __restrict__ dgh_t, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * 48 * 68;  // [4][2][4][64]
+  float* red = staged_lds + 2 * (16 + 16 * RB) * 68;  // [4][RB][4][64]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
   __builtin_amdgcn_s_setprio(3);
   const int lr = lane & 15, lg = lane >> 4;
   int g, tx, ty;
-  step_tile(H / FJ, (B + FR - 1) / FR, groups, g, tx, ty);
-  const int j0 = tx * FJ, r0 = ty * FR;
+  constexpr int FRB = 16 * RB;  // batch rows per workgroup
+  step_tile(H / FJ, (B + FRB - 1) / FRB, groups, g, tx, ty);
+  const int j0 = tx * FJ, r0 = ty * FRB;
   const int H3 = 3 * H;
   const int j = j0 + lr;
-  float r_[2], z_[2], n_[2], q_[2], hp_[2], dh_[2], ab_[2];
+  float r_[RB], z_[RB], n_[RB], q_[RB], hp_[RB], dh_[RB], ab_[RB];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     // unconditional loads from a row clamped into the batch (a select on a loaded value
     // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
     const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
@@ -417,22 +437,22 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
     dh_[rb] = D[g * s_D + e];
     ab_[rb] = above ? above[g * s_above + e] : 0.f;
   }
-  floatx4 acc[2][1];
-  acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  acc[1][0] = acc[0][0];
+  floatx4 acc[RB][1];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) acc[rb][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   if (dgh_next)
-    rolling_contraction<1, false>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
+    rolling_contraction<1, false, RB>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
                                   B - r0, staged_lds, acc);
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb)
+  for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[((wave * 2 + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
+    for (int v = 0; v < 4; ++v) red[((wave * RB + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
   __syncthreads();
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) {
+  for (int rb = 0; rb < RB; ++rb) {
     const int row = r0 + rb * 16 + 4 * lg + wave;
     const int o = (rb * 4 + wave) * 64 + lane;
-    const float rec = (red[o] + red[o + 2 * 256]) + (red[o + 4 * 256] + red[o + 6 * 256]);
+    const float rec = (red[o] + red[o + RB * 256]) + (red[o + 2 * RB * 256] + red[o + 3 * RB * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
       const float dh = (dh_[rb] + ab_[rb]) + rec;
@@ -456,14 +476,27 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   }
 }
 
+template <int RB>
+static hipError_t launch_bwd_rb(const float* WT, long s_wt, const float* dgh_next, long s_dg, float* D, long s_D,
+                                const float* above, long s_above, const float* sv_t, long s_sv,
+                                const float* h_prev, long s_hs, float* dgx_t, float* dgh_t, int B, int H,
+                                int groups, hipStream_t s) {
+  constexpr size_t lds = (2 * (16 + 16 * RB) * 68 + 4 * RB * 4 * 64) * sizeof(float);
+  dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
+  hipLaunchKernelGGL(gru_bwd_step_kernel<RB>, grid, dim3(256), lds, s, WT, s_wt, dgh_next, s_dg, D, s_D, above,
+                     s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups);
+  return hipGetLastError();
+}
+
 hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next, long s_dg,
                                       float* D, long s_D, const float* above, long s_above,
                                       const float* sv_t, long s_sv, const float* h_prev, long s_hs,
                                       float* dgx_t, float* dgh_t, int B, int H, int groups, hipStream_t s) {
-  dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
-  hipLaunchKernelGGL(gru_bwd_step_kernel, grid, dim3(256), kBwdStagedLds, s, WT, s_wt, dgh_next,
-                     s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups);
-  return hipGetLastError();
+  return step_rows16(B, H, groups)
+             ? launch_bwd_rb<1>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t,
+                                dgh_t, B, H, groups, s)
+             : launch_bwd_rb<2>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t,
+                                dgh_t, B, H, groups, s);
 }
 
 // ---------------------------------------------------------------------------- bf16 variants
