@@ -39,9 +39,36 @@ WORKLOAD_TEXT = {
 }
 
 
-def role_work_per_step(cfg, role_name):
+def mfma_probe(hb, torch, dev, prec):
+    """Sustained rate of a pure-MFMA loop (no memory traffic) on every CU, with all-zero and with
+    random operands: the operand data decides the power the matrix cores draw and with it the
+    clock the chip holds, so this is the ceiling any real contraction of that type sees."""
+    out = {}
+    sink = torch.empty(256 * 256, dtype=torch.float32, device=dev)
+    res = torch.zeros(4, dtype=torch.float64, device=dev)
+    iters = 4000
+    for kind in ("zeros", "random"):
+        if kind == "zeros":
+            ops = torch.zeros(16384, dtype=torch.uint8, device=dev)
+        else:
+            g = torch.Generator(device=dev).manual_seed(7)
+            vals = torch.rand(4096, device=dev, generator=g) * 2 - 1
+            ops = (vals.to(torch.bfloat16).view(torch.uint8).repeat(2) if prec == "bf16"
+                   else vals.view(torch.uint8)).contiguous()
+        for _ in range(2):
+            hb.probe_mfma_rate(prec, ops, iters, res, sink)
+        torch.cuda.synchronize()
+        clk, wall, n, flops = res.cpu().tolist()
+        seconds = wall / 100e6
+        # one wave on every SIMD: 256 workgroups x 4 waves
+        out[kind] = {"TFLOP/s": 256 * 4 * n * flops / seconds / 1e12, "shader_MHz": clk / wall * 100.0}
+    return out
+
+
+def role_work_per_step(cfg, role_name, commit_params=None):
     """Algorithmic work of ALL launches of a role in one local step of all K workers:
-    (bound, flops or bytes per step, peak in the same unit per second)."""
+    (bound, flops or bytes per step, peak in the same unit per second).  commit_params: how many
+    parameters per worker the commit kernel handled (the rest are updated in GEMM epilogues)."""
     kind, K, B = cfg["kind"], cfg["K"], cfg["batch"]
     mfma_peak = (PEAK_BF16_MFMA_TFLOPS if cfg.get("prec") == "bf16" else PEAK_FP32_MFMA_TFLOPS) * 1e12
     hbm = PEAK_HBM_GBS * 1e9
@@ -51,6 +78,8 @@ def role_work_per_step(cfg, role_name):
         bwd = (sum(2.0 * B * d[i] * d[i + 1] for i in range(len(d) - 1))
                + sum(2.0 * B * d[i] * d[i + 1] for i in range(1, len(d) - 1))) * K
         P = sum(d[i] * d[i + 1] + d[i + 1] for i in range(len(d) - 1))
+        if commit_params is not None:
+            P = commit_params
         return {"mlp_fwd": ("mfma", fwd, mfma_peak), "mlp_bwd": ("mfma", bwd, mfma_peak),
                 "commit": ("hbm", 12.0 * P * K, hbm)}.get(role_name, (None, None, None))
     T, H, L = cfg["seq_len"], cfg["hidden"], cfg["layers"]
@@ -60,6 +89,8 @@ def role_work_per_step(cfg, role_name):
     classes = cfg["vocab"] if lm else cfg["classes"]
     nrows = TB if lm else B
     P = sum(3 * H * w + 3 * H * H + 6 * H for w in widths) + classes * H + classes + (cfg["vocab"] * cfg["embed"] if lm else 0)
+    if commit_params is not None:
+        P = commit_params
     table = {
         "gemm_input_projection": ("mfma", sum(2.0 * TB * 3 * H * w for w in widths) * K, mfma_peak),
         "gemm_recurrent_fwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K, mfma_peak),
@@ -120,6 +151,7 @@ def main():
         if n:
             breakdown[nm] = {"launches_per_step": n / probe_rounds, "avg_us": 1e3 * ms / n,
                              "us_per_step": 1e3 * ms / probe_rounds}
+    commit_params = tr.ctx.commit_kernel_params()
     dominant = max(breakdown, key=lambda k: breakdown[k]["us_per_step"])
     dom_role = names.index(dominant)
     tr.ctx.timer_enable([dom_role])
@@ -157,7 +189,7 @@ def main():
     tr.ovl_drain()
     ms_per_step_instrumented = 1e3 * (t3 - t2) / args.steps
 
-    bound, work, peak = role_work_per_step(cfg, dominant)
+    bound, work, peak = role_work_per_step(cfg, dominant, commit_params)
     roofline = None
     if bound is not None and n_dom:
         dur = ms_dom * 1e-3 / n_dom
@@ -169,7 +201,7 @@ def main():
                     "ms_per_step_with_event_pairs": ms_per_step_instrumented,
                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)}
     for nm, v in breakdown.items():
-        b_, w_, p_ = role_work_per_step(cfg, nm)
+        b_, w_, p_ = role_work_per_step(cfg, nm, commit_params)
         if b_ is not None:
             v["frac_of_peak"] = w_ / (v["us_per_step"] * 1e-6) / p_
             v["bound"] = b_
@@ -235,6 +267,9 @@ def main():
                "sample": f"{rounds} rounds of (local step of all {K} workers + merge + sync) on the same "
                          f"{args.workload} inputs, float64 numpy, {el:.1f} s"}
 
+    # what a pure-MFMA loop of this workload's operand type sustains on this chip right now
+    prec = "bf16" if cfg.get("prec") == "bf16" else "fp32"
+    probe = {"dtype": prec, **mfma_probe(hb, torch, dev, prec)}
     out = {
         "metric": "local-step samples/sec (overlapped HPSGD round: gather + local step + merge + sync)",
         "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -243,6 +278,7 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
+        "mfma_probe": probe,
     }
     print(json.dumps(out))
 

@@ -185,6 +185,23 @@ enum hpsgd_role {
 int hpsgd_timer_enable(hpsgd_ctx *ctx, unsigned role_mask);
 int hpsgd_timer_read(hpsgd_ctx *ctx, int role, long *launches, double *total_ms);
 const char *hpsgd_role_name(int role); /* static string, NULL if out of range */
+/* How many parameters per worker went through the gradient buffer and the commit kernel in
+ * the last local step of this context (Alg. 2 "update replica" as a separate streaming pass).
+ * The other weight matrices were updated by the epilogue of their own gradient GEMM.  0
+ * before the first step.  For the byte accounting of the HPSGD_ROLE_COMMIT timings. */
+size_t hpsgd_commit_kernel_params(const hpsgd_ctx *ctx);
+
+/* ---- matrix-core rate probe (measurement aid, not part of the method) --------------------
+ * Runs a loop of independent MFMAs with no memory traffic on every CU: `precision` picks
+ * v_mfma_f32_32x32x16_bf16 (HPSGD_BF16_MFMA) or v_mfma_f32_32x32x2_f32 (HPSGD_FP32);
+ * operand registers are filled from `operands` (DEVICE pointer, at least 16 KiB: zeros, ones
+ * or random values: the data decides how much power the matrix cores draw and with it the
+ * clock the chip sustains).  `result` (DEVICE, 4 doubles, written asynchronously):
+ * [0] shader clock ticks and [1] 100 MHz wall-clock ticks of workgroup 0, [2] MFMA
+ * instructions per wave, [3] flops per MFMA instruction.  256 workgroups of 4 waves: one wave
+ * per SIMD, so the chip's rate is 1024 waves x [2] x [3] / ([1] / 100 MHz). */
+int hpsgd_probe_mfma_rate(int precision, const void *operands, int iterations, double *result,
+                          float *sink /* DEVICE, 256*256 floats */, void *hip_stream);
 
 /* Human-readable name of a status code (static string). */
 const char *hpsgd_strerror(int status);

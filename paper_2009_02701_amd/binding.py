@@ -24,6 +24,7 @@ EXPORTS = [
     "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
     "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
+    "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate",
 ]
 ROLE_COUNT = 14
 
@@ -75,6 +76,9 @@ def load_library():
     lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.hpsgd_role_name.argtypes = [C.c_int]
     lib.hpsgd_role_name.restype = C.c_char_p
+    lib.hpsgd_commit_kernel_params.argtypes = [vp]
+    lib.hpsgd_commit_kernel_params.restype = sz
+    lib.hpsgd_probe_mfma_rate.argtypes = [C.c_int, vp, C.c_int, vp, vp, vp]
     lib.hpsgd_strerror.argtypes = [C.c_int]
     lib.hpsgd_strerror.restype = C.c_char_p
     _lib = lib
@@ -180,6 +184,10 @@ class Context:
     def role_names(self):
         return [self.lib.hpsgd_role_name(i).decode() for i in range(ROLE_COUNT)]
 
+    def commit_kernel_params(self):
+        """Parameters per worker that went through the commit kernel in the last local step."""
+        return int(self.lib.hpsgd_commit_kernel_params(self._h))
+
     # ---- entry points ----
     def local_step_all(self, replicas_in, replicas_out, x, y, lr, loss_out, workspace, stream=None):
         """replicas_*: float32 [K, stride] tensors (row k = worker k's flat replica)."""
@@ -238,3 +246,10 @@ def gather_batch_all(shards, idxs, n_chunks, chunk_elems, outs, row_elems=None, 
                                                  idxs[0].numel(), row, int(n_chunks),
                                                  int(chunk_elems) * es, _ptr_array(outs), _stream(stream)),
            "hpsgd_gather_batch_all")
+
+
+def probe_mfma_rate(prec, operands, iterations, result, sink, stream=None):
+    """Pure-MFMA loop on every CU (argument marshalling only; see hpsgd_probe_mfma_rate).
+    operands: >= 16 KiB device tensor; result: float64[4]; sink: float32[256*256]."""
+    _check(load_library().hpsgd_probe_mfma_rate(PREC[prec], _ptr(operands), int(iterations), _ptr(result),
+                                                _ptr(sink), _stream(stream)), "hpsgd_probe_mfma_rate")

@@ -240,4 +240,65 @@ hipError_t launch_rowsum_bf16(const void* in, long ld, long s_in, float* out, lo
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------- matrix-core rate probe
+// 16 independent 32x32 accumulator tiles per wave (256 accumulator registers: one wave per
+// SIMD), operands fixed in registers: nothing but MFMA issue.  256 workgroups of 4 waves: one
+// wave on every SIMD of the chip.  Records the shader-clock and the 100 MHz wall-clock ticks of workgroup 0.
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8p __attribute__((ext_vector_type(8)));
+
+template <bool BF16>
+__global__ void __launch_bounds__(256)
+mfma_probe_kernel(const unsigned char* __restrict__ operands, int iters, double* __restrict__ result,
+                  float* __restrict__ sink) {
+  const int tid = threadIdx.x;
+  uint4 ra[4], rb[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    ra[i] = *reinterpret_cast<const uint4*>(operands + ((tid * 4 + i) * 16) % 8192);
+    rb[i] = *reinterpret_cast<const uint4*>(operands + 8192 + ((tid * 4 + i) * 16) % 8192);
+  }
+  floatx16 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  const long long c0 = clock64(), w0 = wall_clock64();
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      if (BF16)
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8p, ra[i & 3]),
+                                                         __builtin_bit_cast(bf16x8p, rb[(i >> 2) & 3]), acc[i], 0, 0, 0);
+      else
+        acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(__builtin_bit_cast(float, ra[i & 3].x),
+                                                      __builtin_bit_cast(float, rb[(i >> 2) & 3].x), acc[i], 0, 0, 0);
+    }
+  }
+  const long long c1 = clock64(), w1 = wall_clock64();
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sum += acc[i][v];
+  sink[blockIdx.x * 256 + tid] = sum;
+  if (blockIdx.x == 0 && tid == 0) {
+    result[0] = (double)(c1 - c0);
+    result[1] = (double)(w1 - w0);
+    result[2] = 16.0 * iters;
+    result[3] = BF16 ? 32768.0 : 4096.0;
+  }
+}
+
+hipError_t launch_mfma_probe(bool bf16, const void* operands, int iterations, double* result, float* sink,
+                             hipStream_t s) {
+  if (bf16)
+    hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3(256), dim3(256), 0, s, (const unsigned char*)operands,
+                       iterations, result, sink);
+  else
+    hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3(256), dim3(256), 0, s, (const unsigned char*)operands,
+                       iterations, result, sink);
+  return hipGetLastError();
+}
+
 }  // namespace hpsgd

@@ -50,6 +50,7 @@ struct hpsgd_ctx {
   // that order it against the caller's stream
   hipStream_t aux = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  size_t last_commit_params = 0;  // parameters per worker that the commit kernel handled last step
   unsigned timer_mask = 0;
   bool timer_nested = false;    // an enclosing scope already brackets the current launches
   struct Stamp { int role; int launches; hipEvent_t a, b; };
@@ -749,6 +750,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   // ---- commit (Alg. 2 "update replica")
   // the parameters not updated by a GEMM epilogue: one launch per contiguous run of them
   role = HPSGD_ROLE_COMMIT;
+  c->last_commit_params = 0;
   for (size_t e = 0; e < c->entries.size();) {
     if (fused_commit[e]) {
       ++e;
@@ -758,6 +760,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     while (e < c->entries.size() && !fused_commit[e]) ++e;
     const size_t hi = e < c->entries.size() ? c->entries[e].offset : c->P;
     HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
+    c->last_commit_params += hi - lo;
   }
   return HPSGD_OK;
 }
@@ -956,6 +959,19 @@ int hpsgd_timer_read(hpsgd_ctx* ctx, int role, long* launches, double* total_ms)
   ctx->role_launches[role] = 0;
   ctx->role_ms[role] = 0.0;
   return HPSGD_OK;
+}
+
+size_t hpsgd_commit_kernel_params(const hpsgd_ctx* ctx) { return ctx ? ctx->last_commit_params : 0; }
+
+int hpsgd_probe_mfma_rate(int precision, const void* operands, int iterations, double* result, float* sink,
+                          void* hip_stream) {
+  if (!operands || !result || !sink || iterations < 1) return HPSGD_EINVAL;
+  if (precision != HPSGD_FP32 && precision != HPSGD_BF16_MFMA) return HPSGD_EINVAL;
+  if (((uintptr_t)operands & 15) != 0) return HPSGD_EALIGN;
+  return launch_mfma_probe(precision == HPSGD_BF16_MFMA, operands, iterations, result, sink,
+                           (hipStream_t)hip_stream) == hipSuccess
+             ? HPSGD_OK
+             : HPSGD_EHIP;
 }
 
 const char* hpsgd_role_name(int role) {

@@ -117,6 +117,12 @@ def test_gather_all_and_aux_stream_reject_bad_arguments():
     assert lib.hpsgd_timer_enable(None, 0) == 1
     assert lib.hpsgd_timer_read(ctx._h, 99, None, None) == 1
     assert lib.hpsgd_role_name(99) is None and lib.hpsgd_role_name(3) == b"gemm_recurrent_bwd"
+    assert lib.hpsgd_commit_kernel_params(None) == 0 and lib.hpsgd_commit_kernel_params(ctx._h) == 0
+    probe = lib.hpsgd_probe_mfma_rate
+    assert probe(0, None, 10, 0x1000, 0x2000, None) == 1                 # null operands
+    assert probe(0, 0x1000, 0, 0x2000, 0x3000, None) == 1                # no iterations
+    assert probe(7, 0x1000, 10, 0x2000, 0x3000, None) == 1               # unknown precision
+    assert probe(1, 0x1004, 10, 0x2000, 0x3000, None) == 3               # misaligned operands
 
 
 def test_local_step_rejects_bad_arguments_before_launch():

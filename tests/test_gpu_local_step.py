@@ -202,3 +202,28 @@ def test_overlapped_two_streams_equals_one_stream_bitwise():
         tr.s_ovl(cfg["lr"], rounds=4, single_stream=single)
         outs.append(tr.G.cpu().numpy().view(np.uint32).copy())
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+
+
+def test_commit_kernel_params_counts_what_the_epilogues_did_not_update():
+    """MLP: every weight matrix is updated by its gradient GEMM, the commit kernel sees the
+    biases only; the count is what bench.py uses for the commit role's bytes."""
+    cfg = SMALL["mlp_ragged"]
+    tr, init, _, _, _ = _one_step(cfg, cfg["lr"])
+    n_bias = sum(v.size for k, v in init.items() if k.endswith(".b"))
+    assert tr.ctx.commit_kernel_params() == n_bias
+
+
+@pytest.mark.parametrize("prec", ["bf16", "fp32"])
+def test_mfma_probe_reports_a_plausible_rate(prec):
+    sink = torch.empty(256 * 256, dtype=torch.float32, device=DEV)
+    res = torch.zeros(4, dtype=torch.float64, device=DEV)
+    ops = torch.zeros(16384, dtype=torch.uint8, device=DEV)
+    hb.probe_mfma_rate(prec, ops, 200, res, sink)
+    torch.cuda.synchronize()
+    clk, wall, n, flops = res.cpu().tolist()
+    assert n == 16 * 200 and flops == (32768 if prec == "bf16" else 4096)
+    assert clk > 0 and wall > 0
+    mhz = clk / wall * 100.0
+    assert 300 < mhz < 3000, mhz
+    # all-zero operands: the accumulators stay zero
+    assert float(sink.abs().max()) == 0.0
