@@ -310,6 +310,40 @@ def s_ovl(init, batch_fn, K, lr, rounds, step_fn=None, trace=None):
     return G, losses
 
 
+def s_async(init, batch_fn, K, lr, counts, step_fn=None):
+    """Alg. 2 + Alg. 3 with the number of local steps per synchronisation left to the run:
+    counts[r] local steps are made while the synchronisation of round r-1 is in flight
+    (Sec. 3.1: the training process keeps training as long as `status` is `synchronizing`,
+    and starts the next synchronisation as soon as it finds `status` idle).
+
+    Two replica generations alternate.  Round r trains one generation for counts[r] steps
+    (mini-batch index = running step number e); its accumulated change is folded into the
+    global model and the generation is cloned again, while round r+1 already trains the
+    other generation - which was cloned before round r's change existed.  That is the
+    one-synchronisation delay of Alg. 3.  counts = [1]*R is s_ovl.  Returns (global, losses).
+    """
+    step_fn = step_fn or local_step
+    G = _f64(init)
+    S = [sync(G), sync(G)]
+    R = [[sync(G) for _ in range(K)], [sync(G) for _ in range(K)]]
+    g = 0
+    e = 0
+    losses = []
+    for n in counts:
+        for _ in range(n):
+            row = []
+            for k in range(K):
+                R[g][k], loss = step_fn(R[g][k], *batch_fn(k, e), lr)
+                row.append(loss)
+            losses.append(row)
+            e += 1
+        G = merge(G, R[g], S[g])
+        S[g] = sync(G)
+        R[g] = [sync(G) for _ in range(K)]
+        g = 1 - g
+    return G, losses
+
+
 def overlap_counts(gamma, k):
     """Sec. 3.2 worked example: with t_sync = k * t_train, one Local-SGD loop (gamma local
     steps, one more training pass, one synchronisation) lasts (gamma + 1 + k) * t_train.

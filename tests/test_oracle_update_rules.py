@@ -190,6 +190,65 @@ def test_sovl_quadratic_closed_form():
     assert np.abs(G["w"] - want).max() < 1e-12
 
 
+def test_sasync_with_one_step_per_round_is_sovl():
+    bf = _batch_fn(CFG)
+    init = wl.init_params(CFG)
+    K, lr = CFG["K"], CFG["lr"]
+    Ga, la = oc.s_async(init, bf, K, lr, [1, 1, 1, 1])
+    Go, lo = oc.s_ovl(init, bf, K, lr, rounds=4)
+    for k in init:
+        assert np.array_equal(Ga[k], Go[k]), k
+    assert la == lo
+
+
+def test_sasync_single_round_single_worker_is_plain_sgd():
+    """One worker, one round of n steps: the merge adds exactly that worker's change."""
+    bf = _batch_fn(CFG)
+    init = wl.init_params(CFG)
+    lr = CFG["lr"]
+    G, _ = oc.s_async(init, bf, 1, lr, [3])
+    w = {k: v.astype(np.float64) for k, v in init.items()}
+    for e in range(3):
+        w, _ = oc.local_step(w, *bf(0, e), lr)
+    _close(G, w)
+
+
+def test_sasync_is_alg2_alg3_in_gradient_form():
+    """The literal bookkeeping of Alg. 2 / Alg. 3 (accumulated gradients, counter, status, the
+    update applied one synchronisation after its all-reduce, Eq. 1 with the mean) on a model
+    whose gradient is known in closed form, against the delta form the oracle uses.
+    Worker k minimises 0.5*|w - c_k|^2 with plain SGD; `busy` steps after a StartSync find
+    the status `synchronizing`."""
+    g = np.random.default_rng(11)
+    K, lr, P = 3, 0.2, 5
+    c = [g.standard_normal(P) for _ in range(K)]
+    counts = [1, 3, 2, 1, 4, 2]
+    init = {"w": g.standard_normal(P)}
+    step = lambda rep, x, y, lr_: ({"w": rep["w"] - lr_ * (rep["w"] - c[x])}, 0.0)
+    G, _ = oc.s_async(init, lambda k, t: (k, None), K, lr, counts, step_fn=step)
+
+    # Alg. 2 / Alg. 3 as written, all K workers in lockstep
+    w = init["w"].copy()                      # global model
+    pending = None                            # all-reduced gradients waiting for the next StartSync
+    acc = [np.zeros(P) for _ in range(K)]     # accumulated gradients of the running round
+    rep = [w.copy() for _ in range(K)]        # replicas: clone(w) when counter == 0
+    for n in counts:
+        for k in range(K):
+            rep[k] = w.copy()                 # counter == 0: make replica
+        for _ in range(n):
+            for k in range(K):
+                grad = rep[k] - c[k]
+                rep[k] = rep[k] - lr * grad   # update replica
+                acc[k] = acc[k] + grad        # accumulate gradients
+        # status idle: StartSync.  P_s first applies the previous all-reduce, then all-reduces
+        if pending is not None:
+            w = w - lr * pending
+        pending = sum(acc) / K
+        acc = [np.zeros(P) for _ in range(K)]
+    w = w - lr * pending                      # the last all-reduce, applied by the final sync
+    assert np.abs(G["w"] - w).max() < 1e-12
+
+
 def test_overlap_counts_match_the_worked_example():
     """Sec. 3.2: in the span of one Local-SGD loop, gamma + k + 1 trainings and
     (gamma + 1)/k + 1 synchronisations.  Values for gamma = 8 (Sec. 4.1) in tests/golden."""
