@@ -189,6 +189,32 @@ def main():
     tr.ovl_drain()
     ms_per_step_instrumented = 1e3 * (t3 - t2) / args.steps
 
+    # ---- the asynchronous driver (Alg. 2 + Alg. 3 with the status check at run time): the same
+    # kernels, the number of local steps per synchronisation decided by whether stream B is idle;
+    # once as is, once with a synthetic synchronisation latency of about 2.5 local steps
+    async_driver = []
+    for delay in (0, int(2.5e3 * ms_per_step)):
+        torch.cuda.synchronize()
+        a0 = time.perf_counter()
+        counts = tr.s_async(lr, 60, sync_delay_us=delay)
+        a1 = time.perf_counter()
+        async_driver.append({"sync_delay_us": delay, "local_steps": 60, "rounds": len(counts),
+                             "max_steps_per_round": max(counts), "value": 60 * samples_per_step / (a1 - a0),
+                             "unit": unit})
+
+    # ---- the paper's comparison in shape (Sec. 4.3): the same 64 local steps under the same
+    # synthetic synchronisation latency with the blocking schedules (synchronous SGD, Local SGD
+    # with gamma = 8, Sec. 4.1) and with the overlapped asynchronous one
+    delay = int(2.5e3 * ms_per_step)
+    compare = {"sync_delay_us": delay, "local_steps": 64, "unit": unit}
+    for name, run in (("ssgd_blocking", lambda: tr.s_seq(lr, 1, 64, record_loss=False, sync_delay_us=delay)),
+                      ("local_sgd_gamma8_blocking", lambda: tr.s_seq(lr, 8, 8, record_loss=False, sync_delay_us=delay)),
+                      ("hpsgd_async", lambda: tr.s_async(lr, 64, sync_delay_us=delay))):
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        run()
+        compare[name] = 64 * samples_per_step / (time.perf_counter() - c0)
+
     bound, work, peak = role_work_per_step(cfg, dominant, commit_params)
     roofline = None
     if bound is not None and n_dom:
@@ -278,7 +304,7 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
-        "mfma_probe": probe,
+        "mfma_probe": probe, "async_driver": async_driver, "schedules_under_sync_latency": compare,
     }
     print(json.dumps(out))
 

@@ -191,6 +191,13 @@ const char *hpsgd_role_name(int role); /* static string, NULL if out of range */
  * before the first step.  For the byte accounting of the HPSGD_ROLE_COMMIT timings. */
 size_t hpsgd_commit_kernel_params(const hpsgd_ctx *ctx);
 
+/* ---- synthetic synchronisation latency (measurement / test aid) ---------------------------
+ * Occupies `hip_stream` for about `microseconds` (one wave that sleeps until the 100 MHz wall
+ * clock has advanced that far; at most 1 000 000, else HPSGD_EINVAL).  Stands in for a slow
+ * interconnect on the synchronising side (Sec. 3.2: t_sync = k * t_train), so that the
+ * asynchronous schedule of Alg. 2 / Alg. 3 can be driven into rounds of several local steps. */
+int hpsgd_delay_us(unsigned microseconds, void *hip_stream);
+
 /* ---- matrix-core rate probe (measurement aid, not part of the method) --------------------
  * Runs a loop of independent MFMAs with no memory traffic on every CU: `precision` picks
  * v_mfma_f32_32x32x16_bf16 (HPSGD_BF16_MFMA) or v_mfma_f32_32x32x2_f32 (HPSGD_FP32);

@@ -24,7 +24,7 @@ EXPORTS = [
     "hpsgd_param_entry", "hpsgd_workspace_bytes", "hpsgd_local_step_all", "hpsgd_local_step",
     "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
-    "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate",
+    "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
 ]
 ROLE_COUNT = 14
 
@@ -79,6 +79,7 @@ def load_library():
     lib.hpsgd_commit_kernel_params.argtypes = [vp]
     lib.hpsgd_commit_kernel_params.restype = sz
     lib.hpsgd_probe_mfma_rate.argtypes = [C.c_int, vp, C.c_int, vp, vp, vp]
+    lib.hpsgd_delay_us.argtypes = [C.c_uint, vp]
     lib.hpsgd_strerror.argtypes = [C.c_int]
     lib.hpsgd_strerror.restype = C.c_char_p
     _lib = lib
@@ -253,3 +254,8 @@ def probe_mfma_rate(prec, operands, iterations, result, sink, stream=None):
     operands: >= 16 KiB device tensor; result: float64[4]; sink: float32[256*256]."""
     _check(load_library().hpsgd_probe_mfma_rate(PREC[prec], _ptr(operands), int(iterations), _ptr(result),
                                                 _ptr(sink), _stream(stream)), "hpsgd_probe_mfma_rate")
+
+
+def delay_us(microseconds, stream=None):
+    """Occupy `stream` for about that long (synthetic synchronisation latency)."""
+    _check(load_library().hpsgd_delay_us(int(microseconds), _stream(stream)), "hpsgd_delay_us")

@@ -961,6 +961,11 @@ int hpsgd_timer_read(hpsgd_ctx* ctx, int role, long* launches, double* total_ms)
   return HPSGD_OK;
 }
 
+int hpsgd_delay_us(unsigned microseconds, void* hip_stream) {
+  if (microseconds > 1000000u) return HPSGD_EINVAL;
+  return launch_delay(microseconds, (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
+}
+
 size_t hpsgd_commit_kernel_params(const hpsgd_ctx* ctx) { return ctx ? ctx->last_commit_params : 0; }
 
 int hpsgd_probe_mfma_rate(int precision, const void* operands, int iterations, double* result, float* sink,

@@ -112,6 +112,8 @@ hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int3
 hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
                                  const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
                                  hipStream_t s);
+// one wave that sleeps until the wall clock has advanced by `us` microseconds
+hipError_t launch_delay(unsigned us, hipStream_t s);
 // pure-MFMA loop, one wave on every SIMD, operands from `operands` (16 KiB); see hpsgd.h
 hipError_t launch_mfma_probe(bool bf16, const void* operands, int iterations, double* result, float* sink,
                              hipStream_t s);

@@ -218,6 +218,19 @@ hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t str
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------- delay
+// Ends when the 100 MHz wall clock has advanced by `ticks`: the wait is bounded by construction.
+__global__ void __launch_bounds__(64) delay_kernel(long long ticks) {
+  const long long t0 = wall_clock64();
+  while (wall_clock64() - t0 < ticks) __builtin_amdgcn_s_sleep(32);
+}
+
+hipError_t launch_delay(unsigned us, hipStream_t s) {
+  if (us == 0) return hipSuccess;
+  hipLaunchKernelGGL(delay_kernel, dim3(1), dim3(64), 0, s, (long long)us * 100);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------- gather
 // out[(c*n_idx + b)*chunk ...] = shard[idx[b]*row + c*chunk ...], in 4-byte words.
 __global__ void __launch_bounds__(kThreads)

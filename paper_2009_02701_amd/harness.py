@@ -106,7 +106,9 @@ class Trainer:
         return self.ctx.unflatten(self.R[gen][k, :self.P].cpu().numpy())
 
     # ------------------------------------------------------------------ schedules
-    def s_seq(self, lr: float, gamma: int, rounds: int, record_loss=True):
+    def s_seq(self, lr: float, gamma: int, rounds: int, record_loss=True, sync_delay_us: int = 0):
+        """Blocking order (gamma = 1: synchronous SGD; gamma > 1: Local SGD, Alg. 1): the
+        synchronisation - and its optional synthetic latency - sits on the training stream."""
         st = self.stream_a
         st.wait_stream(torch.cuda.current_stream())
         step = 0
@@ -119,6 +121,8 @@ class Trainer:
                     with torch.cuda.stream(st):
                         self.losses.append(self.loss.clone())
                 step += 1
+            if sync_delay_us:
+                hb.delay_us(sync_delay_us, st)
             self.merge(0, st)
         st.synchronize()
 
@@ -128,6 +132,52 @@ class Trainer:
         for t in range(rounds):
             self.ovl_round(t, lr, record_loss)
         self.ovl_drain()
+
+    def s_async(self, lr: float, epochs: int, sync_delay_us: int = 0, record_loss=False):
+        """Alg. 2 + Alg. 3 with the status check made at run time: after every local step the
+        training side (stream A) asks, without waiting, whether the synchronising side
+        (stream B) is idle.  If it is, the generation just trained is handed over (StartSync:
+        merge of its replica changes, then a fresh clone of the global model) and training
+        goes on at once on the other generation; if not, the next local step stays on the
+        same generation.  Returns the number of local steps of every round - what the
+        float64 oracle needs to replay the run.  sync_delay_us: extra time the synchronising
+        side takes per round (a slow interconnect).  At most two local steps are in flight, so
+        the status the host reads is the one the device is in."""
+        sa, sb = self.stream_a, self.stream_b
+        sa.wait_stream(torch.cuda.current_stream())
+        self.sync_all(0, sa)
+        self.sync_all(1, sa)
+        g, n, counts = 0, 0, []
+        busy = None  # event: the synchronising side's running job
+        done = [torch.cuda.Event(), torch.cuda.Event()]
+        for e in range(epochs):
+            if e >= 2:
+                done[e % 2].synchronize()
+            self.gather(e, sa)
+            self.local_step(g, lr, sa)
+            n += 1
+            if record_loss:
+                with torch.cuda.stream(sa):
+                    self.losses.append(self.loss.clone())
+            done[e % 2].record(sa)
+            if busy is None or busy.query():  # status == idle
+                sb.wait_event(done[e % 2])
+                if sync_delay_us:
+                    hb.delay_us(sync_delay_us, sb)
+                self.merge(g, sb)
+                self.sync_all(g, sb)
+                busy = torch.cuda.Event()
+                busy.record(sb)
+                counts.append(n)
+                g, n = 1 - g, 0
+        if busy is not None:
+            sa.wait_event(busy)
+        if n:
+            self.merge(g, sa)
+            counts.append(n)
+        sa.synchronize()
+        sb.synchronize()
+        return counts
 
     def ovl_begin(self, single_stream=False):
         self._sa = self.stream_a

@@ -118,6 +118,8 @@ def test_gather_all_and_aux_stream_reject_bad_arguments():
     assert lib.hpsgd_timer_read(ctx._h, 99, None, None) == 1
     assert lib.hpsgd_role_name(99) is None and lib.hpsgd_role_name(3) == b"gemm_recurrent_bwd"
     assert lib.hpsgd_commit_kernel_params(None) == 0 and lib.hpsgd_commit_kernel_params(ctx._h) == 0
+    assert lib.hpsgd_delay_us(2000000, None) == 1                        # beyond the one-second cap
+    assert lib.hpsgd_delay_us(0, None) == 0                              # nothing to launch
     probe = lib.hpsgd_probe_mfma_rate
     assert probe(0, None, 10, 0x1000, 0x2000, None) == 1                 # null operands
     assert probe(0, 0x1000, 0, 0x2000, 0x3000, None) == 1                # no iterations

@@ -167,6 +167,41 @@ def test_config3_gru_language_model_bf16(sched):
     _schedule_parity(wl.CONFIGS["gru_lm"], sched[0], TOL_BF16, **sched[1])
 
 
+@pytest.mark.parametrize("name,delay_us,epochs", [("tiny_gru", 0, 10), ("tiny_gru", 4000, 14),
+                                                  ("gru_cls_small", 6000, 12)])
+def test_async_driver_replayed_by_the_oracle(name, delay_us, epochs):
+    """Alg. 2 + Alg. 3 with the status check at run time: whatever number of local steps each
+    round ended up with, the float64 oracle replaying those counts must give the same model.
+    A synthetic synchronisation latency drives the rounds to several local steps."""
+    cfg = wl.CONFIGS["tiny_gru"] if name == "tiny_gru" else wl.scaled(
+        wl.CONFIGS["gru_cls"], input=32, hidden=64, seq_len=9, batch=16, K=4)
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    K, lr = cfg["K"], cfg["lr"]
+    counts = tr.s_async(lr, epochs, sync_delay_us=delay_us, record_loss=True)
+    assert sum(counts) == epochs and min(counts) >= 1
+    if delay_us:
+        assert max(counts) > 1, counts  # the slow synchronising side was seen as busy at least once
+    want, losses = oc.s_async(init, batch_fn, K, lr, counts)
+    got = tr.global_params()
+    err, worst, errs = worst_rel_err(got, want)
+    assert err <= TOL_FP32, (counts, worst, errs)
+    gl = np.stack([l.cpu().numpy() for l in tr.losses])
+    assert rel_err(gl, np.asarray(losses)) <= TOL_FP32
+
+
+def test_delay_occupies_the_stream_for_about_the_requested_time():
+    st = torch.cuda.Stream(device=DEV)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    with torch.cuda.stream(st):
+        a.record(st)
+        hb.delay_us(3000, st)
+        b.record(st)
+    st.synchronize()
+    ms = a.elapsed_time(b)
+    assert 2.9 <= ms <= 6.0, ms
+
+
 def test_aux_stream_overlap_matches_single_stream_order():
     """Weight-gradient GEMMs issued chunk by chunk on the auxiliary stream (beside BPTT) give
     the oracle's gradients too, and the same result as the single-stream order up to fp32
