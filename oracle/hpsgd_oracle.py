@@ -244,6 +244,25 @@ def merge(global_, replicas, snapshot):
     return np.asarray(global_, F64) + acc / K
 
 
+def merge_grad(global_, accs, lr):
+    """Eq. 1 as printed: the global model moves by -lr times the mean over the workers of their
+    accumulated gradients (Alg. 3: all-reduce of the accumulators, then the update)."""
+    if isinstance(global_, dict):
+        return {k: merge_grad(global_[k], [a[k] for a in accs], lr) for k in global_}
+    K = len(accs)
+    tot = np.zeros_like(np.asarray(global_, F64))
+    for a in accs:
+        tot = tot + np.asarray(a, F64)
+    return np.asarray(global_, F64) - lr * (tot / K)
+
+
+def local_step_acc(replica, acc, x, y, lr):
+    """Alg. 2, both bookkeeping lines of a local step: update the replica with the step's
+    gradient and add the same gradient to the accumulator.  Returns (replica', acc', loss)."""
+    loss, g = loss_and_grads(replica, x, y)
+    return commit(replica, g, lr), {k: np.asarray(acc[k], F64) + g[k] for k in g}, loss
+
+
 def sync(global_):
     """Alg. 2 'make replica': an exact copy of the global model."""
     if isinstance(global_, dict):
@@ -275,6 +294,28 @@ def s_seq(init, batch_fn, K, lr, gamma, rounds, step_fn=None):
             losses.append(row)
             step += 1
         G = merge(G, R, S)
+    return G, losses
+
+
+def s_seq_grad(init, batch_fn, K, lr, gamma, rounds):
+    """s_seq with the synchronisation in gradient form (what Alg. 2 / Alg. 3 put on the wire):
+    every worker accumulates its gradients over the round, the global model is updated with
+    Eq. 1.  For a learning rate that is constant over the round this is the delta form of
+    `merge` up to rounding.  Returns (global, losses[step][worker])."""
+    G = _f64(init)
+    losses = []
+    step = 0
+    for _ in range(rounds):
+        R = [sync(G) for _ in range(K)]
+        A = [{k: np.zeros_like(v) for k, v in G.items()} for _ in range(K)]
+        for _ in range(gamma):
+            row = []
+            for k in range(K):
+                R[k], A[k], loss = local_step_acc(R[k], A[k], *batch_fn(k, step), lr)
+                row.append(loss)
+            losses.append(row)
+            step += 1
+        G = merge_grad(G, A, lr)
     return G, losses
 
 

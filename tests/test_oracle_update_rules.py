@@ -190,6 +190,36 @@ def test_sovl_quadratic_closed_form():
     assert np.abs(G["w"] - want).max() < 1e-12
 
 
+def test_merge_grad_bruteforce_loops_and_eq1():
+    g = np.random.default_rng(3)
+    K, P, lr = 3, 6, 0.7
+    G = g.standard_normal(P)
+    A = [g.standard_normal(P) for _ in range(K)]
+    want = np.empty(P)
+    for j in range(P):
+        tot = 0.0
+        for k in range(K):
+            tot += A[k][j]
+        want[j] = G[j] - lr * tot / K
+    assert np.abs(oc.merge_grad(G, A, lr) - want).max() < 1e-15
+    assert np.array_equal(oc.merge_grad(G, A, 0.0), G)            # lr = 0: unchanged
+    one = oc.merge_grad(G, [A[0]], lr)                            # one worker: a plain SGD step
+    assert np.abs(one - (G - lr * A[0])).max() < 1e-15
+
+
+def test_sseq_in_gradient_form_equals_the_delta_form():
+    """Eq. 1 (accumulated gradients) and the delta form `merge` are the same update when the
+    learning rate is constant over the round."""
+    bf = _batch_fn(CFG)
+    init = wl.init_params(CFG)
+    K, lr = CFG["K"], CFG["lr"]
+    for gamma, rounds in ((1, 3), (3, 2)):
+        Gg, lg = oc.s_seq_grad(init, bf, K, lr, gamma, rounds)
+        Gd, ld = oc.s_seq(init, bf, K, lr, gamma, rounds)
+        _close(Gg, Gd, tol=1e-12)
+        assert np.allclose(lg, ld, rtol=1e-12, atol=0)
+
+
 def test_sasync_with_one_step_per_round_is_sovl():
     bf = _batch_fn(CFG)
     init = wl.init_params(CFG)
