@@ -215,6 +215,17 @@ def main():
         run()
         compare[name] = 64 * samples_per_step / (time.perf_counter() - c0)
 
+    # gradient-form synchronisation (Eq. 1 as printed): blocking rounds of one local step, for the
+    # cost of accumulating gradients (no update in GEMM epilogues) next to the delta form
+    forms = {"unit": unit}
+    for name, run in (("delta_form_s_seq", lambda: tr.s_seq(lr, 1, 32, record_loss=False)),
+                      ("gradient_form_s_seq_grad", lambda: tr.s_seq_grad(lr, 1, 32, record_loss=False))):
+        run()
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        run()
+        forms[name] = 32 * samples_per_step / (time.perf_counter() - c0)
+
     bound, work, peak = role_work_per_step(cfg, dominant, commit_params)
     roofline = None
     if bound is not None and n_dom:
@@ -263,11 +274,22 @@ def main():
         t_merge = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(iters)) / iters
         t_sync = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(iters)) / iters
         bm, bs = 4.0 * (K5 + 3) * P5, 4.0 * (K5 + 2) * P5
+        # the gradient-form merge (Eq. 1 as printed) on the same buffers taken as accumulators
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            hb.merge_grad(G, reps, 1e-3)
+        g0.record(st)
+        for _ in range(iters):
+            hb.merge_grad(G, reps, 1e-3)
+        g1.record(st)
+        torch.cuda.synchronize()
+        t_mg = g0.elapsed_time(g1) / iters
         merge_stress = {
             "workload": "flat fp32 vector P=1e8, K=8, merge+sync x50",
             "merge_ms": t_merge, "merge_GBps": bm / t_merge / 1e6, "merge_frac_hbm": bm / t_merge / 1e6 / PEAK_HBM_GBS,
             "sync_ms": t_sync, "sync_GBps": bs / t_sync / 1e6, "sync_frac_hbm": bs / t_sync / 1e6 / PEAK_HBM_GBS,
             "merge_plus_sync_GBps": (bm + bs) / (t_merge + t_sync) / 1e6,
+            "merge_grad_ms": t_mg, "merge_grad_GBps": bs / t_mg / 1e6, "merge_grad_frac_hbm": bs / t_mg / 1e6 / PEAK_HBM_GBS,
         }
         del G, S, R, reps
         torch.cuda.empty_cache()
@@ -305,6 +327,7 @@ def main():
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
         "mfma_probe": probe, "async_driver": async_driver, "schedules_under_sync_latency": compare,
+        "synchronisation_forms": forms,
     }
     print(json.dumps(out))
 

@@ -151,6 +151,22 @@ int hpsgd_gather_batch_all(const void *const *shards, const int32_t *const *idx,
 int hpsgd_merge(float *global, const float *const *replicas, const float *snapshot, int K,
                 size_t P, void *hip_stream);
 
+/* ---- synchronisation in gradient form (Eq. 1 as printed; Alg. 2 "accumulate gradients") ----
+ * hpsgd_local_step_all_acc is hpsgd_local_step_all that also adds the step's gradient of
+ * worker k to grad_acc[k * acc_stride .. + P) (DEVICE fp32, 16-byte aligned, acc_stride >= P and
+ * a multiple of 4 when K > 1; must not overlap the replicas, else HPSGD_EALIAS).  The caller
+ * zeroes the accumulators at the start of a round.  In this form every gradient passes through
+ * the gradient buffer (no update in a GEMM epilogue), so a step moves more bytes.
+ * hpsgd_merge_grad: global[j] -= lr * (1/K) * sum_k grad_accs[k][j], the sum taken in worker
+ * order in fp32.  grad_accs: HOST array of K DEVICE pointers, none overlapping `global`.
+ * For a learning rate that is constant over the round this is hpsgd_merge up to rounding. */
+int hpsgd_local_step_all_acc(hpsgd_ctx *ctx, const float *replicas_in, float *replicas_out,
+                             size_t replica_stride, const void *x, const int32_t *y, float lr,
+                             float *loss_out, float *grad_acc, size_t acc_stride, void *workspace,
+                             void *hip_stream);
+int hpsgd_merge_grad(float *global, const float *const *grad_accs, float lr, int K, size_t P,
+                     void *hip_stream);
+
 /* ---- sync (Alg. 2 "make replica": r_i = clone(w)) -------------------------------------
  * replica <- global, bit-exact. */
 int hpsgd_sync_replica(const float *global, float *replica, size_t P, void *hip_stream);

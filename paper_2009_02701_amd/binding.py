@@ -25,6 +25,7 @@ EXPORTS = [
     "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
+    "hpsgd_local_step_all_acc", "hpsgd_merge_grad",
 ]
 ROLE_COUNT = 14
 
@@ -80,6 +81,8 @@ def load_library():
     lib.hpsgd_commit_kernel_params.restype = sz
     lib.hpsgd_probe_mfma_rate.argtypes = [C.c_int, vp, C.c_int, vp, vp, vp]
     lib.hpsgd_delay_us.argtypes = [C.c_uint, vp]
+    lib.hpsgd_local_step_all_acc.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, sz, vp, vp]
+    lib.hpsgd_merge_grad.argtypes = [vp, C.POINTER(vp), C.c_float, C.c_int, sz, vp]
     lib.hpsgd_strerror.argtypes = [C.c_int]
     lib.hpsgd_strerror.restype = C.c_char_p
     _lib = lib
@@ -197,6 +200,14 @@ class Context:
                                              _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
                "hpsgd_local_step_all")
 
+    def local_step_all_acc(self, replicas_in, replicas_out, x, y, lr, loss_out, grad_acc, workspace, stream=None):
+        """local_step_all that also adds every worker's gradient to grad_acc [K, stride]."""
+        _check(self.lib.hpsgd_local_step_all_acc(self._h, _ptr(replicas_in), _ptr(replicas_out),
+                                                 replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
+                                                 _ptr(loss_out), _ptr(grad_acc), grad_acc.stride(0),
+                                                 self._ws_ptr(workspace), _stream(stream)),
+               "hpsgd_local_step_all_acc")
+
     def local_step(self, worker, replica_in, replica_out, x, y, lr, loss_out, workspace, stream=None):
         _check(self.lib.hpsgd_local_step(self._h, int(worker), _ptr(replica_in), _ptr(replica_out),
                                          _ptr(x), _ptr(y), float(lr), _ptr(loss_out),
@@ -259,3 +270,9 @@ def probe_mfma_rate(prec, operands, iterations, result, sink, stream=None):
 def delay_us(microseconds, stream=None):
     """Occupy `stream` for about that long (synthetic synchronisation latency)."""
     _check(load_library().hpsgd_delay_us(int(microseconds), _stream(stream)), "hpsgd_delay_us")
+
+
+def merge_grad(global_, grad_accs, lr, stream=None):
+    """global -= lr * mean_k grad_accs[k] (Eq. 1 as printed)."""
+    _check(load_library().hpsgd_merge_grad(_ptr(global_), _ptr_array(grad_accs), float(lr), len(grad_accs),
+                                           global_.numel(), _stream(stream)), "hpsgd_merge_grad")

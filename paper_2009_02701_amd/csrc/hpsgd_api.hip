@@ -267,8 +267,12 @@ int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float
   } while (0)
 
 // One local step for `groups` workers whose workspace slices start at worker k0.
+// acc (nullable): per-worker gradient accumulators [groups][acc_stride]; the step's gradient
+// is added to them (Alg. 2 "accumulate gradients").  Every gradient then goes through the
+// gradient buffer: no weight matrix is updated in a GEMM epilogue.
 int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, size_t rstride,
-             const void* x, const int32_t* y, float lr, float* loss_out, float* ws, hipStream_t s) {
+             const void* x, const int32_t* y, float lr, float* loss_out, float* ws, hipStream_t s,
+             float* acc = nullptr, size_t acc_stride = 0) {
   const hpsgd_model_desc& d = c->d;
   const int bf = d.prec == HPSGD_BF16_MFMA ? 1 : 0;
   auto reg = [&](const Region& r) { return ws + r.offset + (size_t)k0 * r.stride; };
@@ -284,11 +288,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   // is only updated after the last kernel that reads it (the input-gradient GEMM of its
   // layer) has been issued, so the step may run in place.
   std::vector<char> fused_commit(c->entries.size(), 0);
-  auto commit_view = [&](const std::string& name, const float*& w_in, float*& w_out) {
+  // Where the weight-gradient GEMM of `name` writes: the updated matrix itself (epilogue
+  // W_out = W_in - lr * dW), or, when gradients are accumulated as well, the gradient buffer.
+  struct WgradTarget { float* C; long sC; int epi; const float* aux; };
+  auto wgrad_target = [&](const std::string& name) -> WgradTarget {
     const size_t o = c->off(name);
-    w_in = rin + o;
-    w_out = rout + o;
+    if (acc) return WgradTarget{grad + o, sG, EPI_STORE, nullptr};
     fused_commit[c->find(name)] = 1;
+    return WgradTarget{rout + o, sR, EPI_COMMIT, rin + o};
   };
 
   if (d.kind == HPSGD_MLP) {
@@ -330,11 +337,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                  EPI_RELU_MASK, a_prev, s_prev));
       }
       // W' = W - lr * delta^T a_prev
-      const float* w_in;
-      float* w_out;
-      commit_view(p + ".W", w_in, w_out);
+      const WgradTarget wt = wgrad_target(p + ".W");
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
-               s_prev, 0, w_out, dims[i], sR, EPI_COMMIT, w_in, sR, 0, lr));
+               s_prev, 0, wt.C, dims[i], wt.sC, wt.epi, wt.aux, sR, 0, lr));
       HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + c->off(p + ".b"), sG, B, dims[i + 1],
                             groups, s));
       if (i > 0) delta = dprev;
@@ -514,11 +519,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                 lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
       const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
       const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
-      const float* w_in;
-      float* w_out;
-      commit_view("head.W", w_in, w_out);
-      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, w_out, H, sR,
-                EPI_COMMIT, w_in, sR, vdT, vhT, lr));
+      const WgradTarget wt = wgrad_target("head.W");
+      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
+                wt.epi, wt.aux, sR, vdT, vhT, lr));
       HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
                                     grad + ob, sG, nrows, classes, groups, s));
     } else {
@@ -562,11 +565,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
                     EPI_STORE, nullptr, 0, vl, vw));
         }
-        const float* w_in;
-        float* w_out;
-        commit_view("head.W", w_in, w_out);
-        TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, w_out, H, sR,
-                  EPI_COMMIT, w_in, sR, va, vb, lr));
+        const WgradTarget wt = wgrad_target("head.W");
+        TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
+                  wt.epi, wt.aux, sR, va, vb, lr));
         HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
       }
     }
@@ -725,14 +726,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           return HPSGD_EHIP;
         TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
       } else {
-        const float* w_in;
-        float* w_out;
-        commit_view(p + ".W_ih", w_in, w_out);
-        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, w_out, win,
-                  sR, EPI_COMMIT, w_in, sR, v_dgxT, v_xT, lr));
-        commit_view(p + ".W_hh", w_in, w_out);
-        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, w_out, H, sR, EPI_COMMIT,
-                  w_in, sR, v_dghT, v_hsT, lr));
+        const WgradTarget wi = wgrad_target(p + ".W_ih");
+        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
+                  wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr));
+        const WgradTarget wh = wgrad_target(p + ".W_hh");
+        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
+                  wh.aux, sR, v_dghT, v_hsT, lr));
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
       HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
@@ -759,7 +758,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const size_t lo = c->entries[e].offset;
     while (e < c->entries.size() && !fused_commit[e]) ++e;
     const size_t hi = e < c->entries.size() ? c->entries[e].offset : c->P;
-    HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
+    if (acc)
+      HIP_TRY(launch_commit_acc(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, acc + lo, acc_stride, lr,
+                                groups, hi - lo, s));
+    else
+      HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
     c->last_commit_params += hi - lo;
   }
   return HPSGD_OK;
@@ -841,6 +844,23 @@ int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replic
                   (float*)workspace, (hipStream_t)hip_stream);
 }
 
+int hpsgd_local_step_all_acc(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,
+                             size_t replica_stride, const void* x, const int32_t* y, float lr,
+                             float* loss_out, float* grad_acc, size_t acc_stride, void* workspace,
+                             void* hip_stream) {
+  if (!ctx) return HPSGD_EINVAL;
+  TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
+  if (!grad_acc) return HPSGD_EINVAL;
+  if (((uintptr_t)grad_acc & 15) != 0 || (ctx->K > 1 && (acc_stride < ctx->P || (acc_stride & 3) != 0)))
+    return HPSGD_EALIGN;
+  const size_t span = ((size_t)(ctx->K - 1) * acc_stride + ctx->P) * sizeof(float);
+  const size_t rspan = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
+  if (overlaps(grad_acc, span, replicas_in, rspan) || overlaps(grad_acc, span, replicas_out, rspan))
+    return HPSGD_EALIAS;
+  return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
+                  (float*)workspace, (hipStream_t)hip_stream, grad_acc, acc_stride);
+}
+
 int hpsgd_local_step(hpsgd_ctx* ctx, int worker, const float* replica_in, float* replica_out,
                      const void* x, const int32_t* y, float lr, float* loss_out, void* workspace,
                      void* hip_stream) {
@@ -896,6 +916,23 @@ int hpsgd_merge(float* global, const float* const* replicas, const float* snapsh
     return HPSGD_EALIAS;
   return launch_merge(global, pk, snapshot, K, P, (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK
                                                                                           : HPSGD_EHIP;
+}
+
+int hpsgd_merge_grad(float* global, const float* const* grad_accs, float lr, int K, size_t P,
+                     void* hip_stream) {
+  if (K < 1 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;
+  if (P == 0) return HPSGD_OK;
+  if (!global || !grad_accs) return HPSGD_EINVAL;
+  if (!aligned16(global)) return HPSGD_EALIGN;
+  PtrPack pk;
+  for (int k = 0; k < K; ++k) {
+    if (!grad_accs[k]) return HPSGD_EINVAL;
+    if (!aligned16(grad_accs[k])) return HPSGD_EALIGN;
+    if (overlaps(global, P * sizeof(float), grad_accs[k], P * sizeof(float))) return HPSGD_EALIAS;
+    pk.p[k] = const_cast<float*>(grad_accs[k]);
+  }
+  return launch_merge_grad(global, pk, lr, K, P, (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK
+                                                                                        : HPSGD_EHIP;
 }
 
 int hpsgd_sync_all(const float* global, float* const* replicas, int K, float* snapshot, size_t P,

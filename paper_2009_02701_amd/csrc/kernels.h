@@ -21,6 +21,9 @@ hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, 
 hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s);
 // p[g*stride + i] = 0 for i < n (p 16-byte aligned, stride a multiple of 4)
+hipError_t launch_commit_acc(const float* in, float* out, size_t stride, const float* grad, size_t grad_stride,
+                             float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s);
+hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K, size_t P, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s);
 // p[g*stride + r*ld + c] = 0 for r < rows, c < cols (4-byte words)
 hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t stride, int groups,

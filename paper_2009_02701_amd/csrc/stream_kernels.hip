@@ -176,6 +176,71 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
   return hipGetLastError();
 }
 
+// out[k][j] = in[k][j] - lr * grad[k][j];  acc[k][j] += grad[k][j]  (Alg. 2: update the replica and
+// accumulate the gradient in one pass, 20 B/param)
+__global__ void __launch_bounds__(kThreads)
+commit_acc_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+                  size_t grad_stride, float* __restrict__ acc, size_t acc_stride, float lr, size_t P) {
+  const size_t k = blockIdx.y;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < P; i += (size_t)gridDim.x * kThreads) {
+    const float g = grad[k * grad_stride + i];
+    out[k * stride + i] = in[k * stride + i] - lr * g;
+    acc[k * acc_stride + i] += g;
+  }
+}
+
+hipError_t launch_commit_acc(const float* in, float* out, size_t stride, const float* grad, size_t grad_stride,
+                             float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  size_t blocks = (P + kThreads - 1) / kThreads;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(commit_acc_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
+                     grad_stride, acc, acc_stride, lr, P);
+  return hipGetLastError();
+}
+
+// global[j] -= lr * (1/K) * sum_k acc_k[j], the sum in worker order (Eq. 1 as printed)
+template <int KT>
+__global__ void __launch_bounds__(kThreads)
+merge_grad_kernel(float* global, PtrPack acc, int Krt, float scale, size_t n4, size_t P) {
+  const int K = KT > 0 ? KT : Krt;
+  const size_t stride = (size_t)gridDim.x * kThreads;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += stride) {
+    f4v t = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(acc.p[0]) + i);
+#pragma unroll
+    for (int k = 1; k < K; ++k) t += __builtin_nontemporal_load(reinterpret_cast<const f4v*>(acc.p[k]) + i);
+    const f4v g = __builtin_nontemporal_load(reinterpret_cast<const f4v*>(global) + i);
+    __builtin_nontemporal_store(g - t * scale, reinterpret_cast<f4v*>(global) + i);
+  }
+  if (blockIdx.x == 0) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    if (j < P) {
+      float t = acc.p[0][j];
+      for (int k = 1; k < K; ++k) t += acc.p[k][j];
+      global[j] = global[j] - t * scale;
+    }
+  }
+}
+
+hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K, size_t P, hipStream_t s) {
+  if (P == 0) return hipSuccess;
+  const size_t n4 = P / 4;
+  const int blocks = onepass_blocks(n4);
+  const float scale = lr / (float)K;
+#define HPSGD_MG_CASE(KT) \
+  hipLaunchKernelGGL(merge_grad_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, accs, K, scale, n4, P)
+  switch (K) {
+    case 1: HPSGD_MG_CASE(1); break;
+    case 2: HPSGD_MG_CASE(2); break;
+    case 4: HPSGD_MG_CASE(4); break;
+    case 8: HPSGD_MG_CASE(8); break;
+    case 16: HPSGD_MG_CASE(16); break;
+    default: HPSGD_MG_CASE(0); break;
+  }
+#undef HPSGD_MG_CASE
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------- fill
 // p[g*stride + i] = 0 for i < n, g < groups
 __global__ void __launch_bounds__(kThreads) fill_zero_kernel(float* p, size_t n4, size_t n, size_t stride) {

@@ -133,6 +133,31 @@ class Trainer:
             self.ovl_round(t, lr, record_loss)
         self.ovl_drain()
 
+    def s_seq_grad(self, lr: float, gamma: int, rounds: int, record_loss=True):
+        """s_seq with the synchronisation in gradient form (Eq. 1 as printed): the workers
+        accumulate their gradients over a round, the global model moves by -lr * their mean."""
+        st = self.stream_a
+        st.wait_stream(torch.cuda.current_stream())
+        if self.ws[0] is None:
+            self.ws[0] = self.ctx.new_workspace(self.dev)
+        with torch.cuda.stream(st):
+            acc = torch.zeros_like(self.R[0])
+        step = 0
+        for _ in range(rounds):
+            self.sync_all(0, st)
+            with torch.cuda.stream(st):
+                acc.zero_()
+            for _ in range(gamma):
+                self.gather(step, st)
+                self.ctx.local_step_all_acc(self.R[0], self.R[0], self.xb, self.yb, lr, self.loss, acc,
+                                            self.ws[0], stream=st)
+                if record_loss:
+                    with torch.cuda.stream(st):
+                        self.losses.append(self.loss.clone())
+                step += 1
+            hb.merge_grad(self.G[:self.P], [acc[k, :self.P] for k in range(self.K)], lr, stream=st)
+        st.synchronize()
+
     def s_async(self, lr: float, epochs: int, sync_delay_us: int = 0, record_loss=False):
         """Alg. 2 + Alg. 3 with the status check made at run time: after every local step the
         training side (stream A) asks, without waiting, whether the synchronising side

@@ -118,6 +118,16 @@ def test_gather_all_and_aux_stream_reject_bad_arguments():
     assert lib.hpsgd_timer_read(ctx._h, 99, None, None) == 1
     assert lib.hpsgd_role_name(99) is None and lib.hpsgd_role_name(3) == b"gemm_recurrent_bwd"
     assert lib.hpsgd_commit_kernel_params(None) == 0 and lib.hpsgd_commit_kernel_params(ctx._h) == 0
+    mg = lib.hpsgd_merge_grad
+    ok = (vp * 2)(0x1000, 0x2000)
+    assert mg(0x10000, ok, 0.1, 0, 64, None) == 1                        # K < 1
+    assert mg(0x10000, ok, 0.1, 2, 0, None) == 0                         # P == 0: no-op
+    assert mg(None, ok, 0.1, 2, 64, None) == 1
+    assert mg(0x10004, ok, 0.1, 2, 64, None) == 3                        # misaligned global
+    assert mg(0x10000, (vp * 2)(0x1000, 0x2004), 0.1, 2, 64, None) == 3  # misaligned accumulator
+    assert mg(0x1000, ok, 0.1, 2, 64, None) == 4                         # accumulator aliases global
+    assert lib.hpsgd_local_step_all_acc(None, 0x1000, 0x1000, 64, 0x2000, 0x3000, 0.1, None, 0x4000, 64,
+                                        0x5000, None) == 1
     assert lib.hpsgd_delay_us(2000000, None) == 1                        # beyond the one-second cap
     assert lib.hpsgd_delay_us(0, None) == 0                              # nothing to launch
     probe = lib.hpsgd_probe_mfma_rate

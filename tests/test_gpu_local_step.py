@@ -130,6 +130,9 @@ def _schedule_parity(cfg, kind, tol, **kw):
     if kind == "seq":
         tr.s_seq(lr, kw["gamma"], kw["rounds"])
         want, losses = oc.s_seq(init, batch_fn, K, lr, kw["gamma"], kw["rounds"])
+    elif kind == "seq_grad":
+        tr.s_seq_grad(lr, kw["gamma"], kw["rounds"])
+        want, losses = oc.s_seq_grad(init, batch_fn, K, lr, kw["gamma"], kw["rounds"])
     else:
         tr.s_ovl(lr, kw["rounds"])
         want, losses = oc.s_ovl(init, batch_fn, K, lr, kw["rounds"])
@@ -150,6 +153,18 @@ def _schedule_parity(cfg, kind, tol, **kw):
                                    ("ovl", dict(rounds=3))])
 def test_config1_tiny_gru_schedules(sched):
     _schedule_parity(wl.CONFIGS["tiny_gru"], sched[0], TOL_FP32, **sched[1])
+
+
+@pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "mlp"])
+def test_gradient_form_synchronisation(name):
+    """Eq. 1 as printed: accumulated gradients (hpsgd_local_step_all_acc) and hpsgd_merge_grad
+    against the oracle's gradient-form schedule, two local steps per round."""
+    _schedule_parity(wl.CONFIGS[name], "seq_grad", TOL_FP32, gamma=2, rounds=2)
+
+
+def test_gradient_form_synchronisation_bf16():
+    cfg = BF16["lm_nt_bf16_tiles"]
+    _schedule_parity(cfg, "seq_grad", TOL_BF16, gamma=2, rounds=2)
 
 
 @pytest.mark.parametrize("sched", [("seq", dict(gamma=1, rounds=3)), ("ovl", dict(rounds=3))])
