@@ -184,24 +184,29 @@ __device__ __forceinline__ void staged_contraction(const float* __restrict__ Wba
 // (a CU accepts only ~64 bytes of vector loads per clock: issuing a workgroup's whole operand
 // set up front keeps its waves busy issuing for microseconds before the first MFMA).
 // Registers hold 4 slabs in flight; LDS holds 2 (one barrier per slab).  lds: 2*RT*68 words.
-// RB: 16-row blocks of activations per workgroup (2, or 1 when that is what it takes to put
-// two workgroups on every CU: their barrier and load phases then cover each other).
-template <int NQ, bool BF16, int RB = 2>
+// RB: 16-row blocks of activations per workgroup.  NW: waves per workgroup, 4 or 8.  The
+// contraction index of a slab is always split four ways (wave & 3 takes the 16-word chunks
+// wave & 3, + 4, ..); with 8 waves the two halves of the workgroup take one row block each, so
+// every SIMD holds two waves and one's LDS and barrier latency hides behind the other's MFMAs
+// without loading anything twice.  W: slab width in words (64 or 128; lds: 2*RT*(W+4) words).
+template <int NQ, bool BF16, int RB = 2, int NW = 4, int W = 64>
 __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wbase, long w_qstride,
                                                     const float* __restrict__ Abase, int KD,
                                                     int rows_valid, float* __restrict__ lds,
-                                                    floatx4 (&acc)[RB][NQ]) {
-  constexpr int W = 64, RT = 16 * NQ + 16 * RB, UR = W / 4, UPT = RT * UR / 256, P = W + 4;
+                                                    floatx4 (&acc)[RB * 4 / NW][NQ]) {
+  constexpr int NT = 64 * NW, RBW = RB * 4 / NW, NC = W / 64;
+  constexpr int RT = 16 * NQ + 16 * RB, UR = W / 4, UPT = RT * UR / NT, P = W + 4;
   constexpr int PD = 3, RS = PD + 1;  // prefetch distance in slabs, register sets
-  static_assert(RT * UR % 256 == 0, "slab shape");
+  static_assert(RT * UR % NT == 0 && RB * 4 % NW == 0 && (W == 64 || W == 128), "slab shape");
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
   const int lr = lane & 15, lg = lane >> 4;
   const int nslab = (KD + W - 1) / W;
   const float* rowp[UPT];
   bool rowok[UPT];
 #pragma unroll
   for (int i = 0; i < UPT; ++i) {
-    const int row = (tid + i * 256) / UR;
+    const int row = (tid + i * NT) / UR;
     if (row < 16 * NQ) {
       rowp[i] = Wbase + (row >> 4) * w_qstride + (long)(row & 15) * KD;
       rowok[i] = true;
@@ -228,7 +233,7 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
   auto sstore = [&](int set, int buf) {
 #pragma unroll
     for (int i = 0; i < UPT; ++i) {
-      const int u = tid + i * 256;
+      const int u = tid + i * NT;
       const bool ok = cok[set] && rowok[i];
       const float4 v = regs[set][i];  // (selected per component: a select between two float4
                                       // objects would keep the whole register array in memory)
@@ -238,7 +243,6 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
   };
 #pragma unroll
   for (int u = 0; u < PD; ++u) issue(u, u);
-  const int kcol = 16 * wave + 4 * lg;  // each wave takes one 16-word chunk of a slab
   for (int s0 = 0; s0 < nslab; s0 += RS) {
 #pragma unroll
     for (int u = 0; u < RS; ++u) {  // slab s0 + u: register set u, LDS buffer u & 1
@@ -250,36 +254,41 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
       __syncthreads();
       __builtin_amdgcn_sched_barrier(0);
       issue((u + PD) % RS, s0 + u + PD);  // into the set stored one slab ago
-      float4 a[RB], w[NQ];
 #pragma unroll
-      for (int q = 0; q < NQ; ++q)
-        w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
+      for (int ci = 0; ci < NC; ++ci) {
+        const int kcol = 16 * (kw + 4 * ci) + 4 * lg;
+        float4 a[RBW], w[NQ];
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-        a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * P + kcol]);
-      if (BF16) {
+        for (int q = 0; q < NQ; ++q)
+          w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
 #pragma unroll
-        for (int rb = 0; rb < RB; ++rb)
+        for (int rb = 0; rb < RBW; ++rb)
+          a[rb] = *reinterpret_cast<const float4*>(
+              &lds[(b * RT + 16 * NQ + (rsel * RBW + rb) * 16 + lr) * P + kcol]);
+        if (BF16) {
 #pragma unroll
-          for (int q = 0; q < NQ; ++q) {
-            typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-            acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[rb]),
-                                                                 __builtin_bit_cast(bf16x8_t, w[q]),
-                                                                 acc[rb][q], 0, 0, 0);
-          }
-      } else {
-        // the four contraction steps outermost: consecutive MFMAs update different
-        // accumulators; every accumulator still receives its steps in order
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-#pragma unroll
-          for (int rb = 0; rb < RB; ++rb)
+          for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-              const float av = e == 0 ? a[rb].x : e == 1 ? a[rb].y : e == 2 ? a[rb].z : a[rb].w;
-              const float wv = e == 0 ? w[q].x : e == 1 ? w[q].y : e == 2 ? w[q].z : w[q].w;
-              acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wv, acc[rb][q], 0, 0, 0);
+              typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+              acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[rb]),
+                                                                   __builtin_bit_cast(bf16x8_t, w[q]),
+                                                                   acc[rb][q], 0, 0, 0);
             }
+        } else {
+          // the four contraction steps outermost: consecutive MFMAs update different
+          // accumulators; every accumulator still receives its steps in order
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+#pragma unroll
+            for (int rb = 0; rb < RBW; ++rb)
+#pragma unroll
+              for (int q = 0; q < NQ; ++q) {
+                const float av = e == 0 ? a[rb].x : e == 1 ? a[rb].y : e == 2 ? a[rb].z : a[rb].w;
+                const float wv = e == 0 ? w[q].x : e == 1 ? w[q].y : e == 2 ? w[q].z : w[q].w;
+                acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(av, wv, acc[rb][q], 0, 0, 0);
+              }
+        }
       }
     }
   }
@@ -287,15 +296,17 @@ __device__ __forceinline__ void rolling_contraction(const float* __restrict__ Wb
 }
 
 // Forward step: h_out = cell(gx_t, h_prev W_hh^T + b_hh, h_prev); saves r|z|n|q of the step.
-template <int RB>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+template <int RB, int NW, int W>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
                            const float* __restrict__ gx_t, long s_gx, const float* __restrict__ h_prev,
                            float* __restrict__ h_out, long s_hs, float* __restrict__ sv_t, long s_sv,
                            int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * (48 + 16 * RB) * 68;  // [4][3 * RB][4][64]
+  float* red = staged_lds;  // [4][3 * RB][4][64], over the slab buffers once the contraction is done
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
+  constexpr int RBW = RB * 4 / NW;  // row blocks per wave
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
   __builtin_amdgcn_s_setprio(3);
@@ -308,40 +319,42 @@ gru_fwd_step_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_
   // the epilogue's own inputs first: they arrive during the matrix work
   const float* bh = b_hh + g * s_rep;
   const int j = j0 + lr;
-  float gxv[RB][3], hpv[RB], bias[3];
+  float gxv[RBW][3], hpv[RBW], bias[3];
 #pragma unroll
   for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
+  for (int rb = 0; rb < RBW; ++rb) {
     // unconditional loads from a row clamped into the batch (a select on a loaded value
     // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
-    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
+    const int row = min(r0 + (rsel * RBW + rb) * 16 + 4 * lg + kw, B - 1);
     const float* gxr = gx_t + g * s_gx + (long)row * 3 * H;
 #pragma unroll
     for (int q = 0; q < 3; ++q) gxv[rb][q] = gxr[q * H + j];
     hpv[rb] = hp[(long)row * H + j];
   }
-  floatx4 acc[RB][3];
+  floatx4 acc[RBW][3];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q) acc[rb][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
-  rolling_contraction<3, false, RB>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
+  rolling_contraction<3, false, RB, NW, W>(W_hh + g * s_rep + (long)j0 * H, (long)H * H, hp + (long)r0 * H, H, B - r0,
                                 staged_lds, acc);
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
     for (int q = 0; q < 3; ++q)
 #pragma unroll
-      for (int v = 0; v < 4; ++v) red[((wave * 3 * RB + rb * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
+      for (int v = 0; v < 4; ++v)
+        red[((kw * 3 * RB + (rsel * RBW + rb) * 3 + q) * 4 + v) * 64 + lane] = acc[rb][q][v];
   __syncthreads();
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
+  for (int rb = 0; rb < RBW; ++rb) {
+    const int rbg = rsel * RBW + rb;
+    const int row = r0 + rbg * 16 + 4 * lg + kw;
     float gh[3];
 #pragma unroll
     for (int q = 0; q < 3; ++q) {
-      const int o = ((rb * 3 + q) * 4 + wave) * 64 + lane;
+      const int o = ((rbg * 3 + q) * 4 + kw) * 64 + lane;
       gh[q] = ((red[o] + red[o + 3 * RB * 256]) + (red[o + 6 * RB * 256] + red[o + 9 * RB * 256])) + bias[q];
     }
     if (row < B) {
@@ -366,26 +379,28 @@ static constexpr int TTP = 40;  // pitch (bf16) of a staged transposed-output ro
 static constexpr size_t kFwdBf16Lds = (2 * 80 * (SKB + 4) + 4 * 6 * 4 * 64) * sizeof(float);
 static constexpr size_t kBwdBf16Lds = (2 * 48 * (SKB + 4) + 4 * 2 * 4 * 64) * sizeof(float);
 
-// Two workgroups per CU hide each other's barrier and load phases: when 32-row tiles give
-// fewer workgroups than that, 16-row tiles are used.
-static bool step_rows16(int B, int H, int groups) {
-  return B > 16 && (long)(H / FJ) * ((B + FR - 1) / FR) * groups < 2 * 256;
+// Up to one workgroup per CU: 8 waves per workgroup and 128-word slabs (two waves on every
+// SIMD cover each other's LDS and barrier latency; 84 KB of LDS, one workgroup per CU).
+// More workgroups than CUs: 4 waves and 64-word slabs, so that several fit on a CU.
+static bool step_wide(int B, int H, int groups) {
+  return (long)(H / FJ) * ((B + FR - 1) / FR) * groups <= 256;
 }
 
-template <int RB>
+template <int RB, int NW, int W>
 static hipError_t launch_fwd_rb(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t, long s_gx,
                                 const float* h_prev, float* h_out, long s_hs, float* sv_t, long s_sv, int B,
                                 int H, int groups, hipStream_t s) {
-  constexpr size_t lds = (2 * (48 + 16 * RB) * 68 + 4 * 3 * RB * 4 * 64) * sizeof(float);
+  constexpr size_t slabs = 2 * (48 + 16 * RB) * (W + 4), redn = 4 * 3 * RB * 4 * 64;
+  constexpr size_t lds = (slabs > redn ? slabs : redn) * sizeof(float);
   static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
   if (!ready) {
-    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_kernel<RB>,
+    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_step_kernel<RB, NW, W>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     ready = true;
   }
   dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
-  hipLaunchKernelGGL(gru_fwd_step_kernel<RB>, grid, dim3(256), lds, s, W_hh, b_hh, s_rep, gx_t, s_gx, h_prev,
+  hipLaunchKernelGGL((gru_fwd_step_kernel<RB, NW, W>), grid, dim3(64 * NW), lds, s, W_hh, b_hh, s_rep, gx_t, s_gx, h_prev,
                      h_out, s_hs, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
 }
@@ -393,24 +408,28 @@ static hipError_t launch_fwd_rb(const float* W_hh, const float* b_hh, long s_rep
 hipError_t launch_gru_fwd_step(const float* W_hh, const float* b_hh, long s_rep, const float* gx_t,
                                       long s_gx, const float* h_prev, float* h_out, long s_hs,
                                       float* sv_t, long s_sv, int B, int H, int groups, hipStream_t s) {
-  return step_rows16(B, H, groups)
-             ? launch_fwd_rb<1>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups, s)
-             : launch_fwd_rb<2>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H, groups, s);
+  return step_wide(B, H, groups)
+             ? launch_fwd_rb<2, 8, 128>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H,
+                                        groups, s)
+             : launch_fwd_rb<2, 4, 64>(W_hh, b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, sv_t, s_sv, B, H,
+                                       groups, s);
 }
 
 // Backward step.  WT is W_hh transposed: WT[j][n] = W_hh[n][j], row pitch 3H (unit-stride along
 // the contraction).  D holds dh_{t+1} * z_{t+1} on entry (or the head's gradient at the last
 // step) and dh_t * z_t on exit.  dgh_next == nullptr at the last step (no recurrent term yet).
-template <int RB>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 2)))
+template <int RB, int NW, int W>
+__global__ void __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __restrict__ dgh_next,
                            long s_dg, float* __restrict__ D, long s_D, const float* __restrict__ above,
                            long s_above, const float* __restrict__ sv_t, long s_sv,
                            const float* __restrict__ h_prev, long s_hs, float* __restrict__ dgx_t,
                            float* __restrict__ dgh_t, int B, int H, int groups) {
   extern __shared__ __attribute__((aligned(16))) float staged_lds[];
-  float* red = staged_lds + 2 * (16 + 16 * RB) * 68;  // [4][RB][4][64]
+  float* red = staged_lds;  // [4][RB][4][64], over the slab buffers once the contraction is done
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
+  constexpr int RBW = RB * 4 / NW;  // row blocks per wave
   // the recurrence is the critical path: its waves issue ahead of any throughput kernel
   // (weight-gradient GEMMs, merge) that shares the SIMD
   __builtin_amdgcn_s_setprio(3);
@@ -421,12 +440,12 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   const int j0 = tx * FJ, r0 = ty * FRB;
   const int H3 = 3 * H;
   const int j = j0 + lr;
-  float r_[RB], z_[RB], n_[RB], q_[RB], hp_[RB], dh_[RB], ab_[RB];
+  float r_[RBW], z_[RBW], n_[RBW], q_[RBW], hp_[RBW], dh_[RBW], ab_[RBW];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
+  for (int rb = 0; rb < RBW; ++rb) {
     // unconditional loads from a row clamped into the batch (a select on a loaded value
     // would make the wave wait for it here, ahead of the slab loads); rows >= B are not stored
-    const int row = min(r0 + rb * 16 + 4 * lg + wave, B - 1);
+    const int row = min(r0 + (rsel * RBW + rb) * 16 + 4 * lg + kw, B - 1);
     const long e = (long)row * H + j;
     const float* sv = sv_t + g * s_sv + (long)row * 4 * H;
     r_[rb] = sv[j];
@@ -437,21 +456,22 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
     dh_[rb] = D[g * s_D + e];
     ab_[rb] = above ? above[g * s_above + e] : 0.f;
   }
-  floatx4 acc[RB][1];
+  floatx4 acc[RBW][1];
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) acc[rb][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  for (int rb = 0; rb < RBW; ++rb) acc[rb][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
   if (dgh_next)
-    rolling_contraction<1, false, RB>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
+    rolling_contraction<1, false, RB, NW, W>(WT + g * s_wt + (long)j0 * H3, 0, dgh_next + g * s_dg + (long)r0 * H3, H3,
                                   B - r0, staged_lds, acc);
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb)
+  for (int rb = 0; rb < RBW; ++rb)
 #pragma unroll
-    for (int v = 0; v < 4; ++v) red[((wave * RB + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
+    for (int v = 0; v < 4; ++v) red[((kw * RB + rsel * RBW + rb) * 4 + v) * 64 + lane] = acc[rb][0][v];
   __syncthreads();
 #pragma unroll
-  for (int rb = 0; rb < RB; ++rb) {
-    const int row = r0 + rb * 16 + 4 * lg + wave;
-    const int o = (rb * 4 + wave) * 64 + lane;
+  for (int rb = 0; rb < RBW; ++rb) {
+    const int rbg = rsel * RBW + rb;
+    const int row = r0 + rbg * 16 + 4 * lg + kw;
+    const int o = (rbg * 4 + kw) * 64 + lane;
     const float rec = (red[o] + red[o + RB * 256]) + (red[o + 2 * RB * 256] + red[o + 3 * RB * 256]);
     if (row < B) {
       const long e = (long)row * H + j;
@@ -476,14 +496,22 @@ gru_bwd_step_kernel(const float* __restrict__ WT, long s_wt, const float* __rest
   }
 }
 
-template <int RB>
+template <int RB, int NW, int W>
 static hipError_t launch_bwd_rb(const float* WT, long s_wt, const float* dgh_next, long s_dg, float* D, long s_D,
                                 const float* above, long s_above, const float* sv_t, long s_sv,
                                 const float* h_prev, long s_hs, float* dgx_t, float* dgh_t, int B, int H,
                                 int groups, hipStream_t s) {
-  constexpr size_t lds = (2 * (16 + 16 * RB) * 68 + 4 * RB * 4 * 64) * sizeof(float);
+  constexpr size_t slabs = 2 * (16 + 16 * RB) * (W + 4), redn = 4 * RB * 4 * 64;
+  constexpr size_t lds = (slabs > redn ? slabs : redn) * sizeof(float);
+  static bool ready = false;  // allow the dynamic LDS allocation above 64 KB once
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gru_bwd_step_kernel<RB, NW, W>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
   dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
-  hipLaunchKernelGGL(gru_bwd_step_kernel<RB>, grid, dim3(256), lds, s, WT, s_wt, dgh_next, s_dg, D, s_D, above,
+  hipLaunchKernelGGL((gru_bwd_step_kernel<RB, NW, W>), grid, dim3(64 * NW), lds, s, WT, s_wt, dgh_next, s_dg, D, s_D, above,
                      s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups);
   return hipGetLastError();
 }
@@ -492,11 +520,11 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                       float* D, long s_D, const float* above, long s_above,
                                       const float* sv_t, long s_sv, const float* h_prev, long s_hs,
                                       float* dgx_t, float* dgh_t, int B, int H, int groups, hipStream_t s) {
-  return step_rows16(B, H, groups)
-             ? launch_bwd_rb<1>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t,
-                                dgh_t, B, H, groups, s)
-             : launch_bwd_rb<2>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs, dgx_t,
-                                dgh_t, B, H, groups, s);
+  return step_wide(B, H, groups)
+             ? launch_bwd_rb<2, 8, 128>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs,
+                                        dgx_t, dgh_t, B, H, groups, s)
+             : launch_bwd_rb<2, 4, 64>(WT, s_wt, dgh_next, s_dg, D, s_D, above, s_above, sv_t, s_sv, h_prev, s_hs,
+                                       dgx_t, dgh_t, B, H, groups, s);
 }
 
 // ---------------------------------------------------------------------------- bf16 variants
