@@ -77,6 +77,97 @@ struct GemmNtDesc {
   int M, N, Kd, groups;
 };
 
+// Workgroup -> (group, tile).  Returns false for the padding of the last round of slow tiles.
+__device__ __forceinline__ bool nt_tile(const GemmNtDesc& d, int& g, int& tile_m, int& tile_n) {
+  // Tile order.  Workgroup i runs on XCD i % 8 and every XCD has its own L2.  The dimension
+  // with more tiles ("slow") is dealt out to the XCDs (tile s goes to XCD s % 8), and on an
+  // XCD consecutive workgroups sweep the other ("fast") dimension for a fixed slow tile:
+  // the slow operand's tile is then fetched from memory by one L2 only and is reused at once
+  // by all fast tiles, while the fast operand (the smaller one) stays resident in every L2.
+  {
+    const int tm = (d.M + NBM - 1) / NBM, tn = (d.N + NBN - 1) / NBN;
+    const bool slow_is_n = tn >= tm;
+    const int ts = slow_is_n ? tn : tm, tf = slow_is_n ? tm : tn;
+    const int s8 = (ts + 7) >> 3;
+    const int c = blockIdx.x & 7, li = blockIdx.x >> 3;
+    const int f = li % tf, sl = (li / tf) % s8;
+    g = li / (tf * s8);
+    const int st = c + 8 * sl;
+    if (st >= ts) return false;
+    tile_m = slow_is_n ? f : st;
+    tile_n = slow_is_n ? st : f;
+  }
+  return true;
+}
+
+// Epilogue of both NT kernels: accumulators -> LDS tile -> coalesced 16-byte stores.
+template <bool COMMIT>
+__device__ __forceinline__ void nt_epilogue(const GemmNtDesc& d, floatx16 (&acc)[2][2], unsigned char* nt_smem,
+                                            int g, int m0, int n0) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int lrow = lane & 31, lk = lane >> 5;
+  // Epilogue through LDS (the operand buffers are free after the last barrier): the
+  // accumulators are laid out as the 128 x 128 tile, then every wave instruction moves two
+  // whole 512-byte row segments, so the stores (and the loads of W in the commit form, all
+  // requested before the first is used) are fully coalesced 16-byte accesses.
+  float* C = d.C + (long)g * d.strideC;
+  const float* bias = d.bias ? d.bias + (long)g * d.strideBias : nullptr;
+  float* sC = reinterpret_cast<float*>(nt_smem);
+  constexpr int CP = NBN + 4;  // pitch in floats
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        sC[(wm * 64 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + wn * 64 + j * 32 + lrow] = acc[i][j][v];
+  __syncthreads();
+  const int c4 = (tid & 31) << 2, rbase = tid >> 5;
+  const int col = n0 + c4;
+  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
+                   (!COMMIT || (((uintptr_t)d.win & 15) == 0 && (d.strideWin & 3) == 0));
+  if (vec && col + 3 < d.N) {
+    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!COMMIT && bias) bv = make_float4(bias[col], bias[col + 1], bias[col + 2], bias[col + 3]);
+    float4 w[COMMIT ? 16 : 1];
+    if (COMMIT) {
+      const float* W = d.win + (long)g * d.strideWin;
+#pragma unroll
+      for (int p = 0; p < 16; ++p) {
+        const int row = min(m0 + rbase + 8 * p, d.M - 1);  // clamped: not stored when outside
+        w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < 16; ++p) {
+      const int rl = rbase + 8 * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      const float4 a = *reinterpret_cast<const float4*>(&sC[rl * CP + c4]);
+      float4 o;
+      if (COMMIT) {
+        const float4 wv = w[COMMIT ? p : 0];
+        o = make_float4(wv.x - d.lr * a.x, wv.y - d.lr * a.y, wv.z - d.lr * a.z, wv.w - d.lr * a.w);
+      } else {
+        o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
+      }
+      *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+    }
+  } else {
+    const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
+    for (int p = 0; p < 16; ++p) {
+      const int rl = rbase + 8 * p, row = m0 + rl;
+      if (row >= d.M) continue;
+      for (int e = 0; e < 4; ++e) {
+        if (col + e >= d.N) break;
+        const long off = (long)row * d.ldc + col + e;
+        const float a = sC[rl * CP + c4 + e];
+        C[off] = COMMIT ? W[off] - d.lr * a : a + (bias ? bias[col + e] : 0.f);
+      }
+    }
+  }
+}
+
 // COMMIT: the epilogue is C = win - lr * acc; the tile of win is requested before the
 // contraction starts, so that the epilogue does not wait for it.
 template <typename TA, typename TB, bool COMMIT>
@@ -90,25 +181,8 @@ gemm_bf16_nt_kernel(GemmNtDesc d) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int lrow = lane & 31, lk = lane >> 5;
-  // Tile order.  Workgroup i runs on XCD i % 8 and every XCD has its own L2.  The dimension
-  // with more tiles ("slow") is dealt out to the XCDs (tile s goes to XCD s % 8), and on an
-  // XCD consecutive workgroups sweep the other ("fast") dimension for a fixed slow tile:
-  // the slow operand's tile is then fetched from memory by one L2 only and is reused at once
-  // by all fast tiles, while the fast operand (the smaller one) stays resident in every L2.
   int g, tile_m, tile_n;
-  {
-    const int tm = (d.M + NBM - 1) / NBM, tn = (d.N + NBN - 1) / NBN;
-    const bool slow_is_n = tn >= tm;
-    const int ts = slow_is_n ? tn : tm, tf = slow_is_n ? tm : tn;
-    const int s8 = (ts + 7) >> 3;
-    const int c = blockIdx.x & 7, li = blockIdx.x >> 3;
-    const int f = li % tf, sl = (li / tf) % s8;
-    g = li / (tf * s8);
-    const int st = c + 8 * sl;
-    if (st >= ts) return;  // padding of the last round of slow tiles
-    tile_m = slow_is_n ? f : st;
-    tile_n = slow_is_n ? st : f;
-  }
+  if (!nt_tile(d, g, tile_m, tile_n)) return;  // padding of the last round of slow tiles
   const int m0 = tile_m * NBM, n0 = tile_n * NBN;
   const TA* __restrict__ A = reinterpret_cast<const TA*>(d.A) + (long)g * d.strideA;
   const TB* __restrict__ B = reinterpret_cast<const TB*>(d.B) + (long)g * d.strideB;
@@ -194,65 +268,101 @@ gemm_bf16_nt_kernel(GemmNtDesc d) {
     __syncthreads();
   }
 
-  // Epilogue through LDS (the operand buffers are free after the last barrier): the
-  // accumulators are laid out as the 128 x 128 tile, then every wave instruction moves two
-  // whole 512-byte row segments, so the stores (and the loads of W in the commit form, all
-  // requested before the first is used) are fully coalesced 16-byte accesses.
-  float* C = d.C + (long)g * d.strideC;
-  const float* bias = d.bias ? d.bias + (long)g * d.strideBias : nullptr;
-  float* sC = reinterpret_cast<float*>(nt_smem);
-  constexpr int CP = NBN + 4;  // pitch in floats
+  nt_epilogue<COMMIT>(d, acc, nt_smem, g, m0, n0);
+}
+
+// ---------------------------------------------------------------------------- direct-to-LDS variant
+// Both operands bf16: the tiles go from memory straight into LDS (global_load_lds_dwordx4: no
+// staging registers, no conversion, no LDS store instructions).  A wave instruction fills 1 KB
+// of LDS, lane j at byte 16*j, i.e. 8 rows of 128 bytes; rows carry no padding, so the 16-byte
+// chunks of a row are stored XOR-swizzled (chunk c of row r sits at position c ^ ((r >> 1) & 7)):
+// the 16 rows a quarter-wave reads for one MFMA operand then fall on 64 distinct banks.
+// Chunks beyond Kd (ragged last k-tile) are read from 16 zero bytes instead.  Two LDS stages
+// (64 KB, raised to the 66 KB of the epilogue tile): two workgroups per CU.
+__device__ __attribute__((aligned(16))) unsigned nt_zero16[4] = {0u, 0u, 0u, 0u};
+
+#define HPSGD_GPTR(p) ((const __attribute__((address_space(1))) void*)(p))
+#define HPSGD_LPTR(p) ((__attribute__((address_space(3))) void*)(p))
+
+template <bool COMMIT>
+__global__ void __launch_bounds__(NTHREADS, 2)
+gemm_bf16_dl_kernel(GemmNtDesc d) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char nt_smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave & 1, wn = wave >> 1;
+  const int lrow = lane & 31, lk = lane >> 5;
+  int g, tile_m, tile_n;
+  if (!nt_tile(d, g, tile_m, tile_n)) return;
+  const int m0 = tile_m * NBM, n0 = tile_n * NBN;
+  const __bf16* __restrict__ A = reinterpret_cast<const __bf16*>(d.A) + (long)g * d.strideA;
+  const __bf16* __restrict__ B = reinterpret_cast<const __bf16*>(d.B) + (long)g * d.strideB;
+  // loader: wave w, instruction i covers tile rows (4w + i)*8 .. +7; lane j: row + (j >> 3),
+  // LDS chunk j & 7, which holds the row's chunk (j & 7) ^ ((row >> 1) & 7).  Rows beyond M / N
+  // are clamped (their products are never stored).
+  const __bf16* ga[4];
+  const __bf16* gb[4];
+  int kofs[4];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int i = 0; i < 4; ++i) {
+    const int row = (wave * 4 + i) * 8 + (lane >> 3);
+    kofs[i] = ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+    ga[i] = A + (long)min(m0 + row, d.M - 1) * d.lda + kofs[i];
+    gb[i] = B + (long)min(n0 + row, d.N - 1) * d.ldb + kofs[i];
+  }
+  const __bf16* zero = reinterpret_cast<const __bf16*>(nt_zero16);
+  auto issue = [&](int stage, int kt) {
+    unsigned char* sa = nt_smem + stage * 32768 + wave * 4096;
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int v = 0; v < 16; ++v)
-        sC[(wm * 64 + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + wn * 64 + j * 32 + lrow] = acc[i][j][v];
-  __syncthreads();
-  const int c4 = (tid & 31) << 2, rbase = tid >> 5;
-  const int col = n0 + c4;
-  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
-                   (!COMMIT || (((uintptr_t)d.win & 15) == 0 && (d.strideWin & 3) == 0));
-  if (vec && col + 3 < d.N) {
-    float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (!COMMIT && bias) bv = make_float4(bias[col], bias[col + 1], bias[col + 2], bias[col + 3]);
-    float4 w[COMMIT ? 16 : 1];
-    if (COMMIT) {
-      const float* W = d.win + (long)g * d.strideWin;
-#pragma unroll
-      for (int p = 0; p < 16; ++p) {
-        const int row = min(m0 + rbase + 8 * p, d.M - 1);  // clamped: not stored when outside
-        w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
-      }
+    for (int i = 0; i < 4; ++i) {
+      const bool ok = kt * NBK + kofs[i] < d.Kd;  // Kd is a multiple of 8: a chunk is all in or all out
+      __builtin_amdgcn_global_load_lds(HPSGD_GPTR(ok ? ga[i] + kt * NBK : zero), HPSGD_LPTR(sa + i * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(HPSGD_GPTR(ok ? gb[i] + kt * NBK : zero), HPSGD_LPTR(sa + 16384 + i * 1024),
+                                       16, 0, 0);
     }
+  };
+  floatx16 acc[2][2];
 #pragma unroll
-    for (int p = 0; p < 16; ++p) {
-      const int rl = rbase + 8 * p, row = m0 + rl;
-      if (row >= d.M) continue;
-      const float4 a = *reinterpret_cast<const float4*>(&sC[rl * CP + c4]);
-      float4 o;
-      if (COMMIT) {
-        const float4 wv = w[COMMIT ? p : 0];
-        o = make_float4(wv.x - d.lr * a.x, wv.y - d.lr * a.y, wv.z - d.lr * a.z, wv.w - d.lr * a.w);
-      } else {
-        o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // operand fragments: row r, chunk c = 2*ks + lk at byte r*128 + ((c ^ ((r >> 1) & 7)) << 4)
+  int ra[2], rb[2], swa[2], swb[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = wm * 64 + i * 32 + lrow, rn = wn * 64 + i * 32 + lrow;
+    ra[i] = r * 128;
+    swa[i] = (r >> 1) & 7;
+    rb[i] = 16384 + rn * 128;
+    swb[i] = (rn >> 1) & 7;
+  }
+  const int nk = (d.Kd + NBK - 1) / NBK;
+  issue(0, 0);
+  for (int kt = 0; kt < nk; ++kt) {
+    // The tile's loads are the only ones in flight.  A bare barrier: with __syncthreads the
+    // compiler would add its own wait for every LDS-bound load, also the next tile's.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();  // tile kt is in LDS; everyone is done reading tile kt-1
+    if (kt + 1 < nk) issue((kt + 1) & 1, kt + 1);
+    const unsigned char* sb = nt_smem + (kt & 1) * 32768;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        a[i] = *reinterpret_cast<const bf16x8*>(sb + ra[i] + (((2 * ks + lk) ^ swa[i]) << 4));
+        b[i] = *reinterpret_cast<const bf16x8*>(sb + rb[i] + (((2 * ks + lk) ^ swb[i]) << 4));
       }
-      *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
-    }
-  } else {
-    const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
-    for (int p = 0; p < 16; ++p) {
-      const int rl = rbase + 8 * p, row = m0 + rl;
-      if (row >= d.M) continue;
-      for (int e = 0; e < 4; ++e) {
-        if (col + e >= d.N) break;
-        const long off = (long)row * d.ldc + col + e;
-        const float a = sC[rl * CP + c4 + e];
-        C[off] = COMMIT ? W[off] - d.lr * a : a + (bias ? bias[col + e] : 0.f);
-      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
   }
+  __syncthreads();  // the operand buffers become the epilogue tile
+  nt_epilogue<COMMIT>(d, acc, nt_smem, g, m0, n0);
 }
 
 // a_bf16 / b_bf16: the operand is stored as bf16 (else fp32).  Leading dimensions and group
@@ -299,8 +409,23 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
     if (win) HPSGD_NT1(TA, TB, true);   \
     else HPSGD_NT1(TA, TB, false);      \
   } while (0)
-  if (a_bf16 && b_bf16) HPSGD_NT(__bf16, __bf16);
-  else if (a_bf16) HPSGD_NT(__bf16, float);
+  if (a_bf16 && b_bf16) {
+    constexpr size_t dl_smem = (size_t)NBM * (NBN + 4) * sizeof(float);  // the epilogue tile; operands need 64 KB
+#define HPSGD_DL(CM)                                                                              \
+  do {                                                                                            \
+    static bool ready = false;                                                                    \
+    if (!ready) {                                                                                 \
+      hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_dl_kernel<CM>,                    \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)dl_smem); \
+      if (e != hipSuccess) return e;                                                              \
+      ready = true;                                                                               \
+    }                                                                                             \
+    hipLaunchKernelGGL((gemm_bf16_dl_kernel<CM>), grid, block, dl_smem, s, d);                    \
+  } while (0)
+    if (win) HPSGD_DL(true);
+    else HPSGD_DL(false);
+#undef HPSGD_DL
+  } else if (a_bf16) HPSGD_NT(__bf16, float);
   else if (b_bf16) HPSGD_NT(float, __bf16);
   else HPSGD_NT(float, float);
 #undef HPSGD_NT

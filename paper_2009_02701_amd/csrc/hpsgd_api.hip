@@ -122,7 +122,7 @@ int build_layout(hpsgd_ctx* c) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
       c->dgxb = c->alloc((TB * 3 * H + 1) / 2);
-      const size_t TBp = round_up(TB, 8), TB1p = round_up(TB + d.batch, 8);
+      const size_t TBp = round_up(TB, 64), TB1p = round_up(TB + d.batch, 64);
       const size_t win0 = lm ? d.embed : d.input;
       const size_t wmax = win0 > H ? win0 : H;
       c->dgxT = c->alloc(3 * H * TBp / 2);
@@ -134,13 +134,13 @@ int build_layout(hpsgd_ctx* c) {
         c->wihTl.push_back(c->alloc(((l == 0 ? win0 : H) * 3 * H + 1) / 2));
       }
       const size_t nr = lm ? TB : (size_t)d.batch;
-      c->dlogT = c->alloc((size_t)classes * round_up(nr, 8) / 2);
+      c->dlogT = c->alloc((size_t)classes * round_up(nr, 64) / 2);
       c->wihT = c->alloc(wmax * 3 * H / 2);
-      c->woT = c->alloc(H * round_up(classes, 8) / 2);
+      c->woT = c->alloc(H * round_up(classes, 64) / 2);
       c->xb = c->alloc((TB * win0 + 1) / 2);
       c->wihb = c->alloc((wmax * 3 * H + 1) / 2);
       c->wob = c->alloc(((size_t)classes * H + 1) / 2);
-      c->dlogb = c->alloc((nr * round_up(classes, 8) + 1) / 2);
+      c->dlogb = c->alloc((nr * round_up(classes, 64) + 1) / 2);
       c->rowstat = c->alloc(2 * nr);
     }
     size_t wmax = H;
@@ -363,7 +363,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // bf16 precision: the weight-gradient and input-gradient GEMMs take contraction-contiguous
     // bf16 operands ("NT" form); the fused step kernels write those copies themselves
     const bool ntc = bf && (B % 8 == 0) && (H % 8 == 0);
-    const long TBp = (long)round_up(TB, 8), TB1p = (long)round_up(TB + B, 8);
+    const long TBp = (long)round_up(TB, 64), TB1p = (long)round_up(TB + B, 64);
     auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
     bool xT_ready = false;  // the transposed bf16 layer-0 input was made in the forward pass
     // per layer: the transposed bf16 W_hh / W_ih were made in the forward pass, in the same
@@ -483,7 +483,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const int nrows = lm ? TB : B;
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
     const size_t oW = c->off("head.W"), ob = c->off("head.b");
-    const long nrp = (long)round_up(nrows, 8), clp = (long)round_up(classes, 8);
+    const long nrp = (long)round_up(nrows, 64), clp = (long)round_up(classes, 64);
     const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
     const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
     // bf16 precision with every head operand available as bf16: h of the top layer (written
