@@ -128,6 +128,25 @@ int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float 
  * gradients are summed chunk by chunk). */
 int hpsgd_set_aux_stream(hpsgd_ctx *ctx, void *hip_stream);
 
+/* How the fp32 GRU recurrence of a local step (Alg. 2 "compute local gradients") is launched.
+ * resident != 0 (the default): where the shape allows it (the workgroups of one launch must
+ * all fit the device at once, and a workgroup's slice of W_hh must fit its LDS), the time
+ * steps of a layer run as one launch (BPTT: one per chunk handed to the auxiliary stream)
+ * whose workgroups keep their weights on the chip and wait for each other through counters in
+ * the workspace; otherwise, and with resident == 0, one launch per time step.  Both forms
+ * compute the same values in the same order.  spin_limit bounds every such wait (polls of the
+ * counter; 0 makes every wait fail at once, for testing).  A wait that is given up ends the
+ * launch early on every workgroup, and the local step then delivers NaN in loss_out and in
+ * the first parameter of every output replica; hpsgd_recurrence_gave_up reports it too.
+ * Launches of this kind from different streams are serialised by the library (the device is
+ * synchronised when the stream changes). */
+int hpsgd_set_recurrence(hpsgd_ctx *ctx, int resident, unsigned spin_limit);
+
+/* *gave_up = 1 if a wait of the last local step(s) that used `workspace` was given up, else 0.
+ * Synchronises hip_stream.  workspace: device, as passed to the local step. */
+int hpsgd_recurrence_gave_up(const hpsgd_ctx *ctx, const void *workspace, void *hip_stream,
+                             int *gave_up);
+
 /* ---- batch gather (Sec. 3.2: every worker samples its own sub-dataset) ----------------
  * Time-major gather of n_idx samples: for b < n_idx, c < n_chunks
  *     out[(c*n_idx + b)*chunk_bytes ...] = shard[idx[b]*row_bytes + c*chunk_bytes ...]

@@ -25,7 +25,7 @@ EXPORTS = [
     "hpsgd_gather_batch", "hpsgd_gather_batch_all", "hpsgd_merge", "hpsgd_sync_replica", "hpsgd_sync_all", "hpsgd_strerror",
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
-    "hpsgd_local_step_all_acc", "hpsgd_merge_grad",
+    "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
 ]
 ROLE_COUNT = 14
 
@@ -73,6 +73,8 @@ def load_library():
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
     lib.hpsgd_set_aux_stream.argtypes = [vp, vp]
+    lib.hpsgd_set_recurrence.argtypes = [vp, C.c_int, C.c_uint]
+    lib.hpsgd_recurrence_gave_up.argtypes = [vp, vp, vp, C.POINTER(C.c_int)]
     lib.hpsgd_timer_enable.argtypes = [vp, C.c_uint]
     lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.hpsgd_role_name.argtypes = [C.c_int]
@@ -171,6 +173,17 @@ class Context:
         self._aux = stream  # keep the torch stream alive
         _check(self.lib.hpsgd_set_aux_stream(self._h, C.c_void_p(stream.cuda_stream if stream is not None else None)),
                "hpsgd_set_aux_stream")
+
+    def set_recurrence(self, resident=True, spin_limit=1 << 20):
+        """fp32 GRU recurrence as one launch per run of time steps (weights resident on the chip) or one per step."""
+        _check(self.lib.hpsgd_set_recurrence(self._h, int(bool(resident)), int(spin_limit)), "hpsgd_set_recurrence")
+
+    def recurrence_gave_up(self, workspace, stream=None):
+        """True if a wait inside a resident-weight recurrence launch was given up (synchronises the stream)."""
+        out = C.c_int(0)
+        _check(self.lib.hpsgd_recurrence_gave_up(self._h, self._ws_ptr(workspace), _stream(stream),
+                                                 C.byref(out)), "hpsgd_recurrence_gave_up")
+        return bool(out.value)
 
     # ---- kernel timing (benchmarks) ----
     def timer_enable(self, roles):

@@ -218,8 +218,8 @@ hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
   if (d.M <= 0 || d.N <= 0 || d.groups <= 0) return hipSuccess;
   if (d.bf16) return launch_gemm_bf16(d, s);
   if (!d.background) {
-    // aligned operands: the pipelined kernel.  Not for background work: its 72 KB of LDS per
-    // workgroup would keep the recurrent step kernels (59 KB each) off the CUs it occupies.
+    // aligned operands: the pipelined kernel.  Not for background work: its LDS footprint (up to
+    // 72 KB per workgroup) would keep the recurrent step kernels off the CUs it occupies.
     const hipError_t e = launch_gemm_f32_fast(d, s);
     if (e != hipErrorNotSupported) return e;
   }

@@ -286,7 +286,9 @@ hipError_t launch_gemm_f32_fast(const GemmDesc& d, hipStream_t s) {
   auto tiles = [&](int bm, int bn) {
     return (long)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.groups;
   };
-  if (d.M > 64 && d.N > 64 && tiles(128, 128) >= 192) return launch_fast_layout<128, 128>(d, s);
+  // 128 x 128 tiles from two full rounds of workgroups on: below that the smaller tiles' better
+  // balance over the CUs outweighs their extra LDS traffic (the fp32 matrix rate is low enough)
+  if (d.M > 64 && d.N > 64 && tiles(128, 128) >= 512) return launch_fast_layout<128, 128>(d, s);
   return launch_fast_layout<64, 64>(d, s);
 }
 

@@ -1,0 +1,437 @@
+// Recurrence kernels that stay on the chip for a whole run of time steps (fp32).
+//
+// One launch per time step pays, at every step, a launch gap, a cold L2 and the transfer of
+// the workgroup's slice of W_hh (the larger part of what a step reads).  Here a workgroup
+// keeps its slice of W_hh (forward: the 3 x 16 gate rows of its 16 hidden units; backward:
+// 16 rows of W_hh^T) in LDS for all the steps of the launch; the activations of the step
+// (h_{t-1}, or the gate gradients of step t+1) go from memory straight into MFMA operand
+// registers, every wave fetching exactly the fragments it multiplies, so that the matrix
+// work of a step needs no barrier until the partial sums are combined.
+//
+// The steps of one launch depend on each other across workgroups: h_t of a 32-row batch tile
+// is produced by the NJ = H/16 workgroups that own its hidden units, and every one of them
+// needs all of it for step t+1.  Those NJ workgroups form a synchronisation group with one
+// counter in device memory.  Protocol (no cache-wide write-back or invalidate, which cost
+// several microseconds per step when 32 workgroups of an XCD each ask for one):
+//   producer: the exchanged values are stored with device-scope write-through stores (sc1);
+//             the workgroup barrier waits until every wave's stores have completed; then
+//             thread 0 adds 1 to the group's counter (device-scope atomic);
+//   consumer: thread 0 polls the counter (device-scope loads) until all NJ producers of the
+//             step have added theirs; workgroup barrier; the operand loads that follow are
+//             device-scope loads (sc1), which are served from the level of the memory
+//             hierarchy that all XCDs share, never from a stale line of this XCD's caches.
+// Values nobody reads before the launch ends (the saved gates, dgx) take ordinary stores.
+//
+// Waiting needs every workgroup of the grid resident at the same time: the launcher refuses
+// grids with more workgroups than the device has compute units (a workgroup takes most of a
+// CU's LDS, so there is one per CU), and launches of these kernels from different streams are
+// ordered against each other by the caller.  Every wait is bounded: when the spin limit runs
+// out, or another workgroup has given up, the workgroup sets the abort word and the whole
+// workgroup leaves the kernel, so every wave reaches its end whatever happens.
+//
+// Tiling: 8 waves, 32 batch rows x 16 hidden units per workgroup, v_mfma_f32_16x16x4_f32.
+// The contraction is cut into 32-wide chunks, chunk c belongs to waves with (wave & 3) == c % 4,
+// the two 16-row blocks to the wave halves (wave >> 2); partial sums are combined through LDS.
+// MFMA 16x16x4 lane layout: A lane l holds A[m = l%16][k = l/16], B lane l holds
+// B[k = l/16][n = l%16], accumulator register v holds C[4*(l/16) + v][l%16].  The order of the
+// contraction index is free as long as both operands agree: for the chunk's MFMA number
+// e = 0..7 lane group lg = l/16 takes k = 32c + 16*(e/4) + 4*lg + e%4, i.e. two 16-byte pieces
+// of its row per chunk, and one load instruction reads 64 contiguous bytes of each of 16 rows.
+#include "kernels.h"
+
+namespace hpsgd {
+
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int PNT = 512;     // threads per workgroup
+constexpr int PR = 32;       // batch rows per workgroup
+constexpr int PJ = 16;       // hidden units per workgroup
+constexpr int PC = 32;       // contraction chunk
+
+__device__ __forceinline__ float sigm_p(float a) { return 1.0f / (1.0f + expf(-a)); }
+
+// Workgroup i runs on XCD i % 8; a synchronisation group (worker g, row tile ty) is kept on
+// one XCD when the number of groups allows it.  sg = g * RT + ty.
+__device__ __forceinline__ void persist_tile(int NJ, int RT, int groups, int& g, int& tx, int& ty, int& sg) {
+  const int i = blockIdx.x, SG = groups * RT;
+  if (SG % 8 == 0) {
+    const int c = i & 7, li = i >> 3;
+    sg = c + 8 * (li / NJ);
+    tx = li % NJ;
+  } else {
+    sg = i / NJ;
+    tx = i % NJ;
+  }
+  g = sg / RT;
+  ty = sg % RT;
+}
+
+// Thread 0 polls the group's counter until it has reached `target` (wrap-safe), then the
+// whole workgroup passes a barrier.  Returns false, for every thread alike, if the wait was
+// given up; the abort word is then set.  limit == 0 makes every wait fail (the host-forced
+// way to exercise the abort path).
+__device__ __forceinline__ bool group_wait(unsigned* ctr, unsigned target, unsigned* abort_w, unsigned limit,
+                                           int* lds_flag) {
+  if (threadIdx.x == 0) {
+    int ok = limit != 0;
+    unsigned n = 0;
+    while (ok && (int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+      if (++n > limit || __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+        ok = 0;
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    if (!ok) __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *lds_flag = ok;
+  }
+  __syncthreads();
+  return *lds_flag != 0;
+}
+
+// The barrier waits for the completion of every wave's stores; then thread 0 counts the
+// workgroup in.
+__device__ __forceinline__ void group_signal(unsigned* ctr) {
+  __syncthreads();
+  if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// 16 bytes at byte offset `off` of the buffer, as a device-scope load
+__device__ __forceinline__ float4 ld16_dev(__amdgpu_buffer_rsrc_t rs, int off) {
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(rs, off, 0, 16 /* sc1 */);
+  return __builtin_bit_cast(float4, v);
+}
+// device-scope (write-through) store
+__device__ __forceinline__ void st_dev(float* p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Copies `rows` weight rows of KD words (row r at src + row_off(r)) into LDS at pitch wp and
+// zeroes the columns from KD up to the next multiple of the chunk.
+template <typename RowOff>
+__device__ __forceinline__ void load_resident(float* wres, int wp, const float* src, int rows, int KD,
+                                              RowOff row_off) {
+  const int KDp = (KD + PC - 1) / PC * PC, ur = KDp >> 2;
+  for (int u = threadIdx.x; u < rows * ur; u += PNT) {
+    const int row = u / ur, c4 = u - row * ur;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (4 * c4 < KD) v = *reinterpret_cast<const float4*>(src + row_off(row) + 4 * c4);
+    *reinterpret_cast<float4*>(&wres[row * wp + 4 * c4]) = v;
+  }
+}
+
+// acc[i][q] (i = 0, 1: two accumulators per gate block, summed by the caller) +=
+// sum over this wave's chunks of A[rsel*16 + ..][k] * Wres[q*16 + ..][k].
+// wres: the resident weight rows (pitch wp words, zero beyond KD); rs: buffer over the
+// workgroup's activation tile (row pitch KD words); rows >= rows_valid are read from row 0:
+// their results are never stored.  Columns beyond KD are read from column 0 and meet a zero
+// weight.  NB: chunks per wave whose loads are in flight together.
+template <int NQ, int NB>
+__device__ __forceinline__ void resident_contraction(const float* wres, int wp, __amdgpu_buffer_rsrc_t rs, int KD,
+                                                     int rows_valid, floatx4 (&acc)[2][NQ]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int row = rsel * 16 + lr;
+  const int rowoff = (row < rows_valid ? row : 0) * KD;
+  const int nch = (KD + PC - 1) / PC;
+  for (int c0 = kw; c0 < nch; c0 += 4 * NB) {
+    float4 a[NB][2];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      const int k0 = PC * (c0 + 4 * i) + 4 * lg;
+      // (KD is a multiple of 16: each piece is all in or all out)
+      a[i][0] = ld16_dev(rs, (rowoff + (k0 < KD ? k0 : 0)) * 4);
+      a[i][1] = ld16_dev(rs, (rowoff + (k0 + 16 < KD ? k0 + 16 : 0)) * 4);
+    }
+    __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      // branch-free (a branch would pull the loads of its chunk in behind it): a chunk slot
+      // beyond the contraction reads weight column 0 and gets zeros instead
+      const int c = c0 + 4 * i;
+      const bool cv = c < nch;  // uniform over the wave
+      const int cc = cv ? c : 0;
+      float4 w[NQ][2];
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const float* wr = &wres[(q * 16 + lr) * wp + PC * cc + 4 * lg];
+        const float4 w0 = *reinterpret_cast<const float4*>(wr);
+        const float4 w1 = *reinterpret_cast<const float4*>(wr + 16);
+        w[q][0] = make_float4(cv ? w0.x : 0.f, cv ? w0.y : 0.f, cv ? w0.z : 0.f, cv ? w0.w : 0.f);
+        w[q][1] = make_float4(cv ? w1.x : 0.f, cv ? w1.y : 0.f, cv ? w1.z : 0.f, cv ? w1.w : 0.f);
+      }
+      // consecutive MFMAs update different accumulators
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+          const float4 av = a[i][e >> 2], wv = w[q][e >> 2];
+          const float as = (e & 3) == 0 ? av.x : (e & 3) == 1 ? av.y : (e & 3) == 2 ? av.z : av.w;
+          const float ws = (e & 3) == 0 ? wv.x : (e & 3) == 1 ? wv.y : (e & 3) == 2 ? wv.z : wv.w;
+          acc[e & 1][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, ws, acc[e & 1][q], 0, 0, 0);
+        }
+    }
+  }
+}
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<float*>(base), 0, 0x7fffffff, 0x00020000);
+}
+
+// Forward: steps t = 0 .. T-1.  hs holds h_0 .. h_T ((T+1) blocks of B x H per worker, h_0
+// given), gx the input projections of all steps, sv receives r|z|n|q of every step.
+// sync: the abort word, then one counter per synchronisation group; `base` is what the
+// counters read when the kernel starts.
+__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
+gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
+                       const float* __restrict__ gx, long s_gx, float* hs, long s_hs, float* __restrict__ sv,
+                       long s_sv, int B, int H, int T, int groups, unsigned* sync, unsigned base,
+                       unsigned spin_limit) {
+  extern __shared__ __attribute__((aligned(16))) float persist_lds[];
+  const int wp = (H + PC - 1) / PC * PC + 4;
+  float* wres = persist_lds;                 // [48][wp]
+  float* red = wres + 48 * wp;               // [4][6][4][64]
+  int* lds_flag = reinterpret_cast<int*>(red + 4 * 6 * 4 * 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int NJ = H / PJ, RT = (B + PR - 1) / PR;
+  int g, tx, ty, sg;
+  persist_tile(NJ, RT, groups, g, tx, ty, sg);
+  const int j0 = tx * PJ, r0 = ty * PR;
+  unsigned* abort_w = sync;
+  unsigned* ctr = sync + 1 + sg;
+  __builtin_amdgcn_s_setprio(3);
+  // the resident slice: rows q*16 + r = W_hh[q*H + j0 + r][:]
+  load_resident(wres, wp, W_hh + g * s_rep, 48, H,
+                [&](int row) { return ((long)(row >> 4) * H + j0 + (row & 15)) * H; });
+  const int j = j0 + lr;
+  const int row = r0 + rsel * 16 + 4 * lg + kw;     // this thread's element of the tile
+  const int rowc = min(row, B - 1);                 // loads are clamped, stores guarded
+  const float* bh = b_hh + g * s_rep;
+  float bias[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
+  float* hsg = hs + g * s_hs;
+  float hpv = hsg[(long)rowc * H + j];
+  __syncthreads();
+  for (int t = 0; t < T; ++t) {
+    // the epilogue's inputs do not depend on the recurrence: they travel during the wait
+    const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H;
+    float gxv[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
+    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    floatx4 acc[2][3];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int q = 0; q < 3; ++q) acc[i][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    resident_contraction<3, 4>(wres, wp, tile_rsrc(hsg + ((long)t * B + r0) * H), H, B - r0, acc);
+#pragma unroll
+    for (int q = 0; q < 3; ++q)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        red[((kw * 6 + rsel * 3 + q) * 4 + v) * 64 + lane] = acc[0][q][v] + acc[1][q][v];
+    __syncthreads();
+    float gh[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const int o = ((rsel * 3 + q) * 4 + kw) * 64 + lane;
+      gh[q] = ((red[o] + red[o + 6 * 256]) + (red[o + 12 * 256] + red[o + 18 * 256])) + bias[q];
+    }
+    const float r = sigm_p(gxv[0] + gh[0]);
+    const float z = sigm_p(gxv[1] + gh[1]);
+    const float qv = gh[2];
+    const float n = tanhf(gxv[2] + r * qv);
+    const float hn = (1.0f - z) * n + z * hpv;
+    if (row < B) {
+      st_dev(&hsg[((long)(t + 1) * B + row) * H + j], hn);
+      float* svr = sv + g * s_sv + ((long)t * B + row) * 4 * H;
+      svr[j] = r;
+      svr[H + j] = z;
+      svr[2 * H + j] = n;
+      svr[3 * H + j] = qv;
+    }
+    hpv = hn;
+    group_signal(ctr);  // (its barrier also separates the reads of red from the next step's writes)
+  }
+}
+
+// Backward: steps t = t_hi-1 down to t_lo.  WT is W_hh transposed (row pitch 3H).  dgh and
+// dgx hold the gate gradients of all steps (blocks of B x 3H); block t+1 of dgh is the
+// contraction operand of step t (none at t = T-1).  D holds dh_{t_hi} * z_{t_hi} on entry (the
+// head's gradient when t_hi == T) and dh_{t_lo} * z_{t_lo} on exit.  above: per-step gradient
+// from the layer above (blocks of B x H) or nullptr.
+__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
+gru_bwd_persist_kernel(const float* __restrict__ WT, long s_wt, float* dgh, float* __restrict__ dgx, long s_dg,
+                       float* __restrict__ D, long s_D, const float* __restrict__ above, long s_above,
+                       const float* __restrict__ sv, long s_sv, const float* __restrict__ hs, long s_hs,
+                       int B, int H, int T, int t_hi, int t_lo, int groups, unsigned* sync, unsigned base,
+                       unsigned spin_limit) {
+  extern __shared__ __attribute__((aligned(16))) float persist_lds[];
+  const int H3 = 3 * H;
+  const int wp = (H3 + PC - 1) / PC * PC + 4;
+  float* wres = persist_lds;                 // [16][wp]
+  float* red = wres + 16 * wp;               // [4][2][4][64]
+  int* lds_flag = reinterpret_cast<int*>(red + 4 * 2 * 4 * 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kw = wave & 3, rsel = wave >> 2;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int NJ = H / PJ, RT = (B + PR - 1) / PR;
+  int g, tx, ty, sg;
+  persist_tile(NJ, RT, groups, g, tx, ty, sg);
+  const int j0 = tx * PJ, r0 = ty * PR;
+  unsigned* abort_w = sync;
+  unsigned* ctr = sync + 1 + sg;
+  __builtin_amdgcn_s_setprio(3);
+  load_resident(wres, wp, WT + g * s_wt + (long)j0 * H3, 16, H3, [&](int row) { return (long)row * H3; });
+  const int j = j0 + lr;
+  const int row = r0 + rsel * 16 + 4 * lg + kw;
+  const int rowc = min(row, B - 1);
+  float* Dg = D + g * s_D;
+  float dcar = Dg[(long)rowc * H + j];  // dh_{t+1} * z_{t+1}, carried in a register
+  float* dghg = dgh + g * s_dg;
+  __syncthreads();
+  int it = 0;
+  for (int t = t_hi - 1; t >= t_lo; --t, ++it) {
+    const long e = ((long)t * B + rowc) * H + j;
+    const float* svr = sv + g * s_sv + ((long)t * B + rowc) * 4 * H;
+    const float r = svr[j], z = svr[H + j], n = svr[2 * H + j], q = svr[3 * H + j];
+    const float hp = hs[g * s_hs + e];
+    const float ab = above ? above[g * s_above + e] : 0.f;
+    if (it > 0 && !group_wait(ctr, base + (unsigned)it * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    floatx4 acc[2][1];
+    acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    acc[1][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    if (t + 1 < T)  // uniform over the grid
+      resident_contraction<1, 12>(wres, wp, tile_rsrc(dghg + ((long)(t + 1) * B + r0) * H3), H3, B - r0, acc);
+#pragma unroll
+    for (int v = 0; v < 4; ++v) red[((kw * 2 + rsel) * 4 + v) * 64 + lane] = acc[0][0][v] + acc[1][0][v];
+    __syncthreads();
+    const int o = (rsel * 4 + kw) * 64 + lane;
+    const float rec = (red[o] + red[o + 512]) + (red[o + 1024] + red[o + 1536]);
+    const float dh = (dcar + ab) + rec;
+    const float dn = dh * (1.0f - z);
+    const float dz = dh * (hp - n);
+    const float da_n = dn * (1.0f - n * n);
+    const float dq = da_n * r;
+    const float da_r = da_n * q * r * (1.0f - r);
+    const float da_z = dz * z * (1.0f - z);
+    if (row < B) {
+      float* ox = dgx + g * s_dg + ((long)t * B + row) * H3;
+      float* oh = dghg + ((long)t * B + row) * H3;
+      ox[j] = da_r;
+      ox[H + j] = da_z;
+      ox[2 * H + j] = da_n;
+      st_dev(&oh[j], da_r);
+      st_dev(&oh[H + j], da_z);
+      st_dev(&oh[2 * H + j], dq);
+    }
+    dcar = dh * z;
+    group_signal(ctr);
+  }
+  if (row < B) Dg[(long)row * H + j] = dcar;
+}
+
+int device_cus() {
+  static int cus = -1;
+  if (cus < 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return 0;
+    cus = n;
+  }
+  return cus;
+}
+
+constexpr size_t kLdsLimit = 160 * 1024;
+// forward: 48 rows of H (rounded up to the chunk) + 4 words, the partial sums, the flag;
+// backward: 16 rows of 3H (rounded up) + 4 words and fewer partial sums: never more
+size_t persist_lds_bytes(int H) {
+  return ((size_t)48 * ((H + PC - 1) / PC * PC + 4) + 4 * 6 * 4 * 64 + 4) * sizeof(float);
+}
+
+}  // namespace
+
+// One workgroup per CU and all of them resident: the grid may not exceed the CU count, and
+// the resident slice plus the partial sums must fit the 160 KB of LDS.
+bool gru_persist_supported(int B, int H, int groups) {
+  if (H % 16 != 0 || H < 16 || B < 1 || groups < 1) return false;
+  if (persist_lds_bytes(H) > kLdsLimit) return false;
+  const long grid = (long)(H / PJ) * ((B + PR - 1) / PR) * groups;
+  return grid <= device_cus();
+}
+
+// Words of device memory the kernels synchronise through: the abort word + one counter per group.
+size_t gru_persist_sync_words(int B, int groups) { return (size_t)groups * ((B + PR - 1) / PR) + 1; }
+
+// How much every counter advances per time step of a launch.
+unsigned gru_persist_count_per_step(int H) { return (unsigned)(H / PJ); }
+
+hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
+                                  float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
+                                  unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s) {
+  if (!gru_persist_supported(B, H, groups) || T < 1) return hipErrorInvalidValue;
+  if (((uintptr_t)hs & 15) != 0 || (s_hs & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0)
+    return hipErrorInvalidValue;
+  const size_t lds = persist_lds_bytes(H);
+  static size_t allowed = 0;
+  if (lds > allowed) {
+    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_persist_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    allowed = lds;
+  }
+  dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
+  hipLaunchKernelGGL(gru_fwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, b_hh, s_rep, gx, s_gx, hs, s_hs, sv,
+                     s_sv, B, H, T, groups, sync, base, spin_limit);
+  return hipGetLastError();
+}
+
+hipError_t launch_gru_bwd_persist(const float* WT, long s_wt, float* dgh, float* dgx, long s_dg, float* D,
+                                  long s_D, const float* above, long s_above, const float* sv, long s_sv,
+                                  const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
+                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit,
+                                  hipStream_t s) {
+  if (!gru_persist_supported(B, H, groups) || t_lo < 0 || t_hi > T || t_lo >= t_hi) return hipErrorInvalidValue;
+  if (((uintptr_t)dgh & 15) != 0 || (s_dg & 3) != 0 || ((uintptr_t)WT & 15) != 0 || (s_wt & 3) != 0)
+    return hipErrorInvalidValue;
+  const size_t lds = persist_lds_bytes(H);
+  static size_t allowed = 0;
+  if (lds > allowed) {
+    hipError_t e = hipFuncSetAttribute((const void*)gru_bwd_persist_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    allowed = lds;
+  }
+  dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
+  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, WT, s_wt, dgh, dgx, s_dg, D, s_D, above,
+                     s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit);
+  return hipGetLastError();
+}
+
+// Makes a given-up recurrence visible in the results: NaN in the losses and in the first
+// parameter of every output replica.
+__global__ void poison_on_abort_kernel(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
+                                       int groups) {
+  if (*abort_w == 0u) return;
+  const float nan = __builtin_nanf("");
+  for (int i = threadIdx.x; i < groups; i += blockDim.x) {
+    rout[i * s_rout] = nan;
+    if (loss && i < n_loss) loss[i] = nan;
+  }
+}
+
+hipError_t launch_poison_on_abort(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
+                                  int groups, hipStream_t s) {
+  hipLaunchKernelGGL(poison_on_abort_kernel, dim3(1), dim3(64), 0, s, abort_w, loss, n_loss, rout, s_rout, groups);
+  return hipGetLastError();
+}
+
+}  // namespace hpsgd

@@ -4,6 +4,7 @@
 #include "../../include/hpsgd.h"
 
 #include <string>
+#include <mutex>
 #include <vector>
 
 #include "kernels.h"
@@ -34,6 +35,7 @@ struct hpsgd_ctx {
   size_t ws_floats = 0;
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
+  Region psync;                 // abort word and counters of the resident-weight recurrence kernels (fp32)
   Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
@@ -50,6 +52,8 @@ struct hpsgd_ctx {
   // that order it against the caller's stream
   hipStream_t aux = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool resident = true;         // fp32 recurrence: one launch per run of time steps when supported
+  unsigned spin_limit = 1u << 20;  // bound of every wait inside those launches
   size_t last_commit_params = 0;  // parameters per worker that the commit kernel handled last step
   unsigned timer_mask = 0;
   bool timer_nested = false;    // an enclosing scope already brackets the current launches
@@ -118,6 +122,7 @@ int build_layout(hpsgd_ctx* c) {
     c->gh = c->alloc((size_t)d.batch * 3 * H);
     c->D = c->alloc((size_t)d.batch * H);
     c->wt = c->alloc(3 * H * H);
+    if (d.prec != HPSGD_BF16_MFMA) c->psync = c->alloc(gru_persist_sync_words(d.batch, 1));
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
@@ -266,6 +271,21 @@ int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float
     if (rc_ != HPSGD_OK) return rc_; \
   } while (0)
 
+// The resident-weight recurrence kernels wait for each other inside a launch, which needs all
+// their workgroups on the chip at once: two such launches running side by side (from two
+// streams) could each hold CUs the other is waiting for.  Launches on one stream are ordered
+// anyway; when the stream changes, everything issued before is allowed to finish first.
+int order_resident_launches(hipStream_t s) {
+  static std::mutex mu;
+  static bool have = false;
+  static hipStream_t last = nullptr;
+  std::lock_guard<std::mutex> lock(mu);
+  if (have && last != s && hipDeviceSynchronize() != hipSuccess) return HPSGD_EHIP;
+  have = true;
+  last = s;
+  return HPSGD_OK;
+}
+
 // One local step for `groups` workers whose workspace slices start at worker k0.
 // acc (nullable): per-worker gradient accumulators [groups][acc_stride]; the step's gradient
 // is added to them (Alg. 2 "accumulate gradients").  Every gradient then goes through the
@@ -282,6 +302,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
+  const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
   // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
   // (replica_out = replica_in - lr * dW, no gradient buffer round trip); every other
   // parameter goes through the gradient buffer and the commit kernel at the end.  A matrix
@@ -369,6 +390,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // per layer: the transposed bf16 W_hh / W_ih were made in the forward pass, in the same
     // read as the row-major copies
     bool whhT_ready[16] = {false}, wihT_ready[16] = {false};
+    // fp32: the recurrence of a layer as one launch (a few for BPTT) with W_hh resident in LDS.
+    // Its workgroups wait for each other through counters in the workspace, zeroed here; pbase
+    // follows what the counters read.  A given-up wait shows as NaN in the results (below).
+    const bool use_persist = !bf && c->resident && gru_fused_supported(H) && gru_persist_supported(B, H, groups);
+    unsigned* psync = use_persist ? (unsigned*)reg(c->psync) : nullptr;
+    unsigned pbase = 0;
+    if (use_persist) {
+      TRY(order_resident_launches(s));
+      const size_t nw = gru_persist_sync_words(B, groups);
+      HIP_TRY(launch_fill_zero((float*)psync, nw, nw, 1, s));
+      abort_word = psync;
+    }
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -392,6 +425,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
+      const bool persist = fused && use_persist;
       {
         const float* Wih = rin + c->off(p + ".W_ih");
         NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
@@ -446,9 +480,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
       }
       // one event pair around the whole time loop when its launches are all of one role
-      TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (fused || fused_b) ? T : 0);
+      TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, persist ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
-      for (int t = 0; t < T; ++t) {
+      if (persist) {
+        role = HPSGD_ROLE_GEMM_REC_FWD;
+        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->off(p + ".b_hh"), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
+                                       groups, psync, pbase, c->spin_limit, s));
+        pbase += (unsigned)T * gru_persist_count_per_step(H);
+      }
+      for (int t = 0; t < T && !persist; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         if (fused_b) {
           HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H,
@@ -624,7 +664,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // recurrence is latency-bound and leaves the matrix cores mostly idle).  The steps are
       // cut into chunks; chunk c's GEMMs are issued when BPTT has walked past it, the last
       // one follows on the main stream after the join.  Fixed chunking: deterministic.
-      const int NC = (c->aux && fused && T >= 8) ? 4 : 1;
+      const bool persist = fused && use_persist;
+      const int NC = (c->aux && fused && !persist && T >= 8) ? 4 : 1;
       auto chunk_lo = [&](int ch) { return (int)((long)T * ch / NC); };
       auto wgrad_rows = [&](hipStream_t st, int t0, int t1, int epi) -> int {
         const size_t r0 = (size_t)t0 * B;
@@ -637,10 +678,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                     grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0, bg);
       };
       {
-      TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (fused || fused_b) ? T : 0);
+      TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, persist ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_bwd.active() && (fused || fused_b);
       int next_chunk = NC - 1;  // the chunk BPTT is walking through
-      for (int t = T - 1; t >= 0; --t) {
+      // resident weights: all of BPTT is one launch; its weight-gradient GEMMs follow it (work
+      // that shares the CUs with this launch slows its chain of waits by more than it hides)
+      if (persist) {
+        role = HPSGD_ROLE_GEMM_REC_BWD;
+        HIP_TRY(launch_gru_bwd_persist(wt, s_wt, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
+                                       T, 0, groups, psync, pbase, c->spin_limit, s));
+        pbase += (unsigned)T * gru_persist_count_per_step(H);
+      }
+      for (int t = T - 1; t >= 0 && !persist; --t) {
         if (NC > 1 && next_chunk >= 1 && t < chunk_lo(next_chunk)) {
           // steps [chunk_lo, chunk_hi) are done: hand their weight gradients to the aux stream
           if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
@@ -765,6 +814,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
     c->last_commit_params += hi - lo;
   }
+  if (abort_word) HIP_TRY(launch_poison_on_abort(abort_word, loss_out, groups, rout, sR, groups, s));
   return HPSGD_OK;
 }
 
@@ -969,6 +1019,30 @@ int hpsgd_set_aux_stream(hpsgd_ctx* ctx, void* hip_stream) {
       return HPSGD_EHIP;
   }
   ctx->aux = (hipStream_t)hip_stream;
+  return HPSGD_OK;
+}
+
+int hpsgd_set_recurrence(hpsgd_ctx* ctx, int resident, unsigned spin_limit) {
+  if (!ctx) return HPSGD_EINVAL;
+  ctx->resident = resident != 0;
+  ctx->spin_limit = spin_limit;
+  return HPSGD_OK;
+}
+
+int hpsgd_recurrence_gave_up(const hpsgd_ctx* ctx, const void* workspace, void* hip_stream, int* gave_up) {
+  if (!ctx || !gave_up) return HPSGD_EINVAL;
+  if (!workspace) return HPSGD_EWORKSPACE;
+  *gave_up = 0;
+  if (ctx->psync.stride == 0) return HPSGD_OK;  // no such kernels for this model
+  // the abort word is the first word of a worker's slice (of the first worker's for a grouped step)
+  std::vector<unsigned> host(ctx->psync.stride * (size_t)ctx->K);
+  hipStream_t s = (hipStream_t)hip_stream;
+  if (hipMemcpyAsync(host.data(), (const float*)workspace + ctx->psync.offset, host.size() * sizeof(unsigned),
+                     hipMemcpyDeviceToHost, s) != hipSuccess ||
+      hipStreamSynchronize(s) != hipSuccess)
+    return HPSGD_EHIP;
+  for (int k = 0; k < ctx->K; ++k)
+    if (host[(size_t)k * ctx->psync.stride] == 1u) *gave_up = 1;
   return HPSGD_OK;
 }
 

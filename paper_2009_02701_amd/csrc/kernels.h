@@ -81,6 +81,25 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                long s_D, const float* above, long s_above, const float* sv_t,
                                long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
                                int B, int H, int groups, hipStream_t s);
+// ---- whole runs of time steps in one launch, W_hh resident in LDS (fp32), see gru_persist.hip ----
+// sync: gru_persist_sync_words() words of device memory (the abort word, then one counter per
+// synchronisation group); base: what the counters read when the launch starts; every launch
+// advances them by steps * gru_persist_count_per_step().  spin_limit bounds every wait.
+bool gru_persist_supported(int B, int H, int groups);
+size_t gru_persist_sync_words(int B, int groups);
+unsigned gru_persist_count_per_step(int H);
+hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
+                                  float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
+                                  unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
+// steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches)
+hipError_t launch_gru_bwd_persist(const float* WT, long s_wt, float* dgh, float* dgx, long s_dg, float* D,
+                                  long s_D, const float* above, long s_above, const float* sv, long s_sv,
+                                  const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
+                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit,
+                                  hipStream_t s);
+// NaN into loss[0..n_loss) and into rout[g * s_rout] for every group if *abort_w != 0
+hipError_t launch_poison_on_abort(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
+                                  int groups, hipStream_t s);
 // bf16-operand variants (strides of bf16 buffers are in bf16 elements)
 bool gru_fused_bf16_supported(int H);
 hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep,

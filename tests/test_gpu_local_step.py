@@ -277,3 +277,74 @@ def test_mfma_probe_reports_a_plausible_rate(prec):
     assert 300 < mhz < 3000, mhz
     # all-zero operands: the accumulators stay zero
     assert float(sink.abs().max()) == 0.0
+
+
+RESIDENT = {
+    "gru_cls_ragged": SMALL["gru_cls_ragged"],
+    "cls_fused_3layer": SMALL["cls_fused_3layer"],
+    "lm_tiles_fp32": SMALL["lm_tiles_fp32"],
+    "gru_cls_tiles": SMALL["gru_cls_tiles"],
+    "cls_wide": wl.scaled(wl.CONFIGS["gru_cls"], input=32, hidden=320, seq_len=9, batch=40, K=4),
+    "gru_cls": wl.CONFIGS["gru_cls"],
+}
+
+
+@pytest.mark.parametrize("aux", [False, True])
+@pytest.mark.parametrize("name", list(RESIDENT))
+def test_resident_weight_recurrence_equals_one_launch_per_step(name, aux):
+    """The recurrence as one launch per run of time steps (W_hh kept in LDS, workgroups waiting
+    for each other through counters) computes what one launch per time step computes, up to
+    the order of the fp32 sums inside a dot product (the two forms cut the contraction into
+    chunks differently); no wait was given up; and a second run gives the same bits."""
+    cfg = RESIDENT[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for resident in (True, False, True):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, aux_stream=aux)
+        tr.ctx.set_recurrence(resident)
+        tr.sync_all(0)
+        tr.gather(0)
+        tr.local_step(0, 8.0)  # a large probe rate: the movement of a parameter is 8 x its gradient
+        torch.cuda.synchronize()
+        first = [tr.replica_params(0, k) for k in range(cfg["K"])]
+        tr.sync_all(0)
+        tr.gather(1)
+        tr.local_step(0, cfg["lr"])  # a second call, on other data
+        torch.cuda.synchronize()
+        assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+        outs.append((first, tr.loss.cpu().numpy().copy(), tr.R[0].cpu().numpy().view(np.uint32).copy()))
+    assert rel_err(outs[0][1], outs[1][1]) <= 1e-5
+    for k in range(cfg["K"]):
+        for n in init:
+            d0 = outs[0][0][k][n].astype(np.float64) - init[n]
+            d1 = outs[1][0][k][n].astype(np.float64) - init[n]
+            assert rel_err(d0, d1) <= 2e-5, (k, n)
+            assert np.array_equal(outs[0][0][k][n].view(np.uint32), outs[2][0][k][n].view(np.uint32)), (k, n)
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[2][1].view(np.uint32))
+    assert np.array_equal(outs[0][2], outs[2][2])
+
+
+def test_resident_weight_recurrence_reports_a_wait_that_was_given_up():
+    """A spin limit of zero makes the first wait of every workgroup fail (forced from the host:
+    every workgroup still leaves its kernel normally).  The step then delivers NaN losses and a
+    NaN first parameter in every replica, and the library reports it; with the default limit
+    the same trainer then steps normally again."""
+    cfg = SMALL["gru_cls_tiles"]
+    init, shards, orders, _ = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.ctx.set_recurrence(True, 0)
+    tr.sync_all(0)
+    tr.gather(0)
+    tr.local_step(0, cfg["lr"])
+    torch.cuda.synchronize()
+    assert tr.ctx.recurrence_gave_up(tr.ws[0])
+    assert np.isnan(tr.loss.cpu().numpy()).all()
+    assert np.isnan(tr.R[0][:, 0].cpu().numpy()).all()
+    tr.ctx.set_recurrence(True)
+    tr.sync_all(0)
+    tr.gather(0)
+    tr.local_step(0, cfg["lr"])
+    torch.cuda.synchronize()
+    assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+    assert np.isfinite(tr.loss.cpu().numpy()).all()
+    assert np.isfinite(tr.R[0].cpu().numpy()).all()
