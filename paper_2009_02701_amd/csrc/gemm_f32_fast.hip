@@ -92,8 +92,15 @@ gemm_f32_fast_kernel(GemmDesc d) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave & 1, wn = wave >> 1;
   const int lrow = lane & 31, lk = lane >> 5;
-  const int g = blockIdx.z;
-  const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+  // Tile order.  Workgroup i runs on XCD i % 8 and every XCD has its own L2: the tiles, in
+  // (group, row tile, column tile) order, are cut into 8 contiguous runs, one per XCD, so that
+  // an XCD fetches the A rows of its run once and only the B operands of the groups it touches.
+  const int tn = (d.N + BN - 1) / BN, tm = (d.M + BM - 1) / BM;
+  const long ntiles = (long)tn * tm * d.groups, per = (ntiles + 7) / 8;
+  const long tile = (long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((long)(blockIdx.x >> 3) >= per || tile >= ntiles) return;  // padding of the last run
+  const int g = (int)(tile / ((long)tn * tm));
+  const int m0 = (int)((tile / tn) % tm) * BM, n0 = (int)(tile % tn) * BN;
 
   OpA a;
   OpB b;
@@ -259,7 +266,8 @@ static hipError_t launch_fast_cfg(const GemmDesc& d, hipStream_t s) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, d.groups);
+  const long ntiles = (long)((d.N + BN - 1) / BN) * ((d.M + BM - 1) / BM) * d.groups;
+  dim3 grid((unsigned)(8 * ((ntiles + 7) / 8)));
   hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB>), grid, dim3(FTHREADS), smem, s, d);
   return hipGetLastError();
 }

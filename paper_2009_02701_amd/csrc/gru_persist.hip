@@ -49,6 +49,7 @@ constexpr int PNT = 512;     // threads per workgroup
 constexpr int PR = 32;       // batch rows per workgroup
 constexpr int PJ = 16;       // hidden units per workgroup
 constexpr int PC = 32;       // contraction chunk
+constexpr int SP = 80;       // pitch of the staged dgh tile: 4 batch rows x 16 gate rows hit 64 banks
 
 __device__ __forceinline__ float sigm_p(float a) { return 1.0f / (1.0f + expf(-a)); }
 
@@ -262,23 +263,35 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
   }
 }
 
-// Backward: steps t = t_hi-1 down to t_lo.  WT is W_hh transposed (row pitch 3H).  dgh and
+// Backward: steps t = t_hi-1 down to t_lo.  The workgroup's resident slice is 16 columns of
+// W_hh (3H x H), kept transposed in LDS (16 rows of 3H, unit stride along the contraction).  dgh and
 // dgx hold the gate gradients of all steps (blocks of B x 3H); block t+1 of dgh is the
 // contraction operand of step t (none at t = T-1).  D holds dh_{t_hi} * z_{t_hi} on entry (the
 // head's gradient when t_hi == T) and dh_{t_lo} * z_{t_lo} on exit.  above: per-step gradient
 // from the layer above (blocks of B x H) or nullptr.
+//
+// dWp (nullable, H <= 512): the workgroup also accumulates its share of the recurrent weight
+// gradient over the steps of the launch, dW_hh[q*H + j0 + m][:] += sum over its 32 batch rows
+// of dgh_t[row][q*H + j0 + m] * h_{t-1}[row][:], and stores it at the end to
+// dWp[(g * RT + ty)][3H][H] (one partial sum per batch-row tile; the caller adds the RT of
+// them).  That work does not depend on the other workgroups: it is done between counting
+// the step in and waiting for the next one, in the time the chain of waits leaves idle.
+// Wave w owns columns 64w .. 64w+63 and all 48 gate rows (3 x 4 accumulator tiles); tile
+// (mt, jt) holds the columns 64w + 4*lane%16 + jt, so that a lane fetches h as one float4 per
+// batch row and stores its results as float4s.
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
-gru_bwd_persist_kernel(const float* __restrict__ WT, long s_wt, float* dgh, float* __restrict__ dgx, long s_dg,
+gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, float* __restrict__ dgx, long s_dg,
                        float* __restrict__ D, long s_D, const float* __restrict__ above, long s_above,
                        const float* __restrict__ sv, long s_sv, const float* __restrict__ hs, long s_hs,
                        int B, int H, int T, int t_hi, int t_lo, int groups, unsigned* sync, unsigned base,
-                       unsigned spin_limit) {
+                       unsigned spin_limit, float* __restrict__ dWp, float* __restrict__ dbp) {
   extern __shared__ __attribute__((aligned(16))) float persist_lds[];
   const int H3 = 3 * H;
   const int wp = (H3 + PC - 1) / PC * PC + 4;
   float* wres = persist_lds;                 // [16][wp]
   float* red = wres + 16 * wp;               // [4][2][4][64]
-  int* lds_flag = reinterpret_cast<int*>(red + 4 * 2 * 4 * 64);
+  float* stage = red + 4 * 2 * 4 * 64;       // [32][SP]: the step's dgh tile, batch row x gate row
+  int* lds_flag = reinterpret_cast<int*>(stage + PR * SP);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kw = wave & 3, rsel = wave >> 2;
   const int lr = lane & 15, lg = lane >> 4;
@@ -289,7 +302,30 @@ gru_bwd_persist_kernel(const float* __restrict__ WT, long s_wt, float* dgh, floa
   unsigned* abort_w = sync;
   unsigned* ctr = sync + 1 + sg;
   __builtin_amdgcn_s_setprio(3);
-  load_resident(wres, wp, WT + g * s_wt + (long)j0 * H3, 16, H3, [&](int row) { return (long)row * H3; });
+  // weight-gradient share: this lane's 4 columns (clamped: results outside H are not stored)
+  const int wn = 64 * wave + 4 * lr;
+  const bool wn_ok = dWp != nullptr && wn < H;
+  const int wnc = wn < H ? wn : 0;
+  floatx4 dw[3][4];
+#pragma unroll
+  for (int mt = 0; mt < 3; ++mt)
+#pragma unroll
+    for (int jt = 0; jt < 4; ++jt) dw[mt][jt] = (floatx4){0.f, 0.f, 0.f, 0.f};
+  {
+    // wres[m][k] = W_hh[k][j0 + m]: 64-byte pieces of 3H rows, transposed on the way into LDS
+    const float* Wg = W_hh + g * s_rep + j0;
+    for (int u = tid; u < H3 * 4; u += PNT) {
+      const int k = u >> 2, c4 = u & 3;
+      const float4 v = *reinterpret_cast<const float4*>(Wg + (long)k * H + 4 * c4);
+      wres[(4 * c4 + 0) * wp + k] = v.x;
+      wres[(4 * c4 + 1) * wp + k] = v.y;
+      wres[(4 * c4 + 2) * wp + k] = v.z;
+      wres[(4 * c4 + 3) * wp + k] = v.w;
+    }
+    const int padk = wp - 4 - H3;  // zero columns up to the next multiple of the chunk
+    for (int u = tid; u < 16 * padk; u += PNT) wres[(u / padk) * wp + H3 + u % padk] = 0.f;
+  }
+  float bsum[4] = {0.f, 0.f, 0.f, 0.f};  // this thread's da_r, da_z, da_n, dq summed over the steps
   const int j = j0 + lr;
   const int row = r0 + rsel * 16 + 4 * lg + kw;
   const int rowc = min(row, B - 1);
@@ -333,9 +369,73 @@ gru_bwd_persist_kernel(const float* __restrict__ WT, long s_wt, float* dgh, floa
       st_dev(&oh[2 * H + j], dq);
     }
     dcar = dh * z;
-    group_signal(ctr);
+    if (row < B) {
+      bsum[0] += da_r;
+      bsum[1] += da_z;
+      bsum[2] += da_n;
+      bsum[3] += dq;
+    }
+    float4 hv[8];
+    if (dWp) {  // uniform
+      // rows beyond the batch contribute nothing: their staged gradients are zero, their h is
+      // read from a valid row
+      const bool rv = row < B;
+      float* st = stage + (rsel * 16 + 4 * lg + kw) * SP + lr;
+      st[0] = rv ? da_r : 0.f;
+      st[16] = rv ? da_z : 0.f;
+      st[32] = rv ? dq : 0.f;
+      const float* hrow = hs + g * s_hs + (long)t * B * H + wnc;
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8)
+        hv[s8] = *reinterpret_cast<const float4*>(hrow + (long)min(r0 + 4 * s8 + lg, B - 1) * H);
+    }
+    group_signal(ctr);  // (its barrier also publishes the staged tile to the workgroup)
+    if (dWp) {
+#pragma unroll
+      for (int s8 = 0; s8 < 8; ++s8) {
+        float am[3];
+#pragma unroll
+        for (int mt = 0; mt < 3; ++mt) am[mt] = stage[(4 * s8 + lg) * SP + mt * 16 + lr];
+#pragma unroll
+        for (int mt = 0; mt < 3; ++mt) {
+          dw[mt][0] = __builtin_amdgcn_mfma_f32_16x16x4f32(am[mt], hv[s8].x, dw[mt][0], 0, 0, 0);
+          dw[mt][1] = __builtin_amdgcn_mfma_f32_16x16x4f32(am[mt], hv[s8].y, dw[mt][1], 0, 0, 0);
+          dw[mt][2] = __builtin_amdgcn_mfma_f32_16x16x4f32(am[mt], hv[s8].z, dw[mt][2], 0, 0, 0);
+          dw[mt][3] = __builtin_amdgcn_mfma_f32_16x16x4f32(am[mt], hv[s8].w, dw[mt][3], 0, 0, 0);
+        }
+      }
+    }
   }
   if (row < B) Dg[(long)row * H + j] = dcar;
+  if (dbp) {  // uniform
+    // bias gradients: sums over the tile's 32 batch rows, in row order; one partial sum per
+    // batch-row tile: [b_ih: r | z | n][b_hh: r | z | q], 6H floats
+    __syncthreads();
+    float* bs = stage;  // [32][64]: row, then 4 sums x 16 units
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bs[(rsel * 16 + 4 * lg + kw) * 64 + i * 16 + lr] = bsum[i];
+    __syncthreads();
+    if (tid < 64) {
+      float tot = 0.f;
+      for (int r32 = 0; r32 < PR; ++r32) tot += bs[r32 * 64 + tid];
+      const int i = tid >> 4, jj = j0 + (tid & 15);
+      float* out = dbp + (long)(g * RT + ty) * 6 * H;
+      if (i == 0) out[jj] = out[H3 + jj] = tot;
+      if (i == 1) out[H + jj] = out[H3 + H + jj] = tot;
+      if (i == 2) out[2 * H + jj] = tot;
+      if (i == 3) out[H3 + 2 * H + jj] = tot;
+    }
+  }
+  if (wn_ok) {
+    // accumulator register v of tile (mt, jt): gate row mt*16 + 4*lg + v, column wn + jt
+    float* out = dWp + ((long)(g * RT + ty) * H3) * H;
+#pragma unroll
+    for (int mt = 0; mt < 3; ++mt)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        *reinterpret_cast<float4*>(out + ((long)mt * H + j0 + 4 * lg + v) * H + wn) =
+            make_float4(dw[mt][0][v], dw[mt][1][v], dw[mt][2][v], dw[mt][3][v]);
+  }
 }
 
 int device_cus() {
@@ -368,6 +468,9 @@ bool gru_persist_supported(int B, int H, int groups) {
   return grid <= device_cus();
 }
 
+// The backward kernel can accumulate dW_hh itself when 8 waves x 64 columns cover H.
+bool gru_persist_dw_supported(int H) { return H <= 512; }
+
 // Words of device memory the kernels synchronise through: the abort word + one counter per group.
 size_t gru_persist_sync_words(int B, int groups) { return (size_t)groups * ((B + PR - 1) / PR) + 1; }
 
@@ -394,13 +497,16 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
   return hipGetLastError();
 }
 
-hipError_t launch_gru_bwd_persist(const float* WT, long s_wt, float* dgh, float* dgx, long s_dg, float* D,
+hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dgx, long s_dg, float* D,
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
-                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit,
-                                  hipStream_t s) {
+                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
+                                  float* dbp, hipStream_t s) {
   if (!gru_persist_supported(B, H, groups) || t_lo < 0 || t_hi > T || t_lo >= t_hi) return hipErrorInvalidValue;
-  if (((uintptr_t)dgh & 15) != 0 || (s_dg & 3) != 0 || ((uintptr_t)WT & 15) != 0 || (s_wt & 3) != 0)
+  if (dWp && (!gru_persist_dw_supported(H) || ((uintptr_t)dWp & 15) != 0 || ((uintptr_t)hs & 15) != 0 ||
+              (s_hs & 3) != 0))
+    return hipErrorInvalidValue;
+  if (((uintptr_t)dgh & 15) != 0 || (s_dg & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0)
     return hipErrorInvalidValue;
   const size_t lds = persist_lds_bytes(H);
   static size_t allowed = 0;
@@ -411,8 +517,8 @@ hipError_t launch_gru_bwd_persist(const float* WT, long s_wt, float* dgh, float*
     allowed = lds;
   }
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
-  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, WT, s_wt, dgh, dgx, s_dg, D, s_D, above,
-                     s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit);
+  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dgx, s_dg, D, s_D, above,
+                     s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit, dWp, dbp);
   return hipGetLastError();
 }
 

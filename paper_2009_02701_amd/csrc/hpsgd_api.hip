@@ -36,6 +36,7 @@ struct hpsgd_ctx {
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
   Region psync;                 // abort word and counters of the resident-weight recurrence kernels (fp32)
+  Region dwp, dbp;              // their partial sums of dW_hh and of the bias gradients, one per 32-row batch tile
   Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
@@ -122,7 +123,12 @@ int build_layout(hpsgd_ctx* c) {
     c->gh = c->alloc((size_t)d.batch * 3 * H);
     c->D = c->alloc((size_t)d.batch * H);
     c->wt = c->alloc(3 * H * H);
-    if (d.prec != HPSGD_BF16_MFMA) c->psync = c->alloc(gru_persist_sync_words(d.batch, 1));
+    if (d.prec != HPSGD_BF16_MFMA) {
+      c->psync = c->alloc(gru_persist_sync_words(d.batch, 1));
+      if (gru_fused_supported(d.hidden) && gru_persist_dw_supported(d.hidden))
+        c->dwp = c->alloc((size_t)((d.batch + 31) / 32) * 3 * H * H);
+      if (gru_fused_supported(d.hidden)) c->dbp = c->alloc((size_t)((d.batch + 31) / 32) * 6 * H);
+    }
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
@@ -646,7 +652,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const bool stepT = fused_b && ntc && win % 8 == 0;  // the step kernels write the bf16 copies
       __bf16* dgxb = stepT ? bfreg(c->dgxb) : nullptr;
       const long s_T = 2 * (long)c->dgxT.stride;
-      if (fused) {
+      if (fused && !(use_persist)) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
       }
@@ -665,6 +671,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // cut into chunks; chunk c's GEMMs are issued when BPTT has walked past it, the last
       // one follows on the main stream after the join.  Fixed chunking: deterministic.
       const bool persist = fused && use_persist;
+      // the resident-weight kernel accumulates dW_hh itself (one partial sum per batch-row tile)
+      float* dwp = (persist && c->dwp.stride == (size_t)((B + 31) / 32) * 3 * H * H) ? reg(c->dwp) : nullptr;
+      // ... and the bias gradients, when their partial sums can be added with 16-byte accesses
+      float* dbp = (persist && c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H && (sG & 3) == 0 &&
+                    ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
+                    c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H)
+                       ? reg(c->dbp)
+                       : nullptr;
       const int NC = (c->aux && fused && !persist && T >= 8) ? 4 : 1;
       auto chunk_lo = [&](int ch) { return (int)((long)T * ch / NC); };
       auto wgrad_rows = [&](hipStream_t st, int t0, int t1, int epi) -> int {
@@ -685,8 +699,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // that shares the CUs with this launch slows its chain of waits by more than it hides)
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
-        HIP_TRY(launch_gru_bwd_persist(wt, s_wt, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
-                                       T, 0, groups, psync, pbase, c->spin_limit, s));
+        HIP_TRY(launch_gru_bwd_persist(Whh, sR, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
+                                       T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
       }
       for (int t = T - 1; t >= 0 && !persist; --t) {
@@ -779,12 +793,23 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
                   wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr));
         const WgradTarget wh = wgrad_target(p + ".W_hh");
-        TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
-                  wh.aux, sR, v_dghT, v_hsT, lr));
+        if (dwp) {
+          TimerScope ts_(c, role, s);
+          HIP_TRY(launch_reduce_parts(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sR, wh.C, (size_t)wh.sC,
+                                      lr, wh.epi == EPI_COMMIT, groups, s));
+        } else {
+          TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
+                    wh.aux, sR, v_dghT, v_hsT, lr));
+        }
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
-      HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
-      HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
+      if (dbp) {
+        HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + c->off(p + ".b_ih"),
+                                    (size_t)sG, 0.f, 0, groups, s));
+      } else {
+        HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
+        HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
+      }
       role = HPSGD_ROLE_OTHER;
       if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
     }

@@ -92,11 +92,20 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
                                   float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
                                   unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
 // steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches)
-hipError_t launch_gru_bwd_persist(const float* WT, long s_wt, float* dgh, float* dgx, long s_dg, float* D,
+hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dgx, long s_dg, float* D,
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
-                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit,
-                                  hipStream_t s);
+                                  int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
+                                  float* dbp, hipStream_t s);
+// dbp != nullptr: the launch also leaves dbp[(g * RT + ty)][6H], partial sums over its steps of the
+// bias gradients (b_ih: sum of dgx, then b_hh: sum of dgh)
+// dWp != nullptr (allowed when gru_persist_dw_supported(H)): the launch also leaves
+// dWp[(g * RT + ty)][3H][H], RT = ceil(B / 32) partial sums of dW_hh over its steps per worker.
+bool gru_persist_dw_supported(int H);
+// out[g][i] = in[g][i] - lr * sum_p parts[(g * n_parts + p)][i]  (commit != 0; in may be out)
+// out[g][i] = sum_p parts[(g * n_parts + p)][i]                   (commit == 0)
+hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
+                               float* out, size_t s_out, float lr, int commit, int groups, hipStream_t s);
 // NaN into loss[0..n_loss) and into rout[g * s_rout] for every group if *abort_w != 0
 hipError_t launch_poison_on_abort(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
                                   int groups, hipStream_t s);

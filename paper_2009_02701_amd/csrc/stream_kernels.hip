@@ -176,6 +176,43 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
   return hipGetLastError();
 }
 
+// Partial sums of a weight gradient (one per batch-row tile of the recurrence kernel), added in
+// tile order, then either committed (out = in - lr * sum) or stored (out = sum).  n % 4 == 0.
+__global__ void __launch_bounds__(kThreads)
+reduce_parts_kernel(const float* __restrict__ parts, int n_parts, size_t n4, const float* in, size_t s_in,
+                    float* out, size_t s_out, float lr, int commit) {
+  const size_t k = blockIdx.y;
+  const float4* pk = reinterpret_cast<const float4*>(parts) + k * n_parts * n4;
+  for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
+    float4 sum = pk[i];
+    for (int p = 1; p < n_parts; ++p) {
+      const float4 v = pk[p * n4 + i];
+      sum.x += v.x;
+      sum.y += v.y;
+      sum.z += v.z;
+      sum.w += v.w;
+    }
+    if (commit) {
+      const float4 w = reinterpret_cast<const float4*>(in + k * s_in)[i];
+      sum = make_float4(w.x - lr * sum.x, w.y - lr * sum.y, w.z - lr * sum.z, w.w - lr * sum.w);
+    }
+    reinterpret_cast<float4*>(out + k * s_out)[i] = sum;
+  }
+}
+
+hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
+                               float* out, size_t s_out, float lr, int commit, int groups, hipStream_t s) {
+  if (n == 0 || groups <= 0) return hipSuccess;
+  if (n_parts < 1 || (n & 3) != 0 || ((uintptr_t)parts & 15) != 0 || ((uintptr_t)out & 15) != 0 || (s_out & 3) != 0 ||
+      (commit && (!in || ((uintptr_t)in & 15) != 0 || (s_in & 3) != 0)))
+    return hipErrorInvalidValue;
+  const size_t n4 = n / 4;
+  const int blocks = onepass_blocks(n4);
+  hipLaunchKernelGGL(reduce_parts_kernel, dim3(blocks, groups), dim3(kThreads), 0, s, parts, n_parts, n4, in, s_in,
+                     out, s_out, lr, commit);
+  return hipGetLastError();
+}
+
 // out[k][j] = in[k][j] - lr * grad[k][j];  acc[k][j] += grad[k][j]  (Alg. 2: update the replica and
 // accumulate the gradient in one pass, 20 B/param)
 __global__ void __launch_bounds__(kThreads)
