@@ -130,52 +130,69 @@ __device__ __forceinline__ void load_resident(float* wres, int wp, const float* 
 // workgroup's activation tile (row pitch KD words); rows >= rows_valid are read from row 0:
 // their results are never stored.  Columns beyond KD are read from column 0 and meet a zero
 // weight.  NB: chunks per wave whose loads are in flight together.
+// the loads of NB chunks of this wave, first chunk c0 (= wave & 3, + 4 per chunk)
+template <int NB>
+__device__ __forceinline__ void fragment_loads(__amdgpu_buffer_rsrc_t rs, int KD, int rows_valid, int c0,
+                                               float4 (&a)[NB][2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int rsel = wave >> 2, lr = lane & 15, lg = lane >> 4;
+  const int row = rsel * 16 + lr;
+  const int rowoff = (row < rows_valid ? row : 0) * KD;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int k0 = PC * (c0 + 4 * i) + 4 * lg;
+    // (KD is a multiple of 16: each piece is all in or all out)
+    a[i][0] = ld16_dev(rs, (rowoff + (k0 < KD ? k0 : 0)) * 4);
+    a[i][1] = ld16_dev(rs, (rowoff + (k0 + 16 < KD ? k0 + 16 : 0)) * 4);
+  }
+}
+
+// ... and their products with the resident rows
+template <int NQ, int NB>
+__device__ __forceinline__ void fragment_mfmas(const float* wres, int wp, int KD, int c0, const float4 (&a)[NB][2],
+                                               floatx4 (&acc)[2][NQ]) {
+  const int lane = threadIdx.x & 63;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int nch = (KD + PC - 1) / PC;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    // branch-free (a branch would pull the loads of its chunk in behind it): a chunk slot
+    // beyond the contraction reads weight column 0 and gets zeros instead
+    const int c = c0 + 4 * i;
+    const bool cv = c < nch;  // uniform over the wave
+    const int cc = cv ? c : 0;
+    float4 w[NQ][2];
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+      const float* wr = &wres[(q * 16 + lr) * wp + PC * cc + 4 * lg];
+      const float4 w0 = *reinterpret_cast<const float4*>(wr);
+      const float4 w1 = *reinterpret_cast<const float4*>(wr + 16);
+      w[q][0] = make_float4(cv ? w0.x : 0.f, cv ? w0.y : 0.f, cv ? w0.z : 0.f, cv ? w0.w : 0.f);
+      w[q][1] = make_float4(cv ? w1.x : 0.f, cv ? w1.y : 0.f, cv ? w1.z : 0.f, cv ? w1.w : 0.f);
+    }
+    // consecutive MFMAs update different accumulators
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int q = 0; q < NQ; ++q) {
+        const float4 av = a[i][e >> 2], wv = w[q][e >> 2];
+        const float as = (e & 3) == 0 ? av.x : (e & 3) == 1 ? av.y : (e & 3) == 2 ? av.z : av.w;
+        const float ws = (e & 3) == 0 ? wv.x : (e & 3) == 1 ? wv.y : (e & 3) == 2 ? wv.z : wv.w;
+        acc[e & 1][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, ws, acc[e & 1][q], 0, 0, 0);
+      }
+  }
+}
+
 template <int NQ, int NB>
 __device__ __forceinline__ void resident_contraction(const float* wres, int wp, __amdgpu_buffer_rsrc_t rs, int KD,
                                                      int rows_valid, floatx4 (&acc)[2][NQ]) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int kw = wave & 3, rsel = wave >> 2;
-  const int lr = lane & 15, lg = lane >> 4;
-  const int row = rsel * 16 + lr;
-  const int rowoff = (row < rows_valid ? row : 0) * KD;
+  const int kw = (threadIdx.x >> 6) & 3;
   const int nch = (KD + PC - 1) / PC;
   for (int c0 = kw; c0 < nch; c0 += 4 * NB) {
     float4 a[NB][2];
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      const int k0 = PC * (c0 + 4 * i) + 4 * lg;
-      // (KD is a multiple of 16: each piece is all in or all out)
-      a[i][0] = ld16_dev(rs, (rowoff + (k0 < KD ? k0 : 0)) * 4);
-      a[i][1] = ld16_dev(rs, (rowoff + (k0 + 16 < KD ? k0 + 16 : 0)) * 4);
-    }
+    fragment_loads<NB>(rs, KD, rows_valid, c0, a);
     __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
-#pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      // branch-free (a branch would pull the loads of its chunk in behind it): a chunk slot
-      // beyond the contraction reads weight column 0 and gets zeros instead
-      const int c = c0 + 4 * i;
-      const bool cv = c < nch;  // uniform over the wave
-      const int cc = cv ? c : 0;
-      float4 w[NQ][2];
-#pragma unroll
-      for (int q = 0; q < NQ; ++q) {
-        const float* wr = &wres[(q * 16 + lr) * wp + PC * cc + 4 * lg];
-        const float4 w0 = *reinterpret_cast<const float4*>(wr);
-        const float4 w1 = *reinterpret_cast<const float4*>(wr + 16);
-        w[q][0] = make_float4(cv ? w0.x : 0.f, cv ? w0.y : 0.f, cv ? w0.z : 0.f, cv ? w0.w : 0.f);
-        w[q][1] = make_float4(cv ? w1.x : 0.f, cv ? w1.y : 0.f, cv ? w1.z : 0.f, cv ? w1.w : 0.f);
-      }
-      // consecutive MFMAs update different accumulators
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-#pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-          const float4 av = a[i][e >> 2], wv = w[q][e >> 2];
-          const float as = (e & 3) == 0 ? av.x : (e & 3) == 1 ? av.y : (e & 3) == 2 ? av.z : av.w;
-          const float ws = (e & 3) == 0 ? wv.x : (e & 3) == 1 ? wv.y : (e & 3) == 2 ? wv.z : wv.w;
-          acc[e & 1][q] = __builtin_amdgcn_mfma_f32_16x16x4f32(as, ws, acc[e & 1][q], 0, 0, 0);
-        }
-    }
+    fragment_mfmas<NQ, NB>(wres, wp, KD, c0, a, acc);
   }
 }
 
@@ -187,16 +204,27 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
 // given), gx the input projections of all steps, sv receives r|z|n|q of every step.
 // sync: the abort word, then one counter per synchronisation group; `base` is what the
 // counters read when the kernel starts.
+// XP: the kernel computes the input projection itself, gx_t = x_t W_ih^T + b_ih, from the
+// layer input xin (blocks of B x width per step) with its 48 rows of W_ih resident in LDS too;
+// that part of a step does not depend on the other workgroups and is done before the wait.
+// The r and z gates then take one sum over both contractions; gx is not used.
+template <int XNB>  // chunks of the layer input per wave (width <= 128 * XNB); 0: gx is given
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
                        const float* __restrict__ gx, long s_gx, float* hs, long s_hs, float* __restrict__ sv,
                        long s_sv, int B, int H, int T, int groups, unsigned* sync, unsigned base,
-                       unsigned spin_limit) {
+                       unsigned spin_limit, const float* __restrict__ xin, long s_x, int width,
+                       const float* __restrict__ W_ih, const float* __restrict__ b_ih) {
   extern __shared__ __attribute__((aligned(16))) float persist_lds[];
+  constexpr bool XP = XNB > 0;
+  constexpr int XB = XP ? XNB : 1;
+  constexpr int NP = XP ? 4 : 3;             // planes of partial sums: r, z, q (+ the x part of n)
   const int wp = (H + PC - 1) / PC * PC + 4;
+  const int wp2 = XP ? (width + PC - 1) / PC * PC + 4 : 0;
   float* wres = persist_lds;                 // [48][wp]
-  float* red = wres + 48 * wp;               // [4][6][4][64]
-  int* lds_flag = reinterpret_cast<int*>(red + 4 * 6 * 4 * 64);
+  float* red = wres + 48 * wp;               // [4][2][NP][4][64]
+  float* wres2 = red + 4 * 2 * NP * 4 * 64;  // [48][wp2]
+  int* lds_flag = reinterpret_cast<int*>(wres2 + 48 * wp2);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kw = wave & 3, rsel = wave >> 2;
   const int lr = lane & 15, lg = lane >> 4;
@@ -207,48 +235,75 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
   unsigned* abort_w = sync;
   unsigned* ctr = sync + 1 + sg;
   __builtin_amdgcn_s_setprio(3);
-  // the resident slice: rows q*16 + r = W_hh[q*H + j0 + r][:]
+  // the resident slices: rows q*16 + r = W_hh[q*H + j0 + r][:] (and the same rows of W_ih)
   load_resident(wres, wp, W_hh + g * s_rep, 48, H,
                 [&](int row) { return ((long)(row >> 4) * H + j0 + (row & 15)) * H; });
+  if (XP)
+    load_resident(wres2, wp2, W_ih + g * s_rep, 48, width,
+                  [&](int row) { return ((long)(row >> 4) * H + j0 + (row & 15)) * width; });
   const int j = j0 + lr;
   const int row = r0 + rsel * 16 + 4 * lg + kw;     // this thread's element of the tile
   const int rowc = min(row, B - 1);                 // loads are clamped, stores guarded
   const float* bh = b_hh + g * s_rep;
-  float bias[3];
+  float bias[3], biasx[3] = {0.f, 0.f, 0.f};
 #pragma unroll
   for (int q = 0; q < 3; ++q) bias[q] = bh[q * H + j];
+  if (XP) {
+#pragma unroll
+    for (int q = 0; q < 3; ++q) biasx[q] = (b_ih + g * s_rep)[q * H + j];
+  }
   float* hsg = hs + g * s_hs;
   float hpv = hsg[(long)rowc * H + j];
+  float4 xa[XB][2];  // the next step's fragments of the layer input
+  if (XP) fragment_loads<XB>(tile_rsrc(xin + g * s_x + (long)r0 * width), width, B - r0, kw, xa);
   __syncthreads();
   for (int t = 0; t < T; ++t) {
-    // the epilogue's inputs do not depend on the recurrence: they travel during the wait
-    const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H;
-    float gxv[3];
+    // what does not depend on the recurrence travels, or is computed, during the wait
+    float gxv[3] = {0.f, 0.f, 0.f};
+    floatx4 acc[2][3], accx[2];
 #pragma unroll
-    for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
-    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
-    floatx4 acc[2][3];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < 2; ++i) {
 #pragma unroll
       for (int q = 0; q < 3; ++q) acc[i][q] = (floatx4){0.f, 0.f, 0.f, 0.f};
+      accx[i] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    }
+    if (XP) {
+      fragment_mfmas<3, XB>(wres2, wp2, width, kw, xa, acc);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        accx[i] = acc[i][2];  // n keeps its two parts apart: n = tanh(x part + r * (h part))
+        acc[i][2] = (floatx4){0.f, 0.f, 0.f, 0.f};
+      }
+      // the fragments of step t+1 are on their way during the wait and the recurrent product
+      __builtin_amdgcn_sched_barrier(0);
+      fragment_loads<XB>(tile_rsrc(xin + g * s_x + ((long)min(t + 1, T - 1) * B + r0) * width), width, B - r0, kw,
+                         xa);
+    } else {
+      const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H;
+#pragma unroll
+      for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
+    }
+    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
     resident_contraction<3, 4>(wres, wp, tile_rsrc(hsg + ((long)t * B + r0) * H), H, B - r0, acc);
 #pragma unroll
-    for (int q = 0; q < 3; ++q)
+    for (int v = 0; v < 4; ++v) {
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        red[((kw * 6 + rsel * 3 + q) * 4 + v) * 64 + lane] = acc[0][q][v] + acc[1][q][v];
-    __syncthreads();
-    float gh[3];
-#pragma unroll
-    for (int q = 0; q < 3; ++q) {
-      const int o = ((rsel * 3 + q) * 4 + kw) * 64 + lane;
-      gh[q] = ((red[o] + red[o + 6 * 256]) + (red[o + 12 * 256] + red[o + 18 * 256])) + bias[q];
+      for (int q = 0; q < 3; ++q)
+        red[(((kw * 2 + rsel) * NP + q) * 4 + v) * 64 + lane] = acc[0][q][v] + acc[1][q][v];
+      if (XP) red[(((kw * 2 + rsel) * NP + 3) * 4 + v) * 64 + lane] = accx[0][v] + accx[1][v];
     }
-    const float r = sigm_p(gxv[0] + gh[0]);
-    const float z = sigm_p(gxv[1] + gh[1]);
-    const float qv = gh[2];
-    const float n = tanhf(gxv[2] + r * qv);
+    __syncthreads();
+    float gh[NP];
+#pragma unroll
+    for (int q = 0; q < NP; ++q) {
+      const int o = ((rsel * NP + q) * 4 + kw) * 64 + lane;
+      constexpr int PL = 2 * NP * 256;  // one wave quarter's partial sums
+      gh[q] = (red[o] + red[o + PL]) + (red[o + 2 * PL] + red[o + 3 * PL]);
+    }
+    const float r = sigm_p(gxv[0] + biasx[0] + (gh[0] + bias[0]));
+    const float z = sigm_p(gxv[1] + biasx[1] + (gh[1] + bias[1]));
+    const float qv = gh[2] + bias[2];
+    const float n = tanhf((XP ? gh[NP - 1] + biasx[2] : gxv[2]) + r * qv);
     const float hn = (1.0f - z) * n + z * hpv;
     if (row < B) {
       st_dev(&hsg[((long)(t + 1) * B + row) * H + j], hn);
@@ -456,6 +511,11 @@ constexpr size_t kLdsLimit = 160 * 1024;
 size_t persist_lds_bytes(int H) {
   return ((size_t)48 * ((H + PC - 1) / PC * PC + 4) + 4 * 6 * 4 * 64 + 4) * sizeof(float);
 }
+// forward with the input projection: a fourth plane of partial sums and 48 rows of W_ih
+size_t persist_xp_lds_bytes(int H, int width) {
+  return ((size_t)48 * ((H + PC - 1) / PC * PC + 4) + 4 * 8 * 4 * 64 + (size_t)48 * ((width + PC - 1) / PC * PC + 4) +
+          4) * sizeof(float);
+}
 
 }  // namespace
 
@@ -477,23 +537,42 @@ size_t gru_persist_sync_words(int B, int groups) { return (size_t)groups * ((B +
 // How much every counter advances per time step of a launch.
 unsigned gru_persist_count_per_step(int H) { return (unsigned)(H / PJ); }
 
+// The forward kernel can do the input projection itself when the layer input is narrow enough
+// for the 48 rows of W_ih to fit the LDS beside those of W_hh (at most 2 x 4 chunks of 32).
+bool gru_persist_xproj_supported(int H, int width) {
+  return width >= 16 && width % 16 == 0 && width <= 256 && persist_xp_lds_bytes(H, width) <= kLdsLimit;
+}
+
 hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
                                   float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
-                                  unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s) {
+                                  unsigned* sync, unsigned base, unsigned spin_limit, const float* xin, long s_x,
+                                  int width, const float* W_ih, const float* b_ih, hipStream_t s) {
   if (!gru_persist_supported(B, H, groups) || T < 1) return hipErrorInvalidValue;
   if (((uintptr_t)hs & 15) != 0 || (s_hs & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0)
     return hipErrorInvalidValue;
-  const size_t lds = persist_lds_bytes(H);
-  static size_t allowed = 0;
-  if (lds > allowed) {
-    hipError_t e = hipFuncSetAttribute((const void*)gru_fwd_persist_kernel,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  if (xin && (!gru_persist_xproj_supported(H, width) || !W_ih || !b_ih || ((uintptr_t)xin & 15) != 0 ||
+              (s_x & 3) != 0 || ((uintptr_t)W_ih & 15) != 0))
+    return hipErrorInvalidValue;
+  if (!xin && !gx) return hipErrorInvalidValue;
+  const size_t lds = xin ? persist_xp_lds_bytes(H, width) : persist_lds_bytes(H);
+  const int xnb = !xin ? 0 : width <= 128 ? 1 : 2;
+  static size_t allowed[3] = {0, 0, 0};
+  const void* fn = xnb == 0   ? (const void*)gru_fwd_persist_kernel<0>
+                   : xnb == 1 ? (const void*)gru_fwd_persist_kernel<1>
+                              : (const void*)gru_fwd_persist_kernel<2>;
+  if (lds > allowed[xnb]) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    allowed = lds;
+    allowed[xnb] = lds;
   }
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
-  hipLaunchKernelGGL(gru_fwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, b_hh, s_rep, gx, s_gx, hs, s_hs, sv,
-                     s_sv, B, H, T, groups, sync, base, spin_limit);
+#define HPSGD_FWD_PERSIST(N)                                                                                    \
+  hipLaunchKernelGGL(gru_fwd_persist_kernel<N>, grid, dim3(PNT), lds, s, W_hh, b_hh, s_rep, gx, s_gx, hs, s_hs, \
+                     sv, s_sv, B, H, T, groups, sync, base, spin_limit, xin, s_x, width, W_ih, b_ih)
+  if (xnb == 0) HPSGD_FWD_PERSIST(0);
+  else if (xnb == 1) HPSGD_FWD_PERSIST(1);
+  else HPSGD_FWD_PERSIST(2);
+#undef HPSGD_FWD_PERSIST
   return hipGetLastError();
 }
 

@@ -432,7 +432,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
       const bool persist = fused && use_persist;
-      {
+      // a narrow layer input: the resident-weight kernel does the input projection itself
+      const float* Wih0 = rin + c->off(p + ".W_ih");
+      const bool xproj = persist && gru_persist_xproj_supported(H, width) && ((uintptr_t)lin & 15) == 0 &&
+                         (s_lin & 3) == 0 && ((uintptr_t)Wih0 & 15) == 0;
+      if (!xproj) {
         const float* Wih = rin + c->off(p + ".W_ih");
         NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
         // bf16 precision: both operands as row-major bf16 copies (the layer below wrote its
@@ -491,7 +495,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->off(p + ".b_hh"), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
-                                       groups, psync, pbase, c->spin_limit, s));
+                                       groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
+                                       Wih0, rin + c->off(p + ".b_ih"), s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
       }
       for (int t = 0; t < T && !persist; ++t) {

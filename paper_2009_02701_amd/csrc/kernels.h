@@ -90,7 +90,12 @@ size_t gru_persist_sync_words(int B, int groups);
 unsigned gru_persist_count_per_step(int H);
 hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
                                   float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
-                                  unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
+                                  unsigned* sync, unsigned base, unsigned spin_limit, const float* xin, long s_x,
+                                  int width, const float* W_ih, const float* b_ih, hipStream_t s);
+// xin != nullptr (allowed when gru_persist_xproj_supported(H, width)): the launch computes the input
+// projection itself from the layer input xin (T blocks of B x width per worker, stride s_x) and W_ih,
+// b_ih (in the replica, like W_hh); gx is then unused and may be nullptr.
+bool gru_persist_xproj_supported(int H, int width);
 // steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches)
 hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dgx, long s_dg, float* D,
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
