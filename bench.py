@@ -21,11 +21,12 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of a role's kernel on the default workload, from two rocprofv3 --pmc runs
+# HBM bytes per launch of a role's kernel on the default workload (one launch = the recurrence of
+# all 35 time steps of the layer, all 4 workers), from two rocprofv3 --pmc runs
 # (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration with a plain 1 GiB copy kernel;
 # summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Other workloads: not collected (null).
 MEASURED_TRAFFIC_BYTES = {
-    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 9037.9 + 3584.0) * 1024, "gemm_recurrent_fwd": (2.0 * 7497.3 + 2560.0) * 1024},
+    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 84006.3 + 132984.0) * 1024, "gemm_recurrent_fwd": (2.0 * 27453.2 + 89880.0) * 1024},
 }
 
 
@@ -65,10 +66,14 @@ def mfma_probe(hb, torch, dev, prec):
     return out
 
 
-def role_work_per_step(cfg, role_name, commit_params=None):
+def role_work_per_step(cfg, role_name, commit_params=None, fused=(0, 0, 0)):
     """Algorithmic work of ALL launches of a role in one local step of all K workers:
     (bound, flops or bytes per step, peak in the same unit per second).  commit_params: how many
-    parameters per worker the commit kernel handled (the rest are updated in GEMM epilogues)."""
+    parameters per worker the commit kernel handled (the rest are updated in GEMM epilogues).
+    fused = (resident, xproj, dw) from Context.recurrence_info(): the bottom `xproj` layers' input
+    projections are part of the forward recurrence launches and the top-to-bottom first `dw`
+    layers' dW_hh products part of the backward ones (every layer when dw == layers), so their
+    flops are counted with those roles."""
     kind, K, B = cfg["kind"], cfg["K"], cfg["batch"]
     mfma_peak = (PEAK_BF16_MFMA_TFLOPS if cfg.get("prec") == "bf16" else PEAK_FP32_MFMA_TFLOPS) * 1e12
     hbm = PEAK_HBM_GBS * 1e9
@@ -91,11 +96,16 @@ def role_work_per_step(cfg, role_name, commit_params=None):
     P = sum(3 * H * w + 3 * H * H + 6 * H for w in widths) + classes * H + classes + (cfg["vocab"] * cfg["embed"] if lm else 0)
     if commit_params is not None:
         P = commit_params
+    _, n_xproj, n_dw = fused
+    # a layer's input projection is fused only where its input is narrow: the narrowest first
+    xproj_flops = sum(sorted(2.0 * TB * 3 * H * w for w in widths)[:n_xproj]) * K
+    dw_flops = n_dw * 2.0 * 3 * H * H * TB * K
     table = {
-        "gemm_input_projection": ("mfma", sum(2.0 * TB * 3 * H * w for w in widths) * K, mfma_peak),
-        "gemm_recurrent_fwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K, mfma_peak),
-        "gemm_recurrent_bwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K, mfma_peak),
-        "gemm_weight_grad": ("mfma", sum(2.0 * 3 * H * w * TB + 2.0 * 3 * H * H * TB for w in widths) * K, mfma_peak),
+        "gemm_input_projection": ("mfma", sum(2.0 * TB * 3 * H * w for w in widths) * K - xproj_flops, mfma_peak),
+        "gemm_recurrent_fwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K + xproj_flops, mfma_peak),
+        "gemm_recurrent_bwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K + dw_flops, mfma_peak),
+        "gemm_weight_grad": ("mfma", sum(2.0 * 3 * H * w * TB + 2.0 * 3 * H * H * TB for w in widths) * K - dw_flops,
+                             mfma_peak),
         "gemm_input_grad": ("mfma", sum(2.0 * TB * 3 * H * w for w in (widths if lm else widths[1:])) * K, mfma_peak),
         "gemm_head": ("mfma", 3 * 2.0 * nrows * classes * H * K, mfma_peak),
         "gru_cell_fwd": ("hbm", 48.0 * B * H * T * L * K, hbm),
@@ -152,6 +162,7 @@ def main():
             breakdown[nm] = {"launches_per_step": n / probe_rounds, "avg_us": 1e3 * ms / n,
                              "us_per_step": 1e3 * ms / probe_rounds}
     commit_params = tr.ctx.commit_kernel_params()
+    fused = tr.ctx.recurrence_info()
     dominant = max(breakdown, key=lambda k: breakdown[k]["us_per_step"])
     dom_role = names.index(dominant)
     tr.ctx.timer_enable([dom_role])
@@ -226,7 +237,7 @@ def main():
         run()
         forms[name] = 32 * samples_per_step / (time.perf_counter() - c0)
 
-    bound, work, peak = role_work_per_step(cfg, dominant, commit_params)
+    bound, work, peak = role_work_per_step(cfg, dominant, commit_params, fused)
     roofline = None
     if bound is not None and n_dom:
         dur = ms_dom * 1e-3 / n_dom
@@ -238,7 +249,7 @@ def main():
                     "ms_per_step_with_event_pairs": ms_per_step_instrumented,
                     "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)}
     for nm, v in breakdown.items():
-        b_, w_, p_ = role_work_per_step(cfg, nm, commit_params)
+        b_, w_, p_ = role_work_per_step(cfg, nm, commit_params, fused)
         if b_ is not None:
             v["frac_of_peak"] = w_ / (v["us_per_step"] * 1e-6) / p_
             v["bound"] = b_
@@ -326,6 +337,8 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
+        "recurrence_launches": {"resident_weight_layers": fused[0], "with_input_projection": fused[1],
+                                "with_dW_hh_and_bias_gradients": fused[2]},
         "mfma_probe": probe, "async_driver": async_driver, "schedules_under_sync_latency": compare,
         "synchronisation_forms": forms,
     }

@@ -226,6 +226,15 @@ const char *hpsgd_role_name(int role); /* static string, NULL if out of range */
  * before the first step.  For the byte accounting of the HPSGD_ROLE_COMMIT timings. */
 size_t hpsgd_commit_kernel_params(const hpsgd_ctx *ctx);
 
+/* What the recurrence launches of the last local step included (benchmarks: which role the
+ * work of a fused part is accounted to).  Each count is a number of GRU layers:
+ *   resident_layers: layers whose recurrence ran as resident-weight launches,
+ *   xproj_layers:    of those, layers whose forward launch did the input projection itself,
+ *   dw_layers:       of those, layers whose backward launch accumulated dW_hh and the bias
+ *                    gradients itself.
+ * Any pointer may be NULL. */
+int hpsgd_recurrence_info(const hpsgd_ctx *ctx, int *resident_layers, int *xproj_layers, int *dw_layers);
+
 /* ---- synthetic synchronisation latency (measurement / test aid) ---------------------------
  * Occupies `hip_stream` for about `microseconds` (one wave that sleeps until the 100 MHz wall
  * clock has advanced that far; at most 1 000 000, else HPSGD_EINVAL).  Stands in for a slow

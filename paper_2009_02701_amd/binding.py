@@ -26,6 +26,7 @@ EXPORTS = [
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
+    "hpsgd_recurrence_info",
 ]
 ROLE_COUNT = 14
 
@@ -75,6 +76,7 @@ def load_library():
     lib.hpsgd_set_aux_stream.argtypes = [vp, vp]
     lib.hpsgd_set_recurrence.argtypes = [vp, C.c_int, C.c_uint]
     lib.hpsgd_recurrence_gave_up.argtypes = [vp, vp, vp, C.POINTER(C.c_int)]
+    lib.hpsgd_recurrence_info.argtypes = [vp, C.POINTER(C.c_int), C.POINTER(C.c_int), C.POINTER(C.c_int)]
     lib.hpsgd_timer_enable.argtypes = [vp, C.c_uint]
     lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.hpsgd_role_name.argtypes = [C.c_int]
@@ -177,6 +179,13 @@ class Context:
     def set_recurrence(self, resident=True, spin_limit=1 << 20):
         """fp32 GRU recurrence as one launch per run of time steps (weights resident on the chip) or one per step."""
         _check(self.lib.hpsgd_set_recurrence(self._h, int(bool(resident)), int(spin_limit)), "hpsgd_set_recurrence")
+
+    def recurrence_info(self):
+        """(resident, xproj, dw): GRU layers of the last local step whose recurrence ran as resident-weight
+        launches, whose forward launch did the input projection, whose backward launch accumulated dW_hh."""
+        a, b, c = C.c_int(0), C.c_int(0), C.c_int(0)
+        _check(self.lib.hpsgd_recurrence_info(self._h, C.byref(a), C.byref(b), C.byref(c)), "hpsgd_recurrence_info")
+        return a.value, b.value, c.value
 
     def recurrence_gave_up(self, workspace, stream=None):
         """True if a wait inside a resident-weight recurrence launch was given up (synchronises the stream)."""

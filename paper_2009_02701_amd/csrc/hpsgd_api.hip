@@ -56,6 +56,7 @@ struct hpsgd_ctx {
   bool resident = true;         // fp32 recurrence: one launch per run of time steps when supported
   unsigned spin_limit = 1u << 20;  // bound of every wait inside those launches
   size_t last_commit_params = 0;  // parameters per worker that the commit kernel handled last step
+  int last_resident = 0, last_xproj = 0, last_dw = 0;  // GRU layers of the last step, see hpsgd_recurrence_info
   unsigned timer_mask = 0;
   bool timer_nested = false;    // an enclosing scope already brackets the current launches
   struct Stamp { int role; int launches; hipEvent_t a, b; };
@@ -309,6 +310,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
   const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
+  c->last_resident = c->last_xproj = c->last_dw = 0;
   // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
   // (replica_out = replica_in - lr * dW, no gradient buffer round trip); every other
   // parameter goes through the gradient buffer and the commit kernel at the end.  A matrix
@@ -498,6 +500,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                        groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
                                        Wih0, rin + c->off(p + ".b_ih"), s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
+        ++c->last_resident;
+        c->last_xproj += xproj ? 1 : 0;
       }
       for (int t = 0; t < T && !persist; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
@@ -706,6 +710,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_GEMM_REC_BWD;
         HIP_TRY(launch_gru_bwd_persist(Whh, sR, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
                                        T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, s));
+        c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);
       }
       for (int t = T - 1; t >= 0 && !persist; --t) {
@@ -1108,6 +1113,14 @@ int hpsgd_delay_us(unsigned microseconds, void* hip_stream) {
 }
 
 size_t hpsgd_commit_kernel_params(const hpsgd_ctx* ctx) { return ctx ? ctx->last_commit_params : 0; }
+
+int hpsgd_recurrence_info(const hpsgd_ctx* ctx, int* resident_layers, int* xproj_layers, int* dw_layers) {
+  if (!ctx) return HPSGD_EINVAL;
+  if (resident_layers) *resident_layers = ctx->last_resident;
+  if (xproj_layers) *xproj_layers = ctx->last_xproj;
+  if (dw_layers) *dw_layers = ctx->last_dw;
+  return HPSGD_OK;
+}
 
 int hpsgd_probe_mfma_rate(int precision, const void* operands, int iterations, double* result, float* sink,
                           void* hip_stream) {
