@@ -493,6 +493,345 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
   }
 }
 
+// ---------------------------------------------------------------------------- bf16 operands
+// The same scheme with v_mfma_f32_16x16x32_bf16 on the bf16 copies of W_hh and of the exchanged
+// activations (every operand is the nearest-even bf16 rounding of the fp32 value; accumulation,
+// cell math and everything stored for later use stay fp32).  A workgroup owns 32 batch rows x
+// 32 hidden units.  Its slice of the weights (forward: 96 gate rows x H; backward: 32 rows of
+// W_hh^T x 3H; 192 KB at H = 1024) stays in REGISTERS for the whole launch: the contraction is
+// cut into 32-wide chunks, wave w owns the chunks w, w + 8, .. with all the column blocks, i.e.
+// up to 24 B-operand fragments of 16 bytes per lane.  Per step a wave fetches only its own A
+// fragments (16 bytes per lane per chunk and row block); the 8 partial sums of every output
+// meet in LDS.  MFMA 16x16x32 lane layout: A lane l holds A[m = l%16][k = 8*(l/16) .. +7],
+// B lane l holds B[k = 8*(l/16) .. +7][n = l%16], accumulator as for 16x16x4.
+// Epilogue: thread t owns batch row t/16 and the two units 2*(t%16), +1 of the tile, so that
+// bf16 values are stored in pairs.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int QJ = 32;       // hidden units per workgroup
+constexpr int TP = 40;       // pitch (bf16) of a staged transposed row of 32 batch rows
+
+__device__ __forceinline__ bf16x8 ld_frag(const __bf16* p) {
+  return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4_t*>(p));
+}
+__device__ __forceinline__ bf16x8 ld_frag_dev(__amdgpu_buffer_rsrc_t rs, int byte_off) {
+  return __builtin_bit_cast(bf16x8, __builtin_amdgcn_raw_buffer_load_b128(rs, byte_off, 0, 16 /* sc1 */));
+}
+__device__ __forceinline__ unsigned pack_bf16(float a, float b) {
+  const __bf16 x = (__bf16)a, y = (__bf16)b;
+  return (unsigned)__builtin_bit_cast(unsigned short, x) | ((unsigned)__builtin_bit_cast(unsigned short, y) << 16);
+}
+__device__ __forceinline__ void st_dev_u32(void* p, unsigned v) {
+  __hip_atomic_store(reinterpret_cast<unsigned*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Forward.  Wb: bf16 W_hh [3H][H]; hb: bf16 h_0 .. h_T (blocks of B x H, h_0 given), the
+// exchanged operand; hs: the same in fp32; hT (nullable): bf16 transposed copy [H][ld_hT],
+// column (t+1)*B + row.  NCF: chunks per wave (H <= 256 * NCF).
+template <int NCF>
+__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
+gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh, long s_rep,
+                            const float* __restrict__ gx, long s_gx, float* __restrict__ hs, long s_hs, __bf16* hb,
+                            long s_hb, float* __restrict__ sv, long s_sv, __bf16* __restrict__ hT, long ld_hT,
+                            long s_hT, int B, int H, int T, int groups, unsigned* sync, unsigned base,
+                            unsigned spin_limit) {
+  extern __shared__ __attribute__((aligned(16))) float persist_lds[];
+  float* red = persist_lds;                                     // [8][2][6][4][64]
+  __bf16* tt = reinterpret_cast<__bf16*>(red + 8 * 12 * 256);   // [32 units][TP]
+  int* lds_flag = reinterpret_cast<int*>(tt + QJ * TP);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int NJ = H / QJ, RT = (B + PR - 1) / PR;
+  int g, tx, ty, sg;
+  persist_tile(NJ, RT, groups, g, tx, ty, sg);
+  const int j0 = tx * QJ, r0 = ty * PR;
+  unsigned* abort_w = sync;
+  unsigned* ctr = sync + 1 + sg;
+  __builtin_amdgcn_s_setprio(3);
+  const int nch = H / PC;
+  // resident fragments: chunk wave + 8i, column block cb = 2q + half: rows q*H + j0 + 16*half + lr
+  bf16x8 wf[NCF][6];
+#pragma unroll
+  for (int i = 0; i < NCF; ++i) {
+    const int c = wave + 8 * i;
+#pragma unroll
+    for (int cb = 0; cb < 6; ++cb) {
+      const long wrow = (long)(cb >> 1) * H + j0 + 16 * (cb & 1) + lr;
+      const bf16x8 v = ld_frag(Wb + g * s_wb + wrow * H + PC * (c < nch ? c : 0) + 8 * lg);
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      wf[i][cb] = c < nch ? v : zero;  // a chunk slot beyond the contraction multiplies by zero
+    }
+  }
+  // epilogue element: row rl of the tile, units u0, u0 + 1
+  const int rl = tid >> 4, u0 = 2 * (tid & 15);
+  const int row = r0 + rl, rowc = min(row, B - 1);
+  const int j = j0 + u0;
+  const int ro = ((rl >> 4) * 6) * 256 + (rl & 3) * 64 + ((rl >> 2) & 3) * 16 + (u0 & 15);  // + cb * 256 + w * 3072
+  const int half = u0 >> 4;
+  float2 bias[3];
+#pragma unroll
+  for (int q = 0; q < 3; ++q) bias[q] = *reinterpret_cast<const float2*>(b_hh + g * s_rep + q * H + j);
+  float* hsg = hs + g * s_hs;
+  __bf16* hbg = hb + g * s_hb;
+  float2 hpv = *reinterpret_cast<const float2*>(hsg + (long)rowc * H + j);
+  // A fragments: rows rb*16 + lr of the tile (clamped into the batch), k = 32c + 8*lg
+  int aoff[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) aoff[rb] = ((rb * 16 + lr < B - r0 ? rb * 16 + lr : 0) * H + 8 * lg) * 2;
+  for (int t = 0; t < T; ++t) {
+    const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H + j;
+    float2 gxv[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxv[q] = *reinterpret_cast<const float2*>(gxr + q * H);
+    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hbg + ((long)t * B + r0) * H, 0, 0x7fffffff,
+                                                                        0x00020000);
+    bf16x8 a[NCF][2];
+#pragma unroll
+    for (int i = 0; i < NCF; ++i) {
+      const int c = wave + 8 * i;
+      const int co = (c < nch ? c : 0) * PC * 2;
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
+    }
+    floatx4 acc[2][6];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < 6; ++cb) acc[rb][cb] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
+#pragma unroll
+    for (int i = 0; i < NCF; ++i)
+#pragma unroll
+      for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int cb = 0; cb < 6; ++cb)
+          acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][rb], wf[i][cb], acc[rb][cb], 0, 0, 0);
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < 6; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[(((wave * 2 + rb) * 6 + cb) * 4 + v) * 64 + lane] = acc[rb][cb][v];
+    __syncthreads();
+    float2 gh[3];
+#pragma unroll
+    for (int q = 0; q < 3; ++q) {
+      const float* rp = red + ro + (2 * q + half) * 256;
+      float2 p[8];
+#pragma unroll
+      for (int w = 0; w < 8; ++w) p[w] = *reinterpret_cast<const float2*>(rp + w * 3072);
+      gh[q].x = (((p[0].x + p[1].x) + (p[2].x + p[3].x)) + ((p[4].x + p[5].x) + (p[6].x + p[7].x))) + bias[q].x;
+      gh[q].y = (((p[0].y + p[1].y) + (p[2].y + p[3].y)) + ((p[4].y + p[5].y) + (p[6].y + p[7].y))) + bias[q].y;
+    }
+    const float r0v = sigm_p(gxv[0].x + gh[0].x), r1v = sigm_p(gxv[0].y + gh[0].y);
+    const float z0v = sigm_p(gxv[1].x + gh[1].x), z1v = sigm_p(gxv[1].y + gh[1].y);
+    const float n0v = tanhf(gxv[2].x + r0v * gh[2].x), n1v = tanhf(gxv[2].y + r1v * gh[2].y);
+    const float2 hn = make_float2((1.0f - z0v) * n0v + z0v * hpv.x, (1.0f - z1v) * n1v + z1v * hpv.y);
+    if (row < B) {
+      const long e = ((long)(t + 1) * B + row) * H + j;
+      *reinterpret_cast<float2*>(hsg + e) = hn;
+      st_dev_u32(hbg + e, pack_bf16(hn.x, hn.y));
+      float* svr = sv + g * s_sv + ((long)t * B + row) * 4 * H + j;
+      *reinterpret_cast<float2*>(svr) = make_float2(r0v, r1v);
+      *reinterpret_cast<float2*>(svr + H) = make_float2(z0v, z1v);
+      *reinterpret_cast<float2*>(svr + 2 * H) = make_float2(n0v, n1v);
+      *reinterpret_cast<float2*>(svr + 3 * H) = gh[2];
+    }
+    if (hT) {
+      tt[u0 * TP + rl] = (__bf16)hn.x;
+      tt[(u0 + 1) * TP + rl] = (__bf16)hn.y;
+    }
+    hpv = hn;
+    group_signal(ctr);  // (its barrier also separates the reads of red from the next step's writes)
+    if (hT && tid < 128) {
+      // 64-byte row segments of the transposed copy, 16 bytes per thread
+      const int u = tid >> 2, part = tid & 3;
+      if (r0 + 8 * part < B)  // B is a multiple of 8: a piece of 8 rows is all in or all out
+        *reinterpret_cast<uint4*>(hT + g * s_hT + (long)(j0 + u) * ld_hT + (long)(t + 1) * B + r0 + 8 * part) =
+            *reinterpret_cast<const uint4*>(tt + u * TP + 8 * part);
+    }
+  }
+}
+
+// Backward.  WT: bf16 W_hh^T [H][3H]; dghb: bf16 gate gradients of all steps (blocks of B x 3H),
+// the exchanged operand; dgxb: bf16 dgx row-major; dgxT / dghT: bf16 transposed copies
+// [3H][ld_T], column t*B + row; dbp: partial bias-gradient sums [(g*RT + ty)][6H] (b_ih | b_hh).
+// D: dh_T * z_T on entry (the head's gradient), dh_0 * z_0 on exit.  NCB: chunks per wave
+// (3H <= 256 * NCB).  The fragments of the first half of a wave's chunks stay in registers,
+// those of the second half in LDS (each wave reads back only its own): with all of them in
+// registers the two waves of a SIMD would fill its register file, and no wave of any other
+// kernel (a merge on the second stream) could ever share the CU.
+template <int NCB>
+__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
+gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dghb, long s_dgb, float* __restrict__ D,
+                            long s_D, const float* __restrict__ above, long s_above, const float* __restrict__ sv,
+                            long s_sv, const float* __restrict__ hs, long s_hs, __bf16* __restrict__ dgxb,
+                            __bf16* __restrict__ dgxT, __bf16* __restrict__ dghT, long ld_T, long s_T,
+                            float* __restrict__ dbp, int B, int H, int T, int groups, unsigned* sync, unsigned base,
+                            unsigned spin_limit) {
+  extern __shared__ __attribute__((aligned(16))) float persist_lds[];
+  constexpr int NCR = NCB / 2, NCL = NCB - NCR;                 // chunks in registers / in LDS
+  float* red = persist_lds;                                     // [8][2][2][4][64]
+  __bf16* tt = reinterpret_cast<__bf16*>(red + 8 * 4 * 256);    // [da_r | da_z | da_n | dq][32 units][TP]
+  u32x4_t* wl = reinterpret_cast<u32x4_t*>(tt + 4 * QJ * TP);   // [8 waves][NCL][2][64 lanes] fragments
+  int* lds_flag = reinterpret_cast<int*>(wl + 8 * NCL * 2 * 64);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int lr = lane & 15, lg = lane >> 4;
+  const int NJ = H / QJ, RT = (B + PR - 1) / PR;
+  int g, tx, ty, sg;
+  persist_tile(NJ, RT, groups, g, tx, ty, sg);
+  const int j0 = tx * QJ, r0 = ty * PR;
+  unsigned* abort_w = sync;
+  unsigned* ctr = sync + 1 + sg;
+  __builtin_amdgcn_s_setprio(3);
+  const int H3 = 3 * H;
+  const int nch = H3 / PC;
+  // resident fragments: chunk wave + 8i, column block = half: rows j0 + 16*half + lr of W_hh^T
+  bf16x8 wf[NCR][2];
+#pragma unroll
+  for (int i = 0; i < NCB; ++i) {
+    const int c = wave + 8 * i;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb) {
+      const bf16x8 v = ld_frag(WT + g * s_wt + (long)(j0 + 16 * cb + lr) * H3 + PC * (c < nch ? c : 0) + 8 * lg);
+      const bf16x8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+      const bf16x8 f = c < nch ? v : zero;
+      if (i < NCR)
+        wf[i][cb] = f;
+      else
+        wl[((wave * NCL + (i - NCR)) * 2 + cb) * 64 + lane] = __builtin_bit_cast(u32x4_t, f);
+    }
+  }
+  const int rl = tid >> 4, u0 = 2 * (tid & 15);
+  const int row = r0 + rl, rowc = min(row, B - 1);
+  const int j = j0 + u0;
+  const int ro = ((rl >> 4) * 2 + (u0 >> 4)) * 256 + (rl & 3) * 64 + ((rl >> 2) & 3) * 16 + (u0 & 15);  // + w * 1024
+  float* Dg = D + g * s_D;
+  float2 dcar = *reinterpret_cast<const float2*>(Dg + (long)rowc * H + j);
+  __bf16* dghg = dghb + g * s_dgb;
+  float2 bsum[4] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // da_r, da_z, da_n, dq over the steps
+  int aoff[2];
+#pragma unroll
+  for (int rb = 0; rb < 2; ++rb) aoff[rb] = ((rb * 16 + lr < B - r0 ? rb * 16 + lr : 0) * H3 + 8 * lg) * 2;
+  int it = 0;
+  for (int t = T - 1; t >= 0; --t, ++it) {
+    const long e = ((long)t * B + rowc) * H + j;
+    const float* svr = sv + g * s_sv + ((long)t * B + rowc) * 4 * H + j;
+    const float2 r = *reinterpret_cast<const float2*>(svr), z = *reinterpret_cast<const float2*>(svr + H);
+    const float2 n = *reinterpret_cast<const float2*>(svr + 2 * H), q = *reinterpret_cast<const float2*>(svr + 3 * H);
+    const float2 hp = *reinterpret_cast<const float2*>(hs + g * s_hs + e);
+    const float2 ab = above ? *reinterpret_cast<const float2*>(above + g * s_above + e) : make_float2(0.f, 0.f);
+    if (it > 0 && !group_wait(ctr, base + (unsigned)it * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    floatx4 acc[2][2];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) acc[rb][cb] = (floatx4){0.f, 0.f, 0.f, 0.f};
+    if (t + 1 < T) {  // uniform over the grid
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dghg + ((long)(t + 1) * B + r0) * H3, 0,
+                                                                          0x7fffffff, 0x00020000);
+      bf16x8 a[NCB][2];
+#pragma unroll
+      for (int i = 0; i < NCB; ++i) {
+        const int c = wave + 8 * i;
+        const int co = (c < nch ? c : 0) * PC * 2;
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
+#pragma unroll
+      for (int i = 0; i < NCB; ++i) {
+        bf16x8 w2[2];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb)
+          w2[cb] = i < NCR ? wf[i < NCR ? i : 0][cb]
+                           : __builtin_bit_cast(bf16x8, wl[((wave * NCL + (i - NCR)) * 2 + cb) * 64 + lane]);
+#pragma unroll
+        for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb)
+            acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][rb], w2[cb], acc[rb][cb], 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) red[(((wave * 2 + rb) * 2 + cb) * 4 + v) * 64 + lane] = acc[rb][cb][v];
+    __syncthreads();
+    float2 p[8];
+#pragma unroll
+    for (int w = 0; w < 8; ++w) p[w] = *reinterpret_cast<const float2*>(red + ro + w * 1024);
+    const float recx = ((p[0].x + p[1].x) + (p[2].x + p[3].x)) + ((p[4].x + p[5].x) + (p[6].x + p[7].x));
+    const float recy = ((p[0].y + p[1].y) + (p[2].y + p[3].y)) + ((p[4].y + p[5].y) + (p[6].y + p[7].y));
+    const float2 dh = make_float2((dcar.x + ab.x) + recx, (dcar.y + ab.y) + recy);
+    const float2 dn = make_float2(dh.x * (1.0f - z.x), dh.y * (1.0f - z.y));
+    const float2 dz = make_float2(dh.x * (hp.x - n.x), dh.y * (hp.y - n.y));
+    const float2 da_n = make_float2(dn.x * (1.0f - n.x * n.x), dn.y * (1.0f - n.y * n.y));
+    const float2 dq = make_float2(da_n.x * r.x, da_n.y * r.y);
+    const float2 da_r = make_float2(da_n.x * q.x * r.x * (1.0f - r.x), da_n.y * q.y * r.y * (1.0f - r.y));
+    const float2 da_z = make_float2(dz.x * z.x * (1.0f - z.x), dz.y * z.y * (1.0f - z.y));
+    if (row < B) {
+      const long o = ((long)t * B + row) * H3 + j;
+      const unsigned pr = pack_bf16(da_r.x, da_r.y), pz = pack_bf16(da_z.x, da_z.y);
+      st_dev_u32(dghg + o, pr);
+      st_dev_u32(dghg + o + H, pz);
+      st_dev_u32(dghg + o + 2 * H, pack_bf16(dq.x, dq.y));
+      __bf16* ox = dgxb + g * s_dgb + o;
+      *reinterpret_cast<unsigned*>(ox) = pr;
+      *reinterpret_cast<unsigned*>(ox + H) = pz;
+      *reinterpret_cast<unsigned*>(ox + 2 * H) = pack_bf16(da_n.x, da_n.y);
+      bsum[0].x += da_r.x; bsum[0].y += da_r.y;
+      bsum[1].x += da_z.x; bsum[1].y += da_z.y;
+      bsum[2].x += da_n.x; bsum[2].y += da_n.y;
+      bsum[3].x += dq.x;   bsum[3].y += dq.y;
+    }
+    // the four distinct gate-gradient blocks, staged for the transposed copies
+    tt[(0 * QJ + u0) * TP + rl] = (__bf16)da_r.x;
+    tt[(0 * QJ + u0 + 1) * TP + rl] = (__bf16)da_r.y;
+    tt[(1 * QJ + u0) * TP + rl] = (__bf16)da_z.x;
+    tt[(1 * QJ + u0 + 1) * TP + rl] = (__bf16)da_z.y;
+    tt[(2 * QJ + u0) * TP + rl] = (__bf16)da_n.x;
+    tt[(2 * QJ + u0 + 1) * TP + rl] = (__bf16)da_n.y;
+    tt[(3 * QJ + u0) * TP + rl] = (__bf16)dq.x;
+    tt[(3 * QJ + u0 + 1) * TP + rl] = (__bf16)dq.y;
+    dcar = make_float2(dh.x * z.x, dh.y * z.y);
+    group_signal(ctr);
+    {
+      // transposed copies [gate unit][t*B + row] as 64-byte row segments, 16 bytes per thread:
+      // dgx^T = (da_r, da_z, da_n), dgh^T = (da_r, da_z, dq)
+      const int blk = tid >> 7, u = (tid >> 2) & 31, part = tid & 3;
+      if (r0 + 8 * part < B) {  // B is a multiple of 8
+        const uint4 v = *reinterpret_cast<const uint4*>(tt + (blk * QJ + u) * TP + 8 * part);
+        const int gate = blk == 3 ? 2 : blk;
+        const long o = g * s_T + (long)(gate * H + j0 + u) * ld_T + (long)t * B + r0 + 8 * part;
+        if (blk != 3) *reinterpret_cast<uint4*>(dgxT + o) = v;
+        if (blk != 2) *reinterpret_cast<uint4*>(dghT + o) = v;
+      }
+    }
+  }
+  if (row < B) *reinterpret_cast<float2*>(Dg + (long)row * H + j) = dcar;
+  // bias gradients: sums over the tile's 32 batch rows, in row order
+  __syncthreads();
+  float* bs = red;  // [32 rows][4 sums][32 units]
+#pragma unroll
+  for (int i = 0; i < 4; ++i) *reinterpret_cast<float2*>(bs + (rl * 4 + i) * QJ + u0) = bsum[i];
+  __syncthreads();
+  if (tid < 128) {
+    float tot = 0.f;
+    for (int r32 = 0; r32 < PR; ++r32) tot += bs[r32 * 128 + tid];
+    const int i = tid >> 5, jj = j0 + (tid & 31);
+    float* out = dbp + (long)(g * RT + ty) * 6 * H;
+    if (i == 0) out[jj] = out[H3 + jj] = tot;
+    if (i == 1) out[H + jj] = out[H3 + H + jj] = tot;
+    if (i == 2) out[2 * H + jj] = tot;
+    if (i == 3) out[H3 + 2 * H + jj] = tot;
+  }
+}
+
 int device_cus() {
   static int cus = -1;
   if (cus < 0) {
@@ -616,6 +955,86 @@ __global__ void poison_on_abort_kernel(const unsigned* abort_w, float* loss, int
 hipError_t launch_poison_on_abort(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
                                   int groups, hipStream_t s) {
   hipLaunchKernelGGL(poison_on_abort_kernel, dim3(1), dim3(64), 0, s, abort_w, loss, n_loss, rout, s_rout, groups);
+  return hipGetLastError();
+}
+
+// bf16 operands: 32 units per workgroup, the weight slice in registers (24 fragments per wave at most)
+bool gru_persist_bf16_supported(int B, int H, int groups) {
+  if (H % 32 != 0 || H < 32 || H > 1024 || B < 8 || B % 8 != 0 || groups < 1) return false;
+  const long grid = (long)(H / QJ) * ((B + PR - 1) / PR) * groups;
+  return grid <= device_cus();
+}
+
+unsigned gru_persist_bf16_count_per_step(int H) { return (unsigned)(H / QJ); }
+
+hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep, const float* gx,
+                                       long s_gx, float* hs, long s_hs, void* hb, long s_hb, float* sv, long s_sv,
+                                       void* hT, long ld_hT, long s_hT, int B, int H, int T, int groups,
+                                       unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s) {
+  if (!gru_persist_bf16_supported(B, H, groups) || T < 1) return hipErrorInvalidValue;
+  auto a16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  if (!a16(Wb) || !a16(hb) || !a16(hs) || !a16(gx) || !a16(sv) || !a16(b_hh) || (hT && !a16(hT)) || (s_wb & 7) != 0 ||
+      (s_hb & 7) != 0 || (s_hs & 3) != 0 || (s_gx & 3) != 0 || (s_sv & 3) != 0 || (s_rep & 3) != 0 ||
+      (hT && ((ld_hT & 7) != 0 || (s_hT & 7) != 0)))
+    return hipErrorInvalidValue;
+  const size_t lds = (size_t)8 * 12 * 256 * sizeof(float) + (size_t)QJ * TP * 2 + 16;
+  const int ncf = H <= 256 ? 1 : H <= 512 ? 2 : 4;
+  static bool ready[3] = {false, false, false};
+  const int slot = ncf == 1 ? 0 : ncf == 2 ? 1 : 2;
+  const void* fn = ncf == 1   ? (const void*)gru_fwd_persist_bf16_kernel<1>
+                   : ncf == 2 ? (const void*)gru_fwd_persist_bf16_kernel<2>
+                              : (const void*)gru_fwd_persist_bf16_kernel<4>;
+  if (!ready[slot]) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ready[slot] = true;
+  }
+  dim3 grid((H / QJ) * ((B + PR - 1) / PR) * groups);
+#define HPSGD_FWD_PB(N)                                                                                            \
+  hipLaunchKernelGGL(gru_fwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)Wb, s_wb, b_hh, s_rep, \
+                     gx, s_gx, hs, s_hs, (__bf16*)hb, s_hb, sv, s_sv, (__bf16*)hT, ld_hT, s_hT, B, H, T, groups,    \
+                     sync, base, spin_limit)
+  if (ncf == 1) HPSGD_FWD_PB(1);
+  else if (ncf == 2) HPSGD_FWD_PB(2);
+  else HPSGD_FWD_PB(4);
+#undef HPSGD_FWD_PB
+  return hipGetLastError();
+}
+
+hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghb, long s_dgb, float* D, long s_D,
+                                       const float* above, long s_above, const float* sv, long s_sv, const float* hs,
+                                       long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
+                                       int B, int H, int T, int groups, unsigned* sync, unsigned base,
+                                       unsigned spin_limit, hipStream_t s) {
+  if (!gru_persist_bf16_supported(B, H, groups) || T < 1 || !dbp || !dgxb || !dgxT || !dghT)
+    return hipErrorInvalidValue;
+  auto a16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  if (!a16(WT) || !a16(dghb) || !a16(dgxb) || !a16(dgxT) || !a16(dghT) || !a16(D) || !a16(sv) || !a16(hs) ||
+      (above && !a16(above)) || (s_wt & 7) != 0 || (s_dgb & 7) != 0 || (ld_T & 7) != 0 || (s_T & 7) != 0 ||
+      (s_D & 3) != 0 || (s_above & 3) != 0 || (s_sv & 3) != 0 || (s_hs & 3) != 0)
+    return hipErrorInvalidValue;
+  const int ncf = H <= 256 ? 1 : H <= 512 ? 2 : 4;
+  const int ncl = 3 * ncf - 3 * ncf / 2;
+  const size_t lds = (size_t)8 * 4 * 256 * sizeof(float) + (size_t)4 * QJ * TP * 2 + (size_t)8 * ncl * 2 * 64 * 16 + 16;
+  static bool ready[3] = {false, false, false};
+  const int slot = ncf == 1 ? 0 : ncf == 2 ? 1 : 2;
+  const void* fn = ncf == 1   ? (const void*)gru_bwd_persist_bf16_kernel<3>
+                   : ncf == 2 ? (const void*)gru_bwd_persist_bf16_kernel<6>
+                              : (const void*)gru_bwd_persist_bf16_kernel<12>;
+  if (!ready[slot]) {
+    hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    ready[slot] = true;
+  }
+  dim3 grid((H / QJ) * ((B + PR - 1) / PR) * groups);
+#define HPSGD_BWD_PB(N)                                                                                            \
+  hipLaunchKernelGGL(gru_bwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)WT, s_wt,              \
+                     (__bf16*)dghb, s_dgb, D, s_D, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \
+                     (__bf16*)dghT, ld_T, s_T, dbp, B, H, T, groups, sync, base, spin_limit)
+  if (ncf == 1) HPSGD_BWD_PB(3);
+  else if (ncf == 2) HPSGD_BWD_PB(6);
+  else HPSGD_BWD_PB(12);
+#undef HPSGD_BWD_PB
   return hipGetLastError();
 }
 

@@ -124,12 +124,10 @@ int build_layout(hpsgd_ctx* c) {
     c->gh = c->alloc((size_t)d.batch * 3 * H);
     c->D = c->alloc((size_t)d.batch * H);
     c->wt = c->alloc(3 * H * H);
-    if (d.prec != HPSGD_BF16_MFMA) {
-      c->psync = c->alloc(gru_persist_sync_words(d.batch, 1));
-      if (gru_fused_supported(d.hidden) && gru_persist_dw_supported(d.hidden))
-        c->dwp = c->alloc((size_t)((d.batch + 31) / 32) * 3 * H * H);
-      if (gru_fused_supported(d.hidden)) c->dbp = c->alloc((size_t)((d.batch + 31) / 32) * 6 * H);
-    }
+    c->psync = c->alloc(gru_persist_sync_words(d.batch, 1));
+    if (gru_fused_supported(d.hidden)) c->dbp = c->alloc((size_t)((d.batch + 31) / 32) * 6 * H);
+    if (d.prec != HPSGD_BF16_MFMA && gru_fused_supported(d.hidden) && gru_persist_dw_supported(d.hidden))
+      c->dwp = c->alloc((size_t)((d.batch + 31) / 32) * 3 * H * H);
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
@@ -253,7 +251,8 @@ struct NtView {
 // view (C = a b^T), otherwise the generic kernel on the original fp32 operands.
 int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda, long sA,
           int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC, int epi,
-          const float* aux, long sAux, const NtView& a, const NtView& b, float alpha = 0.f) {
+          const float* aux, long sAux, const NtView& a, const NtView& b, float alpha = 0.f,
+          bool require_nt = false) {
   if (bf16 && a.p && b.p && (epi == EPI_STORE || epi == EPI_BIAS || epi == EPI_COMMIT) &&
       gemm_bf16_nt_supported(a.p, a.bf16, a.ld, a.stride, Kd) &&
       gemm_bf16_nt_supported(b.p, b.bf16, b.ld, b.stride, Kd) && ((uintptr_t)C & 3) == 0) {
@@ -263,6 +262,7 @@ int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float
                ? HPSGD_OK
                : HPSGD_EHIP;
   }
+  if (require_nt) return HPSGD_EINVAL;  // the fp32 operands of the fallback were not produced
   return gemm(s, groups, bf16, M, N, Kd, A, lda, sA, tA, B, ldb, sB, tB, C, ldc, sC, epi, aux, sAux, 0, alpha);
 }
 
@@ -402,9 +402,20 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // Its workgroups wait for each other through counters in the workspace, zeroed here; pbase
     // follows what the counters read.  A given-up wait shows as NaN in the results (below).
     const bool use_persist = !bf && c->resident && gru_fused_supported(H) && gru_persist_supported(B, H, groups);
-    unsigned* psync = use_persist ? (unsigned*)reg(c->psync) : nullptr;
+    // bf16: the same with the weight slices in registers; its backward launch writes only the bf16
+    // copies of the gate gradients, so every GEMM that consumes them must be able to take those
+    // (contraction-contiguous bf16 views: batch, hidden size and every layer width multiples of 8)
+    bool use_persist_b = bf && c->resident && gru_fused_bf16_supported(H) && gru_persist_bf16_supported(B, H, groups) &&
+                         ntc && (lm ? d.embed : d.input) % 8 == 0 && (sG & 3) == 0 &&
+                         c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H;
+    for (int l = 0; l < L && use_persist_b; ++l) {
+      const std::string p = "l" + std::to_string(l);
+      use_persist_b = ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
+                      c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H;
+    }
+    unsigned* psync = (use_persist || use_persist_b) ? (unsigned*)reg(c->psync) : nullptr;
     unsigned pbase = 0;
-    if (use_persist) {
+    if (use_persist || use_persist_b) {
       TRY(order_resident_launches(s));
       const size_t nw = gru_persist_sync_words(B, groups);
       HIP_TRY(launch_fill_zero((float*)psync, nw, nw, 1, s));
@@ -492,7 +503,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
       }
       // one event pair around the whole time loop when its launches are all of one role
-      TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, persist ? 1 : (fused || fused_b) ? T : 0);
+      const bool persist_b = fused_b && use_persist_b && hT != nullptr;
+      TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (persist || persist_b) ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
@@ -503,7 +515,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         ++c->last_resident;
         c->last_xproj += xproj ? 1 : 0;
       }
-      for (int t = 0; t < T && !persist; ++t) {
+      if (persist_b) {
+        role = HPSGD_ROLE_GEMM_REC_FWD;
+        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx, s_gx, hs, s_hs, hb, s_hb, sv,
+                                            s_sv, hT, TB1p, s_hT, B, H, T, groups, psync, pbase, c->spin_limit, s));
+        pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
+        ++c->last_resident;
+      }
+      for (int t = 0; t < T && !persist && !persist_b; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         if (fused_b) {
           HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H,
@@ -680,12 +699,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // cut into chunks; chunk c's GEMMs are issued when BPTT has walked past it, the last
       // one follows on the main stream after the join.  Fixed chunking: deterministic.
       const bool persist = fused && use_persist;
+      const bool persist_b = fused_b && use_persist_b && stepT;
       // the resident-weight kernel accumulates dW_hh itself (one partial sum per batch-row tile)
       float* dwp = (persist && c->dwp.stride == (size_t)((B + 31) / 32) * 3 * H * H) ? reg(c->dwp) : nullptr;
       // ... and the bias gradients, when their partial sums can be added with 16-byte accesses
-      float* dbp = (persist && c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H && (sG & 3) == 0 &&
-                    ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
-                    c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H)
+      float* dbp = persist_b ? reg(c->dbp)  // (its conditions were checked with use_persist_b)
+                   : (persist && c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H && (sG & 3) == 0 &&
+                      ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
+                      c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H)
                        ? reg(c->dbp)
                        : nullptr;
       const int NC = (c->aux && fused && !persist && T >= 8) ? 4 : 1;
@@ -701,7 +722,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                     grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0, bg);
       };
       {
-      TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, persist ? 1 : (fused || fused_b) ? T : 0);
+      TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (persist || persist_b) ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_bwd.active() && (fused || fused_b);
       int next_chunk = NC - 1;  // the chunk BPTT is walking through
       // resident weights: all of BPTT is one launch; its weight-gradient GEMMs follow it (work
@@ -713,7 +734,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);
       }
-      for (int t = T - 1; t >= 0 && !persist; --t) {
+      if (persist_b) {
+        role = HPSGD_ROLE_GEMM_REC_BWD;
+        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, dghb, s_dgb, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, dgxb,
+                                            bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B, H, T, groups, psync,
+                                            pbase, c->spin_limit, s));
+        pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
+      }
+      for (int t = T - 1; t >= 0 && !persist && !persist_b; --t) {
         if (NC > 1 && next_chunk >= 1 && t < chunk_lo(next_chunk)) {
           // steps [chunk_lo, chunk_hi) are done: hand their weight gradients to the aux stream
           if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
@@ -789,7 +817,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (need_dx) {  // reads W_ih: before its update
         const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
         TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
-                  nullptr, 0, v_dgx, v_wihT));
+                  nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
         above = dx;
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
@@ -801,7 +829,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       } else {
         const WgradTarget wi = wgrad_target(p + ".W_ih");
         TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
-                  wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr));
+                  wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
         const WgradTarget wh = wgrad_target(p + ".W_hh");
         if (dwp) {
           TimerScope ts_(c, role, s);
@@ -809,7 +837,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                       lr, wh.epi == EPI_COMMIT, groups, s));
         } else {
           TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
-                    wh.aux, sR, v_dghT, v_hsT, lr));
+                    wh.aux, sR, v_dghT, v_hsT, lr, persist_b));
         }
       }
       role = HPSGD_ROLE_GEMM_WGRAD;

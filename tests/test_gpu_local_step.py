@@ -348,3 +348,33 @@ def test_resident_weight_recurrence_reports_a_wait_that_was_given_up():
     assert not tr.ctx.recurrence_gave_up(tr.ws[0])
     assert np.isfinite(tr.loss.cpu().numpy()).all()
     assert np.isfinite(tr.R[0].cpu().numpy()).all()
+
+
+@pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "cls_nt_bf16_c16", "cls_nt_bf16"])
+def test_resident_weight_recurrence_bf16_equals_one_launch_per_step(name):
+    """bf16 operands: the recurrence as one launch per layer and direction (weight slices in
+    registers) against one launch per time step.  Both round the same fp32 values to bf16; the
+    fp32 sums inside a dot product are taken in a different order, which now and then moves a
+    rounded h or gate gradient by one bf16 step, so the two agree to a fraction of the bf16 parity
+    tolerance rather than to fp32 rounding.  A second run gives the same bits."""
+    cfg = BF16[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for resident in (True, False, True):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+        tr.ctx.set_recurrence(resident)
+        tr.sync_all(0)
+        tr.gather(0)
+        tr.local_step(0, 8.0)
+        torch.cuda.synchronize()
+        assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+        assert tr.ctx.recurrence_info()[0] == (cfg["layers"] if resident else 0)
+        outs.append(([tr.replica_params(0, k) for k in range(cfg["K"])], tr.loss.cpu().numpy().copy()))
+    assert rel_err(outs[0][1], outs[1][1]) <= 1e-3
+    for k in range(cfg["K"]):
+        for n in init:
+            d0 = outs[0][0][k][n].astype(np.float64) - init[n]
+            d1 = outs[1][0][k][n].astype(np.float64) - init[n]
+            assert rel_err(d0, d1) <= TOL_BF16 / 4, (k, n, rel_err(d0, d1))
+            assert np.array_equal(outs[0][0][k][n].view(np.uint32), outs[2][0][k][n].view(np.uint32)), (k, n)
+    assert np.array_equal(outs[0][1].view(np.uint32), outs[2][1].view(np.uint32))
