@@ -216,6 +216,11 @@ hipError_t launch_gemm_f32_fast(const GemmDesc& d, hipStream_t s);  // gemm_f32_
 
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s) {
   if (d.M <= 0 || d.N <= 0 || d.groups <= 0) return hipSuccess;
+  if (d.splits > 1) {  // only the pipelined fp32 kernel cuts the contraction
+    if (d.bf16 || d.background) return hipErrorInvalidValue;
+    const hipError_t e = launch_gemm_f32_fast(d, s);
+    return e == hipErrorNotSupported ? hipErrorInvalidValue : e;
+  }
   if (d.bf16) return launch_gemm_bf16(d, s);
   if (!d.background) {
     // aligned operands: the pipelined kernel.  Not for background work: its LDS footprint (up to

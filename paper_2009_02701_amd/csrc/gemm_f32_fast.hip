@@ -96,16 +96,20 @@ gemm_f32_fast_kernel(GemmDesc d) {
   // (group, row tile, column tile) order, are cut into 8 contiguous runs, one per XCD, so that
   // an XCD fetches the A rows of its run once and only the B operands of the groups it touches.
   const int tn = (d.N + BN - 1) / BN, tm = (d.M + BM - 1) / BM;
-  const long ntiles = (long)tn * tm * d.groups, per = (ntiles + 7) / 8;
+  const int splits = d.splits > 1 ? d.splits : 1;
+  const long ntiles = (long)tn * tm * d.groups * splits, per = (ntiles + 7) / 8;
   const long tile = (long)(blockIdx.x & 7) * per + (blockIdx.x >> 3);
   if ((long)(blockIdx.x >> 3) >= per || tile >= ntiles) return;  // padding of the last run
-  const int g = (int)(tile / ((long)tn * tm));
+  const int gp = (int)(tile / ((long)tn * tm));   // group * splits + part of the contraction
+  const int g = gp / splits, part = gp - g * splits;
   const int m0 = (int)((tile / tn) % tm) * BM, n0 = (int)(tile % tn) * BN;
 
   OpA a;
   OpB b;
-  a.init(d.A + (long)g * d.strideA, d.lda, m0, d.M, tid);
-  b.init(d.B + (long)g * d.strideB, d.ldb, n0, d.N, tid);
+  // a part of a split contraction starts part * Kd further along k
+  const long ka = (long)part * d.Kd * (TA ? d.lda : 1), kb = (long)part * d.Kd * (TB ? 1 : d.ldb);
+  a.init(d.A + (long)g * d.strideA + ka, d.lda, m0, d.M, tid);
+  b.init(d.B + (long)g * d.strideB + kb, d.ldb, n0, d.N, tid);
 
   floatx16 acc[TM][TN];
 #pragma unroll
@@ -172,7 +176,7 @@ gemm_f32_fast_kernel(GemmDesc d) {
   // accumulators are laid out as the BM x BN tile, then every thread moves 16-byte pieces of
   // whole rows, so the stores and the loads of the extra operand (the old C, the ReLU mask or
   // the weights to update; all requested before the first is used) are fully coalesced.
-  float* C = d.C + (long)g * d.strideC;
+  float* C = d.C + (long)(splits > 1 ? gp : g) * d.strideC;
   const float* aux = d.aux ? d.aux + (long)g * d.strideAux : nullptr;
   float* sC = fast_lds;
   constexpr int CP = BN + 4;                       // pitch in floats
@@ -266,7 +270,7 @@ static hipError_t launch_fast_cfg(const GemmDesc& d, hipStream_t s) {
     if (e != hipSuccess) return e;
     ready = true;
   }
-  const long ntiles = (long)((d.N + BN - 1) / BN) * ((d.M + BM - 1) / BM) * d.groups;
+  const long ntiles = (long)((d.N + BN - 1) / BN) * ((d.M + BM - 1) / BM) * d.groups * (d.splits > 1 ? d.splits : 1);
   dim3 grid((unsigned)(8 * ((ntiles + 7) / 8)));
   hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB>), grid, dim3(FTHREADS), smem, s, d);
   return hipGetLastError();
@@ -286,6 +290,7 @@ hipError_t launch_gemm_f32_fast(const GemmDesc& d, hipStream_t s) {
   auto aligned = [](const float* p, long ld, long stride) {
     return ((uintptr_t)p & 15) == 0 && (ld & 3) == 0 && (stride & 3) == 0;
   };
+  if (d.splits > 1 && (d.epilogue != EPI_STORE || (d.Kd & 3) != 0)) return hipErrorInvalidValue;
   if (!aligned(d.A, d.lda, d.strideA) || !aligned(d.B, d.ldb, d.strideB)) return hipErrorNotSupported;
   // unit-stride-along-k operands load float4 along k; the others along m / n
   if (!d.transA ? (d.Kd & 3) != 0 : ((d.M & 3) != 0 || d.M < 4)) return hipErrorNotSupported;

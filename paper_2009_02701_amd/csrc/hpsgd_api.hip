@@ -21,6 +21,8 @@ struct Entry {
 
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+constexpr int kWihSplits = 4;  // parts of the contraction of a narrow layer's dW_ih GEMM (fp32)
+
 struct Region {  // one workspace buffer: K slices of `stride` floats
   size_t offset = 0, stride = 0;
 };
@@ -37,6 +39,7 @@ struct hpsgd_ctx {
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
   Region psync;                 // abort word and counters of the resident-weight recurrence kernels (fp32)
   Region dwp, dbp;              // their partial sums of dW_hh and of the bias gradients, one per 32-row batch tile
+  Region dwip;                  // partial sums of dW_ih of a narrow layer input (contraction cut into kWihSplits)
   Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
@@ -128,6 +131,7 @@ int build_layout(hpsgd_ctx* c) {
     if (gru_fused_supported(d.hidden)) c->dbp = c->alloc((size_t)((d.batch + 31) / 32) * 6 * H);
     if (d.prec != HPSGD_BF16_MFMA && gru_fused_supported(d.hidden) && gru_persist_dw_supported(d.hidden))
       c->dwp = c->alloc((size_t)((d.batch + 31) / 32) * 3 * H * H);
+    if (d.prec != HPSGD_BF16_MFMA) c->dwip = c->alloc((size_t)kWihSplits * 3 * H * (lm ? d.embed : d.input));
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
@@ -227,8 +231,9 @@ struct TimerScope {
 // GEMM helper: C = op(A) op(B) for `groups` workers.
 int gemm(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float* A, long lda,
          long sA, int tA, const float* B, long ldb, long sB, int tB, float* C, long ldc, long sC,
-         int epi, const float* aux, long sAux, int background = 0, float alpha = 0.f) {
+         int epi, const float* aux, long sAux, int background = 0, float alpha = 0.f, int splits = 1) {
   GemmDesc g;
+  g.splits = splits;
   g.background = background;
   g.alpha = alpha;
   g.A = A; g.lda = lda; g.strideA = sA; g.transA = tA;
@@ -828,8 +833,27 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
       } else {
         const WgradTarget wi = wgrad_target(p + ".W_ih");
-        TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
-                  wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
+        // fp32, a narrow layer-0 input: the GEMM has few tiles and a long contraction (T*B), so the
+        // contraction is cut into kWihSplits parts that run side by side; their sums are added
+        // in order by the kernel that also applies the update
+        const size_t n_wih = (size_t)3 * H * win;
+        const bool split_wih = !bf && l == 0 && win <= 256 && win >= 4 && (3 * H) % 4 == 0 &&
+                               TB % (4 * kWihSplits) == 0 &&
+                               c->dwip.stride == (size_t)kWihSplits * n_wih && (n_wih & 3) == 0 &&
+                               ((uintptr_t)dgx & 15) == 0 && ((uintptr_t)layer_in & 15) == 0 && (s_gx & 3) == 0 &&
+                               (s_layer_in & 3) == 0 && (win & 3) == 0 && ((uintptr_t)wi.C & 15) == 0 &&
+                               (wi.sC & 3) == 0 && (!wi.aux || (((uintptr_t)wi.aux & 15) == 0 && (sR & 3) == 0));
+        if (split_wih) {
+          float* parts = reg(c->dwip);
+          TRY(gemm(s, groups, 0, 3 * H, win, TB / kWihSplits, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
+                   parts, win, (long)n_wih, EPI_STORE, nullptr, 0, 0, 0.f, kWihSplits));
+          TimerScope ts_(c, role, s);
+          HIP_TRY(launch_reduce_parts(parts, kWihSplits, n_wih, wi.aux, (size_t)sR, wi.C, (size_t)wi.sC, lr,
+                                      wi.epi == EPI_COMMIT, groups, s));
+        } else {
+          TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
+                    wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
+        }
         const WgradTarget wh = wgrad_target(p + ".W_hh");
         if (dwp) {
           TimerScope ts_(c, role, s);

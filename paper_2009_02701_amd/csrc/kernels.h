@@ -53,6 +53,11 @@ struct GemmDesc {
   float* C; long ldc; long strideC;
   const float* aux; long strideAux;                    // bias [N] or mask [M][N] (ldc)
   int M, N, Kd, groups;
+  // splits > 1 (pipelined fp32 kernel only; the caller checks launch_gemm_f32_split_supported):
+  // the contraction is cut into `splits` equal parts of Kd each, part p of group g reads A and B
+  // advanced by p * Kd along the contraction and writes its own C at C + (g * splits + p) * strideC
+  // (strideC is then the distance between two parts; the epilogue must be EPI_STORE)
+  int splits;
   int epilogue;
   int bf16;                                            // round operands to bf16, use the bf16 MFMA
   float alpha;                                         // EPI_COMMIT: the learning rate
