@@ -1,0 +1,198 @@
+// The head of a classifier with few classes in two small launches per local step (fp32):
+//   logits = feats W^T + b;  loss = mean cross-entropy;  dlogits = (softmax - onehot) / N;
+//   dfeat = dlogits W;  dW = dlogits^T feats;  db = column sums of dlogits;
+//   then either the SGD update (W_out = W_in - lr dW, b_out = b_in - lr db) or the gradients.
+// With N <= 128 rows and C <= 32 classes each of the three products is a fraction of a
+// megaflop per worker: as three GEMM launches, two reductions, a softmax and a loss launch
+// they cost seven launch gaps and little else.  Here the forward part is cut over the rows
+// (8 rows per workgroup, 32 threads per row share a dot product) and the backward part over
+// the feature columns (64 per workgroup), so that a worker's head is spread over 16 CUs (a
+// single workgroup per worker with everything in LDS was measured at ~95 us: bound by one
+// CU's LDS rate).  Every sum runs in a fixed order.
+#include <cmath>
+
+#include "kernels.h"
+
+namespace hpsgd {
+
+namespace {
+
+constexpr int HMAXC = 32;     // classes
+constexpr int HMAXN = 128;    // rows
+constexpr int HROWS = 8;      // rows per workgroup, forward
+constexpr int HCOLS = 64;     // feature columns per workgroup, backward
+
+// Trips 0 .. n-1 of a copy loop, U at a time: the U loads go out before the first value is used
+// (a load whose value is stored at once waits out the memory latency on every trip).
+template <int U, typename Load, typename Store>
+__device__ __forceinline__ void batched_copy(int n, Load load, Store store) {
+  for (int base = 0; base < n; base += U) {
+    float v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) v[u] = load(min(base + u, n - 1));
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (base + u < n) store(base + u, v[u]);
+  }
+}
+
+// grid (ceil(N / 8), groups), 256 threads: thread t works for row t / 32 of the slice on the
+// contraction indices t % 32, + 32, ...
+__global__ void __launch_bounds__(256)
+cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* __restrict__ W,
+                    const float* __restrict__ b, long s_in, const int32_t* __restrict__ y, long s_y,
+                    float* __restrict__ dlog, long s_dlog, float* __restrict__ rowloss, long s_rowloss, int N, int C,
+                    int H) {
+  extern __shared__ __attribute__((aligned(16))) float head_lds[];
+  float* sW = head_lds;  // [C][H]
+  const int g = blockIdx.y, tid = threadIdx.x;
+  const int part = tid & 31, row = blockIdx.x * HROWS + (tid >> 5);
+  const int rowc = min(row, N - 1);
+  const float* Wg = W + g * s_in;
+  const int nW = C * H;
+  batched_copy<8>((nW + 255) / 256, [&](int i) { return Wg[min(tid + 256 * i, nW - 1)]; },
+                  [&](int i, float v) {
+                    if (tid + 256 * i < nW) sW[tid + 256 * i] = v;
+                  });
+  const float* fr = feats + g * s_feats + (long)rowc * H;
+  float acc[HMAXC];
+#pragma unroll
+  for (int c = 0; c < HMAXC; ++c) acc[c] = 0.f;
+  // this thread's share of the row, 8 values at a time
+  const int nk = (H - part + 31) / 32;  // k = part + 32 i < H
+  __syncthreads();
+  for (int base = 0; base < nk; base += 8) {
+    float f[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) f[u] = fr[part + 32 * min(base + u, nk - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (base + u < nk) {
+        const int k = part + 32 * (base + u);
+#pragma unroll
+        for (int c = 0; c < HMAXC; ++c)
+          if (c < C) acc[c] += f[u] * sW[c * H + k];
+      }
+  }
+  // the 32 partial sums of a row: butterfly inside its half of the wave
+#pragma unroll
+  for (int c = 0; c < HMAXC; ++c)
+    if (c < C) {
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) acc[c] += __shfl_xor(acc[c], o);
+    }
+  if (part == 0 && row < N) {
+    const float* bg = b + g * s_in;
+    const int label = y[g * s_y + row];
+    float m = -INFINITY;
+#pragma unroll
+    for (int c = 0; c < HMAXC; ++c)
+      if (c < C) {
+        acc[c] += bg[c];
+        m = fmaxf(m, acc[c]);
+      }
+    float sum = 0.f, zl = 0.f;
+#pragma unroll
+    for (int c = 0; c < HMAXC; ++c)
+      if (c < C) {
+        if (c == label) zl = acc[c];
+        acc[c] = expf(acc[c] - m);
+        sum += acc[c];
+      }
+    rowloss[g * s_rowloss + row] = -((zl - m) - logf(sum));
+    const float inv_sum = 1.0f / sum, inv_n = 1.0f / (float)N;
+    float* dr = dlog + g * s_dlog + (long)row * C;
+#pragma unroll
+    for (int c = 0; c < HMAXC; ++c)
+      if (c < C) dr[c] = (acc[c] * inv_sum - (c == label ? 1.0f : 0.0f)) * inv_n;
+  }
+}
+
+// grid (ceil(H / 64), groups), 256 threads: thread t owns column t % 64 of the slice
+__global__ void __launch_bounds__(256)
+cls_head_bwd_kernel(const float* __restrict__ feats, long s_feats, const float* W_in, const float* b_in, long s_in,
+                    const float* __restrict__ dlog, long s_dlog, const float* __restrict__ rowloss, long s_rowloss,
+                    float* __restrict__ dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr,
+                    int commit, float* __restrict__ loss, int N, int C, int H) {
+  __shared__ float sD[HMAXN * HMAXC];          // dlogits [N][C]
+  __shared__ float sF[HMAXN][HCOLS + 1];       // the slice of the features
+  __shared__ float sW[HMAXC][HCOLS + 1];       // the slice of W
+  const int g = blockIdx.y, tid = threadIdx.x;
+  const int jl = tid & 63, q = tid >> 6, j = blockIdx.x * HCOLS + jl;
+  const bool jv = j < H;
+  const int jc = jv ? j : 0;
+  const int nD = N * C;
+  batched_copy<4>((nD + 255) / 256, [&](int i) { return dlog[g * s_dlog + min(tid + 256 * i, nD - 1)]; },
+                  [&](int i, float v) {
+                    if (tid + 256 * i < nD) sD[tid + 256 * i] = v;
+                  });
+  batched_copy<8>((N - q + 3) / 4, [&](int i) { return feats[g * s_feats + (long)(q + 4 * i) * H + jc]; },
+                  [&](int i, float v) { sF[q + 4 * i][jl] = v; });
+  batched_copy<8>((C - q + 3) / 4, [&](int i) { return W_in[g * s_in + (long)(q + 4 * i) * H + jc]; },
+                  [&](int i, float v) { sW[q + 4 * i][jl] = v; });
+  __syncthreads();
+  for (int r = q; r < N; r += 4) {
+    float a = 0.f;
+    for (int c = 0; c < C; ++c) a += sD[r * C + c] * sW[c][jl];
+    if (jv) dfeat[g * s_dfeat + (long)r * H + j] = a;
+  }
+  for (int c = q; c < C; c += 4) {
+    float a0 = 0.f, a1 = 0.f;
+    int r = 0;
+    for (; r + 1 < N; r += 2) {
+      a0 += sD[r * C + c] * sF[r][jl];
+      a1 += sD[(r + 1) * C + c] * sF[r + 1][jl];
+    }
+    if (r < N) a0 += sD[r * C + c] * sF[r][jl];
+    const float dw = a0 + a1;
+    if (jv) W_out[g * s_out + (long)c * H + j] = commit ? sW[c][jl] - lr * dw : dw;
+  }
+  if (blockIdx.x == 0) {
+    if (tid < C) {
+      float a = 0.f;
+      for (int r = 0; r < N; ++r) a += sD[r * C + tid];
+      b_out[g * s_out + tid] = commit ? b_in[g * s_in + tid] - lr * a : a;
+    }
+    if (tid == 64 && loss) {
+      float v = 0.f;
+      for (int r = 0; r < N; ++r) v += rowloss[g * s_rowloss + r];
+      loss[g] = v / (float)N;
+    }
+  }
+}
+
+}  // namespace
+
+bool cls_head_supported(int N, int C, int H) {
+  return N >= 1 && N <= HMAXN && C >= 2 && C <= HMAXC && H >= 1 && (size_t)C * H * sizeof(float) <= 128 * 1024;
+}
+
+// feats: [groups][N][H] (stride s_feats); W_in / b_in: the head's parameters in the input replicas
+// (stride s_in); dlog ([N][C] per group, stride s_dlog) and rowloss ([N] per group) are scratch
+// that the first launch hands to the second; dfeat: [N][H] per group (stride s_dfeat);
+// commit != 0: W_out / b_out (stride s_out, may be W_in / b_in) receive the updated parameters,
+// else the gradients; loss: per group mean cross-entropy, or nullptr.
+hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, const float* b_in, long s_in,
+                           const int32_t* y, long s_y, float* dlog, long s_dlog, float* rowloss, long s_rowloss,
+                           float* dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr, int commit,
+                           float* loss, int N, int C, int H, int groups, hipStream_t s) {
+  if (!cls_head_supported(N, C, H)) return hipErrorInvalidValue;
+  const size_t lds = (size_t)C * H * sizeof(float);
+  static size_t allowed = 0;
+  if (lds > allowed && lds > 64 * 1024) {
+    hipError_t e = hipFuncSetAttribute((const void*)cls_head_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)lds);
+    if (e != hipSuccess) return e;
+    allowed = lds;
+  }
+  hipLaunchKernelGGL(cls_head_fwd_kernel, dim3((N + HROWS - 1) / HROWS, groups), dim3(256), lds, s, feats, s_feats,
+                     W_in, b_in, s_in, y, s_y, dlog, s_dlog, rowloss, s_rowloss, N, C, H);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(cls_head_bwd_kernel, dim3((H + HCOLS - 1) / HCOLS, groups), dim3(256), 0, s, feats, s_feats,
+                     W_in, b_in, s_in, dlog, s_dlog, rowloss, s_rowloss, dfeat, s_dfeat, W_out, b_out, s_out, lr,
+                     commit, loss, N, C, H);
+  return hipGetLastError();
+}
+
+}  // namespace hpsgd

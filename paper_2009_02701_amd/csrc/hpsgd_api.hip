@@ -603,6 +603,22 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                 wt.epi, wt.aux, sR, vdT, vhT, lr));
       HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
                                     grad + ob, sG, nrows, classes, groups, s));
+    } else if (!bf && !lm && cls_head_supported(nrows, classes, H)) {
+      // a classifier head with few classes: forward and loss in one small launch, the three
+      // gradients and the update (or the gradients, when they are accumulated as well) in another
+      role = HPSGD_ROLE_GEMM_HEAD;
+      TimerScope ts_(c, role, s);
+      if (acc) {
+        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sR, y, nrows, logits, s_log, rowloss,
+                                (long)c->rowloss.stride, D, s_D, grad + oW, grad + ob, sG, lr, 0, loss_out, nrows,
+                                classes, H, groups, s));
+      } else {
+        fused_commit[c->find("head.W")] = 1;
+        fused_commit[c->find("head.b")] = 1;
+        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sR, y, nrows, logits, s_log, rowloss,
+                                (long)c->rowloss.stride, D, s_D, rout + oW, rout + ob, sR, lr, 1, loss_out, nrows,
+                                classes, H, groups, s));
+      }
     } else {
       role = HPSGD_ROLE_GEMM_HEAD;
       {

@@ -66,6 +66,13 @@ struct GemmDesc {
 };
 hipError_t launch_gemm(const GemmDesc& d, hipStream_t s);
 
+// ---- classifier head with few classes in two small launches (fp32), see cls_head.hip ----
+bool cls_head_supported(int N, int C, int H);
+hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, const float* b_in, long s_in,
+                           const int32_t* y, long s_y, float* dlog, long s_dlog, float* rowloss, long s_rowloss,
+                           float* dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr, int commit,
+                           float* loss, int N, int C, int H, int groups, hipStream_t s);
+
 // ---- GRU cell, loss, reductions ----
 // forward cell for one time step of all groups:
 //   gx [B][3H] (b_ih included), gh [B][3H] (b_hh included), h_prev [B][H] -> h [B][H], saved [B][4H] = r|z|n|q
