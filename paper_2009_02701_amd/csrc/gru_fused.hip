@@ -65,121 +65,19 @@ __device__ __forceinline__ void step_tile(int NJ, int RT, int groups, int& g, in
 
 // ---------------------------------------------------------------------------- fp32 step kernels
 // Operands take the path global -> registers -> LDS -> MFMA layout: the workgroup fetches
-// 128-wide slabs of its weight rows and activation rows with fully contiguous loads (one wave
-// instruction = two whole 512-byte row segments).  Loading straight into the MFMA layout
+// 64- or 128-wide slabs of its weight rows and activation rows with fully contiguous loads (one
+// wave instruction = whole 256- or 512-byte row segments; LDS row pitch = slab width + 4 words,
+// so that 16 rows x 16-byte reads hit all 64 banks).  Loading straight into the MFMA layout
 // would need 16 row pieces of 64 bytes per instruction, which a fresh launch with a cold L2
 // serves about 1.7x slower.
-static constexpr int SK = 128;      // slab width along the contraction (4-byte words)
-static constexpr int SP = SK + 4;   // LDS row pitch in words: 16 rows x 16-byte reads hit 64 banks
-
 // acc[rb][q] += sum_k A[rb*16 + ..][k] * W_q[..][k].  Wbase points at the workgroup's first
 // weight row, gate block q starts w_qstride floats further, rows are KD floats apart;
-// Abase at its first activation row (rows >= rows_valid read as zero).  lds: 2*RT*(W+4) words.
-// The global loads of NB slabs (W words wide) at a time are all issued before the first of
-// them is used (one exposed memory latency per batch), then the slabs go through the two LDS
-// buffers one barrier apart.  W = 64 halves the LDS footprint so that more workgroups share
-// a CU and cover each other's latency.
+// Abase at its first activation row (rows >= rows_valid read as zero).
 // BF16: the rows hold bf16 pairs; all sizes (w_qstride, KD) are then counted in 4-byte words
 // (two bf16 each), the data movement is the same byte for byte, and one 16-byte fragment
 // feeds a single v_mfma_f32_16x16x32_bf16 (lane l: k = 32c + 8*(l/16) .. +7).
-template <int NQ, int NB, bool BF16, int W = SK>
-__device__ __forceinline__ void staged_contraction(const float* __restrict__ Wbase, long w_qstride,
-                                                   const float* __restrict__ Abase, int KD,
-                                                   int rows_valid, float* __restrict__ lds,
-                                                   floatx4 (&acc)[2][NQ]) {
-  constexpr int RT = 16 * NQ + 32;       // rows of one slab tile: weight rows, then 32 activation rows
-  constexpr int UR = W / 4;              // float4 units per row
-  constexpr int UPT = RT * UR / 256;     // float4 units per thread per slab
-  constexpr int P = W + 4;               // LDS row pitch
-  constexpr int NC = W / 64;             // 16-word chunks per wave per slab
-  static_assert(RT * UR % 256 == 0 && (W == 64 || W == 128), "slab shape");
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int lr = lane & 15, lg = lane >> 4;
-  const int nslab = (KD + W - 1) / W;
-  // per-thread row pointers and validity of its UPT units (the same for every slab)
-  const float* rowp[UPT];
-  bool rowok[UPT];
-#pragma unroll
-  for (int i = 0; i < UPT; ++i) {
-    const int row = (tid + i * 256) / UR;
-    if (row < 16 * NQ) {
-      rowp[i] = Wbase + (row >> 4) * w_qstride + (long)(row & 15) * KD;
-      rowok[i] = true;
-    } else {
-      const int ar = row - 16 * NQ;
-      rowok[i] = ar < rows_valid;
-      rowp[i] = Abase + (long)(rowok[i] ? ar : 0) * KD;
-    }
-  }
-  const int colofs = (tid % UR) << 2;
-  for (int s0 = 0; s0 < nslab; s0 += NB) {
-    // Branch-free loads (a conditional around a load makes the compiler wait for every
-    // outstanding load before the first use): rows beyond rows_valid read row 0, columns beyond
-    // KD read column 0, and such units are zeroed when they are written to LDS.
-    float4 regs[NB][UPT];
-    bool cok[NB];
-#pragma unroll
-    for (int sb = 0; sb < NB; ++sb) {
-      const int col = (s0 + sb) * W + colofs;
-      cok[sb] = col < KD;  // KD is a multiple of 16: a float4 is all in or all out
-      const int colc = cok[sb] ? col : 0;
-#pragma unroll
-      for (int i = 0; i < UPT; ++i) regs[sb][i] = *reinterpret_cast<const float4*>(rowp[i] + colc);
-    }
-    auto sstore = [&](int sb) {
-#pragma unroll
-      for (int i = 0; i < UPT; ++i) {
-        const int u = tid + i * 256;
-        const bool ok = cok[sb] && rowok[i];
-        const float4 v = regs[sb][i];  // (selected per component: a select between two float4
-                                       // objects would keep the whole register array in memory)
-        *reinterpret_cast<float4*>(&lds[((sb & 1) * RT + u / UR) * P + ((u % UR) << 2)]) =
-            make_float4(ok ? v.x : 0.f, ok ? v.y : 0.f, ok ? v.z : 0.f, ok ? v.w : 0.f);
-      }
-    };
-    __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
-    sstore(0);
-    __syncthreads();
-#pragma unroll
-    for (int sb = 0; sb < NB; ++sb) {
-      const int b = sb & 1;
-#pragma unroll
-      for (int ci = 0; ci < NC; ++ci) {
-        const int kcol = 16 * (wave + 4 * ci) + 4 * lg;  // chunk (wave + 4*ci) of this slab
-        float4 a[2], w[NQ];
-#pragma unroll
-        for (int q = 0; q < NQ; ++q)
-          w[q] = *reinterpret_cast<const float4*>(&lds[(b * RT + q * 16 + lr) * P + kcol]);
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-          a[rb] = *reinterpret_cast<const float4*>(&lds[(b * RT + 16 * NQ + rb * 16 + lr) * P + kcol]);
-#pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-          for (int q = 0; q < NQ; ++q) {
-            if (BF16) {
-              typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-              acc[rb][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a[rb]),
-                                                                   __builtin_bit_cast(bf16x8_t, w[q]),
-                                                                   acc[rb][q], 0, 0, 0);
-            } else {
-              acc[rb][q] = mfma4(a[rb], w[q], acc[rb][q]);
-            }
-          }
-      }
-      // the next slab goes to the other buffer as late as possible: its global loads have
-      // had the matrix work above to arrive (slabs past the end are written as zeros).
-      // The scheduling fences keep the compiler from sinking the MFMAs below the wait for
-      // that slab's loads, which would put the matrix work behind the memory latency.
-      __builtin_amdgcn_sched_barrier(0);
-      if (sb + 1 < NB) sstore(sb + 1);
-      __syncthreads();
-      __builtin_amdgcn_sched_barrier(0);
-    }
-  }
-}
-
-// The same contraction as a rolling pipeline: 64-word slabs, the loads of slab s+3 are issued
+//
+// The contraction as a rolling pipeline: 64-word slabs, the loads of slab s+3 are issued
 // while slab s is multiplied, so the wave never sits behind a long burst of load instructions
 // (a CU accepts only ~64 bytes of vector loads per clock: issuing a workgroup's whole operand
 // set up front keeps its waves busy issuing for microseconds before the first MFMA).

@@ -128,6 +128,15 @@ def test_gather_all_and_aux_stream_reject_bad_arguments():
     assert mg(0x1000, ok, 0.1, 2, 64, None) == 4                         # accumulator aliases global
     assert lib.hpsgd_local_step_all_acc(None, 0x1000, 0x1000, 64, 0x2000, 0x3000, 0.1, None, 0x4000, 64,
                                         0x5000, None) == 1
+    assert lib.hpsgd_set_recurrence(None, 1, 100) == 1
+    assert lib.hpsgd_set_recurrence(ctx._h, 0, 0) == 0 and lib.hpsgd_set_recurrence(ctx._h, 1, 1 << 20) == 0
+    gave, n0, n1, n2 = C.c_int(7), C.c_int(7), C.c_int(7), C.c_int(7)
+    assert lib.hpsgd_recurrence_gave_up(None, 0x1000, None, C.byref(gave)) == 1
+    assert lib.hpsgd_recurrence_gave_up(ctx._h, 0x1000, None, None) == 1
+    assert lib.hpsgd_recurrence_gave_up(ctx._h, None, None, C.byref(gave)) == 5      # no workspace
+    assert lib.hpsgd_recurrence_info(None, C.byref(n0), C.byref(n1), C.byref(n2)) == 1
+    assert lib.hpsgd_recurrence_info(ctx._h, C.byref(n0), None, C.byref(n2)) == 0    # before any step: zeros
+    assert (n0.value, n1.value, n2.value) == (0, 7, 0)
     assert lib.hpsgd_delay_us(2000000, None) == 1                        # beyond the one-second cap
     assert lib.hpsgd_delay_us(0, None) == 0                              # nothing to launch
     probe = lib.hpsgd_probe_mfma_rate

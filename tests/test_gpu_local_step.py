@@ -378,3 +378,34 @@ def test_resident_weight_recurrence_bf16_equals_one_launch_per_step(name):
             assert rel_err(d0, d1) <= TOL_BF16 / 4, (k, n, rel_err(d0, d1))
             assert np.array_equal(outs[0][0][k][n].view(np.uint32), outs[2][0][k][n].view(np.uint32)), (k, n)
     assert np.array_equal(outs[0][1].view(np.uint32), outs[2][1].view(np.uint32))
+
+
+def test_resident_weight_launches_from_two_streams_are_serialised():
+    """Two trainers step on two streams without any host synchronisation between the calls.
+    Resident-weight launches need the whole chip, so the library lets everything issued before
+    finish whenever the issuing stream changes; each trainer must end with the bits it gets
+    when it runs alone."""
+    cfgs = [RESIDENT["gru_cls_tiles"], RESIDENT["cls_wide"]]
+    alone, trainers, streams = [], [], []
+    for cfg in cfgs:
+        init, shards, orders, _ = workload(cfg)
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+        tr.sync_all(0)
+        for it in range(3):
+            tr.gather(it)
+            tr.local_step(0, cfg["lr"])
+        torch.cuda.synchronize()
+        alone.append(tr.R[0].cpu().numpy().view(np.uint32).copy())
+        tr2 = harness.Trainer(cfg, init, shards, orders, device=DEV)
+        tr2.sync_all(0)
+        trainers.append(tr2)
+        streams.append(torch.cuda.Stream(device=DEV))
+    torch.cuda.synchronize()
+    for it in range(3):
+        for tr, st in zip(trainers, streams):
+            tr.gather(it, stream=st)
+            tr.local_step(0, tr.cfg["lr"], stream=st)
+    torch.cuda.synchronize()
+    for tr, want in zip(trainers, alone):
+        assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+        assert np.array_equal(tr.R[0].cpu().numpy().view(np.uint32), want)
