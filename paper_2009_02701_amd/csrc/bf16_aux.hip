@@ -202,9 +202,67 @@ colsum_softmax_kernel(const float* __restrict__ logits, long s_logits, const flo
   }
 }
 
+// The same with four columns per lane (16-byte loads; C % 4 == 0, 16-byte aligned rows) and four
+// rows in flight per trip: a workgroup covers 256 columns with 16 row slices.
+__global__ void __launch_bounds__(1024)
+colsum_softmax4_kernel(const float* __restrict__ logits, long s_logits, const float2* __restrict__ rowstat,
+                       long s_rowstat, const int32_t* __restrict__ y, long s_y, float* __restrict__ out,
+                       long s_out, int N, int C) {
+  __shared__ float4 red[16][64];
+  const int g = blockIdx.y, lane = threadIdx.x & 63, slice = threadIdx.x >> 6;
+  const int c = blockIdx.x * 256 + 4 * lane;
+  const bool cv = c < C;
+  const float* p = logits + g * s_logits + (cv ? c : 0);
+  const float2* st = rowstat + g * s_rowstat;
+  const int32_t* yg = y + g * s_y;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f);
+  // rows slice, slice + 16, ..: four per trip, all their loads issued before the first is used
+  for (int r0 = slice; r0 < N; r0 += 64) {
+    float4 v[4];
+    float2 s4[4];
+    int lab[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int r = min(r0 + 16 * u, N - 1);
+      v[u] = *reinterpret_cast<const float4*>(p + (long)r * C);
+      s4[u] = st[r];
+      lab[u] = yg[r];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+      if (r0 + 16 * u < N) {
+        a.x += expf(v[u].x - s4[u].x) * s4[u].y - (lab[u] == c ? 1.0f : 0.0f);
+        a.y += expf(v[u].y - s4[u].x) * s4[u].y - (lab[u] == c + 1 ? 1.0f : 0.0f);
+        a.z += expf(v[u].z - s4[u].x) * s4[u].y - (lab[u] == c + 2 ? 1.0f : 0.0f);
+        a.w += expf(v[u].w - s4[u].x) * s4[u].y - (lab[u] == c + 3 ? 1.0f : 0.0f);
+      }
+  }
+  red[slice][lane] = a;
+  __syncthreads();
+  if (slice == 0 && cv) {
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const float4 t = red[i][lane];
+      v.x += t.x;
+      v.y += t.y;
+      v.z += t.z;
+      v.w += t.w;
+    }
+    const float inv = 1.0f / (float)N;
+    *reinterpret_cast<float4*>(out + g * s_out + c) = make_float4(v.x * inv, v.y * inv, v.z * inv, v.w * inv);
+  }
+}
+
 hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
                                  const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
                                  hipStream_t s) {
+  if (C % 4 == 0 && ((uintptr_t)logits & 15) == 0 && (s_logits & 3) == 0 && ((uintptr_t)out & 15) == 0 &&
+      (s_out & 3) == 0) {
+    hipLaunchKernelGGL(colsum_softmax4_kernel, dim3((C + 255) / 256, groups), dim3(1024), 0, s, logits, s_logits,
+                       reinterpret_cast<const float2*>(rowstat), s_rowstat / 2, y, s_y, out, s_out, N, C);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(colsum_softmax_kernel, dim3((C + 63) / 64, groups), dim3(1024), 0, s, logits, s_logits,
                      reinterpret_cast<const float2*>(rowstat), s_rowstat / 2, y, s_y, out, s_out, N, C);
   return hipGetLastError();
