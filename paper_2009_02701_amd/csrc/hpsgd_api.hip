@@ -882,8 +882,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
       if (dbp) {
-        HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + c->off(p + ".b_ih"),
-                                    (size_t)sG, 0.f, 0, groups, s));
+        // the kernel that adds the partial sums applies the update too, when it can write the
+        // replica with 16-byte accesses and the gradients are not accumulated as well
+        const size_t ob_ih = c->off(p + ".b_ih");
+        if (!acc && (sR & 3) == 0 && ((uintptr_t)(rin + ob_ih) & 15) == 0 && ((uintptr_t)(rout + ob_ih) & 15) == 0) {
+          fused_commit[c->find(p + ".b_ih")] = 1;
+          fused_commit[c->find(p + ".b_hh")] = 1;
+          HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sR, rout + ob_ih,
+                                      (size_t)sR, lr, 1, groups, s));
+        } else {
+          HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + ob_ih, (size_t)sG, 0.f, 0,
+                                      groups, s));
+        }
       } else {
         HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
         HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
