@@ -124,13 +124,9 @@ __device__ __forceinline__ void load_resident(float* wres, int wp, const float* 
   }
 }
 
-// acc[i][q] (i = 0, 1: two accumulators per gate block, summed by the caller) +=
-// sum over this wave's chunks of A[rsel*16 + ..][k] * Wres[q*16 + ..][k].
-// wres: the resident weight rows (pitch wp words, zero beyond KD); rs: buffer over the
-// workgroup's activation tile (row pitch KD words); rows >= rows_valid are read from row 0:
-// their results are never stored.  Columns beyond KD are read from column 0 and meet a zero
-// weight.  NB: chunks per wave whose loads are in flight together.
-// the loads of NB chunks of this wave, first chunk c0 (= wave & 3, + 4 per chunk)
+// The loads of NB chunks of this wave, first chunk c0 (= wave & 3, + 4 per chunk).  rs: buffer
+// over the workgroup's activation tile (row pitch KD words); rows >= rows_valid are read from
+// row 0 (their results are never stored), columns beyond KD from column 0 (they meet a zero weight).
 template <int NB>
 __device__ __forceinline__ void fragment_loads(__amdgpu_buffer_rsrc_t rs, int KD, int rows_valid, int c0,
                                                float4 (&a)[NB][2]) {
@@ -183,6 +179,10 @@ __device__ __forceinline__ void fragment_mfmas(const float* wres, int wp, int KD
   }
 }
 
+// acc[i][q] (i = 0, 1: two accumulators per gate block, summed by the caller) +=
+// sum over this wave's chunks of A[rsel*16 + ..][k] * Wres[q*16 + ..][k].
+// wres: the resident weight rows (pitch wp words, zero beyond KD).  NB: chunks per wave whose
+// loads are in flight together.
 template <int NQ, int NB>
 __device__ __forceinline__ void resident_contraction(const float* wres, int wp, __amdgpu_buffer_rsrc_t rs, int KD,
                                                      int rows_valid, floatx4 (&acc)[2][NQ]) {
