@@ -11,13 +11,13 @@
 // The steps of one launch depend on each other across workgroups: h_t of a 32-row batch tile
 // is produced by the NJ = H/16 workgroups that own its hidden units, and every one of them
 // needs all of it for step t+1.  Those NJ workgroups form a synchronisation group with one
-// counter in device memory.  Protocol (no cache-wide write-back or invalidate, which cost
-// several microseconds per step when 32 workgroups of an XCD each ask for one):
+// flag word per member in device memory.  Protocol (no cache-wide write-back or invalidate,
+// which cost several microseconds per step when 32 workgroups of an XCD each ask for one):
 //   producer: the exchanged values are stored with device-scope write-through stores (sc1);
 //             the workgroup barrier waits until every wave's stores have completed; then
-//             thread 0 adds 1 to the group's counter (device-scope atomic);
-//   consumer: thread 0 polls the counter (device-scope loads) until all NJ producers of the
-//             step have added theirs; workgroup barrier; the operand loads that follow are
+//             thread 0 stores the number of steps done into the member's flag (device scope);
+//   consumer: wave 0 polls the group's flags (device-scope loads, one lane per member) until
+//             all NJ producers have completed the step; workgroup barrier; the operand loads that follow are
 //             device-scope loads (sc1), which are served from the level of the memory
 //             hierarchy that all XCDs share, never from a stale line of this XCD's caches.
 // Values nobody reads before the launch ends (the saved gates, dgx) take ordinary stores.
@@ -69,34 +69,42 @@ __device__ __forceinline__ void persist_tile(int NJ, int RT, int groups, int& g,
   ty = sg % RT;
 }
 
-// Thread 0 polls the group's counter until it has reached `target` (wrap-safe), then the
+// A synchronisation group owns PF flag words, one per member: a member stores the number of
+// steps it has completed into its own word (plain device-scope stores to distinct words: no
+// read-modify-write that the group's members would queue up for), and the waiting side reads
+// all of them with one load instruction of wave 0, lane l looking at member l.
+constexpr int PF = 64;  // flag words per group (a group has H/16 or H/32 <= 42 members)
+
+// Wave 0 polls the group's flags until every member has reached `target` (wrap-safe), then the
 // whole workgroup passes a barrier.  Returns false, for every thread alike, if the wait was
 // given up; the abort word is then set.  limit == 0 makes every wait fail (the host-forced
 // way to exercise the abort path).
-__device__ __forceinline__ bool group_wait(unsigned* ctr, unsigned target, unsigned* abort_w, unsigned limit,
-                                           int* lds_flag) {
-  if (threadIdx.x == 0) {
+__device__ __forceinline__ bool group_wait(unsigned* flags, int members, unsigned target, unsigned* abort_w,
+                                           unsigned limit, int* lds_flag) {
+  if (threadIdx.x < 64) {
+    const int l = threadIdx.x;
     int ok = limit != 0;
     unsigned n = 0;
-    while (ok && (int)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
-      if (++n > limit || __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
-        ok = 0;
-        break;
-      }
-      __builtin_amdgcn_s_sleep(1);
+    while (ok) {
+      const unsigned v = __hip_atomic_load(flags + (l < members ? l : 0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (__all((int)(v - target) >= 0)) break;
+      if (++n > limit || __hip_atomic_load(abort_w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) ok = 0;
+      else __builtin_amdgcn_s_sleep(1);
     }
-    if (!ok) __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *lds_flag = ok;
+    if (l == 0) {
+      if (!ok) __hip_atomic_store(abort_w, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *lds_flag = ok;
+    }
   }
   __syncthreads();
   return *lds_flag != 0;
 }
 
-// The barrier waits for the completion of every wave's stores; then thread 0 counts the
-// workgroup in.
-__device__ __forceinline__ void group_signal(unsigned* ctr) {
+// The barrier waits for the completion of every wave's stores; then thread 0 publishes the
+// number of steps this member has completed.
+__device__ __forceinline__ void group_signal(unsigned* my_flag, unsigned steps_done) {
   __syncthreads();
-  if (threadIdx.x == 0) __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (threadIdx.x == 0) __hip_atomic_store(my_flag, steps_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // 16 bytes at byte offset `off` of the buffer, as a device-scope load
@@ -202,8 +210,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
 
 // Forward: steps t = 0 .. T-1.  hs holds h_0 .. h_T ((T+1) blocks of B x H per worker, h_0
 // given), gx the input projections of all steps, sv receives r|z|n|q of every step.
-// sync: the abort word, then one counter per synchronisation group; `base` is what the
-// counters read when the kernel starts.
+// sync: the abort word, then 64 flag words per synchronisation group; `base` is what the
+// flags read when the kernel starts.
 // XP: the kernel computes the input projection itself, gx_t = x_t W_ih^T + b_ih, from the
 // layer input xin (blocks of B x width per step) with its 48 rows of W_ih resident in LDS too;
 // that part of a step does not depend on the other workgroups and is done before the wait.
@@ -233,7 +241,7 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
   persist_tile(NJ, RT, groups, g, tx, ty, sg);
   const int j0 = tx * PJ, r0 = ty * PR;
   unsigned* abort_w = sync;
-  unsigned* ctr = sync + 1 + sg;
+  unsigned* flags = sync + 1 + sg * PF;
   __builtin_amdgcn_s_setprio(3);
   // the resident slices: rows q*16 + r = W_hh[q*H + j0 + r][:] (and the same rows of W_ih)
   load_resident(wres, wp, W_hh + g * s_rep, 48, H,
@@ -283,7 +291,7 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
 #pragma unroll
       for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
     }
-    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
     resident_contraction<3, 4>(wres, wp, tile_rsrc(hsg + ((long)t * B + r0) * H), H, B - r0, acc);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
@@ -314,7 +322,7 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
       svr[3 * H + j] = qv;
     }
     hpv = hn;
-    group_signal(ctr);  // (its barrier also separates the reads of red from the next step's writes)
+    group_signal(flags + tx, base + (unsigned)t + 1u);  // (its barrier also separates the reads of red from the next step's writes)
   }
 }
 
@@ -355,7 +363,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
   persist_tile(NJ, RT, groups, g, tx, ty, sg);
   const int j0 = tx * PJ, r0 = ty * PR;
   unsigned* abort_w = sync;
-  unsigned* ctr = sync + 1 + sg;
+  unsigned* flags = sync + 1 + sg * PF;
   __builtin_amdgcn_s_setprio(3);
   // weight-gradient share: this lane's 4 columns (clamped: results outside H are not stored)
   const int wn = 64 * wave + 4 * lr;
@@ -395,7 +403,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
     const float r = svr[j], z = svr[H + j], n = svr[2 * H + j], q = svr[3 * H + j];
     const float hp = hs[g * s_hs + e];
     const float ab = above ? above[g * s_above + e] : 0.f;
-    if (it > 0 && !group_wait(ctr, base + (unsigned)it * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    if (it > 0 && !group_wait(flags, NJ, base + (unsigned)it, abort_w, spin_limit, lds_flag)) return;
     floatx4 acc[2][1];
     acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
     acc[1][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
@@ -444,7 +452,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
       for (int s8 = 0; s8 < 8; ++s8)
         hv[s8] = *reinterpret_cast<const float4*>(hrow + (long)min(r0 + 4 * s8 + lg, B - 1) * H);
     }
-    group_signal(ctr);  // (its barrier also publishes the staged tile to the workgroup)
+    group_signal(flags + tx, base + (unsigned)it + 1u);  // (its barrier also publishes the staged tile to the workgroup)
     if (dWp) {
 #pragma unroll
       for (int s8 = 0; s8 < 8; ++s8) {
@@ -547,7 +555,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
   persist_tile(NJ, RT, groups, g, tx, ty, sg);
   const int j0 = tx * QJ, r0 = ty * PR;
   unsigned* abort_w = sync;
-  unsigned* ctr = sync + 1 + sg;
+  unsigned* flags = sync + 1 + sg * PF;
   __builtin_amdgcn_s_setprio(3);
   const int nch = H / PC;
   // resident fragments: chunk wave + 8i, column block cb = 2q + half: rows q*H + j0 + 16*half + lr
@@ -584,7 +592,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
     float2 gxv[3];
 #pragma unroll
     for (int q = 0; q < 3; ++q) gxv[q] = *reinterpret_cast<const float2*>(gxr + q * H);
-    if (t > 0 && !group_wait(ctr, base + (unsigned)t * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hbg + ((long)t * B + r0) * H, 0, 0x7fffffff,
                                                                         0x00020000);
     bf16x8 a[NCF][2];
@@ -644,7 +652,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
       tt[(u0 + 1) * TP + rl] = (__bf16)hn.y;
     }
     hpv = hn;
-    group_signal(ctr);  // (its barrier also separates the reads of red from the next step's writes)
+    group_signal(flags + tx, base + (unsigned)t + 1u);  // (its barrier also separates the reads of red from the next step's writes)
     if (hT && tid < 128) {
       // 64-byte row segments of the transposed copy, 16 bytes per thread
       const int u = tid >> 2, part = tid & 3;
@@ -684,7 +692,7 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
   persist_tile(NJ, RT, groups, g, tx, ty, sg);
   const int j0 = tx * QJ, r0 = ty * PR;
   unsigned* abort_w = sync;
-  unsigned* ctr = sync + 1 + sg;
+  unsigned* flags = sync + 1 + sg * PF;
   __builtin_amdgcn_s_setprio(3);
   const int H3 = 3 * H;
   const int nch = H3 / PC;
@@ -723,7 +731,7 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
     const float2 n = *reinterpret_cast<const float2*>(svr + 2 * H), q = *reinterpret_cast<const float2*>(svr + 3 * H);
     const float2 hp = *reinterpret_cast<const float2*>(hs + g * s_hs + e);
     const float2 ab = above ? *reinterpret_cast<const float2*>(above + g * s_above + e) : make_float2(0.f, 0.f);
-    if (it > 0 && !group_wait(ctr, base + (unsigned)it * (unsigned)NJ, abort_w, spin_limit, lds_flag)) return;
+    if (it > 0 && !group_wait(flags, NJ, base + (unsigned)it, abort_w, spin_limit, lds_flag)) return;
     floatx4 acc[2][2];
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
@@ -799,7 +807,7 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
     tt[(3 * QJ + u0) * TP + rl] = (__bf16)dq.x;
     tt[(3 * QJ + u0 + 1) * TP + rl] = (__bf16)dq.y;
     dcar = make_float2(dh.x * z.x, dh.y * z.y);
-    group_signal(ctr);
+    group_signal(flags + tx, base + (unsigned)it + 1u);
     {
       // transposed copies [gate unit][t*B + row] as 64-byte row segments, 16 bytes per thread:
       // dgx^T = (da_r, da_z, da_n), dgh^T = (da_r, da_z, dq)
@@ -870,11 +878,11 @@ bool gru_persist_supported(int B, int H, int groups) {
 // The backward kernel can accumulate dW_hh itself when 8 waves x 64 columns cover H.
 bool gru_persist_dw_supported(int H) { return H <= 512; }
 
-// Words of device memory the kernels synchronise through: the abort word + one counter per group.
-size_t gru_persist_sync_words(int B, int groups) { return (size_t)groups * ((B + PR - 1) / PR) + 1; }
+// Words of device memory the kernels synchronise through: the abort word + 64 flag words per group.
+size_t gru_persist_sync_words(int B, int groups) { return (size_t)groups * ((B + PR - 1) / PR) * PF + 1; }
 
-// How much every counter advances per time step of a launch.
-unsigned gru_persist_count_per_step(int H) { return (unsigned)(H / PJ); }
+// How much every flag advances per time step of a launch.
+unsigned gru_persist_count_per_step(int) { return 1u; }
 
 // The forward kernel can do the input projection itself when the layer input is narrow enough
 // for the 48 rows of W_ih to fit the LDS beside those of W_hh (at most 2 x 4 chunks of 32).
@@ -965,7 +973,7 @@ bool gru_persist_bf16_supported(int B, int H, int groups) {
   return grid <= device_cus();
 }
 
-unsigned gru_persist_bf16_count_per_step(int H) { return (unsigned)(H / QJ); }
+unsigned gru_persist_bf16_count_per_step(int) { return 1u; }
 
 hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep, const float* gx,
                                        long s_gx, float* hs, long s_hs, void* hb, long s_hb, float* sv, long s_sv,

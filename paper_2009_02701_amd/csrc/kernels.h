@@ -94,8 +94,8 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
                                int B, int H, int groups, hipStream_t s);
 // ---- whole runs of time steps in one launch, W_hh resident in LDS (fp32), see gru_persist.hip ----
-// sync: gru_persist_sync_words() words of device memory (the abort word, then one counter per
-// synchronisation group); base: what the counters read when the launch starts; every launch
+// sync: gru_persist_sync_words() words of device memory (the abort word, then the flag words of
+// the synchronisation groups); base: what the flags read when the launch starts; every launch
 // advances them by steps * gru_persist_count_per_step().  spin_limit bounds every wait.
 bool gru_persist_supported(int B, int H, int groups);
 size_t gru_persist_sync_words(int B, int groups);
