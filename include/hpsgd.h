@@ -128,16 +128,18 @@ int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float 
  * gradients are summed chunk by chunk). */
 int hpsgd_set_aux_stream(hpsgd_ctx *ctx, void *hip_stream);
 
-/* How the fp32 GRU recurrence of a local step (Alg. 2 "compute local gradients") is launched.
+/* How the GRU recurrence of a local step (Alg. 2 "compute local gradients") is launched.
  * resident != 0 (the default): where the shape allows it (the workgroups of one launch must
- * all fit the device at once, and a workgroup's slice of W_hh must fit its LDS), the time
- * steps of a layer run as one launch (BPTT: one per chunk handed to the auxiliary stream)
- * whose workgroups keep their weights on the chip and wait for each other through counters in
- * the workspace; otherwise, and with resident == 0, one launch per time step.  Both forms
- * compute the same values in the same order.  spin_limit bounds every such wait (polls of the
- * counter; 0 makes every wait fail at once, for testing).  A wait that is given up ends the
- * launch early on every workgroup, and the local step then delivers NaN in loss_out and in
- * the first parameter of every output replica; hpsgd_recurrence_gave_up reports it too.
+ * all fit the device at once, and a workgroup's slice of W_hh must fit its LDS or, with bf16
+ * operands, its registers), all time steps of a layer run as one launch per direction whose
+ * workgroups keep their weights on the chip and wait for each other through flag words in
+ * the workspace; such a launch may also take over the input projection of a narrow layer
+ * input, the recurrent weight gradient and the bias gradients.  Otherwise, and with
+ * resident == 0, one launch per time step.  Both forms compute the same quantities; the fp32
+ * sums inside a dot product are taken in a different order.  spin_limit bounds every such wait
+ * (polls of the flags; 0 makes every wait fail at once, for testing).  A wait that is given up
+ * ends the launch early on every workgroup, and the local step then delivers NaN in loss_out
+ * and in the first parameter of every output replica; hpsgd_recurrence_gave_up reports it too.
  * Launches of this kind from different streams are serialised by the library (the device is
  * synchronised when the stream changes). */
 int hpsgd_set_recurrence(hpsgd_ctx *ctx, int resident, unsigned spin_limit);

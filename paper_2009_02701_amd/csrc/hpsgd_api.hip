@@ -37,7 +37,7 @@ struct hpsgd_ctx {
   size_t ws_floats = 0;
   // workspace regions (floats)
   Region grad, xe, gx, dgh, gh, D, dx, logits, rowloss, wt;
-  Region psync;                 // abort word and counters of the resident-weight recurrence kernels (fp32)
+  Region psync;                 // abort word and flag words of the resident-weight recurrence kernels
   Region dwp, dbp;              // their partial sums of dW_hh and of the bias gradients, one per 32-row batch tile
   Region dwip;                  // partial sums of dW_ih of a narrow layer input (contraction cut into kWihSplits)
   Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
@@ -404,8 +404,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // read as the row-major copies
     bool whhT_ready[16] = {false}, wihT_ready[16] = {false};
     // fp32: the recurrence of a layer as one launch (a few for BPTT) with W_hh resident in LDS.
-    // Its workgroups wait for each other through counters in the workspace, zeroed here; pbase
-    // follows what the counters read.  A given-up wait shows as NaN in the results (below).
+    // Its workgroups wait for each other through flag words in the workspace, zeroed here; pbase
+    // follows what the flags read.  A given-up wait shows as NaN in the results (below).
     const bool use_persist = !bf && c->resident && gru_fused_supported(H) && gru_persist_supported(B, H, groups);
     // bf16: the same with the weight slices in registers; its backward launch writes only the bf16
     // copies of the gate gradients, so every GEMM that consumes them must be able to take those
