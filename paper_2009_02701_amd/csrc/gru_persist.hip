@@ -342,7 +342,13 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
 // Wave w owns columns 64w .. 64w+63 and all 48 gate rows (3 x 4 accumulator tiles); tile
 // (mt, jt) holds the columns 64w + 4*lane%16 + jt, so that a lane fetches h as one float4 per
 // batch row and stores its results as float4s.
-__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
+//
+// Register cap: two waves of this kernel share a SIMD, and at 256 registers each they would own
+// its whole register file, so that no wave of any other kernel (the merge of the other stream,
+// a short kernel queued behind) could start on a CU before this launch has ended.  The
+// attribute counts in halves of the unified VGPR/AGPR file on this target: 124 caps the wave at
+// 248 registers (2 dwords per lane are spilled), which leaves 16 per SIMD for a co-tenant.
+__global__ void __launch_bounds__(PNT) __attribute__((amdgpu_num_vgpr(124)))
 gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, float* __restrict__ dgx, long s_dg,
                        float* __restrict__ D, long s_D, const float* __restrict__ above, long s_above,
                        const float* __restrict__ sv, long s_sv, const float* __restrict__ hs, long s_hs,
