@@ -365,6 +365,233 @@ gemm_bf16_dl_kernel(GemmNtDesc d) {
   nt_epilogue<COMMIT>(d, acc, nt_smem, g, m0, n0);
 }
 
+// ---------------------------------------------------------------------------- one workgroup per CU
+// The same direct-to-LDS scheme with the whole CU given to one workgroup of WGM x WGN waves (two
+// per SIMD), each wave owning (32 TM) x (32 TN) outputs, and S stages of LDS: the loads of the
+// k-tiles kt+1 .. kt+S-1 are in flight while tile kt is multiplied, so that the memory latency is
+// covered by S-1 tiles of matrix work instead of one (with two independent 4-wave workgroups per
+// CU and two stages each, a workgroup waits for most of the latency on every k-tile).
+// The fragments of contraction step ks+1 are read from LDS while the MFMAs of step ks run.
+// A wave's share of a stage's loads is IPW instructions; a wave waits until all but the newest
+// (S-2) IPW of its own loads have landed, and the barrier extends that to every wave's loads.
+// S buffers hold tile kt and the S-1 tiles behind it.
+// Tiles beyond the contraction are still "loaded" (from 16 zero bytes), so the count of loads
+// in flight is the same on every trip.
+template <int WGM, int WGN, int TM, int TN, int S>
+struct DlxShape {
+  static constexpr int NW = WGM * WGN, NT = 64 * NW;
+  static constexpr int BM = WGM * TM * 32, BN = WGN * TN * 32;
+  static constexpr int ROWS = BM + BN;             // rows of 128 bytes per stage: A's, then B's
+  static constexpr int IPW = ROWS / 8 / NW;        // loader instructions (8 rows each) per wave and stage
+  static constexpr int STAGE = ROWS * 128;         // bytes
+  static constexpr int CP = BN + 4;                // pitch (floats) of the epilogue tile
+  static constexpr int EH = (size_t)BM * CP * 4 > 160 * 1024 ? 2 : 1;  // the epilogue goes through LDS in EH row chunks
+  static constexpr int ER = BM / EH;               // rows per chunk
+  static constexpr size_t LDS = (size_t)S * STAGE > (size_t)ER * CP * 4 ? (size_t)S * STAGE : (size_t)ER * CP * 4;
+  static_assert(ROWS % (8 * NW) == 0, "the loader instructions must divide evenly over the waves");
+  static_assert(BM % 16 == 0, "the swizzle of B's rows must not depend on BM");
+  static_assert((NT * 4) % BN == 0 && ER % (NT * 4 / BN) == 0 && ER % 32 == 0, "epilogue passes");
+};
+
+template <int BM, int BN>
+__device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_m, int& tile_n) {
+  // the same order as nt_tile: the dimension with more tiles is dealt out to the XCDs
+  const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
+  const bool slow_is_n = tn >= tm;
+  const int ts = slow_is_n ? tn : tm, tf = slow_is_n ? tm : tn;
+  const int s8 = (ts + 7) >> 3;
+  const int c = blockIdx.x & 7, li = blockIdx.x >> 3;
+  const int f = li % tf, sl = (li / tf) % s8;
+  g = li / (tf * s8);
+  const int st = c + 8 * sl;
+  if (st >= ts) return false;
+  tile_m = slow_is_n ? f : st;
+  tile_n = slow_is_n ? st : f;
+  return true;
+}
+
+template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
+__global__ void __launch_bounds__(64 * WGM * WGN)
+gemm_bf16_dlx_kernel(GemmNtDesc d) {
+  using Sh = DlxShape<WGM, WGN, TM, TN, S>;
+  constexpr int BM = Sh::BM, BN = Sh::BN, IPW = Sh::IPW, CP = Sh::CP, NT = Sh::NT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char nt_smem[];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave % WGM, wn = wave / WGM;
+  const int lrow = lane & 31, lk = lane >> 5;
+  int g, tile_m, tile_n;
+  if (!dlx_tile<BM, BN>(d, g, tile_m, tile_n)) return;
+  const int m0 = tile_m * BM, n0 = tile_n * BN;
+  const __bf16* __restrict__ A = reinterpret_cast<const __bf16*>(d.A) + (long)g * d.strideA;
+  const __bf16* __restrict__ B = reinterpret_cast<const __bf16*>(d.B) + (long)g * d.strideB;
+  // loader: instruction i of wave w covers stage rows (w IPW + i) 8 .. +7 (rows below BM are A's);
+  // lane j: row + (j >> 3), LDS chunk j & 7, which holds the row's chunk (j & 7) ^ ((row >> 1) & 7)
+  const __bf16* gp[IPW];
+  int kofs[IPW];
+#pragma unroll
+  for (int i = 0; i < IPW; ++i) {
+    const int row = (wave * IPW + i) * 8 + (lane >> 3);
+    kofs[i] = ((lane & 7) ^ ((row >> 1) & 7)) * 8;
+    gp[i] = (row < BM ? A + (long)min(m0 + row, d.M - 1) * d.lda : B + (long)min(n0 + row - BM, d.N - 1) * d.ldb) + kofs[i];
+  }
+  const __bf16* zero = reinterpret_cast<const __bf16*>(nt_zero16);
+  auto issue = [&](int stage, int kt) {
+    unsigned char* sa = nt_smem + stage * Sh::STAGE + wave * IPW * 1024;
+#pragma unroll
+    for (int i = 0; i < IPW; ++i) {
+      const bool ok = kt * NBK + kofs[i] < d.Kd;  // Kd is a multiple of 8: a chunk is all in or all out
+      __builtin_amdgcn_global_load_lds(HPSGD_GPTR(ok ? gp[i] + kt * NBK : zero), HPSGD_LPTR(sa + i * 1024), 16, 0, 0);
+    }
+  };
+  floatx16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  // operand fragments: row r, chunk c = 2 ks + lk at byte r * 128 + ((c ^ ((r >> 1) & 7)) << 4)
+  int ra[TM], swa[TM], rb[TN], swb[TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int r = (wm * TM + i) * 32 + lrow;
+    ra[i] = r * 128;
+    swa[i] = (r >> 1) & 7;
+  }
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int r = (wn * TN + j) * 32 + lrow;
+    rb[j] = (BM + r) * 128;
+    swb[j] = (r >> 1) & 7;
+  }
+  const int nk = (d.Kd + NBK - 1) / NBK;
+  bf16x8 fa[2][TM], fb[2][TN];
+  auto fragments = [&](const unsigned char* sb, int ks, bf16x8(&fa_)[TM], bf16x8(&fb_)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) fa_[i] = *reinterpret_cast<const bf16x8*>(sb + ra[i] + (((2 * ks + lk) ^ swa[i]) << 4));
+#pragma unroll
+    for (int j = 0; j < TN; ++j) fb_[j] = *reinterpret_cast<const bf16x8*>(sb + rb[j] + (((2 * ks + lk) ^ swb[j]) << 4));
+  };
+  auto mfmas = [&](const bf16x8(&fa_)[TM], const bf16x8(&fb_)[TN]) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa_[i], fb_[j], acc[i][j], 0, 0, 0);
+  };
+  // Pipeline: the barrier that hands over tile kt+1 sits before the last quarter of tile kt's
+  // MFMAs, and the first fragments of tile kt+1 are read between the two, so that the matrix
+  // cores have work queued while the waves meet and while the first LDS reads are on their way.
+#pragma unroll
+  for (int st = 0; st < S - 1; ++st) issue(st, st);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * IPW) : "memory");
+  __builtin_amdgcn_s_barrier();  // tile 0 is in LDS
+  issue(S - 1, S - 1);
+  fragments(nt_smem, 0, fa[0], fb[0]);
+  int stage = 0;
+  for (int kt = 0; kt < nk; ++kt) {
+    const unsigned char* sb = nt_smem + stage * Sh::STAGE;
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+      fragments(sb, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+      mfmas(fa[ks & 1], fb[ks & 1]);
+    }
+    // this wave's reads of tile kt are complete, its loads of tile kt+1 have landed ...
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * IPW) : "memory");
+    __builtin_amdgcn_s_barrier();  // ... and so are and have everyone's
+    issue(stage, kt + S);          // into the buffer tile kt has left
+    stage = stage + 1 == S ? 0 : stage + 1;
+    fragments(nt_smem + stage * Sh::STAGE, 0, fa[0], fb[0]);
+    mfmas(fa[1], fb[1]);
+  }
+  // the zero loads of the tiles beyond the contraction must have landed before the operand
+  // buffers become the epilogue tile
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+
+  // Epilogue through LDS, as in nt_epilogue: accumulators -> tile of ER rows x BN -> row segments
+  float* C = d.C + (long)g * d.strideC;
+  const float* bias = d.bias ? d.bias + (long)g * d.strideBias : nullptr;
+  float* sC = reinterpret_cast<float*>(nt_smem);
+  constexpr int ER = Sh::ER, TPR = BN / 4, RPP = NT / TPR, PASSES = ER / RPP;
+  const int c4 = (tid % TPR) << 2, rbase = tid / TPR;
+  const int col = n0 + c4;
+  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
+                   (!COMMIT || (((uintptr_t)d.win & 15) == 0 && (d.strideWin & 3) == 0));
+#pragma unroll
+  for (int h = 0; h < Sh::EH; ++h) {
+    if (h > 0) __syncthreads();  // the previous chunk has been read
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+      const int rb = (wm * TM + i) * 32;  // the block's first row in the tile
+      if (rb / ER != h) continue;         // uniform over the wave
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          sC[(rb % ER + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + (wn * TN + j) * 32 + lrow] = acc[i][j][v];
+    }
+    __syncthreads();
+    const int mh = m0 + h * ER;
+    if (vec && col + 3 < d.N) {
+      float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
+      if (!COMMIT && bias) bv = make_float4(bias[col], bias[col + 1], bias[col + 2], bias[col + 3]);
+      float4 w[COMMIT ? PASSES : 1];
+      if (COMMIT) {
+        const float* W = d.win + (long)g * d.strideWin;
+#pragma unroll
+        for (int p = 0; p < PASSES; ++p) {
+          const int row = min(mh + rbase + RPP * p, d.M - 1);  // clamped: not stored when outside
+          w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
+        }
+      }
+#pragma unroll
+      for (int p = 0; p < PASSES; ++p) {
+        const int rl = rbase + RPP * p, row = mh + rl;
+        if (row >= d.M) continue;
+        const float4 a = *reinterpret_cast<const float4*>(&sC[rl * CP + c4]);
+        float4 o;
+        if (COMMIT) {
+          const float4 wv = w[COMMIT ? p : 0];
+          o = make_float4(wv.x - d.lr * a.x, wv.y - d.lr * a.y, wv.z - d.lr * a.z, wv.w - d.lr * a.w);
+        } else {
+          o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
+        }
+        *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+      }
+    } else if (col < d.N) {
+      const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
+      for (int p = 0; p < PASSES; ++p) {
+        const int rl = rbase + RPP * p, row = mh + rl;
+        if (row >= d.M) continue;
+        for (int e = 0; e < 4; ++e) {
+          if (col + e >= d.N) break;
+          const long off = (long)row * d.ldc + col + e;
+          const float a = sC[rl * CP + c4 + e];
+          C[off] = COMMIT ? W[off] - d.lr * a : a + (bias ? bias[col + e] : 0.f);
+        }
+      }
+    }
+  }
+}
+
+template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
+hipError_t launch_dlx(const GemmNtDesc& d, hipStream_t s) {
+  using Sh = DlxShape<WGM, WGN, TM, TN, S>;
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Sh::LDS);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
+  const int tm = (d.M + Sh::BM - 1) / Sh::BM, tn = (d.N + Sh::BN - 1) / Sh::BN;
+  const int ts = tn >= tm ? tn : tm, tf = tn >= tm ? tm : tn;
+  hipLaunchKernelGGL((gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>), dim3(8 * ((ts + 7) / 8) * tf * d.groups),
+                     dim3(Sh::NT), Sh::LDS, s, d);
+  return hipGetLastError();
+}
+
 // a_bf16 / b_bf16: the operand is stored as bf16 (else fp32).  Leading dimensions and group
 // strides are in elements of the operand's own type.  Requires 16-byte aligned bases, row
 // pitches and group strides that are multiples of 16 bytes, and Kd a multiple of 8
@@ -422,6 +649,23 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
     }                                                                                             \
     hipLaunchKernelGGL((gemm_bf16_dl_kernel<CM>), grid, block, dl_smem, s, d);                    \
   } while (0)
+    // Which tile: one 8-wave workgroup per CU with a 256 x 256 tile does more matrix work per
+    // byte through LDS and per byte fetched, but nothing overlaps its epilogue and its first
+    // loads; two independent 128 x 128 workgroups per CU cover each other's.  Measured on the
+    // shapes of the GRU language model (K = 8 groups): the large tile wins where the contraction is
+    // long (>= 2560: 346 against 507 us at Kd = 10000) or where a large output is updated in place
+    // (the head's weight gradient: 338 against 402 us); a 128 x 256 tile wins for the smaller
+    // in-place updates (3072 x 1024: 98 against 105 us); the short contractions with plain
+    // outputs stay with the small tile (input projection: 85 against 94 .. 120 us).
+    const long out = (long)M * N;
+    if (Kd >= 2560 && M > 128 && N > 128) {
+      if (win) return launch_dlx<true, 2, 4, 4, 2, 2>(d, s);
+      return launch_dlx<false, 2, 4, 4, 2, 2>(d, s);
+    }
+    if (win && M > 128 && N > 128 && Kd >= 512) {
+      if (out >= (8L << 20)) return launch_dlx<true, 2, 4, 4, 2, 2>(d, s);
+      if (out >= (1L << 20)) return launch_dlx<true, 2, 4, 2, 2, 3>(d, s);
+    }
     if (win) HPSGD_DL(true);
     else HPSGD_DL(false);
 #undef HPSGD_DL

@@ -36,6 +36,10 @@ BF16 = {
     "lm_nt_bf16": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=8, K=2),
     "lm_nt_bf16_tiles": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=72, hidden=160, seq_len=19, batch=16, K=2),
     "lm_nt_bf16_v2048": wl.scaled(wl.CONFIGS["gru_lm"], vocab=2048, embed=32, hidden=64, seq_len=3, batch=8, K=2),
+    # long contraction (vocab >= 2560) with ragged tiles in every dimension: the 256 x 256 tile form
+    "lm_nt_bf16_long": wl.scaled(wl.CONFIGS["gru_lm"], vocab=2600, embed=40, hidden=136, seq_len=10, batch=14, K=2),
+    # 3H x H >= 2^20 updated in place over a contraction >= 512: the 128 x 256 tile form
+    "lm_nt_bf16_wide": wl.scaled(wl.CONFIGS["gru_lm"], vocab=300, embed=64, hidden=600, seq_len=32, batch=16, K=2),
     "cls_nt_bf16_c16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=40, hidden=96, classes=16, seq_len=3, batch=24, K=2),
     "cls_nt_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", layers=2, input=64, hidden=160, seq_len=4, batch=72, K=2),
     "gru_cls_bf16": wl.scaled(wl.CONFIGS["gru_cls"], prec="bf16", input=64, hidden=160, seq_len=4, batch=70, K=2),
