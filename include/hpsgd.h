@@ -244,6 +244,23 @@ int hpsgd_recurrence_info(const hpsgd_ctx *ctx, int *resident_layers, int *xproj
  * asynchronous schedule of Alg. 2 / Alg. 3 can be driven into rounds of several local steps. */
 int hpsgd_delay_us(unsigned microseconds, void *hip_stream);
 
+/* ---- the bf16 product of the local step, on its own --------------------------------------
+ * Every matrix product of the gradient computation (Alg. 2, the local training step) runs, in
+ * the bf16 configurations, as  C[g] = A[g] * B[g]^T  (M x N, fp32) for g < groups, or, where
+ * the product is a weight gradient, directly as the SGD update  C[g] = win[g] - lr * A[g] * B[g]^T
+ * (win != NULL; win may be C).  This entry point runs that one kernel family on caller data.
+ * A: [M][Kd], B: [N][Kd], bf16 bit patterns (DEVICE), row pitches lda / ldb and group strides
+ * strideA / strideB in elements; C and win: fp32 (DEVICE), row pitch ldc, group strides strideC
+ * / strideWin in elements.  Products are exact, accumulation is fp32 in the order of k
+ * (v_mfma_f32_32x32x16_bf16).  form: 0 lets the library choose the tile by shape; 1 .. 4
+ * force 128 x 128, 128 x 256, 192 x 256, 256 x 256 (the results do not depend on the form).
+ * Asynchronous on hip_stream; the caller owns all buffers.
+ * HPSGD_EINVAL: null pointer, size < 1, Kd not a multiple of 8, form out of range;
+ * HPSGD_EALIGN: A or B not 16-byte aligned, or a pitch / stride of A or B not a multiple of 8. */
+int hpsgd_gemm_bf16_nt(const void *A, long lda, long strideA, const void *B, long ldb, long strideB,
+                       float *C, long ldc, long strideC, const float *win, long strideWin, float lr,
+                       int M, int N, int Kd, int groups, int form, void *hip_stream);
+
 /* ---- matrix-core rate probe (measurement aid, not part of the method) --------------------
  * Runs a loop of independent MFMAs with no memory traffic on every CU: `precision` picks
  * v_mfma_f32_32x32x16_bf16 (HPSGD_BF16_MFMA) or v_mfma_f32_32x32x2_f32 (HPSGD_FP32);

@@ -26,7 +26,7 @@ EXPORTS = [
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
-    "hpsgd_recurrence_info",
+    "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt",
 ]
 ROLE_COUNT = 14
 
@@ -85,6 +85,8 @@ def load_library():
     lib.hpsgd_commit_kernel_params.restype = sz
     lib.hpsgd_probe_mfma_rate.argtypes = [C.c_int, vp, C.c_int, vp, vp, vp]
     lib.hpsgd_delay_us.argtypes = [C.c_uint, vp]
+    lib.hpsgd_gemm_bf16_nt.argtypes = [vp, C.c_long, C.c_long, vp, C.c_long, C.c_long, vp, C.c_long, C.c_long, vp,
+                                       C.c_long, C.c_float, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, vp]
     lib.hpsgd_local_step_all_acc.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, sz, vp, vp]
     lib.hpsgd_merge_grad.argtypes = [vp, C.POINTER(vp), C.c_float, C.c_int, sz, vp]
     lib.hpsgd_strerror.argtypes = [C.c_int]
@@ -287,6 +289,21 @@ def probe_mfma_rate(prec, operands, iterations, result, sink, stream=None):
     operands: >= 16 KiB device tensor; result: float64[4]; sink: float32[256*256]."""
     _check(load_library().hpsgd_probe_mfma_rate(PREC[prec], _ptr(operands), int(iterations), _ptr(result),
                                                 _ptr(sink), _stream(stream)), "hpsgd_probe_mfma_rate")
+
+
+GEMM_FORMS = {"auto": 0, "128x128": 1, "128x256": 2, "192x256": 3, "256x256": 4}
+
+
+def gemm_bf16_nt(A, B, C_out, win=None, lr=0.0, form="auto", stream=None):
+    """C[g] = A[g] B[g]^T, or win[g] - lr * A[g] B[g]^T (argument marshalling only; see hpsgd_gemm_bf16_nt).
+    A: [G, M, Kd] and B: [G, N, Kd] torch.bfloat16, contiguous; C_out / win: [G, M, N] float32."""
+    G, M, Kd = A.shape
+    N = B.shape[1]
+    assert B.shape == (G, N, Kd) and C_out.shape == (G, M, N) and A.is_contiguous() and B.is_contiguous()
+    assert C_out.is_contiguous() and (win is None or (win.shape == C_out.shape and win.is_contiguous()))
+    _check(load_library().hpsgd_gemm_bf16_nt(_ptr(A), Kd, M * Kd, _ptr(B), Kd, N * Kd, _ptr(C_out), N, M * N,
+                                             _ptr(win) if win is not None else None, M * N, float(lr), M, N, Kd, G,
+                                             GEMM_FORMS[form], _stream(stream)), "hpsgd_gemm_bf16_nt")
 
 
 def delay_us(microseconds, stream=None):

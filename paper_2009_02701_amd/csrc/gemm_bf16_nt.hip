@@ -393,20 +393,28 @@ struct DlxShape {
   static_assert((NT * 4) % BN == 0 && ER % (NT * 4 / BN) == 0 && ER % 32 == 0, "epilogue passes");
 };
 
+// Workgroup -> (group, tile): the list of all tiles, ordered by group, then by the dimension with
+// more tiles, is cut into 8 contiguous runs, one per XCD (workgroup i runs on XCD i % 8 and every
+// XCD has its own L2).  An XCD then works on few groups at a time (with 8 groups of up to 32
+// tiles: on one), whose operand panels are fetched into its L2 once and shared by its CUs; dealing
+// the tiles of every group out to all XCDs made each L2 fetch the panels of all groups.
 template <int BM, int BN>
 __device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_m, int& tile_n) {
-  // the same order as nt_tile: the dimension with more tiles is dealt out to the XCDs
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
-  const bool slow_is_n = tn >= tm;
-  const int ts = slow_is_n ? tn : tm, tf = slow_is_n ? tm : tn;
-  const int s8 = (ts + 7) >> 3;
-  const int c = blockIdx.x & 7, li = blockIdx.x >> 3;
-  const int f = li % tf, sl = (li / tf) % s8;
-  g = li / (tf * s8);
-  const int st = c + 8 * sl;
-  if (st >= ts) return false;
-  tile_m = slow_is_n ? f : st;
-  tile_n = slow_is_n ? st : f;
+  const int per_group = tm * tn, total = per_group * d.groups;
+  const int run = (total + 7) >> 3;
+  const int li = blockIdx.x >> 3;
+  const int v = (blockIdx.x & 7) * run + li;
+  if (li >= run || v >= total) return false;
+  g = v / per_group;
+  const int r = v - g * per_group;
+  if (tn >= tm) {
+    tile_n = r / tm;
+    tile_m = r - tile_n * tm;
+  } else {
+    tile_m = r / tn;
+    tile_n = r - tile_m * tn;
+  }
   return true;
 }
 
@@ -416,7 +424,8 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
   using Sh = DlxShape<WGM, WGN, TM, TN, S>;
   constexpr int BM = Sh::BM, BN = Sh::BN, IPW = Sh::IPW, CP = Sh::CP, NT = Sh::NT;
   extern __shared__ __attribute__((aligned(16))) unsigned char nt_smem[];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // in a scalar register: LDS addresses of the loader stay scalar
   const int wm = wave % WGM, wn = wave / WGM;
   const int lrow = lane & 31, lk = lane >> 5;
   int g, tile_m, tile_n;
@@ -437,10 +446,16 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
   const __bf16* zero = reinterpret_cast<const __bf16*>(nt_zero16);
   auto issue = [&](int stage, int kt) {
     unsigned char* sa = nt_smem + stage * Sh::STAGE + wave * IPW * 1024;
+    if ((kt + 1) * NBK <= d.Kd) {  // (uniform) a whole tile: no per-lane checks
 #pragma unroll
-    for (int i = 0; i < IPW; ++i) {
-      const bool ok = kt * NBK + kofs[i] < d.Kd;  // Kd is a multiple of 8: a chunk is all in or all out
-      __builtin_amdgcn_global_load_lds(HPSGD_GPTR(ok ? gp[i] + kt * NBK : zero), HPSGD_LPTR(sa + i * 1024), 16, 0, 0);
+      for (int i = 0; i < IPW; ++i)
+        __builtin_amdgcn_global_load_lds(HPSGD_GPTR(gp[i] + kt * NBK), HPSGD_LPTR(sa + i * 1024), 16, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < IPW; ++i) {
+        const bool ok = kt * NBK + kofs[i] < d.Kd;  // Kd is a multiple of 8: a chunk is all in or all out
+        __builtin_amdgcn_global_load_lds(HPSGD_GPTR(ok ? gp[i] + kt * NBK : zero), HPSGD_LPTR(sa + i * 1024), 16, 0, 0);
+      }
     }
   };
   floatx16 acc[TM][TN];
@@ -451,26 +466,30 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
   // operand fragments: row r, chunk c = 2 ks + lk at byte r * 128 + ((c ^ ((r >> 1) & 7)) << 4)
-  int ra[TM], swa[TM], rb[TN], swb[TN];
+  // (a wave's row blocks are 32 rows = 4096 bytes apart and share the swizzle: one address per
+  // operand and step, the blocks by immediate offsets)
+  unsigned oa[4], ob[4];
+  {
+    const int sw = (lrow >> 1) & 7;
 #pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int r = (wm * TM + i) * 32 + lrow;
-    ra[i] = r * 128;
-    swa[i] = (r >> 1) & 7;
-  }
-#pragma unroll
-  for (int j = 0; j < TN; ++j) {
-    const int r = (wn * TN + j) * 32 + lrow;
-    rb[j] = (BM + r) * 128;
-    swb[j] = (r >> 1) & 7;
+    for (int ks = 0; ks < 4; ++ks) {
+      oa[ks] = (wm * TM * 32 + lrow) * 128 + (((2 * ks + lk) ^ sw) << 4);
+      ob[ks] = (BM + wn * TN * 32 + lrow) * 128 + (((2 * ks + lk) ^ sw) << 4);
+    }
   }
   const int nk = (d.Kd + NBK - 1) / NBK;
+  // The fragment reads and the waits for them are written out (ds_read_b128 / s_waitcnt): the
+  // compiler's own waits are for all outstanding LDS reads at once, which would make every step
+  // wait for the reads issued for the next one.  LDS returns reads in order, so "all but the
+  // newest TM + TN" is exactly the older step's set.
   bf16x8 fa[2][TM], fb[2][TN];
-  auto fragments = [&](const unsigned char* sb, int ks, bf16x8(&fa_)[TM], bf16x8(&fb_)[TN]) {
+  const unsigned lds0 = (unsigned)(uintptr_t)HPSGD_LPTR(nt_smem);
+  auto fragments = [&](unsigned sb, int ks, bf16x8(&fa_)[TM], bf16x8(&fb_)[TN]) {
+    const unsigned aa = sb + oa[ks], ab = sb + ob[ks];
 #pragma unroll
-    for (int i = 0; i < TM; ++i) fa_[i] = *reinterpret_cast<const bf16x8*>(sb + ra[i] + (((2 * ks + lk) ^ swa[i]) << 4));
+    for (int i = 0; i < TM; ++i) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(fa_[i]) : "v"(aa), "n"(i * 4096));
 #pragma unroll
-    for (int j = 0; j < TN; ++j) fb_[j] = *reinterpret_cast<const bf16x8*>(sb + rb[j] + (((2 * ks + lk) ^ swb[j]) << 4));
+    for (int j = 0; j < TN; ++j) asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(fb_[j]) : "v"(ab), "n"(j * 4096));
   };
   auto mfmas = [&](const bf16x8(&fa_)[TM], const bf16x8(&fb_)[TN]) {
 #pragma unroll
@@ -487,23 +506,29 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((S - 2) * IPW) : "memory");
   __builtin_amdgcn_s_barrier();  // tile 0 is in LDS
   issue(S - 1, S - 1);
-  fragments(nt_smem, 0, fa[0], fb[0]);
+  fragments(lds0, 0, fa[0], fb[0]);
   int stage = 0;
   for (int kt = 0; kt < nk; ++kt) {
-    const unsigned char* sb = nt_smem + stage * Sh::STAGE;
+    const unsigned sb = lds0 + stage * Sh::STAGE;
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
       fragments(sb, ks + 1, fa[(ks + 1) & 1], fb[(ks + 1) & 1]);
+      asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(TM + TN) : "memory");  // step ks has landed
+      __builtin_amdgcn_sched_barrier(0);
       mfmas(fa[ks & 1], fb[ks & 1]);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // this wave's reads of tile kt are complete, its loads of tile kt+1 have landed ...
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((S - 2) * IPW) : "memory");
     __builtin_amdgcn_s_barrier();  // ... and so are and have everyone's
     issue(stage, kt + S);          // into the buffer tile kt has left
     stage = stage + 1 == S ? 0 : stage + 1;
-    fragments(nt_smem + stage * Sh::STAGE, 0, fa[0], fb[0]);
+    fragments(lds0 + stage * Sh::STAGE, 0, fa[0], fb[0]);
+    __builtin_amdgcn_sched_barrier(0);
     mfmas(fa[1], fb[1]);
+    __builtin_amdgcn_sched_barrier(0);
   }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");  // the reads issued for the tile after the last
   // the zero loads of the tiles beyond the contraction must have landed before the operand
   // buffers become the epilogue tile
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -586,12 +611,15 @@ hipError_t launch_dlx(const GemmNtDesc& d, hipStream_t s) {
     ready = true;
   }
   const int tm = (d.M + Sh::BM - 1) / Sh::BM, tn = (d.N + Sh::BN - 1) / Sh::BN;
-  const int ts = tn >= tm ? tn : tm, tf = tn >= tm ? tm : tn;
-  hipLaunchKernelGGL((gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>), dim3(8 * ((ts + 7) / 8) * tf * d.groups),
+  const int total = tm * tn * d.groups;
+  hipLaunchKernelGGL((gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>), dim3(8 * ((total + 7) / 8)),
                      dim3(Sh::NT), Sh::LDS, s, d);
   return hipGetLastError();
 }
 
+// form: 0 picks the kernel; for two bf16 operands 1 .. 4 force the 128 x 128, 128 x 256, 192 x 256
+// or 256 x 256 tile (every form computes every element with the same sequence of MFMAs: the
+// results do not depend on it).
 // a_bf16 / b_bf16: the operand is stored as bf16 (else fp32).  Leading dimensions and group
 // strides are in elements of the operand's own type.  Requires 16-byte aligned bases, row
 // pitches and group strides that are multiples of 16 bytes, and Kd a multiple of 8
@@ -604,8 +632,9 @@ bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, in
 hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
                                long ldb, long sB, float* C, long ldc, long sC, const float* bias,
                                long sBias, const float* win, long sWin, float lr, int M, int N, int Kd,
-                               int groups, hipStream_t s) {
+                               int groups, hipStream_t s, int form) {
   if (M <= 0 || N <= 0 || groups <= 0) return hipSuccess;
+  if (form < 0 || form > 4 || (form > 1 && !(a_bf16 && b_bf16))) return hipErrorInvalidValue;
   GemmNtDesc d;
   d.A = A; d.lda = lda; d.strideA = sA;
   d.B = B; d.ldb = ldb; d.strideB = sB;
@@ -649,23 +678,34 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
     }                                                                                             \
     hipLaunchKernelGGL((gemm_bf16_dl_kernel<CM>), grid, block, dl_smem, s, d);                    \
   } while (0)
-    // Which tile: one 8-wave workgroup per CU with a 256 x 256 tile does more matrix work per
-    // byte through LDS and per byte fetched, but nothing overlaps its epilogue and its first
-    // loads; two independent 128 x 128 workgroups per CU cover each other's.  Measured on the
-    // shapes of the GRU language model (K = 8 groups): the large tile wins where the contraction is
-    // long (>= 2560: 346 against 507 us at Kd = 10000) or where a large output is updated in place
-    // (the head's weight gradient: 338 against 402 us); a 128 x 256 tile wins for the smaller
-    // in-place updates (3072 x 1024: 98 against 105 us); the short contractions with plain
-    // outputs stay with the small tile (input projection: 85 against 94 .. 120 us).
-    const long out = (long)M * N;
-    if (Kd >= 2560 && M > 128 && N > 128) {
-      if (win) return launch_dlx<true, 2, 4, 4, 2, 2>(d, s);
-      return launch_dlx<false, 2, 4, 4, 2, 2>(d, s);
+    // Which tile.  One 8-wave workgroup per CU with a tile 256 wide does more matrix work per
+    // byte through LDS and per byte fetched, but nothing overlaps its first loads and its
+    // epilogue, which cost as much as about 8 k-tiles (12 with the in-place update); two
+    // independent 128 x 128 workgroups per CU cover each other's but need 1.3 times as long
+    // per k-tile.  The estimate below (rounds of 256 CUs x rows of the tile x k-tiles incl. the
+    // fixed part) reproduces the measured order of the forms on the shapes of the GRU language
+    // model, e.g. head dX (1120 x 1024 x 10000, 8 groups): 192 rows 314 us, 256 rows 312, 128 x 128
+    // 507; recurrent weight gradient (3072 x 1024 x 1120, in place): 91 / 107 / 104; first
+    // layer's input projection (1120 x 3072 x 256): 46 / 42 / 36.
+    if (form == 0) {
+      const double nk = (Kd + NBK - 1) / NBK;
+      const double fixed = win ? 12.0 : 8.0;
+      auto rounds = [&](int bm, int bn, int slots) {
+        const long t = (long)((M + bm - 1) / bm) * ((N + bn - 1) / bn) * groups;
+        return (double)((t + slots - 1) / slots);
+      };
+      double best = rounds(128, 128, 512) * 128 * (1.3 * nk + (win ? 8.0 : 6.0));
+      form = 1;
+      const double c128 = rounds(128, 256, 256) * 128 * 1.12 * (nk + fixed);
+      const double c192 = rounds(192, 256, 256) * 192 * (nk + fixed);
+      const double c256 = rounds(256, 256, 256) * 256 * (nk + fixed);
+      if (c128 < best) { best = c128; form = 2; }
+      if (c192 < best) { best = c192; form = 3; }
+      if (c256 < best) { best = c256; form = 4; }
     }
-    if (win && M > 128 && N > 128 && Kd >= 512) {
-      if (out >= (8L << 20)) return launch_dlx<true, 2, 4, 4, 2, 2>(d, s);
-      if (out >= (1L << 20)) return launch_dlx<true, 2, 4, 2, 2, 3>(d, s);
-    }
+    if (form == 2) return win ? launch_dlx<true, 2, 4, 2, 2, 3>(d, s) : launch_dlx<false, 2, 4, 2, 2, 3>(d, s);
+    if (form == 3) return win ? launch_dlx<true, 2, 4, 3, 2, 2>(d, s) : launch_dlx<false, 2, 4, 3, 2, 2>(d, s);
+    if (form == 4) return win ? launch_dlx<true, 2, 4, 4, 2, 2>(d, s) : launch_dlx<false, 2, 4, 4, 2, 2>(d, s);
     if (win) HPSGD_DL(true);
     else HPSGD_DL(false);
 #undef HPSGD_DL

@@ -1200,6 +1200,20 @@ int hpsgd_recurrence_info(const hpsgd_ctx* ctx, int* resident_layers, int* xproj
   return HPSGD_OK;
 }
 
+int hpsgd_gemm_bf16_nt(const void* A, long lda, long strideA, const void* B, long ldb, long strideB, float* C,
+                       long ldc, long strideC, const float* win, long strideWin, float lr, int M, int N, int Kd,
+                       int groups, int form, void* hip_stream) {
+  if (!A || !B || !C || M < 1 || N < 1 || Kd < 8 || Kd % 8 != 0 || groups < 1 || form < 0 || form > 4)
+    return HPSGD_EINVAL;
+  if (lda < Kd || ldb < Kd || ldc < N) return HPSGD_EINVAL;
+  if (!gemm_bf16_nt_supported(A, 1, lda, strideA, Kd) || !gemm_bf16_nt_supported(B, 1, ldb, strideB, Kd))
+    return HPSGD_EALIGN;
+  return launch_gemm_bf16_nt(A, 1, lda, strideA, B, 1, ldb, strideB, C, ldc, strideC, nullptr, 0, win, strideWin, lr,
+                             M, N, Kd, groups, (hipStream_t)hip_stream, form) == hipSuccess
+             ? HPSGD_OK
+             : HPSGD_EHIP;
+}
+
 int hpsgd_probe_mfma_rate(int precision, const void* operands, int iterations, double* result, float* sink,
                           void* hip_stream) {
   if (!operands || !result || !sink || iterations < 1) return HPSGD_EINVAL;

@@ -188,7 +188,7 @@ bool gemm_bf16_nt_supported(const void* p, int is_bf16, long ld, long stride, in
 hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, const void* B, int b_bf16,
                                long ldb, long sB, float* C, long ldc, long sC, const float* bias,
                                long sBias, const float* win, long sWin, float lr, int M, int N, int Kd,
-                               int groups, hipStream_t s);
+                               int groups, hipStream_t s, int form = 0);
 // out[c][r] = in[r][c], R x C per group
 hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
                             int groups, hipStream_t s);
