@@ -151,16 +151,128 @@ softmax_ce_bf16_kernel(const float* __restrict__ logits, long s_logits, const in
   }
 }
 
+// The same for SMR consecutive rows per workgroup, which also sums the unrounded gradient of its
+// rows per column (a thread owns the same columns in every row): colpart[g][block][c], the
+// partial sums of the head's bias gradient, added up by a second small kernel.  The next row's
+// loads are issued before the current row is reduced.
+constexpr int SMR = 8;
+
+template <int V4>
+__global__ void __launch_bounds__(256)
+softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, const int32_t* __restrict__ y,
+                            long s_y, __bf16* __restrict__ dlog, long ld_d, long s_d,
+                            float* __restrict__ rowloss, long s_rowloss, float2* __restrict__ rowstat,
+                            long s_rowstat, float* __restrict__ colpart, long s_colpart, int N, int C) {
+  __shared__ float red[4];
+  __shared__ float bcast;
+  const int g = blockIdx.y, row0 = blockIdx.x * SMR;
+  const int nr = min(SMR, N - row0);
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float inv_n = 1.0f / (float)N;
+  float4 acc[V4], nx[V4];
+#pragma unroll
+  for (int i = 0; i < V4; ++i) acc[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  auto load_row = [&](int row) {
+    const float* lr = logits + g * s_logits + (long)row * C;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int c = 4 * (tid + 256 * i);
+      nx[i] = *reinterpret_cast<const float4*>(lr + (c < C ? c : 0));
+    }
+  };
+  load_row(row0);
+  for (int r = 0; r < nr; ++r) {
+    const int row = row0 + r;
+    const int label = y[g * s_y + row];
+    float4 v[V4];
+    float m = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      v[i] = nx[i];
+      if (4 * (tid + 256 * i) < C) m = fmaxf(fmaxf(m, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+    }
+    if (r + 1 < nr) load_row(row + 1);
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+    if (lane == 0) red[wave] = m;
+    __syncthreads();
+    if (tid == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    __syncthreads();
+    m = bcast;
+    __syncthreads();
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < V4; ++i)
+      if (4 * (tid + 256 * i) < C) {
+        v[i].x = expf(v[i].x - m); v[i].y = expf(v[i].y - m);
+        v[i].z = expf(v[i].z - m); v[i].w = expf(v[i].w - m);
+        sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+      }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
+    if (lane == 0) red[wave] = sum;
+    __syncthreads();
+    if (tid == 0) bcast = (red[0] + red[1]) + (red[2] + red[3]);
+    __syncthreads();
+    sum = bcast;
+    __syncthreads();
+    const float inv_sum = 1.0f / sum;
+    if (tid == 0) {
+      rowloss[g * s_rowloss + row] = -((logits[g * s_logits + (long)row * C + label] - m) - logf(sum));
+      rowstat[g * s_rowstat + row] = make_float2(m, inv_sum);
+    }
+    __bf16* dr = dlog + g * s_d + (long)row * ld_d;
+#pragma unroll
+    for (int i = 0; i < V4; ++i) {
+      const int c = 4 * (tid + 256 * i);
+      if (c < C) {
+        const float4 d4 = make_float4((v[i].x * inv_sum - (c + 0 == label ? 1.0f : 0.0f)) * inv_n,
+                                      (v[i].y * inv_sum - (c + 1 == label ? 1.0f : 0.0f)) * inv_n,
+                                      (v[i].z * inv_sum - (c + 2 == label ? 1.0f : 0.0f)) * inv_n,
+                                      (v[i].w * inv_sum - (c + 3 == label ? 1.0f : 0.0f)) * inv_n);
+        acc[i].x += d4.x; acc[i].y += d4.y; acc[i].z += d4.z; acc[i].w += d4.w;
+        bf16x4 o;
+        o[0] = (__bf16)d4.x; o[1] = (__bf16)d4.y; o[2] = (__bf16)d4.z; o[3] = (__bf16)d4.w;
+        *reinterpret_cast<bf16x4*>(dr + c) = o;
+      }
+    }
+  }
+  float* cp = colpart + g * s_colpart + (long)blockIdx.x * C;
+#pragma unroll
+  for (int i = 0; i < V4; ++i) {
+    const int c = 4 * (tid + 256 * i);
+    if (c < C) *reinterpret_cast<float4*>(cp + c) = acc[i];
+  }
+}
+
+int softmax_ce_bf16_row_blocks(int N) { return (N + SMR - 1) / SMR; }
+
 bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* dlog, long ld_d, long s_d,
                                int C) {
   return C % 4 == 0 && C >= 4 && C <= 1024 * 10 && ((uintptr_t)logits & 15) == 0 && s_logits % 4 == 0 &&
          ((uintptr_t)dlog & 7) == 0 && ld_d % 4 == 0 && s_d % 4 == 0;
 }
 
+// colpart (nullable): [groups][softmax_ce_bf16_row_blocks(N)][C] floats (group stride s_colpart, a
+// multiple of 4, 16-byte aligned), receives the per-block column sums of the unrounded gradient.
 hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
                                   long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
-                                  long s_rowstat, int N, int C, int groups, hipStream_t s) {
+                                  long s_rowstat, int N, int C, int groups, hipStream_t s, float* colpart,
+                                  long s_colpart) {
   if (!softmax_ce_bf16_supported(logits, s_logits, dlog, ld_d, s_d, C)) return hipErrorInvalidValue;
+  if (colpart) {
+    if (((uintptr_t)colpart & 15) != 0 || s_colpart % 4 != 0) return hipErrorInvalidValue;
+    dim3 grid(softmax_ce_bf16_row_blocks(N), groups);
+#define HPSGD_SMR(V4)                                                                                        \
+  hipLaunchKernelGGL(softmax_ce_bf16_rows_kernel<V4>, grid, dim3(256), 0, s, logits, s_logits, y, s_y,       \
+                     (__bf16*)dlog, ld_d, s_d, rowloss, s_rowloss, reinterpret_cast<float2*>(rowstat),       \
+                     s_rowstat / 2, colpart, s_colpart, N, C)
+    if (C <= 1024) HPSGD_SMR(1);
+    else if (C <= 4096) HPSGD_SMR(4);
+    else HPSGD_SMR(10);
+#undef HPSGD_SMR
+    return hipGetLastError();
+  }
   dim3 grid(N, groups);
 #define HPSGD_SM(V4)                                                                                    \
   hipLaunchKernelGGL(softmax_ce_bf16_kernel<V4>, grid, dim3(256), 0, s, logits, s_logits, y, s_y,       \

@@ -46,6 +46,7 @@ struct hpsgd_ctx {
   Region dgxT, dghT, xT, dlogT, wihT, woT;
   Region xb, wihb, wob, dlogb;  // row-major bf16 copies: layer-0 input, W_ih, head.W, dlogits
   Region rowstat;               // per logits row: (max, 1 / sum of exponentials)
+  Region colpart;               // per block of logits rows: column sums of the logit gradient
   std::vector<Region> hsT;
   std::vector<Region> whhT, wihTl;  // per layer: transposed bf16 W_hh and W_ih, made in the forward pass
   std::vector<Region> hs, sv;   // per GRU layer
@@ -156,6 +157,7 @@ int build_layout(hpsgd_ctx* c) {
       c->wob = c->alloc(((size_t)classes * H + 1) / 2);
       c->dlogb = c->alloc((nr * round_up(classes, 64) + 1) / 2);
       c->rowstat = c->alloc(2 * nr);
+      c->colpart = c->alloc(round_up((size_t)softmax_ce_bf16_row_blocks((int)nr) * classes, 4));
     }
     size_t wmax = H;
     if (lm && (size_t)d.embed > wmax) wmax = d.embed;
@@ -584,9 +586,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
                 s_log, EPI_BIAS, rin + ob, sR, va, vb));
       role = HPSGD_ROLE_LOSS;
+      // the head's bias gradient: column sums of the unrounded logit gradient, per block of rows
+      // in the loss kernel, added up below (else recomputed from the logits in a pass of its own)
+      // (the partial sums of the groups lie back to back, as the adding kernel reads them)
+      const long s_colpart = (long)softmax_ce_bf16_row_blocks(nrows) * classes;
+      const bool colsum_fused = (((uintptr_t)(grad + ob) | (uintptr_t)reg(c->colpart)) & 15) == 0 && sG % 4 == 0 &&
+                                s_colpart % 4 == 0 && (size_t)s_colpart <= c->colpart.stride;
       HIP_TRY(launch_softmax_ce_bf16(logits, s_log, y, nrows, bfreg(c->dlogb), clp, s_dlb, rowloss,
                                      (long)c->rowloss.stride, reg(c->rowstat), (long)c->rowstat.stride, nrows,
-                                     classes, groups, s));
+                                     classes, groups, s, colsum_fused ? reg(c->colpart) : nullptr, s_colpart));
       if (loss_out)
         HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
       role = HPSGD_ROLE_OTHER;
@@ -601,8 +609,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const WgradTarget wt = wgrad_target("head.W");
       TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
                 wt.epi, wt.aux, sR, vdT, vhT, lr));
-      HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
-                                    grad + ob, sG, nrows, classes, groups, s));
+      if (colsum_fused)
+        HIP_TRY(launch_reduce_parts(reg(c->colpart), softmax_ce_bf16_row_blocks(nrows), (size_t)classes, nullptr, 0,
+                                    grad + ob, (size_t)sG, 0.f, 0, groups, s));
+      else
+        HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
+                                      grad + ob, sG, nrows, classes, groups, s));
     } else if (!bf && !lm && cls_head_supported(nrows, classes, H)) {
       // a classifier head with few classes: forward and loss in one small launch, the three
       // gradients and the update (or the gradients, when they are accumulated as well) in another

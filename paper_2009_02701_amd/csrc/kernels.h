@@ -170,7 +170,9 @@ bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* d
 // rowstat: per row (max logit, 1 / sum of exponentials), two floats (group stride s_rowstat floats, even)
 hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
                                   long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
-                                  long s_rowstat, int N, int C, int groups, hipStream_t s);
+                                  long s_rowstat, int N, int C, int groups, hipStream_t s, float* colpart = nullptr,
+                                  long s_colpart = 0);
+int softmax_ce_bf16_row_blocks(int N);
 // out[c] = mean over rows of (softmax - onehot), from the logits and the rows' rowstat pairs
 hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
                                  const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
