@@ -220,7 +220,8 @@ def main():
     compare = {"sync_delay_us": delay, "local_steps": 64, "unit": unit}
     for name, run in (("ssgd_blocking", lambda: tr.s_seq(lr, 1, 64, record_loss=False, sync_delay_us=delay)),
                       ("local_sgd_gamma8_blocking", lambda: tr.s_seq(lr, 8, 8, record_loss=False, sync_delay_us=delay)),
-                      ("hpsgd_async", lambda: tr.s_async(lr, 64, sync_delay_us=delay))):
+                      ("hpsgd_async", lambda: tr.s_async(lr, 64, sync_delay_us=delay)),
+                      ("psgd_no_sync", lambda: tr.s_psgd(lr, 64, record_loss=False))):
         torch.cuda.synchronize()
         c0 = time.perf_counter()
         run()

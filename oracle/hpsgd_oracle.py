@@ -297,6 +297,21 @@ def s_seq(init, batch_fn, K, lr, gamma, rounds, step_fn=None):
     return G, losses
 
 
+def s_psgd(init, batch_fn, K, lr, steps):
+    """Purely offline training (Sec. 4.1, "Methods": the reference for training speed): every
+    worker starts from the initial model and takes `steps` local steps on its own batches; nothing
+    is ever exchanged.  Returns (the K local models, losses[step][worker])."""
+    R = [sync(_f64(init)) for _ in range(K)]
+    losses = []
+    for step in range(steps):
+        row = []
+        for k in range(K):
+            R[k], loss = local_step(R[k], *batch_fn(k, step), lr)
+            row.append(loss)
+        losses.append(row)
+    return R, losses
+
+
 def s_seq_grad(init, batch_fn, K, lr, gamma, rounds):
     """s_seq with the synchronisation in gradient form (what Alg. 2 / Alg. 3 put on the wire):
     every worker accumulates its gradients over the round, the global model is updated with

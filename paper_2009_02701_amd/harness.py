@@ -126,6 +126,20 @@ class Trainer:
             self.merge(0, st)
         st.synchronize()
 
+    def s_psgd(self, lr: float, steps: int, record_loss=True):
+        """Purely offline training (Sec. 4.1): local steps only, after one initial sync; the K
+        replicas never meet.  The reference for the time the training itself takes."""
+        st = self.stream_a
+        st.wait_stream(torch.cuda.current_stream())
+        self.sync_all(0, st)
+        for step in range(steps):
+            self.gather(step, st)
+            self.local_step(0, lr, st)
+            if record_loss:
+                with torch.cuda.stream(st):
+                    self.losses.append(self.loss.clone())
+        st.synchronize()
+
     def s_ovl(self, lr: float, rounds: int, record_loss=True, single_stream=False):
         """Overlapped schedule; with single_stream=True the same op list runs on one stream."""
         self.ovl_begin(single_stream)

@@ -159,6 +159,32 @@ def test_config1_tiny_gru_schedules(sched):
     _schedule_parity(wl.CONFIGS["tiny_gru"], sched[0], TOL_FP32, **sched[1])
 
 
+@pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "mlp_tiles"])
+def test_offline_training_keeps_workers_apart(name):
+    """Sec. 4.1's PSGD reference: local steps only; every worker's model against the oracle's.
+    (The MLP at a reduced size: among the 4 million pre-activations of the full one a few lie
+    within fp32 rounding of zero, and a flipped ReLU mask moves one worker's model by more than
+    the tolerance when no averaging over workers follows.)"""
+    cfg = SMALL[name] if name in SMALL else wl.CONFIGS[name]
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.s_psgd(cfg["lr"], 3)
+    want, losses = oc.s_psgd(init, batch_fn, cfg["K"], cfg["lr"], 3)
+    for k in range(cfg["K"]):
+        got = tr.replica_params(0, k)
+        err, worst, errs = worst_rel_err(got, want[k])
+        assert err <= TOL_FP32, (k, worst, errs)
+        delta_got = {n: got[n].astype(np.float64) - init[n] for n in init}
+        delta_want = {n: want[k][n] - init[n].astype(np.float64) for n in init}
+        derr, dworst, derrs = worst_rel_err(delta_got, delta_want)
+        assert derr <= max(50 * TOL_FP32, 5e-3), (k, dworst, derrs)
+    # the global model was never touched
+    g = tr.global_params()
+    assert all(np.array_equal(g[n], init[n]) for n in init)
+    gl = np.stack([l.cpu().numpy() for l in tr.losses])
+    assert rel_err(gl, np.asarray(losses)) <= TOL_FP32
+
+
 @pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "mlp"])
 def test_gradient_form_synchronisation(name):
     """Eq. 1 as printed: accumulated gradients (hpsgd_local_step_all_acc) and hpsgd_merge_grad

@@ -136,6 +136,28 @@ def test_sseq_single_worker_is_plain_sgd():
     _close(G, W)
 
 
+def test_psgd_is_plain_sgd_per_worker_and_averages_to_one_long_local_sgd_round():
+    """Sec. 4.1's offline reference: worker i follows w <- w - lr * grad on its own batches (the
+    update written out here), and since Local SGD only averages at a round's end, the mean of the
+    offline models is Local SGD with one round of gamma = steps."""
+    bf = _batch_fn(CFG)
+    init = wl.init_params(CFG)
+    K, lr, steps = CFG["K"], CFG["lr"], 4
+    R, losses = oc.s_psgd(init, bf, K, lr, steps)
+    assert len(R) == K and len(losses) == steps and len(losses[0]) == K
+    for i in range(K):
+        w = {k: v.astype(np.float64) for k, v in init.items()}
+        for e in range(steps):
+            loss, g = oc.loss_and_grads(w, *bf(i, e))
+            assert abs(loss - losses[e][i]) <= 1e-12 * abs(loss)
+            w = {k: w[k] - lr * g[k] for k in g}
+        _close(R[i], w)
+    G, _ = oc.s_seq(init, bf, K, lr, gamma=steps, rounds=1)
+    _close(G, {k: sum(R[i][k] for i in range(K)) / K for k in init})
+    # workers with different batches end up apart
+    assert any(np.abs(R[0][k] - R[1][k]).max() > 0 for k in init)
+
+
 def test_sovl_first_round_applies_nothing_and_update_is_one_round_late():
     """Alg. 3's guard: nothing is applied before the first all-reduce exists; afterwards the
     global model lags the local training by one synchronisation."""
