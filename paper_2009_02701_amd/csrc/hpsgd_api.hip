@@ -424,9 +424,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     unsigned pbase = 0;
     if (use_persist || use_persist_b) {
       TRY(order_resident_launches(s));
-      const size_t nw = gru_persist_sync_words(B, groups);
-      HIP_TRY(launch_fill_zero((float*)psync, nw, nw, 1, s));
-      abort_word = psync;
+      abort_word = psync;  // (cleared together with the first layer's h_0 below)
     }
     // ---- forward
     const float* lin = (const float*)x;
@@ -447,7 +445,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
       role = HPSGD_ROLE_OTHER;
-      HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s));
+      HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s, l == 0 ? (float*)psync : nullptr,
+                               l == 0 && psync ? gru_persist_sync_words(B, groups) : 0));
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
@@ -690,6 +689,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
       const int win = l > 0 ? H : (lm ? d.embed : d.input);
+      ReducePack rp;
+      rp.n = 0;
+      rp.blk0[0] = 0;
+      rp.lr = lr;
+      // queued for the layer's one adding launch; a segment that launch cannot take runs by itself
+      auto queue_reduce = [&](const float* parts, int n_parts, size_t n, const float* in, size_t s_in, float* out,
+                              size_t s_out, int commit) -> int {
+        if (reduce_pack_push(rp, parts, n_parts, n, in, s_in, out, s_out, commit)) return HPSGD_OK;
+        return launch_reduce_parts(parts, n_parts, n, in, s_in, out, s_out, lr, commit, groups, s) == hipSuccess
+                   ? HPSGD_OK
+                   : HPSGD_EHIP;
+      };
       const float* layer_in;
       long s_layer_in;
       if (l > 0) {
@@ -875,18 +886,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           float* parts = reg(c->dwip);
           TRY(gemm(s, groups, 0, 3 * H, win, TB / kWihSplits, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
                    parts, win, (long)n_wih, EPI_STORE, nullptr, 0, 0, 0.f, kWihSplits));
-          TimerScope ts_(c, role, s);
-          HIP_TRY(launch_reduce_parts(parts, kWihSplits, n_wih, wi.aux, (size_t)sR, wi.C, (size_t)wi.sC, lr,
-                                      wi.epi == EPI_COMMIT, groups, s));
+          TRY0(queue_reduce(parts, kWihSplits, n_wih, wi.aux, (size_t)sR, wi.C, (size_t)wi.sC, wi.epi == EPI_COMMIT));
         } else {
           TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
                     wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
         }
         const WgradTarget wh = wgrad_target(p + ".W_hh");
         if (dwp) {
-          TimerScope ts_(c, role, s);
-          HIP_TRY(launch_reduce_parts(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sR, wh.C, (size_t)wh.sC,
-                                      lr, wh.epi == EPI_COMMIT, groups, s));
+          TRY0(queue_reduce(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sR, wh.C, (size_t)wh.sC,
+                           wh.epi == EPI_COMMIT));
         } else {
           TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
                     wh.aux, sR, v_dghT, v_hsT, lr, persist_b));
@@ -900,16 +908,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (!acc && (sR & 3) == 0 && ((uintptr_t)(rin + ob_ih) & 15) == 0 && ((uintptr_t)(rout + ob_ih) & 15) == 0) {
           fused_commit[c->find(p + ".b_ih")] = 1;
           fused_commit[c->find(p + ".b_hh")] = 1;
-          HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sR, rout + ob_ih,
-                                      (size_t)sR, lr, 1, groups, s));
+          TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sR, rout + ob_ih, (size_t)sR, 1));
         } else {
-          HIP_TRY(launch_reduce_parts(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + ob_ih, (size_t)sG, 0.f, 0,
-                                      groups, s));
+          TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + ob_ih, (size_t)sG, 0));
         }
       } else {
         HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
         HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
       }
+      // the layer's sums of partial results (weight gradients of the resident-weight launch and
+      // of the split contraction, bias gradients), with their updates: one launch
+      HIP_TRY(launch_reduce_pack(rp, groups, s));
       role = HPSGD_ROLE_OTHER;
       if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
     }

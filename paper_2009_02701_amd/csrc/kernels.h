@@ -24,7 +24,8 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
 hipError_t launch_commit_acc(const float* in, float* out, size_t stride, const float* grad, size_t grad_stride,
                              float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s);
 hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K, size_t P, hipStream_t s);
-hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s);
+hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s, float* extra = nullptr,
+                            size_t n_extra = 0);
 // p[g*stride + r*ld + c] = 0 for r < rows, c < cols (4-byte words)
 hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t stride, int groups,
                                hipStream_t s);
@@ -121,6 +122,23 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
 bool gru_persist_dw_supported(int H);
 // out[g][i] = in[g][i] - lr * sum_p parts[(g * n_parts + p)][i]  (commit != 0; in may be out)
 // out[g][i] = sum_p parts[(g * n_parts + p)][i]                   (commit == 0)
+// Up to MAXSEG sums of partial results in one launch: reduce_pack_push (false: the segment does
+// not meet the alignment rules of launch_reduce_parts or the pack is full; nothing is added),
+// then launch_reduce_pack.  pk.n = 0, pk.blk0[0] = 0 and pk.lr are set by the caller.
+struct ReduceSeg {
+  const float* parts; int n_parts; size_t n4;
+  const float* in; size_t s_in; float* out; size_t s_out; int commit;
+};
+struct ReducePack {
+  static constexpr int MAXSEG = 4;
+  ReduceSeg seg[MAXSEG];
+  unsigned blk0[MAXSEG + 1];
+  int n;
+  float lr;
+};
+bool reduce_pack_push(ReducePack& pk, const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
+                      float* out, size_t s_out, int commit);
+hipError_t launch_reduce_pack(const ReducePack& pk, int groups, hipStream_t s);
 hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
                                float* out, size_t s_out, float lr, int commit, int groups, hipStream_t s);
 // bf16 operands (strides of bf16 buffers in bf16 elements): hb / dghb hold all time steps and are the

@@ -200,6 +200,53 @@ reduce_parts_kernel(const float* __restrict__ parts, int n_parts, size_t n4, con
   }
 }
 
+// Several such sums in one launch (each of these kernels is a few microseconds of work behind
+// a launch): segment i owns the grid columns blk0[i] .. blk0[i+1]-1.
+__global__ void __launch_bounds__(kThreads) reduce_parts_multi_kernel(ReducePack pk) {
+  int sgi = 0;
+#pragma unroll
+  for (int i = 1; i < ReducePack::MAXSEG; ++i)
+    if (i < pk.n && blockIdx.x >= pk.blk0[i]) sgi = i;
+  const ReduceSeg& sg = pk.seg[sgi];
+  const size_t k = blockIdx.y, n4 = sg.n4;
+  const unsigned nblk = pk.blk0[sgi + 1] - pk.blk0[sgi];
+  const float4* pkp = reinterpret_cast<const float4*>(sg.parts) + k * sg.n_parts * n4;
+  for (size_t i = (size_t)(blockIdx.x - pk.blk0[sgi]) * kThreads + threadIdx.x; i < n4; i += (size_t)nblk * kThreads) {
+    float4 sum = pkp[i];
+    for (int p = 1; p < sg.n_parts; ++p) {
+      const float4 v = pkp[p * n4 + i];
+      sum.x += v.x;
+      sum.y += v.y;
+      sum.z += v.z;
+      sum.w += v.w;
+    }
+    if (sg.commit) {
+      const float4 w = reinterpret_cast<const float4*>(sg.in + k * sg.s_in)[i];
+      sum = make_float4(w.x - pk.lr * sum.x, w.y - pk.lr * sum.y, w.z - pk.lr * sum.z, w.w - pk.lr * sum.w);
+    }
+    reinterpret_cast<float4*>(sg.out + k * sg.s_out)[i] = sum;
+  }
+}
+
+bool reduce_pack_push(ReducePack& pk, const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
+                      float* out, size_t s_out, int commit) {
+  if (pk.n >= ReducePack::MAXSEG || n == 0 || n_parts < 1 || (n & 3) != 0 || ((uintptr_t)parts & 15) != 0 ||
+      ((uintptr_t)out & 15) != 0 || (s_out & 3) != 0 || (commit && (!in || ((uintptr_t)in & 15) != 0 || (s_in & 3) != 0)))
+    return false;
+  ReduceSeg& sg = pk.seg[pk.n];
+  sg.parts = parts; sg.n_parts = n_parts; sg.n4 = n / 4; sg.in = in; sg.s_in = s_in; sg.out = out; sg.s_out = s_out;
+  sg.commit = commit;
+  pk.blk0[pk.n + 1] = pk.blk0[pk.n] + (unsigned)onepass_blocks(n / 4);
+  ++pk.n;
+  return true;
+}
+
+hipError_t launch_reduce_pack(const ReducePack& pk, int groups, hipStream_t s) {
+  if (pk.n == 0 || groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(reduce_parts_multi_kernel, dim3(pk.blk0[pk.n], groups), dim3(kThreads), 0, s, pk);
+  return hipGetLastError();
+}
+
 hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
                                float* out, size_t s_out, float lr, int commit, int groups, hipStream_t s) {
   if (n == 0 || groups <= 0) return hipSuccess;
@@ -279,9 +326,16 @@ hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K
 }
 
 // ---------------------------------------------------------------------------- fill
-// p[g*stride + i] = 0 for i < n, g < groups
-__global__ void __launch_bounds__(kThreads) fill_zero_kernel(float* p, size_t n4, size_t n, size_t stride) {
+// p[g*stride + i] = 0 for i < n, g < groups; grid row `groups`, if launched, clears a second
+// range extra[0 .. n_extra) instead
+__global__ void __launch_bounds__(kThreads)
+fill_zero_kernel(float* p, size_t n4, size_t n, size_t stride, int groups, float* extra, size_t n_extra) {
   float* pg = p + (size_t)blockIdx.y * stride;
+  if ((int)blockIdx.y == groups) {
+    pg = extra;
+    n = n_extra;
+    n4 = n_extra / 4;
+  }
   const size_t step = (size_t)gridDim.x * kThreads;
   const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += step)
@@ -292,12 +346,21 @@ __global__ void __launch_bounds__(kThreads) fill_zero_kernel(float* p, size_t n4
   }
 }
 
-hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s) {
-  if (n == 0 || groups == 0) return hipSuccess;
+// extra (nullable, 16-byte aligned): a second range of n_extra floats cleared by the same launch
+hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s, float* extra,
+                            size_t n_extra) {
+  if (n == 0 || groups == 0) {
+    if (!extra || n_extra == 0) return hipSuccess;
+    return launch_fill_zero(extra, n_extra, n_extra, 1, s, nullptr, 0);
+  }
+  if (extra && ((uintptr_t)extra & 15) != 0) return hipErrorInvalidValue;
   const size_t n4 = n / 4;
-  int blocks = stream_blocks(n4);
-  if (blocks * groups > kMaxBlocks) blocks = (kMaxBlocks + groups - 1) / groups;
-  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks, groups), dim3(kThreads), 0, s, p, n4, n, stride);
+  const size_t big4 = (extra && n_extra / 4 > n4) ? n_extra / 4 : n4;
+  int blocks = stream_blocks(big4);
+  const int rows = groups + ((extra && n_extra) ? 1 : 0);
+  if (blocks * rows > kMaxBlocks) blocks = (kMaxBlocks + rows - 1) / rows;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3(blocks, rows), dim3(kThreads), 0, s, p, n4, n, stride, groups, extra,
+                     n_extra);
   return hipGetLastError();
 }
 
