@@ -50,21 +50,25 @@ cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
   const int rowc = min(row, N - 1);
   const float* Wg = W + g * s_in;
   const int nW = C * H;
-  batched_copy<8>((nW + 255) / 256, [&](int i) { return Wg[min(tid + 256 * i, nW - 1)]; },
-                  [&](int i, float v) {
-                    if (tid + 256 * i < nW) sW[tid + 256 * i] = v;
-                  });
   const float* fr = feats + g * s_feats + (long)rowc * H;
+  const int nk = (H - part + 31) / 32;  // this thread's share of the row: k = part + 32 i < H
+  // the first 8 values of the row are requested before W is copied, so that they arrive with it
+  float f[8];
+#pragma unroll
+  for (int u = 0; u < 8; ++u) f[u] = fr[part + 32 * min(u, nk - 1)];
+  batched_copy<24>((nW + 255) / 256, [&](int i) { return Wg[min(tid + 256 * i, nW - 1)]; },
+                   [&](int i, float v) {
+                     if (tid + 256 * i < nW) sW[tid + 256 * i] = v;
+                   });
   float acc[HMAXC];
 #pragma unroll
   for (int c = 0; c < HMAXC; ++c) acc[c] = 0.f;
-  // this thread's share of the row, 8 values at a time
-  const int nk = (H - part + 31) / 32;  // k = part + 32 i < H
   __syncthreads();
   for (int base = 0; base < nk; base += 8) {
-    float f[8];
+    if (base > 0) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) f[u] = fr[part + 32 * min(base + u, nk - 1)];
+      for (int u = 0; u < 8; ++u) f[u] = fr[part + 32 * min(base + u, nk - 1)];
+    }
 #pragma unroll
     for (int u = 0; u < 8; ++u)
       if (base + u < nk) {
@@ -122,14 +126,27 @@ cls_head_bwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
   const bool jv = j < H;
   const int jc = jv ? j : 0;
   const int nD = N * C;
-  batched_copy<4>((nD + 255) / 256, [&](int i) { return dlog[g * s_dlog + min(tid + 256 * i, nD - 1)]; },
-                  [&](int i, float v) {
-                    if (tid + 256 * i < nD) sD[tid + 256 * i] = v;
-                  });
-  batched_copy<8>((N - q + 3) / 4, [&](int i) { return feats[g * s_feats + (long)(q + 4 * i) * H + jc]; },
-                  [&](int i, float v) { sF[q + 4 * i][jl] = v; });
-  batched_copy<8>((C - q + 3) / 4, [&](int i) { return W_in[g * s_in + (long)(q + 4 * i) * H + jc]; },
-                  [&](int i, float v) { sW[q + 4 * i][jl] = v; });
+  // the slice of W (at most 8 values per thread) and the first 1024 logit gradients are requested
+  // first and stored last: they arrive while the features are copied
+  const int nWq = (C - q + 3) / 4;
+  float wv[HMAXC / 4], dv[4];
+#pragma unroll
+  for (int u = 0; u < HMAXC / 4; ++u) wv[u] = W_in[g * s_in + (long)min(q + 4 * u, C - 1) * H + jc];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) dv[u] = dlog[g * s_dlog + min(tid + 256 * u, nD - 1)];
+  batched_copy<16>((N - q + 3) / 4, [&](int i) { return feats[g * s_feats + (long)(q + 4 * i) * H + jc]; },
+                   [&](int i, float v) { sF[q + 4 * i][jl] = v; });
+#pragma unroll
+  for (int u = 0; u < HMAXC / 4; ++u)
+    if (u < nWq) sW[q + 4 * u][jl] = wv[u];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (tid + 256 * u < nD) sD[tid + 256 * u] = dv[u];
+  if (nD > 1024)
+    batched_copy<4>((nD - 1024 + 255) / 256, [&](int i) { return dlog[g * s_dlog + min(1024 + tid + 256 * i, nD - 1)]; },
+                    [&](int i, float v) {
+                      if (1024 + tid + 256 * i < nD) sD[1024 + tid + 256 * i] = v;
+                    });
   __syncthreads();
   for (int r = q; r < N; r += 4) {
     float a = 0.f;
