@@ -156,6 +156,30 @@ gemm_f32_fast_kernel(GemmDesc d) {
   b.load(0, 1, d.Kd, d.ldb, tid);
   a.load(1, 2, d.Kd, d.lda, tid);
   b.load(1, 2, d.Kd, d.ldb, tid);
+  // The epilogue's extra matrix operand in C's layout (the old C, the ReLU mask or the weights
+  // to update) is requested here, behind the first operand tiles: it arrives during the
+  // contraction instead of holding up the epilogue (a weight gradient over one batch is a few
+  // k-tiles of matrix work and as many bytes of weights to update as of operands).
+  float* C = d.C + (long)(splits > 1 ? gp : g) * d.strideC;
+  const float* aux = d.aux ? d.aux + (long)g * d.strideAux : nullptr;
+  constexpr int CP = BN + 4;                       // pitch in floats
+  constexpr int RPP = FTHREADS / (BN / 4);         // rows per pass
+  constexpr int PASSES = BM / RPP;
+  const int c4 = (tid % (BN / 4)) << 2, rbase = tid / (BN / 4);
+  const int col = n0 + c4;
+  const int epi = d.epilogue;
+  const float* X = epi == EPI_ACCUM ? C : (epi == EPI_RELU_MASK || epi == EPI_COMMIT) ? aux : nullptr;
+  const long xs = epi == EPI_ACCUM ? d.strideC : d.strideAux;
+  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
+                   (!X || (((uintptr_t)(epi == EPI_ACCUM ? d.C : d.aux) & 15) == 0 && (xs & 3) == 0));
+  float4 x[PASSES];
+  if (X && vec && col + 3 < d.N) {
+#pragma unroll
+    for (int p = 0; p < PASSES; ++p) {
+      const int row = min(m0 + rbase + RPP * p, d.M - 1);  // clamped: not stored when outside
+      x[p] = *reinterpret_cast<const float4*>(X + (long)row * d.ldc + col);
+    }
+  }
   __syncthreads();
   for (int kt = 0; kt < nk; kt += 2) {
     compute(0);                                   // tile kt
@@ -176,12 +200,7 @@ gemm_f32_fast_kernel(GemmDesc d) {
   // accumulators are laid out as the BM x BN tile, then every thread moves 16-byte pieces of
   // whole rows, so the stores and the loads of the extra operand (the old C, the ReLU mask or
   // the weights to update; all requested before the first is used) are fully coalesced.
-  float* C = d.C + (long)(splits > 1 ? gp : g) * d.strideC;
-  const float* aux = d.aux ? d.aux + (long)g * d.strideAux : nullptr;
   float* sC = fast_lds;
-  constexpr int CP = BN + 4;                       // pitch in floats
-  constexpr int RPP = FTHREADS / (BN / 4);         // rows per pass
-  constexpr int PASSES = BM / RPP;
   static_assert((size_t)BM * CP <= 2 * (OpA::LDS_FLOATS + OpB::LDS_FLOATS), "epilogue tile fits the operand buffers");
 #pragma unroll
   for (int j = 0; j < TN; ++j)
@@ -192,25 +211,9 @@ gemm_f32_fast_kernel(GemmDesc d) {
         sC[(wm * (BM / 2) + i * 32 + 8 * (v / 4) + 4 * lk + (v % 4)) * CP + wn * (BN / 2) + j * 32 + lrow] =
             acc[i][j][v];
   __syncthreads();
-  const int c4 = (tid % (BN / 4)) << 2, rbase = tid / (BN / 4);
-  const int col = n0 + c4;
-  const int epi = d.epilogue;
-  // the extra matrix operand, in C's layout
-  const float* X = epi == EPI_ACCUM ? C : (epi == EPI_RELU_MASK || epi == EPI_COMMIT) ? aux : nullptr;
-  const long xs = epi == EPI_ACCUM ? d.strideC : d.strideAux;
-  const bool vec = ((d.ldc | d.strideC) & 3) == 0 && ((uintptr_t)d.C & 15) == 0 &&
-                   (!X || (((uintptr_t)(epi == EPI_ACCUM ? d.C : d.aux) & 15) == 0 && (xs & 3) == 0));
   if (vec && col + 3 < d.N) {
     float4 bv = make_float4(0.f, 0.f, 0.f, 0.f);
     if (epi == EPI_BIAS || epi == EPI_BIAS_RELU) bv = make_float4(aux[col], aux[col + 1], aux[col + 2], aux[col + 3]);
-    float4 x[PASSES];
-    if (X) {
-#pragma unroll
-      for (int p = 0; p < PASSES; ++p) {
-        const int row = min(m0 + rbase + RPP * p, d.M - 1);  // clamped: not stored when outside
-        x[p] = *reinterpret_cast<const float4*>(X + (long)row * d.ldc + col);
-      }
-    }
 #pragma unroll
     for (int p = 0; p < PASSES; ++p) {
       const int rl = rbase + RPP * p, row = m0 + rl;
@@ -300,8 +303,11 @@ hipError_t launch_gemm_f32_fast(const GemmDesc& d, hipStream_t s) {
     return (long)((d.M + bm - 1) / bm) * ((d.N + bn - 1) / bn) * d.groups;
   };
   // 128 x 128 tiles from two full rounds of workgroups on: below that the smaller tiles' better
-  // balance over the CUs outweighs their extra LDS traffic (the fp32 matrix rate is low enough)
-  if (d.M > 64 && d.N > 64 && tiles(128, 128) >= 512) return launch_fast_layout<128, 128>(d, s);
+  // balance over the CUs outweighs their extra LDS traffic (the fp32 matrix rate is low enough).
+  // A contraction of a few k-tiles (a weight gradient over one batch) is mostly first loads and
+  // epilogue: four small workgroups per SIMD cover those better than two large ones (matrix
+  // pipes busy 52 % of the time with the large tile at Kd = 128)
+  if (d.M > 64 && d.N > 64 && tiles(128, 128) >= 512 && d.Kd > 256) return launch_fast_layout<128, 128>(d, s);
   return launch_fast_layout<64, 64>(d, s);
 }
 
