@@ -243,9 +243,12 @@ hipError_t launch_embed_fwd(const float* E, long s_E, const int32_t* tok, long s
 // it then adds, in increasing position, the rows of every position that holds v (thread c
 // owns column c).  No atomics: duplicate ids, frequent under a Zipf draw, cost the owner a
 // short serial loop instead of contention, and the order of the sum is fixed.
+// E_in != nullptr: the owner writes the updated row E_in[v] - lr * sum to dE[v] instead of the sum
+// (dE is then the embedding of the output replica; only the rows of tokens that occur are
+// touched, so for an update in place nothing else has to be read or written).
 __global__ void __launch_bounds__(kThreads)
 embed_bwd_kernel(const float* __restrict__ dx, long s_dx, const int32_t* __restrict__ tok,
-                 long s_tok, float* __restrict__ dE, long s_dE, int N, int Ew) {
+                 long s_tok, float* dE, long s_dE, int N, int Ew, const float* E_in, long s_E, float lr) {
   __shared__ int list[kThreads];  // positions of this chunk that hold v, ascending
   __shared__ int wcnt[kThreads / 64];
   const int g = blockIdx.y, i = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -289,14 +292,15 @@ embed_bwd_kernel(const float* __restrict__ dx, long s_dx, const int32_t* __restr
       }
       __syncthreads();
     }
-    if (cok) dst[c] = acc;
+    if (cok) dst[c] = E_in ? E_in[g * s_E + (long)v * Ew + c] - lr * acc : acc;
   }
 }
 
 hipError_t launch_embed_bwd(const float* dx, long s_dx, const int32_t* tok, long s_tok, float* dE,
-                            long s_dE, int N, int Ew, int groups, hipStream_t s) {
+                            long s_dE, int N, int Ew, int groups, hipStream_t s, const float* E_in, long s_E,
+                            float lr) {
   hipLaunchKernelGGL(embed_bwd_kernel, dim3(N, groups), dim3(kThreads), 0, s, dx, s_dx, tok, s_tok, dE,
-                     s_dE, N, Ew);
+                     s_dE, N, Ew, E_in, s_E, lr);
   return hipGetLastError();
 }
 

@@ -925,8 +925,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     if (lm) {
       role = HPSGD_ROLE_EMBED;
       const size_t oE = c->off("embed.E");
-      HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
-      HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, s));
+      if (!acc && rin == rout) {
+        // an update in place: only the rows of the tokens of the batch change, and their owners
+        // write them; no gradient table to clear, fill and stream through the commit kernel
+        fused_commit[c->find("embed.E")] = 1;
+        HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, s, rin + oE, sR, lr));
+      } else {
+        HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
+        HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, s));
+      }
     }
   }
   // ---- commit (Alg. 2 "update replica")

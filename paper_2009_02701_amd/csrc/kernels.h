@@ -228,6 +228,7 @@ hipError_t launch_embed_fwd(const float* E, long s_E, const int32_t* tok, long s
                             long s_out, int N, int Ew, int groups, hipStream_t s);
 // dE[g][v][:] = sum over positions i with tok[g][i]==v of dx[g][i][:], in increasing i; other rows untouched
 hipError_t launch_embed_bwd(const float* dx, long s_dx, const int32_t* tok, long s_tok, float* dE,
-                            long s_dE, int N, int Ew, int groups, hipStream_t s);
+                            long s_dE, int N, int Ew, int groups, hipStream_t s, const float* E_in = nullptr,
+                            long s_E = 0, float lr = 0.f);
 
 }  // namespace hpsgd

@@ -159,6 +159,29 @@ def test_config1_tiny_gru_schedules(sched):
     _schedule_parity(wl.CONFIGS["tiny_gru"], sched[0], TOL_FP32, **sched[1])
 
 
+@pytest.mark.parametrize("name", ["tiny_gru", "lm_small_fp32", "lm_tiles_fp32", "mlp_ragged", "lm_nt_bf16", "lm_nt_bf16_tiles"])
+def test_step_into_other_buffers_equals_step_in_place(name):
+    """hpsgd_local_step_all with replicas_out != replicas_in: the same bits as the update in
+    place (which takes the sparse embedding update and writes through aliased pointers), and
+    the input replicas stay as they were."""
+    cfg = SMALL[name] if name in SMALL else BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.sync_all(0)
+    tr.gather(0)
+    torch.cuda.synchronize()
+    r_in = tr.R[0].clone()
+    before = r_in.clone()
+    r_out = torch.full_like(r_in, float("nan"))
+    loss_o = torch.zeros_like(tr.loss)
+    tr.ctx.local_step_all(r_in, r_out, tr.xb, tr.yb, cfg["lr"], loss_o, tr.ctx.new_workspace(DEV))
+    tr.local_step(0, cfg["lr"])
+    torch.cuda.synchronize()
+    assert torch.equal(r_in, before)
+    assert torch.equal(r_out[:, :tr.P], tr.R[0][:, :tr.P])
+    assert torch.equal(loss_o, tr.loss)
+
+
 @pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "mlp_tiles"])
 def test_offline_training_keeps_workers_apart(name):
     """Sec. 4.1's PSGD reference: local steps only; every worker's model against the oracle's.
