@@ -75,6 +75,42 @@ def test_every_form_matches_float64_product(shape, commit):
     assert np.array_equal(results["auto"], results["128x128"])
 
 
+def test_seeded_random_shapes_every_form():
+    """40 seeded shapes with tails against every tile size; guard rows around C catch a store
+    outside the matrix."""
+    rng = np.random.default_rng(20090270)
+    for case in range(40):
+        G = int(rng.integers(1, 4))
+        M, N = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        Kd = 8 * int(rng.integers(1, 150))
+        commit = bool(case & 1)
+        A, B, W = _operands(1000 + case, G, M, N, Kd)
+        lr = 0.25
+        want, mag = _want(A, B, W if commit else None, lr)
+        tol = (lr if commit else 1.0) * 1e-5 * mag + 2e-7 * np.abs(want)
+        Ad, Bd = A.to(DEV), B.to(DEV)
+        first = None
+        for form in FORMS:
+            # one guard row of the matrix's width before and after the G * M rows
+            buf = torch.full(((G * M + 2) * N,), 12345.0, dtype=torch.float32, device=DEV)
+            out = buf[N:N + G * M * N].view(G, M, N)
+            win = None
+            if commit:
+                out.copy_(torch.from_numpy(W))
+                win = out
+            hb.gemm_bf16_nt(Ad, Bd, out, win=win, lr=lr, form=form)
+            torch.cuda.synchronize()
+            host = buf.cpu().numpy()
+            assert (host[:N] == 12345.0).all() and (host[-N:] == 12345.0).all(), (case, form, "guard")
+            got = host[N:N + G * M * N].reshape(G, M, N)
+            err = np.abs(got.astype(np.float64) - want)
+            assert (err <= tol).all(), (case, (G, M, N, Kd), form, float((err / tol).max()))
+            if first is None:
+                first = got
+            else:
+                assert np.array_equal(got, first), (case, form)
+
+
 def test_padded_pitches_and_untouched_padding():
     """Row pitches larger than the rows (as for the operand copies inside the local step): the
     padding of C keeps its contents."""
