@@ -176,6 +176,32 @@ hipError_t launch_commit(const float* in, float* out, size_t stride, const float
   return hipGetLastError();
 }
 
+// sum + p[n4] + p[2 n4] + .. + p[(n_parts-1) n4], added in that order; the loads of 16 parts are in
+// flight together (with one load per trip a sum over 140 parts waits out 140 memory latencies)
+__device__ __forceinline__ float4 add_parts_in_order(const float4* p, size_t n4, int n_parts, float4 sum) {
+  int q = 1;
+  for (; q + 16 <= n_parts; q += 16) {
+    float4 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = p[(size_t)(q + u) * n4];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      sum.x += v[u].x;
+      sum.y += v[u].y;
+      sum.z += v[u].z;
+      sum.w += v[u].w;
+    }
+  }
+  for (; q < n_parts; ++q) {
+    const float4 v = p[(size_t)q * n4];
+    sum.x += v.x;
+    sum.y += v.y;
+    sum.z += v.z;
+    sum.w += v.w;
+  }
+  return sum;
+}
+
 // Partial sums of a weight gradient (one per batch-row tile of the recurrence kernel), added in
 // tile order, then either committed (out = in - lr * sum) or stored (out = sum).  n % 4 == 0.
 __global__ void __launch_bounds__(kThreads)
@@ -184,14 +210,8 @@ reduce_parts_kernel(const float* __restrict__ parts, int n_parts, size_t n4, con
   const size_t k = blockIdx.y;
   const float4* pk = reinterpret_cast<const float4*>(parts) + k * n_parts * n4;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n4; i += (size_t)gridDim.x * kThreads) {
-    float4 sum = pk[i];
-    for (int p = 1; p < n_parts; ++p) {
-      const float4 v = pk[p * n4 + i];
-      sum.x += v.x;
-      sum.y += v.y;
-      sum.z += v.z;
-      sum.w += v.w;
-    }
+    const float4 sum0 = pk[i];
+    float4 sum = add_parts_in_order(pk + i, n4, n_parts, sum0);
     if (commit) {
       const float4 w = reinterpret_cast<const float4*>(in + k * s_in)[i];
       sum = make_float4(w.x - lr * sum.x, w.y - lr * sum.y, w.z - lr * sum.z, w.w - lr * sum.w);
@@ -212,14 +232,8 @@ __global__ void __launch_bounds__(kThreads) reduce_parts_multi_kernel(ReducePack
   const unsigned nblk = pk.blk0[sgi + 1] - pk.blk0[sgi];
   const float4* pkp = reinterpret_cast<const float4*>(sg.parts) + k * sg.n_parts * n4;
   for (size_t i = (size_t)(blockIdx.x - pk.blk0[sgi]) * kThreads + threadIdx.x; i < n4; i += (size_t)nblk * kThreads) {
-    float4 sum = pkp[i];
-    for (int p = 1; p < sg.n_parts; ++p) {
-      const float4 v = pkp[p * n4 + i];
-      sum.x += v.x;
-      sum.y += v.y;
-      sum.z += v.z;
-      sum.w += v.w;
-    }
+    const float4 sum0 = pkp[i];
+    float4 sum = add_parts_in_order(pkp + i, n4, sg.n_parts, sum0);
     if (sg.commit) {
       const float4 w = reinterpret_cast<const float4*>(sg.in + k * sg.s_in)[i];
       sum = make_float4(w.x - pk.lr * sum.x, w.y - pk.lr * sum.y, w.z - pk.lr * sum.z, w.w - pk.lr * sum.w);
