@@ -426,6 +426,36 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       TRY(order_resident_launches(s));
       abort_word = psync;  // (cleared together with the first layer's h_0 below)
     }
+    // ---- the head's operands
+    const int nrows = lm ? TB : B;
+    const size_t oW = c->off("head.W"), ob = c->off("head.b");
+    const long nrp = (long)round_up(nrows, 64), clp = (long)round_up(classes, 64);
+    const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
+    const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
+    // bf16 precision with every head operand available as bf16: h of the top layer (written
+    // by its step kernels), head.W rounded once (row-major and transposed in one pass), the
+    // logit gradient emitted in bf16 by the loss kernel and transposed from there
+    const bool headb =
+        ntc && gru_fused_bf16_supported(H) && classes % 8 == 0 &&
+        cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
+        softmax_ce_bf16_supported(logits, s_log, bfreg(c->dlogb), clp, s_dlb, classes) &&
+        cvt2_supported(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes);
+    // The head's weights are not needed before the recurrences of all layers are through: with
+    // an auxiliary stream their bf16 copies (a pass over the largest matrix of the model) are
+    // made beside those launches, which wait on each other most of the time and leave the
+    // memory system idle.
+    bool head_w_on_aux = false;
+    auto head_w_beside = [&]() -> int {  // called right before the first resident-weight launch
+      if (head_w_on_aux || !(headb && c->aux && c->ev_fork && c->ev_join)) return HPSGD_OK;
+      if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
+        return HPSGD_EHIP;
+      if (launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H, groups,
+                      c->aux) != hipSuccess)
+        return HPSGD_EHIP;
+      if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
+      head_w_on_aux = true;
+      return HPSGD_OK;
+    };
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -510,6 +540,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       // one event pair around the whole time loop when its launches are all of one role
       const bool persist_b = fused_b && use_persist_b && hT != nullptr;
+      if (persist_b) TRY0(head_w_beside());
       TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (persist || persist_b) ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
@@ -560,24 +591,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // ---- head and loss
     const float* top = reg(c->hs[L - 1]);
     const long s_top = (long)c->hs[L - 1].stride;
-    const int nrows = lm ? TB : B;
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
-    const size_t oW = c->off("head.W"), ob = c->off("head.b");
-    const long nrp = (long)round_up(nrows, 64), clp = (long)round_up(classes, 64);
-    const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
-    const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
-    // bf16 precision with every head operand available as bf16: h of the top layer (written
-    // by its step kernels), head.W rounded once (row-major and transposed in one pass), the
-    // logit gradient emitted in bf16 by the loss kernel and transposed from there
-    const bool headb =
-        ntc && gru_fused_bf16_supported(H) && classes % 8 == 0 &&
-        cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
-        softmax_ce_bf16_supported(logits, s_log, bfreg(c->dlogb), clp, s_dlb, classes) &&
-        cvt2_supported(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes);
     if (headb) {
       role = HPSGD_ROLE_OTHER;
-      HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
-                          groups, s));
+      if (head_w_on_aux) {
+        if (hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
+      } else {
+        HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
+                            groups, s));
+      }
       const long s_hb = 2 * (long)c->hb.stride;
       const NtView va{(const __bf16*)reg(c->hb) + (size_t)(lm ? B : T * B) * H, 1, H, s_hb};
       const NtView vb{bfreg(c->wob), 1, H, s_wob};
