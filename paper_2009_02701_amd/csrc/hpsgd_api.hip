@@ -623,13 +623,30 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                           classes, groups, s));
       role = HPSGD_ROLE_GEMM_HEAD;
       const NtView vdl{bfreg(c->dlogb), 1, clp, s_dlb}, vwT{bfreg(c->woT), 1, clp, s_woT};
-      TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
-                lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
       const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
       const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
       const WgradTarget wt = wgrad_target("head.W");
-      TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
-                wt.epi, wt.aux, sR, vdT, vhT, lr));
+      // The head's input gradient and weight gradient need the same logit gradient and nothing of
+      // each other.  The former has fewer tiles than the chip has CUs (a long contraction over
+      // the classes): with an auxiliary stream the two run side by side and the tiles of the
+      // weight gradient fill the CUs the other leaves idle.  One event pair brackets both.
+      const bool side_by_side = c->aux && c->ev_fork && c->ev_join;
+      {
+        TimerScope pair(c, role, s, 2);
+        const bool nested = c->timer_nested;
+        c->timer_nested = c->timer_nested || pair.active();
+        if (side_by_side &&
+            (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess))
+          return HPSGD_EHIP;
+        TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
+                  lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
+        TRY(gemm2(side_by_side ? c->aux : s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top,
+                  0, wt.C, H, wt.sC, wt.epi, wt.aux, sR, vdT, vhT, lr));
+        if (side_by_side &&
+            (hipEventRecord(c->ev_join, c->aux) != hipSuccess || hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess))
+          return HPSGD_EHIP;
+        c->timer_nested = nested;
+      }
       if (colsum_fused)
         HIP_TRY(launch_reduce_parts(reg(c->colpart), softmax_ce_bf16_row_blocks(nrows), (size_t)classes, nullptr, 0,
                                     grad + ob, (size_t)sG, 0.f, 0, groups, s));
