@@ -201,7 +201,11 @@ int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *sn
  * hpsgd_local_step(_all) records a HIP event pair on the caller's stream around every launch
  * group of that role (the only HIP objects the context ever creates; hpsgd_destroy frees
  * them).  hpsgd_timer_read waits for the recorded events, returns the number of timed
- * launch groups of `role` and their summed duration in milliseconds, and clears that role. */
+ * launch groups of `role` and their summed duration in milliseconds, and clears that role.
+ * With an auxiliary stream set (hpsgd_set_aux_stream) some launches run beside others: the
+ * bf16 head's two backward GEMMs share one pair (counted as two launches), and a launch
+ * that the library issues on the auxiliary stream alone (a layer's input-gradient GEMM beside
+ * its weight-gradient GEMMs, the copy of the head's weights) is not timed. */
 enum hpsgd_role {
   HPSGD_ROLE_OTHER = 0,        /* zero fills */
   HPSGD_ROLE_GEMM_INPUT = 1,   /* time-batched input projection  X W_ih^T */

@@ -897,10 +897,23 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         }
       }
       role = HPSGD_ROLE_GEMM_DX;
+      // bf16 operands: the input gradient reads only bf16 copies (not the weights the gradient
+      // GEMMs below update in place) and has fewer tiles than the chip has CUs: with an auxiliary
+      // stream it runs beside the layer's weight-gradient GEMMs (its launch is then not timed)
+      bool dx_beside = false;
       if (need_dx) {  // reads W_ih: before its update
         const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
-        TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
-                  nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
+        dx_beside = persist_b && stepT && v_wihT.bf16 && c->aux && c->ev_fork && c->ev_join && NC == 1;
+        if (dx_beside) {
+          if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
+            return HPSGD_EHIP;
+          TRY0(gemm2(c->aux, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx,
+                     EPI_STORE, nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
+          if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
+        } else {
+          TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
+                    nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
+        }
         above = dx;
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
@@ -958,6 +971,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the layer's sums of partial results (weight gradients of the resident-weight launch and
       // of the split contraction, bias gradients), with their updates: one launch
       HIP_TRY(launch_reduce_pack(rp, groups, s));
+      if (dx_beside && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
       role = HPSGD_ROLE_OTHER;
       if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
     }
