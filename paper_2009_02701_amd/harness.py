@@ -236,6 +236,10 @@ class Trainer:
         if self._have_delta:
             sb.wait_event(self._ev_a)
             self.merge(1 - g, sb)
+        # ... and clone the global model into that generation for the next round ("make replica"):
+        # it depends on the merge only, so it sits behind it on the synchronising side and off
+        # the training stream's path
+        self.sync_all(1 - g, sb)
         self._ev_b.record(sb)
         # training side (stream A): this round's local step on generation g
         self.gather(t, sa)
@@ -243,10 +247,9 @@ class Trainer:
         if record_loss:
             with torch.cuda.stream(sa):
                 self.losses.append(self.loss.clone())
-        # boundary: A waits for B's merge, then clones the global model into the other generation
-        sa.wait_event(self._ev_b)
-        self.sync_all(1 - g, sa)
+        # boundary: the next round's local step waits for B's merge and clone
         self._ev_a.record(sa)
+        sa.wait_event(self._ev_b)
         self._g = 1 - g
         self._have_delta = True
 
