@@ -123,6 +123,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge-stress", action="store_true")
+    ap.add_argument("--prepare", action="store_true",
+                    help="make the next step's bf16 weight copies on the synchronising stream (measured slower)")
     ap.add_argument("--workload", default="gru_cls", choices=["gru_cls", "gru_lm", "mlp", "tiny_gru"],
                     help="default: config 2, the one the headline metric is quoted on")
     args = ap.parse_args()
@@ -142,7 +144,7 @@ def main():
     init = wl.init_params(cfg)
     shards = [wl.make_shard(cfg, k) for k in range(K)]
     orders = [wl.batch_order(cfg, k) for k in range(K)]
-    tr = harness.Trainer(cfg, init, shards, orders, device=dev)
+    tr = harness.Trainer(cfg, init, shards, orders, device=dev, prepare=args.prepare)
     names = tr.ctx.role_names()
 
     # ---- pass 0: which role dominates the local step (all roles timed, a few rounds)

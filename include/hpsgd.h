@@ -110,6 +110,20 @@ int hpsgd_local_step_all(hpsgd_ctx *ctx, const float *replicas_in, float *replic
                          size_t replica_stride, const void *x, const int32_t *y, float lr,
                          float *loss_out, void *workspace, void *hip_stream);
 
+/* Optional, between "make replica" and the local step (Alg. 2): makes, on hip_stream, the
+ * operand copies that the next hpsgd_local_step_all(_acc) on (replicas, replica_stride,
+ * workspace) would otherwise make at its start - in the bf16 configurations the rounded and the
+ * transposed bf16 copies of every weight matrix; nothing in the others - so that they can
+ * be made on the synchronising side, behind hpsgd_sync_all, while the training stream is busy
+ * with another generation of replicas.  The context remembers (replicas, replica_stride,
+ * workspace); the next local step with exactly these skips its own copies, and every local
+ * step forgets the mark (it changes the weights).  The caller must not write the replicas
+ * between this call and that step, must order the two streams (the step after this call's
+ * work), and must not use the workspace for another step in between.
+ * Errors as for hpsgd_local_step_all's replicas_in and workspace arguments. */
+int hpsgd_prepare_replicas(hpsgd_ctx *ctx, const float *replicas, size_t replica_stride,
+                           void *workspace, void *hip_stream);
+
 /* The same for ONE worker (`worker` in [0, K) selects nothing but the workspace slice,
  * so that different workers may be stepped on different streams).  loss_out: 1 float. */
 int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float *replica_out,

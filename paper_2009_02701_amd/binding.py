@@ -26,7 +26,7 @@ EXPORTS = [
     "hpsgd_set_aux_stream", "hpsgd_timer_enable", "hpsgd_timer_read", "hpsgd_role_name",
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
-    "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt",
+    "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
 ]
 ROLE_COUNT = 14
 
@@ -66,6 +66,7 @@ def load_library():
     lib.hpsgd_workspace_bytes.argtypes = [vp]
     lib.hpsgd_workspace_bytes.restype = sz
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
+    lib.hpsgd_prepare_replicas.argtypes = [vp, vp, sz, vp, vp]
     lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
     lib.hpsgd_gather_batch_all.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, C.c_int, sz, C.c_int, sz,
@@ -223,6 +224,11 @@ class Context:
                                              replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
                                              _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
                "hpsgd_local_step_all")
+
+    def prepare_replicas(self, replicas, workspace, stream=None):
+        """Make the next local step's operand copies of the weights now (see hpsgd_prepare_replicas)."""
+        _check(self.lib.hpsgd_prepare_replicas(self._h, _ptr(replicas), replicas.stride(0), self._ws_ptr(workspace),
+                                               _stream(stream)), "hpsgd_prepare_replicas")
 
     def local_step_all_acc(self, replicas_in, replicas_out, x, y, lr, loss_out, grad_acc, workspace, stream=None):
         """local_step_all that also adds every worker's gradient to grad_acc [K, stride]."""

@@ -49,6 +49,11 @@ struct hpsgd_ctx {
   Region colpart;               // per block of logits rows: column sums of the logit gradient
   std::vector<Region> hsT;
   std::vector<Region> whhT, wihTl;  // per layer: transposed bf16 W_hh and W_ih, made in the forward pass
+  std::vector<Region> whhb, wihbl;  // per layer: row-major bf16 W_hh and W_ih
+  // hpsgd_prepare_replicas made the bf16 copies of these replicas' weights in this workspace
+  const float* prepared_rin = nullptr;
+  const float* prepared_ws = nullptr;
+  size_t prepared_stride = 0;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   std::vector<Region> dact;     // per MLP hidden layer: gradient w.r.t. its output
@@ -147,6 +152,8 @@ int build_layout(hpsgd_ctx* c) {
         c->hsT.push_back(c->alloc(H * TB1p / 2));
         c->whhT.push_back(c->alloc((3 * H * H + 1) / 2));
         c->wihTl.push_back(c->alloc(((l == 0 ? win0 : H) * 3 * H + 1) / 2));
+        c->whhb.push_back(c->alloc((3 * H * H + 1) / 2));
+        c->wihbl.push_back(c->alloc(((l == 0 ? win0 : H) * 3 * H + 1) / 2));
       }
       const size_t nr = lm ? TB : (size_t)d.batch;
       c->dlogT = c->alloc((size_t)classes * round_up(nr, 64) / 2);
@@ -300,6 +307,72 @@ int order_resident_launches(hipStream_t s) {
   return HPSGD_OK;
 }
 
+// bf16 precision: the rounded copies of the weight matrices that a local step's GEMMs and
+// recurrence launches read (row-major, and transposed where an input gradient is needed), all
+// made from the replicas `rin`.  what[l] / head say which copies exist; launch = false only
+// reports.  The head's copies are made when with_head is set.
+struct WeightCopies {
+  bool wih[16] = {false}, wihT[16] = {false}, whh[16] = {false}, whhT[16] = {false};
+  bool head = false;
+};
+
+int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, float* ws, hipStream_t st, bool launch,
+                  bool with_head, WeightCopies& wc) {
+  const hpsgd_model_desc& d = c->d;
+  if (d.prec != HPSGD_BF16_MFMA || d.kind == HPSGD_MLP || c->whhb.empty()) return HPSGD_OK;
+  auto reg = [&](const Region& r) { return ws + r.offset + (size_t)k0 * r.stride; };
+  auto bfreg = [&](const Region& r) { return (__bf16*)reg(r); };
+  const bool lm = d.kind == HPSGD_GRU_LM;
+  const int B = d.batch, H = d.hidden, L = d.layers;
+  const int classes = lm ? d.vocab : d.classes;
+  const bool ntc = (B % 8 == 0) && (H % 8 == 0);
+  const bool fused_b = gru_fused_bf16_supported(H);
+  for (int l = 0; l < L && l < 16; ++l) {
+    const std::string p = "l" + std::to_string(l);
+    const int width = l > 0 ? H : (lm ? d.embed : d.input);
+    const float* Wih = rin + c->off(p + ".W_ih");
+    const float* Whh = rin + c->off(p + ".W_hh");
+    if (fused_b && ntc && width % 8 == 0) {
+      const bool need_T = l > 0 || lm;  // the input gradient of this layer is needed
+      __bf16* wT = need_T ? bfreg(c->wihTl[l]) : nullptr;
+      const long s_wT = 2 * (long)c->wihTl[l].stride, s_wb2 = 2 * (long)c->wihbl[l].stride;
+      if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihbl[l]), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width)) {
+        if (launch && launch_cvt2(Wih, 0, width, sR, bfreg(c->wihbl[l]), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width,
+                                  groups, st) != hipSuccess)
+          return HPSGD_EHIP;
+        wc.wih[l] = true;
+        wc.wihT[l] = need_T;
+      }
+    }
+    if (fused_b) {
+      void* wb = reg(c->whhb[l]);
+      const long s_wb = 2 * (long)c->whhb[l].stride, s_whT = 2 * (long)c->whhT[l].stride;
+      if (cvt2_supported(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H)) {
+        if (launch &&
+            launch_cvt2(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H, groups, st) != hipSuccess)
+          return HPSGD_EHIP;
+        wc.whhT[l] = true;
+      } else if (launch && launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, st) != hipSuccess) {
+        return HPSGD_EHIP;
+      }
+      wc.whh[l] = true;
+    }
+  }
+  if (with_head) {
+    const size_t oW = c->off("head.W");
+    const long clp = (long)round_up(classes, 64);
+    const long s_wob = 2 * (long)c->wob.stride, s_woT = 2 * (long)c->woT.stride;
+    if (ntc && fused_b && classes % 8 == 0 &&
+        cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H)) {
+      if (launch && launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
+                                groups, st) != hipSuccess)
+        return HPSGD_EHIP;
+      wc.head = true;
+    }
+  }
+  return HPSGD_OK;
+}
+
 // One local step for `groups` workers whose workspace slices start at worker k0.
 // acc (nullable): per-worker gradient accumulators [groups][acc_stride]; the step's gradient
 // is added to them (Alg. 2 "accumulate gradients").  Every gradient then goes through the
@@ -316,6 +389,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
+  // the bf16 copies of the weights are already in this workspace (hpsgd_prepare_replicas); the
+  // step changes the weights, so the mark is used once
+  const bool prepared = bf && c->prepared_rin == rin && c->prepared_ws == ws && c->prepared_stride == rstride &&
+                        k0 == 0 && groups == c->K;
+  c->prepared_rin = nullptr;
   const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
   c->last_resident = c->last_xproj = c->last_dw = 0;
   // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
@@ -444,9 +522,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // an auxiliary stream their bf16 copies (a pass over the largest matrix of the model) are
     // made beside those launches, which wait on each other most of the time and leave the
     // memory system idle.
+    // the layers' bf16 weight copies: all at the start (nothing but the replicas feeds them),
+    // unless they were made before the step
+    WeightCopies wc;
+    role = HPSGD_ROLE_OTHER;
+    TRY(weight_copies(c, rin, sR, k0, groups, ws, s, !prepared, false, wc));
     bool head_w_on_aux = false;
     auto head_w_beside = [&]() -> int {  // called right before the first resident-weight launch
-      if (head_w_on_aux || !(headb && c->aux && c->ev_fork && c->ev_join)) return HPSGD_OK;
+      if (prepared || head_w_on_aux || !(headb && c->aux && c->ev_fork && c->ev_join)) return HPSGD_OK;
       if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
         return HPSGD_EHIP;
       if (launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H, groups,
@@ -493,7 +576,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         // for the weight-gradient GEMM)
         if (fused_b && ntc && width % 8 == 0) {
           role = HPSGD_ROLE_OTHER;
-          const long s_xb = 2 * (long)c->xb.stride, s_wb2 = 2 * (long)c->wihb.stride;
+          const long s_xb = 2 * (long)c->xb.stride;
           if (l > 0) {
             va = NtView{(const __bf16*)reg(c->hb) + (size_t)B * H, 1, H, 2 * (long)c->hb.stride};
           } else if (cvt2_supported(lin, 0, width, s_lin, bfreg(c->xb), width, s_xb, bfreg(c->xT), TBp,
@@ -503,14 +586,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
             va = NtView{bfreg(c->xb), 1, width, s_xb};
             xT_ready = true;
           }
-          const bool need_T = l > 0 || lm;  // the input gradient of this layer is needed
-          __bf16* wT = need_T ? bfreg(c->wihTl[l]) : nullptr;
-          const long s_wT = 2 * (long)c->wihTl[l].stride;
-          if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width)) {
-            HIP_TRY(launch_cvt2(Wih, 0, width, sR, bfreg(c->wihb), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width,
-                                groups, s));
-            vb = NtView{bfreg(c->wihb), 1, width, s_wb2};
-            wihT_ready[l] = need_T;
+          if (wc.wih[l]) {  // made at the start of the step, or before it
+            vb = NtView{bfreg(c->wihbl[l]), 1, width, 2 * (long)c->wihbl[l].stride};
+            wihT_ready[l] = wc.wihT[l];
           }
         }
         role = HPSGD_ROLE_GEMM_INPUT;
@@ -519,21 +597,16 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
       // not use) and of h
-      void* wb = reg(c->wt);
-      const long s_wb = 2 * (long)c->wt.stride;
+      void* wb = wc.whh[l] ? reg(c->whhb[l]) : reg(c->wt);
+      const long s_wb = 2 * (long)(wc.whh[l] ? c->whhb[l].stride : c->wt.stride);
       __bf16* hb = fused_b ? (__bf16*)reg(c->hb) : nullptr;
       const long s_hb = 2 * (long)c->hb.stride;
       __bf16* hT = (fused_b && ntc) ? bfreg(c->hsT[l]) : nullptr;  // hsT exists in bf16 precision only
       const long s_hT = hT ? 2 * (long)c->hsT[l].stride : 0;
       if (fused_b) {
         role = HPSGD_ROLE_OTHER;
-        const long s_whT = 2 * (long)c->whhT[l].stride;
-        if (cvt2_supported(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H)) {
-          HIP_TRY(launch_cvt2(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H, groups, s));
-          whhT_ready[l] = true;
-        } else {
-          HIP_TRY(launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, s));
-        }
+        if (!wc.whh[l]) return HPSGD_ESHAPE;  // (bf16 precision allocates the per-layer copies)
+        whhT_ready[l] = wc.whhT[l];
         HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
         if (hT)  // h_0 = 0: the first B columns of the transposed copy
           HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
@@ -596,7 +669,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       role = HPSGD_ROLE_OTHER;
       if (head_w_on_aux) {
         if (hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
-      } else {
+      } else if (!prepared) {
         HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             groups, s));
       }
@@ -1086,6 +1159,26 @@ int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replic
   TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
   return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
                   (float*)workspace, (hipStream_t)hip_stream);
+}
+
+int hpsgd_prepare_replicas(hpsgd_ctx* ctx, const float* replicas, size_t replica_stride, void* workspace,
+                           void* hip_stream) {
+  if (!ctx || !replicas) return HPSGD_EINVAL;
+  if (!workspace || ((uintptr_t)workspace & 255) != 0) return HPSGD_EWORKSPACE;
+  if (!aligned16(replicas) || (ctx->K > 1 && (replica_stride < ctx->P || (replica_stride & 3) != 0)))
+    return HPSGD_EALIGN;
+  const size_t span = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
+  if (overlaps(workspace, ctx->ws_floats * sizeof(float), replicas, span)) return HPSGD_EALIAS;
+  ctx->prepared_rin = nullptr;
+  if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
+  WeightCopies wc;
+  const int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace,
+                               (hipStream_t)hip_stream, true, true, wc);
+  if (rc != HPSGD_OK) return rc;
+  ctx->prepared_rin = replicas;
+  ctx->prepared_ws = (const float*)workspace;
+  ctx->prepared_stride = replica_stride;
+  return HPSGD_OK;
 }
 
 int hpsgd_local_step_all_acc(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,

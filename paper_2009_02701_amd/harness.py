@@ -23,7 +23,11 @@ from . import binding as hb
 
 class Trainer:
     def __init__(self, cfg: dict, init_params: dict, shards: list, orders: list, device="cuda",
-                 aux_stream=True):
+                 aux_stream=True, prepare=False):
+        # hpsgd_prepare_replicas behind every clone on the synchronising side.  Off by default: on
+        # MI355X the copies then run beside the training stream's resident-weight launches, whose
+        # chains of waits slow down by more than the copies cost (config 3: 3.37 -> 3.60 ms per round)
+        self.use_prepare = prepare
         self.cfg = cfg
         self.ctx = hb.Context(cfg)
         self.K, self.P, self.stride = self.ctx.K, self.ctx.P, self.ctx.stride
@@ -88,6 +92,13 @@ class Trainer:
             self.ws[ws] = self.ctx.new_workspace(self.dev)
         self.ctx.local_step_all(self.R[gen], self.R[gen], self.xb, self.yb, lr, self.loss,
                                 self.ws[ws], stream=stream)
+
+    def prepare(self, gen: int, stream=None):
+        """hpsgd_prepare_replicas for generation `gen`, whose local steps use workspace `gen`."""
+        if self.ws[gen] is None:
+            self.ws[gen] = self.ctx.new_workspace(self.dev)
+        if self.use_prepare:
+            self.ctx.prepare_replicas(self.R[gen], self.ws[gen], stream=stream)
 
     def merge(self, gen: int, stream=None):
         hb.merge(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
@@ -193,7 +204,7 @@ class Trainer:
             if e >= 2:
                 done[e % 2].synchronize()
             self.gather(e, sa)
-            self.local_step(g, lr, sa)
+            self.local_step(g, lr, sa, ws=g)
             n += 1
             if record_loss:
                 with torch.cuda.stream(sa):
@@ -205,6 +216,7 @@ class Trainer:
                     hb.delay_us(sync_delay_us, sb)
                 self.merge(g, sb)
                 self.sync_all(g, sb)
+                self.prepare(g, sb)
                 busy = torch.cuda.Event()
                 busy.record(sb)
                 counts.append(n)
@@ -240,10 +252,13 @@ class Trainer:
         # it depends on the merge only, so it sits behind it on the synchronising side and off
         # the training stream's path
         self.sync_all(1 - g, sb)
+        # ... and the operand copies of its weights that the next local step would make at its
+        # start (bf16 configurations), in that generation's own workspace
+        self.prepare(1 - g, sb)
         self._ev_b.record(sb)
         # training side (stream A): this round's local step on generation g
         self.gather(t, sa)
-        self.local_step(g, lr, sa)
+        self.local_step(g, lr, sa, ws=g)
         if record_loss:
             with torch.cuda.stream(sa):
                 self.losses.append(self.loss.clone())

@@ -162,4 +162,10 @@ def test_local_step_rejects_bad_arguments_before_launch():
     assert call(R, R + 64, 5132, X, Y, W) == 4                           # partial overlap in/out
     assert call(R, O, 5132, X, Y, R) == 4                                # workspace over the replicas
     assert lib.hpsgd_local_step(ctx._h, 2, vp(R), vp(O), vp(X), vp(Y), 0.1, None, vp(W), None) == 1
+    prep = lambda r, stride, w: lib.hpsgd_prepare_replicas(ctx._h, vp(r), stride, vp(w), None)
+    assert prep(0, 5132, W) == 1
+    assert prep(R, 5132, 0) == 5 and prep(R, 5132, W + 16) == 5
+    assert prep(R + 4, 5132, W) == 3 and prep(R, 5130, W) == 3 and prep(R, 5000, W) == 3
+    assert prep(R, 5132, R) == 4
+    assert prep(R, 5132, W) == 0                                         # fp32: nothing to prepare, nothing launched
     assert hb.load_library().hpsgd_strerror(4) == b"buffers overlap"

@@ -182,6 +182,48 @@ def test_step_into_other_buffers_equals_step_in_place(name):
     assert torch.equal(loss_o, tr.loss)
 
 
+@pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "cls_nt_bf16", "lm_small_bf16", "tiny_gru"])
+def test_prepared_step_equals_unprepared_step(name):
+    """hpsgd_prepare_replicas: the step that follows it gives the same bits as a step that makes
+    its operand copies itself; the mark is used once (a second step on the same buffers sees the
+    weights the first one wrote); preparing other replicas than the ones stepped changes nothing."""
+    cfg = BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.sync_all(0)
+    tr.sync_all(1)
+    tr.gather(0)
+    torch.cuda.synchronize()
+    lr = cfg["lr"]
+    # reference: two steps in place, no preparation
+    ref = tr.R[0].clone()
+    ws_ref = tr.ctx.new_workspace(DEV)
+    loss_ref = [torch.zeros_like(tr.loss), torch.zeros_like(tr.loss)]
+    for i in range(2):
+        tr.ctx.local_step_all(ref, ref, tr.xb, tr.yb, lr, loss_ref[i], ws_ref)
+    # prepared: same two steps, the first after prepare_replicas on another stream
+    got = tr.R[1]
+    ws = tr.ctx.new_workspace(DEV)
+    side = torch.cuda.Stream(device=DEV)
+    loss_got = [torch.zeros_like(tr.loss), torch.zeros_like(tr.loss)]
+    torch.cuda.synchronize()
+    tr.ctx.prepare_replicas(got, ws, stream=side)
+    side.synchronize()
+    for i in range(2):
+        tr.ctx.local_step_all(got, got, tr.xb, tr.yb, lr, loss_got[i], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(got[:, :tr.P], ref[:, :tr.P])
+    assert torch.equal(loss_got[0], loss_ref[0]) and torch.equal(loss_got[1], loss_ref[1])
+    # a mark for other replicas (or another workspace) is not used
+    other = tr.R[0].clone()
+    tr.ctx.prepare_replicas(other, ws)
+    third_ref, third_got = ref.clone(), got.clone()
+    tr.ctx.local_step_all(third_ref, third_ref, tr.xb, tr.yb, lr, loss_ref[0], ws_ref)
+    tr.ctx.local_step_all(third_got, third_got, tr.xb, tr.yb, lr, loss_got[0], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(third_got[:, :tr.P], third_ref[:, :tr.P])
+
+
 @pytest.mark.parametrize("name", ["tiny_gru", "gru_cls", "mlp_tiles"])
 def test_offline_training_keeps_workers_apart(name):
     """Sec. 4.1's PSGD reference: local steps only; every worker's model against the oracle's.
