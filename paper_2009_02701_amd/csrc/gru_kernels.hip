@@ -215,6 +215,57 @@ colsum_kernel(const float* __restrict__ in, long ld, long s_in, float* __restric
   }
 }
 
+// Column sums of several matrices in one launch (the bias gradients of all MLP layers: each is a
+// few microseconds of work behind a launch); segment i owns grid columns blk0[i] .. blk0[i+1]-1.
+// With b_in the sum is applied at once: out = b_in - lr * sum.
+__global__ void __launch_bounds__(64 * kColsumSlices) colsum_multi_kernel(ColsumPack pk) {
+  __shared__ float red[kColsumSlices][64];
+  int sgi = 0;
+#pragma unroll
+  for (int i = 1; i < ColsumPack::MAXSEG; ++i)
+    if (i < pk.n && blockIdx.x >= pk.blk0[i]) sgi = i;
+  const ColsumSeg& sg = pk.seg[sgi];
+  const int g = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const int c = (blockIdx.x - pk.blk0[sgi]) * 64 + lane;
+  const int slice = threadIdx.x >> 6;
+  float a0 = 0.f, a1 = 0.f;
+  if (c < sg.N) {
+    const float* p = sg.in + g * sg.s_in + c;
+    int r = slice;
+    for (; r + kColsumSlices < sg.R; r += 2 * kColsumSlices) {
+      a0 += p[(long)r * sg.ld];
+      a1 += p[(long)(r + kColsumSlices) * sg.ld];
+    }
+    if (r < sg.R) a0 += p[(long)r * sg.ld];
+  }
+  red[slice][lane] = a0 + a1;
+  __syncthreads();
+  if (slice == 0 && c < sg.N) {
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < kColsumSlices; ++i) v += red[i][lane];
+    sg.out[g * sg.s_out + c] = sg.b_in ? sg.b_in[g * sg.s_bin + c] - pk.lr * v : v;
+  }
+}
+
+bool colsum_pack_push(ColsumPack& pk, const float* in, long ld, long s_in, float* out, long s_out, const float* b_in,
+                      long s_bin, int R, int N) {
+  if (pk.n >= ColsumPack::MAXSEG || N <= 0 || R <= 0) return false;
+  ColsumSeg& sg = pk.seg[pk.n];
+  sg.in = in; sg.ld = ld; sg.s_in = s_in; sg.out = out; sg.s_out = s_out; sg.b_in = b_in; sg.s_bin = s_bin;
+  sg.R = R; sg.N = N;
+  pk.blk0[pk.n + 1] = pk.blk0[pk.n] + (unsigned)((N + 63) / 64);
+  ++pk.n;
+  return true;
+}
+
+hipError_t launch_colsum_pack(const ColsumPack& pk, int groups, hipStream_t s) {
+  if (pk.n == 0 || groups <= 0) return hipSuccess;
+  hipLaunchKernelGGL(colsum_multi_kernel, dim3(pk.blk0[pk.n], groups), dim3(64 * kColsumSlices), 0, s, pk);
+  return hipGetLastError();
+}
+
 hipError_t launch_colsum(const float* in, long ld, long s_in, float* out, long s_out, int R, int N,
                          int groups, hipStream_t s) {
   hipLaunchKernelGGL(colsum_kernel, dim3((N + 63) / 64, groups), dim3(64 * kColsumSlices), 0, s, in,

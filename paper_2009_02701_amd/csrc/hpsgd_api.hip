@@ -436,6 +436,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                               (long)c->rowloss.stride, B, dims[L], groups, s));
     if (loss_out) HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, B, groups, s));
     // backward
+    // the bias gradients (column sums of every layer's delta) are taken in one launch behind the
+    // last layer, which also applies them unless the gradients are accumulated as well
+    ColsumPack cp;
+    cp.n = 0;
+    cp.blk0[0] = 0;
+    cp.lr = lr;
     for (int i = L - 1; i >= 0; --i) {
       const std::string p = "fc" + std::to_string(i);
       const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;
@@ -454,10 +460,18 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const WgradTarget wt = wgrad_target(p + ".W");
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
                s_prev, 0, wt.C, dims[i], wt.sC, wt.epi, wt.aux, sR, 0, lr));
-      HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + c->off(p + ".b"), sG, B, dims[i + 1],
-                            groups, s));
+      {
+        const size_t ob = c->off(p + ".b");
+        const bool pushed = acc ? colsum_pack_push(cp, delta, dims[i + 1], s_delta, grad + ob, sG, nullptr, 0, B, dims[i + 1])
+                                : colsum_pack_push(cp, delta, dims[i + 1], s_delta, rout + ob, sR, rin + ob, sR, B,
+                                                   dims[i + 1]);
+        if (pushed && !acc) fused_commit[c->find(p + ".b")] = 1;
+        if (!pushed)
+          HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + ob, sG, B, dims[i + 1], groups, s));
+      }
       if (i > 0) delta = dprev;
     }
+    HIP_TRY(launch_colsum_pack(cp, groups, s));
   } else {
     const bool lm = d.kind == HPSGD_GRU_LM;
     const int T = d.seq_len, H = d.hidden, L = d.layers;

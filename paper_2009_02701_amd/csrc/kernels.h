@@ -221,6 +221,24 @@ hipError_t launch_softmax_ce(const float* logits, long s_logits, const int32_t* 
 hipError_t launch_loss_mean(const float* rowloss, long s_rowloss, float* loss, int N, int groups,
                             hipStream_t s);
 // out[g][n] = sum_r in[g][r][n]
+// Column sums of up to MAXSEG matrices in one launch, optionally applied as out = b_in - lr * sum.
+// pk.n = 0, pk.blk0[0] = 0 and pk.lr are set by the caller.
+struct ColsumSeg {
+  const float* in; long ld, s_in;
+  float* out; long s_out;
+  const float* b_in; long s_bin;
+  int R, N;
+};
+struct ColsumPack {
+  static constexpr int MAXSEG = 8;
+  ColsumSeg seg[MAXSEG];
+  unsigned blk0[MAXSEG + 1];
+  int n;
+  float lr;
+};
+bool colsum_pack_push(ColsumPack& pk, const float* in, long ld, long s_in, float* out, long s_out, const float* b_in,
+                      long s_bin, int R, int N);
+hipError_t launch_colsum_pack(const ColsumPack& pk, int groups, hipStream_t s);
 hipError_t launch_colsum(const float* in, long ld, long s_in, float* out, long s_out, int R, int N,
                          int groups, hipStream_t s);
 // embedding rows: out[g][i][:] = E[g][tok[g][i]][:]

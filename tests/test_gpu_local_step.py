@@ -350,11 +350,17 @@ def test_overlapped_two_streams_equals_one_stream_bitwise():
 
 
 def test_commit_kernel_params_counts_what_the_epilogues_did_not_update():
-    """MLP: every weight matrix is updated by its gradient GEMM, the commit kernel sees the
-    biases only; the count is what bench.py uses for the commit role's bytes."""
+    """MLP: every weight matrix is updated by its gradient GEMM and every bias by the launch
+    that sums its gradient: nothing is left for the commit kernel.  A GRU whose shapes take
+    no resident-weight launch leaves it the biases of the recurrence.  The count
+    is what bench.py uses for the commit role's bytes."""
     cfg = SMALL["mlp_ragged"]
     tr, init, _, _, _ = _one_step(cfg, cfg["lr"])
-    n_bias = sum(v.size for k, v in init.items() if k.endswith(".b"))
+    assert tr.ctx.commit_kernel_params() == 0
+    cfg = SMALL["gru_cls_ragged"]
+    tr, init, _, _, _ = _one_step(cfg, cfg["lr"])
+    # (its weight matrices are updated by GEMM epilogues, its head by the classifier-head launch)
+    n_bias = sum(v.size for k, v in init.items() if k.endswith((".b_ih", ".b_hh")))
     assert tr.ctx.commit_kernel_params() == n_bias
 
 
