@@ -217,7 +217,8 @@ colsum_kernel(const float* __restrict__ in, long ld, long s_in, float* __restric
 
 // Column sums of several matrices in one launch (the bias gradients of all MLP layers: each is a
 // few microseconds of work behind a launch); segment i owns grid columns blk0[i] .. blk0[i+1]-1.
-// With b_in the sum is applied at once: out = b_in - lr * sum.
+// With b_in the sum is applied at once: out = b_in - lr * sum; without, out = scale * sum (a mean
+// of per-row losses is a column sum of an R x 1 matrix scaled by 1 / R).
 __global__ void __launch_bounds__(64 * kColsumSlices) colsum_multi_kernel(ColsumPack pk) {
   __shared__ float red[kColsumSlices][64];
   int sgi = 0;
@@ -245,16 +246,16 @@ __global__ void __launch_bounds__(64 * kColsumSlices) colsum_multi_kernel(Colsum
     float v = 0.f;
 #pragma unroll
     for (int i = 0; i < kColsumSlices; ++i) v += red[i][lane];
-    sg.out[g * sg.s_out + c] = sg.b_in ? sg.b_in[g * sg.s_bin + c] - pk.lr * v : v;
+    sg.out[g * sg.s_out + c] = sg.b_in ? sg.b_in[g * sg.s_bin + c] - pk.lr * v : v * sg.scale;
   }
 }
 
 bool colsum_pack_push(ColsumPack& pk, const float* in, long ld, long s_in, float* out, long s_out, const float* b_in,
-                      long s_bin, int R, int N) {
+                      long s_bin, int R, int N, float scale) {
   if (pk.n >= ColsumPack::MAXSEG || N <= 0 || R <= 0) return false;
   ColsumSeg& sg = pk.seg[pk.n];
   sg.in = in; sg.ld = ld; sg.s_in = s_in; sg.out = out; sg.s_out = s_out; sg.b_in = b_in; sg.s_bin = s_bin;
-  sg.R = R; sg.N = N;
+  sg.R = R; sg.N = N; sg.scale = scale;
   pk.blk0[pk.n + 1] = pk.blk0[pk.n] + (unsigned)((N + 63) / 64);
   ++pk.n;
   return true;

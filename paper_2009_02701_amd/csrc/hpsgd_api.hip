@@ -434,7 +434,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     role = HPSGD_ROLE_LOSS;
     HIP_TRY(launch_softmax_ce(delta, (long)c->act[L - 1].stride, y, B, delta, rowloss,
                               (long)c->rowloss.stride, B, dims[L], groups, s));
-    if (loss_out) HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, B, groups, s));
     // backward
     // the bias gradients (column sums of every layer's delta) are taken in one launch behind the
     // last layer, which also applies them unless the gradients are accumulated as well
@@ -442,6 +441,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     cp.n = 0;
     cp.blk0[0] = 0;
     cp.lr = lr;
+    // (the mean of the per-row losses rides along: a column sum of a B x 1 matrix)
+    if (loss_out && !colsum_pack_push(cp, rowloss, 1, (long)c->rowloss.stride, loss_out, 1, nullptr, 0, B, 1,
+                                      1.0f / (float)B))
+      return HPSGD_ESHAPE;
     for (int i = L - 1; i >= 0; --i) {
       const std::string p = "fc" + std::to_string(i);
       const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;

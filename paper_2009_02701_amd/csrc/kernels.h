@@ -228,6 +228,7 @@ struct ColsumSeg {
   float* out; long s_out;
   const float* b_in; long s_bin;
   int R, N;
+  float scale;  // applied when b_in is null
 };
 struct ColsumPack {
   static constexpr int MAXSEG = 8;
@@ -237,7 +238,7 @@ struct ColsumPack {
   float lr;
 };
 bool colsum_pack_push(ColsumPack& pk, const float* in, long ld, long s_in, float* out, long s_out, const float* b_in,
-                      long s_bin, int R, int N);
+                      long s_bin, int R, int N, float scale = 1.0f);
 hipError_t launch_colsum_pack(const ColsumPack& pk, int groups, hipStream_t s);
 hipError_t launch_colsum(const float* in, long ld, long s_in, float* out, long s_out, int R, int N,
                          int groups, hipStream_t s);
