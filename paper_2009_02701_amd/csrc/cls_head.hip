@@ -38,13 +38,15 @@ __device__ __forceinline__ void batched_copy(int n, Load load, Store store) {
 
 // grid (ceil(N / 8), groups), 256 threads: thread t works for row t / 32 of the slice on the
 // contraction indices t % 32, + 32, ...
+template <int CPAD>  // classes rounded up to 8, 16 or 32: the rows of W beyond C are zero in LDS, so that
+                     // the inner loops carry no guards (a guard per class keeps the LDS reads from being batched)
 __global__ void __launch_bounds__(256)
 cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* __restrict__ W,
                     const float* __restrict__ b, long s_in, const int32_t* __restrict__ y, long s_y,
                     float* __restrict__ dlog, long s_dlog, float* __restrict__ rowloss, long s_rowloss, int N, int C,
                     int H) {
   extern __shared__ __attribute__((aligned(16))) float head_lds[];
-  float* sW = head_lds;  // [C][H]
+  float* sW = head_lds;  // [CPAD][H]
   const int g = blockIdx.y, tid = threadIdx.x;
   const int part = tid & 31, row = blockIdx.x * HROWS + (tid >> 5);
   const int rowc = min(row, N - 1);
@@ -60,9 +62,10 @@ cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
                    [&](int i, float v) {
                      if (tid + 256 * i < nW) sW[tid + 256 * i] = v;
                    });
-  float acc[HMAXC];
+  for (int i = nW + tid; i < CPAD * H; i += 256) sW[i] = 0.f;
+  float acc[CPAD];
 #pragma unroll
-  for (int c = 0; c < HMAXC; ++c) acc[c] = 0.f;
+  for (int c = 0; c < CPAD; ++c) acc[c] = 0.f;
   __syncthreads();
   for (int base = 0; base < nk; base += 8) {
     if (base > 0) {
@@ -74,30 +77,28 @@ cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
       if (base + u < nk) {
         const int k = part + 32 * (base + u);
 #pragma unroll
-        for (int c = 0; c < HMAXC; ++c)
-          if (c < C) acc[c] += f[u] * sW[c * H + k];
+        for (int c = 0; c < CPAD; ++c) acc[c] += f[u] * sW[c * H + k];
       }
   }
   // the 32 partial sums of a row: butterfly inside its half of the wave
 #pragma unroll
-  for (int c = 0; c < HMAXC; ++c)
-    if (c < C) {
+  for (int c = 0; c < CPAD; ++c) {
 #pragma unroll
-      for (int o = 16; o > 0; o >>= 1) acc[c] += __shfl_xor(acc[c], o);
-    }
+    for (int o = 16; o > 0; o >>= 1) acc[c] += __shfl_xor(acc[c], o);
+  }
   if (part == 0 && row < N) {
     const float* bg = b + g * s_in;
     const int label = y[g * s_y + row];
     float m = -INFINITY;
 #pragma unroll
-    for (int c = 0; c < HMAXC; ++c)
+    for (int c = 0; c < CPAD; ++c)
       if (c < C) {
         acc[c] += bg[c];
         m = fmaxf(m, acc[c]);
       }
     float sum = 0.f, zl = 0.f;
 #pragma unroll
-    for (int c = 0; c < HMAXC; ++c)
+    for (int c = 0; c < CPAD; ++c)
       if (c < C) {
         if (c == label) zl = acc[c];
         acc[c] = expf(acc[c] - m);
@@ -107,7 +108,7 @@ cls_head_fwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
     const float inv_sum = 1.0f / sum, inv_n = 1.0f / (float)N;
     float* dr = dlog + g * s_dlog + (long)row * C;
 #pragma unroll
-    for (int c = 0; c < HMAXC; ++c)
+    for (int c = 0; c < CPAD; ++c)
       if (c < C) dr[c] = (acc[c] * inv_sum - (c == label ? 1.0f : 0.0f)) * inv_n;
   }
 }
@@ -181,7 +182,8 @@ cls_head_bwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
 }  // namespace
 
 bool cls_head_supported(int N, int C, int H) {
-  return N >= 1 && N <= HMAXN && C >= 2 && C <= HMAXC && H >= 1 && (size_t)C * H * sizeof(float) <= 128 * 1024;
+  const int cpad = C <= 8 ? 8 : C <= 16 ? 16 : 32;
+  return N >= 1 && N <= HMAXN && C >= 2 && C <= HMAXC && H >= 1 && (size_t)cpad * H * sizeof(float) <= 128 * 1024;
 }
 
 // feats: [groups][N][H] (stride s_feats); W_in / b_in: the head's parameters in the input replicas
@@ -194,16 +196,24 @@ hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, 
                            float* dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr, int commit,
                            float* loss, int N, int C, int H, int groups, hipStream_t s) {
   if (!cls_head_supported(N, C, H)) return hipErrorInvalidValue;
-  const size_t lds = (size_t)C * H * sizeof(float);
-  static size_t allowed = 0;
-  if (lds > allowed && lds > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute((const void*)cls_head_fwd_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)lds);
-    if (e != hipSuccess) return e;
-    allowed = lds;
-  }
-  hipLaunchKernelGGL(cls_head_fwd_kernel, dim3((N + HROWS - 1) / HROWS, groups), dim3(256), lds, s, feats, s_feats,
-                     W_in, b_in, s_in, y, s_y, dlog, s_dlog, rowloss, s_rowloss, N, C, H);
+  const int cpad = C <= 8 ? 8 : C <= 16 ? 16 : 32;
+  const size_t lds = (size_t)cpad * H * sizeof(float);
+#define HPSGD_HEAD_FWD(CP)                                                                                         \
+  do {                                                                                                             \
+    static size_t allowed = 0;                                                                                     \
+    if (lds > allowed && lds > 64 * 1024) {                                                                        \
+      hipError_t e_ = hipFuncSetAttribute((const void*)cls_head_fwd_kernel<CP>,                                    \
+                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                  \
+      if (e_ != hipSuccess) return e_;                                                                             \
+      allowed = lds;                                                                                               \
+    }                                                                                                              \
+    hipLaunchKernelGGL(cls_head_fwd_kernel<CP>, dim3((N + HROWS - 1) / HROWS, groups), dim3(256), lds, s, feats,   \
+                       s_feats, W_in, b_in, s_in, y, s_y, dlog, s_dlog, rowloss, s_rowloss, N, C, H);               \
+  } while (0)
+  if (cpad == 8) HPSGD_HEAD_FWD(8);
+  else if (cpad == 16) HPSGD_HEAD_FWD(16);
+  else HPSGD_HEAD_FWD(32);
+#undef HPSGD_HEAD_FWD
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cls_head_bwd_kernel, dim3((H + HCOLS - 1) / HCOLS, groups), dim3(256), 0, s, feats, s_feats,
