@@ -26,7 +26,7 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration with a plain 1 GiB copy kernel;
 # summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Other workloads: not collected (null).
 MEASURED_TRAFFIC_BYTES = {
-    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 84006.3 + 132984.0) * 1024, "gemm_recurrent_fwd": (2.0 * 27453.2 + 89880.0) * 1024},
+    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 84280.5 + 133496.3) * 1024, "gemm_recurrent_fwd": (2.0 * 27504.8 + 89880.0) * 1024},
 }
 
 
