@@ -336,6 +336,28 @@ def test_aux_stream_overlap_matches_single_stream_order():
             assert rel_err(outs[0][k][n], outs[1][k][n]) <= 1e-5, n
 
 
+@pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "cls_nt_bf16", "gru_lm"])
+def test_bf16_work_beside_other_work_changes_no_bit(name):
+    """With an auxiliary stream the bf16 step makes the head's weight copies beside the first
+    recurrence launch and runs input-gradient GEMMs beside weight-gradient GEMMs: the same
+    kernels on the same data, so two local steps give the same bits as without it."""
+    cfg = BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for aux in (True, False):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, aux_stream=aux)
+        tr.sync_all(0)
+        for step in range(2):
+            tr.gather(step)
+            tr.local_step(0, cfg["lr"])
+        torch.cuda.synchronize()
+        assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+        outs.append((tr.R[0][:, :tr.P].clone(), tr.loss.clone()))
+        del tr
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.isfinite(outs[0][0]).all() and torch.isfinite(outs[0][1]).all()
+
+
 def test_overlapped_two_streams_equals_one_stream_bitwise():
     """The two-stream schedule must give the bits of the same op list run on one stream,
     and the same bits run to run."""
