@@ -569,14 +569,39 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       s_lin = (long)c->xe.stride;
       width = d.embed;
     }
+    // everything a step clears before its first layer, in one launch: the flag words of the
+    // resident-weight launches, h_0 of every layer (fp32, and in bf16 precision the bf16 copy and
+    // the first B columns of the transposed copy)
+    bool cleared = false;
+    {
+      FillPack fp;
+      fp.n = 0;
+      fp.blk0[0] = 0;
+      fp.max_groups = 0;
+      bool ok = true;
+      if (psync) ok = ok && fill_pack_push(fp, (float*)psync, 0, 1, (long)gru_persist_sync_words(B, groups), 0, 1);
+      for (int l = 0; l < L && ok; ++l) {
+        ok = ok && fill_pack_push(fp, reg(c->hs[l]), 0, 1, (long)B * H, c->hs[l].stride, groups);
+        if (bf && gru_fused_bf16_supported(H) && ntc)
+          ok = ok && fill_pack_push(fp, reg(c->hsT[l]), TB1p / 2, H, B / 2, c->hsT[l].stride, groups);
+      }
+      if (bf && gru_fused_bf16_supported(H))
+        ok = ok && fill_pack_push(fp, reg(c->hb), 0, 1, (long)B * H / 2, c->hb.stride, groups);
+      if (ok) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_fill_pack(fp, s));
+        cleared = true;
+      }
+    }
     for (int l = 0; l < L; ++l) {
       const std::string p = "l" + std::to_string(l);
       float* hs = reg(c->hs[l]);
       float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
       role = HPSGD_ROLE_OTHER;
-      HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s, l == 0 ? (float*)psync : nullptr,
-                               l == 0 && psync ? gru_persist_sync_words(B, groups) : 0));
+      if (!cleared)
+        HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s, l == 0 ? (float*)psync : nullptr,
+                                 l == 0 && psync ? gru_persist_sync_words(B, groups) : 0));
       const float* Whh = rin + c->off(p + ".W_hh");
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
@@ -624,9 +649,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_OTHER;
         if (!wc.whh[l]) return HPSGD_ESHAPE;  // (bf16 precision allocates the per-layer copies)
         whhT_ready[l] = wc.whhT[l];
-        HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
-        if (hT)  // h_0 = 0: the first B columns of the transposed copy
-          HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
+        if (!cleared) {
+          HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
+          if (hT)  // h_0 = 0: the first B columns of the transposed copy
+            HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
+        }
       }
       // one event pair around the whole time loop when its launches are all of one role
       const bool persist_b = fused_b && use_persist_b && hT != nullptr;

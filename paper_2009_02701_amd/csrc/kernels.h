@@ -27,6 +27,18 @@ hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K
 hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s, float* extra = nullptr,
                             size_t n_extra = 0);
 // p[g*stride + r*ld + c] = 0 for r < rows, c < cols (4-byte words)
+// Up to MAXSEG clears in one launch.  pk.n = 0, pk.blk0[0] = 0, pk.max_groups = 0 are set by the caller.
+struct FillSeg {
+  float* p; long ld; int rows; long cols; size_t stride; int groups;
+};
+struct FillPack {
+  static constexpr int MAXSEG = 12;
+  FillSeg seg[MAXSEG];
+  unsigned blk0[MAXSEG + 1];
+  int n, max_groups;
+};
+bool fill_pack_push(FillPack& pk, float* p, long ld, int rows, long cols, size_t stride, int groups);
+hipError_t launch_fill_pack(const FillPack& pk, hipStream_t s);
 hipError_t launch_fill_zero_2d(float* p, long ld, int rows, int cols, size_t stride, int groups,
                                hipStream_t s);
 hipError_t launch_gather(const void* shard, const int32_t* idx, int n_idx, size_t row_bytes,

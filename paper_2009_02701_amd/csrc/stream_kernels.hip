@@ -378,6 +378,42 @@ hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipSt
   return hipGetLastError();
 }
 
+// Several such clears in one launch (the h_0 slots and flag words a step clears before its first
+// layer: each a few microseconds behind a launch); segment i owns grid columns blk0[i] .. blk0[i+1]-1.
+// Segment: p[g*stride + r*ld + c] = 0 for r < rows, c < cols, g < its groups.
+__global__ void __launch_bounds__(kThreads) fill_zero_multi_kernel(FillPack pk) {
+  int sgi = 0;
+#pragma unroll
+  for (int i = 1; i < FillPack::MAXSEG; ++i)
+    if (i < pk.n && blockIdx.x >= pk.blk0[i]) sgi = i;
+  const FillSeg& sg = pk.seg[sgi];
+  if ((int)blockIdx.y >= sg.groups) return;
+  float* pg = sg.p + (size_t)blockIdx.y * sg.stride;
+  const long n = (long)sg.rows * sg.cols;
+  const unsigned nblk = pk.blk0[sgi + 1] - pk.blk0[sgi];
+  for (long i = (long)(blockIdx.x - pk.blk0[sgi]) * kThreads + threadIdx.x; i < n; i += (long)nblk * kThreads)
+    pg[(i / sg.cols) * sg.ld + i % sg.cols] = 0.f;
+}
+
+bool fill_pack_push(FillPack& pk, float* p, long ld, int rows, long cols, size_t stride, int groups) {
+  if (pk.n >= FillPack::MAXSEG || !p || rows <= 0 || cols <= 0 || groups <= 0) return false;
+  FillSeg& sg = pk.seg[pk.n];
+  sg.p = p; sg.ld = ld; sg.rows = rows; sg.cols = cols; sg.stride = stride; sg.groups = groups;
+  const long n = (long)rows * cols;
+  long blocks = (n + kThreads - 1) / kThreads;
+  if (blocks > 64) blocks = 64;
+  pk.blk0[pk.n + 1] = pk.blk0[pk.n] + (unsigned)blocks;
+  if (groups > pk.max_groups) pk.max_groups = groups;
+  ++pk.n;
+  return true;
+}
+
+hipError_t launch_fill_pack(const FillPack& pk, hipStream_t s) {
+  if (pk.n == 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_zero_multi_kernel, dim3(pk.blk0[pk.n], pk.max_groups), dim3(kThreads), 0, s, pk);
+  return hipGetLastError();
+}
+
 // p[g*stride + r*ld + c] = 0 for r < rows, c < cols: a column block of a row-major matrix
 __global__ void __launch_bounds__(kThreads)
 fill_zero_2d_kernel(float* p, long ld, int rows, int cols, size_t stride) {
