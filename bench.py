@@ -24,9 +24,17 @@ PEAK_HBM_GBS = 8000.0
 # HBM bytes per launch of a role's kernel on the default workload (one launch = the recurrence of
 # all 35 time steps of the layer, all 4 workers), from two rocprofv3 --pmc runs
 # (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration with a plain 1 GiB copy kernel;
-# summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Other workloads: not collected (null).
+# summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Configs 3 and 4: the role's launches of one
+# step added up and divided by the launches the role's timer counts, like `achieved`
+# (profiles/pmc_hbm_traffic_gru_lm_and_mlp.md).  Other roles: not collected (null).
 MEASURED_TRAFFIC_BYTES = {
     "gru_cls": {"gemm_recurrent_bwd": (2.0 * 84280.5 + 133496.3) * 1024, "gemm_recurrent_fwd": (2.0 * 27504.8 + 89880.0) * 1024},
+    # logits GEMM + head dX + head dW with update + bias-gradient reduction, 5 timed launches
+    "gru_lm": {"gemm_head": ((2.0 * 185896.3 + 351619.4) + (2.0 * 168394.5 + 35840.0) + (2.0 * 296277.5 + 320924.6)
+                             + (2.0 * 22242.0 + 312.5)) * 1024 / 5},
+    # dX and dW GEMMs of layers 3 and 2, dW of layer 1, the bias/loss column sums: 6 launches
+    "mlp": {"mlp_bwd": ((2.0 * 4942.5 + 8192.0) + (2.0 * 5017.5 + 710.3) + (2.0 * 41198.8 + 8192.0)
+                        + (2.0 * 37054.7 + 65536.4) + (2.0 * 29373.9 + 50233.4) + (2.0 * 8337.2 + 136.3)) * 1024 / 6},
 }
 
 
