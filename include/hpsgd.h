@@ -219,7 +219,7 @@ int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *sn
  * With an auxiliary stream set (hpsgd_set_aux_stream) some launches run beside others: the
  * bf16 head's two backward GEMMs share one pair (counted as two launches), and a launch
  * that the library issues on the auxiliary stream alone (a layer's input-gradient GEMM beside
- * its weight-gradient GEMMs, the copy of the head's weights) is not timed. */
+ * its weight-gradient GEMMs) is not timed. */
 enum hpsgd_role {
   HPSGD_ROLE_OTHER = 0,        /* zero fills */
   HPSGD_ROLE_GEMM_INPUT = 1,   /* time-batched input projection  X W_ih^T */

@@ -31,18 +31,25 @@ cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restric
   const int g = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
   const TIN* src = in + g * s_in;
+  // All four loads are issued before anything waits for one (clamped addresses instead of
+  // branches: behind a branch each load would be waited for, and stored, before the next is issued).
+  const int c = c0 + 4 * tx;
+  const bool c_ok = c < C;
+  const int cl = c_ok ? c : C - 4;
+  bf16x4 v[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = load4_as_bf16(src + (long)min(r0 + ty + 16 * i, R - 1) * ld_in + cl);
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int rl = ty + 16 * i, r = r0 + rl, c = c0 + 4 * tx;
-    bf16x4 v;
-    v[0] = v[1] = v[2] = v[3] = (__bf16)0.f;
-    if (r < R && c < C) {
-      v = load4_as_bf16(src + (long)r * ld_in + c);
-      if (out_p) *reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c) = v;
+    const int rl = ty + 16 * i, r = r0 + rl;
+    if (r < R && c_ok) {
+      if (out_p) *reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c) = v[i];
+    } else {
+      v[i][0] = v[i][1] = v[i][2] = v[i][3] = (__bf16)0.f;
     }
     if (out_t) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e) tile[4 * tx + e][rl] = v[e];
+      for (int e = 0; e < 4; ++e) tile[4 * tx + e][rl] = v[i][e];
     }
   }
   if (!out_t) return;

@@ -535,27 +535,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
         softmax_ce_bf16_supported(logits, s_log, bfreg(c->dlogb), clp, s_dlb, classes) &&
         cvt2_supported(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes);
-    // The head's weights are not needed before the recurrences of all layers are through: with
-    // an auxiliary stream their bf16 copies (a pass over the largest matrix of the model) are
-    // made beside those launches, which wait on each other most of the time and leave the
-    // memory system idle.
     // the layers' bf16 weight copies: all at the start (nothing but the replicas feeds them),
     // unless they were made before the step
     WeightCopies wc;
     role = HPSGD_ROLE_OTHER;
     TRY(weight_copies(c, rin, sR, k0, groups, ws, s, !prepared, false, wc));
-    bool head_w_on_aux = false;
-    auto head_w_beside = [&]() -> int {  // called right before the first resident-weight launch
-      if (prepared || head_w_on_aux || !(headb && c->aux && c->ev_fork && c->ev_join)) return HPSGD_OK;
-      if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
-        return HPSGD_EHIP;
-      if (launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H, groups,
-                      c->aux) != hipSuccess)
-        return HPSGD_EHIP;
-      if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
-      head_w_on_aux = true;
-      return HPSGD_OK;
-    };
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -657,7 +641,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       // one event pair around the whole time loop when its launches are all of one role
       const bool persist_b = fused_b && use_persist_b && hT != nullptr;
-      if (persist_b) TRY0(head_w_beside());
       TimerScope loop_fwd(c, HPSGD_ROLE_GEMM_REC_FWD, s, (persist || persist_b) ? 1 : (fused || fused_b) ? T : 0);
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
@@ -711,9 +694,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const float* feats = lm ? top + (size_t)B * H : top + (size_t)T * B * H;
     if (headb) {
       role = HPSGD_ROLE_OTHER;
-      if (head_w_on_aux) {
-        if (hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
-      } else if (!prepared) {
+      // the bf16 copies of the head's weights: here, when the synchronising stream has finished and
+      // the copy has the memory system to itself (beside a resident-weight launch it takes 2.3
+      // times as long and slows that launch by more than it takes alone; at the start of the step it
+      // shares the bandwidth with the merge and the clone)
+      if (!prepared) {
         HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             groups, s));
       }
