@@ -1,15 +1,18 @@
 #!/usr/bin/env python3
 """Benchmark of the HPSGD hot path on one MI355X.
 
-One "step" is one round of the overlapped schedule on the GRU classifier workload
-(config 2: I128 H512 T35 B64, K=4 workers, fp32): batch gather, local step of all K workers
-(forward, BPTT, SGD commit) on stream A, merge of the previous round on stream B, and the
-replica sync at the round boundary.  Inputs (shards, parameters) are resident in HBM before
-the timed region.  Prints ONE JSON line.
+One "step" is one round of the overlapped schedule (Sec. 3.1): batch gather and local step of
+all K workers (forward, BPTT, SGD commit) on the training stream, merge of the previous round's
+replica changes and the clone of the global model on the synchronising stream.  The default
+workload is the GRU language model (config 3: V10000 E256 H1024 L2 T35 B32, K=8, bf16 GEMM
+operands / fp32 accumulate), the largest configuration that runs on one GPU; `--workload`
+selects configs 1, 2, 4.  Inputs (shards, parameters) are resident in HBM before the timed
+region.  Prints ONE JSON line.
 """
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -21,20 +24,18 @@ PEAK_FP32_MFMA_TFLOPS = 157.3
 PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
-# HBM bytes per launch of a role's kernel on the default workload (one launch = the recurrence of
-# all 35 time steps of the layer, all 4 workers), from two rocprofv3 --pmc runs
-# (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after calibration with a plain 1 GiB copy kernel;
-# summary in profiles/pmc_hbm_traffic_gru_cls_and_merge.md).  Configs 3 and 4: the role's launches of one
-# step added up and divided by the launches the role's timer counts, like `achieved`
-# (profiles/pmc_hbm_traffic_gru_lm_and_mlp.md).  Other roles: not collected (null).
+# Kernels whose work is counted in bytes (HBM roofline); every other timed kernel is a contraction.
+STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel"}
+
+# HBM bytes per launch of a kernel, from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
+# WRITE_SIZE, in KiB per dispatch; FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 after calibration
+# with a plain copy kernel of known size), averaged over the kernel's launches.  Summaries with the
+# full commands: profiles/pmc_hbm_traffic_*.md.  Kernels not collected: null.
 MEASURED_TRAFFIC_BYTES = {
-    "gru_cls": {"gemm_recurrent_bwd": (2.0 * 84280.5 + 133496.3) * 1024, "gemm_recurrent_fwd": (2.0 * 27504.8 + 89880.0) * 1024},
-    # logits GEMM + head dX + head dW with update + bias-gradient reduction, 5 timed launches
-    "gru_lm": {"gemm_head": ((2.0 * 185896.3 + 351619.4) + (2.0 * 168394.5 + 35840.0) + (2.0 * 296277.5 + 320924.6)
-                             + (2.0 * 22242.0 + 312.5)) * 1024 / 5},
-    # dX and dW GEMMs of layers 3 and 2, dW of layer 1, the bias/loss column sums: 6 launches
-    "mlp": {"mlp_bwd": ((2.0 * 4942.5 + 8192.0) + (2.0 * 5017.5 + 710.3) + (2.0 * 41198.8 + 8192.0)
-                        + (2.0 * 37054.7 + 65536.4) + (2.0 * 29373.9 + 50233.4) + (2.0 * 8337.2 + 136.3)) * 1024 / 6},
+    "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 84280.5 + 133496.3) * 1024,
+                "gru_fwd_persist_kernel": (2.0 * 27504.8 + 89880.0) * 1024},
+    "gru_lm": {},
+    "mlp": {},
 }
 
 
@@ -74,54 +75,40 @@ def mfma_probe(hb, torch, dev, prec):
     return out
 
 
-def role_work_per_step(cfg, role_name, commit_params=None, fused=(0, 0, 0)):
-    """Algorithmic work of ALL launches of a role in one local step of all K workers:
-    (bound, flops or bytes per step, peak in the same unit per second).  commit_params: how many
-    parameters per worker the commit kernel handled (the rest are updated in GEMM epilogues).
-    fused = (resident, xproj, dw) from Context.recurrence_info(): the bottom `xproj` layers' input
-    projections are part of the forward recurrence launches and the top-to-bottom first `dw`
-    layers' dW_hh products part of the backward ones (every layer when dw == layers), so their
-    flops are counted with those roles."""
-    kind, K, B = cfg["kind"], cfg["K"], cfg["batch"]
-    mfma_peak = (PEAK_BF16_MFMA_TFLOPS if cfg.get("prec") == "bf16" else PEAK_FP32_MFMA_TFLOPS) * 1e12
-    hbm = PEAK_HBM_GBS * 1e9
-    if kind == "mlp":
-        d = cfg["dims"]
-        fwd = sum(2.0 * B * d[i] * d[i + 1] for i in range(len(d) - 1)) * K
-        bwd = (sum(2.0 * B * d[i] * d[i + 1] for i in range(len(d) - 1))
-               + sum(2.0 * B * d[i] * d[i + 1] for i in range(1, len(d) - 1))) * K
-        P = sum(d[i] * d[i + 1] + d[i + 1] for i in range(len(d) - 1))
-        if commit_params is not None:
-            P = commit_params
-        return {"mlp_fwd": ("mfma", fwd, mfma_peak), "mlp_bwd": ("mfma", bwd, mfma_peak),
-                "commit": ("hbm", 12.0 * P * K, hbm)}.get(role_name, (None, None, None))
-    T, H, L = cfg["seq_len"], cfg["hidden"], cfg["layers"]
-    TB = T * B
-    lm = kind == "gru_lm"
-    widths = [cfg["embed"] if lm else cfg["input"]] + [H] * (L - 1)
-    classes = cfg["vocab"] if lm else cfg["classes"]
-    nrows = TB if lm else B
-    P = sum(3 * H * w + 3 * H * H + 6 * H for w in widths) + classes * H + classes + (cfg["vocab"] * cfg["embed"] if lm else 0)
-    if commit_params is not None:
-        P = commit_params
-    _, n_xproj, n_dw = fused
-    # a layer's input projection is fused only where its input is narrow: the narrowest first
-    xproj_flops = sum(sorted(2.0 * TB * 3 * H * w for w in widths)[:n_xproj]) * K
-    dw_flops = n_dw * 2.0 * 3 * H * H * TB * K
-    table = {
-        "gemm_input_projection": ("mfma", sum(2.0 * TB * 3 * H * w for w in widths) * K - xproj_flops, mfma_peak),
-        "gemm_recurrent_fwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K + xproj_flops, mfma_peak),
-        "gemm_recurrent_bwd": ("mfma", 2.0 * B * 3 * H * H * T * L * K + dw_flops, mfma_peak),
-        "gemm_weight_grad": ("mfma", sum(2.0 * 3 * H * w * TB + 2.0 * 3 * H * H * TB for w in widths) * K - dw_flops,
-                             mfma_peak),
-        "gemm_input_grad": ("mfma", sum(2.0 * TB * 3 * H * w for w in (widths if lm else widths[1:])) * K, mfma_peak),
-        "gemm_head": ("mfma", 3 * 2.0 * nrows * classes * H * K, mfma_peak),
-        "gru_cell_fwd": ("hbm", 48.0 * B * H * T * L * K, hbm),
-        "gru_cell_bwd": ("hbm", 56.0 * B * H * T * L * K, hbm),
-        "softmax_ce": ("hbm", 8.0 * nrows * classes * K, hbm),
-        "commit": ("hbm", 12.0 * P * K, hbm),
-    }
-    return table.get(role_name, (None, None, None))
+def samples_per_round(cfg):
+    return cfg["K"] * cfg["batch"] * (cfg["seq_len"] if cfg["kind"] == "gru_lm" else 1)
+
+
+def make_trainer(wl, harness, name, dev, prepare=False):
+    cfg = wl.CONFIGS[name]
+    K = cfg["K"]
+    init = wl.init_params(cfg)
+    shards = [wl.make_shard(cfg, k) for k in range(K)]
+    orders = [wl.batch_order(cfg, k) for k in range(K)]
+    return cfg, init, shards, harness.Trainer(cfg, init, shards, orders, device=dev, prepare=prepare)
+
+
+def timed_rounds(torch, tr, lr, step, n):
+    """n overlapped rounds bracketed by device synchronisation; returns (seconds, next step)."""
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        tr.ovl_round(step, lr)
+        step += 1
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, step
+
+
+def quick_workload(torch, wl, harness, name, dev, rounds=100, warmup=10):
+    """Throughput of another configuration in the same overlapped schedule (an extra key of the line)."""
+    cfg, _, _, tr = make_trainer(wl, harness, name, dev)
+    tr.ovl_begin()
+    _, step = timed_rounds(torch, tr, cfg["lr"], 0, warmup)
+    el, step = timed_rounds(torch, tr, cfg["lr"], step, rounds)
+    tr.ovl_drain()
+    unit = "tokens/s" if cfg["kind"] == "gru_lm" else "samples/s"
+    return {"workload": WORKLOAD_TEXT[name], "value": samples_per_round(cfg) * rounds / el, "unit": unit,
+            "ms_per_step": 1e3 * el / rounds, "steps": rounds}
 
 
 def main():
@@ -131,147 +118,179 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-merge-stress", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the other configurations, the schedule comparisons and the matrix-core probe")
     ap.add_argument("--prepare", action="store_true",
                     help="make the next step's bf16 weight copies on the synchronising stream (measured slower)")
-    ap.add_argument("--workload", default="gru_cls", choices=["gru_cls", "gru_lm", "mlp", "tiny_gru"],
-                    help="default: config 2, the one the headline metric is quoted on")
+    ap.add_argument("--workload", default="gru_lm", choices=["gru_cls", "gru_lm", "mlp", "tiny_gru"],
+                    help="default: config 3, the largest configuration that fits one GPU")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (K workers are a group dimension on it); "
               "--gpus must be 1", file=sys.stderr)
         sys.exit(2)
 
-    import numpy as np
     import torch
     from paper_2009_02701_amd import binding as hb
     from paper_2009_02701_amd import harness, workloads as wl
 
     dev = "cuda:0"
-    cfg = wl.CONFIGS[args.workload]
+    cfg, init, shards, tr = make_trainer(wl, harness, args.workload, dev, args.prepare)
     K, B, lr = cfg["K"], cfg["batch"], cfg["lr"]
-    init = wl.init_params(cfg)
-    shards = [wl.make_shard(cfg, k) for k in range(K)]
-    orders = [wl.batch_order(cfg, k) for k in range(K)]
-    tr = harness.Trainer(cfg, init, shards, orders, device=dev, prepare=args.prepare)
-    names = tr.ctx.role_names()
+    knames = tr.ctx.kernel_names()
+    per_round = samples_per_round(cfg)
+    unit = "tokens/s" if cfg["kind"] == "gru_lm" else "samples/s"
+    mfma_peak = (PEAK_BF16_MFMA_TFLOPS if cfg.get("prec") == "bf16" else PEAK_FP32_MFMA_TFLOPS) * 1e12
 
-    # ---- pass 0: which role dominates the local step (all roles timed, a few rounds)
+    # ---- pass 0: every timed kernel with an event pair of its own, a few rounds: which single
+    # kernel takes the most time of a round
     tr.ovl_begin()
-    for t in range(3):
-        tr.ovl_round(t, lr)
-    torch.cuda.synchronize()
-    tr.ctx.timer_enable(range(hb.ROLE_COUNT))
+    _, step = timed_rounds(torch, tr, lr, 0, 3)
+    tr.ctx.kernel_timer_enable(range(1, hb.KERNEL_COUNT))
     probe_rounds = 5
-    for t in range(probe_rounds):
-        tr.ovl_round(3 + t, lr)
-    torch.cuda.synchronize()
-    breakdown = {}
-    for r, nm in enumerate(names):
-        n, ms = tr.ctx.timer_read(r)
+    _, step = timed_rounds(torch, tr, lr, step, probe_rounds)
+    kernels = {}
+    for kid in range(1, hb.KERNEL_COUNT):
+        n, ms, work = tr.ctx.kernel_timer_read(kid)
         if n:
-            breakdown[nm] = {"launches_per_step": n / probe_rounds, "avg_us": 1e3 * ms / n,
-                             "us_per_step": 1e3 * ms / probe_rounds}
-    commit_params = tr.ctx.commit_kernel_params()
+            streaming = knames[kid] in STREAMING_KERNELS
+            peak = PEAK_HBM_GBS * 1e9 if streaming else mfma_peak
+            kernels[knames[kid]] = {"id": kid, "launches_per_step": n / probe_rounds, "avg_us": 1e3 * ms / n,
+                                    "us_per_step": 1e3 * ms / probe_rounds, "bound": "hbm" if streaming else "mfma",
+                                    "frac_of_peak": work / (ms * 1e-3) / peak}
+    tr.ctx.kernel_timer_enable([])
+    dominant = max(kernels, key=lambda k: kernels[k]["us_per_step"])
+    dom_id = kernels[dominant]["id"]
     fused = tr.ctx.recurrence_info()
-    dominant = max(breakdown, key=lambda k: breakdown[k]["us_per_step"])
-    dom_role = names.index(dominant)
-    tr.ctx.timer_enable([dom_role])
 
     # ---- warm-up, then the timed region: `value` comes from K rounds with no instrumentation
-    tr.ctx.timer_enable([])
-    step = 3 + probe_rounds
-    for t in range(args.warmup):
-        tr.ovl_round(step, lr)
-        step += 1
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(args.steps):
-        tr.ovl_round(step, lr)
-        step += 1
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = 1e3 * (t1 - t0) / args.steps
-    samples_per_step = K * B * (cfg["seq_len"] if cfg["kind"] == "gru_lm" else 1)
-    unit = "tokens/s" if cfg["kind"] == "gru_lm" else "samples/s"
-    value = samples_per_step / (ms_per_step * 1e-3)
+    _, step = timed_rounds(torch, tr, lr, step, args.warmup)
+    elapsed, step = timed_rounds(torch, tr, lr, step, args.steps)
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = per_round / (ms_per_step * 1e-3)
 
-    # ---- the same region once more with HIP event pairs around every launch of the dominant
-    # role (on the stream the kernels run on): the roofline's launch duration
-    tr.ctx.timer_enable([dom_role])
-    tr.ctx.timer_read(dom_role)
-    t2 = time.perf_counter()
-    for t in range(args.steps):
+    # ---- the spread: every round of a second pass between two events on the training stream
+    n_spread = max(20, min(args.steps, 100))
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_spread + 1)]
+    torch.cuda.synchronize()
+    evs[0].record(tr.stream_a)
+    for i in range(n_spread):
         tr.ovl_round(step, lr)
         step += 1
+        evs[i + 1].record(tr.stream_a)
     torch.cuda.synchronize()
-    t3 = time.perf_counter()
-    n_dom, ms_dom = tr.ctx.timer_read(dom_role)
-    tr.ctx.timer_enable([])
+    per_round_ms = [evs[i].elapsed_time(evs[i + 1]) for i in range(n_spread)]
+    spread = {"rounds": n_spread, "median_ms": statistics.median(per_round_ms), "min_ms": min(per_round_ms),
+              "max_ms": max(per_round_ms), "mean_ms": sum(per_round_ms) / n_spread}
+
+    # ---- the same region once more with a HIP event pair around every launch of the dominant
+    # kernel only (recorded by its launcher on the stream the launch goes to): the roofline's
+    # launch duration, and the kernel's algorithmic work as its launcher counts it
+    tr.ctx.kernel_timer_enable([dom_id])
+    el_i, step = timed_rounds(torch, tr, lr, step, args.steps)
+    n_dom, ms_dom, work_dom = tr.ctx.kernel_timer_read(dom_id)
+    tr.ctx.kernel_timer_enable([])
     tr.ovl_drain()
-    ms_per_step_instrumented = 1e3 * (t3 - t2) / args.steps
+    streaming = dominant in STREAMING_KERNELS
+    peak = PEAK_HBM_GBS * 1e9 if streaming else mfma_peak
+    scale = 1e9 if streaming else 1e12
+    dur = ms_dom * 1e-3 / n_dom
+    ach = work_dom / n_dom / dur
+    roofline = {"kernel": dominant, "bound": "hbm" if streaming else "mfma", "achieved": ach / scale,
+                "peak": peak / scale, "unit": "GB/s" if streaming else "TFLOP/s", "frac": ach / peak,
+                "avg_launch_us": dur * 1e6, "launches_timed": n_dom, "launches_per_step": n_dom / args.steps,
+                "work_per_launch": work_dom / n_dom,
+                "ms_per_step_with_event_pairs": 1e3 * el_i / args.steps,
+                "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)}
 
-    # ---- the asynchronous driver (Alg. 2 + Alg. 3 with the status check at run time): the same
-    # kernels, the number of local steps per synchronisation decided by whether stream B is idle;
-    # once as is, once with a synthetic synchronisation latency of about 2.5 local steps
-    async_driver = []
-    for delay in (0, int(2.5e3 * ms_per_step)):
-        torch.cuda.synchronize()
-        a0 = time.perf_counter()
-        counts = tr.s_async(lr, 60, sync_delay_us=delay)
-        a1 = time.perf_counter()
-        async_driver.append({"sync_delay_us": delay, "local_steps": 60, "rounds": len(counts),
-                             "max_steps_per_round": max(counts), "value": 60 * samples_per_step / (a1 - a0),
-                             "unit": unit})
+    # ---- overlap (Sec. 3.1 / 3.2): the training side alone (gather + local step, no exchange), the
+    # synchronising side alone (merge + clone), the blocking order of the two, and the overlapped
+    # round.  efficiency = (t_A + t_B) / t_overlapped: 1 = nothing hidden, (t_A + t_B) / max(t_A, t_B)
+    # = everything hidden (what Sec. 3.2's count gives for gamma = 1 and t_sync = k t_train, k < 1).
+    n_ov = max(20, min(args.steps, 60))
+    tr.s_psgd(lr, 5, record_loss=False)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    tr.s_psgd(lr, n_ov, record_loss=False)
+    t_a = (time.perf_counter() - c0) / n_ov
+    sb = tr.stream_b
+    for _ in range(3):
+        tr.merge(0, sb)
+        tr.sync_all(0, sb)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    for _ in range(n_ov):
+        tr.merge(0, sb)
+        tr.sync_all(0, sb)
+    torch.cuda.synchronize()
+    t_b = (time.perf_counter() - c0) / n_ov
+    tr.s_seq(lr, 1, 5, record_loss=False)
+    torch.cuda.synchronize()
+    c0 = time.perf_counter()
+    tr.s_seq(lr, 1, n_ov, record_loss=False)
+    t_blocking = (time.perf_counter() - c0) / n_ov
+    t_ovl = ms_per_step * 1e-3
+    overlap = {"t_train_ms": 1e3 * t_a, "t_sync_ms": 1e3 * t_b, "t_blocking_round_ms": 1e3 * t_blocking,
+               "t_overlapped_round_ms": 1e3 * t_ovl, "overlap_efficiency": (t_a + t_b) / t_ovl,
+               "all_hidden_would_be": (t_a + t_b) / max(t_a, t_b),
+               "hidden_fraction_of_sync": max(0.0, min(1.0, (t_a + t_b - t_ovl) / t_b)), "rounds": n_ov}
 
-    # ---- the paper's comparison in shape (Sec. 4.3): the same 64 local steps under the same
-    # synthetic synchronisation latency with the blocking schedules (synchronous SGD, Local SGD
-    # with gamma = 8, Sec. 4.1) and with the overlapped asynchronous one
-    delay = int(2.5e3 * ms_per_step)
-    compare = {"sync_delay_us": delay, "local_steps": 64, "unit": unit}
-    for name, run in (("ssgd_blocking", lambda: tr.s_seq(lr, 1, 64, record_loss=False, sync_delay_us=delay)),
-                      ("local_sgd_gamma8_blocking", lambda: tr.s_seq(lr, 8, 8, record_loss=False, sync_delay_us=delay)),
-                      ("hpsgd_async", lambda: tr.s_async(lr, 64, sync_delay_us=delay)),
-                      ("psgd_no_sync", lambda: tr.s_psgd(lr, 64, record_loss=False))):
-        torch.cuda.synchronize()
-        c0 = time.perf_counter()
-        run()
-        compare[name] = 64 * samples_per_step / (time.perf_counter() - c0)
+    async_driver, compare, forms, others, probe = None, None, None, None, None
+    if not args.no_extras:
+        # ---- the asynchronous driver (Alg. 2 + Alg. 3 with the status check at run time): the same
+        # kernels, the number of local steps per synchronisation decided by whether stream B is idle;
+        # once as is, once with a synthetic synchronisation latency of about 2.5 local steps
+        async_driver = []
+        for delay in (0, int(2.5e3 * ms_per_step)):
+            torch.cuda.synchronize()
+            a0 = time.perf_counter()
+            counts = tr.s_async(lr, 60, sync_delay_us=delay)
+            a1 = time.perf_counter()
+            async_driver.append({"sync_delay_us": delay, "local_steps": 60, "rounds": len(counts),
+                                 "max_steps_per_round": max(counts), "value": 60 * per_round / (a1 - a0),
+                                 "unit": unit})
 
-    # gradient-form synchronisation (Eq. 1 as printed): blocking rounds of one local step, for the
-    # cost of accumulating gradients (no update in GEMM epilogues) next to the delta form
-    forms = {"unit": unit}
-    for name, run in (("delta_form_s_seq", lambda: tr.s_seq(lr, 1, 32, record_loss=False)),
-                      ("gradient_form_s_seq_grad", lambda: tr.s_seq_grad(lr, 1, 32, record_loss=False))):
-        run()
-        torch.cuda.synchronize()
-        c0 = time.perf_counter()
-        run()
-        forms[name] = 32 * samples_per_step / (time.perf_counter() - c0)
+        # ---- the paper's comparison in shape (Sec. 4.3): the same 64 local steps under the same
+        # synthetic synchronisation latency with the blocking schedules (synchronous SGD, Local SGD
+        # with gamma = 8, Sec. 4.1) and with the overlapped asynchronous one
+        delay = int(2.5e3 * ms_per_step)
+        compare = {"sync_delay_us": delay, "local_steps": 64, "unit": unit}
+        for name, run in (("ssgd_blocking", lambda: tr.s_seq(lr, 1, 64, record_loss=False, sync_delay_us=delay)),
+                          ("local_sgd_gamma8_blocking", lambda: tr.s_seq(lr, 8, 8, record_loss=False, sync_delay_us=delay)),
+                          ("hpsgd_async", lambda: tr.s_async(lr, 64, sync_delay_us=delay)),
+                          ("psgd_no_sync", lambda: tr.s_psgd(lr, 64, record_loss=False))):
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            run()
+            compare[name] = 64 * per_round / (time.perf_counter() - c0)
 
-    bound, work, peak = role_work_per_step(cfg, dominant, commit_params, fused)
-    roofline = None
-    if bound is not None and n_dom:
-        dur = ms_dom * 1e-3 / n_dom
-        ach = work / breakdown[dominant]["launches_per_step"] / dur
-        scale = 1e12 if bound == "mfma" else 1e9
-        roofline = {"kernel": dominant, "bound": bound, "achieved": ach / scale, "peak": peak / scale,
-                    "unit": "TFLOP/s" if bound == "mfma" else "GB/s", "frac": ach / peak,
-                    "avg_launch_us": dur * 1e6, "launches_timed": n_dom,
-                    "ms_per_step_with_event_pairs": ms_per_step_instrumented,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.workload, {}).get(dominant)}
-    for nm, v in breakdown.items():
-        b_, w_, p_ = role_work_per_step(cfg, nm, commit_params, fused)
-        if b_ is not None:
-            v["frac_of_peak"] = w_ / (v["us_per_step"] * 1e-6) / p_
-            v["bound"] = b_
+        # gradient-form synchronisation (Eq. 1 as printed): blocking rounds of one local step, for the
+        # cost of accumulating gradients (no update in GEMM epilogues) next to the delta form
+        forms = {"unit": unit}
+        for name, run in (("delta_form_s_seq", lambda: tr.s_seq(lr, 1, 32, record_loss=False)),
+                          ("gradient_form_s_seq_grad", lambda: tr.s_seq_grad(lr, 1, 32, record_loss=False))):
+            run()
+            torch.cuda.synchronize()
+            c0 = time.perf_counter()
+            run()
+            forms[name] = 32 * per_round / (time.perf_counter() - c0)
+        # what a pure-MFMA loop of this workload's operand type sustains on this chip right now
+        prec = "bf16" if cfg.get("prec") == "bf16" else "fp32"
+        probe = {"dtype": prec, **mfma_probe(hb, torch, dev, prec)}
+
+    del tr
+    torch.cuda.empty_cache()
+    if not args.no_extras:
+        # ---- the other single-GPU configurations in the same schedule (parity cases; extra keys)
+        others = {name: quick_workload(torch, wl, harness, name, dev)
+                  for name in ("gru_cls", "mlp", "gru_lm") if name != args.workload}
+        torch.cuda.empty_cache()
 
     # ---- merge-only stress (config 5): merge + sync of 100M floats, K = 8, pure HBM streaming
     merge_stress = None
     if not args.no_merge_stress:
         c5 = wl.CONFIGS["merge_stress"]
         P5, K5, iters = c5["P"], c5["K"], c5["iters"]
-        del tr
-        torch.cuda.empty_cache()
         gen = torch.Generator(device=dev).manual_seed(wl.BASE_SEED)
         G = torch.rand(P5, device=dev, generator=gen) * 2 - 1
         S = torch.empty_like(G)
@@ -293,8 +312,9 @@ def main():
             hb.sync_all(G, reps, S)
             ev[2 * i + 2].record(st)
         torch.cuda.synchronize()
-        t_merge = sum(ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(iters)) / iters
-        t_sync = sum(ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(iters)) / iters
+        tm = [ev[2 * i].elapsed_time(ev[2 * i + 1]) for i in range(iters)]
+        ts = [ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(iters)]
+        t_merge, t_sync = sum(tm) / iters, sum(ts) / iters
         bm, bs = 4.0 * (K5 + 3) * P5, 4.0 * (K5 + 2) * P5
         # the gradient-form merge (Eq. 1 as printed) on the same buffers taken as accumulators
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -307,39 +327,57 @@ def main():
         torch.cuda.synchronize()
         t_mg = g0.elapsed_time(g1) / iters
         merge_stress = {
-            "workload": "flat fp32 vector P=1e8, K=8, merge+sync x50",
-            "merge_ms": t_merge, "merge_GBps": bm / t_merge / 1e6, "merge_frac_hbm": bm / t_merge / 1e6 / PEAK_HBM_GBS,
-            "sync_ms": t_sync, "sync_GBps": bs / t_sync / 1e6, "sync_frac_hbm": bs / t_sync / 1e6 / PEAK_HBM_GBS,
+            "workload": "config 5: flat fp32 vector P=1e8, K=8, merge+sync x50",
+            "merge_ms": t_merge, "merge_ms_median": statistics.median(tm), "merge_ms_min": min(tm),
+            "merge_GBps": bm / t_merge / 1e6, "merge_frac_hbm": bm / t_merge / 1e6 / PEAK_HBM_GBS,
+            "sync_ms": t_sync, "sync_ms_median": statistics.median(ts), "sync_ms_min": min(ts),
+            "sync_GBps": bs / t_sync / 1e6, "sync_frac_hbm": bs / t_sync / 1e6 / PEAK_HBM_GBS,
+            "merge_plus_sync_ms": t_merge + t_sync,
             "merge_plus_sync_GBps": (bm + bs) / (t_merge + t_sync) / 1e6,
+            "merge_plus_sync_frac_hbm": (bm + bs) / (t_merge + t_sync) / 1e6 / PEAK_HBM_GBS,
             "merge_grad_ms": t_mg, "merge_grad_GBps": bs / t_mg / 1e6, "merge_grad_frac_hbm": bs / t_mg / 1e6 / PEAK_HBM_GBS,
         }
         del G, S, R, reps
         torch.cuda.empty_cache()
 
     # ---- CPU baseline: the float64 oracle on the host cores, same workload, bounded sample
-    cpu = None
+    cpu, cpu_1t = None, None
     if not args.no_cpu_baseline:
         from oracle import hpsgd_oracle as oc
         try:
-            from threadpoolctl import threadpool_info
+            from threadpoolctl import threadpool_info, threadpool_limits
             cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
         except Exception:
+            threadpool_limits = None
             cores = os.cpu_count()
-        bf = lambda k, s: wl.host_batch(cfg, shards[k], wl.batch_indices(cfg, k, s))
-        oc.s_seq(init, bf, K, lr, gamma=1, rounds=1)   # warm
-        rounds, el = 0, 0.0
-        c0 = time.perf_counter()
-        while el < 10.0 or rounds < 2:
-            oc.s_seq(init, bf, K, lr, gamma=1, rounds=1)
-            rounds += 1
-            el = time.perf_counter() - c0
-        cpu = {"value": samples_per_step * rounds / el, "unit": unit, "cores": int(cores), "kind": "oracle",
+
+        def oracle_rate(name, min_rounds, min_seconds):
+            c = wl.CONFIGS[name]
+            ini = init if name == args.workload else wl.init_params(c)
+            shs = shards if name == args.workload else [wl.make_shard(c, k) for k in range(c["K"])]
+            bf = lambda k, s: oc.gather_batch(c["kind"], shs[k][0], shs[k][1], wl.batch_indices(c, k, s))
+            rounds, el = 0, 0.0
+            c0 = time.perf_counter()
+            while rounds < min_rounds or el < min_seconds:
+                oc.s_seq(ini, bf, c["K"], c["lr"], gamma=1, rounds=1)
+                rounds += 1
+                el = time.perf_counter() - c0
+            return samples_per_round(c) * rounds / el, rounds, el
+
+        # the headline workload: 2 rounds at least (config 3 is about 1.1 TFLOP of float64 per round)
+        v, rounds, el = oracle_rate(args.workload, 2, 10.0 if cfg["kind"] != "gru_lm" else 0.0)
+        cpu = {"value": v, "unit": unit, "cores": int(cores), "kind": "oracle",
                "sample": f"{rounds} rounds of (local step of all {K} workers + merge + sync) on the same "
                          f"{args.workload} inputs, float64 numpy, {el:.1f} s"}
+        # one thread, configs 1, 2 and 4
+        if threadpool_limits is not None and not args.no_extras:
+            cpu_1t = {}
+            with threadpool_limits(limits=1):
+                for name in ("tiny_gru", "gru_cls", "mlp"):
+                    v, rounds, el = oracle_rate(name, 1, 2.0)
+                    cpu_1t[name] = {"value": v, "unit": "samples/s", "cores": 1, "kind": "oracle",
+                                    "sample": f"{rounds} rounds, {el:.1f} s"}
 
-    # what a pure-MFMA loop of this workload's operand type sustains on this chip right now
-    prec = "bf16" if cfg.get("prec") == "bf16" else "fp32"
-    probe = {"dtype": prec, **mfma_probe(hb, torch, dev, prec)}
     out = {
         "metric": "local-step samples/sec (overlapped HPSGD round: gather + local step + merge + sync)",
         "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -347,7 +385,9 @@ def main():
         "dtype": "bf16" if cfg.get("prec") == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
-        "roofline": roofline, "cpu_baseline": cpu, "kernels": breakdown, "merge_stress": merge_stress,
+        "roofline": roofline, "cpu_baseline": cpu, "ms_per_step_spread": spread, "overlap": overlap,
+        "kernels": kernels, "merge_stress": merge_stress, "other_workloads": others,
+        "cpu_baseline_one_thread": cpu_1t,
         "recurrence_launches": {"resident_weight_layers": fused[0], "with_input_projection": fused[1],
                                 "with_dW_hh_and_bias_gradients": fused[2]},
         "mfma_probe": probe, "async_driver": async_driver, "schedules_under_sync_latency": compare,

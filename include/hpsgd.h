@@ -10,10 +10,17 @@
  * Conventions for every entry point
  *   - All data pointers are DEVICE pointers unless a parameter says HOST.
  *   - The caller owns every device buffer, the workspace included.  The library never
- *     allocates or frees device memory and never synchronises, creates or destroys a
- *     stream; the context holds host memory only.
+ *     allocates or frees device memory and never creates or destroys a stream.
+ *   - What the library owns besides host memory: HIP events.  A context creates two when an
+ *     auxiliary stream is set (hpsgd_set_aux_stream) and pairs of them while timing is enabled
+ *     (hpsgd_timer_enable, hpsgd_kernel_timer_enable); hpsgd_destroy frees them.  One more
+ *     event per device lives as long as the process: it is recorded behind the most recent
+ *     resident-weight recurrence launch (hpsgd_set_recurrence) and is, with the stream that
+ *     launch went to and a mutex, the library's only per-process state.
  *   - `hip_stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
- *     enqueue work and return; ordering between streams is the caller's job.
+ *     enqueue work and return without waiting for the device; ordering between streams is the
+ *     caller's job.  Two entry points wait by design and say so: hpsgd_recurrence_gave_up and
+ *     hpsgd_timer_read / hpsgd_kernel_timer_read (they read results back).
  *   - Return value: HPSGD_OK or an error code.  Arguments are validated before
  *     anything is enqueued; on error nothing has been written.
  *   - Parameter buffers (global, snapshot, replicas) must be 16-byte aligned and replica
@@ -30,7 +37,7 @@
 extern "C" {
 #endif
 
-typedef struct hpsgd_ctx hpsgd_ctx; /* opaque, host memory only: shapes, layout table, launch plan */
+typedef struct hpsgd_ctx hpsgd_ctx; /* opaque: shapes, layout table, launch plan (host memory), HIP events */
 
 enum hpsgd_status {
   HPSGD_OK = 0,
@@ -75,7 +82,7 @@ typedef struct hpsgd_model_desc {
 
 /* ---- context --------------------------------------------------------------------------
  * Describes the model every worker trains (Sec. 3.1: each worker runs the same local
- * training phase on its own sub-dataset) and the number of workers K.  Host memory only. */
+ * training phase on its own sub-dataset) and the number of workers K.  No device memory. */
 int hpsgd_create(const hpsgd_model_desc *desc, int K, hpsgd_ctx **out);
 int hpsgd_destroy(hpsgd_ctx *ctx);
 
@@ -154,8 +161,10 @@ int hpsgd_set_aux_stream(hpsgd_ctx *ctx, void *hip_stream);
  * (polls of the flags; 0 makes every wait fail at once, for testing).  A wait that is given up
  * ends the launch early on every workgroup, and the local step then delivers NaN in loss_out
  * and in the first parameter of every output replica; hpsgd_recurrence_gave_up reports it too.
- * Launches of this kind from different streams are serialised by the library (the device is
- * synchronised when the stream changes). */
+ * Launches of this kind need the whole chip and must not run side by side.  The library orders
+ * them itself, across streams, contexts and host threads: a local step holds a per-device lock
+ * while it issues them, and when the previous ones went to another stream it lets its stream
+ * wait (hipStreamWaitEvent, the host does not block) for the event recorded behind them. */
 int hpsgd_set_recurrence(hpsgd_ctx *ctx, int resident, unsigned spin_limit);
 
 /* *gave_up = 1 if a wait of the last local step(s) that used `workspace` was given up, else 0.
@@ -213,8 +222,7 @@ int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *sn
 /* ---- kernel timing for benchmarks (not part of the method) ------------------------------
  * The launches of one local step fall into roles.  While a role's bit is set in the mask,
  * hpsgd_local_step(_all) records a HIP event pair on the caller's stream around every launch
- * group of that role (the only HIP objects the context ever creates; hpsgd_destroy frees
- * them).  hpsgd_timer_read waits for the recorded events, returns the number of timed
+ * group of that role (hpsgd_destroy frees the events).  hpsgd_timer_read waits for the recorded events, returns the number of timed
  * launch groups of `role` and their summed duration in milliseconds, and clears that role.
  * With an auxiliary stream set (hpsgd_set_aux_stream) some launches run beside others: the
  * bf16 head's two backward GEMMs share one pair (counted as two launches), and a launch
@@ -245,6 +253,40 @@ const char *hpsgd_role_name(int role); /* static string, NULL if out of range */
  * The other weight matrices were updated by the epilogue of their own gradient GEMM.  0
  * before the first step.  For the byte accounting of the HPSGD_ROLE_COMMIT timings. */
 size_t hpsgd_commit_kernel_params(const hpsgd_ctx *ctx);
+
+/* The same per KERNEL instead of per role: while a kernel's bit is set in the mask, every launch
+ * of that kernel inside hpsgd_local_step(_all)(_acc) is bracketed by a HIP event pair on the
+ * stream the launch goes to (the auxiliary stream included), and the launch's algorithmic work
+ * is added up: flops (2 M N Kd per group; a recurrence launch 2 B 3H H per time step, plus the
+ * products it fuses) for the contractions, bytes (each operand once) for the streaming kernels.
+ * hpsgd_kernel_timer_read waits for the recorded events, returns the number of timed launches of
+ * `kernel`, their summed duration in milliseconds and their summed work, and clears that kernel.
+ * Names are those a kernel trace shows (template arguments included where they tell forms apart). */
+enum hpsgd_kernel {
+  HPSGD_KERNEL_NONE = 0,
+  HPSGD_KERNEL_GRU_FWD_PERSIST = 1,
+  HPSGD_KERNEL_GRU_BWD_PERSIST = 2,
+  HPSGD_KERNEL_GRU_FWD_PERSIST_BF16 = 3,
+  HPSGD_KERNEL_GRU_BWD_PERSIST_BF16 = 4,
+  HPSGD_KERNEL_GEMM_BF16_DL = 5,
+  HPSGD_KERNEL_GEMM_BF16_DL_COMMIT = 6,
+  HPSGD_KERNEL_GEMM_BF16_DLX128 = 7,
+  HPSGD_KERNEL_GEMM_BF16_DLX128_COMMIT = 8,
+  HPSGD_KERNEL_GEMM_BF16_DLX192 = 9,
+  HPSGD_KERNEL_GEMM_BF16_DLX192_COMMIT = 10,
+  HPSGD_KERNEL_GEMM_BF16_DLX256 = 11,
+  HPSGD_KERNEL_GEMM_BF16_DLX256_COMMIT = 12,
+  HPSGD_KERNEL_GEMM_BF16_NT = 13,
+  HPSGD_KERNEL_GEMM_F32_FAST = 14,
+  HPSGD_KERNEL_GEMM_F32 = 15,
+  HPSGD_KERNEL_CVT2 = 16,           /* streaming: bytes */
+  HPSGD_KERNEL_SOFTMAX_CE_BF16 = 17, /* streaming: bytes */
+  HPSGD_KERNEL_GRU_STEP = 18,
+  HPSGD_KERNEL_COUNT = 19
+};
+int hpsgd_kernel_timer_enable(hpsgd_ctx *ctx, unsigned kernel_mask);
+int hpsgd_kernel_timer_read(hpsgd_ctx *ctx, int kernel, long *launches, double *total_ms, double *work);
+const char *hpsgd_kernel_name(int kernel); /* static string, NULL if out of range */
 
 /* What the recurrence launches of the last local step included (benchmarks: which role the
  * work of a fused part is accounted to).  Each count is a number of GRU layers:

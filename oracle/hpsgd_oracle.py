@@ -13,6 +13,7 @@ What fixes each function:
                      workers: W <- W_prev - mu * sum_i sum_e grad_i^e / n, written
                      with replica_k - snapshot = -mu * (accumulated gradients of k).
   * sync          -- Alg. 2, "make replica": r_i <- clone(w).
+  * gather_batch  -- Sec. 3.2, a worker's mini-batch out of its own sub-dataset (exact copies).
   * model forward / backward -- the paper names a GRU (Sec. 1) and cross-entropy
                      with plain SGD (Sec. 4.1) but prints no model equations; the
                      cell is the one of the library the paper ran on (gate order
@@ -22,7 +23,7 @@ What fixes each function:
                      Alg. 1, by Eq. 2); s_ovl applies each merge one round late,
                      the one-synchronisation delay stated after Alg. 3.
 
-Pins (tests/test_oracle_*.py): central finite differences of every parameter,
+Pins (tests/test_oracle_*.py): a hand-written mini-batch for gather_batch; central finite differences of every parameter,
 a double-precision library GRU with autograd, the T=1 closed form, loss = ln C at
 zero weights, Eq. 2, K identical replicas, K=1 == plain SGD, lr=0, SSGD and
 Local-SGD equivalences, a closed-form delayed recursion on a quadratic.
@@ -268,6 +269,47 @@ def sync(global_):
     if isinstance(global_, dict):
         return {k: np.array(v, copy=True) for k, v in global_.items()}
     return np.array(global_, copy=True)
+
+
+def gather_batch(kind, samples, labels, idx):
+    """A worker's mini-batch, assembled from its own sub-dataset (Sec. 3.2: every worker trains on
+    its sub-dataset) by the sample numbers `idx`, in the layouts the local step takes.  Plain
+    element-by-element copies: the result is exact, whatever the element type.
+
+      kind "gru_cls": samples [N, T, I], labels [N] -> x [T, B, I] (time-major), y [B]
+      kind "mlp":     samples [N, D],    labels [N] -> x [B, D],                 y [B]
+      kind "gru_lm":  samples [N, T+1] token ids (labels unused): a sample is a run of T+1 tokens,
+                      its inputs are the first T and its targets the same run one token later
+                                                   -> x [T, B], y [T, B]
+    """
+    samples = np.asarray(samples)
+    B = len(idx)
+    if kind == "gru_cls":
+        _, T, I = samples.shape
+        x = np.empty((T, B, I), samples.dtype)
+        y = np.empty((B,), np.asarray(labels).dtype)
+        for b in range(B):
+            for t in range(T):
+                x[t, b, :] = samples[idx[b], t, :]
+            y[b] = labels[idx[b]]
+        return x, y
+    if kind == "mlp":
+        x = np.empty((B, samples.shape[1]), samples.dtype)
+        y = np.empty((B,), np.asarray(labels).dtype)
+        for b in range(B):
+            x[b, :] = samples[idx[b], :]
+            y[b] = labels[idx[b]]
+        return x, y
+    if kind == "gru_lm":
+        T = samples.shape[1] - 1
+        x = np.empty((T, B), samples.dtype)
+        y = np.empty((T, B), samples.dtype)
+        for b in range(B):
+            for t in range(T):
+                x[t, b] = samples[idx[b], t]
+                y[t, b] = samples[idx[b], t + 1]
+        return x, y
+    raise ValueError(kind)
 
 
 # ----------------------------------------------------------------------------

@@ -27,8 +27,10 @@ EXPORTS = [
     "hpsgd_commit_kernel_params", "hpsgd_probe_mfma_rate", "hpsgd_delay_us",
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
+    "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
 ]
 ROLE_COUNT = 14
+KERNEL_COUNT = 19
 
 
 class ModelDesc(C.Structure):
@@ -82,6 +84,11 @@ def load_library():
     lib.hpsgd_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double)]
     lib.hpsgd_role_name.argtypes = [C.c_int]
     lib.hpsgd_role_name.restype = C.c_char_p
+    lib.hpsgd_kernel_timer_enable.argtypes = [vp, C.c_uint]
+    lib.hpsgd_kernel_timer_read.argtypes = [vp, C.c_int, C.POINTER(C.c_long), C.POINTER(C.c_double),
+                                            C.POINTER(C.c_double)]
+    lib.hpsgd_kernel_name.argtypes = [C.c_int]
+    lib.hpsgd_kernel_name.restype = C.c_char_p
     lib.hpsgd_commit_kernel_params.argtypes = [vp]
     lib.hpsgd_commit_kernel_params.restype = sz
     lib.hpsgd_probe_mfma_rate.argtypes = [C.c_int, vp, C.c_int, vp, vp, vp]
@@ -212,6 +219,26 @@ class Context:
 
     def role_names(self):
         return [self.lib.hpsgd_role_name(i).decode() for i in range(ROLE_COUNT)]
+
+    def kernel_timer_enable(self, kernels):
+        mask = 0
+        for k in kernels:
+            mask |= 1 << int(k)
+        _check(self.lib.hpsgd_kernel_timer_enable(self._h, mask), "hpsgd_kernel_timer_enable")
+
+    def kernel_timer_read(self, kernel):
+        """(launches, total ms, summed algorithmic work) of `kernel` since the last read; waits for the events."""
+        n, ms, w = C.c_long(), C.c_double(), C.c_double()
+        _check(self.lib.hpsgd_kernel_timer_read(self._h, int(kernel), C.byref(n), C.byref(ms), C.byref(w)),
+               "hpsgd_kernel_timer_read")
+        return int(n.value), float(ms.value), float(w.value)
+
+    def kernel_names(self):
+        """Index = kernel id; index 0 (no kernel) is None."""
+        out = [None]
+        for i in range(1, KERNEL_COUNT):
+            out.append(self.lib.hpsgd_kernel_name(i).decode())
+        return out
 
     def commit_kernel_params(self):
         """Parameters per worker that went through the commit kernel in the last local step."""

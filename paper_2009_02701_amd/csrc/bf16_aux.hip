@@ -78,6 +78,8 @@ hipError_t launch_cvt2(const void* in, int in_bf16, long ld_in, long s_in, void*
   if (!cvt2_supported(in, in_bf16, ld_in, s_in, out_p, ld_p, s_p, out_t, ld_t, s_t, R, C))
     return hipErrorInvalidValue;
   dim3 grid((C + 63) / 64, (R + 63) / 64, groups);
+  // bytes: one read of the input, one write of each copy
+  KernelTimer kt(KID_CVT2, (double)R * C * groups * ((in_bf16 ? 2 : 4) + (out_p ? 2 : 0) + (out_t ? 2 : 0)), s);
   if (in_bf16)
     hipLaunchKernelGGL(cvt2_kernel<__bf16>, grid, dim3(256), 0, s, (const __bf16*)in, ld_in, s_in,
                        (__bf16*)out_p, ld_p, s_p, (__bf16*)out_t, ld_t, s_t, R, C);
@@ -267,6 +269,8 @@ hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int3
                                   long s_rowstat, int N, int C, int groups, hipStream_t s, float* colpart,
                                   long s_colpart) {
   if (!softmax_ce_bf16_supported(logits, s_logits, dlog, ld_d, s_d, C)) return hipErrorInvalidValue;
+  // bytes: the logits read once (fp32), the logit gradient written in bf16
+  KernelTimer kt(KID_SOFTMAX_CE_BF16, 6.0 * N * C * groups, s);
   if (colpart) {
     if (((uintptr_t)colpart & 15) != 0 || s_colpart % 4 != 0) return hipErrorInvalidValue;
     dim3 grid(softmax_ce_bf16_row_blocks(N), groups);

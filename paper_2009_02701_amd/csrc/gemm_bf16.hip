@@ -190,6 +190,7 @@ template <int BM, int BN, int WM, int WN>
 static hipError_t launch_cfg_bf16(const GemmDesc& d, int vecA, int vecB, hipStream_t s) {
   dim3 grid((d.N + BN - 1) / BN, (d.M + BM - 1) / BM, d.groups);
   dim3 block((BM / WM) * (BN / WN) * 64);
+  KernelTimer kt(KID_GEMM_F32, 2.0 * d.M * d.N * (double)d.Kd * d.groups, s);
   if (!d.transA && d.transB)
     hipLaunchKernelGGL((gemm_bf16_kernel<BM, BN, WM, WN, false, true>), grid, block, 0, s, d, vecA, vecB);
   else if (!d.transA && !d.transB)

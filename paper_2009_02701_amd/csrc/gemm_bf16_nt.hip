@@ -612,6 +612,8 @@ hipError_t launch_dlx(const GemmNtDesc& d, hipStream_t s) {
   }
   const int tm = (d.M + Sh::BM - 1) / Sh::BM, tn = (d.N + Sh::BN - 1) / Sh::BN;
   const int total = tm * tn * d.groups;
+  const int kid = (TM == 2 ? KID_GEMM_BF16_DLX128 : TM == 3 ? KID_GEMM_BF16_DLX192 : KID_GEMM_BF16_DLX256) + (COMMIT ? 1 : 0);
+  KernelTimer kt(kid, 2.0 * d.M * d.N * (double)d.Kd * d.groups, s);
   hipLaunchKernelGGL((gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>), dim3(8 * ((total + 7) / 8)),
                      dim3(Sh::NT), Sh::LDS, s, d);
   return hipGetLastError();
@@ -649,6 +651,7 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
   dim3 grid(8 * ((ts + 7) / 8) * tf * groups);  // see the tile order in the kernel
   dim3 block(NTHREADS);
   constexpr size_t smem = (size_t)2 * (NBM + NBN) * NPITCH * sizeof(__bf16);  // 72 KB: above the static limit
+  const double flops = 2.0 * M * N * (double)Kd * groups;
 #define HPSGD_NT1(TA, TB, CM)                                                                     \
   do {                                                                                            \
     static bool ready = false; /* per instantiation: allow the large dynamic LDS allocation */    \
@@ -658,6 +661,7 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
       if (e != hipSuccess) return e;                                                              \
       ready = true;                                                                               \
     }                                                                                             \
+    KernelTimer kt(KID_GEMM_BF16_NT, flops, s);                                                   \
     hipLaunchKernelGGL((gemm_bf16_nt_kernel<TA, TB, CM>), grid, block, smem, s, d);               \
   } while (0)
 #define HPSGD_NT(TA, TB)                \
@@ -676,6 +680,7 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
       if (e != hipSuccess) return e;                                                              \
       ready = true;                                                                               \
     }                                                                                             \
+    KernelTimer kt(CM ? KID_GEMM_BF16_DL_COMMIT : KID_GEMM_BF16_DL, flops, s);                    \
     hipLaunchKernelGGL((gemm_bf16_dl_kernel<CM>), grid, block, dl_smem, s, d);                    \
   } while (0)
     // Which tile.  One 8-wave workgroup per CU with a tile 256 wide does more matrix work per

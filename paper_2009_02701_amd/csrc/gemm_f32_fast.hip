@@ -275,6 +275,7 @@ static hipError_t launch_fast_cfg(const GemmDesc& d, hipStream_t s) {
   }
   const long ntiles = (long)((d.N + BN - 1) / BN) * ((d.M + BM - 1) / BM) * d.groups * (d.splits > 1 ? d.splits : 1);
   dim3 grid((unsigned)(8 * ((ntiles + 7) / 8)));
+  KernelTimer kt(KID_GEMM_F32_FAST, 2.0 * d.M * d.N * (double)d.Kd * d.groups * (d.splits > 1 ? d.splits : 1), s);
   hipLaunchKernelGGL((gemm_f32_fast_kernel<BM, BN, TA, TB>), grid, dim3(FTHREADS), smem, s, d);
   return hipGetLastError();
 }

@@ -298,6 +298,7 @@ static hipError_t launch_fwd_rb(const float* W_hh, const float* b_hh, long s_rep
     ready = true;
   }
   dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
+  KernelTimer kt(KID_GRU_STEP, 2.0 * B * 3 * H * (double)H * groups, s);
   hipLaunchKernelGGL((gru_fwd_step_kernel<RB, NW, W>), grid, dim3(64 * NW), lds, s, W_hh, b_hh, s_rep, gx_t, s_gx, h_prev,
                      h_out, s_hs, sv_t, s_sv, B, H, groups);
   return hipGetLastError();
@@ -409,6 +410,7 @@ static hipError_t launch_bwd_rb(const float* WT, long s_wt, const float* dgh_nex
     ready = true;
   }
   dim3 grid((H / FJ) * ((B + 16 * RB - 1) / (16 * RB)) * groups);
+  KernelTimer kt(KID_GRU_STEP, 2.0 * B * 3 * H * (double)H * groups, s);
   hipLaunchKernelGGL((gru_bwd_step_kernel<RB, NW, W>), grid, dim3(64 * NW), lds, s, WT, s_wt, dgh_next, s_dg, D, s_D, above,
                      s_above, sv_t, s_sv, h_prev, s_hs, dgx_t, dgh_t, B, H, groups);
   return hipGetLastError();
@@ -533,6 +535,7 @@ hipError_t launch_gru_fwd_step_bf16(const void* Wb, long s_wb, const float* b_hh
     ready = true;
   }
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
+  KernelTimer kt(KID_GRU_STEP, 2.0 * B * 3 * H * (double)H * groups, s);
   hipLaunchKernelGGL(gru_fwd_step_bf16_kernel, grid, dim3(256), kFwdBf16Lds, s, (const __bf16*)Wb, s_wb,
                      b_hh, s_rep, gx_t, s_gx, h_prev, h_out, s_hs, (const __bf16*)hb_prev, (__bf16*)hb_out,
                      s_hb, sv_t, s_sv, (__bf16*)hT_out, ld_hT, s_hT, B, H, groups);
@@ -656,6 +659,7 @@ hipError_t launch_gru_bwd_step_bf16(const void* WTb, long s_wt, const void* dghb
                                     void* dghT_t, long ld_T, long s_T, int B, int H, int groups,
                                     hipStream_t s) {
   dim3 grid((H / FJ) * ((B + FR - 1) / FR) * groups);
+  KernelTimer kt(KID_GRU_STEP, 2.0 * B * 3 * H * (double)H * groups, s);
   hipLaunchKernelGGL(gru_bwd_step_bf16_kernel, grid, dim3(256), kBwdBf16Lds, s, (const __bf16*)WTb, s_wt,
                      (const __bf16*)dghb_next, (__bf16*)dghb_t, s_dgb, D, s_D, above, s_above, sv_t, s_sv,
                      h_prev, s_hs, dgx_t, dgh_t, s_dg, (__bf16*)dgxb_t, (__bf16*)dgxT_t, (__bf16*)dghT_t, ld_T,

@@ -100,9 +100,21 @@ __device__ __forceinline__ bool group_wait(unsigned* flags, int members, unsigne
   return *lds_flag != 0;
 }
 
-// The barrier waits for the completion of every wave's stores; then thread 0 publishes the
-// number of steps this member has completed.
+// Publishes the number of steps this member has completed, after the step's exchanged values.
+// Order of data and count, by construction:
+//   1. every wave waits until the vector-memory counter of its own accesses is zero
+//      (s_waitcnt vmcnt(0): on this target stores count in vmcnt too, and a device-scope
+//      write-through store is counted out only when the level of the memory hierarchy that all
+//      XCDs share has acknowledged it);
+//   2. the workgroup barrier: every wave of the workgroup has passed step 1;
+//   3. thread 0 stores the count (device scope).
+// A consumer that reads the count (device-scope load) and then issues its operand loads
+// (device-scope, behind a barrier of its own workgroup) therefore reads the data of the step.
+// The wait is written out: a workgroup-scope fence would only have to order LDS traffic here,
+// and an agent-scope release would write back the XCD's whole L2.
 __device__ __forceinline__ void group_signal(unsigned* my_flag, unsigned steps_done) {
+  // vmcnt = 0 (bits 3:0 and 15:14), expcnt and lgkmcnt left at their maxima (no wait)
+  __builtin_amdgcn_s_waitcnt(0x0F70);
   __syncthreads();
   if (threadIdx.x == 0) __hip_atomic_store(my_flag, steps_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
@@ -919,6 +931,7 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
     allowed[xnb] = lds;
   }
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
+  KernelTimer kt(KID_GRU_FWD_PERSIST, 2.0 * B * 3 * H * ((double)H + (xin ? width : 0)) * T * groups, s);
 #define HPSGD_FWD_PERSIST(N)                                                                                    \
   hipLaunchKernelGGL(gru_fwd_persist_kernel<N>, grid, dim3(PNT), lds, s, W_hh, b_hh, s_rep, gx, s_gx, hs, s_hs, \
                      sv, s_sv, B, H, T, groups, sync, base, spin_limit, xin, s_x, width, W_ih, b_ih)
@@ -949,6 +962,7 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
     allowed = lds;
   }
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
+  KernelTimer kt(KID_GRU_BWD_PERSIST, 2.0 * B * 3 * H * (double)H * (t_hi - t_lo) * groups * (dWp ? 2 : 1), s);
   hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dgx, s_dg, D, s_D, above,
                      s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit, dWp, dbp);
   return hipGetLastError();
@@ -1004,6 +1018,7 @@ hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b
     ready[slot] = true;
   }
   dim3 grid((H / QJ) * ((B + PR - 1) / PR) * groups);
+  KernelTimer kt(KID_GRU_FWD_PERSIST_BF16, 2.0 * B * 3 * H * (double)H * T * groups, s);
 #define HPSGD_FWD_PB(N)                                                                                            \
   hipLaunchKernelGGL(gru_fwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)Wb, s_wb, b_hh, s_rep, \
                      gx, s_gx, hs, s_hs, (__bf16*)hb, s_hb, sv, s_sv, (__bf16*)hT, ld_hT, s_hT, B, H, T, groups,    \
@@ -1041,6 +1056,7 @@ hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghb, lo
     ready[slot] = true;
   }
   dim3 grid((H / QJ) * ((B + PR - 1) / PR) * groups);
+  KernelTimer kt(KID_GRU_BWD_PERSIST_BF16, 2.0 * B * 3 * H * (double)H * T * groups, s);
 #define HPSGD_BWD_PB(N)                                                                                            \
   hipLaunchKernelGGL(gru_bwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)WT, s_wt,              \
                      (__bf16*)dghb, s_dgb, D, s_D, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \

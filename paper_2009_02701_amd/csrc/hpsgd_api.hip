@@ -73,6 +73,12 @@ struct hpsgd_ctx {
   std::vector<hipEvent_t> free_events;
   double role_ms[HPSGD_ROLE_COUNT] = {0};
   long role_launches[HPSGD_ROLE_COUNT] = {0};
+  // per-kernel timing: event pairs recorded by the launchers themselves (KernelTimer)
+  unsigned kernel_mask = 0;
+  struct KStamp { int kid; double work; hipEvent_t a, b; };
+  std::vector<KStamp> kstamps;
+  double kernel_ms[HPSGD_KERNEL_COUNT] = {0}, kernel_work[HPSGD_KERNEL_COUNT] = {0};
+  long kernel_launches[HPSGD_KERNEL_COUNT] = {0};
 
   int find(const std::string& n) const {
     for (size_t i = 0; i < entries.size(); ++i)
@@ -230,6 +236,14 @@ struct TimerScope {
   bool active() const { return idx >= 0; }
 };
 
+// The context whose local step the calling thread is issuing (KernelTimer looks here).
+thread_local hpsgd_ctx* t_step_ctx = nullptr;
+struct StepCtxScope {
+  hpsgd_ctx* prev;
+  explicit StepCtxScope(hpsgd_ctx* c) : prev(t_step_ctx) { t_step_ctx = c; }
+  ~StepCtxScope() { t_step_ctx = prev; }
+};
+
 // inside run_step: `role` names what the next launches are for
 #define HIP_TRY(expr)                              \
   do {                                             \
@@ -295,17 +309,56 @@ int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float
 // The resident-weight recurrence kernels wait for each other inside a launch, which needs all
 // their workgroups on the chip at once: two such launches running side by side (from two
 // streams) could each hold CUs the other is waiting for.  Launches on one stream are ordered
-// anyway; when the stream changes, everything issued before is allowed to finish first.
-int order_resident_launches(hipStream_t s) {
-  static std::mutex mu;
-  static bool have = false;
-  static hipStream_t last = nullptr;
-  std::lock_guard<std::mutex> lock(mu);
-  if (have && last != s && hipDeviceSynchronize() != hipSuccess) return HPSGD_EHIP;
-  have = true;
-  last = s;
-  return HPSGD_OK;
-}
+// anyway.  Across streams, contexts and host threads they are ordered here: the one piece of
+// per-process state of the library, per device, is the event recorded behind the most recent
+// resident-weight launch and the stream it went to.  A local step that issues such launches
+// holds the lock from its first one to its last (so that no other thread's launches fall in
+// between) and, if the previous ones went to another stream, lets its stream wait for that
+// event (hipStreamWaitEvent: the host never blocks).
+struct ResidentOrder {
+  std::mutex mu;
+  hipEvent_t ev = nullptr;   // behind the last resident-weight launch issued on this device
+  hipStream_t last = nullptr;
+  bool have = false;
+};
+constexpr int kMaxDevices = 64;
+ResidentOrder g_resident[kMaxDevices];
+
+struct ResidentScope {
+  ResidentOrder* o = nullptr;
+  std::unique_lock<std::mutex> lock;
+  hipStream_t s = nullptr;
+  // Called before the step's first resident-weight launch.
+  int begin(hipStream_t stream) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HPSGD_EHIP;
+    o = &g_resident[dev];
+    s = stream;
+    lock = std::unique_lock<std::mutex>(o->mu);
+    if (!o->ev && hipEventCreateWithFlags(&o->ev, hipEventDisableTiming) != hipSuccess) {
+      o->ev = nullptr;
+      return HPSGD_EHIP;
+    }
+    if (o->have && o->last != s && hipStreamWaitEvent(s, o->ev, 0) != hipSuccess) return HPSGD_EHIP;
+    return HPSGD_OK;
+  }
+  // note(): a resident-weight launch was issued; mark(): ... and the event is recorded behind
+  // it (the last record stands).  The step marks behind its backward launches; a launch that was
+  // only noted is marked when the step has been issued, where the lock is released too.
+  bool pending = false;
+  void note() { pending = o != nullptr; }
+  int mark() {
+    if (!o) return HPSGD_OK;
+    pending = false;
+    if (hipEventRecord(o->ev, s) != hipSuccess) return HPSGD_EHIP;
+    o->have = true;
+    o->last = s;
+    return HPSGD_OK;
+  }
+  ~ResidentScope() {
+    if (pending) (void)mark();
+  }
+};
 
 // bf16 precision: the rounded copies of the weight matrices that a local step's GEMMs and
 // recurrence launches read (row-major, and transposed where an input gradient is needed), all
@@ -389,6 +442,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
+  StepCtxScope step_scope(c);
+  ResidentScope resident;  // orders this step's resident-weight launches against other streams
   // the bf16 copies of the weights are already in this workspace (hpsgd_prepare_replicas); the
   // step changes the weights, so the mark is used once
   const bool prepared = bf && c->prepared_rin == rin && c->prepared_ws == ws && c->prepared_stride == rstride &&
@@ -518,7 +573,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     unsigned* psync = (use_persist || use_persist_b) ? (unsigned*)reg(c->psync) : nullptr;
     unsigned pbase = 0;
     if (use_persist || use_persist_b) {
-      TRY(order_resident_launches(s));
+      TRY0(resident.begin(s));
       abort_word = psync;  // (cleared together with the first layer's h_0 below)
     }
     // ---- the head's operands
@@ -651,6 +706,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         pbase += (unsigned)T * gru_persist_count_per_step(H);
         ++c->last_resident;
         c->last_xproj += xproj ? 1 : 0;
+        resident.note();
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
@@ -658,6 +714,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                             s_sv, hT, TB1p, s_hT, B, H, T, groups, psync, pbase, c->spin_limit, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         ++c->last_resident;
+        resident.note();
       }
       for (int t = 0; t < T && !persist && !persist_b; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
@@ -740,8 +797,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (side_by_side &&
             (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess))
           return HPSGD_EHIP;
+        // (bf16 views only: the fp32 head matrix may be updated in place by the GEMM beside this one)
         TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
-                  lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT));
+                  lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT, 0.f, true));
         TRY(gemm2(side_by_side ? c->aux : s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top,
                   0, wt.C, H, wt.sC, wt.epi, wt.aux, sR, vdT, vhT, lr));
         if (side_by_side &&
@@ -918,6 +976,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                        T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, s));
         c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);
+        if (l == 0) TRY0(resident.mark());
+        else resident.note();
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
@@ -925,6 +985,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                             bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B, H, T, groups, psync,
                                             pbase, c->spin_limit, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
+        if (l == 0) TRY0(resident.mark());
+        else resident.note();
       }
       for (int t = T - 1; t >= 0 && !persist && !persist_b; --t) {
         if (NC > 1 && next_chunk >= 1 && t < chunk_lo(next_chunk)) {
@@ -1131,6 +1193,26 @@ int check_step_args(const hpsgd_ctx* c, const float* rin, float* rout, size_t rs
 
 }  // namespace
 
+namespace hpsgd {
+static_assert((int)KID_COUNT == (int)HPSGD_KERNEL_COUNT, "kernel ids of kernels.h and hpsgd.h differ");
+
+KernelTimer::KernelTimer(int kid, double work, hipStream_t s) : ctx_(nullptr), idx_(-1), s_(s) {
+  hpsgd_ctx* c = t_step_ctx;
+  if (!c || kid <= 0 || kid >= KID_COUNT || !(c->kernel_mask & (1u << kid))) return;
+  hipEvent_t a = TimerScope::get(c), b = TimerScope::get(c);
+  if (!a || !b) return;
+  c->kstamps.push_back({kid, work, a, b});
+  ctx_ = c;
+  idx_ = (int)c->kstamps.size() - 1;
+  (void)hipEventRecord(a, s);
+}
+KernelTimer::~KernelTimer() {
+  if (!ctx_) return;
+  hpsgd_ctx* c = static_cast<hpsgd_ctx*>(ctx_);
+  (void)hipEventRecord(c->kstamps[idx_].b, s_);
+}
+}  // namespace hpsgd
+
 extern "C" {
 
 int hpsgd_create(const hpsgd_model_desc* desc, int K, hpsgd_ctx** out) {
@@ -1154,6 +1236,10 @@ int hpsgd_create(const hpsgd_model_desc* desc, int K, hpsgd_ctx** out) {
 int hpsgd_destroy(hpsgd_ctx* ctx) {
   if (ctx) {
     for (auto& st : ctx->stamps) {
+      (void)hipEventDestroy(st.a);
+      (void)hipEventDestroy(st.b);
+    }
+    for (auto& st : ctx->kstamps) {
       (void)hipEventDestroy(st.a);
       (void)hipEventDestroy(st.b);
     }
@@ -1386,6 +1472,58 @@ int hpsgd_timer_read(hpsgd_ctx* ctx, int role, long* launches, double* total_ms)
   ctx->role_launches[role] = 0;
   ctx->role_ms[role] = 0.0;
   return HPSGD_OK;
+}
+
+int hpsgd_kernel_timer_enable(hpsgd_ctx* ctx, unsigned kernel_mask) {
+  if (!ctx) return HPSGD_EINVAL;
+  ctx->kernel_mask = kernel_mask & ((1u << HPSGD_KERNEL_COUNT) - 1u) & ~1u;
+  return HPSGD_OK;
+}
+
+int hpsgd_kernel_timer_read(hpsgd_ctx* ctx, int kernel, long* launches, double* total_ms, double* work) {
+  if (!ctx || kernel <= 0 || kernel >= HPSGD_KERNEL_COUNT) return HPSGD_EINVAL;
+  for (auto& st : ctx->kstamps) {
+    if (hipEventSynchronize(st.b) != hipSuccess) return HPSGD_EHIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, st.a, st.b) != hipSuccess) return HPSGD_EHIP;
+    ctx->kernel_ms[st.kid] += ms;
+    ctx->kernel_work[st.kid] += st.work;
+    ctx->kernel_launches[st.kid] += 1;
+    ctx->free_events.push_back(st.a);
+    ctx->free_events.push_back(st.b);
+  }
+  ctx->kstamps.clear();
+  if (launches) *launches = ctx->kernel_launches[kernel];
+  if (total_ms) *total_ms = ctx->kernel_ms[kernel];
+  if (work) *work = ctx->kernel_work[kernel];
+  ctx->kernel_launches[kernel] = 0;
+  ctx->kernel_ms[kernel] = 0.0;
+  ctx->kernel_work[kernel] = 0.0;
+  return HPSGD_OK;
+}
+
+const char* hpsgd_kernel_name(int kernel) {
+  switch (kernel) {
+    case HPSGD_KERNEL_GRU_FWD_PERSIST: return "gru_fwd_persist_kernel";
+    case HPSGD_KERNEL_GRU_BWD_PERSIST: return "gru_bwd_persist_kernel";
+    case HPSGD_KERNEL_GRU_FWD_PERSIST_BF16: return "gru_fwd_persist_bf16_kernel";
+    case HPSGD_KERNEL_GRU_BWD_PERSIST_BF16: return "gru_bwd_persist_bf16_kernel";
+    case HPSGD_KERNEL_GEMM_BF16_DL: return "gemm_bf16_dl_kernel<false>";
+    case HPSGD_KERNEL_GEMM_BF16_DL_COMMIT: return "gemm_bf16_dl_kernel<true>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX128: return "gemm_bf16_dlx_kernel<false, 2, 4, 2, 2, 3>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX128_COMMIT: return "gemm_bf16_dlx_kernel<true, 2, 4, 2, 2, 3>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX192: return "gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX192_COMMIT: return "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX256: return "gemm_bf16_dlx_kernel<false, 2, 4, 4, 2, 2>";
+    case HPSGD_KERNEL_GEMM_BF16_DLX256_COMMIT: return "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>";
+    case HPSGD_KERNEL_GEMM_BF16_NT: return "gemm_bf16_nt_kernel";
+    case HPSGD_KERNEL_GEMM_F32_FAST: return "gemm_f32_fast_kernel";
+    case HPSGD_KERNEL_GEMM_F32: return "gemm_f32_kernel";
+    case HPSGD_KERNEL_CVT2: return "cvt2_kernel";
+    case HPSGD_KERNEL_SOFTMAX_CE_BF16: return "softmax_ce_bf16_rows_kernel";
+    case HPSGD_KERNEL_GRU_STEP: return "gru_step_kernel";
+    default: return nullptr;
+  }
 }
 
 int hpsgd_delay_us(unsigned microseconds, void* hip_stream) {

@@ -12,6 +12,45 @@ struct PtrPack {  // K device pointers passed by value as a kernel argument
   float* p[HPSGD_KMAX];
 };
 
+// ---- per-kernel timing (benchmarks) ----
+// The kernels whose launches can be timed one by one (enum hpsgd_kernel in hpsgd.h has the
+// same numbering).  A launcher creates a KernelTimer around its launch: when the calling
+// thread is inside a local step whose context has that kernel's timing enabled, a HIP event
+// pair is recorded on the launch's own stream, together with the launch's algorithmic work
+// (flops for the contractions, bytes for the streaming kernels); otherwise it does nothing.
+enum KernelId : int {
+  KID_NONE = 0,
+  KID_GRU_FWD_PERSIST = 1,        // gru_fwd_persist_kernel (fp32, any input-projection form)
+  KID_GRU_BWD_PERSIST = 2,        // gru_bwd_persist_kernel
+  KID_GRU_FWD_PERSIST_BF16 = 3,   // gru_fwd_persist_bf16_kernel
+  KID_GRU_BWD_PERSIST_BF16 = 4,   // gru_bwd_persist_bf16_kernel
+  KID_GEMM_BF16_DL = 5,           // gemm_bf16_dl_kernel<false>   (128 x 128)
+  KID_GEMM_BF16_DL_COMMIT = 6,    // gemm_bf16_dl_kernel<true>
+  KID_GEMM_BF16_DLX128 = 7,       // gemm_bf16_dlx_kernel<false, 2, 4, 2, 2, 3>  (128 x 256)
+  KID_GEMM_BF16_DLX128_COMMIT = 8,
+  KID_GEMM_BF16_DLX192 = 9,       // gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>  (192 x 256)
+  KID_GEMM_BF16_DLX192_COMMIT = 10,
+  KID_GEMM_BF16_DLX256 = 11,      // gemm_bf16_dlx_kernel<false, 2, 4, 4, 2, 2>  (256 x 256)
+  KID_GEMM_BF16_DLX256_COMMIT = 12,
+  KID_GEMM_BF16_NT = 13,          // gemm_bf16_nt_kernel (an fp32 operand rounded while staged)
+  KID_GEMM_F32_FAST = 14,         // gemm_f32_fast_kernel (all tile forms)
+  KID_GEMM_F32 = 15,              // gemm_f32_kernel / gemm_bf16_kernel (generic fallbacks)
+  KID_CVT2 = 16,                  // cvt2_kernel (bf16 copy + transposed copy)
+  KID_SOFTMAX_CE_BF16 = 17,       // softmax_ce_bf16_rows_kernel / softmax_ce_bf16_kernel
+  KID_GRU_STEP = 18,              // gru_{fwd,bwd}_step(_bf16)_kernel: one launch per time step
+  KID_COUNT = 19
+};
+struct KernelTimer {
+  KernelTimer(int kid, double work, hipStream_t s);
+  ~KernelTimer();
+  KernelTimer(const KernelTimer&) = delete;
+  KernelTimer& operator=(const KernelTimer&) = delete;
+ private:
+  void* ctx_;  // the context that holds the open stamp, or nullptr
+  int idx_;    // its index there
+  hipStream_t s_;
+};
+
 // ---- HBM-streaming kernels over flat parameter buffers ----
 hipError_t launch_merge(float* global, const PtrPack& replicas, const float* snapshot, int K,
                         size_t P, hipStream_t s);

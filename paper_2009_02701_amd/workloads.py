@@ -167,24 +167,6 @@ def batch_indices(cfg: dict, worker: int, step: int) -> np.ndarray:
     return batch_order(cfg, worker)[s * b:(s + 1) * b].copy()
 
 
-def host_batch(cfg: dict, shard, idx: np.ndarray):
-    """Plain host-side batch assembly in the layouts the local step takes.
-
-    gru_cls: x [T, B, I] (time-major), y [B];  mlp: x [B, D0], y [B];
-    gru_lm: x int32 [T, B] = tokens[:, :T].T, y int32 [T, B] = tokens[:, 1:].T
-    """
-    x, y = shard
-    kind = cfg["kind"]
-    if kind == "gru_cls":
-        return np.ascontiguousarray(x[idx].transpose(1, 0, 2)), y[idx].copy()
-    if kind == "mlp":
-        return x[idx].copy(), y[idx].copy()
-    if kind == "gru_lm":
-        tok = x[idx]
-        return (np.ascontiguousarray(tok[:, :-1].T), np.ascontiguousarray(tok[:, 1:].T))
-    raise ValueError(kind)
-
-
 # ----------------------------------------------------------------------------
 # merge-only stress (flat vectors)
 # ----------------------------------------------------------------------------

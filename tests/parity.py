@@ -1,6 +1,7 @@
 """Shared helpers of the GPU parity tests (no arithmetic of the method)."""
 import numpy as np
 
+from oracle import hpsgd_oracle as oc
 from paper_2009_02701_amd import workloads as wl
 
 # spec tolerances: max relative error per tensor, ||gpu - ref||_inf / ||ref||_inf
@@ -29,12 +30,13 @@ def workload(cfg):
     init = wl.init_params(cfg)
     shards = [wl.make_shard(cfg, k) for k in range(K)]
     orders = [wl.batch_order(cfg, k) for k in range(K)]
-    batch_fn = lambda k, s: wl.host_batch(cfg, shards[k], wl.batch_indices(cfg, k, s))
+    batch_fn = lambda k, s: oc.gather_batch(cfg["kind"], shards[k][0], shards[k][1], wl.batch_indices(cfg, k, s))
     return init, shards, orders, batch_fn
 
 
 def round_bf16(a):
-    """Round-to-nearest-even to bfloat16 (8 significand bits), returned as float64."""
-    u = np.asarray(a, np.float32).view(np.uint32).astype(np.uint64)
-    u = (u + 0x7FFF + ((u >> 16) & 1)) & 0xFFFF0000
-    return u.astype(np.uint32).view(np.float32).astype(np.float64)
+    """Round-to-nearest-even to bfloat16 (8 significand bits), returned as float64.
+    Pinned in tests/test_oracle_model.py against the library's conversion and hand-written ties."""
+    u = np.ascontiguousarray(a, np.float32).view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)

@@ -169,3 +169,24 @@ def test_local_step_rejects_bad_arguments_before_launch():
     assert prep(R, 5132, R) == 4
     assert prep(R, 5132, W) == 0                                         # fp32: nothing to prepare, nothing launched
     assert hb.load_library().hpsgd_strerror(4) == b"buffers overlap"
+
+
+def test_kernel_timer_entry_points_on_the_host():
+    """hpsgd_kernel_name covers ids 1 .. HPSGD_KERNEL_COUNT-1 (the enum of the header), and the
+    timer calls check their arguments; nothing here launches."""
+    lib = hb.load_library()
+    hdr = open(os.path.join(ROOT, "include", "hpsgd.h")).read()
+    count = int(re.search(r"HPSGD_KERNEL_COUNT = (\d+)", hdr).group(1))
+    assert count == hb.KERNEL_COUNT
+    names = [lib.hpsgd_kernel_name(i) for i in range(count)]
+    assert names[0] is None and all(n for n in names[1:]) and len(set(names[1:])) == count - 1
+    assert lib.hpsgd_kernel_name(count) is None and lib.hpsgd_kernel_name(-1) is None
+    ctx = hb.Context(wl.CONFIGS["tiny_gru"])
+    assert lib.hpsgd_kernel_timer_enable(None, 1) == 1
+    assert lib.hpsgd_kernel_timer_enable(ctx._h, 0xFFFFFFFF) == 0
+    n, ms, w = C.c_long(-1), C.c_double(-1), C.c_double(-1)
+    assert lib.hpsgd_kernel_timer_read(ctx._h, 0, C.byref(n), C.byref(ms), C.byref(w)) == 1
+    assert lib.hpsgd_kernel_timer_read(ctx._h, count, C.byref(n), C.byref(ms), C.byref(w)) == 1
+    assert lib.hpsgd_kernel_timer_read(ctx._h, 1, C.byref(n), C.byref(ms), C.byref(w)) == 0
+    assert n.value == 0 and ms.value == 0.0 and w.value == 0.0
+    assert ctx.kernel_names()[4] == "gru_bwd_persist_bf16_kernel"

@@ -141,7 +141,7 @@ def test_gather_time_major_bit_exact():
     cfg = wl.scaled(wl.CONFIGS["gru_cls"], input=13, seq_len=7, batch=5)
     x, y = wl.make_shard(cfg, 0)
     idx = wl.batch_indices(cfg, 0, 3)
-    want_x, want_y = wl.host_batch(cfg, (x, y), idx)
+    want_x, want_y = oc.gather_batch(cfg["kind"], x, y, idx)
     xs, ys, it = (torch.from_numpy(a).to(DEV) for a in (x, y, idx))
     out = torch.zeros(7, 5, 13, device=DEV)
     outy = torch.zeros(5, dtype=torch.int32, device=DEV)
@@ -156,7 +156,7 @@ def test_gather_tokens_and_shifted_targets_bit_exact():
     cfg = wl.scaled(wl.CONFIGS["gru_lm"], seq_len=9, batch=6, vocab=50)
     tok, _ = wl.make_shard(cfg, 1)
     idx = wl.batch_indices(cfg, 1, 2)
-    want_x, want_y = wl.host_batch(cfg, (tok, None), idx)
+    want_x, want_y = oc.gather_batch(cfg["kind"], tok, None, idx)
     ts, it = torch.from_numpy(tok).to(DEV), torch.from_numpy(idx).to(DEV)
     ox = torch.zeros(9, 6, dtype=torch.int32, device=DEV)
     oy = torch.zeros(9, 6, dtype=torch.int32, device=DEV)
@@ -188,6 +188,6 @@ def test_gather_all_workers_one_launch_bit_exact():
     hb.gather_batch_all(ys, its, 1, 1, list(oy), row_elems=1)
     torch.cuda.synchronize()
     for k in range(3):
-        wx, wy = wl.host_batch(cfg, shards[k], idx[k])
+        wx, wy = oc.gather_batch(cfg["kind"], shards[k][0], shards[k][1], idx[k])
         assert np.array_equal(ox[k].cpu().numpy().view(np.uint32), wx.view(np.uint32))
         assert np.array_equal(oy[k].cpu().numpy(), wy)

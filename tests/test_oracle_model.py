@@ -8,14 +8,20 @@ import math
 
 import numpy as np
 import pytest
+import os
+import sys
+
 import torch
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
 
 from oracle import hpsgd_oracle as oc
 from paper_2009_02701_amd import workloads as wl
 
 
 def _batch(cfg, worker=0, step=0):
-    return wl.host_batch(cfg, wl.make_shard(cfg, worker), wl.batch_indices(cfg, worker, step))
+    x, y = wl.make_shard(cfg, worker)
+    return oc.gather_batch(cfg["kind"], x, y, wl.batch_indices(cfg, worker, step))
 
 
 def _fd_check(params, x, y, names=None, eps=1e-6, tol=1e-6, stride=1):
@@ -192,3 +198,174 @@ def test_softmax_ce_bruteforce():
     # shift invariance / large logits do not overflow
     loss2, _ = oc.softmax_ce(logits + 1000.0, y)
     assert abs(loss2 - loss) < 1e-9
+
+
+# ---------------------------------------------------------------------------- batch gather
+def test_gather_batch_hand_written_examples():
+    """Sec. 3.2: a worker's mini-batch out of its sub-dataset.  The expected arrays are typed out
+    by hand (not produced by indexing code): a wrong axis order, a missing shift of the targets
+    or an off-by-one in the sample number changes them."""
+    # classifier: 4 samples of T = 2 steps x I = 3 features; sample n, step t, feature i = 100n + 10t + i
+    samples = np.array([[[0, 1, 2], [10, 11, 12]],
+                        [[100, 101, 102], [110, 111, 112]],
+                        [[200, 201, 202], [210, 211, 212]],
+                        [[300, 301, 302], [310, 311, 312]]], np.float32)
+    labels = np.array([7, 5, 3, 1], np.int32)
+    x, y = oc.gather_batch("gru_cls", samples, labels, np.array([2, 0, 3], np.int32))
+    want_x = np.array([[[200, 201, 202], [0, 1, 2], [300, 301, 302]],          # step 0 of samples 2, 0, 3
+                       [[210, 211, 212], [10, 11, 12], [310, 311, 312]]],       # step 1
+                      np.float32)
+    assert x.dtype == np.float32 and x.shape == (2, 3, 3) and np.array_equal(x, want_x)
+    assert y.dtype == np.int32 and np.array_equal(y, np.array([3, 7, 1], np.int32))
+    # MLP: rows as they are
+    flat = np.array([[1, 2], [3, 4], [5, 6]], np.float32)
+    x, y = oc.gather_batch("mlp", flat, np.array([9, 8, 7], np.int32), np.array([1, 1, 2], np.int32))
+    assert np.array_equal(x, np.array([[3, 4], [3, 4], [5, 6]], np.float32))
+    assert np.array_equal(y, np.array([8, 8, 7], np.int32))
+    # language model: samples are runs of T + 1 = 4 tokens; inputs = first 3, targets = last 3
+    tok = np.array([[11, 12, 13, 14],
+                    [21, 22, 23, 24],
+                    [31, 32, 33, 34]], np.int32)
+    x, y = oc.gather_batch("gru_lm", tok, None, np.array([2, 0], np.int32))
+    assert np.array_equal(x, np.array([[31, 11], [32, 12], [33, 13]], np.int32))
+    assert np.array_equal(y, np.array([[32, 12], [33, 13], [34, 14]], np.int32))
+
+
+def test_gather_batch_is_a_selection_of_the_shard():
+    """Every gathered value is the shard's value at the named sample, for a seeded shard and the
+    seeded batch order; the targets of the language model are its inputs one token later."""
+    for name in ("tiny_gru", "mlp", "gru_lm"):
+        cfg = wl.scaled(wl.CONFIGS[name], batch=6) if name != "gru_lm" else wl.scaled(
+            wl.CONFIGS[name], batch=6, seq_len=9, vocab=50)
+        if name == "mlp":
+            cfg = wl.scaled(cfg, dims=[12, 8, 4])
+        xs, ys = wl.make_shard(cfg, 1)
+        idx = wl.batch_indices(cfg, 1, 5)
+        x, y = oc.gather_batch(cfg["kind"], xs, ys, idx)
+        rng = np.random.default_rng(3)
+        for _ in range(50):
+            b = int(rng.integers(0, len(idx)))
+            if cfg["kind"] == "gru_cls":
+                t, i = int(rng.integers(0, cfg["seq_len"])), int(rng.integers(0, cfg["input"]))
+                assert x[t, b, i] == xs[idx[b], t, i] and y[b] == ys[idx[b]]
+            elif cfg["kind"] == "mlp":
+                i = int(rng.integers(0, cfg["dims"][0]))
+                assert x[b, i] == xs[idx[b], i] and y[b] == ys[idx[b]]
+            else:
+                t = int(rng.integers(0, cfg["seq_len"]))
+                assert x[t, b] == xs[idx[b], t] and y[t, b] == xs[idx[b], t + 1]
+                if t + 1 < cfg["seq_len"]:
+                    assert y[t, b] == x[t + 1, b]
+
+
+# ---------------------------------------------------------------------------- rounded-operand mode
+def test_round_bf16_matches_the_library_conversion_and_hand_written_ties():
+    """tests/parity.py::round_bf16 (nearest, ties to even, 8 significand bits) against the
+    library's float32 -> bfloat16 conversion on random values of many magnitudes, and on ties
+    written out by hand."""
+    from parity import round_bf16
+    rng = np.random.default_rng(11)
+    v = (rng.standard_normal(200_000) * np.exp(rng.uniform(-30, 30, 200_000))).astype(np.float32)
+    want = torch.from_numpy(v).to(torch.bfloat16).to(torch.float64).numpy()
+    assert np.array_equal(round_bf16(v), want)
+    # bf16 has 7 stored fraction bits: the spacing at 1.0 is 2^-7
+    ulp = 2.0 ** -7
+    cases = {
+        1.0: 1.0,
+        1.0 + ulp / 2: 1.0,                 # tie -> even (fraction 0)
+        1.0 + ulp + ulp / 2: 1.0 + 2 * ulp,  # tie -> even (fraction 2)
+        1.0 + ulp / 2 + 2.0 ** -20: 1.0 + ulp,  # just above the tie
+        1.0 + ulp / 2 - 2.0 ** -20: 1.0,        # just below
+        -(1.0 + ulp + ulp / 2): -(1.0 + 2 * ulp),
+        0.0: 0.0,
+        3.0e38: float(np.float32(2.0 ** 127 * (1 + 98 / 128))),  # nearest bf16 of 3e38
+    }
+    for x, r in cases.items():
+        assert float(round_bf16(np.float32(x)).reshape(-1)[0]) == r, (x, r)
+
+
+class _RoundedMM(torch.autograd.Function):
+    """a @ b with both operands rounded to bf16, in the forward product and in both products of
+    the backward pass (upstream gradient and the other factor): the rule of the bf16 path."""
+
+    @staticmethod
+    def r(t):
+        return t.to(torch.float32).to(torch.bfloat16).to(torch.float64)
+
+    @staticmethod
+    def forward(ctx, a, b):
+        ctx.save_for_backward(a, b)
+        return _RoundedMM.r(a) @ _RoundedMM.r(b)
+
+    @staticmethod
+    def backward(ctx, g):
+        a, b = ctx.saved_tensors
+        r = _RoundedMM.r
+        return r(g) @ r(b).T, r(a).T @ r(g)
+
+
+def _torch_rounded_loss_and_grads(params, x, y):
+    """The model in double precision with the library's autograd for everything that is not a
+    matrix product; every matrix product through _RoundedMM."""
+    p = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in params.items()}
+    mm = _RoundedMM.apply
+    if "fc0.W" in p:
+        a = torch.tensor(np.asarray(x, np.float64))
+        L = sum(1 for k in p if k.endswith(".W"))
+        for i in range(L):
+            a = mm(a, p[f"fc{i}.W"].T) + p[f"fc{i}.b"]
+            if i < L - 1:
+                a = torch.relu(a)
+        logits, tgt = a, torch.tensor(np.asarray(y), dtype=torch.long)
+    else:
+        lm = "embed.E" in p
+        inp = p["embed.E"][torch.tensor(np.asarray(x), dtype=torch.long)] if lm else torch.tensor(np.asarray(x, np.float64))
+        T, B = inp.shape[0], inp.shape[1]
+        L = sum(1 for k in p if k.endswith(".W_hh"))
+        for l in range(L):
+            W_ih, W_hh, b_ih, b_hh = (p[f"l{l}.{n}"] for n in ("W_ih", "W_hh", "b_ih", "b_hh"))
+            H = W_hh.shape[1]
+            h = torch.zeros(B, H, dtype=torch.float64)
+            outs = []
+            for t in range(T):
+                gx = mm(inp[t], W_ih.T) + b_ih
+                gh = mm(h, W_hh.T) + b_hh
+                r = torch.sigmoid(gx[:, :H] + gh[:, :H])
+                z = torch.sigmoid(gx[:, H:2 * H] + gh[:, H:2 * H])
+                n = torch.tanh(gx[:, 2 * H:] + r * gh[:, 2 * H:])
+                h = (1 - z) * n + z * h
+                outs.append(h)
+            inp = torch.stack(outs)
+        if lm:
+            logits = mm(inp.reshape(T * B, -1), p["head.W"].T) + p["head.b"]
+            tgt = torch.tensor(np.asarray(y).reshape(-1), dtype=torch.long)
+        else:
+            logits = mm(inp[-1], p["head.W"].T) + p["head.b"]
+            tgt = torch.tensor(np.asarray(y), dtype=torch.long)
+    loss = torch.nn.functional.cross_entropy(logits, tgt)
+    loss.backward()
+    return float(loss), {k: (v.grad.numpy() if v.grad is not None else np.zeros(v.shape)) for k, v in p.items()}
+
+
+@pytest.mark.parametrize("name", ["lm", "cls2", "mlp"])
+def test_rounded_operand_mode_rounds_exactly_the_matrix_products(name):
+    """The oracle's rnd= mode (used for the tight bar of the bf16 parity tests) against the
+    library's autograd with every matrix product - and nothing else - taking bf16-rounded
+    operands.  A product the oracle forgot to round, or a rounding applied to something that is
+    not a GEMM operand (a bias sum, the embedding gradient), shows as an error of the order of
+    the bf16 spacing (4e-3); agreement is at float64 rounding."""
+    from parity import round_bf16
+    cfg = {"lm": wl.scaled(wl.CONFIGS["gru_lm"], vocab=40, embed=12, hidden=16, seq_len=5, batch=6, K=1),
+           "cls2": wl.scaled(wl.CONFIGS["gru_cls"], layers=2, input=10, hidden=16, seq_len=4, batch=5, K=1),
+           "mlp": wl.scaled(wl.CONFIGS["mlp"], dims=[20, 24, 16, 5], batch=9, K=1)}[name]
+    params = wl.init_params(cfg)
+    x, y = _batch(cfg)
+    loss, g = oc.loss_and_grads(params, x, y, rnd=round_bf16)
+    tl, tg = _torch_rounded_loss_and_grads(params, x, y)
+    assert abs(loss - tl) <= 1e-12 * abs(tl)
+    for k in g:
+        scale = max(np.abs(tg[k]).max(), 1e-30)
+        assert np.abs(g[k] - tg[k]).max() <= 1e-11 * scale, k
+    # and the mode does change the result (it is not a no-op)
+    l0, g0 = oc.loss_and_grads(params, x, y)
+    assert abs(l0 - loss) > 1e-7

@@ -11,7 +11,7 @@ CFG = wl.CONFIGS["tiny_gru"]
 
 def _batch_fn(cfg):
     shards = [wl.make_shard(cfg, k) for k in range(cfg["K"])]
-    return lambda k, s: wl.host_batch(cfg, shards[k], wl.batch_indices(cfg, k, s))
+    return lambda k, s: oc.gather_batch(cfg["kind"], shards[k][0], shards[k][1], wl.batch_indices(cfg, k, s))
 
 
 def _close(a, b, tol=1e-12):
