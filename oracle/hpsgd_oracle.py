@@ -189,8 +189,13 @@ def gru_loss_and_grads(params, x, y, rnd=None):
     return loss, g
 
 
-def mlp_loss_and_grads(params, x, y, rnd=None):
-    """ReLU MLP, x float [B,D0], y int [B]; ReLU'(0) = 0."""
+def mlp_loss_and_grads(params, x, y, rnd=None, flip=()):
+    """ReLU MLP, x float [B,D0], y int [B]; ReLU'(0) = 0.
+
+    flip: (layer i, sample b, unit j) triples of hidden units whose ReLU takes the OTHER branch in
+    the backward pass.  For a pre-activation within rounding of zero the branch is decided by the
+    last bits of a sum, so an fp32 implementation may land on either side; a test that finds such
+    units (mlp_preactivations) may accept either branch for them.  Empty by default."""
     p = _f64(params)
     L = 0
     while f"fc{L}.W" in p:
@@ -201,14 +206,29 @@ def mlp_loss_and_grads(params, x, y, rnd=None):
         if i < L - 1:
             a = np.maximum(a, 0.0)
         acts.append(a)
+    masks = [acts[i] > 0.0 for i in range(L)]
+    for (i, b, j) in flip:
+        masks[i + 1][b, j] = not masks[i + 1][b, j]
     loss, delta = softmax_ce(acts[-1], np.asarray(y))
     g = {}
     for i in range(L - 1, -1, -1):
         g[f"fc{i}.W"] = _mm(delta.T, acts[i], rnd)
         g[f"fc{i}.b"] = delta.sum(axis=0)
         if i > 0:
-            delta = _mm(delta, p[f"fc{i}.W"], rnd) * (acts[i] > 0.0)
+            delta = _mm(delta, p[f"fc{i}.W"], rnd) * masks[i]
     return loss, g
+
+
+def mlp_preactivations(params, x):
+    """The hidden layers' pre-activations a_i = h_{i-1} W_i^T + b_i (before the ReLU), i = 0 .. L-2."""
+    p = _f64(params)
+    out, h, i = [], np.asarray(x, F64), 0
+    while f"fc{i + 1}.W" in p:
+        a = h @ p[f"fc{i}.W"].T + p[f"fc{i}.b"]
+        out.append(a)
+        h = np.maximum(a, 0.0)
+        i += 1
+    return out
 
 
 def loss_and_grads(params, x, y, rnd=None):

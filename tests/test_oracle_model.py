@@ -369,3 +369,38 @@ def test_rounded_operand_mode_rounds_exactly_the_matrix_products(name):
     # and the mode does change the result (it is not a no-op)
     l0, g0 = oc.loss_and_grads(params, x, y)
     assert abs(l0 - loss) > 1e-7
+
+
+def test_mlp_relu_branch_hook_is_the_derivative_through_the_other_branch():
+    """mlp_loss_and_grads(flip=...): for the named hidden units the backward pass takes the other
+    branch of the ReLU.  Pinned with the library's autograd on a network whose ReLU derivative is
+    an explicit constant mask (the forward values stay those of the ReLU); with no unit named the
+    gradients are the plain ones."""
+    cfg = wl.scaled(wl.CONFIGS["mlp"], dims=[20, 24, 16, 5], batch=9, K=1)
+    params = wl.init_params(cfg)
+    x, y = _batch(cfg)
+    pre = oc.mlp_preactivations(params, x)
+    assert [a.shape for a in pre] == [(9, 24), (9, 16)]
+    flips = [(0, 1, 2), (0, 3, 7), (1, 8, 15), (1, 0, 0)]
+    masks = [a > 0.0 for a in pre]
+    for (i, b, j) in flips:
+        masks[i][b, j] = not masks[i][b, j]
+    p = {k: torch.tensor(np.asarray(v, np.float64), requires_grad=True) for k, v in params.items()}
+    h = torch.tensor(np.asarray(x, np.float64))
+    for i in range(3):
+        a = h @ p[f"fc{i}.W"].T + p[f"fc{i}.b"]
+        if i < 2:
+            m = torch.tensor(masks[i].astype(np.float64))
+            h = a * m + (torch.relu(a) - a * m).detach()
+        else:
+            h = a
+    loss = torch.nn.functional.cross_entropy(h, torch.tensor(np.asarray(y), dtype=torch.long))
+    loss.backward()
+    l, g = oc.mlp_loss_and_grads(params, x, y, flip=flips)
+    assert abs(l - float(loss)) <= 1e-12
+    for k in g:
+        assert np.abs(g[k] - p[k].grad.numpy()).max() <= 1e-12 * max(1.0, np.abs(g[k]).max()), k
+    l0, g0 = oc.mlp_loss_and_grads(params, x, y)
+    l1, g1 = oc.mlp_loss_and_grads(params, x, y, flip=())
+    assert l0 == l1 and all(np.array_equal(g0[k], g1[k]) for k in g0)
+    assert np.abs(g0["fc0.W"] - g["fc0.W"]).max() > 1e-6
