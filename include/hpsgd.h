@@ -117,6 +117,24 @@ int hpsgd_local_step_all(hpsgd_ctx *ctx, const float *replicas_in, float *replic
                          size_t replica_stride, const void *x, const int32_t *y, float lr,
                          float *loss_out, void *workspace, void *hip_stream);
 
+/* hpsgd_local_step_all for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is a fixed array of HPSGD_STATIC_WORKSPACE_BYTES in the library's own device image
+ * (every GPU the library runs on holds one copy until the process ends); its address on the
+ * current device is looked up on the first call there.  The call allocates nothing, and computes
+ * exactly what hpsgd_local_step_all computes (same kernels, same bits).
+ * HPSGD_EWORKSPACE if hpsgd_workspace_bytes(ctx) exceeds HPSGD_STATIC_WORKSPACE_BYTES (checked
+ * first, before any device is touched); otherwise errors as for hpsgd_local_step_all.
+ * All calls on one GPU share that GPU's array, whatever their context: two calls that may run
+ * concurrently on one GPU race (order them on one stream or with events).  The array keeps the
+ * last call's contents; a step clears what it needs to start from zero itself.
+ * hpsgd_recurrence_gave_up does not apply (it reads a caller's workspace): a given-up wait still
+ * shows as NaN in loss_out and in the first parameter of every output replica. */
+#define HPSGD_STATIC_WORKSPACE_BYTES (32u << 20)
+int hpsgd_local_step_all_static(hpsgd_ctx *ctx, const float *replicas_in, float *replicas_out,
+                                size_t replica_stride, const void *x, const int32_t *y, float lr,
+                                float *loss_out, void *hip_stream);
+
 /* Optional, between "make replica" and the local step (Alg. 2): makes, on hip_stream, the
  * operand copies that the next hpsgd_local_step_all(_acc) on (replicas, replica_stride,
  * workspace) would otherwise make at its start - in the bf16 configurations the rounded and the

@@ -28,6 +28,7 @@ EXPORTS = [
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
     "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
+    "hpsgd_local_step_all_static",
 ]
 ROLE_COUNT = 14
 KERNEL_COUNT = 19
@@ -68,6 +69,7 @@ def load_library():
     lib.hpsgd_workspace_bytes.argtypes = [vp]
     lib.hpsgd_workspace_bytes.restype = sz
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
+    lib.hpsgd_local_step_all_static.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp]
     lib.hpsgd_prepare_replicas.argtypes = [vp, vp, sz, vp, vp]
     lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
@@ -251,6 +253,13 @@ class Context:
                                              replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
                                              _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
                "hpsgd_local_step_all")
+
+    def local_step_all_static(self, replicas_in, replicas_out, x, y, lr, loss_out, stream=None):
+        """local_step_all on the library's fixed workspace (no workspace argument, nothing allocated)."""
+        _check(self.lib.hpsgd_local_step_all_static(self._h, _ptr(replicas_in), _ptr(replicas_out),
+                                                    replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
+                                                    _ptr(loss_out), _stream(stream)),
+               "hpsgd_local_step_all_static")
 
     def prepare_replicas(self, replicas, workspace, stream=None):
         """Make the next local step's operand copies of the weights now (see hpsgd_prepare_replicas)."""

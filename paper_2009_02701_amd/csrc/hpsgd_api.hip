@@ -1176,6 +1176,27 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   return HPSGD_OK;
 }
 
+// ---- the workspace of hpsgd_local_step_all_static: a fixed array in device memory, one copy per
+// device (every device that loads the library holds it until the process ends).  In host code the
+// array's name is only a handle for hipGetSymbolAddress; the address kernels and copies use is
+// the one that call returns, looked up once per device with that device current.
+static __device__ __align__(256) unsigned char g_static_workspace[HPSGD_STATIC_WORKSPACE_BYTES];
+std::mutex g_static_mu;
+void* g_static_workspace_ptr[kMaxDevices] = {nullptr};
+
+int static_workspace(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return HPSGD_EHIP;
+  std::lock_guard<std::mutex> lock(g_static_mu);
+  if (!g_static_workspace_ptr[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_workspace)) != hipSuccess || !p) return HPSGD_EHIP;
+    g_static_workspace_ptr[dev] = p;
+  }
+  *out = g_static_workspace_ptr[dev];
+  return HPSGD_OK;
+}
+
 int check_step_args(const hpsgd_ctx* c, const float* rin, float* rout, size_t rstride, int groups,
                     const void* x, const int32_t* y, const void* ws) {
   if (!c || !rin || !rout || !x || !y) return HPSGD_EINVAL;
@@ -1274,6 +1295,20 @@ int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replic
   TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
   return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
                   (float*)workspace, (hipStream_t)hip_stream);
+}
+
+int hpsgd_local_step_all_static(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,
+                                size_t replica_stride, const void* x, const int32_t* y, float lr,
+                                float* loss_out, void* hip_stream) {
+  if (!ctx) return HPSGD_EINVAL;
+  // the size check comes first and needs no device
+  if (ctx->ws_floats * sizeof(float) > (size_t)HPSGD_STATIC_WORKSPACE_BYTES) return HPSGD_EWORKSPACE;
+  if (!replicas_in || !replicas_out || !x || !y) return HPSGD_EINVAL;
+  void* ws = nullptr;
+  TRY0(static_workspace(&ws));
+  TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, ws));
+  return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out, (float*)ws,
+                  (hipStream_t)hip_stream);
 }
 
 int hpsgd_prepare_replicas(hpsgd_ctx* ctx, const float* replicas, size_t replica_stride, void* workspace,

@@ -190,3 +190,18 @@ def test_kernel_timer_entry_points_on_the_host():
     assert lib.hpsgd_kernel_timer_read(ctx._h, 1, C.byref(n), C.byref(ms), C.byref(w)) == 0
     assert n.value == 0 and ms.value == 0.0 and w.value == 0.0
     assert ctx.kernel_names()[4] == "gru_bwd_persist_bf16_kernel"
+
+
+def test_static_workspace_entry_point_checks_the_size_before_any_device():
+    """hpsgd_local_step_all_static refuses a model whose workspace exceeds its fixed array; the
+    check needs no GPU.  The limit is the header's."""
+    lib = hb.load_library()
+    hdr = open(os.path.join(ROOT, "include", "hpsgd.h")).read()
+    assert re.search(r"#define HPSGD_STATIC_WORKSPACE_BYTES \(32u << 20\)", hdr)
+    ctx = hb.Context(wl.CONFIGS["gru_cls"])
+    assert ctx.workspace_bytes > (32 << 20)
+    dummy = C.c_void_p(4096)
+    assert lib.hpsgd_local_step_all_static(ctx._h, dummy, dummy, C.c_size_t(ctx.stride), dummy, dummy,
+                                           C.c_float(0.1), None, None) == 5
+    assert lib.hpsgd_local_step_all_static(None, dummy, dummy, C.c_size_t(4), dummy, dummy, C.c_float(0.1), None,
+                                           None) == 1
