@@ -316,6 +316,18 @@ def main():
         ts = [ev[2 * i + 1].elapsed_time(ev[2 * i + 2]) for i in range(iters)]
         t_merge, t_sync = sum(tm) / iters, sum(ts) / iters
         bm, bs = 4.0 * (K5 + 3) * P5, 4.0 * (K5 + 2) * P5
+        # merge and clone of the same generation as one pass (hpsgd_merge_sync, 4 (2K + 4) B/param)
+        fe = [torch.cuda.Event(enable_timing=True) for _ in range(iters + 1)]
+        for _ in range(3):
+            hb.merge_sync(G, reps, S)
+        fe[0].record(st)
+        for i in range(iters):
+            hb.merge_sync(G, reps, S)
+            fe[i + 1].record(st)
+        torch.cuda.synchronize()
+        tf = [fe[i].elapsed_time(fe[i + 1]) for i in range(iters)]
+        t_fused = sum(tf) / iters
+        bf_ = 4.0 * (2 * K5 + 4) * P5
         # the gradient-form merge (Eq. 1 as printed) on the same buffers taken as accumulators
         g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         for _ in range(3):
@@ -335,6 +347,9 @@ def main():
             "merge_plus_sync_ms": t_merge + t_sync,
             "merge_plus_sync_GBps": (bm + bs) / (t_merge + t_sync) / 1e6,
             "merge_plus_sync_frac_hbm": (bm + bs) / (t_merge + t_sync) / 1e6 / PEAK_HBM_GBS,
+            "merge_sync_one_pass_ms": t_fused, "merge_sync_one_pass_ms_median": statistics.median(tf),
+            "merge_sync_one_pass_ms_min": min(tf), "merge_sync_one_pass_GBps": bf_ / t_fused / 1e6,
+            "merge_sync_one_pass_frac_hbm": bf_ / t_fused / 1e6 / PEAK_HBM_GBS,
             "merge_grad_ms": t_mg, "merge_grad_GBps": bs / t_mg / 1e6, "merge_grad_frac_hbm": bs / t_mg / 1e6 / PEAK_HBM_GBS,
         }
         del G, S, R, reps

@@ -237,6 +237,16 @@ int hpsgd_sync_replica(const float *global, float *replica, size_t P, void *hip_
 int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *snapshot,
                    size_t P, void *hip_stream);
 
+/* ---- merge and sync of one generation in one pass (Eq. 1 / Alg. 3 "update global model", then
+ *      Alg. 2 "make replica" for the same workers) ---------------------------------------------
+ * Exactly hpsgd_merge(global, replicas, snapshot, K, P) followed by hpsgd_sync_all(global, replicas,
+ * K, snapshot, P), bit for bit, with every buffer read once and written once: 4 (2K + 4) bytes per
+ * parameter instead of 4 (2K + 5).  For the synchronising side of the overlapped schedule, where
+ * the replicas whose changes were just merged are the ones cloned next.  All K + 2 buffers are
+ * written: none may overlap another (HPSGD_EALIAS; `snapshot` may therefore not be `global` here). */
+int hpsgd_merge_sync(float *global, float *const *replicas, float *snapshot, int K, size_t P,
+                     void *hip_stream);
+
 /* ---- kernel timing for benchmarks (not part of the method) ------------------------------
  * The launches of one local step fall into roles.  While a role's bit is set in the mask,
  * hpsgd_local_step(_all) records a HIP event pair on the caller's stream around every launch

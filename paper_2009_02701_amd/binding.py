@@ -28,7 +28,7 @@ EXPORTS = [
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
     "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
-    "hpsgd_local_step_all_static",
+    "hpsgd_local_step_all_static", "hpsgd_merge_sync",
 ]
 ROLE_COUNT = 14
 KERNEL_COUNT = 19
@@ -76,6 +76,7 @@ def load_library():
     lib.hpsgd_gather_batch_all.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, C.c_int, sz, C.c_int, sz,
                                            C.POINTER(vp), vp]
     lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
+    lib.hpsgd_merge_sync.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
     lib.hpsgd_set_aux_stream.argtypes = [vp, vp]
@@ -294,6 +295,13 @@ def merge(global_, replicas, snapshot, stream=None):
     P = global_.numel()
     _check(load_library().hpsgd_merge(_ptr(global_), _ptr_array(reps), _ptr(snapshot), len(reps), P,
                                       _stream(stream)), "hpsgd_merge")
+
+
+def merge_sync(global_, replicas, snapshot, stream=None):
+    """merge followed by sync_all of the same replicas and snapshot, in one pass."""
+    reps = list(replicas)
+    _check(load_library().hpsgd_merge_sync(_ptr(global_), _ptr_array(reps), _ptr(snapshot), len(reps),
+                                           global_.numel(), _stream(stream)), "hpsgd_merge_sync")
 
 
 def sync_replica(global_, replica, stream=None):

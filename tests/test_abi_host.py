@@ -205,3 +205,19 @@ def test_static_workspace_entry_point_checks_the_size_before_any_device():
                                            C.c_float(0.1), None, None) == 5
     assert lib.hpsgd_local_step_all_static(None, dummy, dummy, C.c_size_t(4), dummy, dummy, C.c_float(0.1), None,
                                            None) == 1
+
+
+def test_merge_sync_checks_its_arguments_on_the_host():
+    lib = hb.load_library()
+    P = 64
+    a = lambda i: C.c_void_p(0x10000 + 0x1000 * i)
+    reps = (C.c_void_p * 2)(a(2), a(3))
+    assert lib.hpsgd_merge_sync(a(0), reps, a(1), 0, P, None) == 1                      # K < 1
+    assert lib.hpsgd_merge_sync(None, reps, a(1), 2, P, None) == 1                      # null
+    assert lib.hpsgd_merge_sync(a(0), reps, a(1), 2, 0, None) == 0                      # empty: no-op
+    assert lib.hpsgd_merge_sync(C.c_void_p(0x10004), reps, a(1), 2, P, None) == 3       # alignment
+    assert lib.hpsgd_merge_sync(a(0), reps, a(0), 2, P, None) == 4                      # snapshot == global
+    same = (C.c_void_p * 2)(a(2), a(2))
+    assert lib.hpsgd_merge_sync(a(0), same, a(1), 2, P, None) == 4                      # a replica twice
+    onto = (C.c_void_p * 2)(a(2), a(1))
+    assert lib.hpsgd_merge_sync(a(0), onto, a(1), 2, P, None) == 4                      # replica == snapshot

@@ -191,3 +191,57 @@ def test_gather_all_workers_one_launch_bit_exact():
         wx, wy = oc.gather_batch(cfg["kind"], shards[k][0], shards[k][1], idx[k])
         assert np.array_equal(ox[k].cpu().numpy().view(np.uint32), wx.view(np.uint32))
         assert np.array_equal(oy[k].cpu().numpy(), wy)
+
+
+@pytest.mark.parametrize("P", [0, 1, 3, 4, 1021, 65536, 1000003])
+@pytest.mark.parametrize("K", [1, 2, 3, 8, 16, 32])
+def test_merge_sync_equals_merge_then_sync_bit_for_bit(P, K):
+    """hpsgd_merge_sync against hpsgd_merge followed by hpsgd_sync_all on copies of the same
+    buffers (every bit of the K + 2 outputs), and the merged model against the oracle."""
+    g0, s0 = _vec(1, P), _vec(2, P)
+    reps = [(s0 + _vec(10 + k, P, 1e-2)).astype(np.float32) for k in range(K)]
+    outs = []
+    for fused in (False, True):
+        G = torch.from_numpy(g0.copy()).to(DEV)
+        S = torch.from_numpy(s0.copy()).to(DEV)
+        R = [torch.from_numpy(r.copy()).to(DEV) for r in reps]
+        if fused:
+            hb.merge_sync(G, R, S)
+        else:
+            hb.merge(G, R, S)
+            hb.sync_all(G, R, S)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().view(np.uint32) for t in [G, S] + R])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    if P:
+        want = oc.merge(g0, reps, s0)
+        got = outs[1][0].view(np.float32).astype(np.float64)
+        assert np.abs(got - want).max() <= 1e-4 * np.abs(want - g0).max() + 6e-8 * np.abs(want).max()
+        for t in outs[1][1:]:
+            assert np.array_equal(t, outs[1][0])   # replicas and snapshot are clones of the merged model
+
+
+def test_merge_sync_full_size_sampled():
+    """Config 5 at its full size through hpsgd_merge_sync: sampled outputs against the oracle, and
+    the whole vectors of the K + 1 clones against the merged model."""
+    P, K = CFG5["P"], CFG5["K"]
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    G = torch.rand(P, device=DEV, generator=gen) * 2 - 1
+    S = torch.empty_like(G)
+    R = torch.empty(K, P, device=DEV)
+    hb.sync_all(G, list(R), S)
+    G.add_(torch.randn(P, device=DEV, generator=gen) * 1e-3)   # the global model has moved since the clone
+    for k in range(K):
+        R[k].add_(torch.randn(P, device=DEV, generator=gen) * 1e-3)
+    idx = np.unique(np.concatenate([np.arange(0, 4096), np.arange(P - 4096, P),
+                                    np.random.default_rng(6).integers(0, P, 200_000)]))
+    it = torch.from_numpy(idx).to(DEV)
+    g0, s0 = G[it].cpu().numpy(), S[it].cpu().numpy()
+    reps = [R[k][it].cpu().numpy() for k in range(K)]
+    hb.merge_sync(G, list(R), S)
+    torch.cuda.synchronize()
+    want = oc.merge(g0, reps, s0)
+    got = G[it].cpu().numpy().astype(np.float64)
+    assert np.abs(got - want).max() <= 1e-4 * np.abs(want - g0).max() + 6e-8 * np.abs(want).max()
+    assert torch.equal(S, G) and all(torch.equal(R[k], G) for k in range(K))
