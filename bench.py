@@ -120,8 +120,10 @@ def main():
     ap.add_argument("--no-merge-stress", action="store_true")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the other configurations, the schedule comparisons and the matrix-core probe")
-    ap.add_argument("--prepare", action="store_true",
-                    help="make the next step's bf16 weight copies on the synchronising stream (measured slower)")
+    ap.add_argument("--prepare", default="clones_a", choices=["off", "replicas_b", "clones_b", "clones_a"],
+                    help="where the bf16 weight copies of a round's freshly cloned replicas are made: by the local "
+                         "step itself from the K replicas (off), ahead on the synchronising stream from the replicas "
+                         "or from the clone's source, or on the training stream from the clone's source (default)")
     ap.add_argument("--workload", default="gru_lm", choices=["gru_cls", "gru_lm", "mlp", "tiny_gru"],
                     help="default: config 3, the largest configuration that fits one GPU")
     args = ap.parse_args()
@@ -135,7 +137,7 @@ def main():
     from paper_2009_02701_amd import harness, workloads as wl
 
     dev = "cuda:0"
-    cfg, init, shards, tr = make_trainer(wl, harness, args.workload, dev, args.prepare)
+    cfg, init, shards, tr = make_trainer(wl, harness, args.workload, dev, False if args.prepare == "off" else args.prepare)
     K, B, lr = cfg["K"], cfg["batch"], cfg["lr"]
     knames = tr.ctx.kernel_names()
     per_round = samples_per_round(cfg)

@@ -149,6 +149,17 @@ int hpsgd_local_step_all_static(hpsgd_ctx *ctx, const float *replicas_in, float 
 int hpsgd_prepare_replicas(hpsgd_ctx *ctx, const float *replicas, size_t replica_stride,
                            void *workspace, void *hip_stream);
 
+/* The same for replicas that are clones of the global model (Alg. 2 "make replica": the caller has
+ * called, or will have called by the time of the local step, hpsgd_sync_all(global, replicas ...)
+ * and nothing has written them since): the K workers' operand copies are made from `global`, which
+ * is read once instead of K times.  A clone knows that its K outputs are equal; the local step that
+ * follows does not use that, it reads K separate sets of copies.  The caller vouches for the
+ * equality: a step whose replicas differ from `global` would multiply with the wrong weights.
+ * `replicas` / replica_stride / workspace are those of the next local step (they name the mark, as
+ * for hpsgd_prepare_replicas; the replicas are not read here).  Errors as above. */
+int hpsgd_prepare_clones(hpsgd_ctx *ctx, const float *global, const float *replicas, size_t replica_stride,
+                         void *workspace, void *hip_stream);
+
 /* The same for ONE worker (`worker` in [0, K) selects nothing but the workspace slice,
  * so that different workers may be stepped on different streams).  loss_out: 1 float. */
 int hpsgd_local_step(hpsgd_ctx *ctx, int worker, const float *replica_in, float *replica_out,

@@ -28,7 +28,7 @@ EXPORTS = [
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
     "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
-    "hpsgd_local_step_all_static", "hpsgd_merge_sync",
+    "hpsgd_local_step_all_static", "hpsgd_merge_sync", "hpsgd_prepare_clones",
 ]
 ROLE_COUNT = 14
 KERNEL_COUNT = 19
@@ -71,6 +71,7 @@ def load_library():
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_local_step_all_static.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp]
     lib.hpsgd_prepare_replicas.argtypes = [vp, vp, sz, vp, vp]
+    lib.hpsgd_prepare_clones.argtypes = [vp, vp, vp, sz, vp, vp]
     lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
     lib.hpsgd_gather_batch_all.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, C.c_int, sz, C.c_int, sz,
@@ -266,6 +267,11 @@ class Context:
         """Make the next local step's operand copies of the weights now (see hpsgd_prepare_replicas)."""
         _check(self.lib.hpsgd_prepare_replicas(self._h, _ptr(replicas), replicas.stride(0), self._ws_ptr(workspace),
                                                _stream(stream)), "hpsgd_prepare_replicas")
+
+    def prepare_clones(self, global_, replicas, workspace, stream=None):
+        """prepare_replicas for replicas that are clones of `global_` (read once instead of K times)."""
+        _check(self.lib.hpsgd_prepare_clones(self._h, _ptr(global_), _ptr(replicas), replicas.stride(0),
+                                             self._ws_ptr(workspace), _stream(stream)), "hpsgd_prepare_clones")
 
     def local_step_all_acc(self, replicas_in, replicas_out, x, y, lr, loss_out, grad_acc, workspace, stream=None):
         """local_step_all that also adds every worker's gradient to grad_acc [K, stride]."""

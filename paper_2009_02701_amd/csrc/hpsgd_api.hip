@@ -1331,6 +1331,29 @@ int hpsgd_prepare_replicas(hpsgd_ctx* ctx, const float* replicas, size_t replica
   return HPSGD_OK;
 }
 
+int hpsgd_prepare_clones(hpsgd_ctx* ctx, const float* global, const float* replicas, size_t replica_stride,
+                         void* workspace, void* hip_stream) {
+  if (!ctx || !global || !replicas) return HPSGD_EINVAL;
+  if (!workspace || ((uintptr_t)workspace & 255) != 0) return HPSGD_EWORKSPACE;
+  if (!aligned16(global) || !aligned16(replicas) ||
+      (ctx->K > 1 && (replica_stride < ctx->P || (replica_stride & 3) != 0)))
+    return HPSGD_EALIGN;
+  const size_t span = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
+  const size_t ws_bytes = ctx->ws_floats * sizeof(float);
+  if (overlaps(workspace, ws_bytes, replicas, span) || overlaps(workspace, ws_bytes, global, ctx->P * sizeof(float)))
+    return HPSGD_EALIAS;
+  ctx->prepared_rin = nullptr;
+  if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
+  WeightCopies wc;
+  // every worker's copies from the one source: group stride 0
+  const int rc = weight_copies(ctx, global, 0, 0, ctx->K, (float*)workspace, (hipStream_t)hip_stream, true, true, wc);
+  if (rc != HPSGD_OK) return rc;
+  ctx->prepared_rin = replicas;
+  ctx->prepared_ws = (const float*)workspace;
+  ctx->prepared_stride = replica_stride;
+  return HPSGD_OK;
+}
+
 int hpsgd_local_step_all_acc(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,
                              size_t replica_stride, const void* x, const int32_t* y, float lr,
                              float* loss_out, float* grad_acc, size_t acc_stride, void* workspace,

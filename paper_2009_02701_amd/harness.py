@@ -102,8 +102,20 @@ class Trainer:
         """hpsgd_prepare_replicas for generation `gen`, whose local steps use workspace `gen`."""
         if self.ws[gen] is None:
             self.ws[gen] = self.ctx.new_workspace(self.dev)
-        if self.use_prepare:
+        if self.use_prepare == "clones_b":
+            # (the snapshot is the clone's source as it was at clone time; the global model moves on)
+            self.ctx.prepare_clones(self.S[gen][:self.P], self.R[gen], self.ws[gen], stream=stream)
+        elif self.use_prepare is True or self.use_prepare == "replicas_b":
             self.ctx.prepare_replicas(self.R[gen], self.ws[gen], stream=stream)
+
+    def prepare_clones_on_training_stream(self, gen: int, stream=None):
+        """The operand copies of freshly cloned replicas, made on the training stream right before the
+        local step (which then skips its own) from the generation's snapshot: the global model as it
+        was when the replicas were cloned (the global model itself may already have moved on)."""
+        if self.use_prepare == "clones_a":
+            if self.ws[gen] is None:
+                self.ws[gen] = self.ctx.new_workspace(self.dev)
+            self.ctx.prepare_clones(self.S[gen][:self.P], self.R[gen], self.ws[gen], stream=stream)
 
     def merge(self, gen: int, stream=None):
         hb.merge(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
@@ -276,6 +288,7 @@ class Trainer:
         self._ev_b.record(sb)
         # training side (stream A): this round's local step on generation g
         self.gather(t, sa)
+        self.prepare_clones_on_training_stream(g, sa)
         self.local_step(g, lr, sa, ws=g)
         if record_loss:
             with torch.cuda.stream(sa):

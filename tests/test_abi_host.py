@@ -221,3 +221,18 @@ def test_merge_sync_checks_its_arguments_on_the_host():
     assert lib.hpsgd_merge_sync(a(0), same, a(1), 2, P, None) == 4                      # a replica twice
     onto = (C.c_void_p * 2)(a(2), a(1))
     assert lib.hpsgd_merge_sync(a(0), onto, a(1), 2, P, None) == 4                      # replica == snapshot
+
+
+def test_prepare_clones_checks_its_arguments_on_the_host():
+    lib = hb.load_library()
+    ctx = hb.Context(wl.CONFIGS["tiny_gru"])   # fp32: nothing to prepare, but the arguments are checked
+    a = lambda i: C.c_void_p(0x100000 + 0x10000 * i)
+    ws = C.c_void_p(0x4000000)
+    assert lib.hpsgd_prepare_clones(None, a(0), a(1), C.c_size_t(ctx.stride), ws, None) == 1
+    assert lib.hpsgd_prepare_clones(ctx._h, None, a(1), C.c_size_t(ctx.stride), ws, None) == 1
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), None, None) == 5
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), C.c_void_p(0x4000010), None) == 5
+    assert lib.hpsgd_prepare_clones(ctx._h, C.c_void_p(0x100004), a(1), C.c_size_t(ctx.stride), ws, None) == 3
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.P - 1), ws, None) == 3   # stride < P
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), a(1), None) == 4  # workspace on the replicas
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), ws, None) == 0

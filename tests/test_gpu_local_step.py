@@ -690,3 +690,53 @@ def test_kernel_timer_counts_the_launches_of_one_kernel():
     assert sum(v for k, v in seen.items() if k.startswith("gemm_bf16")) >= 3 + 3 * L
     assert all(tr.ctx.kernel_timer_read(kid)[0] == 0 for kid in range(1, hb.KERNEL_COUNT))
     tr.ctx.kernel_timer_enable([])
+
+
+@pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "lm_nt_bf16_h384", "cls_nt_bf16", "tiny_gru"])
+@pytest.mark.parametrize("mode", ["clones_a", "clones_b", "replicas_b"])
+def test_operand_copies_made_from_the_clone_source_change_no_bit(name, mode):
+    """hpsgd_prepare_clones (the bf16 weight copies of freshly cloned replicas made from the clone's
+    source, read once instead of K times) and hpsgd_prepare_replicas in the overlapped schedule: the
+    same global model, bit for bit, as with the copies made by the local step itself; also for a
+    model that has no such copies (fp32), where the calls do nothing."""
+    cfg = BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for prepare in (False, mode):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, prepare=prepare)
+        tr.s_ovl(cfg["lr"], rounds=4)
+        outs.append((tr.G.clone(), torch.stack(tr.losses)))
+        del tr
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    assert torch.isfinite(outs[0][0]).all()
+
+
+def test_prepare_clones_mark_is_used_once_and_only_for_its_buffers():
+    """A step after hpsgd_prepare_clones equals a plain step; the second step on the same buffers
+    makes its own copies again (the weights have changed); a mark for other replicas is ignored."""
+    cfg = BF16["lm_nt_bf16_tiles"]
+    init, shards, orders, _ = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.sync_all(0)
+    tr.sync_all(1)
+    tr.gather(0)
+    torch.cuda.synchronize()
+    lr = cfg["lr"]
+    ref, got = tr.R[0], tr.R[1]
+    ws_ref, ws = tr.ctx.new_workspace(DEV), tr.ctx.new_workspace(DEV)
+    l_ref, l_got = torch.zeros(2, cfg["K"], device=DEV), torch.zeros(2, cfg["K"], device=DEV)
+    for i in range(2):
+        tr.ctx.local_step_all(ref, ref, tr.xb, tr.yb, lr, l_ref[i], ws_ref)
+    tr.ctx.prepare_clones(tr.S[1][:tr.P], got, ws)
+    for i in range(2):
+        tr.ctx.local_step_all(got, got, tr.xb, tr.yb, lr, l_got[i], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(got[:, :tr.P], ref[:, :tr.P]) and torch.equal(l_got, l_ref)
+    # a mark made for other replicas (from a source that does not match) must not be picked up
+    other = torch.zeros_like(got)
+    junk = torch.full_like(tr.S[1], 3.0)
+    tr.ctx.prepare_clones(junk[:tr.P], other, ws)
+    tr.ctx.local_step_all(ref, ref, tr.xb, tr.yb, lr, l_ref[0], ws_ref)
+    tr.ctx.local_step_all(got, got, tr.xb, tr.yb, lr, l_got[0], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(got[:, :tr.P], ref[:, :tr.P]) and torch.equal(l_got[0], l_ref[0])
