@@ -185,6 +185,24 @@ def main():
     spread = {"rounds": n_spread, "median_ms": statistics.median(per_round_ms), "min_ms": min(per_round_ms),
               "max_ms": max(per_round_ms), "mean_ms": sum(per_round_ms) / n_spread}
 
+    # ---- the same rounds replayed from a HIP graph (one graph = `period` rounds; extra key, the
+    # headline stays the eagerly issued schedule): what is left of the host's share
+    graph_replay = None
+    if not args.no_extras:
+        graph = tr.ovl_capture(step, lr)
+        period = tr.ovl_replay(graph)   # the capture itself ran nothing: this replay issues the captured rounds
+        step += period
+        n_rep = max(1, args.steps // period)
+        torch.cuda.synchronize()
+        c0 = time.perf_counter()
+        for _ in range(n_rep):
+            step += tr.ovl_replay(graph)
+        torch.cuda.synchronize()
+        el_g = time.perf_counter() - c0
+        graph_replay = {"rounds_per_graph": period, "replays": n_rep, "ms_per_step": 1e3 * el_g / (n_rep * period),
+                        "value": per_round * n_rep * period / el_g, "unit": unit}
+        del graph
+
     # ---- the same region once more with a HIP event pair around every launch of the dominant
     # kernel only (recorded by its launcher on the stream the launch goes to): the roofline's
     # launch duration, and the kernel's algorithmic work as its launcher counts it
@@ -403,7 +421,7 @@ def main():
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
                    "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
         "roofline": roofline, "cpu_baseline": cpu, "ms_per_step_spread": spread, "overlap": overlap,
-        "kernels": kernels, "merge_stress": merge_stress, "other_workloads": others,
+        "kernels": kernels, "hip_graph_replay": graph_replay, "merge_stress": merge_stress, "other_workloads": others,
         "cpu_baseline_one_thread": cpu_1t,
         "recurrence_launches": {"resident_weight_layers": fused[0], "with_input_projection": fused[1],
                                 "with_dW_hh_and_bias_gradients": fused[2]},

@@ -299,6 +299,42 @@ class Trainer:
         self._g = 1 - g
         self._have_delta = True
 
+    # ------------------------------------------------------------------ overlapped rounds as a HIP graph
+    def ovl_capture(self, t0: int, lr: float):
+        """Captures the next `period` overlapped rounds (starting at round t0, which must continue an
+        ovl_begin / ovl_round sequence with at least two rounds behind it) into one HIP graph and
+        returns it; period = lcm(2 buffer generations, batches per shard), after which the rounds'
+        arguments repeat, so every replay issues the rounds t0 + i * period ... of the schedule.
+        The host then launches one graph per `period` rounds instead of some twenty to forty kernels
+        per round.  The two side streams (synchronising, auxiliary) join the capture through the
+        events the schedule records anyway, and every round ends with the training stream waiting
+        for the synchronising one, so the capture closes on the training stream alone.
+        Nothing in the rounds is a memset (cleared memory is cleared by kernels), and nothing
+        allocates."""
+        assert self._have_delta and self._sb is not self._sa
+        period = self.n_batches if self.n_batches % 2 == 0 else 2 * self.n_batches
+        graph = torch.cuda.CUDAGraph()
+        torch.cuda.synchronize(self.dev)
+        with torch.cuda.stream(self._sa):
+            graph.capture_begin(capture_error_mode="thread_local")
+            try:
+                # the event the synchronising stream waits for at the start of a round, recorded anew
+                # inside the capture: a wait for the one recorded before it would tie the graph to
+                # work outside it (everything before the capture precedes the graph on this stream)
+                self._ev_a.record(self._sa)
+                for i in range(period):
+                    self.ovl_round(t0 + i, lr)
+            finally:
+                graph.capture_end()
+        self._graph_period = period
+        return graph
+
+    def ovl_replay(self, graph):
+        """One replay = `period` rounds (see ovl_capture), issued on the training stream."""
+        with torch.cuda.stream(self._sa):
+            graph.replay()
+        return self._graph_period
+
     def ovl_drain(self):
         if self._have_delta:
             self.merge(1 - self._g, self._sa)

@@ -740,3 +740,52 @@ def test_prepare_clones_mark_is_used_once_and_only_for_its_buffers():
     tr.ctx.local_step_all(got, got, tr.xb, tr.yb, lr, l_got[0], ws)
     torch.cuda.synchronize()
     assert torch.equal(got[:, :tr.P], ref[:, :tr.P]) and torch.equal(l_got[0], l_ref[0])
+
+
+@pytest.mark.parametrize("name", ["tiny_gru", "mlp_tiles", "lm_nt_bf16_tiles", "gru_cls_tiles"])
+def test_overlapped_rounds_replayed_from_a_hip_graph(name):
+    """Trainer.ovl_capture / ovl_replay: one graph holds a whole period of overlapped rounds (three
+    streams, resident-weight launches, fill kernels instead of memsets).  Replayed several times,
+    with the program's own eager rounds and device synchronisations between the replays, every
+    replay must leave the bits the eagerly issued schedule leaves at the same round."""
+    cfg = (SMALL.get(name) or BF16.get(name) or wl.CONFIGS[name])
+    init, shards, orders, _ = workload(cfg)
+    lr = cfg["lr"]
+
+    def run(plan):
+        """plan: 'g' = one replay of the graph (captured at its first use), n = n eager rounds;
+        the device is synchronised after every item; returns the global model after each."""
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, prepare="clones_a")
+        tr.ovl_begin()
+        t, snaps, graph, t_cap = 0, [], None, None
+        for _ in range(3):
+            tr.ovl_round(t, lr)
+            t += 1
+        for item in plan:
+            if item == "g":
+                if graph is None:
+                    graph, t_cap = tr.ovl_capture(t, lr), t
+                # a replay issues the rounds t .. t + period - 1 only if t is congruent to the
+                # captured start modulo the period: the plans below keep it so
+                assert (t - t_cap) % tr._graph_period == 0
+                t += tr.ovl_replay(graph)
+            else:
+                for _ in range(item):
+                    tr.ovl_round(t, lr)
+                    t += 1
+            torch.cuda.synchronize()
+            snaps.append(tr.G.clone())
+        tr.ovl_drain()
+        snaps.append(tr.G.clone())
+        return snaps, getattr(tr, "_graph_period", None)
+
+    snaps_g, period = run(["g", "g", 0, "g"])
+    # the same with a whole period of eagerly issued rounds between the first and second replay
+    snaps_g2, _ = run(["g", period, "g", "g"])
+    snaps_e, _ = run([period, period, 0, period])
+    snaps_e2, _ = run([period, period, period, period])
+    for a, b in zip(snaps_g, snaps_e):
+        assert torch.equal(a, b)
+    for a, b in zip(snaps_g2, snaps_e2):
+        assert torch.equal(a, b)
+    assert torch.isfinite(snaps_g[-1]).all()
