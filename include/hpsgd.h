@@ -156,7 +156,10 @@ int hpsgd_prepare_replicas(hpsgd_ctx *ctx, const float *replicas, size_t replica
  * follows does not use that, it reads K separate sets of copies.  The caller vouches for the
  * equality: a step whose replicas differ from `global` would multiply with the wrong weights.
  * `replicas` / replica_stride / workspace are those of the next local step (they name the mark, as
- * for hpsgd_prepare_replicas; the replicas are not read here).  Errors as above. */
+ * for hpsgd_prepare_replicas; the replicas are not read here).  The copies of the GRU layers'
+ * matrices are made by this call; those of the head's matrix are made by the marked local step
+ * itself, from `global`, right before its logits product: `global` must stay unchanged until that
+ * step has run (a snapshot of the clone's source does).  Errors as above. */
 int hpsgd_prepare_clones(hpsgd_ctx *ctx, const float *global, const float *replicas, size_t replica_stride,
                          void *workspace, void *hip_stream);
 

@@ -54,6 +54,9 @@ struct hpsgd_ctx {
   const float* prepared_rin = nullptr;
   const float* prepared_ws = nullptr;
   size_t prepared_stride = 0;
+  // hpsgd_prepare_clones left the head's copies to the step: made there from this source (every
+  // worker's from the one matrix), right before the logits GEMM
+  const float* prepared_head_src = nullptr;
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   std::vector<Region> dact;     // per MLP hidden layer: gradient w.r.t. its output
@@ -448,7 +451,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   // step changes the weights, so the mark is used once
   const bool prepared = bf && c->prepared_rin == rin && c->prepared_ws == ws && c->prepared_stride == rstride &&
                         k0 == 0 && groups == c->K;
+  const float* head_src = prepared ? c->prepared_head_src : nullptr;
   c->prepared_rin = nullptr;
+  c->prepared_head_src = nullptr;
   const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
   c->last_resident = c->last_xproj = c->last_dw = 0;
   // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
@@ -755,7 +760,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the copy has the memory system to itself (beside a resident-weight launch it takes 2.3
       // times as long and slows that launch by more than it takes alone; at the start of the step it
       // shares the bandwidth with the merge and the clone)
-      if (!prepared) {
+      if (head_src) {  // the replicas are clones of one model: its head matrix is read once for all workers
+        HIP_TRY(launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
+                            groups, s));
+      } else if (!prepared) {
         HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             groups, s));
       }
@@ -1320,6 +1328,7 @@ int hpsgd_prepare_replicas(hpsgd_ctx* ctx, const float* replicas, size_t replica
   const size_t span = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
   if (overlaps(workspace, ctx->ws_floats * sizeof(float), replicas, span)) return HPSGD_EALIAS;
   ctx->prepared_rin = nullptr;
+  ctx->prepared_head_src = nullptr;
   if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
   WeightCopies wc;
   const int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace,
@@ -1345,9 +1354,13 @@ int hpsgd_prepare_clones(hpsgd_ctx* ctx, const float* global, const float* repli
   ctx->prepared_rin = nullptr;
   if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
   WeightCopies wc;
-  // every worker's copies from the one source: group stride 0
-  const int rc = weight_copies(ctx, global, 0, 0, ctx->K, (float*)workspace, (hipStream_t)hip_stream, true, true, wc);
+  // every worker's copies from the one source: group stride 0.  The GRU layers' now; the head's are
+  // left to the step, which makes them from `global` right before the logits GEMM (made here they
+  // would share the memory system with whatever the synchronising side is doing at a round's start)
+  ctx->prepared_head_src = nullptr;
+  const int rc = weight_copies(ctx, global, 0, 0, ctx->K, (float*)workspace, (hipStream_t)hip_stream, true, false, wc);
   if (rc != HPSGD_OK) return rc;
+  ctx->prepared_head_src = global;
   ctx->prepared_rin = replicas;
   ctx->prepared_ws = (const float*)workspace;
   ctx->prepared_stride = replica_stride;
