@@ -28,13 +28,22 @@ PEAK_HBM_GBS = 8000.0
 STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel"}
 
 # HBM bytes per launch of a kernel, from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
-# WRITE_SIZE, in KiB per dispatch; FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 after calibration
-# with a plain copy kernel of known size), averaged over the kernel's launches.  Summaries with the
-# full commands: profiles/pmc_hbm_traffic_*.md.  Kernels not collected: null.
+# WRITE_SIZE, in KiB per dispatch; FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0: the config-5
+# kernels of the same run are the copy kernels of known size), averaged over the kernel's launches
+# of a round.  Summaries with the full commands: profiles/bench_*.md.  Kernels not collected: null.
+KIB = 1024.0
 MEASURED_TRAFFIC_BYTES = {
-    "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 84280.5 + 133496.3) * 1024,
-                "gru_fwd_persist_kernel": (2.0 * 27504.8 + 89880.0) * 1024},
-    "gru_lm": {},
+    "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 84262.1 + 133497.6) * KIB,
+                "gru_fwd_persist_kernel": (2.0 * 27325.3 + 89880.0) * KIB},
+    # the 192 x 256 form runs three products per round: the logits (746 MB) and two input gradients
+    # (head and top layer; both launch 192 tiles and average 262 MB)
+    "gru_lm": {"gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>":
+                   ((2.0 * 188388.9 + 351905.6) + 2 * (2.0 * 109970.5 + 35840.0)) * KIB / 3,
+               "gru_bwd_persist_bf16_kernel": (2.0 * 159743.3 + 241826.7) * KIB,
+               "gru_fwd_persist_bf16_kernel": (2.0 * 90507.2 + 215604.1) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>": (2.0 * 296277.9 + 320906.3) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>": (2.0 * 95348.4 + 98392.6) * KIB,
+               "softmax_ce_bf16_rows_kernel": (2.0 * 175604.1 + 219299.5) * KIB},
     "mlp": {},
 }
 
