@@ -172,8 +172,9 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
                             long s_y, __bf16* __restrict__ dlog, long ld_d, long s_d,
                             float* __restrict__ rowloss, long s_rowloss, float2* __restrict__ rowstat,
                             long s_rowstat, float* __restrict__ colpart, long s_colpart, int N, int C) {
-  __shared__ float red[4];
-  __shared__ float bcast;
+  // partial results of the four waves, one set per reduction and row parity: a set is written
+  // again two rows later, with two barriers in between, so one barrier per reduction is enough
+  __shared__ float red_m[2][4], red_s[2][4];
   const int g = blockIdx.y, row0 = blockIdx.x * SMR;
   const int nr = min(SMR, N - row0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -203,12 +204,9 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
     if (r + 1 < nr) load_row(row + 1);
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
-    if (lane == 0) red[wave] = m;
+    if (lane == 0) red_m[r & 1][wave] = m;
     __syncthreads();
-    if (tid == 0) bcast = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    m = bcast;
-    __syncthreads();
+    m = fmaxf(fmaxf(red_m[r & 1][0], red_m[r & 1][1]), fmaxf(red_m[r & 1][2], red_m[r & 1][3]));
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < V4; ++i)
@@ -219,12 +217,9 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
       }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o);
-    if (lane == 0) red[wave] = sum;
+    if (lane == 0) red_s[r & 1][wave] = sum;
     __syncthreads();
-    if (tid == 0) bcast = (red[0] + red[1]) + (red[2] + red[3]);
-    __syncthreads();
-    sum = bcast;
-    __syncthreads();
+    sum = (red_s[r & 1][0] + red_s[r & 1][1]) + (red_s[r & 1][2] + red_s[r & 1][3]);
     const float inv_sum = 1.0f / sum;
     if (tid == 0) {
       rowloss[g * s_rowloss + row] = -((logits[g * s_logits + (long)row * C + label] - m) - logf(sum));
