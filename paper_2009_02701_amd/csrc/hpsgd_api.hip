@@ -83,12 +83,14 @@ struct hpsgd_ctx {
   double kernel_ms[HPSGD_KERNEL_COUNT] = {0}, kernel_work[HPSGD_KERNEL_COUNT] = {0};
   long kernel_launches[HPSGD_KERNEL_COUNT] = {0};
 
-  int find(const std::string& n) const {
-    for (size_t i = 0; i < entries.size(); ++i)
-      if (entries[i].name == n) return (int)i;
-    return -1;
-  }
-  size_t off(const std::string& n) const { return entries[find(n)].offset; }
+  // entries of the flat layout by role, filled once by build_layout: the launch plan of a step looks
+  // nothing up by name
+  struct LayerIdx { int wih, whh, bih, bhh; };
+  std::vector<LayerIdx> lidx;       // per GRU layer
+  std::vector<int> fc_w, fc_b;      // per MLP layer
+  int i_embed = -1, i_head_w = -1, i_head_b = -1;
+  size_t eoff(int entry) const { return entries[entry].offset; }
+
 
   Region alloc(size_t per_worker) {
     Region r;
@@ -118,16 +120,23 @@ int build_layout(hpsgd_ctx* c) {
     int width = lm ? d.embed : d.input;
     const int classes = lm ? d.vocab : d.classes;
     if ((long)d.seq_len * d.batch * (long)classes >= big) return HPSGD_ESHAPE;
-    if (lm) add_entry(c, "embed.E", d.vocab, d.embed);
+    if (lm) {
+      c->i_embed = (int)c->entries.size();
+      add_entry(c, "embed.E", d.vocab, d.embed);
+    }
     for (int l = 0; l < d.layers; ++l) {
       const std::string p = "l" + std::to_string(l);
+      const int e0 = (int)c->entries.size();
+      c->lidx.push_back({e0, e0 + 1, e0 + 2, e0 + 3});
       add_entry(c, p + ".W_ih", 3 * d.hidden, width);
       add_entry(c, p + ".W_hh", 3 * d.hidden, d.hidden);
       add_entry(c, p + ".b_ih", 3 * d.hidden, 1);
       add_entry(c, p + ".b_hh", 3 * d.hidden, 1);
       width = d.hidden;
     }
+    c->i_head_w = (int)c->entries.size();
     add_entry(c, "head.W", classes, d.hidden);
+    c->i_head_b = (int)c->entries.size();
     add_entry(c, "head.b", classes, 1);
 
     const size_t TB = (size_t)d.seq_len * d.batch, H = d.hidden;
@@ -188,7 +197,9 @@ int build_layout(hpsgd_ctx* c) {
     if (d.mlp_dims[d.n_mlp_dims - 1] < 2) return HPSGD_ESHAPE;
     for (int i = 0; i + 1 < d.n_mlp_dims; ++i) {
       const std::string p = "fc" + std::to_string(i);
+      c->fc_w.push_back((int)c->entries.size());
       add_entry(c, p + ".W", d.mlp_dims[i + 1], d.mlp_dims[i]);
+      c->fc_b.push_back((int)c->entries.size());
       add_entry(c, p + ".b", d.mlp_dims[i + 1], 1);
     }
     c->grad = c->alloc(c->P);
@@ -384,10 +395,9 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
   const bool ntc = (B % 8 == 0) && (H % 8 == 0);
   const bool fused_b = gru_fused_bf16_supported(H);
   for (int l = 0; l < L && l < 16; ++l) {
-    const std::string p = "l" + std::to_string(l);
     const int width = l > 0 ? H : (lm ? d.embed : d.input);
-    const float* Wih = rin + c->off(p + ".W_ih");
-    const float* Whh = rin + c->off(p + ".W_hh");
+    const float* Wih = rin + c->eoff(c->lidx[l].wih);
+    const float* Whh = rin + c->eoff(c->lidx[l].whh);
     if (fused_b && ntc && width % 8 == 0) {
       const bool need_T = l > 0 || lm;  // the input gradient of this layer is needed
       __bf16* wT = need_T ? bfreg(c->wihTl[l]) : nullptr;
@@ -415,7 +425,7 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
     }
   }
   if (with_head) {
-    const size_t oW = c->off("head.W");
+    const size_t oW = c->eoff(c->i_head_w);
     const long clp = (long)round_up(classes, 64);
     const long s_wob = 2 * (long)c->wob.stride, s_woT = 2 * (long)c->woT.stride;
     if (ntc && fused_b && classes % 8 == 0 &&
@@ -465,10 +475,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   // Where the weight-gradient GEMM of `name` writes: the updated matrix itself (epilogue
   // W_out = W_in - lr * dW), or, when gradients are accumulated as well, the gradient buffer.
   struct WgradTarget { float* C; long sC; int epi; const float* aux; };
-  auto wgrad_target = [&](const std::string& name) -> WgradTarget {
-    const size_t o = c->off(name);
+  auto wgrad_target = [&](int entry) -> WgradTarget {
+    const size_t o = c->eoff(entry);
     if (acc) return WgradTarget{grad + o, sG, EPI_STORE, nullptr};
-    fused_commit[c->find(name)] = 1;
+    fused_commit[entry] = 1;
     return WgradTarget{rout + o, sR, EPI_COMMIT, rin + o};
   };
 
@@ -479,12 +489,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const float* a_in = (const float*)x;
     long s_in = (long)B * dims[0];
     for (int i = 0; i < L; ++i) {
-      const std::string p = "fc" + std::to_string(i);
       float* a_out = reg(c->act[i]);
       role = HPSGD_ROLE_MLP_FWD;
-      TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->off(p + ".W"),
+      TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->eoff(c->fc_w[i]),
                dims[i], sR, 1, a_out, dims[i + 1], (long)c->act[i].stride,
-               i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->off(p + ".b"), sR));
+               i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->eoff(c->fc_b[i]), sR));
       a_in = a_out;
       s_in = (long)c->act[i].stride;
     }
@@ -506,7 +515,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                       1.0f / (float)B))
       return HPSGD_ESHAPE;
     for (int i = L - 1; i >= 0; --i) {
-      const std::string p = "fc" + std::to_string(i);
       const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;
       const long s_prev = i > 0 ? (long)c->act[i - 1].stride : (long)B * dims[0];
       const long s_delta = i == L - 1 ? (long)c->act[i].stride : (long)c->dact[i].stride;
@@ -516,19 +524,19 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         // delta_prev = (delta W) * [a_prev > 0]: before W is updated
         dprev = reg(c->dact[i - 1]);
         TRY(gemm(s, groups, bf, B, dims[i], dims[i + 1], delta, dims[i + 1], s_delta, 0,
-                 rin + c->off(p + ".W"), dims[i], sR, 0, dprev, dims[i], (long)c->dact[i - 1].stride,
+                 rin + c->eoff(c->fc_w[i]), dims[i], sR, 0, dprev, dims[i], (long)c->dact[i - 1].stride,
                  EPI_RELU_MASK, a_prev, s_prev));
       }
       // W' = W - lr * delta^T a_prev
-      const WgradTarget wt = wgrad_target(p + ".W");
+      const WgradTarget wt = wgrad_target(c->fc_w[i]);
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
                s_prev, 0, wt.C, dims[i], wt.sC, wt.epi, wt.aux, sR, 0, lr));
       {
-        const size_t ob = c->off(p + ".b");
+        const size_t ob = c->eoff(c->fc_b[i]);
         const bool pushed = acc ? colsum_pack_push(cp, delta, dims[i + 1], s_delta, grad + ob, sG, nullptr, 0, B, dims[i + 1])
                                 : colsum_pack_push(cp, delta, dims[i + 1], s_delta, rout + ob, sR, rin + ob, sR, B,
                                                    dims[i + 1]);
-        if (pushed && !acc) fused_commit[c->find(p + ".b")] = 1;
+        if (pushed && !acc) fused_commit[c->fc_b[i]] = 1;
         if (!pushed)
           HIP_TRY(launch_colsum(delta, dims[i + 1], s_delta, grad + ob, sG, B, dims[i + 1], groups, s));
       }
@@ -571,9 +579,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                          ntc && (lm ? d.embed : d.input) % 8 == 0 && (sG & 3) == 0 &&
                          c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H;
     for (int l = 0; l < L && use_persist_b; ++l) {
-      const std::string p = "l" + std::to_string(l);
-      use_persist_b = ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
-                      c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H;
+      use_persist_b = ((uintptr_t)(grad + c->eoff(c->lidx[l].bih)) & 15) == 0 &&
+                      c->eoff(c->lidx[l].bhh) == c->eoff(c->lidx[l].bih) + (size_t)3 * H;
     }
     unsigned* psync = (use_persist || use_persist_b) ? (unsigned*)reg(c->psync) : nullptr;
     unsigned pbase = 0;
@@ -583,7 +590,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     }
     // ---- the head's operands
     const int nrows = lm ? TB : B;
-    const size_t oW = c->off("head.W"), ob = c->off("head.b");
+    const size_t oW = c->eoff(c->i_head_w), ob = c->eoff(c->i_head_b);
     const long nrp = (long)round_up(nrows, 64), clp = (long)round_up(classes, 64);
     const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
     const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
@@ -607,7 +614,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     if (lm) {
       float* xe = reg(c->xe);
       role = HPSGD_ROLE_EMBED;
-      HIP_TRY(launch_embed_fwd(rin + c->off("embed.E"), sR, tok, TB, xe, (long)c->xe.stride, TB,
+      HIP_TRY(launch_embed_fwd(rin + c->eoff(c->i_embed), sR, tok, TB, xe, (long)c->xe.stride, TB,
                                d.embed, groups, s));
       lin = xe;
       s_lin = (long)c->xe.stride;
@@ -638,7 +645,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
     }
     for (int l = 0; l < L; ++l) {
-      const std::string p = "l" + std::to_string(l);
       float* hs = reg(c->hs[l]);
       float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
@@ -646,16 +652,16 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (!cleared)
         HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s, l == 0 ? (float*)psync : nullptr,
                                  l == 0 && psync ? gru_persist_sync_words(B, groups) : 0));
-      const float* Whh = rin + c->off(p + ".W_hh");
+      const float* Whh = rin + c->eoff(c->lidx[l].whh);
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
       const bool persist = fused && use_persist;
       // a narrow layer input: the resident-weight kernel does the input projection itself
-      const float* Wih0 = rin + c->off(p + ".W_ih");
+      const float* Wih0 = rin + c->eoff(c->lidx[l].wih);
       const bool xproj = persist && gru_persist_xproj_supported(H, width) && ((uintptr_t)lin & 15) == 0 &&
                          (s_lin & 3) == 0 && ((uintptr_t)Wih0 & 15) == 0;
       if (!xproj) {
-        const float* Wih = rin + c->off(p + ".W_ih");
+        const float* Wih = rin + c->eoff(c->lidx[l].wih);
         NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
         // bf16 precision: both operands as row-major bf16 copies (the layer below wrote its
         // h in bf16; the layer-0 input and W_ih are rounded here, the input also transposed
@@ -679,7 +685,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         }
         role = HPSGD_ROLE_GEMM_INPUT;
         TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
-                  EPI_BIAS, rin + c->off(p + ".b_ih"), sR, va, vb));
+                  EPI_BIAS, rin + c->eoff(c->lidx[l].bih), sR, va, vb));
       }
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
       // not use) and of h
@@ -705,9 +711,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->off(p + ".b_hh"), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
+        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
                                        groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
-                                       Wih0, rin + c->off(p + ".b_ih"), s));
+                                       Wih0, rin + c->eoff(c->lidx[l].bih), s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
         ++c->last_resident;
         c->last_xproj += xproj ? 1 : 0;
@@ -715,7 +721,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx, s_gx, hs, s_hs, hb, s_hb, sv,
+        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, hb, s_hb, sv,
                                             s_sv, hT, TB1p, s_hT, B, H, T, groups, psync, pbase, c->spin_limit, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         ++c->last_resident;
@@ -724,7 +730,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       for (int t = 0; t < T && !persist && !persist_b; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         if (fused_b) {
-          HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H,
+          HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx + (size_t)t * B * 3 * H,
                                            s_gx, hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
                                            hb + (size_t)t * B * H, hb + (size_t)(t + 1) * B * H, s_hb,
                                            sv + (size_t)t * B * 4 * H, s_sv,
@@ -733,13 +739,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           continue;
         }
         if (fused) {
-          HIP_TRY(launch_gru_fwd_step(Whh, rin + c->off(p + ".b_hh"), sR, gx + (size_t)t * B * 3 * H, s_gx,
+          HIP_TRY(launch_gru_fwd_step(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx + (size_t)t * B * 3 * H, s_gx,
                                       hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
                                       sv + (size_t)t * B * 4 * H, s_sv, B, H, groups, s));
           continue;
         }
         TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0, Whh, H, sR, 1, gh, 3 * H,
-                 s_gh, EPI_BIAS, rin + c->off(p + ".b_hh"), sR));
+                 s_gh, EPI_BIAS, rin + c->eoff(c->lidx[l].bhh), sR));
         role = HPSGD_ROLE_CELL_FWD;
         HIP_TRY(launch_gru_cell_fwd(gx + (size_t)t * B * 3 * H, s_gx, gh, s_gh, hs + (size_t)t * B * H,
                                     hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
@@ -792,7 +798,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const NtView vdl{bfreg(c->dlogb), 1, clp, s_dlb}, vwT{bfreg(c->woT), 1, clp, s_woT};
       const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
       const NtView vhT{bfreg(c->hsT[L - 1]) + (lm ? B : T * B), 1, TB1p, 2 * (long)c->hsT[L - 1].stride};
-      const WgradTarget wt = wgrad_target("head.W");
+      const WgradTarget wt = wgrad_target(c->i_head_w);
       // The head's input gradient and weight gradient need the same logit gradient and nothing of
       // each other.  The former has fewer tiles than the chip has CUs (a long contraction over
       // the classes): with an auxiliary stream the two run side by side and the tiles of the
@@ -831,8 +837,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                 (long)c->rowloss.stride, D, s_D, grad + oW, grad + ob, sG, lr, 0, loss_out, nrows,
                                 classes, H, groups, s));
       } else {
-        fused_commit[c->find("head.W")] = 1;
-        fused_commit[c->find("head.b")] = 1;
+        fused_commit[c->i_head_w] = 1;
+        fused_commit[c->i_head_b] = 1;
         HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sR, y, nrows, logits, s_log, rowloss,
                                 (long)c->rowloss.stride, D, s_D, rout + oW, rout + ob, sR, lr, 1, loss_out, nrows,
                                 classes, H, groups, s));
@@ -878,7 +884,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
                     EPI_STORE, nullptr, 0, vl, vw));
         }
-        const WgradTarget wt = wgrad_target("head.W");
+        const WgradTarget wt = wgrad_target(c->i_head_w);
         TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
                   wt.epi, wt.aux, sR, va, vb, lr));
         HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
@@ -891,7 +897,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     }
     // ---- backward: GRU layers, top to bottom
     for (int l = L - 1; l >= 0; --l) {
-      const std::string p = "l" + std::to_string(l);
       const float* hs = reg(c->hs[l]);
       const float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
@@ -921,7 +926,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         s_layer_in = (long)TB * d.input;
       }
       float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
-      const float* Whh = rin + c->off(p + ".W_hh");
+      const float* Whh = rin + c->eoff(c->lidx[l].whh);
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
       float* wt = reg(c->wt);
@@ -956,8 +961,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // ... and the bias gradients, when their partial sums can be added with 16-byte accesses
       float* dbp = persist_b ? reg(c->dbp)  // (its conditions were checked with use_persist_b)
                    : (persist && c->dbp.stride == (size_t)((B + 31) / 32) * 6 * H && (sG & 3) == 0 &&
-                      ((uintptr_t)(grad + c->off(p + ".b_ih")) & 15) == 0 &&
-                      c->off(p + ".b_hh") == c->off(p + ".b_ih") + (size_t)3 * H)
+                      ((uintptr_t)(grad + c->eoff(c->lidx[l].bih)) & 15) == 0 &&
+                      c->eoff(c->lidx[l].bhh) == c->eoff(c->lidx[l].bih) + (size_t)3 * H)
                        ? reg(c->dbp)
                        : nullptr;
       const int NC = (c->aux && fused && !persist && T >= 8) ? 4 : 1;
@@ -967,10 +972,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         const int rows = (t1 - t0) * B;
         const int bg = st != s;  // on the auxiliary stream: beside the recurrence
         int rc = gemm(st, groups, bf, 3 * H, win, rows, dgx + r0 * 3 * H, 3 * H, s_gx, 1, layer_in + r0 * win,
-                      win, s_layer_in, 0, grad + c->off(p + ".W_ih"), win, sG, epi, nullptr, 0, bg);
+                      win, s_layer_in, 0, grad + c->eoff(c->lidx[l].wih), win, sG, epi, nullptr, 0, bg);
         if (rc != HPSGD_OK) return rc;
         return gemm(st, groups, bf, 3 * H, H, rows, dgh + r0 * 3 * H, 3 * H, s_gx, 1, hs + r0 * H, H, s_hs, 0,
-                    grad + c->off(p + ".W_hh"), H, sG, epi, nullptr, 0, bg);
+                    grad + c->eoff(c->lidx[l].whh), H, sG, epi, nullptr, 0, bg);
       };
       {
       TimerScope loop_bwd(c, HPSGD_ROLE_GEMM_REC_BWD, s, (persist || persist_b) ? 1 : (fused || fused_b) ? T : 0);
@@ -1038,7 +1043,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       c->timer_nested = false;
       }
-      const float* Wih = rin + c->off(p + ".W_ih");
+      const float* Wih = rin + c->eoff(c->lidx[l].wih);
       const bool need_dx = l > 0 || lm;
       NtView v_dgxT, v_dghT, v_xT, v_hsT, v_wihT;
       if (ntc && win % 8 == 0) {
@@ -1095,7 +1100,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           return HPSGD_EHIP;
         TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
       } else {
-        const WgradTarget wi = wgrad_target(p + ".W_ih");
+        const WgradTarget wi = wgrad_target(c->lidx[l].wih);
         // fp32, a narrow layer-0 input: the GEMM has few tiles and a long contraction (T*B), so the
         // contraction is cut into kWihSplits parts that run side by side; their sums are added
         // in order by the kernel that also applies the update
@@ -1115,7 +1120,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
                     wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
         }
-        const WgradTarget wh = wgrad_target(p + ".W_hh");
+        const WgradTarget wh = wgrad_target(c->lidx[l].whh);
         if (dwp) {
           TRY0(queue_reduce(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sR, wh.C, (size_t)wh.sC,
                            wh.epi == EPI_COMMIT));
@@ -1128,17 +1133,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (dbp) {
         // the kernel that adds the partial sums applies the update too, when it can write the
         // replica with 16-byte accesses and the gradients are not accumulated as well
-        const size_t ob_ih = c->off(p + ".b_ih");
+        const size_t ob_ih = c->eoff(c->lidx[l].bih);
         if (!acc && (sR & 3) == 0 && ((uintptr_t)(rin + ob_ih) & 15) == 0 && ((uintptr_t)(rout + ob_ih) & 15) == 0) {
-          fused_commit[c->find(p + ".b_ih")] = 1;
-          fused_commit[c->find(p + ".b_hh")] = 1;
+          fused_commit[c->lidx[l].bih] = 1;
+          fused_commit[c->lidx[l].bhh] = 1;
           TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sR, rout + ob_ih, (size_t)sR, 1));
         } else {
           TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + ob_ih, (size_t)sG, 0));
         }
       } else {
-        HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->off(p + ".b_ih"), sG, TB, 3 * H, groups, s));
-        HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->off(p + ".b_hh"), sG, TB, 3 * H, groups, s));
+        HIP_TRY(launch_colsum(dgx, 3 * H, s_gx, grad + c->eoff(c->lidx[l].bih), sG, TB, 3 * H, groups, s));
+        HIP_TRY(launch_colsum(dgh, 3 * H, s_gx, grad + c->eoff(c->lidx[l].bhh), sG, TB, 3 * H, groups, s));
       }
       // the layer's sums of partial results (weight gradients of the resident-weight launch and
       // of the split contraction, bias gradients), with their updates: one launch
@@ -1149,11 +1154,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     }
     if (lm) {
       role = HPSGD_ROLE_EMBED;
-      const size_t oE = c->off("embed.E");
+      const size_t oE = c->eoff(c->i_embed);
       if (!acc && rin == rout) {
         // an update in place: only the rows of the tokens of the batch change, and their owners
         // write them; no gradient table to clear, fill and stream through the commit kernel
-        fused_commit[c->find("embed.E")] = 1;
+        fused_commit[c->i_embed] = 1;
         HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, s, rin + oE, sR, lr));
       } else {
         HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
