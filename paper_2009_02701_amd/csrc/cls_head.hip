@@ -118,7 +118,7 @@ __global__ void __launch_bounds__(256)
 cls_head_bwd_kernel(const float* __restrict__ feats, long s_feats, const float* W_in, const float* b_in, long s_in,
                     const float* __restrict__ dlog, long s_dlog, const float* __restrict__ rowloss, long s_rowloss,
                     float* __restrict__ dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr,
-                    int commit, float* __restrict__ loss, int N, int C, int H) {
+                    int commit, float* __restrict__ loss, int N, int C, int H, int relu_mask) {
   __shared__ float sD[HMAXN * HMAXC];          // dlogits [N][C]
   __shared__ float sF[HMAXN][HCOLS + 1];       // the slice of the features
   __shared__ float sW[HMAXC][HCOLS + 1];       // the slice of W
@@ -152,6 +152,8 @@ cls_head_bwd_kernel(const float* __restrict__ feats, long s_feats, const float* 
   for (int r = q; r < N; r += 4) {
     float a = 0.f;
     for (int c = 0; c < C; ++c) a += sD[r * C + c] * sW[c][jl];
+    // the features are the output of a ReLU layer: the gradient passes where the feature is positive
+    if (relu_mask && !(sF[r][jl] > 0.f)) a = 0.f;
     if (jv) dfeat[g * s_dfeat + (long)r * H + j] = a;
   }
   for (int c = q; c < C; c += 4) {
@@ -190,11 +192,13 @@ bool cls_head_supported(int N, int C, int H) {
 // (stride s_in); dlog ([N][C] per group, stride s_dlog) and rowloss ([N] per group) are scratch
 // that the first launch hands to the second; dfeat: [N][H] per group (stride s_dfeat);
 // commit != 0: W_out / b_out (stride s_out, may be W_in / b_in) receive the updated parameters,
-// else the gradients; loss: per group mean cross-entropy, or nullptr.
+// else the gradients; loss: per group mean cross-entropy, or nullptr.  relu_mask != 0: the features
+// are the output of a ReLU layer and dfeat is the gradient in front of that ReLU (zero where the
+// feature is not positive).
 hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, const float* b_in, long s_in,
                            const int32_t* y, long s_y, float* dlog, long s_dlog, float* rowloss, long s_rowloss,
                            float* dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr, int commit,
-                           float* loss, int N, int C, int H, int groups, hipStream_t s) {
+                           float* loss, int N, int C, int H, int groups, hipStream_t s, int relu_mask) {
   if (!cls_head_supported(N, C, H)) return hipErrorInvalidValue;
   const int cpad = C <= 8 ? 8 : C <= 16 ? 16 : 32;
   const size_t lds = (size_t)cpad * H * sizeof(float);
@@ -218,7 +222,7 @@ hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, 
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(cls_head_bwd_kernel, dim3((H + HCOLS - 1) / HCOLS, groups), dim3(256), 0, s, feats, s_feats,
                      W_in, b_in, s_in, dlog, s_dlog, rowloss, s_rowloss, dfeat, s_dfeat, W_out, b_out, s_out, lr,
-                     commit, loss, N, C, H);
+                     commit, loss, N, C, H, relu_mask);
   return hipGetLastError();
 }
 

@@ -485,10 +485,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   if (d.kind == HPSGD_MLP) {
     const int L = d.n_mlp_dims - 1;
     const int* dims = d.mlp_dims;
+    // A last layer with few classes (the softmax head): forward, loss, its three gradients and its
+    // update as the two small launches of the classifier head instead of three GEMMs, the loss
+    // kernel and a share of the column sums
+    const bool small_head = !bf && L >= 2 && cls_head_supported(B, dims[L], dims[L - 1]) && c->dact.size() + 1 >= (size_t)L;
     // forward
     const float* a_in = (const float*)x;
     long s_in = (long)B * dims[0];
-    for (int i = 0; i < L; ++i) {
+    for (int i = 0; i < (small_head ? L - 1 : L); ++i) {
       float* a_out = reg(c->act[i]);
       role = HPSGD_ROLE_MLP_FWD;
       TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->eoff(c->fc_w[i]),
@@ -501,8 +505,25 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     float* delta = reg(c->act[L - 1]);
     float* rowloss = reg(c->rowloss);
     role = HPSGD_ROLE_LOSS;
-    HIP_TRY(launch_softmax_ce(delta, (long)c->act[L - 1].stride, y, B, delta, rowloss,
-                              (long)c->rowloss.stride, B, dims[L], groups, s));
+    if (small_head) {
+      const size_t oW = c->eoff(c->fc_w[L - 1]), ob = c->eoff(c->fc_b[L - 1]);
+      float* dprev = reg(c->dact[L - 2]);
+      if (acc) {
+        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sR, y, B, delta, (long)c->act[L - 1].stride, rowloss,
+                                (long)c->rowloss.stride, dprev, (long)c->dact[L - 2].stride, grad + oW, grad + ob, sG, lr,
+                                0, loss_out, B, dims[L], dims[L - 1], groups, s, 1));
+      } else {
+        fused_commit[c->fc_w[L - 1]] = 1;
+        fused_commit[c->fc_b[L - 1]] = 1;
+        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sR, y, B, delta, (long)c->act[L - 1].stride, rowloss,
+                                (long)c->rowloss.stride, dprev, (long)c->dact[L - 2].stride, rout + oW, rout + ob, sR, lr,
+                                1, loss_out, B, dims[L], dims[L - 1], groups, s, 1));
+      }
+      delta = dprev;
+    } else {
+      HIP_TRY(launch_softmax_ce(delta, (long)c->act[L - 1].stride, y, B, delta, rowloss,
+                                (long)c->rowloss.stride, B, dims[L], groups, s));
+    }
     // backward
     // the bias gradients (column sums of every layer's delta) are taken in one launch behind the
     // last layer, which also applies them unless the gradients are accumulated as well
@@ -510,15 +531,16 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     cp.n = 0;
     cp.blk0[0] = 0;
     cp.lr = lr;
-    // (the mean of the per-row losses rides along: a column sum of a B x 1 matrix)
-    if (loss_out && !colsum_pack_push(cp, rowloss, 1, (long)c->rowloss.stride, loss_out, 1, nullptr, 0, B, 1,
-                                      1.0f / (float)B))
+    // (the mean of the per-row losses rides along: a column sum of a B x 1 matrix; the small head
+    // has taken it already)
+    if (loss_out && !small_head &&
+        !colsum_pack_push(cp, rowloss, 1, (long)c->rowloss.stride, loss_out, 1, nullptr, 0, B, 1, 1.0f / (float)B))
       return HPSGD_ESHAPE;
-    for (int i = L - 1; i >= 0; --i) {
+    for (int i = (small_head ? L - 2 : L - 1); i >= 0; --i) {
       const float* a_prev = i > 0 ? reg(c->act[i - 1]) : (const float*)x;
       const long s_prev = i > 0 ? (long)c->act[i - 1].stride : (long)B * dims[0];
       const long s_delta = i == L - 1 ? (long)c->act[i].stride : (long)c->dact[i].stride;
-      role = HPSGD_ROLE_MLP_BWD;
+      role = HPSGD_ROLE_MLP_BWD;  // (with the small head the loop starts at layer L-2, whose delta is dact[L-2])
       float* dprev = nullptr;
       if (i > 0) {
         // delta_prev = (delta W) * [a_prev > 0]: before W is updated

@@ -126,7 +126,7 @@ bool cls_head_supported(int N, int C, int H);
 hipError_t launch_cls_head(const float* feats, long s_feats, const float* W_in, const float* b_in, long s_in,
                            const int32_t* y, long s_y, float* dlog, long s_dlog, float* rowloss, long s_rowloss,
                            float* dfeat, long s_dfeat, float* W_out, float* b_out, long s_out, float lr, int commit,
-                           float* loss, int N, int C, int H, int groups, hipStream_t s);
+                           float* loss, int N, int C, int H, int groups, hipStream_t s, int relu_mask = 0);
 
 // ---- GRU cell, loss, reductions ----
 // forward cell for one time step of all groups:
