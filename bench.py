@@ -25,7 +25,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 # Kernels whose work is counted in bytes (HBM roofline); every other timed kernel is a contraction.
-STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel"}
+STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel", "commit_kernel", "commit_acc4_kernel"}
 
 # HBM bytes per launch of a kernel, from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE, in KiB per dispatch; FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0: the config-5
@@ -303,6 +303,20 @@ def main():
             c0 = time.perf_counter()
             run()
             forms[name] = 32 * per_round / (time.perf_counter() - c0)
+        # the commit kernels of the two forms against HBM (update: 12 B per parameter it touches;
+        # update + accumulate: 20 B per parameter), one event pair per launch
+        commit_ids = [knames.index("commit_kernel"), knames.index("commit_acc4_kernel")]
+        tr.ctx.kernel_timer_enable(commit_ids)
+        tr.s_seq(lr, 1, 8, record_loss=False)
+        tr.s_seq_grad(lr, 1, 8, record_loss=False)
+        torch.cuda.synchronize()
+        for kid in commit_ids:
+            n, ms, work = tr.ctx.kernel_timer_read(kid)
+            if n:
+                forms[knames[kid]] = {"avg_us": 1e3 * ms / n, "bytes_per_launch": work / n,
+                                      "GBps": work / (ms * 1e-3) / 1e9,
+                                      "frac_hbm_peak": work / (ms * 1e-3) / (PEAK_HBM_GBS * 1e9)}
+        tr.ctx.kernel_timer_enable([])
         # what a pure-MFMA loop of this workload's operand type sustains on this chip right now
         prec = "bf16" if cfg.get("prec") == "bf16" else "fp32"
         probe = {"dtype": prec, **mfma_probe(hb, torch, dev, prec)}

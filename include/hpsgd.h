@@ -324,7 +324,9 @@ enum hpsgd_kernel {
   HPSGD_KERNEL_CVT2 = 16,           /* streaming: bytes */
   HPSGD_KERNEL_SOFTMAX_CE_BF16 = 17, /* streaming: bytes */
   HPSGD_KERNEL_GRU_STEP = 18,
-  HPSGD_KERNEL_COUNT = 19
+  HPSGD_KERNEL_COMMIT_ACC = 19,     /* streaming: bytes */
+  HPSGD_KERNEL_COMMIT = 20,         /* streaming: bytes */
+  HPSGD_KERNEL_COUNT = 21
 };
 int hpsgd_kernel_timer_enable(hpsgd_ctx *ctx, unsigned kernel_mask);
 int hpsgd_kernel_timer_read(hpsgd_ctx *ctx, int kernel, long *launches, double *total_ms, double *work);

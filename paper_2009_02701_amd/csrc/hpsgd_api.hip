@@ -1640,6 +1640,8 @@ const char* hpsgd_kernel_name(int kernel) {
     case HPSGD_KERNEL_CVT2: return "cvt2_kernel";
     case HPSGD_KERNEL_SOFTMAX_CE_BF16: return "softmax_ce_bf16_rows_kernel";
     case HPSGD_KERNEL_GRU_STEP: return "gru_step_kernel";
+    case HPSGD_KERNEL_COMMIT_ACC: return "commit_acc4_kernel";
+    case HPSGD_KERNEL_COMMIT: return "commit_kernel";
     default: return nullptr;
   }
 }

@@ -38,7 +38,9 @@ enum KernelId : int {
   KID_CVT2 = 16,                  // cvt2_kernel (bf16 copy + transposed copy)
   KID_SOFTMAX_CE_BF16 = 17,       // softmax_ce_bf16_rows_kernel / softmax_ce_bf16_kernel
   KID_GRU_STEP = 18,              // gru_{fwd,bwd}_step(_bf16)_kernel: one launch per time step
-  KID_COUNT = 19
+  KID_COMMIT_ACC = 19,            // commit_acc4_kernel / commit_acc_kernel (update + accumulate, 20 B/param)
+  KID_COMMIT = 20,                // commit_kernel (update of what no GEMM epilogue updated, 12 B/param)
+  KID_COUNT = 21
 };
 struct KernelTimer {
   KernelTimer(int kid, double work, hipStream_t s);
