@@ -151,10 +151,11 @@ int hpsgd_prepare_replicas(hpsgd_ctx *ctx, const float *replicas, size_t replica
 
 /* The same for replicas that are clones of the global model (Alg. 2 "make replica": the caller has
  * called, or will have called by the time of the local step, hpsgd_sync_all(global, replicas ...)
- * and nothing has written them since): the K workers' operand copies are made from `global`, which
- * is read once instead of K times.  A clone knows that its K outputs are equal; the local step that
- * follows does not use that, it reads K separate sets of copies.  The caller vouches for the
- * equality: a step whose replicas differ from `global` would multiply with the wrong weights.
+ * and nothing has written them since): ONE set of operand copies is made from `global` and the
+ * marked local step hands it to all K workers (the K sets would hold the same bits; one set is an
+ * eighth of the bytes to write at K = 8 and is fetched once by the products of all workers).  The
+ * caller vouches for the equality: a step whose replicas differ from `global` would multiply with
+ * the wrong weights.
  * `replicas` / replica_stride / workspace are those of the next local step (they name the mark, as
  * for hpsgd_prepare_replicas; the replicas are not read here).  The copies of the GRU layers'
  * matrices are made by this call; those of the head's matrix are made by the marked local step

@@ -5,6 +5,7 @@
 
 #include <string>
 #include <mutex>
+#include <cstring>
 #include <vector>
 
 #include "kernels.h"
@@ -462,6 +463,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   const bool prepared = bf && c->prepared_rin == rin && c->prepared_ws == ws && c->prepared_stride == rstride &&
                         k0 == 0 && groups == c->K;
   const float* head_src = prepared ? c->prepared_head_src : nullptr;
+  // the replicas are clones of one model (hpsgd_prepare_clones): one set of bf16 weight copies, in
+  // worker 0's slice of the workspace, is every worker's operand (group stride 0)
+  const bool shared = head_src != nullptr;
+  auto wstride = [&](const Region& r) { return shared ? 0L : 2 * (long)r.stride; };
   c->prepared_rin = nullptr;
   c->prepared_head_src = nullptr;
   const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
@@ -614,8 +619,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     const int nrows = lm ? TB : B;
     const size_t oW = c->eoff(c->i_head_w), ob = c->eoff(c->i_head_b);
     const long nrp = (long)round_up(nrows, 64), clp = (long)round_up(classes, 64);
-    const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = 2 * (long)c->wob.stride;
-    const long s_woT = 2 * (long)c->woT.stride, s_dlT = 2 * (long)c->dlogT.stride;
+    const long s_dlb = 2 * (long)c->dlogb.stride, s_wob = wstride(c->wob);
+    const long s_woT = wstride(c->woT), s_dlT = 2 * (long)c->dlogT.stride;
     // bf16 precision with every head operand available as bf16: h of the top layer (written
     // by its step kernels), head.W rounded once (row-major and transposed in one pass), the
     // logit gradient emitted in bf16 by the loss kernel and transposed from there
@@ -701,7 +706,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
             xT_ready = true;
           }
           if (wc.wih[l]) {  // made at the start of the step, or before it
-            vb = NtView{bfreg(c->wihbl[l]), 1, width, 2 * (long)c->wihbl[l].stride};
+            vb = NtView{bfreg(c->wihbl[l]), 1, width, wstride(c->wihbl[l])};
             wihT_ready[l] = wc.wihT[l];
           }
         }
@@ -712,7 +717,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
       // not use) and of h
       void* wb = wc.whh[l] ? reg(c->whhb[l]) : reg(c->wt);
-      const long s_wb = 2 * (long)(wc.whh[l] ? c->whhb[l].stride : c->wt.stride);
+      const long s_wb = wc.whh[l] ? wstride(c->whhb[l]) : 2 * (long)c->wt.stride;
       __bf16* hb = fused_b ? (__bf16*)reg(c->hb) : nullptr;
       const long s_hb = 2 * (long)c->hb.stride;
       __bf16* hT = (fused_b && ntc) ? bfreg(c->hsT[l]) : nullptr;  // hsT exists in bf16 precision only
@@ -788,9 +793,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the copy has the memory system to itself (beside a resident-weight launch it takes 2.3
       // times as long and slows that launch by more than it takes alone; at the start of the step it
       // shares the bandwidth with the merge and the clone)
-      if (head_src) {  // the replicas are clones of one model: its head matrix is read once for all workers
+      if (head_src) {  // the replicas are clones of one model: one copy of its head matrix serves all workers
         HIP_TRY(launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
-                            groups, s));
+                            1, s));
       } else if (!prepared) {
         HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             groups, s));
@@ -966,7 +971,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       long s_wtb = 2 * s_wt;
       if (fused_b && whhT_ready[l]) {
         wtb = bfreg(c->whhT[l]);
-        s_wtb = 2 * (long)c->whhT[l].stride;
+        s_wtb = wstride(c->whhT[l]);
       } else if (fused_b) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
@@ -1088,7 +1093,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           v_xT = NtView{bfreg(c->xT), 1, TBp, 2 * (long)c->xT.stride};
         }
         if (need_dx && wihT_ready[l]) {
-          v_wihT = NtView{bfreg(c->wihTl[l]), 1, 3 * H, 2 * (long)c->wihTl[l].stride};
+          v_wihT = NtView{bfreg(c->wihTl[l]), 1, 3 * H, wstride(c->wihTl[l])};
         } else if (need_dx) {
           HIP_TRY(launch_cvt_bf16(Wih, win, sR, bfreg(c->wihT), 3 * H, 2 * (long)c->wihT.stride, 3 * H, win, true,
                                   groups, s));
@@ -1381,11 +1386,19 @@ int hpsgd_prepare_clones(hpsgd_ctx* ctx, const float* global, const float* repli
   ctx->prepared_rin = nullptr;
   if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
   WeightCopies wc;
-  // every worker's copies from the one source: group stride 0.  The GRU layers' now; the head's are
-  // left to the step, which makes them from `global` right before the logits GEMM (made here they
-  // would share the memory system with whatever the synchronising side is doing at a round's start)
+  // one set of copies, in worker 0's slice, which the step hands to every worker (the replicas are
+  // clones: their copies would be the same bits).  The GRU layers' now; the head's are left to the
+  // step, which makes them from `global` right before the logits GEMM (made here they would share
+  // the memory system with whatever the synchronising side is doing at a round's start)
   ctx->prepared_head_src = nullptr;
-  const int rc = weight_copies(ctx, global, 0, 0, ctx->K, (float*)workspace, (hipStream_t)hip_stream, true, false, wc);
+  // (the step decides from the replicas' addresses which copies it has; made from another address
+  // the set must come out the same, else the step makes its own)
+  WeightCopies want;
+  int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace, nullptr, false, false, want);
+  if (rc == HPSGD_OK) rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, nullptr, false, false, wc);
+  if (rc != HPSGD_OK) return rc;
+  if (std::memcmp(&want, &wc, sizeof(WeightCopies)) != 0) return HPSGD_OK;
+  rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, (hipStream_t)hip_stream, true, false, wc);
   if (rc != HPSGD_OK) return rc;
   ctx->prepared_head_src = global;
   ctx->prepared_rin = replicas;
