@@ -532,6 +532,18 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
 // B lane l holds B[k = 8*(l/16) .. +7][n = l%16], accumulator as for 16x16x4.
 // Epilogue: thread t owns batch row t/16 and the two units 2*(t%16), +1 of the tile, so that
 // bf16 values are stored in pairs.
+//
+// Layout of the exchanged operand.  A wave's A fragment is 16 rows x 32 contraction indices,
+// 16 bytes per lane.  Read from a row-major matrix that is 64 bytes of each of 16 rows, half a
+// cache line per row, and a CU then takes 5.3 us to fetch the 196 KB a backward step needs
+// (measured: the same whether the lines come from L2 or past it, whatever the cache policy of the
+// load and however few CUs read at once), against 1.9 us when every load instruction reads whole
+// lines.  So the exchange buffers are kept fragment-major: per step, row block (16 batch rows) and
+// chunk, the 1 KB that one load instruction reads, lane l's 16 bytes at byte 16 l (lane l holds row
+// l % 16, contraction indices 8 (l / 16) .. + 7 of the chunk).  A workgroup's 32 units are exactly
+// one chunk (per gate), so a workgroup writes whole fragments and nobody else writes into them.
+// Rows of the last row block beyond the batch are never written: what a consumer reads there goes
+// into output rows that are never stored.
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
 
@@ -551,15 +563,21 @@ __device__ __forceinline__ unsigned pack_bf16(float a, float b) {
 __device__ __forceinline__ void st_dev_u32(void* p, unsigned v) {
   __hip_atomic_store(reinterpret_cast<unsigned*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
+// Element offset, inside a step's block of a fragment-major exchange buffer with nch chunks per
+// row, of (row, chunk c, index u within the chunk)
+__device__ __forceinline__ long xfrag(int row, int nch, int c, int u) {
+  return ((long)(row >> 4) * nch + c) * 512 + (((u >> 3) << 4) + (row & 15)) * 8 + (u & 7);
+}
 
-// Forward.  Wb: bf16 W_hh [3H][H]; hb: bf16 h_0 .. h_T (blocks of B x H, h_0 given), the
-// exchanged operand; hs: the same in fp32; hT (nullable): bf16 transposed copy [H][ld_hT],
-// column (t+1)*B + row.  NCF: chunks per wave (H <= 256 * NCF).
+// Forward.  Wb: bf16 W_hh [3H][H]; hx: bf16 h_0 .. h_T fragment-major (blocks of 16 ceil(B/16) x H,
+// h_0 given), the exchanged operand; hb: the same row-major (blocks of B x H; written, not read);
+// hs: the same in fp32; hT (nullable): bf16 transposed copy [H][ld_hT], column (t+1)*B + row.
+// NCF: chunks per wave (H <= 256 * NCF).
 template <int NCF>
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const float* __restrict__ b_hh, long s_rep,
-                            const float* __restrict__ gx, long s_gx, float* __restrict__ hs, long s_hs, __bf16* hb,
-                            long s_hb, float* __restrict__ sv, long s_sv, __bf16* __restrict__ hT, long ld_hT,
+                            const float* __restrict__ gx, long s_gx, float* __restrict__ hs, long s_hs,
+                            __bf16* __restrict__ hb, long s_hb, __bf16* hx, long s_hx, float* __restrict__ sv, long s_sv, __bf16* __restrict__ hT, long ld_hT,
                             long s_hT, int B, int H, int T, int groups, unsigned* sync, unsigned base,
                             unsigned spin_limit) {
   extern __shared__ __attribute__((aligned(16))) float persist_lds[];
@@ -600,24 +618,25 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
   for (int q = 0; q < 3; ++q) bias[q] = *reinterpret_cast<const float2*>(b_hh + g * s_rep + q * H + j);
   float* hsg = hs + g * s_hs;
   __bf16* hbg = hb + g * s_hb;
+  __bf16* hxg = hx + g * s_hx;
+  const long xblk = (long)((B + 15) / 16) * 16 * H;  // elements of a step's block of hx
   float2 hpv = *reinterpret_cast<const float2*>(hsg + (long)rowc * H + j);
-  // A fragments: rows rb*16 + lr of the tile (clamped into the batch), k = 32c + 8*lg
+  // A fragments: row blocks r0/16 + rb (one that lies beyond the batch is read from the tile's first)
   int aoff[2];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) aoff[rb] = ((rb * 16 + lr < B - r0 ? rb * 16 + lr : 0) * H + 8 * lg) * 2;
+  for (int rb = 0; rb < 2; ++rb) aoff[rb] = (((r0 + rb * 16 < B ? r0 + rb * 16 : r0) >> 4) * nch) * 1024 + lane * 16;
   for (int t = 0; t < T; ++t) {
     const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H + j;
     float2 gxv[3];
 #pragma unroll
     for (int q = 0; q < 3; ++q) gxv[q] = *reinterpret_cast<const float2*>(gxr + q * H);
     if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
-    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hbg + ((long)t * B + r0) * H, 0, 0x7fffffff,
-                                                                        0x00020000);
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hxg + (long)t * xblk, 0, 0x7fffffff, 0x00020000);
     bf16x8 a[NCF][2];
 #pragma unroll
     for (int i = 0; i < NCF; ++i) {
       const int c = wave + 8 * i;
-      const int co = (c < nch ? c : 0) * PC * 2;
+      const int co = (c < nch ? c : 0) * 1024;
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
     }
@@ -658,7 +677,9 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
     if (row < B) {
       const long e = ((long)(t + 1) * B + row) * H + j;
       *reinterpret_cast<float2*>(hsg + e) = hn;
-      st_dev_u32(hbg + e, pack_bf16(hn.x, hn.y));
+      const unsigned hp2 = pack_bf16(hn.x, hn.y);
+      st_dev_u32(hxg + (long)(t + 1) * xblk + xfrag(row, nch, tx, u0), hp2);
+      *reinterpret_cast<unsigned*>(hbg + e) = hp2;
       float* svr = sv + g * s_sv + ((long)t * B + row) * 4 * H + j;
       *reinterpret_cast<float2*>(svr) = make_float2(r0v, r1v);
       *reinterpret_cast<float2*>(svr + H) = make_float2(z0v, z1v);
@@ -681,8 +702,8 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
   }
 }
 
-// Backward.  WT: bf16 W_hh^T [H][3H]; dghb: bf16 gate gradients of all steps (blocks of B x 3H),
-// the exchanged operand; dgxb: bf16 dgx row-major; dgxT / dghT: bf16 transposed copies
+// Backward.  WT: bf16 W_hh^T [H][3H]; dghx: bf16 gate gradients of all steps, fragment-major
+// (blocks of 16 ceil(B/16) x 3H), the exchanged operand; dgxb: bf16 dgx row-major; dgxT / dghT: bf16 transposed copies
 // [3H][ld_T], column t*B + row; dbp: partial bias-gradient sums [(g*RT + ty)][6H] (b_ih | b_hh).
 // D: dh_T * z_T on entry (the head's gradient), dh_0 * z_0 on exit.  NCB: chunks per wave
 // (3H <= 256 * NCB).  The fragments of the first half of a wave's chunks stay in registers,
@@ -691,7 +712,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
 // kernel (a merge on the second stream) could ever share the CU.
 template <int NCB>
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
-gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dghb, long s_dgb, float* __restrict__ D,
+gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dghx, long s_dgh, long s_dgb, float* __restrict__ D,
                             long s_D, const float* __restrict__ above, long s_above, const float* __restrict__ sv,
                             long s_sv, const float* __restrict__ hs, long s_hs, __bf16* __restrict__ dgxb,
                             __bf16* __restrict__ dgxT, __bf16* __restrict__ dghT, long ld_T, long s_T,
@@ -736,11 +757,12 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
   const int ro = ((rl >> 4) * 2 + (u0 >> 4)) * 256 + (rl & 3) * 64 + ((rl >> 2) & 3) * 16 + (u0 & 15);  // + w * 1024
   float* Dg = D + g * s_D;
   float2 dcar = *reinterpret_cast<const float2*>(Dg + (long)rowc * H + j);
-  __bf16* dghg = dghb + g * s_dgb;
+  __bf16* dghg = dghx + g * s_dgh;
+  const long xblk = (long)((B + 15) / 16) * 16 * H3;  // elements of a step's block of dghx
   float2 bsum[4] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // da_r, da_z, da_n, dq over the steps
   int aoff[2];
 #pragma unroll
-  for (int rb = 0; rb < 2; ++rb) aoff[rb] = ((rb * 16 + lr < B - r0 ? rb * 16 + lr : 0) * H3 + 8 * lg) * 2;
+  for (int rb = 0; rb < 2; ++rb) aoff[rb] = (((r0 + rb * 16 < B ? r0 + rb * 16 : r0) >> 4) * nch) * 1024 + lane * 16;
   int it = 0;
   for (int t = T - 1; t >= 0; --t, ++it) {
     const long e = ((long)t * B + rowc) * H + j;
@@ -756,13 +778,13 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
 #pragma unroll
       for (int cb = 0; cb < 2; ++cb) acc[rb][cb] = (floatx4){0.f, 0.f, 0.f, 0.f};
     if (t + 1 < T) {  // uniform over the grid
-      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dghg + ((long)(t + 1) * B + r0) * H3, 0,
-                                                                          0x7fffffff, 0x00020000);
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(dghg + (long)(t + 1) * xblk, 0, 0x7fffffff,
+                                                                          0x00020000);
       bf16x8 a[NCB][2];
 #pragma unroll
       for (int i = 0; i < NCB; ++i) {
         const int c = wave + 8 * i;
-        const int co = (c < nch ? c : 0) * PC * 2;
+        const int co = (c < nch ? c : 0) * 1024;
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
       }
@@ -803,9 +825,10 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
     if (row < B) {
       const long o = ((long)t * B + row) * H3 + j;
       const unsigned pr = pack_bf16(da_r.x, da_r.y), pz = pack_bf16(da_z.x, da_z.y);
-      st_dev_u32(dghg + o, pr);
-      st_dev_u32(dghg + o + H, pz);
-      st_dev_u32(dghg + o + 2 * H, pack_bf16(dq.x, dq.y));
+      const long ox3 = (long)t * xblk + xfrag(row, nch, tx, u0);  // gate q: chunk q H/32 + tx
+      st_dev_u32(dghg + ox3, pr);
+      st_dev_u32(dghg + ox3 + (long)(H / PC) * 512, pz);
+      st_dev_u32(dghg + ox3 + (long)(2 * H / PC) * 512, pack_bf16(dq.x, dq.y));
       __bf16* ox = dgxb + g * s_dgb + o;
       *reinterpret_cast<unsigned*>(ox) = pr;
       *reinterpret_cast<unsigned*>(ox + H) = pz;
@@ -995,12 +1018,15 @@ bool gru_persist_bf16_supported(int B, int H, int groups) {
 
 unsigned gru_persist_bf16_count_per_step(int) { return 1u; }
 
+size_t gru_persist_bf16_exchange_elems(int B, int width) { return (size_t)((B + 15) / 16) * 16 * (size_t)width; }
+
 hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep, const float* gx,
-                                       long s_gx, float* hs, long s_hs, void* hb, long s_hb, float* sv, long s_sv,
-                                       void* hT, long ld_hT, long s_hT, int B, int H, int T, int groups,
-                                       unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s) {
+                                       long s_gx, float* hs, long s_hs, void* hb, long s_hb, void* hx, long s_hx,
+                                       float* sv, long s_sv, void* hT, long ld_hT, long s_hT, int B, int H, int T,
+                                       int groups, unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s) {
   if (!gru_persist_bf16_supported(B, H, groups) || T < 1) return hipErrorInvalidValue;
   auto a16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  if (!hx || !a16(hx) || (s_hx & 7) != 0) return hipErrorInvalidValue;
   if (!a16(Wb) || !a16(hb) || !a16(hs) || !a16(gx) || !a16(sv) || !a16(b_hh) || (hT && !a16(hT)) || (s_wb & 7) != 0 ||
       (s_hb & 7) != 0 || (s_hs & 3) != 0 || (s_gx & 3) != 0 || (s_sv & 3) != 0 || (s_rep & 3) != 0 ||
       (hT && ((ld_hT & 7) != 0 || (s_hT & 7) != 0)))
@@ -1021,7 +1047,7 @@ hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b
   KernelTimer kt(KID_GRU_FWD_PERSIST_BF16, 2.0 * B * 3 * H * (double)H * T * groups, s);
 #define HPSGD_FWD_PB(N)                                                                                            \
   hipLaunchKernelGGL(gru_fwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)Wb, s_wb, b_hh, s_rep, \
-                     gx, s_gx, hs, s_hs, (__bf16*)hb, s_hb, sv, s_sv, (__bf16*)hT, ld_hT, s_hT, B, H, T, groups,    \
+                     gx, s_gx, hs, s_hs, (__bf16*)hb, s_hb, (__bf16*)hx, s_hx, sv, s_sv, (__bf16*)hT, ld_hT, s_hT, B, H, T, groups,    \
                      sync, base, spin_limit)
   if (ncf == 1) HPSGD_FWD_PB(1);
   else if (ncf == 2) HPSGD_FWD_PB(2);
@@ -1030,15 +1056,16 @@ hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b
   return hipGetLastError();
 }
 
-hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghb, long s_dgb, float* D, long s_D,
+hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, long s_dgh, long s_dgb, float* D, long s_D,
                                        const float* above, long s_above, const float* sv, long s_sv, const float* hs,
                                        long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
                                        int B, int H, int T, int groups, unsigned* sync, unsigned base,
                                        unsigned spin_limit, hipStream_t s) {
-  if (!gru_persist_bf16_supported(B, H, groups) || T < 1 || !dbp || !dgxb || !dgxT || !dghT)
+  if (!gru_persist_bf16_supported(B, H, groups) || T < 1 || !dbp || !dgxb || !dgxT || !dghT || !dghx)
     return hipErrorInvalidValue;
   auto a16 = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
-  if (!a16(WT) || !a16(dghb) || !a16(dgxb) || !a16(dgxT) || !a16(dghT) || !a16(D) || !a16(sv) || !a16(hs) ||
+  if ((s_dgh & 7) != 0) return hipErrorInvalidValue;
+  if (!a16(WT) || !a16(dghx) || !a16(dgxb) || !a16(dgxT) || !a16(dghT) || !a16(D) || !a16(sv) || !a16(hs) ||
       (above && !a16(above)) || (s_wt & 7) != 0 || (s_dgb & 7) != 0 || (ld_T & 7) != 0 || (s_T & 7) != 0 ||
       (s_D & 3) != 0 || (s_above & 3) != 0 || (s_sv & 3) != 0 || (s_hs & 3) != 0)
     return hipErrorInvalidValue;
@@ -1059,7 +1086,7 @@ hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghb, lo
   KernelTimer kt(KID_GRU_BWD_PERSIST_BF16, 2.0 * B * 3 * H * (double)H * T * groups, s);
 #define HPSGD_BWD_PB(N)                                                                                            \
   hipLaunchKernelGGL(gru_bwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)WT, s_wt,              \
-                     (__bf16*)dghb, s_dgb, D, s_D, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \
+                     (__bf16*)dghx, s_dgh, s_dgb, D, s_D, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \
                      (__bf16*)dghT, ld_T, s_T, dbp, B, H, T, groups, sync, base, spin_limit)
   if (ncf == 1) HPSGD_BWD_PB(3);
   else if (ncf == 2) HPSGD_BWD_PB(6);

@@ -42,6 +42,7 @@ struct hpsgd_ctx {
   Region dwp, dbp;              // their partial sums of dW_hh and of the bias gradients, one per 32-row batch tile
   Region dwip;                  // partial sums of dW_ih of a narrow layer input (contraction cut into kWihSplits)
   Region hb, dghb, dgxb;        // bf16 copies of h, dgh and dgx (bf16 precision only)
+  Region hx, dghx;              // h and dgh as the resident-weight launches exchange them (fragment-major)
   // transposed bf16 copies that bring the weight-gradient and input-gradient GEMMs into the
   // contraction-contiguous form (bf16 precision only); sizes in floats = bf16 count / 2
   Region dgxT, dghT, xT, dlogT, wihT, woT;
@@ -160,6 +161,8 @@ int build_layout(hpsgd_ctx* c) {
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
+      c->hx = c->alloc(((size_t)(d.seq_len + 1) * gru_persist_bf16_exchange_elems(d.batch, d.hidden) + 1) / 2);
+      c->dghx = c->alloc(((size_t)d.seq_len * gru_persist_bf16_exchange_elems(d.batch, 3 * d.hidden) + 1) / 2);
       c->dgxb = c->alloc((TB * 3 * H + 1) / 2);
       const size_t TBp = round_up(TB, 64), TB1p = round_up(TB + d.batch, 64);
       const size_t win0 = lm ? d.embed : d.input;
@@ -665,6 +668,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (bf && gru_fused_bf16_supported(H))
         ok = ok && fill_pack_push(fp, reg(c->hb), 0, 1, (long)B * H / 2, c->hb.stride, groups);
+      if (use_persist_b)
+        ok = ok && fill_pack_push(fp, reg(c->hx), 0, 1, (long)(gru_persist_bf16_exchange_elems(B, H) / 2), c->hx.stride, groups);
       if (ok) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_fill_pack(fp, s));
@@ -728,6 +733,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         whhT_ready[l] = wc.whhT[l];
         if (!cleared) {
           HIP_TRY(launch_fill_zero((float*)hb, (size_t)B * H / 2, (size_t)c->hb.stride, groups, s));
+          if (use_persist_b)
+            HIP_TRY(launch_fill_zero(reg(c->hx), gru_persist_bf16_exchange_elems(B, H) / 2, c->hx.stride, groups, s));
           if (hT)  // h_0 = 0: the first B columns of the transposed copy
             HIP_TRY(launch_fill_zero_2d((float*)hT, TB1p / 2, H, B / 2, c->hsT[l].stride, groups, s));
         }
@@ -748,8 +755,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, hb, s_hb, sv,
-                                            s_sv, hT, TB1p, s_hT, B, H, T, groups, psync, pbase, c->spin_limit, s));
+        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, hb, s_hb,
+                                            bfreg(c->hx), 2 * (long)c->hx.stride, sv, s_sv, hT, TB1p, s_hT, B, H, T, groups,
+                                            psync, pbase, c->spin_limit, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         ++c->last_resident;
         resident.note();
@@ -1021,7 +1029,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
-        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, dghb, s_dgb, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, dgxb,
+        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, bfreg(c->dghx), 2 * (long)c->dghx.stride, s_dgb, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, dgxb,
                                             bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B, H, T, groups, psync,
                                             pbase, c->spin_limit, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);

@@ -197,17 +197,21 @@ bool reduce_pack_push(ReducePack& pk, const float* parts, int n_parts, size_t n,
 hipError_t launch_reduce_pack(const ReducePack& pk, int groups, hipStream_t s);
 hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const float* in, size_t s_in,
                                float* out, size_t s_out, float lr, int commit, int groups, hipStream_t s);
-// bf16 operands (strides of bf16 buffers in bf16 elements): hb / dghb hold all time steps and are the
-// operands the workgroups exchange; hT, dgxT, dghT are the transposed copies [unit][time * B + row].
+// bf16 operands (strides of bf16 buffers in bf16 elements): hx / dghx hold all time steps and are the
+// operands the workgroups exchange, kept fragment-major (per step a block of 16 ceil(B/16) rows;
+// gru_persist_bf16_exchange_elems gives a step's block); hb is the row-major copy of h for the
+// GEMMs; hT, dgxT, dghT are the transposed copies [unit][time * B + row].
 // The backward launch always leaves the partial bias-gradient sums in dbp and writes no fp32
 // gate gradients.  Counters advance by steps * gru_persist_bf16_count_per_step().
 bool gru_persist_bf16_supported(int B, int H, int groups);
 unsigned gru_persist_bf16_count_per_step(int H);
 hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep, const float* gx,
-                                       long s_gx, float* hs, long s_hs, void* hb, long s_hb, float* sv, long s_sv,
-                                       void* hT, long ld_hT, long s_hT, int B, int H, int T, int groups,
-                                       unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
-hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghb, long s_dgb, float* D, long s_D,
+                                       long s_gx, float* hs, long s_hs, void* hb, long s_hb, void* hx, long s_hx,
+                                       float* sv, long s_sv, void* hT, long ld_hT, long s_hT, int B, int H, int T,
+                                       int groups, unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
+// bf16 elements of one time step's block of an exchange buffer whose rows are `width` wide
+size_t gru_persist_bf16_exchange_elems(int B, int width);
+hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, long s_dgh, long s_dgb, float* D, long s_D,
                                        const float* above, long s_above, const float* sv, long s_sv, const float* hs,
                                        long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
                                        int B, int H, int T, int groups, unsigned* sync, unsigned base,
