@@ -190,7 +190,11 @@ int hpsgd_set_aux_stream(hpsgd_ctx *ctx, void *hip_stream);
  * the workspace; such a launch may also take over the input projection of a narrow layer
  * input, the recurrent weight gradient and the bias gradients.  Otherwise, and with
  * resident == 0, one launch per time step.  Both forms compute the same quantities; the fp32
- * sums inside a dot product are taken in a different order.  spin_limit bounds every such wait
+ * sums inside a dot product are taken in a different order.  The workgroups of such a launch
+ * exchange h_t (forward) and the gate gradients (backward) through the L2 of the XCD they share
+ * when the launch fills the chip and can seat each group of workgroups on one XCD, else, and always with
+ * resident == 2, through memory at device scope; the results are the same bits.  spin_limit
+ * bounds every such wait
  * (polls of the flags; 0 makes every wait fail at once, for testing).  A wait that is given up
  * ends the launch early on every workgroup, and the local step then delivers NaN in loss_out
  * and in the first parameter of every output replica; hpsgd_recurrence_gave_up reports it too.

@@ -192,7 +192,7 @@ class Context:
 
     def set_recurrence(self, resident=True, spin_limit=1 << 20):
         """fp32 GRU recurrence as one launch per run of time steps (weights resident on the chip) or one per step."""
-        _check(self.lib.hpsgd_set_recurrence(self._h, int(bool(resident)), int(spin_limit)), "hpsgd_set_recurrence")
+        _check(self.lib.hpsgd_set_recurrence(self._h, int(resident), int(spin_limit)), "hpsgd_set_recurrence")
 
     def recurrence_info(self):
         """(resident, xproj, dw): GRU layers of the last local step whose recurrence ran as resident-weight

@@ -68,6 +68,7 @@ struct hpsgd_ctx {
   hipStream_t aux = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool resident = true;         // fp32 recurrence: one launch per run of time steps when supported
+  bool device_scope = false;    // resident-weight launches exchange at device scope even where an XCD's L2 would do
   unsigned spin_limit = 1u << 20;  // bound of every wait inside those launches
   size_t last_commit_params = 0;  // parameters per worker that the commit kernel handled last step
   int last_resident = 0, last_xproj = 0, last_dw = 0;  // GRU layers of the last step, see hpsgd_recurrence_info
@@ -614,6 +615,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     }
     unsigned* psync = (use_persist || use_persist_b) ? (unsigned*)reg(c->psync) : nullptr;
     unsigned pbase = 0;
+    unsigned ticket_launches = 0;  // launches of this step that placed their workgroups by ticket
     if (use_persist || use_persist_b) {
       TRY0(resident.begin(s));
       abort_word = psync;  // (cleared together with the first layer's h_0 below)
@@ -747,7 +749,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_GEMM_REC_FWD;
         HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
                                        groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
-                                       Wih0, rin + c->eoff(c->lidx[l].bih), s));
+                                       Wih0, rin + c->eoff(c->lidx[l].bih), c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
         ++c->last_resident;
         c->last_xproj += xproj ? 1 : 0;
@@ -757,7 +759,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_GEMM_REC_FWD;
         HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, hb, s_hb,
                                             bfreg(c->hx), 2 * (long)c->hx.stride, sv, s_sv, hT, TB1p, s_hT, B, H, T, groups,
-                                            psync, pbase, c->spin_limit, s));
+                                            psync, pbase, c->spin_limit, c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         ++c->last_resident;
         resident.note();
@@ -1021,7 +1023,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
         HIP_TRY(launch_gru_bwd_persist(Whh, sR, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
-                                       T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, s));
+                                       T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, c->device_scope, &ticket_launches, s));
         c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);
         if (l == 0) TRY0(resident.mark());
@@ -1029,9 +1031,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
-        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, bfreg(c->dghx), 2 * (long)c->dghx.stride, s_dgb, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, dgxb,
-                                            bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B, H, T, groups, psync,
-                                            pbase, c->spin_limit, s));
+        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, bfreg(c->dghx), 2 * (long)c->dghx.stride, s_dgb, D, s_D, above,
+                                            s_dx, sv, s_sv, hs, s_hs, dgxb, bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B,
+                                            H, T, groups, psync, pbase, c->spin_limit, c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         if (l == 0) TRY0(resident.mark());
         else resident.note();
@@ -1566,6 +1568,7 @@ int hpsgd_set_aux_stream(hpsgd_ctx* ctx, void* hip_stream) {
 int hpsgd_set_recurrence(hpsgd_ctx* ctx, int resident, unsigned spin_limit) {
   if (!ctx) return HPSGD_EINVAL;
   ctx->resident = resident != 0;
+  ctx->device_scope = resident == 2;
   ctx->spin_limit = spin_limit;
   return HPSGD_OK;
 }

@@ -151,16 +151,22 @@ hipError_t launch_gru_bwd_step(const float* WT, long s_wt, const float* dgh_next
                                long s_sv, const float* h_prev, long s_hs, float* dgx_t, float* dgh_t,
                                int B, int H, int groups, hipStream_t s);
 // ---- whole runs of time steps in one launch, W_hh resident in LDS (fp32), see gru_persist.hip ----
-// sync: gru_persist_sync_words() words of device memory (the abort word, then the flag words of
-// the synchronisation groups); base: what the flags read when the launch starts; every launch
+// sync: gru_persist_sync_words() words of device memory (the abort word, the flag words of the
+// synchronisation groups, 8 ticket counters); base: what the flags read when the launch starts; every launch
 // advances them by steps * gru_persist_count_per_step().  spin_limit bounds every wait.
 bool gru_persist_supported(int B, int H, int groups);
 size_t gru_persist_sync_words(int B, int groups);
 unsigned gru_persist_count_per_step(int H);
+// device_scope: the workgroups exchange through memory that every XCD sees; false lets a launch
+// that fills the chip with one workgroup per CU exchange through the L2 of the XCD a
+// synchronisation group runs on (the workgroups then take their tiles by where they run: they draw
+// tickets from 8 counters at the end of the sync words, zero at the start of a step).
+// ticket_launches: the step's count of launches that have drawn tickets (advanced by the launcher;
+// all launches of a step that share the sync words must share it).
 hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
                                   float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
                                   unsigned* sync, unsigned base, unsigned spin_limit, const float* xin, long s_x,
-                                  int width, const float* W_ih, const float* b_ih, hipStream_t s);
+                                  int width, const float* W_ih, const float* b_ih, bool device_scope, unsigned* ticket_launches, hipStream_t s);
 // xin != nullptr (allowed when gru_persist_xproj_supported(H, width)): the launch computes the input
 // projection itself from the layer input xin (T blocks of B x width per worker, stride s_x) and W_ih,
 // b_ih (in the replica, like W_hh); gx is then unused and may be nullptr.
@@ -170,7 +176,7 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
                                   int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
-                                  float* dbp, hipStream_t s);
+                                  float* dbp, bool device_scope, unsigned* ticket_launches, hipStream_t s);
 // dbp != nullptr: the launch also leaves dbp[(g * RT + ty)][6H], partial sums over its steps of the
 // bias gradients (b_ih: sum of dgx, then b_hh: sum of dgh)
 // dWp != nullptr (allowed when gru_persist_dw_supported(H)): the launch also leaves
@@ -208,14 +214,15 @@ unsigned gru_persist_bf16_count_per_step(int H);
 hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b_hh, long s_rep, const float* gx,
                                        long s_gx, float* hs, long s_hs, void* hb, long s_hb, void* hx, long s_hx,
                                        float* sv, long s_sv, void* hT, long ld_hT, long s_hT, int B, int H, int T,
-                                       int groups, unsigned* sync, unsigned base, unsigned spin_limit, hipStream_t s);
+                                       int groups, unsigned* sync, unsigned base, unsigned spin_limit, bool device_scope,
+                                       unsigned* ticket_launches, hipStream_t s);
 // bf16 elements of one time step's block of an exchange buffer whose rows are `width` wide
 size_t gru_persist_bf16_exchange_elems(int B, int width);
 hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, long s_dgh, long s_dgb, float* D, long s_D,
                                        const float* above, long s_above, const float* sv, long s_sv, const float* hs,
                                        long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
                                        int B, int H, int T, int groups, unsigned* sync, unsigned base,
-                                       unsigned spin_limit, hipStream_t s);
+                                       unsigned spin_limit, bool device_scope, unsigned* ticket_launches, hipStream_t s);
 // NaN into loss[0..n_loss) and into rout[g * s_rout] for every group if *abort_w != 0
 hipError_t launch_poison_on_abort(const unsigned* abort_w, float* loss, int n_loss, float* rout, long s_rout,
                                   int groups, hipStream_t s);

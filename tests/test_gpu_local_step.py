@@ -593,6 +593,43 @@ def test_resident_weight_recurrence_reports_a_wait_that_was_given_up():
     assert np.isfinite(tr.R[0].cpu().numpy()).all()
 
 
+EXCHANGE_SCOPE = {
+    # synchronisation groups (workers x row tiles of 32) a multiple of 8: each sits on one XCD
+    "gru_cls": wl.CONFIGS["gru_cls"],
+    "gru_lm": wl.CONFIGS["gru_lm"],
+    "lm_bf16_k8": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=72, hidden=160, seq_len=9, batch=24, K=8),
+    "cls_fp32_ragged": wl.scaled(wl.CONFIGS["gru_cls"], input=24, hidden=96, seq_len=7, batch=40, K=4),
+    # ... and not a multiple of 8: both settings exchange at device scope
+    "lm_nt_bf16": None,
+}
+
+
+@pytest.mark.parametrize("name", list(EXCHANGE_SCOPE))
+def test_exchange_through_the_l2_of_one_xcd_equals_exchange_at_device_scope(name):
+    """The resident-weight launches hand h_t and the gate gradients from workgroup to workgroup
+    through the L2 of the XCD a synchronisation group sits on (ordinary stores) or through memory
+    every XCD sees (write-through stores; forced by set_recurrence(2)): same loads, same
+    arithmetic, so the same bits in every replica and loss, over two local steps; no workgroup found
+    itself on another XCD than the library had probed (that would show as a wait given up)."""
+    cfg = EXCHANGE_SCOPE[name] or BF16[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for mode in (1, 2):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+        tr.ctx.set_recurrence(mode)
+        tr.sync_all(0)
+        for step in range(2):
+            tr.gather(step)
+            tr.local_step(0, cfg["lr"])
+        torch.cuda.synchronize()
+        assert not tr.ctx.recurrence_gave_up(tr.ws[0])
+        assert tr.ctx.recurrence_info()[0] == cfg["layers"]
+        outs.append((tr.R[0].cpu().numpy().view(np.uint32).copy(), tr.loss.cpu().numpy().view(np.uint32).copy()))
+        del tr
+    assert np.array_equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1], outs[1][1])
+
+
 @pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "cls_nt_bf16_c16", "cls_nt_bf16", "lm_nt_bf16_h384",
                                   "lm_nt_bf16_h1024"])
 def test_resident_weight_recurrence_bf16_equals_one_launch_per_step(name):
