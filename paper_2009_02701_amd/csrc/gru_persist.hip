@@ -66,6 +66,16 @@ constexpr int PC = 32;       // contraction chunk
 constexpr int SP = 80;       // pitch of the staged dgh tile: 4 batch rows x 16 gate rows hit 64 banks
 
 __device__ __forceinline__ float sigm_p(float a) { return 1.0f / (1.0f + expf(-a)); }
+// The gates of the bf16 forward launch, whose cell math is a fifth of a step: the hardware's
+// exp2 and reciprocal (1 ulp each) in place of the library's expf, tanhf and division.  Absolute
+// error about 1e-7 (tanh near 0 included: 1 - 2 / (e^2a + 1) loses relative, not absolute, accuracy),
+// against gate values that are then rounded to bf16 (4e-3 relative) as operands.
+__device__ __forceinline__ float sigm_fast(float a) {
+  return __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.44269504f * a));
+}
+__device__ __forceinline__ float tanh_fast(float a) {
+  return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(2.88539008f * a));
+}
 
 // Workgroup i runs on XCD i % 8; a synchronisation group (worker g, row tile ty) is kept on
 // one XCD when the number of groups allows it.  sg = g * RT + ty.
@@ -730,9 +740,9 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
       gh[q].x = (((p[0].x + p[1].x) + (p[2].x + p[3].x)) + ((p[4].x + p[5].x) + (p[6].x + p[7].x))) + bias[q].x;
       gh[q].y = (((p[0].y + p[1].y) + (p[2].y + p[3].y)) + ((p[4].y + p[5].y) + (p[6].y + p[7].y))) + bias[q].y;
     }
-    const float r0v = sigm_p(gxv[0].x + gh[0].x), r1v = sigm_p(gxv[0].y + gh[0].y);
-    const float z0v = sigm_p(gxv[1].x + gh[1].x), z1v = sigm_p(gxv[1].y + gh[1].y);
-    const float n0v = tanhf(gxv[2].x + r0v * gh[2].x), n1v = tanhf(gxv[2].y + r1v * gh[2].y);
+    const float r0v = sigm_fast(gxv[0].x + gh[0].x), r1v = sigm_fast(gxv[0].y + gh[0].y);
+    const float z0v = sigm_fast(gxv[1].x + gh[1].x), z1v = sigm_fast(gxv[1].y + gh[1].y);
+    const float n0v = tanh_fast(gxv[2].x + r0v * gh[2].x), n1v = tanh_fast(gxv[2].y + r1v * gh[2].y);
     const float2 hn = make_float2((1.0f - z0v) * n0v + z0v * hpv.x, (1.0f - z1v) * n1v + z1v * hpv.y);
     if (row < B) {
       const long e = ((long)(t + 1) * B + row) * H + j;
