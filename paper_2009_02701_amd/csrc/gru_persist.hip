@@ -257,6 +257,36 @@ __device__ __forceinline__ void fragment_mfmas(const float* wres, int wp, int KD
   }
 }
 
+// The exchanged operands (h_t, the gate gradients) are not read from a row-major matrix: there a
+// load instruction fetches 64 bytes of each of 16 rows, half a cache line per row, which a CU
+// does 2.8 times slower than whole lines (see the bf16 part below).  They are kept
+// fragment-major: per step a block of ceil(B/16) row blocks x ceil(KD/32) chunks x 2 halves,
+// each the 1 KB one load instruction reads, lane l's 16 bytes at byte 16 l (lane l: row l % 16,
+// contraction indices 16 half + 4 (l / 16) .. + 3 of the chunk).  xoff: word offset of (row, k)
+// inside a step's block; halves beyond KD are never written and never read.
+__device__ __forceinline__ long xoff(int row, int nch, int k) {
+  return ((((long)(row >> 4) * nch + (k >> 5)) * 2 + ((k >> 4) & 1)) * 64 + (((k & 15) >> 2) << 4) + (row & 15)) * 4 + (k & 3);
+}
+// words of a step's block
+__host__ __device__ __forceinline__ long xblock_words(int B, int KD) {
+  return (long)((B + 15) / 16) * 16 * ((KD + PC - 1) / PC) * PC;
+}
+// fragment_loads from a step's fragment-major block (rs), row block rbx of it
+template <int NB>
+__device__ __forceinline__ void fragment_loads_x(__amdgpu_buffer_rsrc_t rs, int KD, int rbx, int c0, float4 (&a)[NB][2]) {
+  const int lane = threadIdx.x & 63;
+  const int nch = (KD + PC - 1) / PC;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int c = c0 + 4 * i;
+    // (KD is a multiple of 16: a half is all in or all out; one that is out meets zero weights and
+    // is read from the block's first fragment)
+    const bool v0 = PC * c < KD, v1 = PC * c + 16 < KD;
+    a[i][0] = ld16_dev(rs, ((rbx * nch + (v0 ? c : 0)) * 2) * 1024 + lane * 16);
+    a[i][1] = ld16_dev(rs, ((rbx * nch + (v1 ? c : 0)) * 2 + (v1 ? 1 : 0)) * 1024 + lane * 16);
+  }
+}
+
 // acc[i][q] (i = 0, 1: two accumulators per gate block, summed by the caller) +=
 // sum over this wave's chunks of A[rsel*16 + ..][k] * Wres[q*16 + ..][k].
 // wres: the resident weight rows (pitch wp words, zero beyond KD).  NB: chunks per wave whose
@@ -269,6 +299,20 @@ __device__ __forceinline__ void resident_contraction(const float* wres, int wp, 
   for (int c0 = kw; c0 < nch; c0 += 4 * NB) {
     float4 a[NB][2];
     fragment_loads<NB>(rs, KD, rows_valid, c0, a);
+    __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
+    fragment_mfmas<NQ, NB>(wres, wp, KD, c0, a, acc);
+  }
+}
+
+// ... with the activations in a fragment-major block
+template <int NQ, int NB>
+__device__ __forceinline__ void resident_contraction_x(const float* wres, int wp, __amdgpu_buffer_rsrc_t rs, int KD,
+                                                       int rbx, floatx4 (&acc)[2][NQ]) {
+  const int kw = (threadIdx.x >> 6) & 3;
+  const int nch = (KD + PC - 1) / PC;
+  for (int c0 = kw; c0 < nch; c0 += 4 * NB) {
+    float4 a[NB][2];
+    fragment_loads_x<NB>(rs, KD, rbx, c0, a);
     __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
     fragment_mfmas<NQ, NB>(wres, wp, KD, c0, a, acc);
   }
@@ -289,8 +333,8 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
 template <int XNB>  // chunks of the layer input per wave (width <= 128 * XNB); 0: gx is given
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__ b_hh, long s_rep,
-                       const float* __restrict__ gx, long s_gx, float* hs, long s_hs, float* __restrict__ sv,
-                       long s_sv, int B, int H, int T, int groups, unsigned* sync, unsigned base,
+                       const float* __restrict__ gx, long s_gx, float* __restrict__ hs, long s_hs, float* hx, long s_hx,
+                       float* __restrict__ sv, long s_sv, int B, int H, int T, int groups, unsigned* sync, unsigned base,
                        unsigned spin_limit, unsigned* tickets, unsigned ticket_base, unsigned per_xcd,
                        const float* __restrict__ xin, long s_x, int width,
                        const float* __restrict__ W_ih, const float* __restrict__ b_ih) {
@@ -335,6 +379,9 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
     for (int q = 0; q < 3; ++q) biasx[q] = (b_ih + g * s_rep)[q * H + j];
   }
   float* hsg = hs + g * s_hs;
+  float* hxg = hx + g * s_hx;                 // h_0 .. h_T as the workgroups exchange them
+  const long xblk = xblock_words(B, H);
+  const int rbx = (r0 + rsel * 16 < B ? r0 + rsel * 16 : r0) >> 4;  // this wave's row block (one beyond the batch: the tile's first)
   float hpv = hsg[(long)rowc * H + j];
   float4 xa[XB][2];  // the next step's fragments of the layer input
   if (XP) fragment_loads<XB>(tile_rsrc(xin + g * s_x + (long)r0 * width), width, B - r0, kw, xa);
@@ -366,7 +413,7 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
       for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
     }
     if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
-    resident_contraction<3, 4>(wres, wp, tile_rsrc(hsg + ((long)t * B + r0) * H), H, B - r0, acc);
+    resident_contraction_x<3, 4>(wres, wp, tile_rsrc(hxg + (long)t * xblk), H, rbx, acc);
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
 #pragma unroll
@@ -388,7 +435,8 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
     const float n = tanhf((XP ? gh[NP - 1] + biasx[2] : gxv[2]) + r * qv);
     const float hn = (1.0f - z) * n + z * hpv;
     if (row < B) {
-      st_dev(&hsg[((long)(t + 1) * B + row) * H + j], hn, l2x);
+      hsg[((long)(t + 1) * B + row) * H + j] = hn;
+      st_dev(hxg + (long)(t + 1) * xblk + xoff(row, (H + PC - 1) / PC, j), hn, l2x);
       float* svr = sv + g * s_sv + ((long)t * B + row) * 4 * H;
       svr[j] = r;
       svr[H + j] = z;
@@ -423,7 +471,8 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
 // attribute counts in halves of the unified VGPR/AGPR file on this target: 124 caps the wave at
 // 248 registers (2 dwords per lane are spilled), which leaves 16 per SIMD for a co-tenant.
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_num_vgpr(124)))
-gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, float* __restrict__ dgx, long s_dg,
+gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* __restrict__ dgh, float* dghx, long s_dghx,
+                       float* __restrict__ dgx, long s_dg,
                        float* __restrict__ D, long s_D, const float* __restrict__ above, long s_above,
                        const float* __restrict__ sv, long s_sv, const float* __restrict__ hs, long s_hs,
                        int B, int H, int T, int t_hi, int t_lo, int groups, unsigned* sync, unsigned base,
@@ -478,7 +527,11 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
   const int rowc = min(row, B - 1);
   float* Dg = D + g * s_D;
   float dcar = Dg[(long)rowc * H + j];  // dh_{t+1} * z_{t+1}, carried in a register
-  float* dghg = dgh + g * s_dg;
+  float* dghg = dgh ? dgh + g * s_dg : nullptr;  // row-major, for later launches (nullptr: nobody reads it)
+  float* dgxg = dghx + g * s_dghx;               // the gate gradients as the workgroups exchange them
+  const long xblk = xblock_words(B, H3);
+  const int nchx = (H3 + PC - 1) / PC;
+  const int rbx = (r0 + rsel * 16 < B ? r0 + rsel * 16 : r0) >> 4;
   __syncthreads();
   int it = 0;
   for (int t = t_hi - 1; t >= t_lo; --t, ++it) {
@@ -492,7 +545,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
     acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
     acc[1][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
     if (t + 1 < T)  // uniform over the grid
-      resident_contraction<1, 12>(wres, wp, tile_rsrc(dghg + ((long)(t + 1) * B + r0) * H3), H3, B - r0, acc);
+      resident_contraction_x<1, 12>(wres, wp, tile_rsrc(dgxg + (long)(t + 1) * xblk), H3, rbx, acc);
 #pragma unroll
     for (int v = 0; v < 4; ++v) red[((kw * 2 + rsel) * 4 + v) * 64 + lane] = acc[0][0][v] + acc[1][0][v];
     __syncthreads();
@@ -507,13 +560,19 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* dgh, f
     const float da_z = dz * z * (1.0f - z);
     if (row < B) {
       float* ox = dgx + g * s_dg + ((long)t * B + row) * H3;
-      float* oh = dghg + ((long)t * B + row) * H3;
       ox[j] = da_r;
       ox[H + j] = da_z;
       ox[2 * H + j] = da_n;
-      st_dev(&oh[j], da_r, l2x);
-      st_dev(&oh[H + j], da_z, l2x);
-      st_dev(&oh[2 * H + j], dq, l2x);
+      float* oe = dgxg + (long)t * xblk;
+      st_dev(oe + xoff(row, nchx, j), da_r, l2x);
+      st_dev(oe + xoff(row, nchx, H + j), da_z, l2x);
+      st_dev(oe + xoff(row, nchx, 2 * H + j), dq, l2x);
+      if (dghg) {
+        float* oh = dghg + ((long)t * B + row) * H3;
+        oh[j] = da_r;
+        oh[H + j] = da_z;
+        oh[2 * H + j] = dq;
+      }
     }
     dcar = dh * z;
     if (row < B) {
@@ -1020,12 +1079,16 @@ bool gru_persist_xproj_supported(int H, int width) {
   return width >= 16 && width % 16 == 0 && width <= 256 && persist_xp_lds_bytes(H, width) <= kLdsLimit;
 }
 
+size_t gru_persist_exchange_words(int B, int width) { return (size_t)xblock_words(B, width); }
+
 hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
-                                  float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
+                                  float* hs, long s_hs, float* hx, long s_hx, float* sv, long s_sv, int B, int H, int T,
+                                  int groups,
                                   unsigned* sync, unsigned base, unsigned spin_limit, const float* xin, long s_x,
                                   int width, const float* W_ih, const float* b_ih, bool device_scope, unsigned* ticket_launches, hipStream_t s) {
   if (!gru_persist_supported(B, H, groups) || T < 1) return hipErrorInvalidValue;
-  if (((uintptr_t)hs & 15) != 0 || (s_hs & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0)
+  if (((uintptr_t)hs & 15) != 0 || (s_hs & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0 || !hx ||
+      ((uintptr_t)hx & 15) != 0 || (s_hx & 3) != 0)
     return hipErrorInvalidValue;
   if (xin && (!gru_persist_xproj_supported(H, width) || !W_ih || !b_ih || ((uintptr_t)xin & 15) != 0 ||
               (s_x & 3) != 0 || ((uintptr_t)W_ih & 15) != 0))
@@ -1047,7 +1110,7 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
   KernelTimer kt(KID_GRU_FWD_PERSIST, 2.0 * B * 3 * H * ((double)H + (xin ? width : 0)) * T * groups, s);
 #define HPSGD_FWD_PERSIST(N)                                                                                    \
   hipLaunchKernelGGL(gru_fwd_persist_kernel<N>, grid, dim3(PNT), lds, s, W_hh, b_hh, s_rep, gx, s_gx, hs, s_hs, \
-                     sv, s_sv, B, H, T, groups, sync, base, spin_limit, pl.tickets, pl.ticket_base, pl.per_xcd, xin, s_x,  \
+                     hx, s_hx, sv, s_sv, B, H, T, groups, sync, base, spin_limit, pl.tickets, pl.ticket_base, pl.per_xcd, xin, s_x,  \
                      width, W_ih, b_ih)
   if (xnb == 0) HPSGD_FWD_PERSIST(0);
   else if (xnb == 1) HPSGD_FWD_PERSIST(1);
@@ -1056,7 +1119,8 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
   return hipGetLastError();
 }
 
-hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dgx, long s_dg, float* D,
+hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dghx, long s_dghx, float* dgx,
+                                  long s_dg, float* D,
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
                                   int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
@@ -1065,7 +1129,8 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
   if (dWp && (!gru_persist_dw_supported(H) || ((uintptr_t)dWp & 15) != 0 || ((uintptr_t)hs & 15) != 0 ||
               (s_hs & 3) != 0))
     return hipErrorInvalidValue;
-  if (((uintptr_t)dgh & 15) != 0 || (s_dg & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0)
+  if (((uintptr_t)dgh & 15) != 0 || (s_dg & 3) != 0 || ((uintptr_t)W_hh & 15) != 0 || (s_rep & 3) != 0 || !dghx ||
+      ((uintptr_t)dghx & 15) != 0 || (s_dghx & 3) != 0)
     return hipErrorInvalidValue;
   const size_t lds = persist_lds_bytes(H);
   static size_t allowed = 0;
@@ -1078,7 +1143,7 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
   const Placement pl = placement(sync, groups * ((B + PR - 1) / PR), (long)grid.x, lds, device_scope, ticket_launches);
   KernelTimer kt(KID_GRU_BWD_PERSIST, 2.0 * B * 3 * H * (double)H * (t_hi - t_lo) * groups * (dWp ? 2 : 1), s);
-  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dgx, s_dg, D, s_D, above,
+  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dghx, s_dghx, dgx, s_dg, D, s_D, above,
                      s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit,
                      pl.tickets, pl.ticket_base, pl.per_xcd, dWp, dbp);
   return hipGetLastError();

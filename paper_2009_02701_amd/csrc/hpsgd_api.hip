@@ -159,6 +159,10 @@ int build_layout(hpsgd_ctx* c) {
     if (d.prec != HPSGD_BF16_MFMA && gru_fused_supported(d.hidden) && gru_persist_dw_supported(d.hidden))
       c->dwp = c->alloc((size_t)((d.batch + 31) / 32) * 3 * H * H);
     if (d.prec != HPSGD_BF16_MFMA) c->dwip = c->alloc((size_t)kWihSplits * 3 * H * (lm ? d.embed : d.input));
+    if (d.prec != HPSGD_BF16_MFMA && gru_fused_supported(d.hidden)) {
+      c->hx = c->alloc((size_t)(d.seq_len + 1) * gru_persist_exchange_words(d.batch, d.hidden));
+      c->dghx = c->alloc((size_t)d.seq_len * gru_persist_exchange_words(d.batch, 3 * d.hidden));
+    }
     if (d.prec == HPSGD_BF16_MFMA) {
       c->hb = c->alloc(((TB + d.batch) * H + 1) / 2);
       c->dghb = c->alloc((TB * 3 * H + 1) / 2);
@@ -672,6 +676,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         ok = ok && fill_pack_push(fp, reg(c->hb), 0, 1, (long)B * H / 2, c->hb.stride, groups);
       if (use_persist_b)
         ok = ok && fill_pack_push(fp, reg(c->hx), 0, 1, (long)(gru_persist_bf16_exchange_elems(B, H) / 2), c->hx.stride, groups);
+      if (use_persist)
+        ok = ok && fill_pack_push(fp, reg(c->hx), 0, 1, (long)gru_persist_exchange_words(B, H), c->hx.stride, groups);
       if (ok) {
         role = HPSGD_ROLE_OTHER;
         HIP_TRY(launch_fill_pack(fp, s));
@@ -683,9 +689,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       float* sv = reg(c->sv[l]);
       const long s_hs = (long)c->hs[l].stride, s_sv = (long)c->sv[l].stride;
       role = HPSGD_ROLE_OTHER;
-      if (!cleared)
+      if (!cleared) {
         HIP_TRY(launch_fill_zero(hs, (size_t)B * H, (size_t)s_hs, groups, s, l == 0 ? (float*)psync : nullptr,
                                  l == 0 && psync ? gru_persist_sync_words(B, groups) : 0));
+        if (use_persist && l == 0)
+          HIP_TRY(launch_fill_zero(reg(c->hx), gru_persist_exchange_words(B, H), c->hx.stride, groups, s));
+      }
       const float* Whh = rin + c->eoff(c->lidx[l].whh);
       const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
@@ -747,7 +756,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, sv, s_sv, B, H, T,
+        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, reg(c->hx),
+                                       (long)c->hx.stride, sv, s_sv, B, H, T,
                                        groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
                                        Wih0, rin + c->eoff(c->lidx[l].bih), c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_count_per_step(H);
@@ -1022,7 +1032,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // that shares the CUs with this launch slows its chain of waits by more than it hides)
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
-        HIP_TRY(launch_gru_bwd_persist(Whh, sR, dgh, dgx, s_gx, D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
+        // (the row-major gate gradients only when a later launch reads them)
+        HIP_TRY(launch_gru_bwd_persist(Whh, sR, (dwp && dbp) ? nullptr : dgh, reg(c->dghx), (long)c->dghx.stride, dgx, s_gx,
+                                       D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
                                        T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, c->device_scope, &ticket_launches, s));
         c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);

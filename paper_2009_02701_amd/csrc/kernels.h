@@ -163,8 +163,14 @@ unsigned gru_persist_count_per_step(int H);
 // tickets from 8 counters at the end of the sync words, zero at the start of a step).
 // ticket_launches: the step's count of launches that have drawn tickets (advanced by the launcher;
 // all launches of a step that share the sync words must share it).
+// hx / dghx: h_0 .. h_T and the gate gradients of all steps as the workgroups exchange them,
+// fragment-major, gru_persist_exchange_words(B, H) resp. (B, 3H) floats per time step (hx: T + 1
+// steps, the first one, h_0, given); hs / dgh are the row-major copies for the other kernels
+// (dgh may be nullptr in the backward launch when nothing reads it later).
+size_t gru_persist_exchange_words(int B, int width);
 hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_rep, const float* gx, long s_gx,
-                                  float* hs, long s_hs, float* sv, long s_sv, int B, int H, int T, int groups,
+                                  float* hs, long s_hs, float* hx, long s_hx, float* sv, long s_sv, int B, int H, int T,
+                                  int groups,
                                   unsigned* sync, unsigned base, unsigned spin_limit, const float* xin, long s_x,
                                   int width, const float* W_ih, const float* b_ih, bool device_scope, unsigned* ticket_launches, hipStream_t s);
 // xin != nullptr (allowed when gru_persist_xproj_supported(H, width)): the launch computes the input
@@ -172,7 +178,8 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
 // b_ih (in the replica, like W_hh); gx is then unused and may be nullptr.
 bool gru_persist_xproj_supported(int H, int width);
 // steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches)
-hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dgx, long s_dg, float* D,
+hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dghx, long s_dghx, float* dgx,
+                                  long s_dg, float* D,
                                   long s_D, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
                                   int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
