@@ -33,17 +33,17 @@ STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel", "commit_kerne
 # of a round.  Summaries with the full commands: profiles/bench_*.md.  Kernels not collected: null.
 KIB = 1024.0
 MEASURED_TRAFFIC_BYTES = {
-    "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 84262.1 + 133497.6) * KIB,
-                "gru_fwd_persist_kernel": (2.0 * 27325.3 + 89880.0) * KIB},
-    # the 192 x 256 form runs three products per round: the logits (746 MB) and two input gradients
+    "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 91903.0 + 150171.0) * KIB,
+                "gru_fwd_persist_kernel": (2.0 * 26935.9 + 107529.2) * KIB},
+    # the 192 x 256 form runs three products per round: the logits (728 MB) and two input gradients
     # (head and top layer; both launch 192 tiles and average 262 MB)
     "gru_lm": {"gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>":
-                   ((2.0 * 188388.9 + 351905.6) + 2 * (2.0 * 109970.5 + 35840.0)) * KIB / 3,
-               "gru_bwd_persist_bf16_kernel": (2.0 * 159743.3 + 241826.7) * KIB,
-               "gru_fwd_persist_bf16_kernel": (2.0 * 90507.2 + 215604.1) * KIB,
-               "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>": (2.0 * 296277.9 + 320906.3) * KIB,
-               "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>": (2.0 * 95348.4 + 98392.6) * KIB,
-               "softmax_ce_bf16_rows_kernel": (2.0 * 175604.1 + 219299.5) * KIB},
+                   ((2.0 * 179701.7 + 351608.1) + 2 * (2.0 * 109970.5 + 35840.0)) * KIB / 3,
+               "gru_bwd_persist_bf16_kernel": (2.0 * 158788.8 + 242274.1) * KIB,
+               "gru_fwd_persist_bf16_kernel": (2.0 * 87909.3 + 233560.1) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>": (2.0 * 296282.1 + 320984.4) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>": (2.0 * 95348.4 + 98414.9) * KIB,
+               "softmax_ce_bf16_rows_kernel": (2.0 * 175758.4 + 219302.6) * KIB},
     "mlp": {},
 }
 
