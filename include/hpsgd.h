@@ -141,8 +141,9 @@ int hpsgd_local_step_all_static(hpsgd_ctx *ctx, const float *replicas_in, float 
  * transposed bf16 copies of every weight matrix; nothing in the others - so that they can
  * be made on the synchronising side, behind hpsgd_sync_all, while the training stream is busy
  * with another generation of replicas.  The context remembers (replicas, replica_stride,
- * workspace); the next local step with exactly these skips its own copies, and every local
- * step forgets the mark (it changes the weights).  The caller must not write the replicas
+ * workspace), one such mark per workspace; the next local step on that workspace skips its own
+ * copies if it is given exactly these, and forgets the workspace's mark either way (it changes
+ * the weights).  The caller must not write the replicas
  * between this call and that step, must order the two streams (the step after this call's
  * work), and must not use the workspace for another step in between.
  * Errors as for hpsgd_local_step_all's replicas_in and workspace arguments. */
@@ -156,13 +157,15 @@ int hpsgd_prepare_replicas(hpsgd_ctx *ctx, const float *replicas, size_t replica
  * eighth of the bytes to write at K = 8 and is fetched once by the products of all workers).  The
  * caller vouches for the equality: a step whose replicas differ from `global` would multiply with
  * the wrong weights.
- * `replicas` / replica_stride / workspace are those of the next local step (they name the mark, as
- * for hpsgd_prepare_replicas; the replicas are not read here).  The copies of the GRU layers'
- * matrices are made by this call; those of the head's matrix are made by the marked local step
- * itself, from `global`, right before its logits product: `global` must stay unchanged until that
- * step has run (a snapshot of the clone's source does).  Errors as above. */
+ * `replicas` / replica_stride / workspace are those of the local step meant (they name the mark, as
+ * for hpsgd_prepare_replicas; the replicas are not read here).  A context keeps one mark per
+ * workspace (up to four), so a schedule with two generations of buffers may prepare one
+ * generation, on its synchronising stream, while the other one steps.  The copies of the GRU
+ * layers' matrices are made by this call; those of the head's matrix too if with_head != 0, else by
+ * the marked local step itself, from `global`, right before its logits product: `global` must then
+ * stay unchanged until that step has run (a snapshot of the clone's source does).  Errors as above. */
 int hpsgd_prepare_clones(hpsgd_ctx *ctx, const float *global, const float *replicas, size_t replica_stride,
-                         void *workspace, void *hip_stream);
+                         void *workspace, int with_head, void *hip_stream);
 
 /* The same for ONE worker (`worker` in [0, K) selects nothing but the workspace slice,
  * so that different workers may be stepped on different streams).  loss_out: 1 float. */

@@ -71,7 +71,7 @@ def load_library():
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_local_step_all_static.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp]
     lib.hpsgd_prepare_replicas.argtypes = [vp, vp, sz, vp, vp]
-    lib.hpsgd_prepare_clones.argtypes = [vp, vp, vp, sz, vp, vp]
+    lib.hpsgd_prepare_clones.argtypes = [vp, vp, vp, sz, vp, C.c_int, vp]
     lib.hpsgd_local_step.argtypes = [vp, C.c_int, vp, vp, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_gather_batch.argtypes = [vp, i32p, C.c_int, sz, C.c_int, sz, vp, vp]
     lib.hpsgd_gather_batch_all.argtypes = [C.POINTER(vp), C.POINTER(vp), C.c_int, C.c_int, sz, C.c_int, sz,
@@ -268,10 +268,11 @@ class Context:
         _check(self.lib.hpsgd_prepare_replicas(self._h, _ptr(replicas), replicas.stride(0), self._ws_ptr(workspace),
                                                _stream(stream)), "hpsgd_prepare_replicas")
 
-    def prepare_clones(self, global_, replicas, workspace, stream=None):
-        """prepare_replicas for replicas that are clones of `global_` (read once instead of K times)."""
+    def prepare_clones(self, global_, replicas, workspace, stream=None, with_head=False):
+        """prepare_replicas for replicas that are clones of `global_`: one set of copies for all workers."""
         _check(self.lib.hpsgd_prepare_clones(self._h, _ptr(global_), _ptr(replicas), replicas.stride(0),
-                                             self._ws_ptr(workspace), _stream(stream)), "hpsgd_prepare_clones")
+                                             self._ws_ptr(workspace), int(bool(with_head)), _stream(stream)),
+               "hpsgd_prepare_clones")
 
     def local_step_all_acc(self, replicas_in, replicas_out, x, y, lr, loss_out, grad_acc, workspace, stream=None):
         """local_step_all that also adds every worker's gradient to grad_acc [K, stride]."""

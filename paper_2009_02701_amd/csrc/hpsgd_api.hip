@@ -52,13 +52,32 @@ struct hpsgd_ctx {
   std::vector<Region> hsT;
   std::vector<Region> whhT, wihTl;  // per layer: transposed bf16 W_hh and W_ih, made in the forward pass
   std::vector<Region> whhb, wihbl;  // per layer: row-major bf16 W_hh and W_ih
-  // hpsgd_prepare_replicas made the bf16 copies of these replicas' weights in this workspace
-  const float* prepared_rin = nullptr;
-  const float* prepared_ws = nullptr;
-  size_t prepared_stride = 0;
-  // hpsgd_prepare_clones left the head's copies to the step: made there from this source (every
-  // worker's from the one matrix), right before the logits GEMM
-  const float* prepared_head_src = nullptr;
+  // Marks left by hpsgd_prepare_replicas / hpsgd_prepare_clones, one per workspace (a schedule with
+  // two generations of buffers prepares one while the other steps): the bf16 copies of these
+  // replicas' weights are in that workspace.  clone_src (prepare_clones): ONE set of copies, made
+  // from this model, serves every worker; head_done: the head's copies are among them (else the
+  // step makes them from clone_src right before the logits GEMM).
+  struct Mark { const float* rin; const float* ws; size_t stride; const float* clone_src; bool head_done; };
+  std::vector<Mark> marks;
+  void set_mark(const Mark& m) {
+    drop_mark(m.ws);
+    if (marks.size() >= 4) marks.erase(marks.begin());
+    marks.push_back(m);
+  }
+  void drop_mark(const float* ws) {
+    for (size_t i = 0; i < marks.size();)
+      if (marks[i].ws == ws) marks.erase(marks.begin() + i);
+      else ++i;
+  }
+  // the mark of this workspace if it was made for exactly these replicas; the workspace's mark is
+  // gone afterwards either way (the step rewrites the copies, and changes the weights)
+  bool take_mark(const float* rin, const float* ws, size_t stride, Mark& out) {
+    bool found = false;
+    for (const Mark& m : marks)
+      if (m.ws == ws && m.rin == rin && m.stride == stride) { out = m; found = true; }
+    drop_mark(ws);
+    return found;
+  }
   std::vector<Region> hs, sv;   // per GRU layer
   std::vector<Region> act;      // per MLP layer output
   std::vector<Region> dact;     // per MLP hidden layer: gradient w.r.t. its output
@@ -468,15 +487,16 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   ResidentScope resident;  // orders this step's resident-weight launches against other streams
   // the bf16 copies of the weights are already in this workspace (hpsgd_prepare_replicas); the
   // step changes the weights, so the mark is used once
-  const bool prepared = bf && c->prepared_rin == rin && c->prepared_ws == ws && c->prepared_stride == rstride &&
+  hpsgd_ctx::Mark mark{nullptr, nullptr, 0, nullptr, false};
+  const bool marked = c->take_mark(rin, ws, rstride, mark);
+  const bool prepared = bf && marked &&
                         k0 == 0 && groups == c->K;
-  const float* head_src = prepared ? c->prepared_head_src : nullptr;
+  const float* head_src = prepared ? mark.clone_src : nullptr;
+  const bool head_done = prepared && mark.head_done;
   // the replicas are clones of one model (hpsgd_prepare_clones): one set of bf16 weight copies, in
   // worker 0's slice of the workspace, is every worker's operand (group stride 0)
   const bool shared = head_src != nullptr;
   auto wstride = [&](const Region& r) { return shared ? 0L : 2 * (long)r.stride; };
-  c->prepared_rin = nullptr;
-  c->prepared_head_src = nullptr;
   const unsigned* abort_word = nullptr;  // set when resident-weight recurrence kernels were launched
   c->last_resident = c->last_xproj = c->last_dw = 0;
   // Weight matrices whose SGD update is applied by the epilogue of their own gradient GEMM
@@ -813,7 +833,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the copy has the memory system to itself (beside a resident-weight launch it takes 2.3
       // times as long and slows that launch by more than it takes alone; at the start of the step it
       // shares the bandwidth with the merge and the clone)
-      if (head_src) {  // the replicas are clones of one model: one copy of its head matrix serves all workers
+      if (head_done) {
+        // made with the layers' copies, before the step
+      } else if (head_src) {  // the replicas are clones of one model: one copy of its head matrix serves all workers
         HIP_TRY(launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             1, s));
       } else if (!prepared) {
@@ -1381,21 +1403,18 @@ int hpsgd_prepare_replicas(hpsgd_ctx* ctx, const float* replicas, size_t replica
     return HPSGD_EALIGN;
   const size_t span = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
   if (overlaps(workspace, ctx->ws_floats * sizeof(float), replicas, span)) return HPSGD_EALIAS;
-  ctx->prepared_rin = nullptr;
-  ctx->prepared_head_src = nullptr;
+  ctx->drop_mark((const float*)workspace);
   if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
   WeightCopies wc;
   const int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace,
                                (hipStream_t)hip_stream, true, true, wc);
   if (rc != HPSGD_OK) return rc;
-  ctx->prepared_rin = replicas;
-  ctx->prepared_ws = (const float*)workspace;
-  ctx->prepared_stride = replica_stride;
+  ctx->set_mark(hpsgd_ctx::Mark{replicas, (const float*)workspace, replica_stride, nullptr, false});
   return HPSGD_OK;
 }
 
 int hpsgd_prepare_clones(hpsgd_ctx* ctx, const float* global, const float* replicas, size_t replica_stride,
-                         void* workspace, void* hip_stream) {
+                         void* workspace, int with_head, void* hip_stream) {
   if (!ctx || !global || !replicas) return HPSGD_EINVAL;
   if (!workspace || ((uintptr_t)workspace & 255) != 0) return HPSGD_EWORKSPACE;
   if (!aligned16(global) || !aligned16(replicas) ||
@@ -1405,27 +1424,25 @@ int hpsgd_prepare_clones(hpsgd_ctx* ctx, const float* global, const float* repli
   const size_t ws_bytes = ctx->ws_floats * sizeof(float);
   if (overlaps(workspace, ws_bytes, replicas, span) || overlaps(workspace, ws_bytes, global, ctx->P * sizeof(float)))
     return HPSGD_EALIAS;
-  ctx->prepared_rin = nullptr;
+  ctx->drop_mark((const float*)workspace);
   if (ctx->d.prec != HPSGD_BF16_MFMA || ctx->d.kind == HPSGD_MLP) return HPSGD_OK;  // nothing to prepare
   WeightCopies wc;
   // one set of copies, in worker 0's slice, which the step hands to every worker (the replicas are
-  // clones: their copies would be the same bits).  The GRU layers' now; the head's are left to the
-  // step, which makes them from `global` right before the logits GEMM (made here they would share
-  // the memory system with whatever the synchronising side is doing at a round's start)
-  ctx->prepared_head_src = nullptr;
+  // clones: their copies would be the same bits).  The GRU layers' always; the head's when asked
+  // for, else they are left to the step, which makes them from `global` right before the logits
+  // GEMM (a training stream that makes them here, at a round's start, would share the memory
+  // system with whatever the synchronising side is doing then)
   // (the step decides from the replicas' addresses which copies it has; made from another address
   // the set must come out the same, else the step makes its own)
+  const bool head = with_head != 0;
   WeightCopies want;
-  int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace, nullptr, false, false, want);
-  if (rc == HPSGD_OK) rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, nullptr, false, false, wc);
+  int rc = weight_copies(ctx, replicas, (long)replica_stride, 0, ctx->K, (float*)workspace, nullptr, false, head, want);
+  if (rc == HPSGD_OK) rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, nullptr, false, head, wc);
   if (rc != HPSGD_OK) return rc;
   if (std::memcmp(&want, &wc, sizeof(WeightCopies)) != 0) return HPSGD_OK;
-  rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, (hipStream_t)hip_stream, true, false, wc);
+  rc = weight_copies(ctx, global, 0, 0, 1, (float*)workspace, (hipStream_t)hip_stream, true, head, wc);
   if (rc != HPSGD_OK) return rc;
-  ctx->prepared_head_src = global;
-  ctx->prepared_rin = replicas;
-  ctx->prepared_ws = (const float*)workspace;
-  ctx->prepared_stride = replica_stride;
+  ctx->set_mark(hpsgd_ctx::Mark{replicas, (const float*)workspace, replica_stride, global, head && wc.head});
   return HPSGD_OK;
 }
 

@@ -104,7 +104,7 @@ class Trainer:
             self.ws[gen] = self.ctx.new_workspace(self.dev)
         if self.use_prepare == "clones_b":
             # (the snapshot is the clone's source as it was at clone time; the global model moves on)
-            self.ctx.prepare_clones(self.S[gen][:self.P], self.R[gen], self.ws[gen], stream=stream)
+            self.ctx.prepare_clones(self.S[gen][:self.P], self.R[gen], self.ws[gen], stream=stream, with_head=True)
         elif self.use_prepare is True or self.use_prepare == "replicas_b":
             self.ctx.prepare_replicas(self.R[gen], self.ws[gen], stream=stream)
 

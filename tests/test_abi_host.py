@@ -228,11 +228,11 @@ def test_prepare_clones_checks_its_arguments_on_the_host():
     ctx = hb.Context(wl.CONFIGS["tiny_gru"])   # fp32: nothing to prepare, but the arguments are checked
     a = lambda i: C.c_void_p(0x100000 + 0x10000 * i)
     ws = C.c_void_p(0x4000000)
-    assert lib.hpsgd_prepare_clones(None, a(0), a(1), C.c_size_t(ctx.stride), ws, None) == 1
-    assert lib.hpsgd_prepare_clones(ctx._h, None, a(1), C.c_size_t(ctx.stride), ws, None) == 1
-    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), None, None) == 5
-    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), C.c_void_p(0x4000010), None) == 5
-    assert lib.hpsgd_prepare_clones(ctx._h, C.c_void_p(0x100004), a(1), C.c_size_t(ctx.stride), ws, None) == 3
-    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.P - 1), ws, None) == 3   # stride < P
-    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), a(1), None) == 4  # workspace on the replicas
-    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), ws, None) == 0
+    assert lib.hpsgd_prepare_clones(None, a(0), a(1), C.c_size_t(ctx.stride), ws, 0, None) == 1
+    assert lib.hpsgd_prepare_clones(ctx._h, None, a(1), C.c_size_t(ctx.stride), ws, 0, None) == 1
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), None, 0, None) == 5
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), C.c_void_p(0x4000010), 0, None) == 5
+    assert lib.hpsgd_prepare_clones(ctx._h, C.c_void_p(0x100004), a(1), C.c_size_t(ctx.stride), ws, 0, None) == 3
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.P - 1), ws, 0, None) == 3   # stride < P
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), a(1), 0, None) == 4  # workspace on the replicas
+    assert lib.hpsgd_prepare_clones(ctx._h, a(0), a(1), C.c_size_t(ctx.stride), ws, 0, None) == 0

@@ -779,6 +779,38 @@ def test_prepare_clones_mark_is_used_once_and_only_for_its_buffers():
     assert torch.equal(got[:, :tr.P], ref[:, :tr.P]) and torch.equal(l_got[0], l_ref[0])
 
 
+def test_a_mark_per_workspace_survives_steps_on_other_workspaces():
+    """Two generations of buffers: the copies of generation 1 are prepared (head included) while
+    generation 0 steps on its own workspace; generation 1's step then still finds its mark - it
+    launches fewer copy kernels than an unprepared step - and leaves the bits of an unprepared one."""
+    cfg = BF16["lm_nt_bf16_tiles"]
+    init, shards, orders, _ = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    tr.sync_all(0)
+    tr.sync_all(1)
+    tr.gather(0)
+    torch.cuda.synchronize()
+    lr = cfg["lr"]
+    ws0, ws1 = tr.ctx.new_workspace(DEV), tr.ctx.new_workspace(DEV)
+    loss = torch.zeros(cfg["K"], device=DEV)
+    cvt = tr.ctx.kernel_names().index("cvt2_kernel")
+    ref = tr.R[1].clone()
+    tr.ctx.kernel_timer_enable([cvt])
+    tr.ctx.local_step_all(ref, ref, tr.xb, tr.yb, lr, loss, ws0)     # unprepared, for the count and the bits
+    torch.cuda.synchronize()
+    n_plain = tr.ctx.kernel_timer_read(cvt)[0]
+    tr.ctx.prepare_clones(tr.S[1][:tr.P], tr.R[1], ws1, with_head=True)
+    tr.ctx.local_step_all(tr.R[0], tr.R[0], tr.xb, tr.yb, lr, loss, ws0)   # generation 0, its own workspace
+    torch.cuda.synchronize()
+    tr.ctx.kernel_timer_read(cvt)
+    tr.ctx.local_step_all(tr.R[1], tr.R[1], tr.xb, tr.yb, lr, loss, ws1)
+    torch.cuda.synchronize()
+    n_marked = tr.ctx.kernel_timer_read(cvt)[0]
+    tr.ctx.kernel_timer_enable([])
+    assert 0 < n_marked < n_plain, (n_marked, n_plain)
+    assert torch.equal(tr.R[1][:, :tr.P], ref[:, :tr.P])
+
+
 @pytest.mark.parametrize("name", ["tiny_gru", "mlp_tiles", "lm_nt_bf16_tiles", "gru_cls_tiles"])
 def test_overlapped_rounds_replayed_from_a_hip_graph(name):
     """Trainer.ovl_capture / ovl_replay: one graph holds a whole period of overlapped rounds (three
