@@ -164,19 +164,21 @@ softmax_ce_bf16_kernel(const float* __restrict__ logits, long s_logits, const in
 // rows per column (a thread owns the same columns in every row): colpart[g][block][c], the
 // partial sums of the head's bias gradient, added up by a second small kernel.  The next row's
 // loads are issued before the current row is reduced.
-constexpr int SMR = 8;
+constexpr int SMR = 8;  // the fewest rows per workgroup
 
-template <int V4>
-__global__ void __launch_bounds__(256)
+template <int V4, int NT>
+__global__ void __launch_bounds__(NT)
 softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, const int32_t* __restrict__ y,
                             long s_y, __bf16* __restrict__ dlog, long ld_d, long s_d,
                             float* __restrict__ rowloss, long s_rowloss, float2* __restrict__ rowstat,
-                            long s_rowstat, float* __restrict__ colpart, long s_colpart, int N, int C) {
-  // partial results of the four waves, one set per reduction and row parity: a set is written
+                            long s_rowstat, float* __restrict__ colpart, long s_colpart, int N, int C, int rpb) {
+  // partial results of the NW waves, one set per reduction and row parity: a set is written
   // again two rows later, with two barriers in between, so one barrier per reduction is enough
-  __shared__ float red_m[2][4], red_s[2][4];
-  const int g = blockIdx.y, row0 = blockIdx.x * SMR;
-  const int nr = min(SMR, N - row0);
+  constexpr int NW = NT / 64;
+  static_assert(NW == 4 || NW == 8, "four or eight waves");
+  __shared__ float red_m[2][NW], red_s[2][NW];
+  const int g = blockIdx.y, row0 = blockIdx.x * rpb;
+  const int nr = min(rpb, N - row0);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const float inv_n = 1.0f / (float)N;
   float4 acc[V4], nx[V4];
@@ -186,8 +188,10 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
     const float* lr = logits + g * s_logits + (long)row * C;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-      const int c = 4 * (tid + 256 * i);
-      nx[i] = *reinterpret_cast<const float4*>(lr + (c < C ? c : 0));
+      const int c = 4 * (tid + NT * i);
+      typedef float f4nt __attribute__((ext_vector_type(4)));
+      const f4nt t4 = __builtin_nontemporal_load(reinterpret_cast<const f4nt*>(lr + (c < C ? c : 0)));
+      nx[i] = make_float4(t4.x, t4.y, t4.z, t4.w);
     }
   };
   load_row(row0);
@@ -199,7 +203,7 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
       v[i] = nx[i];
-      if (4 * (tid + 256 * i) < C) m = fmaxf(fmaxf(m, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+      if (4 * (tid + NT * i) < C) m = fmaxf(fmaxf(m, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
     }
     if (r + 1 < nr) load_row(row + 1);
 #pragma unroll
@@ -207,10 +211,12 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
     if (lane == 0) red_m[r & 1][wave] = m;
     __syncthreads();
     m = fmaxf(fmaxf(red_m[r & 1][0], red_m[r & 1][1]), fmaxf(red_m[r & 1][2], red_m[r & 1][3]));
+    if (NW == 8)
+      m = fmaxf(m, fmaxf(fmaxf(red_m[r & 1][NW - 4], red_m[r & 1][NW - 3]), fmaxf(red_m[r & 1][NW - 2], red_m[r & 1][NW - 1])));
     float sum = 0.f;
 #pragma unroll
     for (int i = 0; i < V4; ++i)
-      if (4 * (tid + 256 * i) < C) {
+      if (4 * (tid + NT * i) < C) {
         v[i].x = expf(v[i].x - m); v[i].y = expf(v[i].y - m);
         v[i].z = expf(v[i].z - m); v[i].w = expf(v[i].w - m);
         sum += (v[i].x + v[i].y) + (v[i].z + v[i].w);
@@ -220,6 +226,8 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
     if (lane == 0) red_s[r & 1][wave] = sum;
     __syncthreads();
     sum = (red_s[r & 1][0] + red_s[r & 1][1]) + (red_s[r & 1][2] + red_s[r & 1][3]);
+    if (NW == 8)
+      sum += (red_s[r & 1][NW - 4] + red_s[r & 1][NW - 3]) + (red_s[r & 1][NW - 2] + red_s[r & 1][NW - 1]);
     const float inv_sum = 1.0f / sum;
     if (tid == 0) {
       rowloss[g * s_rowloss + row] = -((logits[g * s_logits + (long)row * C + label] - m) - logf(sum));
@@ -228,7 +236,7 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
     __bf16* dr = dlog + g * s_d + (long)row * ld_d;
 #pragma unroll
     for (int i = 0; i < V4; ++i) {
-      const int c = 4 * (tid + 256 * i);
+      const int c = 4 * (tid + NT * i);
       if (c < C) {
         const float4 d4 = make_float4((v[i].x * inv_sum - (c + 0 == label ? 1.0f : 0.0f)) * inv_n,
                                       (v[i].y * inv_sum - (c + 1 == label ? 1.0f : 0.0f)) * inv_n,
@@ -237,19 +245,49 @@ softmax_ce_bf16_rows_kernel(const float* __restrict__ logits, long s_logits, con
         acc[i].x += d4.x; acc[i].y += d4.y; acc[i].z += d4.z; acc[i].w += d4.w;
         bf16x4 o;
         o[0] = (__bf16)d4.x; o[1] = (__bf16)d4.y; o[2] = (__bf16)d4.z; o[3] = (__bf16)d4.w;
-        *reinterpret_cast<bf16x4*>(dr + c) = o;
+        __builtin_nontemporal_store(o, reinterpret_cast<bf16x4*>(dr + c));
       }
     }
   }
   float* cp = colpart + g * s_colpart + (long)blockIdx.x * C;
 #pragma unroll
   for (int i = 0; i < V4; ++i) {
-    const int c = 4 * (tid + 256 * i);
+    const int c = 4 * (tid + NT * i);
     if (c < C) *reinterpret_cast<float4*>(cp + c) = acc[i];
   }
 }
 
-int softmax_ce_bf16_row_blocks(int N) { return (N + SMR - 1) / SMR; }
+// Rows per workgroup.  The kernel holds three workgroups of four waves per CU (168 registers; two of
+// eight waves for long rows), and a launch
+// whose workgroups outnumber those places leaves the chip half empty at its end: 1120 x 8 rows in
+// blocks of 8 are 1120 workgroups for 768 places, i.e. 16 rows' time where blocks of 12 take 12.
+// So: as many rows per workgroup as fill every place once, at least SMR, at most 64.
+// sizing_groups: the number of workers the launch is sized for (0: the upper bound on the number
+// of blocks, for allocations).
+static bool softmax_rows_wide(int C) { return C > 4096; }  // eight waves, five vectors per thread
+
+int softmax_ce_bf16_rows_per_block(int N, int sizing_groups, int C) {
+  if (sizing_groups <= 0) return SMR;
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      return SMR;
+  }
+  const int places = (softmax_rows_wide(C) ? 2 : 3) * cus;
+  const long rows = (long)N * sizing_groups;
+  long rpb = (rows + places - 1) / places;
+  if (rpb < SMR) rpb = SMR;
+  if (rpb > 64) rpb = 64;
+  return (int)rpb;
+}
+int softmax_ce_bf16_row_blocks(int N, int sizing_groups, int C) {
+  const int rpb = softmax_ce_bf16_rows_per_block(N, sizing_groups, C);
+  return (N + rpb - 1) / rpb;
+}
 
 bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* dlog, long ld_d, long s_d,
                                int C) {
@@ -262,20 +300,21 @@ bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* d
 hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
                                   long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
                                   long s_rowstat, int N, int C, int groups, hipStream_t s, float* colpart,
-                                  long s_colpart) {
+                                  long s_colpart, int sizing_groups) {
   if (!softmax_ce_bf16_supported(logits, s_logits, dlog, ld_d, s_d, C)) return hipErrorInvalidValue;
   // bytes: the logits read once (fp32), the logit gradient written in bf16
   KernelTimer kt(KID_SOFTMAX_CE_BF16, 6.0 * N * C * groups, s);
   if (colpart) {
     if (((uintptr_t)colpart & 15) != 0 || s_colpart % 4 != 0) return hipErrorInvalidValue;
-    dim3 grid(softmax_ce_bf16_row_blocks(N), groups);
-#define HPSGD_SMR(V4)                                                                                        \
-  hipLaunchKernelGGL(softmax_ce_bf16_rows_kernel<V4>, grid, dim3(256), 0, s, logits, s_logits, y, s_y,       \
+    const int rpb = softmax_ce_bf16_rows_per_block(N, sizing_groups, C);
+    dim3 grid((N + rpb - 1) / rpb, groups);
+#define HPSGD_SMR(V4, NT)                                                                                      \
+  hipLaunchKernelGGL((softmax_ce_bf16_rows_kernel<V4, NT>), grid, dim3(NT), 0, s, logits, s_logits, y, s_y,  \
                      (__bf16*)dlog, ld_d, s_d, rowloss, s_rowloss, reinterpret_cast<float2*>(rowstat),       \
-                     s_rowstat / 2, colpart, s_colpart, N, C)
-    if (C <= 1024) HPSGD_SMR(1);
-    else if (C <= 4096) HPSGD_SMR(4);
-    else HPSGD_SMR(10);
+                     s_rowstat / 2, colpart, s_colpart, N, C, rpb)
+    if (C <= 1024) HPSGD_SMR(1, 256);
+    else if (!softmax_rows_wide(C)) HPSGD_SMR(4, 256);
+    else HPSGD_SMR(5, 512);
 #undef HPSGD_SMR
     return hipGetLastError();
   }

@@ -852,12 +852,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the head's bias gradient: column sums of the unrounded logit gradient, per block of rows
       // in the loss kernel, added up below (else recomputed from the logits in a pass of its own)
       // (the partial sums of the groups lie back to back, as the adding kernel reads them)
-      const long s_colpart = (long)softmax_ce_bf16_row_blocks(nrows) * classes;
+      // (sized for all K workers also when fewer are stepped: the sums then do not depend on the entry point)
+      const int n_colparts = softmax_ce_bf16_row_blocks(nrows, c->K, classes);
+      const long s_colpart = (long)n_colparts * classes;
       const bool colsum_fused = (((uintptr_t)(grad + ob) | (uintptr_t)reg(c->colpart)) & 15) == 0 && sG % 4 == 0 &&
                                 s_colpart % 4 == 0 && (size_t)s_colpart <= c->colpart.stride;
       HIP_TRY(launch_softmax_ce_bf16(logits, s_log, y, nrows, bfreg(c->dlogb), clp, s_dlb, rowloss,
                                      (long)c->rowloss.stride, reg(c->rowstat), (long)c->rowstat.stride, nrows,
-                                     classes, groups, s, colsum_fused ? reg(c->colpart) : nullptr, s_colpart));
+                                     classes, groups, s, colsum_fused ? reg(c->colpart) : nullptr, s_colpart, c->K));
       if (loss_out)
         HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
       role = HPSGD_ROLE_OTHER;
@@ -891,7 +893,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         c->timer_nested = nested;
       }
       if (colsum_fused)
-        HIP_TRY(launch_reduce_parts(reg(c->colpart), softmax_ce_bf16_row_blocks(nrows), (size_t)classes, nullptr, 0,
+        HIP_TRY(launch_reduce_parts(reg(c->colpart), n_colparts, (size_t)classes, nullptr, 0,
                                     grad + ob, (size_t)sG, 0.f, 0, groups, s));
       else
         HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,

@@ -263,8 +263,11 @@ bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* d
 hipError_t launch_softmax_ce_bf16(const float* logits, long s_logits, const int32_t* y, long s_y, void* dlog,
                                   long ld_d, long s_d, float* rowloss, long s_rowloss, float* rowstat,
                                   long s_rowstat, int N, int C, int groups, hipStream_t s, float* colpart = nullptr,
-                                  long s_colpart = 0);
-int softmax_ce_bf16_row_blocks(int N);
+                                  long s_colpart = 0, int sizing_groups = 0);
+// colpart holds one partial sum per block of rows: softmax_ce_bf16_row_blocks(N, sizing_groups)
+// blocks per group, where sizing_groups is the number of workers the launch is sized for (the
+// same value must go to the launch); 0 gives the upper bound, for allocations
+int softmax_ce_bf16_row_blocks(int N, int sizing_groups = 0, int C = 0);
 // out[c] = mean over rows of (softmax - onehot), from the logits and the rows' rowstat pairs
 hipError_t launch_colsum_softmax(const float* logits, long s_logits, const float* rowstat, long s_rowstat,
                                  const int32_t* y, long s_y, float* out, long s_out, int N, int C, int groups,
