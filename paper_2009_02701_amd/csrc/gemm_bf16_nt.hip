@@ -418,6 +418,19 @@ __device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_
   return true;
 }
 
+// The epilogue's traffic is used once (the matrix to update is read once, the result is read by a
+// later kernel at the earliest): non-temporal, so that it does not push the operand panels, which
+// other tiles of the XCD are still reading, out of the L2.
+typedef float f4nt_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float* p) {
+  const f4nt_t v = __builtin_nontemporal_load(reinterpret_cast<const f4nt_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float* p, float4 v) {
+  const f4nt_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<f4nt_t*>(p));
+}
+
 template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 gemm_bf16_dlx_kernel(GemmNtDesc d) {
@@ -567,7 +580,7 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
 #pragma unroll
         for (int p = 0; p < PASSES; ++p) {
           const int row = min(mh + rbase + RPP * p, d.M - 1);  // clamped: not stored when outside
-          w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
+          w[COMMIT ? p : 0] = nt_load4(W + (long)row * d.ldc + col);
         }
       }
 #pragma unroll
@@ -582,7 +595,7 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
         } else {
           o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
         }
-        *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+        nt_store4(C + (long)row * d.ldc + col, o);
       }
     } else if (col < d.N) {
       const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
