@@ -101,6 +101,19 @@ __device__ __forceinline__ bool nt_tile(const GemmNtDesc& d, int& g, int& tile_m
 }
 
 // Epilogue of both NT kernels: accumulators -> LDS tile -> coalesced 16-byte stores.
+// The epilogue's traffic is used once (the matrix to update is read once, the result is read by a
+// later kernel at the earliest): non-temporal, so that it does not push the operand panels, which
+// other tiles of the XCD are still reading, out of the L2.
+typedef float f4nt_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 nt_load4(const float* p) {
+  const f4nt_t v = __builtin_nontemporal_load(reinterpret_cast<const f4nt_t*>(p));
+  return make_float4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void nt_store4(float* p, float4 v) {
+  const f4nt_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<f4nt_t*>(p));
+}
+
 template <bool COMMIT>
 __device__ __forceinline__ void nt_epilogue(const GemmNtDesc& d, floatx16 (&acc)[2][2], unsigned char* nt_smem,
                                             int g, int m0, int n0) {
@@ -136,7 +149,7 @@ __device__ __forceinline__ void nt_epilogue(const GemmNtDesc& d, floatx16 (&acc)
 #pragma unroll
       for (int p = 0; p < 16; ++p) {
         const int row = min(m0 + rbase + 8 * p, d.M - 1);  // clamped: not stored when outside
-        w[COMMIT ? p : 0] = *reinterpret_cast<const float4*>(W + (long)row * d.ldc + col);
+        w[COMMIT ? p : 0] = nt_load4(W + (long)row * d.ldc + col);
       }
     }
 #pragma unroll
@@ -151,7 +164,7 @@ __device__ __forceinline__ void nt_epilogue(const GemmNtDesc& d, floatx16 (&acc)
       } else {
         o = make_float4(a.x + bv.x, a.y + bv.y, a.z + bv.z, a.w + bv.w);
       }
-      *reinterpret_cast<float4*>(C + (long)row * d.ldc + col) = o;
+      nt_store4(C + (long)row * d.ldc + col, o);
     }
   } else {
     const float* W = COMMIT ? d.win + (long)g * d.strideWin : nullptr;
@@ -416,19 +429,6 @@ __device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_
     tile_n = r - tile_m * tn;
   }
   return true;
-}
-
-// The epilogue's traffic is used once (the matrix to update is read once, the result is read by a
-// later kernel at the earliest): non-temporal, so that it does not push the operand panels, which
-// other tiles of the XCD are still reading, out of the L2.
-typedef float f4nt_t __attribute__((ext_vector_type(4)));
-__device__ __forceinline__ float4 nt_load4(const float* p) {
-  const f4nt_t v = __builtin_nontemporal_load(reinterpret_cast<const f4nt_t*>(p));
-  return make_float4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void nt_store4(float* p, float4 v) {
-  const f4nt_t t = {v.x, v.y, v.z, v.w};
-  __builtin_nontemporal_store(t, reinterpret_cast<f4nt_t*>(p));
 }
 
 template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>

@@ -695,6 +695,25 @@ __device__ __forceinline__ long xfrag(int row, int nch, int c, int u) {
   return ((long)(row >> 4) * nch + c) * 512 + (((u >> 3) << 4) + (row & 15)) * 8 + (u & 7);
 }
 
+// What a launch reads once (input projections, saved gates, the gradient from above) or leaves for
+// later launches (saved gates, h, the copies for the GEMMs) goes past the L2 with the non-temporal
+// hint: the L2 is where the exchanged operand lives between its stores and its loads.
+typedef float f2nt_t __attribute__((ext_vector_type(2)));
+typedef unsigned u4nt_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float2 ld2_nt(const float* p) {
+  const f2nt_t v = __builtin_nontemporal_load(reinterpret_cast<const f2nt_t*>(p));
+  return make_float2(v.x, v.y);
+}
+__device__ __forceinline__ void st2_nt(float* p, float2 v) {
+  const f2nt_t t = {v.x, v.y};
+  __builtin_nontemporal_store(t, reinterpret_cast<f2nt_t*>(p));
+}
+__device__ __forceinline__ void st_u32_nt(void* p, unsigned v) { __builtin_nontemporal_store(v, reinterpret_cast<unsigned*>(p)); }
+__device__ __forceinline__ void st16_nt(void* p, uint4 v) {
+  const u4nt_t t = {v.x, v.y, v.z, v.w};
+  __builtin_nontemporal_store(t, reinterpret_cast<u4nt_t*>(p));
+}
+
 // Forward.  Wb: bf16 W_hh [3H][H]; hx: bf16 h_0 .. h_T fragment-major (blocks of 16 ceil(B/16) x H,
 // h_0 given), the exchanged operand; hb: the same row-major (blocks of B x H; written, not read);
 // hs: the same in fp32; hT (nullable): bf16 transposed copy [H][ld_hT], column (t+1)*B + row.
@@ -758,7 +777,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
     const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H + j;
     float2 gxv[3];
 #pragma unroll
-    for (int q = 0; q < 3; ++q) gxv[q] = *reinterpret_cast<const float2*>(gxr + q * H);
+    for (int q = 0; q < 3; ++q) gxv[q] = ld2_nt(gxr + q * H);
     if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hxg + (long)t * xblk, 0, 0x7fffffff, 0x00020000);
     bf16x8 a[NCF][2];
@@ -805,15 +824,15 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
     const float2 hn = make_float2((1.0f - z0v) * n0v + z0v * hpv.x, (1.0f - z1v) * n1v + z1v * hpv.y);
     if (row < B) {
       const long e = ((long)(t + 1) * B + row) * H + j;
-      *reinterpret_cast<float2*>(hsg + e) = hn;
       const unsigned hp2 = pack_bf16(hn.x, hn.y);
       st_dev_u32(hxg + (long)(t + 1) * xblk + xfrag(row, nch, tx, u0), hp2, l2x);
-      *reinterpret_cast<unsigned*>(hbg + e) = hp2;
+      st2_nt(hsg + e, hn);
+      st_u32_nt(hbg + e, hp2);
       float* svr = sv + g * s_sv + ((long)t * B + row) * 4 * H + j;
-      *reinterpret_cast<float2*>(svr) = make_float2(r0v, r1v);
-      *reinterpret_cast<float2*>(svr + H) = make_float2(z0v, z1v);
-      *reinterpret_cast<float2*>(svr + 2 * H) = make_float2(n0v, n1v);
-      *reinterpret_cast<float2*>(svr + 3 * H) = gh[2];
+      st2_nt(svr, make_float2(r0v, r1v));
+      st2_nt(svr + H, make_float2(z0v, z1v));
+      st2_nt(svr + 2 * H, make_float2(n0v, n1v));
+      st2_nt(svr + 3 * H, gh[2]);
     }
     if (hT) {
       tt[u0 * TP + rl] = (__bf16)hn.x;
@@ -825,8 +844,8 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
       // 64-byte row segments of the transposed copy, 16 bytes per thread
       const int u = tid >> 2, part = tid & 3;
       if (r0 + 8 * part < B)  // B is a multiple of 8: a piece of 8 rows is all in or all out
-        *reinterpret_cast<uint4*>(hT + g * s_hT + (long)(j0 + u) * ld_hT + (long)(t + 1) * B + r0 + 8 * part) =
-            *reinterpret_cast<const uint4*>(tt + u * TP + 8 * part);
+        st16_nt(hT + g * s_hT + (long)(j0 + u) * ld_hT + (long)(t + 1) * B + r0 + 8 * part,
+                *reinterpret_cast<const uint4*>(tt + u * TP + 8 * part));
     }
   }
 }
@@ -899,10 +918,10 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
   for (int t = T - 1; t >= 0; --t, ++it) {
     const long e = ((long)t * B + rowc) * H + j;
     const float* svr = sv + g * s_sv + ((long)t * B + rowc) * 4 * H + j;
-    const float2 r = *reinterpret_cast<const float2*>(svr), z = *reinterpret_cast<const float2*>(svr + H);
-    const float2 n = *reinterpret_cast<const float2*>(svr + 2 * H), q = *reinterpret_cast<const float2*>(svr + 3 * H);
-    const float2 hp = *reinterpret_cast<const float2*>(hs + g * s_hs + e);
-    const float2 ab = above ? *reinterpret_cast<const float2*>(above + g * s_above + e) : make_float2(0.f, 0.f);
+    const float2 r = ld2_nt(svr), z = ld2_nt(svr + H);
+    const float2 n = ld2_nt(svr + 2 * H), q = ld2_nt(svr + 3 * H);
+    const float2 hp = ld2_nt(hs + g * s_hs + e);
+    const float2 ab = above ? ld2_nt(above + g * s_above + e) : make_float2(0.f, 0.f);
     if (it > 0 && !group_wait(flags, NJ, base + (unsigned)it, abort_w, spin_limit, lds_flag)) return;
     floatx4 acc[2][2];
 #pragma unroll
@@ -962,9 +981,9 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
       st_dev_u32(dghg + ox3 + (long)(H / PC) * 512, pz, l2x);
       st_dev_u32(dghg + ox3 + (long)(2 * H / PC) * 512, pack_bf16(dq.x, dq.y), l2x);
       __bf16* ox = dgxb + g * s_dgb + o;
-      *reinterpret_cast<unsigned*>(ox) = pr;
-      *reinterpret_cast<unsigned*>(ox + H) = pz;
-      *reinterpret_cast<unsigned*>(ox + 2 * H) = pack_bf16(da_n.x, da_n.y);
+      st_u32_nt(ox, pr);
+      st_u32_nt(ox + H, pz);
+      st_u32_nt(ox + 2 * H, pack_bf16(da_n.x, da_n.y));
       bsum[0].x += da_r.x; bsum[0].y += da_r.y;
       bsum[1].x += da_z.x; bsum[1].y += da_z.y;
       bsum[2].x += da_n.x; bsum[2].y += da_n.y;
@@ -989,8 +1008,8 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
         const uint4 v = *reinterpret_cast<const uint4*>(tt + (blk * QJ + u) * TP + 8 * part);
         const int gate = blk == 3 ? 2 : blk;
         const long o = g * s_T + (long)(gate * H + j0 + u) * ld_T + (long)t * B + r0 + 8 * part;
-        if (blk != 3) *reinterpret_cast<uint4*>(dgxT + o) = v;
-        if (blk != 2) *reinterpret_cast<uint4*>(dghT + o) = v;
+        if (blk != 3) st16_nt(dgxT + o, v);
+        if (blk != 2) st16_nt(dghT + o, v);
       }
     }
   }
