@@ -8,14 +8,17 @@ namespace hpsgd {
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
+// (the copy kernels read their input once and write what later launches read: non-temporal)
+typedef float f4nt_a __attribute__((ext_vector_type(4)));
+typedef unsigned u4nt_a __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ bf16x4 load4_as_bf16(const float* p) {
-  const float4 v = *reinterpret_cast<const float4*>(p);
+  const f4nt_a v = __builtin_nontemporal_load(reinterpret_cast<const f4nt_a*>(p));
   bf16x4 r;
   r[0] = (__bf16)v.x; r[1] = (__bf16)v.y; r[2] = (__bf16)v.z; r[3] = (__bf16)v.w;
   return r;
 }
 __device__ __forceinline__ bf16x4 load4_as_bf16(const __bf16* p) {
-  return *reinterpret_cast<const bf16x4*>(p);
+  return __builtin_nontemporal_load(reinterpret_cast<const bf16x4*>(p));
 }
 
 // in: R x C (fp32 or bf16, row pitch ld_in).  out_p (nullable): the bf16 rounding, row pitch
@@ -43,7 +46,7 @@ cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restric
   for (int i = 0; i < 4; ++i) {
     const int rl = ty + 16 * i, r = r0 + rl;
     if (r < R && c_ok) {
-      if (out_p) *reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c) = v[i];
+      if (out_p) __builtin_nontemporal_store(v[i], reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c));
     } else {
       v[i][0] = v[i][1] = v[i][2] = v[i][3] = (__bf16)0.f;
     }
@@ -59,8 +62,8 @@ cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restric
     const int idx = threadIdx.x + 256 * q, col = idx >> 3, part = idx & 7;
     const int c = c0 + col, r = r0 + 8 * part;
     if (c < C && r < R)
-      *reinterpret_cast<uint4*>(out_t + g * s_t + (long)c * ld_t + r) =
-          *reinterpret_cast<const uint4*>(&tile[col][8 * part]);
+      __builtin_nontemporal_store(*reinterpret_cast<const u4nt_a*>(&tile[col][8 * part]),
+                                  reinterpret_cast<u4nt_a*>(out_t + g * s_t + (long)c * ld_t + r));
   }
 }
 
