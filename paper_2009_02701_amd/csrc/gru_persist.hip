@@ -773,11 +773,19 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
   int aoff[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) aoff[rb] = (((r0 + rb * 16 < B ? r0 + rb * 16 : r0) >> 4) * nch) * 1024 + lane * 16;
+  // The step's input projection is loaded one step ahead, behind the operand loads of the step
+  // before: requested in front of the wait, it would sit between the polling wave and its view
+  // of the flags (a wave's loads return in order, and these come from memory, not from the L2).
+  float2 gxn[3];
+  {
+    const float* gxr = gx + g * s_gx + (long)rowc * 3 * H + j;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxn[q] = ld2_nt(gxr + q * H);
+  }
   for (int t = 0; t < T; ++t) {
-    const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H + j;
     float2 gxv[3];
 #pragma unroll
-    for (int q = 0; q < 3; ++q) gxv[q] = ld2_nt(gxr + q * H);
+    for (int q = 0; q < 3; ++q) gxv[q] = gxn[q];
     if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(hxg + (long)t * xblk, 0, 0x7fffffff, 0x00020000);
     bf16x8 a[NCF][2];
@@ -787,6 +795,12 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
       const int co = (c < nch ? c : 0) * 1024;
 #pragma unroll
       for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    {
+      const float* gxr = gx + g * s_gx + ((long)min(t + 1, T - 1) * B + rowc) * 3 * H + j;
+#pragma unroll
+      for (int q = 0; q < 3; ++q) gxn[q] = ld2_nt(gxr + q * H);
     }
     floatx4 acc[2][6];
 #pragma unroll
@@ -914,14 +928,22 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
   int aoff[2];
 #pragma unroll
   for (int rb = 0; rb < 2; ++rb) aoff[rb] = (((r0 + rb * 16 < B ? r0 + rb * 16 : r0) >> 4) * nch) * 1024 + lane * 16;
+  // The step's saved gates, h and the gradient from above are loaded one step ahead, behind the
+  // operand loads of the step before (see the forward kernel: in front of the wait they would
+  // delay the polling wave's view of the flags by a trip to memory).
+  float2 nr, nz, nn, nq, nhp, nab;
+  auto prefetch = [&](int tn) {
+    const long e = ((long)tn * B + rowc) * H + j;
+    const float* svr = sv + g * s_sv + ((long)tn * B + rowc) * 4 * H + j;
+    nr = ld2_nt(svr), nz = ld2_nt(svr + H);
+    nn = ld2_nt(svr + 2 * H), nq = ld2_nt(svr + 3 * H);
+    nhp = ld2_nt(hs + g * s_hs + e);
+    nab = above ? ld2_nt(above + g * s_above + e) : make_float2(0.f, 0.f);
+  };
+  prefetch(T - 1);
   int it = 0;
   for (int t = T - 1; t >= 0; --t, ++it) {
-    const long e = ((long)t * B + rowc) * H + j;
-    const float* svr = sv + g * s_sv + ((long)t * B + rowc) * 4 * H + j;
-    const float2 r = ld2_nt(svr), z = ld2_nt(svr + H);
-    const float2 n = ld2_nt(svr + 2 * H), q = ld2_nt(svr + 3 * H);
-    const float2 hp = ld2_nt(hs + g * s_hs + e);
-    const float2 ab = above ? ld2_nt(above + g * s_above + e) : make_float2(0.f, 0.f);
+    const float2 r = nr, z = nz, n = nn, q = nq, hp = nhp, ab = nab;
     if (it > 0 && !group_wait(flags, NJ, base + (unsigned)it, abort_w, spin_limit, lds_flag)) return;
     floatx4 acc[2][2];
 #pragma unroll
@@ -939,6 +961,8 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
 #pragma unroll
         for (int rb = 0; rb < 2; ++rb) a[i][rb] = ld_frag_dev(rs, aoff[rb] + co);
       }
+      __builtin_amdgcn_sched_barrier(0);
+      prefetch(max(t - 1, 0));
       __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
 #pragma unroll
       for (int i = 0; i < NCB; ++i) {
@@ -953,6 +977,8 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
           for (int cb = 0; cb < 2; ++cb)
             acc[rb][cb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[i][rb], w2[cb], acc[rb][cb], 0, 0, 0);
       }
+    } else {
+      prefetch(max(t - 1, 0));
     }
 #pragma unroll
     for (int rb = 0; rb < 2; ++rb)
