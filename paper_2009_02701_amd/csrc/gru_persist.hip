@@ -854,9 +854,10 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
     }
     hpv = hn;
     group_signal(flags + tx, base + (unsigned)t + 1u, l2x);  // (its barrier also separates the reads of red from the next step's writes)
-    if (hT && tid < 128) {
-      // 64-byte row segments of the transposed copy, 16 bytes per thread
-      const int u = tid >> 2, part = tid & 3;
+    if (hT && tid >= PNT - 128) {
+      // 64-byte row segments of the transposed copy, 16 bytes per thread (the last two waves: the
+      // first one polls the flags next, and would see them only behind its own stores)
+      const int u = (tid - (PNT - 128)) >> 2, part = tid & 3;
       if (r0 + 8 * part < B)  // B is a multiple of 8: a piece of 8 rows is all in or all out
         st16_nt(hT + g * s_hT + (long)(j0 + u) * ld_hT + (long)(t + 1) * B + r0 + 8 * part,
                 *reinterpret_cast<const uint4*>(tt + u * TP + 8 * part));
@@ -1026,10 +1027,11 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
     tt[(3 * QJ + u0 + 1) * TP + rl] = (__bf16)dq.y;
     dcar = make_float2(dh.x * z.x, dh.y * z.y);
     group_signal(flags + tx, base + (unsigned)it + 1u, l2x);
-    {
-      // transposed copies [gate unit][t*B + row] as 64-byte row segments, 16 bytes per thread:
-      // dgx^T = (da_r, da_z, da_n), dgh^T = (da_r, da_z, dq)
-      const int blk = tid >> 7, u = (tid >> 2) & 31, part = tid & 3;
+    // transposed copies [gate unit][t*B + row] as 64-byte row segments, 16 bytes per piece:
+    // dgx^T = (da_r, da_z, da_n), dgh^T = (da_r, da_z, dq).  512 pieces, by the waves 1 .. 7: wave
+    // 0 polls the flags next, and would see them only behind its own stores
+    for (int idx = tid - 64; idx >= 0 && idx < PNT; idx += PNT - 64) {
+      const int blk = idx >> 7, u = (idx >> 2) & 31, part = idx & 3;
       if (r0 + 8 * part < B) {  // B is a multiple of 8
         const uint4 v = *reinterpret_cast<const uint4*>(tt + (blk * QJ + u) * TP + 8 * part);
         const int gate = blk == 3 ? 2 : blk;
