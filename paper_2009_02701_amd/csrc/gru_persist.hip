@@ -305,17 +305,25 @@ __device__ __forceinline__ void resident_contraction(const float* wres, int wp, 
 }
 
 // ... with the activations in a fragment-major block
-template <int NQ, int NB>
+// behind(): called once, behind the first trip's loads - where a step requests what it needs one
+// step later from memory (requested in front of the flag wait, such loads would sit between the
+// polling wave and its view of the flags: a wave's loads return in order).
+template <int NQ, int NB, typename Behind>
 __device__ __forceinline__ void resident_contraction_x(const float* wres, int wp, __amdgpu_buffer_rsrc_t rs, int KD,
-                                                       int rbx, floatx4 (&acc)[2][NQ]) {
+                                                       int rbx, floatx4 (&acc)[2][NQ], Behind behind) {
   const int kw = (threadIdx.x >> 6) & 3;
   const int nch = (KD + PC - 1) / PC;
+  bool first = true;
   for (int c0 = kw; c0 < nch; c0 += 4 * NB) {
     float4 a[NB][2];
     fragment_loads_x<NB>(rs, KD, rbx, c0, a);
+    __builtin_amdgcn_sched_barrier(0);
+    if (first) behind();
+    first = false;
     __builtin_amdgcn_sched_barrier(0);  // every load is issued before anything waits for one
     fragment_mfmas<NQ, NB>(wres, wp, KD, c0, a, acc);
   }
+  if (first) behind();
 }
 
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t tile_rsrc(const float* base) {
@@ -383,12 +391,19 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
   const long xblk = xblock_words(B, H);
   const int rbx = (r0 + rsel * 16 < B ? r0 + rsel * 16 : r0) >> 4;  // this wave's row block (one beyond the batch: the tile's first)
   float hpv = hsg[(long)rowc * H + j];
-  float4 xa[XB][2];  // the next step's fragments of the layer input
-  if (XP) fragment_loads<XB>(tile_rsrc(xin + g * s_x + (long)r0 * width), width, B - r0, kw, xa);
+  float4 xa[XB][2];  // this step's fragments of the layer input, loaded one step ahead
+  float gxn[3] = {0.f, 0.f, 0.f};  // ... or its input projection
+  if (XP) {
+    fragment_loads<XB>(tile_rsrc(xin + g * s_x + (long)r0 * width), width, B - r0, kw, xa);
+  } else {
+    const float* gxr = gx + g * s_gx + (long)rowc * 3 * H;
+#pragma unroll
+    for (int q = 0; q < 3; ++q) gxn[q] = gxr[q * H + j];
+  }
   __syncthreads();
   for (int t = 0; t < T; ++t) {
-    // what does not depend on the recurrence travels, or is computed, during the wait
-    float gxv[3] = {0.f, 0.f, 0.f};
+    // what does not depend on the recurrence is computed in front of the wait
+    float gxv[3] = {gxn[0], gxn[1], gxn[2]};
     floatx4 acc[2][3], accx[2];
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -403,17 +418,19 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
         accx[i] = acc[i][2];  // n keeps its two parts apart: n = tanh(x part + r * (h part))
         acc[i][2] = (floatx4){0.f, 0.f, 0.f, 0.f};
       }
-      // the fragments of step t+1 are on their way during the wait and the recurrent product
       __builtin_amdgcn_sched_barrier(0);
-      fragment_loads<XB>(tile_rsrc(xin + g * s_x + ((long)min(t + 1, T - 1) * B + r0) * width), width, B - r0, kw,
-                         xa);
-    } else {
-      const float* gxr = gx + g * s_gx + ((long)t * B + rowc) * 3 * H;
-#pragma unroll
-      for (int q = 0; q < 3; ++q) gxv[q] = gxr[q * H + j];
     }
     if (t > 0 && !group_wait(flags, NJ, base + (unsigned)t, abort_w, spin_limit, lds_flag)) return;
-    resident_contraction_x<3, 4>(wres, wp, tile_rsrc(hxg + (long)t * xblk), H, rbx, acc);
+    resident_contraction_x<3, 4>(wres, wp, tile_rsrc(hxg + (long)t * xblk), H, rbx, acc, [&]() {
+      // step t+1's layer input (or input projection) travels during this step's product
+      if (XP) {
+        fragment_loads<XB>(tile_rsrc(xin + g * s_x + ((long)min(t + 1, T - 1) * B + r0) * width), width, B - r0, kw, xa);
+      } else {
+        const float* gxr = gx + g * s_gx + ((long)min(t + 1, T - 1) * B + rowc) * 3 * H;
+#pragma unroll
+        for (int q = 0; q < 3; ++q) gxn[q] = gxr[q * H + j];
+      }
+    });
 #pragma unroll
     for (int v = 0; v < 4; ++v) {
 #pragma unroll
@@ -535,6 +552,8 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* __rest
   __syncthreads();
   int it = 0;
   for (int t = t_hi - 1; t >= t_lo; --t, ++it) {
+    // (loaded in front of the wait: one step ahead they would cost this kernel, which is held at 248
+    // registers, spills - measured, 400 -> 620 us)
     const long e = ((long)t * B + rowc) * H + j;
     const float* svr = sv + g * s_sv + ((long)t * B + rowc) * 4 * H;
     const float r = svr[j], z = svr[H + j], n = svr[2 * H + j], q = svr[3 * H + j];
@@ -545,7 +564,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* __rest
     acc[0][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
     acc[1][0] = (floatx4){0.f, 0.f, 0.f, 0.f};
     if (t + 1 < T)  // uniform over the grid
-      resident_contraction_x<1, 12>(wres, wp, tile_rsrc(dgxg + (long)(t + 1) * xblk), H3, rbx, acc);
+      resident_contraction_x<1, 12>(wres, wp, tile_rsrc(dgxg + (long)(t + 1) * xblk), H3, rbx, acc, []() {});
 #pragma unroll
     for (int v = 0; v < 4; ++v) red[((kw * 2 + rsel) * 4 + v) * 64 + lane] = acc[0][0][v] + acc[1][0][v];
     __syncthreads();
