@@ -25,7 +25,7 @@ PEAK_BF16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 # Kernels whose work is counted in bytes (HBM roofline); every other timed kernel is a contraction.
-STREAMING_KERNELS = {"cvt2_kernel", "softmax_ce_bf16_rows_kernel", "commit_kernel", "commit_acc4_kernel"}
+STREAMING_KERNELS = {"cvt2_kernel", "cvt2_pack_kernel", "softmax_ce_bf16_rows_kernel", "commit_kernel", "commit_acc4_kernel"}
 
 # HBM bytes per launch of a kernel, from two `rocprofv3 --pmc` runs of this file (FETCH_SIZE, then
 # WRITE_SIZE, in KiB per dispatch; FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0: the config-5

@@ -334,7 +334,8 @@ enum hpsgd_kernel {
   HPSGD_KERNEL_GRU_STEP = 18,
   HPSGD_KERNEL_COMMIT_ACC = 19,     /* streaming: bytes */
   HPSGD_KERNEL_COMMIT = 20,         /* streaming: bytes */
-  HPSGD_KERNEL_COUNT = 21
+  HPSGD_KERNEL_CVT2_PACK = 21,      /* streaming: bytes */
+  HPSGD_KERNEL_COUNT = 22
 };
 int hpsgd_kernel_timer_enable(hpsgd_ctx *ctx, unsigned kernel_mask);
 int hpsgd_kernel_timer_read(hpsgd_ctx *ctx, int kernel, long *launches, double *total_ms, double *work);

@@ -31,7 +31,7 @@ EXPORTS = [
     "hpsgd_local_step_all_static", "hpsgd_merge_sync", "hpsgd_prepare_clones",
 ]
 ROLE_COUNT = 14
-KERNEL_COUNT = 21
+KERNEL_COUNT = 22
 
 
 class ModelDesc(C.Structure):

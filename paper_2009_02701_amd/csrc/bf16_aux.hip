@@ -27,13 +27,10 @@ __device__ __forceinline__ bf16x4 load4_as_bf16(const __bf16* p) {
 // transposed tile goes through LDS and leaves as 16-byte pieces of 8 consecutive input rows.
 // Needs C % 4 == 0, R % 8 == 0 and the alignments cvt2_supported checks.
 template <typename TIN>
-__global__ void __launch_bounds__(256)
-cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restrict__ out_p, long ld_p,
-            long s_p, __bf16* __restrict__ out_t, long ld_t, long s_t, int R, int C) {
-  __shared__ __attribute__((aligned(16))) __bf16 tile[64][72];  // [column][row]
-  const int g = blockIdx.z, c0 = blockIdx.x * 64, r0 = blockIdx.y * 64;
+__device__ __forceinline__ void cvt2_tile(const TIN* __restrict__ src, long ld_in, __bf16* __restrict__ dst_p, long ld_p,
+                                          __bf16* __restrict__ dst_t, long ld_t, int R, int C, int c0, int r0,
+                                          __bf16 (&tile)[64][72]) {
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
-  const TIN* src = in + g * s_in;
   // All four loads are issued before anything waits for one (clamped addresses instead of
   // branches: behind a branch each load would be waited for, and stored, before the next is issued).
   const int c = c0 + 4 * tx;
@@ -46,16 +43,16 @@ cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restric
   for (int i = 0; i < 4; ++i) {
     const int rl = ty + 16 * i, r = r0 + rl;
     if (r < R && c_ok) {
-      if (out_p) __builtin_nontemporal_store(v[i], reinterpret_cast<bf16x4*>(out_p + g * s_p + (long)r * ld_p + c));
+      if (dst_p) __builtin_nontemporal_store(v[i], reinterpret_cast<bf16x4*>(dst_p + (long)r * ld_p + c));
     } else {
       v[i][0] = v[i][1] = v[i][2] = v[i][3] = (__bf16)0.f;
     }
-    if (out_t) {
+    if (dst_t) {
 #pragma unroll
       for (int e = 0; e < 4; ++e) tile[4 * tx + e][rl] = v[i][e];
     }
   }
-  if (!out_t) return;
+  if (!dst_t) return;
   __syncthreads();
 #pragma unroll
   for (int q = 0; q < 2; ++q) {
@@ -63,8 +60,33 @@ cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restric
     const int c = c0 + col, r = r0 + 8 * part;
     if (c < C && r < R)
       __builtin_nontemporal_store(*reinterpret_cast<const u4nt_a*>(&tile[col][8 * part]),
-                                  reinterpret_cast<u4nt_a*>(out_t + g * s_t + (long)c * ld_t + r));
+                                  reinterpret_cast<u4nt_a*>(dst_t + (long)c * ld_t + r));
   }
+}
+
+template <typename TIN>
+__global__ void __launch_bounds__(256)
+cvt2_kernel(const TIN* __restrict__ in, long ld_in, long s_in, __bf16* __restrict__ out_p, long ld_p,
+            long s_p, __bf16* __restrict__ out_t, long ld_t, long s_t, int R, int C) {
+  __shared__ __attribute__((aligned(16))) __bf16 tile[64][72];  // [column][row]
+  const int g = blockIdx.z;
+  cvt2_tile<TIN>(in + g * s_in, ld_in, out_p ? out_p + g * s_p : nullptr, ld_p, out_t ? out_t + g * s_t : nullptr, ld_t,
+                 R, C, blockIdx.x * 64, blockIdx.y * 64, tile);
+}
+
+// Several fp32 matrices in one launch (the weight matrices of a model: each is a few hundred
+// tiles, and a launch of its own costs more than its copies).  blockIdx.x runs over the tiles of
+// all jobs, job j owning [tile0[j], tile0[j+1]).
+__global__ void __launch_bounds__(256) cvt2_pack_kernel(Cvt2Pack p) {
+  __shared__ __attribute__((aligned(16))) __bf16 tile[64][72];
+  int j = 0;
+  while (j + 1 < p.n && (int)blockIdx.x >= p.tile0[j + 1]) ++j;  // (uniform)
+  const Cvt2Job& q = p.job[j];
+  const int t = blockIdx.x - p.tile0[j], g = blockIdx.z;
+  __bf16* op = reinterpret_cast<__bf16*>(q.out_p);
+  __bf16* ot = reinterpret_cast<__bf16*>(q.out_t);
+  cvt2_tile<float>(q.in + g * q.s_in, q.ld_in, op ? op + g * q.s_p : nullptr, q.ld_p, ot ? ot + g * q.s_t : nullptr,
+                   q.ld_t, q.R, q.C, (t % q.tiles_x) * 64, (t / q.tiles_x) * 64, tile);
 }
 
 bool cvt2_supported(const void* in, int in_bf16, long ld_in, long s_in, const void* out_p, long ld_p,
@@ -89,6 +111,30 @@ hipError_t launch_cvt2(const void* in, int in_bf16, long ld_in, long s_in, void*
   else
     hipLaunchKernelGGL(cvt2_kernel<float>, grid, dim3(256), 0, s, (const float*)in, ld_in, s_in,
                        (__bf16*)out_p, ld_p, s_p, (__bf16*)out_t, ld_t, s_t, R, C);
+  return hipGetLastError();
+}
+
+bool cvt2_pack_push(Cvt2Pack& p, const float* in, long ld_in, long s_in, void* out_p, long ld_p, long s_p,
+                    void* out_t, long ld_t, long s_t, int R, int C) {
+  if (p.n >= Cvt2Pack::MAX || !cvt2_supported(in, 0, ld_in, s_in, out_p, ld_p, s_p, out_t, ld_t, s_t, R, C)) return false;
+  Cvt2Job& q = p.job[p.n];
+  q.in = in; q.ld_in = ld_in; q.s_in = s_in;
+  q.out_p = out_p; q.ld_p = ld_p; q.s_p = s_p;
+  q.out_t = out_t; q.ld_t = ld_t; q.s_t = s_t;
+  q.R = R; q.C = C;
+  q.tiles_x = (C + 63) / 64;
+  const long tiles = (long)q.tiles_x * ((R + 63) / 64);
+  if (tiles + p.tile0[p.n] > (1L << 30)) return false;
+  p.tile0[p.n + 1] = p.tile0[p.n] + (int)tiles;
+  p.bytes += (double)R * C * (4 + (out_p ? 2 : 0) + (out_t ? 2 : 0));
+  ++p.n;
+  return true;
+}
+
+hipError_t launch_cvt2_pack(const Cvt2Pack& p, int groups, hipStream_t s) {
+  if (p.n == 0 || groups <= 0) return hipSuccess;
+  KernelTimer kt(KID_CVT2_PACK, p.bytes * groups, s);
+  hipLaunchKernelGGL(cvt2_pack_kernel, dim3(p.tile0[p.n], 1, groups), dim3(256), 0, s, p);
   return hipGetLastError();
 }
 

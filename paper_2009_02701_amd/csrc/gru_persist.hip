@@ -469,8 +469,8 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
 // W_hh (3H x H), kept transposed in LDS (16 rows of 3H, unit stride along the contraction).  dgh and
 // dgx hold the gate gradients of all steps (blocks of B x 3H); block t+1 of dgh is the
 // contraction operand of step t (none at t = T-1).  D holds dh_{t_hi} * z_{t_hi} on entry (the
-// head's gradient when t_hi == T) and dh_{t_lo} * z_{t_lo} on exit.  above: per-step gradient
-// from the layer above (blocks of B x H) or nullptr.
+// head's gradient when t_hi == T; d_zero: it is zero and D is not read) and dh_{t_lo} * z_{t_lo}
+// on exit.  above: per-step gradient from the layer above (blocks of B x H) or nullptr.
 //
 // dWp (nullable, H <= 512): the workgroup also accumulates its share of the recurrent weight
 // gradient over the steps of the launch, dW_hh[q*H + j0 + m][:] += sum over its 32 batch rows
@@ -490,7 +490,7 @@ gru_fwd_persist_kernel(const float* __restrict__ W_hh, const float* __restrict__
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_num_vgpr(124)))
 gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* __restrict__ dgh, float* dghx, long s_dghx,
                        float* __restrict__ dgx, long s_dg,
-                       float* __restrict__ D, long s_D, const float* __restrict__ above, long s_above,
+                       float* __restrict__ D, long s_D, int d_zero, const float* __restrict__ above, long s_above,
                        const float* __restrict__ sv, long s_sv, const float* __restrict__ hs, long s_hs,
                        int B, int H, int T, int t_hi, int t_lo, int groups, unsigned* sync, unsigned base,
                        unsigned spin_limit, unsigned* tickets, unsigned ticket_base, unsigned per_xcd,
@@ -543,7 +543,7 @@ gru_bwd_persist_kernel(const float* __restrict__ W_hh, long s_rep, float* __rest
   const int row = r0 + rsel * 16 + 4 * lg + kw;
   const int rowc = min(row, B - 1);
   float* Dg = D + g * s_D;
-  float dcar = Dg[(long)rowc * H + j];  // dh_{t+1} * z_{t+1}, carried in a register
+  float dcar = d_zero ? 0.f : Dg[(long)rowc * H + j];  // dh_{t+1} * z_{t+1}, carried in a register
   float* dghg = dgh ? dgh + g * s_dg : nullptr;  // row-major, for later launches (nullptr: nobody reads it)
   float* dgxg = dghx + g * s_dghx;               // the gate gradients as the workgroups exchange them
   const long xblk = xblock_words(B, H3);
@@ -887,7 +887,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
 // Backward.  WT: bf16 W_hh^T [H][3H]; dghx: bf16 gate gradients of all steps, fragment-major
 // (blocks of 16 ceil(B/16) x 3H), the exchanged operand; dgxb: bf16 dgx row-major; dgxT / dghT: bf16 transposed copies
 // [3H][ld_T], column t*B + row; dbp: partial bias-gradient sums [(g*RT + ty)][6H] (b_ih | b_hh).
-// D: dh_T * z_T on entry (the head's gradient), dh_0 * z_0 on exit.  NCB: chunks per wave
+// D: dh_T * z_T on entry (the head's gradient; d_zero: zero, D is not read), dh_0 * z_0 on exit.  NCB: chunks per wave
 // (3H <= 256 * NCB).  The fragments of the first half of a wave's chunks stay in registers,
 // those of the second half in LDS (each wave reads back only its own): with all of them in
 // registers the two waves of a SIMD would fill its register file, and no wave of any other
@@ -895,7 +895,7 @@ gru_fwd_persist_bf16_kernel(const __bf16* __restrict__ Wb, long s_wb, const floa
 template <int NCB>
 __global__ void __launch_bounds__(PNT) __attribute__((amdgpu_waves_per_eu(1, 2)))
 gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dghx, long s_dgh, long s_dgb, float* __restrict__ D,
-                            long s_D, const float* __restrict__ above, long s_above, const float* __restrict__ sv,
+                            long s_D, int d_zero, const float* __restrict__ above, long s_above, const float* __restrict__ sv,
                             long s_sv, const float* __restrict__ hs, long s_hs, __bf16* __restrict__ dgxb,
                             __bf16* __restrict__ dgxT, __bf16* __restrict__ dghT, long ld_T, long s_T,
                             float* __restrict__ dbp, int B, int H, int T, int groups, unsigned* sync, unsigned base,
@@ -941,7 +941,8 @@ gru_bwd_persist_bf16_kernel(const __bf16* __restrict__ WT, long s_wt, __bf16* dg
   const int j = j0 + u0;
   const int ro = ((rl >> 4) * 2 + (u0 >> 4)) * 256 + (rl & 3) * 64 + ((rl >> 2) & 3) * 16 + (u0 & 15);  // + w * 1024
   float* Dg = D + g * s_D;
-  float2 dcar = *reinterpret_cast<const float2*>(Dg + (long)rowc * H + j);
+  float2 dcar = make_float2(0.f, 0.f);
+  if (!d_zero) dcar = *reinterpret_cast<const float2*>(Dg + (long)rowc * H + j);
   __bf16* dghg = dghx + g * s_dgh;
   const long xblk = (long)((B + 15) / 16) * 16 * H3;  // elements of a step's block of dghx
   float2 bsum[4] = {{0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}, {0.f, 0.f}};  // da_r, da_z, da_n, dq over the steps
@@ -1187,7 +1188,7 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
 
 hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dghx, long s_dghx, float* dgx,
                                   long s_dg, float* D,
-                                  long s_D, const float* above, long s_above, const float* sv, long s_sv,
+                                  long s_D, bool d_zero, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
                                   int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
                                   float* dbp, bool device_scope, unsigned* ticket_launches, hipStream_t s) {
@@ -1209,8 +1210,8 @@ hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, flo
   dim3 grid((H / PJ) * ((B + PR - 1) / PR) * groups);
   const Placement pl = placement(sync, groups * ((B + PR - 1) / PR), (long)grid.x, lds, device_scope, ticket_launches);
   KernelTimer kt(KID_GRU_BWD_PERSIST, 2.0 * B * 3 * H * (double)H * (t_hi - t_lo) * groups * (dWp ? 2 : 1), s);
-  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dghx, s_dghx, dgx, s_dg, D, s_D, above,
-                     s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit,
+  hipLaunchKernelGGL(gru_bwd_persist_kernel, grid, dim3(PNT), lds, s, W_hh, s_rep, dgh, dghx, s_dghx, dgx, s_dg, D, s_D,
+                     d_zero ? 1 : 0, above, s_above, sv, s_sv, hs, s_hs, B, H, T, t_hi, t_lo, groups, sync, base, spin_limit,
                      pl.tickets, pl.ticket_base, pl.per_xcd, dWp, dbp);
   return hipGetLastError();
 }
@@ -1283,7 +1284,7 @@ hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b
 }
 
 hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, long s_dgh, long s_dgb, float* D, long s_D,
-                                       const float* above, long s_above, const float* sv, long s_sv, const float* hs,
+                                       bool d_zero, const float* above, long s_above, const float* sv, long s_sv, const float* hs,
                                        long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
                                        int B, int H, int T, int groups, unsigned* sync, unsigned base,
                                        unsigned spin_limit, bool device_scope, unsigned* ticket_launches, hipStream_t s) {
@@ -1313,7 +1314,7 @@ hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, lo
   KernelTimer kt(KID_GRU_BWD_PERSIST_BF16, 2.0 * B * 3 * H * (double)H * T * groups, s);
 #define HPSGD_BWD_PB(N)                                                                                            \
   hipLaunchKernelGGL(gru_bwd_persist_bf16_kernel<N>, grid, dim3(PNT), lds, s, (const __bf16*)WT, s_wt,              \
-                     (__bf16*)dghx, s_dgh, s_dgb, D, s_D, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \
+                     (__bf16*)dghx, s_dgh, s_dgb, D, s_D, d_zero ? 1 : 0, above, s_above, sv, s_sv, hs, s_hs, (__bf16*)dgxb, (__bf16*)dgxT, \
                      (__bf16*)dghT, ld_T, s_T, dbp, B, H, T, groups, sync, base, spin_limit,                        \
                      pl.tickets, pl.ticket_base, pl.per_xcd)
   if (ncf == 1) HPSGD_BWD_PB(3);

@@ -422,6 +422,14 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
   const int classes = lm ? d.vocab : d.classes;
   const bool ntc = (B % 8 == 0) && (H % 8 == 0);
   const bool fused_b = gru_fused_bf16_supported(H);
+  // the matrices go through one launch (each is a few hundred tiles); what the pack does not
+  // take is launched by itself
+  Cvt2Pack pack;
+  auto copy2 = [&](const float* in, long ld_in, void* out_p, long ld_p, long s_p, void* out_t, long ld_t, long s_t,
+                   int R, int C) -> bool {
+    if (!launch || cvt2_pack_push(pack, in, ld_in, sR, out_p, ld_p, s_p, out_t, ld_t, s_t, R, C)) return true;
+    return launch_cvt2(in, 0, ld_in, sR, out_p, ld_p, s_p, out_t, ld_t, s_t, R, C, groups, st) == hipSuccess;
+  };
   for (int l = 0; l < L && l < 16; ++l) {
     const int width = l > 0 ? H : (lm ? d.embed : d.input);
     const float* Wih = rin + c->eoff(c->lidx[l].wih);
@@ -431,9 +439,7 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
       __bf16* wT = need_T ? bfreg(c->wihTl[l]) : nullptr;
       const long s_wT = 2 * (long)c->wihTl[l].stride, s_wb2 = 2 * (long)c->wihbl[l].stride;
       if (cvt2_supported(Wih, 0, width, sR, bfreg(c->wihbl[l]), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width)) {
-        if (launch && launch_cvt2(Wih, 0, width, sR, bfreg(c->wihbl[l]), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width,
-                                  groups, st) != hipSuccess)
-          return HPSGD_EHIP;
+        if (!copy2(Wih, width, bfreg(c->wihbl[l]), width, s_wb2, wT, 3 * H, s_wT, 3 * H, width)) return HPSGD_EHIP;
         wc.wih[l] = true;
         wc.wihT[l] = need_T;
       }
@@ -442,9 +448,7 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
       void* wb = reg(c->whhb[l]);
       const long s_wb = 2 * (long)c->whhb[l].stride, s_whT = 2 * (long)c->whhT[l].stride;
       if (cvt2_supported(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H)) {
-        if (launch &&
-            launch_cvt2(Whh, 0, H, sR, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H, groups, st) != hipSuccess)
-          return HPSGD_EHIP;
+        if (!copy2(Whh, H, wb, H, s_wb, bfreg(c->whhT[l]), 3 * H, s_whT, 3 * H, H)) return HPSGD_EHIP;
         wc.whhT[l] = true;
       } else if (launch && launch_cvt_bf16(Whh, H, sR, wb, H, s_wb, 3 * H, H, false, groups, st) != hipSuccess) {
         return HPSGD_EHIP;
@@ -458,12 +462,11 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
     const long s_wob = 2 * (long)c->wob.stride, s_woT = 2 * (long)c->woT.stride;
     if (ntc && fused_b && classes % 8 == 0 &&
         cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H)) {
-      if (launch && launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
-                                groups, st) != hipSuccess)
-        return HPSGD_EHIP;
+      if (!copy2(rin + oW, H, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H)) return HPSGD_EHIP;
       wc.head = true;
     }
   }
+  if (launch && launch_cvt2_pack(pack, groups, st) != hipSuccess) return HPSGD_EHIP;
   return HPSGD_OK;
 }
 
@@ -962,9 +965,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
     }
     const float* above = nullptr;
+    // the gradient carried into a layer's last step is zero unless the head wrote it (the
+    // classifier on the top layer): a resident-weight launch is told so, any other path has D cleared
+    bool d_zero = false;
     if (lm) {
       above = dx;
-      HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
+      d_zero = true;
     }
     // ---- backward: GRU layers, top to bottom
     for (int l = L - 1; l >= 0; --l) {
@@ -1027,6 +1033,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // one follows on the main stream after the join.  Fixed chunking: deterministic.
       const bool persist = fused && use_persist;
       const bool persist_b = fused_b && use_persist_b && stepT;
+      if (d_zero && !persist && !persist_b) {
+        role = HPSGD_ROLE_OTHER;
+        HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
+      }
       // the resident-weight kernel accumulates dW_hh itself (one partial sum per batch-row tile)
       float* dwp = (persist && c->dwp.stride == (size_t)((B + 31) / 32) * 3 * H * H) ? reg(c->dwp) : nullptr;
       // ... and the bias gradients, when their partial sums can be added with 16-byte accesses
@@ -1058,7 +1068,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         role = HPSGD_ROLE_GEMM_REC_BWD;
         // (the row-major gate gradients only when a later launch reads them)
         HIP_TRY(launch_gru_bwd_persist(Whh, sR, (dwp && dbp) ? nullptr : dgh, reg(c->dghx), (long)c->dghx.stride, dgx, s_gx,
-                                       D, s_D, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
+                                       D, s_D, d_zero, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
                                        T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, c->device_scope, &ticket_launches, s));
         c->last_dw += dwp ? 1 : 0;
         pbase += (unsigned)T * gru_persist_count_per_step(H);
@@ -1067,8 +1077,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
-        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, bfreg(c->dghx), 2 * (long)c->dghx.stride, s_dgb, D, s_D, above,
-                                            s_dx, sv, s_sv, hs, s_hs, dgxb, bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B,
+        HIP_TRY(launch_gru_bwd_persist_bf16(wtb, s_wtb, bfreg(c->dghx), 2 * (long)c->dghx.stride, s_dgb, D, s_D, d_zero,
+                                            above, s_dx, sv, s_sv, hs, s_hs, dgxb, bfreg(c->dgxT), bfreg(c->dghT), TBp, s_T, dbp, B,
                                             H, T, groups, psync, pbase, c->spin_limit, c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
         if (l == 0) TRY0(resident.mark());
@@ -1223,7 +1233,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_reduce_pack(rp, groups, s));
       if (dx_beside && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
       role = HPSGD_ROLE_OTHER;
-      if (l > 0) HIP_TRY(launch_fill_zero(D, (size_t)B * H, (size_t)s_D, groups, s));
+      d_zero = true;  // below the top layer nothing but `above` feeds a layer's gradient
     }
     if (lm) {
       role = HPSGD_ROLE_EMBED;
@@ -1697,6 +1707,7 @@ const char* hpsgd_kernel_name(int kernel) {
     case HPSGD_KERNEL_GRU_STEP: return "gru_step_kernel";
     case HPSGD_KERNEL_COMMIT_ACC: return "commit_acc4_kernel";
     case HPSGD_KERNEL_COMMIT: return "commit_kernel";
+    case HPSGD_KERNEL_CVT2_PACK: return "cvt2_pack_kernel";
     default: return nullptr;
   }
 }

@@ -40,7 +40,8 @@ enum KernelId : int {
   KID_GRU_STEP = 18,              // gru_{fwd,bwd}_step(_bf16)_kernel: one launch per time step
   KID_COMMIT_ACC = 19,            // commit_acc4_kernel / commit_acc_kernel (update + accumulate, 20 B/param)
   KID_COMMIT = 20,                // commit_kernel (update of what no GEMM epilogue updated, 12 B/param)
-  KID_COUNT = 21
+  KID_CVT2_PACK = 21,             // cvt2_pack_kernel (the copies of several matrices in one launch)
+  KID_COUNT = 22
 };
 struct KernelTimer {
   KernelTimer(int kid, double work, hipStream_t s);
@@ -177,10 +178,11 @@ hipError_t launch_gru_fwd_persist(const float* W_hh, const float* b_hh, long s_r
 // projection itself from the layer input xin (T blocks of B x width per worker, stride s_x) and W_ih,
 // b_ih (in the replica, like W_hh); gx is then unused and may be nullptr.
 bool gru_persist_xproj_supported(int H, int width);
-// steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches)
+// steps t_hi-1 .. t_lo of BPTT (a range: a caller may cut BPTT into several launches);
+// d_zero: the gradient carried into step t_hi-1 is zero (D is written at the end, not read)
 hipError_t launch_gru_bwd_persist(const float* W_hh, long s_rep, float* dgh, float* dghx, long s_dghx, float* dgx,
                                   long s_dg, float* D,
-                                  long s_D, const float* above, long s_above, const float* sv, long s_sv,
+                                  long s_D, bool d_zero, const float* above, long s_above, const float* sv, long s_sv,
                                   const float* hs, long s_hs, int B, int H, int T, int t_hi, int t_lo,
                                   int groups, unsigned* sync, unsigned base, unsigned spin_limit, float* dWp,
                                   float* dbp, bool device_scope, unsigned* ticket_launches, hipStream_t s);
@@ -226,7 +228,7 @@ hipError_t launch_gru_fwd_persist_bf16(const void* Wb, long s_wb, const float* b
 // bf16 elements of one time step's block of an exchange buffer whose rows are `width` wide
 size_t gru_persist_bf16_exchange_elems(int B, int width);
 hipError_t launch_gru_bwd_persist_bf16(const void* WT, long s_wt, void* dghx, long s_dgh, long s_dgb, float* D, long s_D,
-                                       const float* above, long s_above, const float* sv, long s_sv, const float* hs,
+                                       bool d_zero, const float* above, long s_above, const float* sv, long s_sv, const float* hs,
                                        long s_hs, void* dgxb, void* dgxT, void* dghT, long ld_T, long s_T, float* dbp,
                                        int B, int H, int T, int groups, unsigned* sync, unsigned base,
                                        unsigned spin_limit, bool device_scope, unsigned* ticket_launches, hipStream_t s);
@@ -256,6 +258,27 @@ bool cvt2_supported(const void* in, int in_bf16, long ld_in, long s_in, const vo
                     long s_p, const void* out_t, long ld_t, long s_t, int R, int C);
 hipError_t launch_cvt2(const void* in, int in_bf16, long ld_in, long s_in, void* out_p, long ld_p, long s_p,
                        void* out_t, long ld_t, long s_t, int R, int C, int groups, hipStream_t s);
+// several fp32 matrices through one launch of the same copies (one group count for all of them)
+struct Cvt2Job {
+  const float* in;
+  long ld_in, s_in;
+  void* out_p;
+  long ld_p, s_p;
+  void* out_t;
+  long ld_t, s_t;
+  int R, C, tiles_x, pad;
+};
+struct Cvt2Pack {
+  static constexpr int MAX = 8;
+  int n = 0;
+  int tile0[MAX + 1] = {0};  // first tile of job j in blockIdx.x; tile0[n] = all tiles
+  double bytes = 0;          // per group, for the launch timer
+  Cvt2Job job[MAX];
+};
+// false: the pack is full or the job is not one cvt2_supported takes (launch it by itself)
+bool cvt2_pack_push(Cvt2Pack& p, const float* in, long ld_in, long s_in, void* out_p, long ld_p, long s_p,
+                    void* out_t, long ld_t, long s_t, int R, int C);
+hipError_t launch_cvt2_pack(const Cvt2Pack& p, int groups, hipStream_t s);
 // mean softmax-CE whose logit gradient is written rounded to bf16 (row pitch ld_d); logits intact
 bool softmax_ce_bf16_supported(const float* logits, long s_logits, const void* dlog, long ld_d, long s_d,
                                int C);
