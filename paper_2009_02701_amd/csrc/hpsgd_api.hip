@@ -863,8 +863,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_softmax_ce_bf16(logits, s_log, y, nrows, bfreg(c->dlogb), clp, s_dlb, rowloss,
                                      (long)c->rowloss.stride, reg(c->rowstat), (long)c->rowstat.stride, nrows,
                                      classes, groups, s, colsum_fused ? reg(c->colpart) : nullptr, s_colpart, c->K));
-      if (loss_out)
-        HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
       role = HPSGD_ROLE_OTHER;
       HIP_TRY(launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows,
                           classes, groups, s));
@@ -878,6 +876,21 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the classes): with an auxiliary stream the two run side by side and the tiles of the
       // weight gradient fill the CUs the other leaves idle.  One event pair brackets both.
       const bool side_by_side = c->aux && c->ev_fork && c->ev_join;
+      // What needs the loss kernel's results only (the mean loss, the bias gradient from its
+      // partial column sums): side by side, the weight gradient outlasts the input gradient, and
+      // these follow the latter on this stream while the other stream is still busy.
+      auto loss_followers = [&]() -> int {
+        if (loss_out)
+          HIP_TRY(launch_loss_mean(rowloss, (long)c->rowloss.stride, loss_out, nrows, groups, s));
+        if (colsum_fused)
+          HIP_TRY(launch_reduce_parts(reg(c->colpart), n_colparts, (size_t)classes, nullptr, 0,
+                                      grad + ob, (size_t)sG, 0.f, 0, groups, s));
+        else
+          HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
+                                        grad + ob, sG, nrows, classes, groups, s));
+        return HPSGD_OK;
+      };
+      if (!side_by_side) TRY0(loss_followers());
       {
         TimerScope pair(c, role, s, 2);
         const bool nested = c->timer_nested;
@@ -890,17 +903,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                   lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT, 0.f, true));
         TRY(gemm2(side_by_side ? c->aux : s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top,
                   0, wt.C, H, wt.sC, wt.epi, wt.aux, sR, vdT, vhT, lr));
+        if (side_by_side) {
+          const int saved_role = role;
+          role = HPSGD_ROLE_OTHER;
+          TRY0(loss_followers());
+          role = saved_role;
+        }
         if (side_by_side &&
             (hipEventRecord(c->ev_join, c->aux) != hipSuccess || hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess))
           return HPSGD_EHIP;
         c->timer_nested = nested;
       }
-      if (colsum_fused)
-        HIP_TRY(launch_reduce_parts(reg(c->colpart), n_colparts, (size_t)classes, nullptr, 0,
-                                    grad + ob, (size_t)sG, 0.f, 0, groups, s));
-      else
-        HIP_TRY(launch_colsum_softmax(logits, s_log, reg(c->rowstat), (long)c->rowstat.stride, y, nrows,
-                                      grad + ob, sG, nrows, classes, groups, s));
     } else if (!bf && !lm && cls_head_supported(nrows, classes, H)) {
       // a classifier head with few classes: forward and loss in one small launch, the three
       // gradients and the update (or the gradients, when they are accumulated as well) in another
@@ -964,6 +977,24 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
       }
     }
+    // the embedding gradient from the first layer's input gradient dx (Alg. 2 "update replica"
+    // for the table, when the update is in place)
+    bool embed_done = false;
+    auto embed_grad = [&](hipStream_t st) -> int {
+      const size_t oE = c->eoff(c->i_embed);
+      if (!acc && rin == rout) {
+        // an update in place: only the rows of the tokens of the batch change, and their owners
+        // write them; no gradient table to clear, fill and stream through the commit kernel
+        fused_commit[c->i_embed] = 1;
+        if (launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, st, rin + oE, sR, lr) != hipSuccess)
+          return HPSGD_EHIP;
+      } else {
+        if (launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, st) != hipSuccess ||
+            launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, st) != hipSuccess)
+          return HPSGD_EHIP;
+      }
+      return HPSGD_OK;
+    };
     const float* above = nullptr;
     // the gradient carried into a layer's last step is zero unless the head wrote it (the
     // classifier on the top layer): a resident-weight launch is told so, any other path has D cleared
@@ -1169,6 +1200,11 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
             return HPSGD_EHIP;
           TRY0(gemm2(c->aux, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx,
                      EPI_STORE, nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
+          // the embedding rows need this product and nothing of the weight gradients beside it
+          if (l == 0 && lm) {
+            TRY0(embed_grad(c->aux));
+            embed_done = true;
+          }
           if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
         } else {
           TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
@@ -1235,18 +1271,9 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       role = HPSGD_ROLE_OTHER;
       d_zero = true;  // below the top layer nothing but `above` feeds a layer's gradient
     }
-    if (lm) {
+    if (lm && !embed_done) {
       role = HPSGD_ROLE_EMBED;
-      const size_t oE = c->eoff(c->i_embed);
-      if (!acc && rin == rout) {
-        // an update in place: only the rows of the tokens of the batch change, and their owners
-        // write them; no gradient table to clear, fill and stream through the commit kernel
-        fused_commit[c->i_embed] = 1;
-        HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, s, rin + oE, sR, lr));
-      } else {
-        HIP_TRY(launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, s));
-        HIP_TRY(launch_embed_bwd(dx, s_dx, tok, TB, grad + oE, sG, TB, d.embed, groups, s));
-      }
+      TRY(embed_grad(s));
     }
   }
   // ---- commit (Alg. 2 "update replica")
