@@ -683,6 +683,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // resident-weight launches, h_0 of every layer (fp32, and in bf16 precision the bf16 copy and
     // the first B columns of the transposed copy)
     bool cleared = false;
+    bool head_early = false;
     {
       FillPack fp;
       fp.n = 0;
@@ -749,9 +750,22 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
             wihT_ready[l] = wc.wihT[l];
           }
         }
+        // The one copy of the head matrix that serves cloned replicas: beside the top layer's
+        // input projection (between two resident-weight launches, when the synchronising stream
+        // has finished), joined before the recurrence starts.
+        const bool early = l == L - 1 && l > 0 && headb && !head_done && head_src && c->aux && c->ev_fork && c->ev_join;
+        if (early) {
+          if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess ||
+              launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H, 1,
+                          c->aux) != hipSuccess ||
+              hipEventRecord(c->ev_join, c->aux) != hipSuccess)
+            return HPSGD_EHIP;
+          head_early = true;
+        }
         role = HPSGD_ROLE_GEMM_INPUT;
         TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
                   EPI_BIAS, rin + c->eoff(c->lidx[l].bih), sR, va, vb));
+        if (early && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
       }
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
       // not use) and of h
@@ -836,8 +850,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // the copy has the memory system to itself (beside a resident-weight launch it takes 2.3
       // times as long and slows that launch by more than it takes alone; at the start of the step it
       // shares the bandwidth with the merge and the clone)
-      if (head_done) {
-        // made with the layers' copies, before the step
+      if (head_done || head_early) {
+        // made with the layers' copies, before the step, or beside the top layer's input projection
       } else if (head_src) {  // the replicas are clones of one model: one copy of its head matrix serves all workers
         HIP_TRY(launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             1, s));
@@ -863,9 +877,6 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       HIP_TRY(launch_softmax_ce_bf16(logits, s_log, y, nrows, bfreg(c->dlogb), clp, s_dlb, rowloss,
                                      (long)c->rowloss.stride, reg(c->rowstat), (long)c->rowstat.stride, nrows,
                                      classes, groups, s, colsum_fused ? reg(c->colpart) : nullptr, s_colpart, c->K));
-      role = HPSGD_ROLE_OTHER;
-      HIP_TRY(launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows,
-                          classes, groups, s));
       role = HPSGD_ROLE_GEMM_HEAD;
       const NtView vdl{bfreg(c->dlogb), 1, clp, s_dlb}, vwT{bfreg(c->woT), 1, clp, s_woT};
       const NtView vdT{bfreg(c->dlogT), 1, nrp, s_dlT};
@@ -891,13 +902,25 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         return HPSGD_OK;
       };
       if (!side_by_side) TRY0(loss_followers());
+      // The transposed logit gradient is the weight gradient's operand only: side by side it is
+      // made on that product's stream, under the start of the input gradient.
+      if (side_by_side &&
+          (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess))
+        return HPSGD_EHIP;
+      role = HPSGD_ROLE_OTHER;
+      if (side_by_side) {
+        if (launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes,
+                        groups, c->aux) != hipSuccess)
+          return HPSGD_EHIP;
+      } else {
+        HIP_TRY(launch_cvt2(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows,
+                            classes, groups, s));
+      }
+      role = HPSGD_ROLE_GEMM_HEAD;
       {
         TimerScope pair(c, role, s, 2);
         const bool nested = c->timer_nested;
         c->timer_nested = c->timer_nested || pair.active();
-        if (side_by_side &&
-            (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess))
-          return HPSGD_EHIP;
         // (bf16 views only: the fp32 head matrix may be updated in place by the GEMM beside this one)
         TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
                   lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT, 0.f, true));
