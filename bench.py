@@ -234,23 +234,25 @@ def main():
 
     # ---- overlap (Sec. 3.1 / 3.2): the training side alone (gather + local step, no exchange), the
     # synchronising side alone (merge + clone), the blocking order of the two, and the overlapped
-    # round.  efficiency = (t_A + t_B) / t_overlapped: 1 = nothing hidden, (t_A + t_B) / max(t_A, t_B)
+    # round - each side in the form the overlapped round runs it (the clone is the snapshot alone,
+    # the local step reads its parameters from it).  efficiency = (t_A + t_B) / t_overlapped: 1 = nothing hidden, (t_A + t_B) / max(t_A, t_B)
     # = everything hidden (what Sec. 3.2's count gives for gamma = 1 and t_sync = k t_train, k < 1).
     n_ov = max(20, min(args.steps, 60))
-    tr.s_psgd(lr, 5, record_loss=False)
+    tr.s_train_side(lr, 5)
     torch.cuda.synchronize()
     c0 = time.perf_counter()
-    tr.s_psgd(lr, n_ov, record_loss=False)
+    tr.s_train_side(lr, n_ov)
     t_a = (time.perf_counter() - c0) / n_ov
     sb = tr.stream_b
+    clone = tr.snapshot if tr.implicit_clone else tr.sync_all
     for _ in range(3):
         tr.merge(0, sb)
-        tr.sync_all(0, sb)
+        clone(0, sb)
     torch.cuda.synchronize()
     c0 = time.perf_counter()
     for _ in range(n_ov):
         tr.merge(0, sb)
-        tr.sync_all(0, sb)
+        clone(0, sb)
     torch.cuda.synchronize()
     t_b = (time.perf_counter() - c0) / n_ov
     tr.s_seq(lr, 1, 5, record_loss=False)

@@ -117,6 +117,21 @@ int hpsgd_local_step_all(hpsgd_ctx *ctx, const float *replicas_in, float *replic
                          size_t replica_stride, const void *x, const int32_t *y, float lr,
                          float *loss_out, void *workspace, void *hip_stream);
 
+/* Alg. 2 "make replica" and the local step behind it as one call: every worker's replica is a
+ * clone of `source` (DEVICE, P floats, 16-byte aligned: the global model, or the copy of it taken
+ * when the round began) that has not been written out.  The step reads every parameter from
+ * `source` and writes every parameter of every worker's updated replica to replicas_out
+ * [K][replica_stride]: the same bits as hpsgd_sync_all(source -> replicas) followed by
+ * hpsgd_local_step_all in place, without the K copies of the model ever being written and read
+ * back (4 (K + 1) bytes per parameter of traffic less per round).  What hpsgd_merge needs
+ * afterwards - the replicas and the model they were cloned from - is there: replicas_out and
+ * `source`.  `source` must not overlap replicas_out or the workspace (HPSGD_EALIAS); other
+ * arguments and errors as for hpsgd_local_step_all.  hpsgd_prepare_clones(source, replicas_out,
+ * ..) before the call is honoured as for a step on written-out clones. */
+int hpsgd_local_step_all_cloned(hpsgd_ctx *ctx, const float *source, float *replicas_out,
+                                size_t replica_stride, const void *x, const int32_t *y, float lr,
+                                float *loss_out, void *workspace, void *hip_stream);
+
 /* hpsgd_local_step_all for callers that cannot allocate device memory or hand over a workspace:
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
  * workspace is a fixed array of HPSGD_STATIC_WORKSPACE_BYTES in the library's own device image

@@ -28,7 +28,7 @@ EXPORTS = [
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
     "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
-    "hpsgd_local_step_all_static", "hpsgd_merge_sync", "hpsgd_prepare_clones",
+    "hpsgd_local_step_all_static", "hpsgd_local_step_all_cloned", "hpsgd_merge_sync", "hpsgd_prepare_clones",
 ]
 ROLE_COUNT = 14
 KERNEL_COUNT = 22
@@ -69,6 +69,7 @@ def load_library():
     lib.hpsgd_workspace_bytes.argtypes = [vp]
     lib.hpsgd_workspace_bytes.restype = sz
     lib.hpsgd_local_step_all.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
+    lib.hpsgd_local_step_all_cloned.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp, vp]
     lib.hpsgd_local_step_all_static.argtypes = [vp, vp, vp, sz, vp, i32p, C.c_float, vp, vp]
     lib.hpsgd_prepare_replicas.argtypes = [vp, vp, sz, vp, vp]
     lib.hpsgd_prepare_clones.argtypes = [vp, vp, vp, sz, vp, C.c_int, vp]
@@ -255,6 +256,14 @@ class Context:
                                              replicas_in.stride(0), _ptr(x), _ptr(y), float(lr),
                                              _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
                "hpsgd_local_step_all")
+
+    def local_step_all_cloned(self, source, replicas_out, x, y, lr, loss_out, workspace, stream=None):
+        """Clone + local step as one call: parameters are read from `source` (float32 [P]), every
+        worker's updated replica is written to replicas_out [K, stride]."""
+        _check(self.lib.hpsgd_local_step_all_cloned(self._h, _ptr(source), _ptr(replicas_out),
+                                                    replicas_out.stride(0), _ptr(x), _ptr(y), float(lr),
+                                                    _ptr(loss_out), self._ws_ptr(workspace), _stream(stream)),
+               "hpsgd_local_step_all_cloned")
 
     def local_step_all_static(self, replicas_in, replicas_out, x, y, lr, loss_out, stream=None):
         """local_step_all on the library's fixed workspace (no workspace argument, nothing allocated)."""

@@ -474,15 +474,19 @@ int weight_copies(hpsgd_ctx* c, const float* rin, long sR, int k0, int groups, f
 // acc (nullable): per-worker gradient accumulators [groups][acc_stride]; the step's gradient
 // is added to them (Alg. 2 "accumulate gradients").  Every gradient then goes through the
 // gradient buffer: no weight matrix is updated in a GEMM epilogue.
+// cloned: rin is ONE model that every worker's replica is a clone of (Alg. 2 "make replica" not
+// yet written out): parameters are read from it with group stride 0, rout receives every
+// parameter of every worker.
 int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, size_t rstride,
              const void* x, const int32_t* y, float lr, float* loss_out, float* ws, hipStream_t s,
-             float* acc = nullptr, size_t acc_stride = 0) {
+             float* acc = nullptr, size_t acc_stride = 0, bool cloned = false) {
   const hpsgd_model_desc& d = c->d;
   const int bf = d.prec == HPSGD_BF16_MFMA ? 1 : 0;
   auto reg = [&](const Region& r) { return ws + r.offset + (size_t)k0 * r.stride; };
   float* grad = reg(c->grad);
   const long sG = (long)c->grad.stride;
-  const long sR = (long)rstride;
+  const long sR = (long)rstride;            // of rout
+  const long sRi = cloned ? 0L : (long)rstride;  // of rin
   const int B = d.batch;
   int role = HPSGD_ROLE_OTHER;
   c->timer_nested = false;
@@ -491,10 +495,12 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
   // the bf16 copies of the weights are already in this workspace (hpsgd_prepare_replicas); the
   // step changes the weights, so the mark is used once
   hpsgd_ctx::Mark mark{nullptr, nullptr, 0, nullptr, false};
-  const bool marked = c->take_mark(rin, ws, rstride, mark);
-  const bool prepared = bf && marked &&
-                        k0 == 0 && groups == c->K;
-  const float* head_src = prepared ? mark.clone_src : nullptr;
+  // (a mark is kept under the replicas' address: rout when they are still clones of rin)
+  const bool marked = c->take_mark(cloned ? rout : rin, ws, rstride, mark);
+  const bool prepared = bf && marked && k0 == 0 && groups == c->K && (!cloned || mark.clone_src == rin);
+  // clones without prepared copies: the step makes the one set itself, from rin
+  const bool own_set = cloned && !prepared && bf && k0 == 0;
+  const float* head_src = prepared ? mark.clone_src : own_set ? rin : nullptr;
   const bool head_done = prepared && mark.head_done;
   // the replicas are clones of one model (hpsgd_prepare_clones): one set of bf16 weight copies, in
   // worker 0's slice of the workspace, is every worker's operand (group stride 0)
@@ -532,8 +538,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       float* a_out = reg(c->act[i]);
       role = HPSGD_ROLE_MLP_FWD;
       TRY(gemm(s, groups, bf, B, dims[i + 1], dims[i], a_in, dims[i], s_in, 0, rin + c->eoff(c->fc_w[i]),
-               dims[i], sR, 1, a_out, dims[i + 1], (long)c->act[i].stride,
-               i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->eoff(c->fc_b[i]), sR));
+               dims[i], sRi, 1, a_out, dims[i + 1], (long)c->act[i].stride,
+               i + 1 < L ? EPI_BIAS_RELU : EPI_BIAS, rin + c->eoff(c->fc_b[i]), sRi));
       a_in = a_out;
       s_in = (long)c->act[i].stride;
     }
@@ -545,13 +551,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const size_t oW = c->eoff(c->fc_w[L - 1]), ob = c->eoff(c->fc_b[L - 1]);
       float* dprev = reg(c->dact[L - 2]);
       if (acc) {
-        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sR, y, B, delta, (long)c->act[L - 1].stride, rowloss,
+        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sRi, y, B, delta, (long)c->act[L - 1].stride, rowloss,
                                 (long)c->rowloss.stride, dprev, (long)c->dact[L - 2].stride, grad + oW, grad + ob, sG, lr,
                                 0, loss_out, B, dims[L], dims[L - 1], groups, s, 1));
       } else {
         fused_commit[c->fc_w[L - 1]] = 1;
         fused_commit[c->fc_b[L - 1]] = 1;
-        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sR, y, B, delta, (long)c->act[L - 1].stride, rowloss,
+        HIP_TRY(launch_cls_head(a_in, s_in, rin + oW, rin + ob, sRi, y, B, delta, (long)c->act[L - 1].stride, rowloss,
                                 (long)c->rowloss.stride, dprev, (long)c->dact[L - 2].stride, rout + oW, rout + ob, sR, lr,
                                 1, loss_out, B, dims[L], dims[L - 1], groups, s, 1));
       }
@@ -582,17 +588,17 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         // delta_prev = (delta W) * [a_prev > 0]: before W is updated
         dprev = reg(c->dact[i - 1]);
         TRY(gemm(s, groups, bf, B, dims[i], dims[i + 1], delta, dims[i + 1], s_delta, 0,
-                 rin + c->eoff(c->fc_w[i]), dims[i], sR, 0, dprev, dims[i], (long)c->dact[i - 1].stride,
+                 rin + c->eoff(c->fc_w[i]), dims[i], sRi, 0, dprev, dims[i], (long)c->dact[i - 1].stride,
                  EPI_RELU_MASK, a_prev, s_prev));
       }
       // W' = W - lr * delta^T a_prev
       const WgradTarget wt = wgrad_target(c->fc_w[i]);
       TRY(gemm(s, groups, bf, dims[i + 1], dims[i], B, delta, dims[i + 1], s_delta, 1, a_prev, dims[i],
-               s_prev, 0, wt.C, dims[i], wt.sC, wt.epi, wt.aux, sR, 0, lr));
+               s_prev, 0, wt.C, dims[i], wt.sC, wt.epi, wt.aux, sRi, 0, lr));
       {
         const size_t ob = c->eoff(c->fc_b[i]);
         const bool pushed = acc ? colsum_pack_push(cp, delta, dims[i + 1], s_delta, grad + ob, sG, nullptr, 0, B, dims[i + 1])
-                                : colsum_pack_push(cp, delta, dims[i + 1], s_delta, rout + ob, sR, rin + ob, sR, B,
+                                : colsum_pack_push(cp, delta, dims[i + 1], s_delta, rout + ob, sR, rin + ob, sRi, B,
                                                    dims[i + 1]);
         if (pushed && !acc) fused_commit[c->fc_b[i]] = 1;
         if (!pushed)
@@ -658,14 +664,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // logit gradient emitted in bf16 by the loss kernel and transposed from there
     const bool headb =
         ntc && gru_fused_bf16_supported(H) && classes % 8 == 0 &&
-        cvt2_supported(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
+        cvt2_supported(rin + oW, 0, H, sRi, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H) &&
         softmax_ce_bf16_supported(logits, s_log, bfreg(c->dlogb), clp, s_dlb, classes) &&
         cvt2_supported(bfreg(c->dlogb), 1, clp, s_dlb, nullptr, 0, 0, bfreg(c->dlogT), nrp, s_dlT, nrows, classes);
     // the layers' bf16 weight copies: all at the start (nothing but the replicas feeds them),
     // unless they were made before the step
     WeightCopies wc;
     role = HPSGD_ROLE_OTHER;
-    TRY(weight_copies(c, rin, sR, k0, groups, ws, s, !prepared, false, wc));
+    TRY(weight_copies(c, rin, sRi, k0, own_set ? 1 : groups, ws, s, !prepared, false, wc));
     // ---- forward
     const float* lin = (const float*)x;
     long s_lin = (long)TB * d.input;
@@ -673,7 +679,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     if (lm) {
       float* xe = reg(c->xe);
       role = HPSGD_ROLE_EMBED;
-      HIP_TRY(launch_embed_fwd(rin + c->eoff(c->i_embed), sR, tok, TB, xe, (long)c->xe.stride, TB,
+      HIP_TRY(launch_embed_fwd(rin + c->eoff(c->i_embed), sRi, tok, TB, xe, (long)c->xe.stride, TB,
                                d.embed, groups, s));
       lin = xe;
       s_lin = (long)c->xe.stride;
@@ -720,7 +726,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           HIP_TRY(launch_fill_zero(reg(c->hx), gru_persist_exchange_words(B, H), c->hx.stride, groups, s));
       }
       const float* Whh = rin + c->eoff(c->lidx[l].whh);
-      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
+      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sRi & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
       const bool persist = fused && use_persist;
       // a narrow layer input: the resident-weight kernel does the input projection itself
@@ -729,7 +735,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                          (s_lin & 3) == 0 && ((uintptr_t)Wih0 & 15) == 0;
       if (!xproj) {
         const float* Wih = rin + c->eoff(c->lidx[l].wih);
-        NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sR};
+        NtView va{lin, 0, width, s_lin}, vb{Wih, 0, width, sRi};
         // bf16 precision: both operands as row-major bf16 copies (the layer below wrote its
         // h in bf16; the layer-0 input and W_ih are rounded here, the input also transposed
         // for the weight-gradient GEMM)
@@ -763,8 +769,8 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           head_early = true;
         }
         role = HPSGD_ROLE_GEMM_INPUT;
-        TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sR, 1, gx, 3 * H, s_gx,
-                  EPI_BIAS, rin + c->eoff(c->lidx[l].bih), sR, va, vb));
+        TRY(gemm2(s, groups, bf, TB, 3 * H, width, lin, width, s_lin, 0, Wih, width, sRi, 1, gx, 3 * H, s_gx,
+                  EPI_BIAS, rin + c->eoff(c->lidx[l].bih), sRi, va, vb));
         if (early && hipStreamWaitEvent(s, c->ev_join, 0) != hipSuccess) return HPSGD_EHIP;
       }
       // bf16 path: bf16 copy of W_hh (kept in the W_hh^T region, which the forward pass does
@@ -793,7 +799,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       c->timer_nested = loop_fwd.active() && (fused || fused_b);
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, reg(c->hx),
+        HIP_TRY(launch_gru_fwd_persist(Whh, rin + c->eoff(c->lidx[l].bhh), sRi, gx, s_gx, hs, s_hs, reg(c->hx),
                                        (long)c->hx.stride, sv, s_sv, B, H, T,
                                        groups, psync, pbase, c->spin_limit, xproj ? lin : nullptr, s_lin, width,
                                        Wih0, rin + c->eoff(c->lidx[l].bih), c->device_scope, &ticket_launches, s));
@@ -804,7 +810,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       if (persist_b) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
-        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx, s_gx, hs, s_hs, hb, s_hb,
+        HIP_TRY(launch_gru_fwd_persist_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sRi, gx, s_gx, hs, s_hs, hb, s_hb,
                                             bfreg(c->hx), 2 * (long)c->hx.stride, sv, s_sv, hT, TB1p, s_hT, B, H, T, groups,
                                             psync, pbase, c->spin_limit, c->device_scope, &ticket_launches, s));
         pbase += (unsigned)T * gru_persist_bf16_count_per_step(H);
@@ -814,7 +820,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       for (int t = 0; t < T && !persist && !persist_b; ++t) {
         role = HPSGD_ROLE_GEMM_REC_FWD;
         if (fused_b) {
-          HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sR, gx + (size_t)t * B * 3 * H,
+          HIP_TRY(launch_gru_fwd_step_bf16(wb, s_wb, rin + c->eoff(c->lidx[l].bhh), sRi, gx + (size_t)t * B * 3 * H,
                                            s_gx, hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
                                            hb + (size_t)t * B * H, hb + (size_t)(t + 1) * B * H, s_hb,
                                            sv + (size_t)t * B * 4 * H, s_sv,
@@ -823,13 +829,13 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           continue;
         }
         if (fused) {
-          HIP_TRY(launch_gru_fwd_step(Whh, rin + c->eoff(c->lidx[l].bhh), sR, gx + (size_t)t * B * 3 * H, s_gx,
+          HIP_TRY(launch_gru_fwd_step(Whh, rin + c->eoff(c->lidx[l].bhh), sRi, gx + (size_t)t * B * 3 * H, s_gx,
                                       hs + (size_t)t * B * H, hs + (size_t)(t + 1) * B * H, s_hs,
                                       sv + (size_t)t * B * 4 * H, s_sv, B, H, groups, s));
           continue;
         }
-        TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0, Whh, H, sR, 1, gh, 3 * H,
-                 s_gh, EPI_BIAS, rin + c->eoff(c->lidx[l].bhh), sR));
+        TRY(gemm(s, groups, bf, B, 3 * H, H, hs + (size_t)t * B * H, H, s_hs, 0, Whh, H, sRi, 1, gh, 3 * H,
+                 s_gh, EPI_BIAS, rin + c->eoff(c->lidx[l].bhh), sRi));
         role = HPSGD_ROLE_CELL_FWD;
         HIP_TRY(launch_gru_cell_fwd(gx + (size_t)t * B * 3 * H, s_gx, gh, s_gh, hs + (size_t)t * B * H,
                                     hs + (size_t)(t + 1) * B * H, s_hs, sv + (size_t)t * B * 4 * H,
@@ -856,15 +862,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         HIP_TRY(launch_cvt2(head_src + oW, 0, H, 0, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             1, s));
       } else if (!prepared) {
-        HIP_TRY(launch_cvt2(rin + oW, 0, H, sR, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
+        HIP_TRY(launch_cvt2(rin + oW, 0, H, sRi, bfreg(c->wob), H, s_wob, bfreg(c->woT), clp, s_woT, classes, H,
                             groups, s));
       }
       const long s_hb = 2 * (long)c->hb.stride;
       const NtView va{(const __bf16*)reg(c->hb) + (size_t)(lm ? B : T * B) * H, 1, H, s_hb};
       const NtView vb{bfreg(c->wob), 1, H, s_wob};
       role = HPSGD_ROLE_GEMM_HEAD;
-      TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
-                s_log, EPI_BIAS, rin + ob, sR, va, vb));
+      TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sRi, 1, logits, classes,
+                s_log, EPI_BIAS, rin + ob, sRi, va, vb));
       role = HPSGD_ROLE_LOSS;
       // the head's bias gradient: column sums of the unrounded logit gradient, per block of rows
       // in the loss kernel, added up below (else recomputed from the logits in a pass of its own)
@@ -922,10 +928,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         const bool nested = c->timer_nested;
         c->timer_nested = c->timer_nested || pair.active();
         // (bf16 views only: the fp32 head matrix may be updated in place by the GEMM beside this one)
-        TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, lm ? dx : D, H,
+        TRY(gemm2(s, groups, bf, nrows, H, classes, logits, classes, s_log, 0, rin + oW, H, sRi, 0, lm ? dx : D, H,
                   lm ? s_dx : s_D, EPI_STORE, nullptr, 0, vdl, vwT, 0.f, true));
         TRY(gemm2(side_by_side ? c->aux : s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top,
-                  0, wt.C, H, wt.sC, wt.epi, wt.aux, sR, vdT, vhT, lr));
+                  0, wt.C, H, wt.sC, wt.epi, wt.aux, sRi, vdT, vhT, lr));
         if (side_by_side) {
           const int saved_role = role;
           role = HPSGD_ROLE_OTHER;
@@ -943,22 +949,22 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       role = HPSGD_ROLE_GEMM_HEAD;
       TimerScope ts_(c, role, s);
       if (acc) {
-        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sR, y, nrows, logits, s_log, rowloss,
+        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sRi, y, nrows, logits, s_log, rowloss,
                                 (long)c->rowloss.stride, D, s_D, grad + oW, grad + ob, sG, lr, 0, loss_out, nrows,
                                 classes, H, groups, s));
       } else {
         fused_commit[c->i_head_w] = 1;
         fused_commit[c->i_head_b] = 1;
-        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sR, y, nrows, logits, s_log, rowloss,
+        HIP_TRY(launch_cls_head(feats, s_top, rin + oW, rin + ob, sRi, y, nrows, logits, s_log, rowloss,
                                 (long)c->rowloss.stride, D, s_D, rout + oW, rout + ob, sR, lr, 1, loss_out, nrows,
                                 classes, H, groups, s));
       }
     } else {
       role = HPSGD_ROLE_GEMM_HEAD;
       {
-        const NtView va{feats, 0, H, s_top}, vb{rin + oW, 0, H, sR};
-        TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sR, 1, logits, classes,
-                  s_log, EPI_BIAS, rin + ob, sR, va, vb));
+        const NtView va{feats, 0, H, s_top}, vb{rin + oW, 0, H, sRi};
+        TRY(gemm2(s, groups, bf, nrows, classes, H, feats, H, s_top, 0, rin + oW, H, sRi, 1, logits, classes,
+                  s_log, EPI_BIAS, rin + ob, sRi, va, vb));
       }
       role = HPSGD_ROLE_LOSS;
       HIP_TRY(launch_softmax_ce(logits, s_log, y, nrows, logits, rowloss, (long)c->rowloss.stride, nrows,
@@ -975,7 +981,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                     2 * (long)c->hsT[l].stride, TB + B, H, true, groups, s));
         HIP_TRY(launch_cvt_bf16(logits, classes, s_log, bfreg(c->dlogT), nrp, 2 * (long)c->dlogT.stride, nrows,
                                 classes, true, groups, s));
-        HIP_TRY(launch_cvt_bf16(rin + oW, H, sR, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
+        HIP_TRY(launch_cvt_bf16(rin + oW, H, sRi, bfreg(c->woT), clp, 2 * (long)c->woT.stride, classes, H, true,
                                 groups, s));
       }
       role = HPSGD_ROLE_GEMM_HEAD;
@@ -988,15 +994,15 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         }
         const NtView vl{logits, 0, classes, s_log};
         if (lm) {
-          TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, dx, H, s_dx,
+          TRY(gemm2(s, groups, bf, TB, H, classes, logits, classes, s_log, 0, rin + oW, H, sRi, 0, dx, H, s_dx,
                     EPI_STORE, nullptr, 0, vl, vw));
         } else {
-          TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sR, 0, D, H, s_D,
+          TRY(gemm2(s, groups, bf, B, H, classes, logits, classes, s_log, 0, rin + oW, H, sRi, 0, D, H, s_D,
                     EPI_STORE, nullptr, 0, vl, vw));
         }
         const WgradTarget wt = wgrad_target(c->i_head_w);
         TRY(gemm2(s, groups, bf, classes, H, nrows, logits, classes, s_log, 1, feats, H, s_top, 0, wt.C, H, wt.sC,
-                  wt.epi, wt.aux, sR, va, vb, lr));
+                  wt.epi, wt.aux, sRi, va, vb, lr));
         HIP_TRY(launch_colsum(logits, classes, s_log, grad + ob, sG, nrows, classes, groups, s));
       }
     }
@@ -1005,11 +1011,20 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     bool embed_done = false;
     auto embed_grad = [&](hipStream_t st) -> int {
       const size_t oE = c->eoff(c->i_embed);
-      if (!acc && rin == rout) {
+      // clones: the table is written out first (one read, a write per worker), then updated like
+      // one that is already there
+      bool table_out = false;
+      if (!acc && cloned && aligned16(rin + oE) && aligned16(rout + oE) && (sR & 3) == 0 && groups <= HPSGD_KMAX) {
+        PtrPack pk;
+        for (int g = 0; g < groups; ++g) pk.p[g] = rout + oE + (size_t)g * sR;
+        if (launch_sync_all(rin + oE, pk, groups, nullptr, (size_t)d.vocab * d.embed, st) != hipSuccess) return HPSGD_EHIP;
+        table_out = true;
+      }
+      if (!acc && (rin == rout || table_out)) {
         // an update in place: only the rows of the tokens of the batch change, and their owners
         // write them; no gradient table to clear, fill and stream through the commit kernel
         fused_commit[c->i_embed] = 1;
-        if (launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, st, rin + oE, sR, lr) != hipSuccess)
+        if (launch_embed_bwd(dx, s_dx, tok, TB, rout + oE, sR, TB, d.embed, groups, st, rin + oE, sRi, lr) != hipSuccess)
           return HPSGD_EHIP;
       } else {
         if (launch_fill_zero(grad + oE, (size_t)d.vocab * d.embed, (size_t)sG, groups, st) != hipSuccess ||
@@ -1058,7 +1073,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       }
       float* dgx = gx;  // the gate pre-activation buffer is free once the layer's forward is done
       const float* Whh = rin + c->eoff(c->lidx[l].whh);
-      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sR & 3) == 0;
+      const bool fused = !bf && gru_fused_supported(H) && ((uintptr_t)Whh & 15) == 0 && (sRi & 3) == 0;
       const bool fused_b = bf && gru_fused_bf16_supported(H);
       float* wt = reg(c->wt);
       const long s_wt = (long)c->wt.stride;
@@ -1069,7 +1084,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       const long s_T = 2 * (long)c->dgxT.stride;
       if (fused && !(use_persist)) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_transpose(Whh, sR, wt, s_wt, 3 * H, H, groups, s));
+        HIP_TRY(launch_transpose(Whh, sRi, wt, s_wt, 3 * H, H, groups, s));
       }
       const void* wtb = wt;   // bf16 W_hh^T of this layer
       long s_wtb = 2 * s_wt;
@@ -1078,7 +1093,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         s_wtb = wstride(c->whhT[l]);
       } else if (fused_b) {
         role = HPSGD_ROLE_OTHER;
-        HIP_TRY(launch_cvt_bf16(Whh, H, sR, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
+        HIP_TRY(launch_cvt_bf16(Whh, H, sRi, wt, 3 * H, 2 * s_wt, 3 * H, H, true, groups, s));
       }
       // fp32 path with an auxiliary stream: the weight-gradient GEMMs of the time steps that
       // BPTT has already finished run on that stream beside the rest of the recurrence (the
@@ -1121,7 +1136,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       if (persist) {
         role = HPSGD_ROLE_GEMM_REC_BWD;
         // (the row-major gate gradients only when a later launch reads them)
-        HIP_TRY(launch_gru_bwd_persist(Whh, sR, (dwp && dbp) ? nullptr : dgh, reg(c->dghx), (long)c->dghx.stride, dgx, s_gx,
+        HIP_TRY(launch_gru_bwd_persist(Whh, sRi, (dwp && dbp) ? nullptr : dgh, reg(c->dghx), (long)c->dghx.stride, dgx, s_gx,
                                        D, s_D, d_zero, above, s_dx, sv, s_sv, hs, s_hs, B, H, T,
                                        T, 0, groups, psync, pbase, c->spin_limit, dwp, dbp, c->device_scope, &ticket_launches, s));
         c->last_dw += dwp ? 1 : 0;
@@ -1175,7 +1190,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                     dgh + (size_t)t * B * 3 * H, s_gx, B, H, groups, s));
         role = HPSGD_ROLE_GEMM_REC_BWD;
         if (t > 0)
-          TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0, Whh, H, sR, 0, D,
+          TRY(gemm(s, groups, bf, B, H, 3 * H, dgh + (size_t)t * B * 3 * H, 3 * H, s_gx, 0, Whh, H, sRi, 0, D,
                    H, s_D, EPI_ACCUM, nullptr, 0));
       }
       c->timer_nested = false;
@@ -1205,7 +1220,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (need_dx && wihT_ready[l]) {
           v_wihT = NtView{bfreg(c->wihTl[l]), 1, 3 * H, wstride(c->wihTl[l])};
         } else if (need_dx) {
-          HIP_TRY(launch_cvt_bf16(Wih, win, sR, bfreg(c->wihT), 3 * H, 2 * (long)c->wihT.stride, 3 * H, win, true,
+          HIP_TRY(launch_cvt_bf16(Wih, win, sRi, bfreg(c->wihT), 3 * H, 2 * (long)c->wihT.stride, 3 * H, win, true,
                                   groups, s));
           v_wihT = NtView{bfreg(c->wihT), 1, 3 * H, 2 * (long)c->wihT.stride};
         }
@@ -1221,7 +1236,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         if (dx_beside) {
           if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
             return HPSGD_EHIP;
-          TRY0(gemm2(c->aux, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx,
+          TRY0(gemm2(c->aux, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sRi, 0, dx, win, s_dx,
                      EPI_STORE, nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
           // the embedding rows need this product and nothing of the weight gradients beside it
           if (l == 0 && lm) {
@@ -1230,7 +1245,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           }
           if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
         } else {
-          TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sR, 0, dx, win, s_dx, EPI_STORE,
+          TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sRi, 0, dx, win, s_dx, EPI_STORE,
                     nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
         }
         above = dx;
@@ -1252,23 +1267,23 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                                c->dwip.stride == (size_t)kWihSplits * n_wih && (n_wih & 3) == 0 &&
                                ((uintptr_t)dgx & 15) == 0 && ((uintptr_t)layer_in & 15) == 0 && (s_gx & 3) == 0 &&
                                (s_layer_in & 3) == 0 && (win & 3) == 0 && ((uintptr_t)wi.C & 15) == 0 &&
-                               (wi.sC & 3) == 0 && (!wi.aux || (((uintptr_t)wi.aux & 15) == 0 && (sR & 3) == 0));
+                               (wi.sC & 3) == 0 && (!wi.aux || (((uintptr_t)wi.aux & 15) == 0 && (sRi & 3) == 0));
         if (split_wih) {
           float* parts = reg(c->dwip);
           TRY(gemm(s, groups, 0, 3 * H, win, TB / kWihSplits, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0,
                    parts, win, (long)n_wih, EPI_STORE, nullptr, 0, 0, 0.f, kWihSplits));
-          TRY0(queue_reduce(parts, kWihSplits, n_wih, wi.aux, (size_t)sR, wi.C, (size_t)wi.sC, wi.epi == EPI_COMMIT));
+          TRY0(queue_reduce(parts, kWihSplits, n_wih, wi.aux, (size_t)sRi, wi.C, (size_t)wi.sC, wi.epi == EPI_COMMIT));
         } else {
           TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
-                    wi.sC, wi.epi, wi.aux, sR, v_dgxT, v_xT, lr, persist_b));
+                    wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
         }
         const WgradTarget wh = wgrad_target(c->lidx[l].whh);
         if (dwp) {
-          TRY0(queue_reduce(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sR, wh.C, (size_t)wh.sC,
+          TRY0(queue_reduce(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sRi, wh.C, (size_t)wh.sC,
                            wh.epi == EPI_COMMIT));
         } else {
           TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
-                    wh.aux, sR, v_dghT, v_hsT, lr, persist_b));
+                    wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
         }
       }
       role = HPSGD_ROLE_GEMM_WGRAD;
@@ -1276,10 +1291,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         // the kernel that adds the partial sums applies the update too, when it can write the
         // replica with 16-byte accesses and the gradients are not accumulated as well
         const size_t ob_ih = c->eoff(c->lidx[l].bih);
-        if (!acc && (sR & 3) == 0 && ((uintptr_t)(rin + ob_ih) & 15) == 0 && ((uintptr_t)(rout + ob_ih) & 15) == 0) {
+        if (!acc && ((sR | sRi) & 3) == 0 && ((uintptr_t)(rin + ob_ih) & 15) == 0 && ((uintptr_t)(rout + ob_ih) & 15) == 0) {
           fused_commit[c->lidx[l].bih] = 1;
           fused_commit[c->lidx[l].bhh] = 1;
-          TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sR, rout + ob_ih, (size_t)sR, 1));
+          TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, rin + ob_ih, (size_t)sRi, rout + ob_ih, (size_t)sR, 1));
         } else {
           TRY0(queue_reduce(dbp, (B + 31) / 32, (size_t)6 * H, nullptr, 0, grad + ob_ih, (size_t)sG, 0));
         }
@@ -1312,10 +1327,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     while (e < c->entries.size() && !fused_commit[e]) ++e;
     const size_t hi = e < c->entries.size() ? c->entries[e].offset : c->P;
     if (acc)
-      HIP_TRY(launch_commit_acc(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, acc + lo, acc_stride, lr,
+      HIP_TRY(launch_commit_acc(rin + lo, (size_t)sRi, rout + lo, rstride, grad + lo, (size_t)sG, acc + lo, acc_stride, lr,
                                 groups, hi - lo, s));
     else
-      HIP_TRY(launch_commit(rin + lo, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
+      HIP_TRY(launch_commit(rin + lo, (size_t)sRi, rout + lo, rstride, grad + lo, (size_t)sG, lr, groups, hi - lo, s));
     c->last_commit_params += hi - lo;
   }
   if (abort_word) HIP_TRY(launch_poison_on_abort(abort_word, loss_out, groups, rout, sR, groups, s));
@@ -1441,6 +1456,23 @@ int hpsgd_local_step_all(hpsgd_ctx* ctx, const float* replicas_in, float* replic
   TRY0(check_step_args(ctx, replicas_in, replicas_out, replica_stride, ctx->K, x, y, workspace));
   return run_step(ctx, 0, ctx->K, replicas_in, replicas_out, replica_stride, x, y, lr, loss_out,
                   (float*)workspace, (hipStream_t)hip_stream);
+}
+
+int hpsgd_local_step_all_cloned(hpsgd_ctx* ctx, const float* source, float* replicas_out, size_t replica_stride,
+                                const void* x, const int32_t* y, float lr, float* loss_out, void* workspace,
+                                void* hip_stream) {
+  if (!ctx) return HPSGD_EINVAL;
+  // the output replicas alone are checked like those of a step in place, the source like a model
+  TRY0(check_step_args(ctx, replicas_out, replicas_out, replica_stride, ctx->K, x, y, workspace));
+  if (!source) return HPSGD_EINVAL;
+  if (!aligned16(source)) return HPSGD_EALIGN;
+  const size_t span = ((size_t)(ctx->K - 1) * replica_stride + ctx->P) * sizeof(float);
+  const size_t pbytes = ctx->P * sizeof(float);
+  if (overlaps(source, pbytes, replicas_out, span) ||
+      overlaps(source, pbytes, workspace, ctx->ws_floats * sizeof(float)))
+    return HPSGD_EALIAS;
+  return run_step(ctx, 0, ctx->K, source, replicas_out, replica_stride, x, y, lr, loss_out, (float*)workspace,
+                  (hipStream_t)hip_stream, nullptr, 0, true);
 }
 
 int hpsgd_local_step_all_static(hpsgd_ctx* ctx, const float* replicas_in, float* replicas_out,

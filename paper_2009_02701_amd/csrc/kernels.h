@@ -62,12 +62,12 @@ hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, 
 // merge, then sync of the same replicas and snapshot, in one pass
 hipError_t launch_merge_sync(float* global, const PtrPack& replicas, float* snapshot, int K, size_t P,
                              hipStream_t s);
-// out[k] = in[k] - lr * grad[k] for K strided slices of P floats
-hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
+// out[k] = in[k] - lr * grad[k] for K strided slices of P floats (in_stride 0: one model for all)
+hipError_t launch_commit(const float* in, size_t in_stride, float* out, size_t stride, const float* grad,
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s);
 // p[g*stride + i] = 0 for i < n (p 16-byte aligned, stride a multiple of 4)
-hipError_t launch_commit_acc(const float* in, float* out, size_t stride, const float* grad, size_t grad_stride,
-                             float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s);
+hipError_t launch_commit_acc(const float* in, size_t in_stride, float* out, size_t stride, const float* grad,
+                             size_t grad_stride, float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s);
 hipError_t launch_merge_grad(float* global, const PtrPack& accs, float lr, int K, size_t P, hipStream_t s);
 hipError_t launch_fill_zero(float* p, size_t n, size_t stride, int groups, hipStream_t s, float* extra = nullptr,
                             size_t n_extra = 0);

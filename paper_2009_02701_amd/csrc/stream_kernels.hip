@@ -185,12 +185,12 @@ hipError_t launch_merge_sync(float* global, const PtrPack& replicas, float* snap
 }
 
 // ---------------------------------------------------------------------------- commit
-// out[k][j] = in[k][j] - lr * grad[k][j]
+// out[k][j] = in[k][j] - lr * grad[k][j]  (in_stride 0: every worker starts from the one model `in`)
 __global__ void __launch_bounds__(kThreads)
-commit_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+commit_kernel(const float* in, size_t in_stride, float* out, size_t stride, const float* __restrict__ grad,
               size_t grad_stride, float lr, size_t n4, size_t P) {
   const int k = blockIdx.y;
-  const float* ink = in + (size_t)k * stride;
+  const float* ink = in + (size_t)k * in_stride;
   float* outk = out + (size_t)k * stride;
   const float* gk = grad + (size_t)k * grad_stride;
   const size_t step = (size_t)gridDim.x * kThreads;
@@ -212,27 +212,27 @@ commit_kernel(const float* in, float* out, size_t stride, const float* __restric
 
 // the same, one element per thread: for ranges that do not start on a 16-byte boundary
 __global__ void __launch_bounds__(kThreads)
-commit_scalar_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+commit_scalar_kernel(const float* in, size_t in_stride, float* out, size_t stride, const float* __restrict__ grad,
                      size_t grad_stride, float lr, size_t P) {
   const size_t k = blockIdx.y;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < P; i += (size_t)gridDim.x * kThreads)
-    out[k * stride + i] = in[k * stride + i] - lr * grad[k * grad_stride + i];
+    out[k * stride + i] = in[k * in_stride + i] - lr * grad[k * grad_stride + i];
 }
 
-hipError_t launch_commit(const float* in, float* out, size_t stride, const float* grad,
+hipError_t launch_commit(const float* in, size_t in_stride, float* out, size_t stride, const float* grad,
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
   KernelTimer kt(KID_COMMIT, 12.0 * (double)P * K, s);
-  if ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)grad) & 15) != 0 || ((stride | grad_stride) & 3) != 0) {
+  if ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)grad) & 15) != 0 || ((in_stride | stride | grad_stride) & 3) != 0) {
     size_t blocks = (P + kThreads - 1) / kThreads;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(commit_scalar_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, out, stride,
+    hipLaunchKernelGGL(commit_scalar_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, in_stride, out, stride,
                        grad, grad_stride, lr, P);
     return hipGetLastError();
   }
   const size_t n4 = P / 4;
   const int blocks = onepass_blocks(n4);
-  hipLaunchKernelGGL(commit_kernel, dim3(blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
+  hipLaunchKernelGGL(commit_kernel, dim3(blocks, K), dim3(kThreads), 0, s, in, in_stride, out, stride, grad,
                      grad_stride, lr, n4, P);
   return hipGetLastError();
 }
@@ -338,12 +338,12 @@ hipError_t launch_reduce_parts(const float* parts, int n_parts, size_t n, const 
 // out[k][j] = in[k][j] - lr * grad[k][j];  acc[k][j] += grad[k][j]  (Alg. 2: update the replica and
 // accumulate the gradient in one pass, 20 B/param)
 __global__ void __launch_bounds__(kThreads)
-commit_acc_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+commit_acc_kernel(const float* in, size_t in_stride, float* out, size_t stride, const float* __restrict__ grad,
                   size_t grad_stride, float* __restrict__ acc, size_t acc_stride, float lr, size_t P) {
   const size_t k = blockIdx.y;
   for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < P; i += (size_t)gridDim.x * kThreads) {
     const float g = grad[k * grad_stride + i];
-    out[k * stride + i] = in[k * stride + i] - lr * g;
+    out[k * stride + i] = in[k * in_stride + i] - lr * g;
     acc[k * acc_stride + i] += g;
   }
 }
@@ -351,10 +351,10 @@ commit_acc_kernel(const float* in, float* out, size_t stride, const float* __res
 // The same on 16-byte vectors, one per lane (all four buffers 16-byte aligned, strides multiples
 // of 4): three loads in flight per lane, every wave reads and writes 1 KiB contiguous per stream.
 __global__ void __launch_bounds__(kThreads)
-commit_acc4_kernel(const float* in, float* out, size_t stride, const float* __restrict__ grad,
+commit_acc4_kernel(const float* in, size_t in_stride, float* out, size_t stride, const float* __restrict__ grad,
                    size_t grad_stride, float* __restrict__ acc, size_t acc_stride, float lr, size_t n4, size_t P) {
   const size_t k = blockIdx.y;
-  const f4v* in4 = reinterpret_cast<const f4v*>(in + k * stride);
+  const f4v* in4 = reinterpret_cast<const f4v*>(in + k * in_stride);
   f4v* out4 = reinterpret_cast<f4v*>(out + k * stride);
   const f4v* g4 = reinterpret_cast<const f4v*>(grad + k * grad_stride);
   f4v* a4 = reinterpret_cast<f4v*>(acc + k * acc_stride);
@@ -369,27 +369,27 @@ commit_acc4_kernel(const float* in, float* out, size_t stride, const float* __re
     const size_t j = n4 * 4 + threadIdx.x;
     if (j < P) {
       const float g = grad[k * grad_stride + j];
-      out[k * stride + j] = in[k * stride + j] - lr * g;
+      out[k * stride + j] = in[k * in_stride + j] - lr * g;
       acc[k * acc_stride + j] += g;
     }
   }
 }
 
-hipError_t launch_commit_acc(const float* in, float* out, size_t stride, const float* grad, size_t grad_stride,
-                             float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s) {
+hipError_t launch_commit_acc(const float* in, size_t in_stride, float* out, size_t stride, const float* grad,
+                             size_t grad_stride, float* acc, size_t acc_stride, float lr, int K, size_t P, hipStream_t s) {
   if (P == 0) return hipSuccess;
   const bool vec = ((((uintptr_t)in | (uintptr_t)out | (uintptr_t)grad | (uintptr_t)acc) & 15) == 0) &&
-                   ((stride | grad_stride | acc_stride) & 3) == 0 && P >= 4;
+                   ((in_stride | stride | grad_stride | acc_stride) & 3) == 0 && P >= 4;
   KernelTimer kt(KID_COMMIT_ACC, 20.0 * (double)P * K, s);
   if (vec) {
     const size_t n4 = P / 4;
-    hipLaunchKernelGGL(commit_acc4_kernel, dim3(onepass_blocks(n4), K), dim3(kThreads), 0, s, in, out, stride, grad,
+    hipLaunchKernelGGL(commit_acc4_kernel, dim3(onepass_blocks(n4), K), dim3(kThreads), 0, s, in, in_stride, out, stride, grad,
                        grad_stride, acc, acc_stride, lr, n4, P);
     return hipGetLastError();
   }
   size_t blocks = (P + kThreads - 1) / kThreads;
   if (blocks > 8192) blocks = 8192;
-  hipLaunchKernelGGL(commit_acc_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, out, stride, grad,
+  hipLaunchKernelGGL(commit_acc_kernel, dim3((unsigned)blocks, K), dim3(kThreads), 0, s, in, in_stride, out, stride, grad,
                      grad_stride, acc, acc_stride, lr, P);
   return hipGetLastError();
 }

@@ -23,7 +23,12 @@ from . import binding as hb
 
 class Trainer:
     def __init__(self, cfg: dict, init_params: dict, shards: list, orders: list, device="cuda",
-                 aux_stream=True, prepare=False):
+                 aux_stream=True, prepare=False, implicit_clone=True):
+        # Overlapped schedule: "make replica" (Alg. 2) is not a copy of its own.  The synchronising
+        # side only takes the snapshot of the merged global model; the local step reads its
+        # parameters from that one snapshot and writes the K updated replicas
+        # (hpsgd_local_step_all_cloned): the same bits, 4 (K + 1) bytes per parameter less per round.
+        self.implicit_clone = implicit_clone
         # hpsgd_prepare_replicas behind every clone on the synchronising side.  Off by default: on
         # MI355X the copies then run beside the training stream's resident-weight launches, whose
         # chains of waits slow down by more than the copies cost (config 3: 3.37 -> 3.60 ms per round)
@@ -92,6 +97,17 @@ class Trainer:
             hb.gather_batch_all(tok, idx, T, 1, xb, row_elems=T + 1, stream=stream)
             hb.gather_batch_all([t[1:] for t in tok], idx, T, 1, yb, row_elems=T + 1, stream=stream)
 
+    def local_step_cloned(self, gen: int, lr: float, stream=None, ws=0):
+        """The local step of generation `gen` whose replicas are still clones of its snapshot."""
+        if self.ws[ws] is None:
+            self.ws[ws] = self.ctx.new_workspace(self.dev)
+        self.ctx.local_step_all_cloned(self.S[gen][:self.P], self.R[gen], self.xb, self.yb, lr, self.loss,
+                                       self.ws[ws], stream=stream)
+
+    def snapshot(self, gen: int, stream=None):
+        """S[gen] = global model (hpsgd_sync_all with no replica to write)."""
+        hb.sync_all(self.G[:self.P], [], self.S[gen][:self.P], stream=stream)
+
     def local_step(self, gen: int, lr: float, stream=None, ws=0):
         if self.ws[ws] is None:
             self.ws[ws] = self.ctx.new_workspace(self.dev)
@@ -146,10 +162,17 @@ class Trainer:
         st.wait_stream(torch.cuda.current_stream())
         step = 0
         for _ in range(rounds):
-            self.sync_all(0, st)
-            for _ in range(gamma):
+            # (the clone is implicit here too: the first local step after a synchronisation reads the snapshot)
+            if self.implicit_clone:
+                self.snapshot(0, st)
+            else:
+                self.sync_all(0, st)
+            for i in range(gamma):
                 self.gather(step, st)
-                self.local_step(0, lr, st)
+                if self.implicit_clone and i == 0:
+                    self.local_step_cloned(0, lr, st)
+                else:
+                    self.local_step(0, lr, st)
                 if record_loss:
                     with torch.cuda.stream(st):
                         self.losses.append(self.loss.clone())
@@ -171,6 +194,25 @@ class Trainer:
             if record_loss:
                 with torch.cuda.stream(st):
                     self.losses.append(self.loss.clone())
+        st.synchronize()
+
+    def s_train_side(self, lr: float, steps: int):
+        """The training side of an overlapped round by itself, as that round runs it (gather, the
+        operand copies if they are made on this stream, the local step from the snapshot), with
+        nothing on the synchronising side: a time reference, not a training schedule."""
+        st = self.stream_a
+        st.wait_stream(torch.cuda.current_stream())
+        if self.implicit_clone:
+            self.snapshot(0, st)
+        else:
+            self.sync_all(0, st)
+        for step in range(steps):
+            self.gather(step, st)
+            if self.implicit_clone:
+                self.prepare_clones_on_training_stream(0, st)
+                self.local_step_cloned(0, lr, st)
+            else:
+                self.local_step(0, lr, st)
         st.synchronize()
 
     def s_ovl(self, lr: float, rounds: int, record_loss=True, single_stream=False):
@@ -259,7 +301,10 @@ class Trainer:
         self._sa = self.stream_a
         self._sb = self.stream_a if single_stream else self.stream_b
         self._sa.wait_stream(torch.cuda.current_stream())
-        self.sync_all(0, self._sa)
+        if self.implicit_clone:
+            self.snapshot(0, self._sa)
+        else:
+            self.sync_all(0, self._sa)
         self._g = 0
         self._ev_a = torch.cuda.Event()
         self._ev_b = torch.cuda.Event()
@@ -273,15 +318,16 @@ class Trainer:
         # ... and clone the global model into that generation for the next round ("make replica"):
         # it depends on the merge only, so it sits behind it on the synchronising side and off
         # the training stream's path; merge and clone of one generation are one pass (the same bits)
+        clone = self.snapshot if self.implicit_clone else self.sync_all
         if self._have_delta:
             sb.wait_event(self._ev_a)
-            if self.fused_merge_sync:
+            if self.fused_merge_sync and not self.implicit_clone:
                 self.merge_sync(1 - g, sb)
             else:
                 self.merge(1 - g, sb)
-                self.sync_all(1 - g, sb)
+                clone(1 - g, sb)
         else:
-            self.sync_all(1 - g, sb)
+            clone(1 - g, sb)
         # ... and the operand copies of its weights that the next local step would make at its
         # start (bf16 configurations), in that generation's own workspace
         self.prepare(1 - g, sb)
@@ -289,7 +335,10 @@ class Trainer:
         # training side (stream A): this round's local step on generation g
         self.gather(t, sa)
         self.prepare_clones_on_training_stream(g, sa)
-        self.local_step(g, lr, sa, ws=g)
+        if self.implicit_clone:
+            self.local_step_cloned(g, lr, sa, ws=g)
+        else:
+            self.local_step(g, lr, sa, ws=g)
         if record_loss:
             with torch.cuda.stream(sa):
                 self.losses.append(self.loss.clone())

@@ -169,6 +169,19 @@ def test_local_step_rejects_bad_arguments_before_launch():
     assert prep(R, 5132, R) == 4
     assert prep(R, 5132, W) == 0                                         # fp32: nothing to prepare, nothing launched
     assert hb.load_library().hpsgd_strerror(4) == b"buffers overlap"
+    # clone + step as one call: the source is one model of P floats beside the K output replicas
+    G = 0x080000
+    cl = lambda g, o, stride, x, y, w: lib.hpsgd_local_step_all_cloned(ctx._h, vp(g), vp(o), stride, vp(x), vp(y),
+                                                                      0.1, None, vp(w), None)
+    assert lib.hpsgd_local_step_all_cloned(None, vp(G), vp(O), 5132, vp(X), vp(Y), 0.1, None, vp(W), None) == 1
+    assert cl(0, O, 5132, X, Y, W) == 1                                   # no source
+    assert cl(G, 0, 5132, X, Y, W) == 1                                   # no output
+    assert cl(G + 4, O, 5132, X, Y, W) == 3                               # misaligned source
+    assert cl(G, O, 5130, X, Y, W) == 3 and cl(G, O, 5000, X, Y, W) == 3  # output stride
+    assert cl(O, O, 5132, X, Y, W) == 4                                   # the source is a replica being written
+    assert cl(O + 4 * 5132, O, 5132, X, Y, W) == 4                        # ... any of them
+    assert cl(W + 256, O, 5132, X, Y, W) == 4                             # the source inside the workspace
+    assert cl(G, O, 5132, X, Y, 0) == 5
 
 
 def test_kernel_timer_entry_points_on_the_host():

@@ -285,6 +285,63 @@ def test_step_into_other_buffers_equals_step_in_place(name):
     assert torch.equal(loss_o, tr.loss)
 
 
+CLONED = ["tiny_gru", "gru_cls_ragged", "gru_cls_2layer", "lm_small_fp32", "lm_tiles_fp32", "mlp_ragged", "mlp_tiles",
+          "gru_cls_K1", "lm_small_bf16", "lm_nt_bf16", "lm_nt_bf16_tiles", "lm_nt_bf16_h384", "cls_nt_bf16", "mlp_bf16",
+          "lm_nt_bf16_K1", "gru_cls", "mlp", "gru_lm"]
+
+
+@pytest.mark.parametrize("prepare", [False, True])
+@pytest.mark.parametrize("name", CLONED)
+def test_clone_and_step_as_one_call_equals_clone_then_step(name, prepare):
+    """hpsgd_local_step_all_cloned (Alg. 2 "make replica" + local step, the K clones never written
+    out): the same bits as hpsgd_sync_all followed by the step in place - every parameter of every
+    worker (the output starts as NaN), the losses - and the source stays as it was; with and
+    without hpsgd_prepare_clones in front; a second step, in place on what the first wrote, too."""
+    cfg = SMALL[name] if name in SMALL else BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, batch_fn = workload(cfg)
+    tr = harness.Trainer(cfg, init, shards, orders, device=DEV)
+    lr = cfg["lr"]
+    tr.sync_all(0)            # R[0] = clones of G, S[0] = G
+    tr.gather(0)
+    torch.cuda.synchronize()
+    ref = tr.R[0]
+    l_ref, l_got = torch.zeros(2, cfg["K"], device=DEV), torch.zeros(2, cfg["K"], device=DEV)
+    ws_ref, ws = tr.ctx.new_workspace(DEV), tr.ctx.new_workspace(DEV)
+    for i in range(2):
+        tr.ctx.local_step_all(ref, ref, tr.xb, tr.yb, lr, l_ref[i], ws_ref)
+    src = tr.S[0][:tr.P]
+    before = src.clone()
+    got = torch.full_like(tr.R[1], float("nan"))
+    if prepare:
+        tr.ctx.prepare_clones(src, got, ws)
+    tr.ctx.local_step_all_cloned(src, got, tr.xb, tr.yb, lr, l_got[0], ws)
+    tr.ctx.local_step_all(got, got, tr.xb, tr.yb, lr, l_got[1], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(src, before)
+    assert torch.equal(got[:, :tr.P], ref[:, :tr.P])
+    assert torch.equal(l_got, l_ref)
+
+
+@pytest.mark.parametrize("name", ["tiny_gru", "gru_cls_tiles", "mlp_tiles", "lm_tiles_fp32", "lm_nt_bf16_tiles", "lm_nt_bf16_h384",
+                                  "gru_cls", "mlp", "gru_lm"])
+def test_overlapped_schedule_without_written_out_clones_changes_no_bit(name):
+    """The overlapped schedule whose synchronising side takes only the snapshot and whose local
+    step reads it (hpsgd_local_step_all_cloned) against the one that writes K clones and steps in
+    place: the same global model and losses, bit for bit."""
+    cfg = SMALL[name] if name in SMALL else BF16[name] if name in BF16 else wl.CONFIGS[name]
+    init, shards, orders, _ = workload(cfg)
+    outs = []
+    for implicit in (False, True):
+        tr = harness.Trainer(cfg, init, shards, orders, device=DEV, implicit_clone=implicit,
+                             prepare="clones_a" if cfg.get("prec") == "bf16" else False)
+        tr.s_ovl(cfg["lr"], rounds=3)
+        torch.cuda.synchronize()
+        outs.append((tr.G.clone(), torch.stack(tr.losses)))
+        del tr
+    assert torch.isfinite(outs[0][0]).all()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+
+
 @pytest.mark.parametrize("name", ["lm_nt_bf16", "lm_nt_bf16_tiles", "cls_nt_bf16", "lm_small_bf16", "tiny_gru"])
 def test_prepared_step_equals_unprepared_step(name):
     """hpsgd_prepare_replicas: the step that follows it gives the same bits as a step that makes
