@@ -35,15 +35,15 @@ KIB = 1024.0
 MEASURED_TRAFFIC_BYTES = {
     "gru_cls": {"gru_bwd_persist_kernel": (2.0 * 91903.0 + 150171.0) * KIB,
                 "gru_fwd_persist_kernel": (2.0 * 26935.9 + 107529.2) * KIB},
-    # the 192 x 256 form runs three products per round: the logits (671 MB) and two input gradients
+    # the 192 x 256 form runs three products per round: the logits (679 MB) and two input gradients
     # (head and top layer; both launch 192 tiles and average 262 MB)
     "gru_lm": {"gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>":
-                   ((2.0 * 150533.5 + 354642.0) + 2 * (2.0 * 109983.5 + 35862.3)) * KIB / 3,
-               "gru_bwd_persist_bf16_kernel": (2.0 * 161767.9 + 240185.6) * KIB,
-               "gru_fwd_persist_bf16_kernel": (2.0 * 89353.6 + 238893.1) * KIB,
-               "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>": (2.0 * 297960.8 + 326058.7) * KIB,
-               "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>": (2.0 * 95687.1 + 100397.9) * KIB,
-               "softmax_ce_bf16_rows_kernel": (2.0 * 177861.0 + 194819.7) * KIB},
+                   ((2.0 * 153894.5 + 355321.4) + 2 * (2.0 * 109983.5 + 35879.3)) * KIB / 3,
+               "gru_bwd_persist_bf16_kernel": (2.0 * 161238.2 + 240383.4) * KIB,
+               "gru_fwd_persist_bf16_kernel": (2.0 * 89352.9 + 238874.5) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 4, 2, 2>": (2.0 * 296087.8 + 325485.9) * KIB,
+               "gemm_bf16_dlx_kernel<true, 2, 4, 3, 2, 2>": (2.0 * 95253.1 + 100010.3) * KIB,
+               "softmax_ce_bf16_rows_kernel": (2.0 * 177839.5 + 194819.1) * KIB},
     "mlp": {},
 }
 
