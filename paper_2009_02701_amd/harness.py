@@ -259,8 +259,11 @@ class Trainer:
         the status the host reads is the one the device is in."""
         sa, sb = self.stream_a, self.stream_b
         sa.wait_stream(torch.cuda.current_stream())
-        self.sync_all(0, sa)
-        self.sync_all(1, sa)
+        # (implicit clones: a generation's first local step after its synchronisation reads the snapshot)
+        clone = self.snapshot if self.implicit_clone else self.sync_all
+        clone(0, sa)
+        clone(1, sa)
+        fresh = [self.implicit_clone, self.implicit_clone]
         g, n, counts = 0, 0, []
         busy = None  # event: the synchronising side's running job
         done = [torch.cuda.Event(), torch.cuda.Event()]
@@ -268,7 +271,11 @@ class Trainer:
             if e >= 2:
                 done[e % 2].synchronize()
             self.gather(e, sa)
-            self.local_step(g, lr, sa, ws=g)
+            if fresh[g]:
+                self.local_step_cloned(g, lr, sa, ws=g)
+                fresh[g] = False
+            else:
+                self.local_step(g, lr, sa, ws=g)
             n += 1
             if record_loss:
                 with torch.cuda.stream(sa):
@@ -278,11 +285,12 @@ class Trainer:
                 sb.wait_event(done[e % 2])
                 if sync_delay_us:
                     hb.delay_us(sync_delay_us, sb)
-                if self.fused_merge_sync:
+                if self.fused_merge_sync and not self.implicit_clone:
                     self.merge_sync(g, sb)
                 else:
                     self.merge(g, sb)
-                    self.sync_all(g, sb)
+                    clone(g, sb)
+                fresh[g] = self.implicit_clone
                 self.prepare(g, sb)
                 busy = torch.cuda.Event()
                 busy.record(sb)
