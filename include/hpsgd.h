@@ -270,7 +270,8 @@ int hpsgd_merge_grad(float *global, const float *const *grad_accs, float lr, int
  * replica <- global, bit-exact. */
 int hpsgd_sync_replica(const float *global, float *replica, size_t P, void *hip_stream);
 /* One pass over `global` that writes all K replicas (HOST array of DEVICE pointers) and,
- * if not NULL, the snapshot. */
+ * if not NULL, the snapshot.  0 <= K <= HPSGD_MAX_WORKERS; K = 0 writes the snapshot alone
+ * (what a round needs when its local step is hpsgd_local_step_all_cloned). */
 int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *snapshot,
                    size_t P, void *hip_stream);
 
