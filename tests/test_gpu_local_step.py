@@ -53,6 +53,8 @@ BF16 = {
     # H > 512 (four): the register-resident forms that the full-size language model runs
     "lm_nt_bf16_h384": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=64, hidden=384, seq_len=6, batch=32, K=4),
     "lm_nt_bf16_h1024": wl.scaled(wl.CONFIGS["gru_lm"], vocab=264, embed=64, hidden=1024, seq_len=4, batch=16, K=2),
+    # more GRU weight matrices than one launch of the packed copy kernel takes (8): the rest go one by one
+    "lm_nt_bf16_5layer": wl.scaled(wl.CONFIGS["gru_lm"], layers=5, vocab=80, embed=32, hidden=64, seq_len=4, batch=8, K=2),
     # degenerate sizes on the bf16 path
     "lm_nt_bf16_T1": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=1, batch=8, K=2),
     "lm_nt_bf16_K1": wl.scaled(wl.CONFIGS["gru_lm"], vocab=80, embed=32, hidden=64, seq_len=5, batch=8, K=1),
@@ -285,7 +287,7 @@ def test_step_into_other_buffers_equals_step_in_place(name):
     assert torch.equal(loss_o, tr.loss)
 
 
-CLONED = ["tiny_gru", "gru_cls_ragged", "gru_cls_2layer", "lm_small_fp32", "lm_tiles_fp32", "mlp_ragged", "mlp_tiles",
+CLONED = ["lm_nt_bf16_5layer", "tiny_gru", "gru_cls_ragged", "gru_cls_2layer", "lm_small_fp32", "lm_tiles_fp32", "mlp_ragged", "mlp_tiles",
           "gru_cls_K1", "lm_small_bf16", "lm_nt_bf16", "lm_nt_bf16_tiles", "lm_nt_bf16_h384", "cls_nt_bf16", "mlp_bf16",
           "lm_nt_bf16_K1", "gru_cls", "mlp", "gru_lm"]
 
