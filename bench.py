@@ -88,13 +88,14 @@ def samples_per_round(cfg):
     return cfg["K"] * cfg["batch"] * (cfg["seq_len"] if cfg["kind"] == "gru_lm" else 1)
 
 
-def make_trainer(wl, harness, name, dev, prepare=False):
+def make_trainer(wl, harness, name, dev, prepare=False, implicit_clone=True):
     cfg = wl.CONFIGS[name]
     K = cfg["K"]
     init = wl.init_params(cfg)
     shards = [wl.make_shard(cfg, k) for k in range(K)]
     orders = [wl.batch_order(cfg, k) for k in range(K)]
-    return cfg, init, shards, harness.Trainer(cfg, init, shards, orders, device=dev, prepare=prepare)
+    return cfg, init, shards, harness.Trainer(cfg, init, shards, orders, device=dev, prepare=prepare,
+                                              implicit_clone=implicit_clone)
 
 
 def timed_rounds(torch, tr, lr, step, n):
@@ -108,9 +109,9 @@ def timed_rounds(torch, tr, lr, step, n):
     return time.perf_counter() - t0, step
 
 
-def quick_workload(torch, wl, harness, name, dev, rounds=100, warmup=10):
+def quick_workload(torch, wl, harness, name, dev, rounds=100, warmup=10, **trainer_args):
     """Throughput of another configuration in the same overlapped schedule (an extra key of the line)."""
-    cfg, _, _, tr = make_trainer(wl, harness, name, dev)
+    cfg, _, _, tr = make_trainer(wl, harness, name, dev, **trainer_args)
     tr.ovl_begin()
     _, step = timed_rounds(torch, tr, cfg["lr"], 0, warmup)
     el, step = timed_rounds(torch, tr, cfg["lr"], step, rounds)
@@ -266,7 +267,7 @@ def main():
                "all_hidden_would_be": (t_a + t_b) / max(t_a, t_b),
                "hidden_fraction_of_sync": max(0.0, min(1.0, (t_a + t_b - t_ovl) / t_b)), "rounds": n_ov}
 
-    async_driver, compare, forms, others, probe = None, None, None, None, None
+    async_driver, compare, forms, others, probe, written_out = None, None, None, None, None, None
     if not args.no_extras:
         # ---- the asynchronous driver (Alg. 2 + Alg. 3 with the status check at run time): the same
         # kernels, the number of local steps per synchronisation decided by whether stream B is idle;
@@ -329,6 +330,12 @@ def main():
         # ---- the other single-GPU configurations in the same schedule (parity cases; extra keys)
         others = {name: quick_workload(torch, wl, harness, name, dev)
                   for name in ("gru_cls", "mlp", "gru_lm") if name != args.workload}
+        torch.cuda.empty_cache()
+        # ---- this workload with "make replica" as a copy of its own (hpsgd_sync_all writes the K clones,
+        # the local step runs in place): the same bits as the headline's schedule, more bytes
+        written_out = quick_workload(torch, wl, harness, args.workload, dev, implicit_clone=False,
+                                     prepare=False if args.prepare == "off" else args.prepare)
+        written_out.pop("workload")
         torch.cuda.empty_cache()
 
     # ---- merge-only stress (config 5): merge + sync of 100M floats, K = 8, pure HBM streaming
@@ -444,9 +451,13 @@ def main():
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if cfg.get("prec") == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "global_batch": K * B,
-                   "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers"},
+                   "seq_len": cfg.get("seq_len"), "parallelism": f"1 GPU, K={K} simulated workers",
+                   "make_replica": "part of the local step: it reads the one model the replicas are clones of and "
+                                   "writes all K updated replicas (hpsgd_local_step_all_cloned; bit-identical to "
+                                   "hpsgd_sync_all + the step in place, which `written_out_clones` times)"},
         "roofline": roofline, "cpu_baseline": cpu, "ms_per_step_spread": spread, "overlap": overlap,
         "kernels": kernels, "hip_graph_replay": graph_replay, "merge_stress": merge_stress, "other_workloads": others,
+        "written_out_clones": written_out,
         "cpu_baseline_one_thread": cpu_1t,
         "recurrence_launches": {"resident_weight_layers": fused[0], "with_input_projection": fused[1],
                                 "with_dW_hh_and_bias_gradients": fused[2]},
