@@ -1229,11 +1229,23 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
       // bf16 operands: the input gradient reads only bf16 copies (not the weights the gradient
       // GEMMs below update in place) and has fewer tiles than the chip has CUs: with an auxiliary
       // stream it runs beside the layer's weight-gradient GEMMs (its launch is then not timed)
-      bool dx_beside = false;
+      bool dx_beside = false, swap = false;
       if (need_dx) {  // reads W_ih: before its update
         const NtView v_dgx = stepT ? NtView{dgxb, 1, 3 * H, s_dgb} : NtView{dgx, 0, 3 * H, s_gx};
         dx_beside = persist_b && stepT && v_wihT.bf16 && c->aux && c->ev_fork && c->ev_join && NC == 1;
-        if (dx_beside) {
+        // Above the first layer the input gradient is the product with the long tiles (a contraction
+        // over 3H, fewer tiles than CUs): it goes first, on this stream, and the first weight
+        // gradient beside it on the auxiliary one, whose many short tiles fill in around it (issued
+        // the other way round, the weight gradient's first wave of tiles held every CU and the
+        // long tiles started a tile late).  The first layer's input gradient is short and has the
+        // embedding gradient behind it: it stays on the auxiliary stream.
+        swap = dx_beside && l > 0;
+        if (swap) {
+          if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
+            return HPSGD_EHIP;
+          TRY(gemm2(s, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sRi, 0, dx, win, s_dx, EPI_STORE,
+                    nullptr, 0, v_dgx, v_wihT, 0.f, persist_b));
+        } else if (dx_beside) {
           if (hipEventRecord(c->ev_fork, s) != hipSuccess || hipStreamWaitEvent(c->aux, c->ev_fork, 0) != hipSuccess)
             return HPSGD_EHIP;
           TRY0(gemm2(c->aux, groups, bf, TB, win, 3 * H, dgx, 3 * H, s_gx, 0, Wih, win, sRi, 0, dx, win, s_dx,
@@ -1274,8 +1286,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                    parts, win, (long)n_wih, EPI_STORE, nullptr, 0, 0, 0.f, kWihSplits));
           TRY0(queue_reduce(parts, kWihSplits, n_wih, wi.aux, (size_t)sRi, wi.C, (size_t)wi.sC, wi.epi == EPI_COMMIT));
         } else {
-          TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
-                    wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
+          if (swap) {
+            TRY0(gemm2(c->aux, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
+                       wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
+            if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
+          } else {
+            TRY(gemm2(s, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
+                      wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
+          }
         }
         const WgradTarget wh = wgrad_target(c->lidx[l].whh);
         if (dwp) {
