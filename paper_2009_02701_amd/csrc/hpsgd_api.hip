@@ -1009,17 +1009,24 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
     // the embedding gradient from the first layer's input gradient dx (Alg. 2 "update replica"
     // for the table, when the update is in place)
     bool embed_done = false;
+    // clones: the table is written out first (one read, a write per worker), then updated like
+    // one that is already there.  (Nothing of the step reads the output table, so the copy could be
+    // issued earlier; beside the layer above's weight gradients it cost more than it saved here.)
+    bool table_out = false;
+    auto embed_table_out = [&](hipStream_t st) -> int {
+      const size_t oE = c->eoff(c->i_embed);
+      if (table_out || acc || !cloned || !lm || !aligned16(rin + oE) || !aligned16(rout + oE) || (sR & 3) != 0 ||
+          groups > HPSGD_KMAX)
+        return HPSGD_OK;
+      PtrPack pk;
+      for (int g = 0; g < groups; ++g) pk.p[g] = rout + oE + (size_t)g * sR;
+      if (launch_sync_all(rin + oE, pk, groups, nullptr, (size_t)d.vocab * d.embed, st) != hipSuccess) return HPSGD_EHIP;
+      table_out = true;
+      return HPSGD_OK;
+    };
     auto embed_grad = [&](hipStream_t st) -> int {
       const size_t oE = c->eoff(c->i_embed);
-      // clones: the table is written out first (one read, a write per worker), then updated like
-      // one that is already there
-      bool table_out = false;
-      if (!acc && cloned && aligned16(rin + oE) && aligned16(rout + oE) && (sR & 3) == 0 && groups <= HPSGD_KMAX) {
-        PtrPack pk;
-        for (int g = 0; g < groups; ++g) pk.p[g] = rout + oE + (size_t)g * sR;
-        if (launch_sync_all(rin + oE, pk, groups, nullptr, (size_t)d.vocab * d.embed, st) != hipSuccess) return HPSGD_EHIP;
-        table_out = true;
-      }
+      TRY0(embed_table_out(st));
       if (!acc && (rin == rout || table_out)) {
         // an update in place: only the rows of the tokens of the batch change, and their owners
         // write them; no gradient table to clear, fill and stream through the commit kernel
@@ -1270,6 +1277,7 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
         TRY(wgrad_rows(s, 0, chunk_lo(1), EPI_ACCUM));
       } else {
         const WgradTarget wi = wgrad_target(c->lidx[l].wih);
+        bool hh_first = false;
         // fp32, a narrow layer-0 input: the GEMM has few tiles and a long contraction (T*B), so the
         // contraction is cut into kWihSplits parts that run side by side; their sums are added
         // in order by the kernel that also applies the update
@@ -1286,6 +1294,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                    parts, win, (long)n_wih, EPI_STORE, nullptr, 0, 0, 0.f, kWihSplits));
           TRY0(queue_reduce(parts, kWihSplits, n_wih, wi.aux, (size_t)sRi, wi.C, (size_t)wi.sC, wi.epi == EPI_COMMIT));
         } else {
+          // the first layer beside its input gradient: the recurrent weight gradient (the longer
+          // tiles) before the input one, whose short tiles fill in at the end
+          hh_first = dx_beside && !swap && !dwp;
+          if (hh_first) {
+            const WgradTarget wh = wgrad_target(c->lidx[l].whh);
+            TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
+                      wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
+          }
           if (swap) {
             TRY0(gemm2(c->aux, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
                        wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
@@ -1295,11 +1311,14 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                       wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
           }
         }
-        const WgradTarget wh = wgrad_target(c->lidx[l].whh);
-        if (dwp) {
+        if (hh_first) {
+          // issued above
+        } else if (dwp) {
+          const WgradTarget wh = wgrad_target(c->lidx[l].whh);
           TRY0(queue_reduce(dwp, (B + 31) / 32, (size_t)3 * H * H, wh.aux, (size_t)sRi, wh.C, (size_t)wh.sC,
                            wh.epi == EPI_COMMIT));
         } else {
+          const WgradTarget wh = wgrad_target(c->lidx[l].whh);
           TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
                     wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
         }
