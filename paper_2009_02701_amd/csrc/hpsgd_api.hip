@@ -357,6 +357,10 @@ int gemm2(hipStream_t s, int groups, int bf16, int M, int N, int Kd, const float
 // holds the lock from its first one to its last (so that no other thread's launches fall in
 // between) and, if the previous ones went to another stream, lets its stream wait for that
 // event (hipStreamWaitEvent: the host never blocks).
+// how far behind the training stream's product the auxiliary stream's starts where the former must
+// be dispatched first (see the layers' backward pass)
+constexpr unsigned kAuxHeadStartUs = 5;
+
 struct ResidentOrder {
   std::mutex mu;
   hipEvent_t ev = nullptr;   // behind the last resident-weight launch issued on this device
@@ -1303,6 +1307,10 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
                       wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
           }
           if (swap) {
+            // (both streams become runnable at the same event; a few microseconds' head start keeps the
+            // long tiles in front also when this stream has marker packets - a timer's events - to
+            // get through first)
+            if (launch_delay(kAuxHeadStartUs, c->aux) != hipSuccess) return HPSGD_EHIP;
             TRY0(gemm2(c->aux, groups, bf, 3 * H, win, TB, dgx, 3 * H, s_gx, 1, layer_in, win, s_layer_in, 0, wi.C, win,
                        wi.sC, wi.epi, wi.aux, sRi, v_dgxT, v_xT, lr, persist_b));
             if (hipEventRecord(c->ev_join, c->aux) != hipSuccess) return HPSGD_EHIP;
