@@ -412,12 +412,12 @@ struct DlxShape {
 // tiles: on one), whose operand panels are fetched into its L2 once and shared by its CUs; dealing
 // the tiles of every group out to all XCDs made each L2 fetch the panels of all groups.
 template <int BM, int BN>
-__device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_m, int& tile_n) {
+__device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, unsigned bid, int& g, int& tile_m, int& tile_n) {
   const int tm = (d.M + BM - 1) / BM, tn = (d.N + BN - 1) / BN;
   const int per_group = tm * tn, total = per_group * d.groups;
   const int run = (total + 7) >> 3;
-  const int li = blockIdx.x >> 3;
-  const int v = (blockIdx.x & 7) * run + li;
+  const int li = bid >> 3;
+  const int v = (bid & 7) * run + li;
   if (li >= run || v >= total) return false;
   g = v / per_group;
   const int r = v - g * per_group;
@@ -431,9 +431,9 @@ __device__ __forceinline__ bool dlx_tile(const GemmNtDesc& d, int& g, int& tile_
   return true;
 }
 
+// bid: the workgroup's index among those of this product (blockIdx.x, unless a launch holds two products)
 template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
-__global__ void __launch_bounds__(64 * WGM * WGN)
-gemm_bf16_dlx_kernel(GemmNtDesc d) {
+__device__ __forceinline__ void dlx_body(const GemmNtDesc& d, unsigned bid) {
   using Sh = DlxShape<WGM, WGN, TM, TN, S>;
   constexpr int BM = Sh::BM, BN = Sh::BN, IPW = Sh::IPW, CP = Sh::CP, NT = Sh::NT;
   extern __shared__ __attribute__((aligned(16))) unsigned char nt_smem[];
@@ -442,7 +442,7 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
   const int wm = wave % WGM, wn = wave / WGM;
   const int lrow = lane & 31, lk = lane >> 5;
   int g, tile_m, tile_n;
-  if (!dlx_tile<BM, BN>(d, g, tile_m, tile_n)) return;
+  if (!dlx_tile<BM, BN>(d, bid, g, tile_m, tile_n)) return;
   const int m0 = tile_m * BM, n0 = tile_n * BN;
   const __bf16* __restrict__ A = reinterpret_cast<const __bf16*>(d.A) + (long)g * d.strideA;
   const __bf16* __restrict__ B = reinterpret_cast<const __bf16*>(d.B) + (long)g * d.strideB;
@@ -619,6 +619,23 @@ gemm_bf16_dlx_kernel(GemmNtDesc d) {
 }
 
 template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
+__global__ void __launch_bounds__(64 * WGM * WGN)
+gemm_bf16_dlx_kernel(GemmNtDesc d) {
+  dlx_body<COMMIT, WGM, WGN, TM, TN, S>(d, blockIdx.x);
+}
+
+// Two independent products of the same form in one launch: the first blocks0 workgroups (a
+// multiple of 8, so that a workgroup's XCD is the same as in a launch of its own) are d0's, the
+// rest d1's.  For two products that would otherwise follow each other on one stream although
+// neither needs the other: the second one's tiles fill the first one's last, partial round.
+template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
+__global__ void __launch_bounds__(64 * WGM * WGN)
+gemm_bf16_dlx_pair_kernel(GemmNtDesc d0, GemmNtDesc d1, unsigned blocks0) {
+  const bool first = blockIdx.x < blocks0;  // (uniform)
+  dlx_body<COMMIT, WGM, WGN, TM, TN, S>(first ? d0 : d1, first ? blockIdx.x : blockIdx.x - blocks0);
+}
+
+template <bool COMMIT, int WGM, int WGN, int TM, int TN, int S>
 hipError_t launch_dlx(const GemmNtDesc& d, hipStream_t s) {
   using Sh = DlxShape<WGM, WGN, TM, TN, S>;
   static bool ready = false;
@@ -634,6 +651,45 @@ hipError_t launch_dlx(const GemmNtDesc& d, hipStream_t s) {
   KernelTimer kt(kid, 2.0 * d.M * d.N * (double)d.Kd * d.groups, s);
   hipLaunchKernelGGL((gemm_bf16_dlx_kernel<COMMIT, WGM, WGN, TM, TN, S>), dim3(8 * ((total + 7) / 8)),
                      dim3(Sh::NT), Sh::LDS, s, d);
+  return hipGetLastError();
+}
+
+static bool pair_desc(const GemmBf16Args& a, GemmNtDesc& d) {
+  if (a.M <= 0 || a.N <= 0 || a.groups <= 0 || !a.win || !a.C) return false;
+  if (!gemm_bf16_nt_supported(a.A, 1, a.lda, a.sA, a.Kd) || !gemm_bf16_nt_supported(a.B, 1, a.ldb, a.sB, a.Kd)) return false;
+  d.A = a.A; d.lda = a.lda; d.strideA = a.sA;
+  d.B = a.B; d.ldb = a.ldb; d.strideB = a.sB;
+  d.C = a.C; d.ldc = a.ldc; d.strideC = a.sC;
+  d.bias = nullptr; d.strideBias = 0;
+  d.win = a.win; d.strideWin = a.sWin; d.lr = a.lr;
+  d.M = a.M; d.N = a.N; d.Kd = a.Kd; d.groups = a.groups;
+  return true;
+}
+
+bool gemm_bf16_update_pair_supported(const GemmBf16Args& p0, const GemmBf16Args& p1) {
+  GemmNtDesc d;
+  return pair_desc(p0, d) && pair_desc(p1, d);
+}
+
+hipError_t launch_gemm_bf16_update_pair(const GemmBf16Args& p0, const GemmBf16Args& p1, hipStream_t s) {
+  GemmNtDesc d0, d1;
+  if (!pair_desc(p0, d0) || !pair_desc(p1, d1)) return hipErrorInvalidValue;
+  using Sh = DlxShape<2, 4, 3, 2, 2>;
+  static bool ready = false;
+  if (!ready) {
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_dlx_pair_kernel<true, 2, 4, 3, 2, 2>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)Sh::LDS);
+    if (e != hipSuccess) return e;
+    ready = true;
+  }
+  auto blocks = [](const GemmNtDesc& d) {
+    const long total = (long)((d.M + Sh::BM - 1) / Sh::BM) * ((d.N + Sh::BN - 1) / Sh::BN) * d.groups;
+    return (unsigned)(8 * ((total + 7) / 8));
+  };
+  const unsigned b0 = blocks(d0), b1 = blocks(d1);
+  KernelTimer kt(KID_GEMM_BF16_DLX192_COMMIT,
+                 2.0 * d0.M * d0.N * (double)d0.Kd * d0.groups + 2.0 * d1.M * d1.N * (double)d1.Kd * d1.groups, s);
+  hipLaunchKernelGGL((gemm_bf16_dlx_pair_kernel<true, 2, 4, 3, 2, 2>), dim3(b0 + b1), dim3(Sh::NT), Sh::LDS, s, d0, d1, b0);
   return hipGetLastError();
 }
 

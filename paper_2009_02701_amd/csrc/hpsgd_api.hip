@@ -1301,12 +1301,28 @@ int run_step(hpsgd_ctx* c, int k0, int groups, const float* rin, float* rout, si
           // the first layer beside its input gradient: the recurrent weight gradient (the longer
           // tiles) before the input one, whose short tiles fill in at the end
           hh_first = dx_beside && !swap && !dwp;
+          bool paired = false;
           if (hh_first) {
             const WgradTarget wh = wgrad_target(c->lidx[l].whh);
-            TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
-                      wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
+            // ... and both in one launch when both are updates in place: neither needs the other,
+            // and on one stream the second would wait for the first one's last, partial round
+            if (wh.epi == EPI_COMMIT && wi.epi == EPI_COMMIT && v_dghT.bf16 && v_hsT.bf16 && v_dgxT.bf16 && v_xT.bf16) {
+              const GemmBf16Args ph{v_dghT.p, v_dghT.ld, v_dghT.stride, v_hsT.p, v_hsT.ld, v_hsT.stride, wh.C, H, wh.sC,
+                                    wh.aux, sRi, lr, 3 * H, H, TB, groups};
+              const GemmBf16Args pi{v_dgxT.p, v_dgxT.ld, v_dgxT.stride, v_xT.p, v_xT.ld, v_xT.stride, wi.C, win, wi.sC,
+                                    wi.aux, sRi, lr, 3 * H, win, TB, groups};
+              if (gemm_bf16_update_pair_supported(ph, pi)) {
+                HIP_TRY(launch_gemm_bf16_update_pair(ph, pi, s));
+                paired = true;
+              }
+            }
+            if (!paired)
+              TRY(gemm2(s, groups, bf, 3 * H, H, TB, dgh, 3 * H, s_gx, 1, hs, H, s_hs, 0, wh.C, H, wh.sC, wh.epi,
+                        wh.aux, sRi, v_dghT, v_hsT, lr, persist_b));
           }
-          if (swap) {
+          if (paired) {
+            // issued above
+          } else if (swap) {
             // (both streams become runnable at the same event; a few microseconds' head start keeps the
             // long tiles in front also when this stream has marker packets - a timer's events - to
             // get through first)

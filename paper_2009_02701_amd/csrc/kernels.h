@@ -309,6 +309,20 @@ hipError_t launch_gemm_bf16_nt(const void* A, int a_bf16, long lda, long sA, con
                                long ldb, long sB, float* C, long ldc, long sC, const float* bias,
                                long sBias, const float* win, long sWin, float lr, int M, int N, int Kd,
                                int groups, hipStream_t s, int form = 0);
+// Two products with bf16 operands and the update epilogue (C = win - lr * A B^T) in ONE launch of
+// the 192 x 256 form: for two that neither need each other nor fill the chip alone.  Strides in
+// elements of each buffer's own type; the same conditions as launch_gemm_bf16_nt per product.
+struct GemmBf16Args {
+  const void* A; long lda, sA;
+  const void* B; long ldb, sB;
+  float* C; long ldc, sC;
+  const float* win; long sWin;
+  float lr;
+  int M, N, Kd, groups;
+};
+bool gemm_bf16_update_pair_supported(const GemmBf16Args& p0, const GemmBf16Args& p1);
+hipError_t launch_gemm_bf16_update_pair(const GemmBf16Args& p0, const GemmBf16Args& p1, hipStream_t s);
+
 // out[c][r] = in[r][c], R x C per group
 hipError_t launch_transpose(const float* in, long s_in, float* out, long s_out, int R, int C,
                             int groups, hipStream_t s);
