@@ -245,15 +245,18 @@ def main():
     tr.s_train_side(lr, n_ov)
     t_a = (time.perf_counter() - c0) / n_ov
     sb = tr.stream_b
-    clone = tr.snapshot if tr.implicit_clone else tr.sync_all
+    def sync_side():
+        if tr.implicit_clone:
+            tr.merge_snapshot(0, sb)
+        else:
+            tr.merge(0, sb)
+            tr.sync_all(0, sb)
     for _ in range(3):
-        tr.merge(0, sb)
-        clone(0, sb)
+        sync_side()
     torch.cuda.synchronize()
     c0 = time.perf_counter()
     for _ in range(n_ov):
-        tr.merge(0, sb)
-        clone(0, sb)
+        sync_side()
     torch.cuda.synchronize()
     t_b = (time.perf_counter() - c0) / n_ov
     tr.s_seq(lr, 1, 5, record_loss=False)

@@ -285,6 +285,13 @@ int hpsgd_sync_all(const float *global, float *const *replicas, int K, float *sn
 int hpsgd_merge_sync(float *global, float *const *replicas, float *snapshot, int K, size_t P,
                      void *hip_stream);
 
+/* hpsgd_merge(global, replicas, snapshot, ..) followed by snapshot = global (hpsgd_sync_all with K = 0),
+ * bit for bit, in one pass: 4 (K + 4) bytes per parameter instead of 4 (K + 5).  The synchronising side
+ * of a round whose local step is hpsgd_local_step_all_cloned: the replicas are only read.  `global` and
+ * `snapshot` are written and may overlap neither each other nor a replica (HPSGD_EALIAS). */
+int hpsgd_merge_snapshot(float *global, const float *const *replicas, float *snapshot, int K, size_t P,
+                         void *hip_stream);
+
 /* ---- kernel timing for benchmarks (not part of the method) ------------------------------
  * The launches of one local step fall into roles.  While a role's bit is set in the mask,
  * hpsgd_local_step(_all) records a HIP event pair on the caller's stream around every launch

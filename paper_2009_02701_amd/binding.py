@@ -28,7 +28,7 @@ EXPORTS = [
     "hpsgd_local_step_all_acc", "hpsgd_merge_grad", "hpsgd_set_recurrence", "hpsgd_recurrence_gave_up",
     "hpsgd_recurrence_info", "hpsgd_gemm_bf16_nt", "hpsgd_prepare_replicas",
     "hpsgd_kernel_timer_enable", "hpsgd_kernel_timer_read", "hpsgd_kernel_name",
-    "hpsgd_local_step_all_static", "hpsgd_local_step_all_cloned", "hpsgd_merge_sync", "hpsgd_prepare_clones",
+    "hpsgd_local_step_all_static", "hpsgd_local_step_all_cloned", "hpsgd_merge_sync", "hpsgd_merge_snapshot", "hpsgd_prepare_clones",
 ]
 ROLE_COUNT = 14
 KERNEL_COUNT = 22
@@ -79,6 +79,7 @@ def load_library():
                                            C.POINTER(vp), vp]
     lib.hpsgd_merge.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_merge_sync.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
+    lib.hpsgd_merge_snapshot.argtypes = [vp, C.POINTER(vp), vp, C.c_int, sz, vp]
     lib.hpsgd_sync_replica.argtypes = [vp, vp, sz, vp]
     lib.hpsgd_sync_all.argtypes = [vp, C.POINTER(vp), C.c_int, vp, sz, vp]
     lib.hpsgd_set_aux_stream.argtypes = [vp, vp]
@@ -323,6 +324,13 @@ def merge_sync(global_, replicas, snapshot, stream=None):
 def sync_replica(global_, replica, stream=None):
     _check(load_library().hpsgd_sync_replica(_ptr(global_), _ptr(replica), global_.numel(),
                                              _stream(stream)), "hpsgd_sync_replica")
+
+
+def merge_snapshot(global_, replicas, snapshot, stream=None):
+    """merge, then snapshot = the merged model, in one pass (the replicas are only read)."""
+    reps = list(replicas)
+    _check(load_library().hpsgd_merge_snapshot(_ptr(global_), _ptr_array(reps), _ptr(snapshot), len(reps),
+                                               global_.numel(), _stream(stream)), "hpsgd_merge_snapshot")
 
 
 def sync_all(global_, replicas, snapshot, stream=None):

@@ -1695,6 +1695,26 @@ int hpsgd_merge_sync(float* global, float* const* replicas, float* snapshot, int
   return launch_merge_sync(global, pk, snapshot, K, P, (hipStream_t)hip_stream) == hipSuccess ? HPSGD_OK : HPSGD_EHIP;
 }
 
+int hpsgd_merge_snapshot(float* global, const float* const* replicas, float* snapshot, int K, size_t P,
+                         void* hip_stream) {
+  if (K < 1 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;
+  if (P == 0) return HPSGD_OK;
+  if (!global || !replicas || !snapshot) return HPSGD_EINVAL;
+  if (!aligned16(global) || !aligned16(snapshot)) return HPSGD_EALIGN;
+  const size_t bytes = P * sizeof(float);
+  PtrPack pk;
+  for (int k = 0; k < K; ++k) {
+    if (!replicas[k]) return HPSGD_EINVAL;
+    if (!aligned16(replicas[k])) return HPSGD_EALIGN;
+    // the replicas are read while the two models are written
+    if (overlaps(global, bytes, replicas[k], bytes) || overlaps(snapshot, bytes, replicas[k], bytes)) return HPSGD_EALIAS;
+    pk.p[k] = const_cast<float*>(replicas[k]);
+  }
+  if (overlaps(global, bytes, snapshot, bytes)) return HPSGD_EALIAS;
+  return launch_merge_sync(global, pk, snapshot, K, P, (hipStream_t)hip_stream, false) == hipSuccess ? HPSGD_OK
+                                                                                                      : HPSGD_EHIP;
+}
+
 int hpsgd_merge_grad(float* global, const float* const* grad_accs, float lr, int K, size_t P,
                      void* hip_stream) {
   if (K < 1 || K > HPSGD_MAX_WORKERS) return HPSGD_EINVAL;

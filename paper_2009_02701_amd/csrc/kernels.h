@@ -60,8 +60,9 @@ hipError_t launch_merge(float* global, const PtrPack& replicas, const float* sna
 hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, float* snapshot,
                            size_t P, hipStream_t s);
 // merge, then sync of the same replicas and snapshot, in one pass
+// (clone = false: the replicas are only read, the snapshot alone is taken)
 hipError_t launch_merge_sync(float* global, const PtrPack& replicas, float* snapshot, int K, size_t P,
-                             hipStream_t s);
+                             hipStream_t s, bool clone = true);
 // out[k] = in[k] - lr * grad[k] for K strided slices of P floats (in_stride 0: one model for all)
 hipError_t launch_commit(const float* in, size_t in_stride, float* out, size_t stride, const float* grad,
                          size_t grad_stride, float lr, int K, size_t P, hipStream_t s);

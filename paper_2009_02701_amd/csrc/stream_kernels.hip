@@ -129,7 +129,9 @@ hipError_t launch_sync_all(const float* global, const PtrPack& replicas, int K, 
 // what merge_kernel followed by sync_kernel leaves, with every buffer read once and written once
 // (4 (2K + 4) bytes per parameter instead of 4 (2K + 5)).  A lane reads its elements of all K + 2
 // buffers before it writes any of them, so the update in place is safe.
-template <int KT>
+// CLONE = false: the replicas are only read (the snapshot alone is taken: 4 (K + 4) bytes per
+// parameter, against 4 (K + 3) + 8 for the merge followed by a copy of its result).
+template <int KT, bool CLONE>
 __global__ void __launch_bounds__(kThreads)
 merge_sync_kernel(float* global, PtrPack rep, float* snapshot, int Krt, float inv_k, size_t n4, size_t P) {
   const int K = KT > 0 ? KT : Krt;
@@ -145,8 +147,10 @@ merge_sync_kernel(float* global, PtrPack rep, float* snapshot, int Krt, float in
     }
     const f4v o = g + acc * inv_k;
     __builtin_nontemporal_store(o, reinterpret_cast<f4v*>(global) + i);
+    if (CLONE) {
 #pragma unroll
-    for (int k = 0; k < K; ++k) __builtin_nontemporal_store(o, reinterpret_cast<f4v*>(rep.p[k]) + i);
+      for (int k = 0; k < K; ++k) __builtin_nontemporal_store(o, reinterpret_cast<f4v*>(rep.p[k]) + i);
+    }
     __builtin_nontemporal_store(o, reinterpret_cast<f4v*>(snapshot) + i);
   }
   if (blockIdx.x == 0) {
@@ -157,21 +161,28 @@ merge_sync_kernel(float* global, PtrPack rep, float* snapshot, int Krt, float in
       for (int k = 0; k < K; ++k) acc += rep.p[k][j] - s;
       const float o = global[j] + acc * inv_k;
       global[j] = o;
-      for (int k = 0; k < K; ++k) rep.p[k][j] = o;
+      if (CLONE)
+        for (int k = 0; k < K; ++k) rep.p[k][j] = o;
       snapshot[j] = o;
     }
   }
 }
 
 hipError_t launch_merge_sync(float* global, const PtrPack& replicas, float* snapshot, int K, size_t P,
-                             hipStream_t s) {
+                             hipStream_t s, bool clone) {
   if (P == 0) return hipSuccess;
   const size_t n4 = P / 4;
   const int blocks = onepass_blocks(n4);
   const float inv_k = 1.0f / (float)K;
-#define HPSGD_MS_CASE(KT)                                                                          \
-  hipLaunchKernelGGL(merge_sync_kernel<KT>, dim3(blocks), dim3(kThreads), 0, s, global, replicas, \
-                     snapshot, K, inv_k, n4, P)
+#define HPSGD_MS_CASE(KT)                                                                                  \
+  do {                                                                                                     \
+    if (clone)                                                                                             \
+      hipLaunchKernelGGL((merge_sync_kernel<KT, true>), dim3(blocks), dim3(kThreads), 0, s, global, replicas, \
+                         snapshot, K, inv_k, n4, P);                                                       \
+    else                                                                                                   \
+      hipLaunchKernelGGL((merge_sync_kernel<KT, false>), dim3(blocks), dim3(kThreads), 0, s, global, replicas, \
+                         snapshot, K, inv_k, n4, P);                                                       \
+  } while (0)
   switch (K) {
     case 1: HPSGD_MS_CASE(1); break;
     case 2: HPSGD_MS_CASE(2); break;

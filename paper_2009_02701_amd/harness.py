@@ -137,6 +137,11 @@ class Trainer:
         hb.merge(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
                  self.S[gen][:self.P], stream=stream)
 
+    def merge_snapshot(self, gen: int, stream=None):
+        """merge(gen) followed by snapshot(gen) in one pass (the replicas are only read)."""
+        hb.merge_snapshot(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
+                          self.S[gen][:self.P], stream=stream)
+
     def merge_sync(self, gen: int, stream=None):
         """merge(gen) followed by sync_all(gen) in one pass over the buffers."""
         hb.merge_sync(self.G[:self.P], [self.R[gen][k, :self.P] for k in range(self.K)],
@@ -161,10 +166,13 @@ class Trainer:
         st = self.stream_a
         st.wait_stream(torch.cuda.current_stream())
         step = 0
+        have_snapshot = False
         for _ in range(rounds):
-            # (the clone is implicit here too: the first local step after a synchronisation reads the snapshot)
+            # (the clone is implicit here too: the first local step after a synchronisation reads the
+            # snapshot, which the merge of the round before has left behind in the same pass)
             if self.implicit_clone:
-                self.snapshot(0, st)
+                if not have_snapshot:
+                    self.snapshot(0, st)
             else:
                 self.sync_all(0, st)
             for i in range(gamma):
@@ -179,7 +187,11 @@ class Trainer:
                 step += 1
             if sync_delay_us:
                 hb.delay_us(sync_delay_us, st)
-            self.merge(0, st)
+            if self.implicit_clone:
+                self.merge_snapshot(0, st)
+                have_snapshot = True
+            else:
+                self.merge(0, st)
         st.synchronize()
 
     def s_psgd(self, lr: float, steps: int, record_loss=True):
@@ -285,7 +297,9 @@ class Trainer:
                 sb.wait_event(done[e % 2])
                 if sync_delay_us:
                     hb.delay_us(sync_delay_us, sb)
-                if self.fused_merge_sync and not self.implicit_clone:
+                if self.implicit_clone:
+                    self.merge_snapshot(g, sb)
+                elif self.fused_merge_sync:
                     self.merge_sync(g, sb)
                 else:
                     self.merge(g, sb)
@@ -329,7 +343,9 @@ class Trainer:
         clone = self.snapshot if self.implicit_clone else self.sync_all
         if self._have_delta:
             sb.wait_event(self._ev_a)
-            if self.fused_merge_sync and not self.implicit_clone:
+            if self.implicit_clone:
+                self.merge_snapshot(1 - g, sb)
+            elif self.fused_merge_sync:
                 self.merge_sync(1 - g, sb)
             else:
                 self.merge(1 - g, sb)

@@ -234,6 +234,15 @@ def test_merge_sync_checks_its_arguments_on_the_host():
     assert lib.hpsgd_merge_sync(a(0), same, a(1), 2, P, None) == 4                      # a replica twice
     onto = (C.c_void_p * 2)(a(2), a(1))
     assert lib.hpsgd_merge_sync(a(0), onto, a(1), 2, P, None) == 4                      # replica == snapshot
+    # merge + snapshot in one pass: the replicas are only read (one may be passed twice)
+    ms = lib.hpsgd_merge_snapshot
+    assert ms(a(0), reps, a(1), 0, P, None) == 1 and ms(None, reps, a(1), 2, P, None) == 1
+    assert ms(a(0), reps, None, 2, P, None) == 1
+    assert ms(a(0), reps, a(1), 2, 0, None) == 0
+    assert ms(C.c_void_p(0x10004), reps, a(1), 2, P, None) == 3
+    assert ms(a(0), reps, a(0), 2, P, None) == 4                                        # snapshot == global
+    assert ms(a(0), onto, a(1), 2, P, None) == 4                                        # replica == snapshot
+    assert ms(a(2), reps, a(1), 2, P, None) == 4                                        # replica == global
 
 
 def test_prepare_clones_checks_its_arguments_on_the_host():

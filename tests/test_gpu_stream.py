@@ -222,6 +222,32 @@ def test_merge_sync_equals_merge_then_sync_bit_for_bit(P, K):
             assert np.array_equal(t, outs[1][0])   # replicas and snapshot are clones of the merged model
 
 
+@pytest.mark.parametrize("P", [0, 1, 5, 4096, 1000003])
+@pytest.mark.parametrize("K", [1, 3, 8])
+def test_merge_snapshot_equals_merge_then_snapshot_bit_for_bit(P, K):
+    """hpsgd_merge_snapshot against hpsgd_merge followed by hpsgd_sync_all with no replica to write:
+    the merged model and the snapshot, every bit; the replicas stay as they were."""
+    g0, s0 = _vec(1, P), _vec(2, P)
+    reps = [(s0 + _vec(10 + k, P, 1e-2)).astype(np.float32) for k in range(K)]
+    outs = []
+    for fused in (False, True):
+        G = torch.from_numpy(g0.copy()).to(DEV)
+        S = torch.from_numpy(s0.copy()).to(DEV)
+        R = [torch.from_numpy(r.copy()).to(DEV) for r in reps]
+        if fused:
+            hb.merge_snapshot(G, R, S)
+        else:
+            hb.merge(G, R, S)
+            hb.sync_all(G, [], S)
+        torch.cuda.synchronize()
+        outs.append([t.cpu().numpy().view(np.uint32) for t in [G, S] + R])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)
+    for k in range(K):
+        assert np.array_equal(outs[1][2 + k], reps[k].view(np.uint32))
+    assert np.array_equal(outs[1][0], outs[1][1])
+
+
 def test_merge_sync_full_size_sampled():
     """Config 5 at its full size through hpsgd_merge_sync: sampled outputs against the oracle, and
     the whole vectors of the K + 1 clones against the merged model."""
