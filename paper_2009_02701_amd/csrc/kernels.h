@@ -29,7 +29,7 @@ enum KernelId : int {
   KID_GEMM_BF16_DLX128 = 7,       // gemm_bf16_dlx_kernel<false, 2, 4, 2, 2, 3>  (128 x 256)
   KID_GEMM_BF16_DLX128_COMMIT = 8,
   KID_GEMM_BF16_DLX192 = 9,       // gemm_bf16_dlx_kernel<false, 2, 4, 3, 2, 2>  (192 x 256)
-  KID_GEMM_BF16_DLX192_COMMIT = 10,
+  KID_GEMM_BF16_DLX192_COMMIT = 10,  // (also gemm_bf16_dlx_pair_kernel<true, 2, 4, 3, 2, 2>: two such products in one launch)
   KID_GEMM_BF16_DLX256 = 11,      // gemm_bf16_dlx_kernel<false, 2, 4, 4, 2, 2>  (256 x 256)
   KID_GEMM_BF16_DLX256_COMMIT = 12,
   KID_GEMM_BF16_NT = 13,          // gemm_bf16_nt_kernel (an fp32 operand rounded while staged)
